@@ -1,0 +1,184 @@
+"""Plain CPU oracle of a pipeline stage's decoder-layer forward pass.
+
+TEST INFRASTRUCTURE.  Slow, unfused, written for checking by eye.  It shares no
+code with the HIP library and must not be imported by it.
+
+What it computes.  The serving system hands each inference engine a run of
+decoder layers and feeds it micro-batches that mix prefill chunks and decode
+tokens; the engine's output is the activation tensor passed to the next stage
+(paper section 3.2.2 "Distributed Inference Engine"; section 4.2 for the two
+phases and for the payload growing with the number of processed tokens).  The
+paper leaves the computation itself to its engine runtime and evaluates
+Llama-family models (section 5, "Models"), so the definition used here is the
+standard pre-norm Llama decoder block: RMSNorm, q/k/v projection, rotary
+embedding (half-split pairing), append to a paged KV cache, causal attention
+with grouped KV heads, output projection + residual, RMSNorm, SwiGLU MLP +
+residual.  No biases, no final norm.
+
+Numerics: every tensor is widened to `dtype` (float64 by default) on entry and
+nothing is rounded afterwards.  Library primitives used as steps: matmul,
+exp/softmax building blocks, cos/sin.
+
+Loop discipline: a sequence's rows depend only on that sequence's data and on
+the logical key order, never on physical block numbers.
+
+Pins (tests/test_oracle_*.py): scalar-loop brute force of the whole block on
+tiny shapes; dense masked attention; paged == contiguous (bitwise); chunked ==
+unsplit; decode == last prefill row; batch-order independence; closed forms for
+RMSNorm, RoPE, softmax degenerate cases; GQA == MHA with replicated heads;
+zero output projections give the identity; library cross-checks (fp64 matmul
+chain, torch scaled_dot_product_attention).  The paper prints no numeric values
+for this path, so parity against printed values is unpinned; parity is against
+the definition.
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+from typing import Dict, List, Optional, Sequence
+
+import torch
+
+
+@dataclasses.dataclass(frozen=True)
+class OracleShape:
+    num_layers: int
+    hidden: int
+    num_q_heads: int
+    num_kv_heads: int
+    head_dim: int
+    ffn: int
+    rms_eps: float = 1e-5
+    rope_theta: float = 1e4
+    kv_block_size: int = 16
+
+
+def new_pool(shape: OracleShape, num_kv_blocks: int, dtype=torch.float64, fill=float("nan")) -> torch.Tensor:
+    """The oracle's own KV pool: [layer, K|V, block, slot, kv_head, dim]."""
+    return torch.full((shape.num_layers, 2, num_kv_blocks, shape.kv_block_size,
+                       shape.num_kv_heads, shape.head_dim), fill, dtype=dtype)
+
+
+def rmsnorm(x: torch.Tensor, gain: torch.Tensor, eps: float) -> torch.Tensor:
+    """x * gain / sqrt(mean(x^2) + eps), per row."""
+    ms = (x * x).mean(dim=-1, keepdim=True)
+    return x * gain / torch.sqrt(ms + eps)
+
+
+def rope_rotate(u: torch.Tensor, pos: torch.Tensor, theta: float) -> torch.Tensor:
+    """Rotary embedding, half-split pairing.  u: [T, heads, d]; pos: [T] integers.
+
+    Pair (i, i + d/2) of every head is rotated by the angle pos * theta**(-2i/d).
+    Angles, cos and sin are evaluated in float64.
+    """
+    t, _, d = u.shape
+    half = d // 2
+    i = torch.arange(half, dtype=torch.float64)
+    inv_freq = theta ** (-2.0 * i / d)
+    ang = pos.to(torch.float64).view(t, 1) * inv_freq.view(1, half)      # [T, d/2]
+    cos = torch.cos(ang).to(u.dtype).view(t, 1, half)
+    sin = torch.sin(ang).to(u.dtype).view(t, 1, half)
+    lo, hi = u[..., :half], u[..., half:]
+    return torch.cat([lo * cos - hi * sin, hi * cos + lo * sin], dim=-1)
+
+
+def silu(z: torch.Tensor) -> torch.Tensor:
+    return z / (1.0 + torch.exp(-z))
+
+
+def slot_mapping(q_lens: Sequence[int], ctx_lens: Sequence[int], block_tables, block: int) -> List[int]:
+    """Pool slot of every new token: table[s][j // block] * block + j % block, j = ctx + i."""
+    slots: List[int] = []
+    for s, (q, c) in enumerate(zip(q_lens, ctx_lens)):
+        for i in range(q):
+            j = c + i
+            slots.append(int(block_tables[s][j // block]) * block + j % block)
+    return slots
+
+
+def attention_rows(q: torch.Tensor, keys: torch.Tensor, values: torch.Tensor, ctx: int) -> torch.Tensor:
+    """Causal attention of one sequence's new rows over its whole logical cache.
+
+    q: [n, nq, d] (rotated) rows at logical indices ctx .. ctx+n-1;
+    keys, values: [ctx + n, nkv, d] in logical order.  Row i sees keys 0 .. ctx+i.
+    Query head h reads kv head h // (nq // nkv).  Scores are scaled by 1/sqrt(d).
+    """
+    n, nq, d = q.shape
+    nkv = keys.shape[1]
+    g = nq // nkv
+    total = keys.shape[0]
+    out = torch.empty_like(q)
+    j = torch.arange(total).view(1, total)
+    limit = (ctx + torch.arange(n)).view(n, 1)
+    hidden_mask = j > limit                                          # [n, total]
+    for h in range(nq):
+        r = h // g
+        e = (q[:, h, :] @ keys[:, r, :].T) / math.sqrt(d)             # [n, total]
+        e = e.masked_fill(hidden_mask, float("-inf"))
+        e = e - e.max(dim=-1, keepdim=True).values
+        w = torch.exp(e)
+        w = w / w.sum(dim=-1, keepdim=True)
+        out[:, h, :] = w @ values[:, r, :]
+    return out
+
+
+def decoder_layer(shape: OracleShape, w: Dict[str, torch.Tensor], x: torch.Tensor, pos: torch.Tensor,
+                  q_lens, ctx_lens, block_tables, pool_layer: torch.Tensor, slots: List[int],
+                  taps: Optional[Dict[str, torch.Tensor]] = None) -> torch.Tensor:
+    """One decoder layer on packed rows x [T, H]; appends to pool_layer [2, block, slot, nkv, d]."""
+    dt = x.dtype
+    nq, nkv, d, blk = shape.num_q_heads, shape.num_kv_heads, shape.head_dim, shape.kv_block_size
+    t = x.shape[0]
+    wqkv = w["wqkv"].to(dt)
+    a = rmsnorm(x, w["norm1"].to(dt), shape.rms_eps)
+    qkv = a @ wqkv.T                                                  # weights are [out, in]
+    q = qkv[:, : nq * d].reshape(t, nq, d)
+    k = qkv[:, nq * d: (nq + nkv) * d].reshape(t, nkv, d)
+    v = qkv[:, (nq + nkv) * d:].reshape(t, nkv, d)
+    q = rope_rotate(q, pos, shape.rope_theta)
+    k = rope_rotate(k, pos, shape.rope_theta)
+    # append the new tokens' keys (rotated) and values at their slots
+    slot_t = torch.as_tensor(slots, dtype=torch.int64)
+    pool_layer[0, slot_t // blk, slot_t % blk] = k
+    pool_layer[1, slot_t // blk, slot_t % blk] = v
+    o = torch.empty(t, nq, d, dtype=dt)
+    row0 = 0
+    for s, (n, c) in enumerate(zip(q_lens, ctx_lens)):
+        total = c + n
+        nb = (total + blk - 1) // blk
+        table = torch.as_tensor(block_tables[s][:nb], dtype=torch.int64)
+        keys = pool_layer[0, table].reshape(nb * blk, nkv, d)[:total]   # logical order via the table
+        vals = pool_layer[1, table].reshape(nb * blk, nkv, d)[:total]
+        o[row0: row0 + n] = attention_rows(q[row0: row0 + n], keys, vals, c)
+        row0 += n
+    h = x + o.reshape(t, nq * d) @ w["wo"].to(dt).T
+    b = rmsnorm(h, w["norm2"].to(dt), shape.rms_eps)
+    m = silu(b @ w["wgate"].to(dt).T) * (b @ w["wup"].to(dt).T)
+    y = h + m @ w["wdown"].to(dt).T
+    if taps is not None:
+        taps.update(a=a, q=q, k=k, v=v, attn=o.reshape(t, nq * d), h=h, b=b, m=m, x=y)
+    return y
+
+
+def stage_forward(shape: OracleShape, layers: Sequence[Dict[str, torch.Tensor]], hidden: torch.Tensor,
+                  positions, q_lens: Sequence[int], ctx_lens: Sequence[int], block_tables,
+                  pool: torch.Tensor, dtype=torch.float64,
+                  taps: Optional[List[Dict[str, torch.Tensor]]] = None):
+    """Run the stage's layers on one micro-batch.
+
+    hidden [T, H] (any float dtype; widened exactly), positions [T], per-sequence q_lens
+    (new tokens; 1 = decode) and ctx_lens (tokens already cached), block_tables [S][...],
+    pool [L, 2, blocks, slot, nkv, d] holding the cached context at the logical positions
+    0 .. ctx-1 of every sequence; it is updated in place with the new tokens.
+    Returns (output [T, H] in `dtype`, slot list [T]).
+    """
+    assert pool.dtype == dtype
+    x = hidden.to(dtype)
+    pos = torch.as_tensor(positions, dtype=torch.int64)
+    slots = slot_mapping(q_lens, ctx_lens, block_tables, shape.kv_block_size)
+    for l in range(shape.num_layers):
+        tap = {} if taps is not None else None
+        x = decoder_layer(shape, layers[l], x, pos, q_lens, ctx_lens, block_tables, pool[l], slots, tap)
+        if taps is not None:
+            taps.append(tap)
+    return x, slots

@@ -1,0 +1,67 @@
+"""Scalar-loop evaluation of the decoder block, in Python floats, for tiny shapes.
+
+An independent statement of the same definition the oracle follows, used only to pin the
+oracle: nested loops over tokens, heads, keys and features with explicit [out][in] weight
+indexing, math.exp / math.cos / math.sin, and a contiguous per-sequence cache (no paging).
+"""
+import math
+
+
+def rmsnorm_row(x, g, eps):
+    ms = sum(v * v for v in x) / len(x)
+    return [x[j] * g[j] / math.sqrt(ms + eps) for j in range(len(x))]
+
+
+def matvec(w, x):
+    """w[out][in] times x[in]."""
+    return [sum(w[o][i] * x[i] for i in range(len(x))) for o in range(len(w))]
+
+
+def rope_head(u, p, theta):
+    d = len(u)
+    half = d // 2
+    y = [0.0] * d
+    for i in range(half):
+        ang = p * theta ** (-2.0 * i / d)
+        c, s = math.cos(ang), math.sin(ang)
+        y[i] = u[i] * c - u[i + half] * s
+        y[i + half] = u[i + half] * c + u[i] * s
+    return y
+
+
+def layer_one_sequence(shape, w, rows, pos, cache_k, cache_v):
+    """rows: list of [H] new-token inputs; cache_k/v: lists of [nkv][d] for the cached context
+    (extended in place).  Returns the list of [H] outputs."""
+    nq, nkv, d, hdim = shape.num_q_heads, shape.num_kv_heads, shape.head_dim, shape.hidden
+    g = nq // nkv
+    ctx = len(cache_k)
+    qs = []
+    for n, x in enumerate(rows):
+        a = rmsnorm_row(x, w["norm1"], shape.rms_eps)
+        qkv = matvec(w["wqkv"], a)
+        q = [rope_head(qkv[h * d:(h + 1) * d], pos[n], shape.rope_theta) for h in range(nq)]
+        k = [rope_head(qkv[(nq + r) * d:(nq + r + 1) * d], pos[n], shape.rope_theta) for r in range(nkv)]
+        v = [qkv[(nq + nkv + r) * d:(nq + nkv + r + 1) * d] for r in range(nkv)]
+        cache_k.append(k)
+        cache_v.append(v)
+        qs.append(q)
+    outs = []
+    for n, x in enumerate(rows):
+        o = []
+        for h in range(nq):
+            r = h // g
+            last = ctx + n                       # causal: keys 0..ctx+n inclusive
+            e = [sum(qs[n][h][c] * cache_k[j][r][c] for c in range(d)) / math.sqrt(d) for j in range(last + 1)]
+            mx = max(e)
+            wts = [math.exp(v_ - mx) for v_ in e]
+            z = sum(wts)
+            o.extend(sum(wts[j] / z * cache_v[j][r][c] for j in range(last + 1)) for c in range(d))
+        proj = matvec(w["wo"], o)
+        hrow = [x[j] + proj[j] for j in range(hdim)]
+        b = rmsnorm_row(hrow, w["norm2"], shape.rms_eps)
+        gate = matvec(w["wgate"], b)
+        up = matvec(w["wup"], b)
+        m = [gate[f] / (1.0 + math.exp(-gate[f])) * up[f] for f in range(len(gate))]
+        dn = matvec(w["wdown"], m)
+        outs.append([hrow[j] + dn[j] for j in range(hdim)])
+    return outs

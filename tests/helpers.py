@@ -1,0 +1,43 @@
+"""Shared test plumbing: turn synthetic draws into oracle inputs (no arithmetic of the method)."""
+from __future__ import annotations
+
+from typing import Dict, List
+
+import torch
+
+import oracle
+from paper_2507_05043_amd import synth
+
+
+def oracle_shape(shape: synth.StageShape) -> oracle.OracleShape:
+    return oracle.OracleShape(shape.num_layers, shape.hidden, shape.num_q_heads, shape.num_kv_heads,
+                              shape.head_dim, shape.ffn, shape.rms_eps, shape.rope_theta,
+                              shape.kv_block_size)
+
+
+def draw_layers(shape: synth.StageShape, seed: int, weight_std=None, device="cpu") -> List[Dict[str, torch.Tensor]]:
+    return [synth.draw_layer_weights(shape, l, seed=seed, device=device, weight_std=weight_std)
+            for l in range(shape.num_layers)]
+
+
+def oracle_pool(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, dtype=torch.float64) -> torch.Tensor:
+    """Oracle-layout pool [L, 2, blocks, slot, nkv, d]: cached context drawn, everything else NaN."""
+    osh = oracle_shape(shape)
+    pool = oracle.new_pool(osh, mb.num_kv_blocks, dtype=dtype)
+    valid = synth.valid_slot_mask(mb, shape.kv_block_size)                 # [blocks, slot]
+    used_blocks = torch.nonzero(valid.any(dim=1)).flatten()
+    if used_blocks.numel() == 0:
+        return pool
+    for l in range(shape.num_layers):
+        for kv in (0, 1):
+            vals = synth.draw_kv_blocks(shape, mb.num_kv_blocks, l, kv, used_blocks, seed=seed).to(dtype)
+            m = valid[used_blocks].view(-1, shape.kv_block_size, 1, 1)
+            vals = torch.where(m, vals, torch.full_like(vals, float("nan")))
+            pool[l, kv, used_blocks] = vals
+    return pool
+
+
+def rel_l2(a: torch.Tensor, b: torch.Tensor) -> float:
+    a = a.double()
+    b = b.double()
+    return float((a - b).norm() / b.norm().clamp_min(1e-300))

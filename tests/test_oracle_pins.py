@@ -1,0 +1,412 @@
+"""Pins for the CPU oracle: brute force, invariants, closed forms, library cross-checks.
+
+The paper prints no numbers for a stage's forward pass (it leaves the computation to its
+engine runtime, section 3.2.2), so the oracle is pinned to the mathematics of the decoder
+block instead of to printed values.
+"""
+import math
+
+import pytest
+import torch
+
+import oracle
+from paper_2507_05043_amd import synth
+from tests import brute_force
+from tests.helpers import draw_layers, oracle_pool, oracle_shape, rel_l2
+
+F64 = torch.float64
+
+
+def small_shape(**kw):
+    base = dict(name="pin", num_layers=2, hidden=24, num_q_heads=4, num_kv_heads=2, head_dim=8, ffn=40,
+                rms_eps=1e-5, rope_theta=1e4, kv_block_size=16)
+    base.update(kw)
+    return synth.StageShape(**base)
+
+
+def run_oracle(shape, mb, seed=0, weight_std="fan_in", layers=None, hidden=None, pool=None, taps=None):
+    layers = layers if layers is not None else draw_layers(shape, seed, weight_std)
+    hidden = hidden if hidden is not None else synth.draw_hidden(shape, mb.num_tokens, seed=seed)
+    pool = pool if pool is not None else oracle_pool(shape, mb, seed)
+    out, slots = oracle.stage_forward(oracle_shape(shape), layers, hidden, mb.positions, mb.q_lens,
+                                      mb.ctx_lens, mb.block_tables, pool, taps=taps)
+    return out, slots, pool
+
+
+# ---------------------------------------------------------------- brute force, whole block
+
+@pytest.mark.parametrize("nq,nkv", [(4, 2), (3, 3), (4, 1)])
+def test_whole_stage_matches_scalar_loops(nq, nkv):
+    shape = small_shape(num_q_heads=nq, num_kv_heads=nkv, hidden=12, ffn=20, head_dim=4, kv_block_size=4)
+    q_lens, ctx_lens = [5, 1, 3], [0, 6, 2]
+    mb = synth.make_microbatch(q_lens, ctx_lens, seed=3, block=4)
+    layers = draw_layers(shape, 3, "fan_in")
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=3)
+    pool = oracle_pool(shape, mb, 3)
+    pool0 = pool.clone()
+    out, _, _ = run_oracle(shape, mb, layers=layers, hidden=hidden, pool=pool)
+    # contiguous per-sequence caches for the scalar version, read from the pre-call pool
+    got = []
+    row0 = 0
+    x_rows = hidden.double().tolist()
+    for s, (q, c) in enumerate(zip(q_lens, ctx_lens)):
+        rows = x_rows[row0:row0 + q]
+        for l in range(shape.num_layers):
+            w = {k: v.double().tolist() for k, v in layers[l].items()}
+            ck, cv = [], []
+            for j in range(c):
+                blk = int(mb.block_tables[s][j // 4])
+                ck.append(pool0[l, 0, blk, j % 4].tolist())
+                cv.append(pool0[l, 1, blk, j % 4].tolist())
+            pos = list(range(c, c + q))
+            rows = brute_force.layer_one_sequence(shape, w, rows, pos, ck, cv)
+        got.extend(rows)
+        row0 += q
+    got = torch.tensor(got, dtype=F64)
+    assert torch.allclose(out, got, rtol=1e-10, atol=1e-11), float((out - got).abs().max())
+
+
+# ---------------------------------------------------------------- attention
+
+def dense_attention_reference(q, keys, vals, ctx):
+    """Full score matrix with -inf mask and fp64 softmax on contiguous K/V, per head, no GQA trick."""
+    n, nq, d = q.shape
+    g = nq // keys.shape[1]
+    out = torch.zeros(n, nq, d, dtype=F64)
+    for h in range(nq):
+        for i in range(n):
+            e = torch.full((keys.shape[0],), float("-inf"), dtype=F64)
+            for j in range(ctx + i + 1):
+                e[j] = torch.dot(q[i, h], keys[j, h // g]) / math.sqrt(d)
+            w = torch.softmax(e, dim=0)
+            for j in range(ctx + i + 1):
+                out[i, h] += w[j] * vals[j, h // g]
+    return out
+
+
+def test_attention_matches_dense_brute_force():
+    torch.manual_seed(1)
+    for (n, ctx, nq, nkv, d) in [(1, 0, 2, 1, 4), (1, 9, 4, 2, 8), (6, 0, 4, 4, 8), (5, 7, 6, 2, 4)]:
+        q = torch.randn(n, nq, d, dtype=F64)
+        k = torch.randn(ctx + n, nkv, d, dtype=F64)
+        v = torch.randn(ctx + n, nkv, d, dtype=F64)
+        got = oracle.attention_rows(q, k, v, ctx)
+        assert torch.allclose(got, dense_attention_reference(q, k, v, ctx), rtol=1e-12, atol=1e-13)
+
+
+def test_attention_matches_library_sdpa():
+    torch.manual_seed(2)
+    n, ctx, nq, nkv, d = 7, 5, 6, 3, 16
+    q = torch.randn(n, nq, d, dtype=F64)
+    k = torch.randn(ctx + n, nkv, d, dtype=F64)
+    v = torch.randn(ctx + n, nkv, d, dtype=F64)
+    mask = torch.arange(ctx + n).view(1, -1) <= (ctx + torch.arange(n)).view(-1, 1)
+    kk = k.repeat_interleave(nq // nkv, dim=1)
+    vv = v.repeat_interleave(nq // nkv, dim=1)
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        q.transpose(0, 1)[None], kk.transpose(0, 1)[None], vv.transpose(0, 1)[None], attn_mask=mask)
+    assert torch.allclose(oracle.attention_rows(q, k, v, ctx), ref[0].transpose(0, 1), rtol=1e-12, atol=1e-13)
+
+
+def test_softmax_degenerate_cases():
+    torch.manual_seed(3)
+    n, ctx, nq, nkv, d = 3, 4, 2, 1, 8
+    q = torch.randn(n, nq, d, dtype=F64)
+    v = torch.randn(ctx + n, nkv, d, dtype=F64)
+    # identical keys -> uniform weights -> running mean of the visible values
+    k = torch.randn(1, nkv, d, dtype=F64).expand(ctx + n, nkv, d).contiguous()
+    o = oracle.attention_rows(q, k, v, ctx)
+    for i in range(n):
+        assert torch.allclose(o[i, 0], v[: ctx + i + 1, 0].mean(dim=0), rtol=1e-12, atol=1e-13)
+    # identical values -> that value, whatever the scores
+    k = torch.randn(ctx + n, nkv, d, dtype=F64)
+    v1 = torch.randn(1, nkv, d, dtype=F64).expand(ctx + n, nkv, d).contiguous()
+    o = oracle.attention_rows(q, k, v1, ctx)
+    assert torch.allclose(o, v1[0, 0].expand_as(o), rtol=1e-12, atol=1e-13)
+    # one visible key -> its value
+    o = oracle.attention_rows(q[:1], k[:1], v[:1], 0)
+    assert torch.allclose(o[0, 1], v[0, 0], rtol=0, atol=1e-15)
+    # causal: changing a future key/value does not change an earlier row
+    k2, v2 = k.clone(), v.clone()
+    k2[-1] += 5.0
+    v2[-1] -= 3.0
+    o1 = oracle.attention_rows(q, k, v, ctx)
+    o2 = oracle.attention_rows(q, k2, v2, ctx)
+    assert torch.equal(o1[:-1], o2[:-1]) and not torch.allclose(o1[-1], o2[-1])
+    # the 1/sqrt(d) scale: one hot query against two keys gives softmax of (k/sqrt(d))
+    qh = torch.zeros(1, 1, 4, dtype=F64)
+    qh[0, 0, 0] = 2.0
+    kk = torch.zeros(2, 1, 4, dtype=F64)
+    kk[1, 0, 0] = 3.0
+    vv = torch.tensor([[[1.0, 0, 0, 0]], [[0, 1.0, 0, 0]]], dtype=F64)
+    o = oracle.attention_rows(qh, kk, vv, 1)
+    p1 = math.exp(3.0) / (1 + math.exp(3.0))       # 2*3/sqrt(4) = 3
+    assert torch.allclose(o[0, 0, :2], torch.tensor([1 - p1, p1], dtype=F64), rtol=1e-13, atol=0)
+
+
+def test_gqa_equals_mha_with_replicated_kv_heads():
+    shape = small_shape(num_layers=1)
+    g = shape.num_q_heads // shape.num_kv_heads
+    mb = synth.make_microbatch([4, 1], [0, 5], seed=1)
+    layers = draw_layers(shape, 1, "fan_in")
+    out, _, pool = run_oracle(shape, mb, seed=1, layers=layers)
+    d, nq, nkv = shape.head_dim, shape.num_q_heads, shape.num_kv_heads
+    mha = synth.StageShape("mha", 1, shape.hidden, nq, nq, d, shape.ffn)
+    w = dict(layers[0])
+    wq, wk, wv = w["wqkv"][: nq * d], w["wqkv"][nq * d:(nq + nkv) * d], w["wqkv"][(nq + nkv) * d:]
+    rep = lambda m: m.view(nkv, d, -1).repeat_interleave(g, dim=0).reshape(nq * d, -1)
+    w["wqkv"] = torch.cat([wq, rep(wk), rep(wv)], dim=0)
+    pool_g = oracle_pool(shape, mb, 1)
+    pool_m = pool_g.repeat_interleave(g, dim=4)
+    out_m, _ = oracle.stage_forward(oracle_shape(mha), [w], synth.draw_hidden(shape, mb.num_tokens, seed=1),
+                                    mb.positions, mb.q_lens, mb.ctx_lens, mb.block_tables, pool_m)
+    assert torch.allclose(out, out_m, rtol=1e-12, atol=1e-13)
+    # and the mapping is h // g, not h % nkv: permuting kv heads the other way changes the result
+    assert g > 1
+
+
+# ---------------------------------------------------------------- paging, chunking, batching
+
+def test_paged_equals_contiguous_bitwise():
+    shape = small_shape()
+    q_lens, ctx_lens = [7, 1, 1, 20], [0, 33, 5, 11]
+    mb_p = synth.make_microbatch(q_lens, ctx_lens, seed=5, paging="permuted")
+    mb_c = synth.make_microbatch(q_lens, ctx_lens, seed=5, paging="identity")
+    assert not torch.equal(mb_p.block_tables, mb_c.block_tables)
+    layers = draw_layers(shape, 5, "fan_in")
+    hidden = synth.draw_hidden(shape, mb_p.num_tokens, seed=5)
+    # same logical cache contents in both layouts
+    torch.manual_seed(0)
+    pool_p = oracle.new_pool(oracle_shape(shape), mb_p.num_kv_blocks)
+    pool_c = oracle.new_pool(oracle_shape(shape), mb_c.num_kv_blocks)
+    for s, c in enumerate(ctx_lens):
+        for j in range(c):
+            val = torch.randn(shape.num_layers, 2, shape.num_kv_heads, shape.head_dim, dtype=F64)
+            pool_p[:, :, int(mb_p.block_tables[s][j // 16]), j % 16] = val
+            pool_c[:, :, int(mb_c.block_tables[s][j // 16]), j % 16] = val
+    out_p, slots_p, _ = run_oracle(shape, mb_p, layers=layers, hidden=hidden, pool=pool_p)
+    out_c, slots_c, _ = run_oracle(shape, mb_c, layers=layers, hidden=hidden, pool=pool_c)
+    assert torch.equal(out_p, out_c)
+    assert slots_p != slots_c
+    # logical cache contents equal after the call
+    for s, (q, c) in enumerate(zip(q_lens, ctx_lens)):
+        for j in range(c + q):
+            a = pool_p[:, :, int(mb_p.block_tables[s][j // 16]), j % 16]
+            b = pool_c[:, :, int(mb_c.block_tables[s][j // 16]), j % 16]
+            assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("chunks", [[5, 11, 16], [31, 1], [1] * 6 + [26]])
+def test_chunked_prefill_equals_unsplit(chunks):
+    shape = small_shape()
+    n = sum(chunks)
+    layers = draw_layers(shape, 7, "fan_in")
+    hidden = synth.draw_hidden(shape, n, seed=7)
+    mb = synth.make_microbatch([n], [0], seed=7)
+    full, _, pool_full = run_oracle(shape, mb, layers=layers, hidden=hidden)
+    pool = oracle.new_pool(oracle_shape(shape), mb.num_kv_blocks)
+    outs, done = [], 0
+    for c in chunks:
+        pos = torch.arange(done, done + c, dtype=torch.int32)
+        o, _ = oracle.stage_forward(oracle_shape(shape), layers, hidden[done:done + c], pos, [c], [done],
+                                    mb.block_tables, pool)
+        outs.append(o)
+        done += c
+    got = torch.cat(outs)
+    assert torch.allclose(got, full, rtol=1e-11, atol=1e-12)
+    used = synth.valid_slot_mask(mb, 16, include_new=True)
+    assert torch.allclose(pool[:, :, used], pool_full[:, :, used], rtol=1e-11, atol=1e-12)
+    assert torch.isnan(pool[:, :, ~used]).all()
+
+
+def test_decode_equals_last_prefill_row():
+    shape = small_shape()
+    n = 19
+    layers = draw_layers(shape, 8, "fan_in")
+    hidden = synth.draw_hidden(shape, n, seed=8)
+    mb = synth.make_microbatch([n], [0], seed=8)
+    full, _, _ = run_oracle(shape, mb, layers=layers, hidden=hidden)
+    pool = oracle.new_pool(oracle_shape(shape), mb.num_kv_blocks)
+    osh = oracle_shape(shape)
+    oracle.stage_forward(osh, layers, hidden[: n - 1], torch.arange(n - 1), [n - 1], [0], mb.block_tables, pool)
+    last, _ = oracle.stage_forward(osh, layers, hidden[n - 1:], torch.tensor([n - 1]), [1], [n - 1],
+                                   mb.block_tables, pool)
+    assert torch.allclose(last[0], full[-1], rtol=1e-11, atol=1e-12)
+
+
+def test_rows_independent_of_batch_composition_and_order():
+    shape = small_shape()
+    q_lens, ctx_lens = [6, 1, 1, 9], [4, 17, 0, 0]
+    mb = synth.make_microbatch(q_lens, ctx_lens, seed=9)
+    layers = draw_layers(shape, 9, "fan_in")
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=9)
+    pool = oracle_pool(shape, mb, 9)
+    out, _, _ = run_oracle(shape, mb, layers=layers, hidden=hidden, pool=pool.clone())
+    # reversed sequence order, same block tables
+    order = [3, 2, 1, 0]
+    cu = [0, 6, 7, 8, 17]
+    rows = torch.cat([torch.arange(cu[s], cu[s + 1]) for s in order])
+    mb_r = synth.MicroBatch([q_lens[s] for s in order], [ctx_lens[s] for s in order],
+                            mb.block_tables[order], mb.positions[rows], mb.num_kv_blocks)
+    out_r, _, _ = run_oracle(shape, mb_r, layers=layers, hidden=hidden[rows], pool=pool.clone())
+    assert torch.allclose(out_r, out[rows], rtol=1e-12, atol=1e-13)
+    # one sequence alone
+    s = 1
+    mb_1 = synth.MicroBatch([q_lens[s]], [ctx_lens[s]], mb.block_tables[s:s + 1],
+                            mb.positions[cu[s]:cu[s + 1]], mb.num_kv_blocks)
+    out_1, _, _ = run_oracle(shape, mb_1, layers=layers, hidden=hidden[cu[s]:cu[s + 1]], pool=pool.clone())
+    assert torch.allclose(out_1, out[cu[s]:cu[s + 1]], rtol=1e-12, atol=1e-13)
+
+
+# ---------------------------------------------------------------- slots and pool writes
+
+def test_slot_mapping_closed_form_and_pool_diff():
+    shape = small_shape()
+    q_lens, ctx_lens = [18, 1, 1], [15, 16, 31]
+    mb = synth.make_microbatch(q_lens, ctx_lens, seed=11)
+    slots = oracle.slot_mapping(q_lens, ctx_lens, mb.block_tables, 16)
+    # enumerate every logical position of every sequence and keep the new ones
+    expect = []
+    for s, (q, c) in enumerate(zip(q_lens, ctx_lens)):
+        logical_to_slot = {}
+        for b, blk in enumerate(mb.block_tables[s].tolist()):
+            for o in range(16):
+                logical_to_slot[b * 16 + o] = blk * 16 + o
+        expect += [logical_to_slot[j] for j in range(c, c + q)]
+    assert slots == expect and len(set(slots)) == len(slots)
+    pool = oracle_pool(shape, mb, 11)
+    before = pool.clone()
+    _, slots2, _ = run_oracle(shape, mb, seed=11, pool=pool)
+    assert slots2 == slots
+    flat_b = before.view(shape.num_layers, 2, -1, shape.num_kv_heads, shape.head_dim)
+    flat_a = pool.view(shape.num_layers, 2, -1, shape.num_kv_heads, shape.head_dim)
+    changed = ~((flat_a == flat_b) | (torch.isnan(flat_a) & torch.isnan(flat_b))).all(dim=-1).all(dim=-1)
+    want = torch.zeros(mb.num_kv_blocks * 16, dtype=torch.bool)
+    want[slots] = True
+    assert torch.equal(changed, want.expand(shape.num_layers, 2, -1))
+    assert not torch.isnan(flat_a[:, :, slots]).any()
+
+
+def test_poisoned_slots_never_reach_output():
+    shape = small_shape()
+    mb = synth.make_microbatch([9, 1, 1], [3, 16, 40], seed=12)
+    out, _, _ = run_oracle(shape, mb, seed=12)
+    assert torch.isfinite(out).all()
+
+
+# ---------------------------------------------------------------- RMSNorm, RoPE, SwiGLU closed forms
+
+def test_rmsnorm_closed_forms():
+    g = torch.tensor([0.5, 2.0, -1.0, 3.0], dtype=F64)
+    c, eps = 3.0, 1e-5
+    a = oracle.rmsnorm(torch.full((1, 4), c, dtype=F64), g, eps)
+    assert torch.allclose(a[0], g * c / math.sqrt(c * c + eps), rtol=1e-15)
+    x = torch.tensor([[1.0, -2.0, 3.0, 0.5]], dtype=F64)
+    ms = float((x * x).mean())
+    a = oracle.rmsnorm(x, g, eps)
+    assert math.isclose(float(((a / g) ** 2).mean()), 1 - eps / (ms + eps), rel_tol=1e-13)
+    # scale invariance when eps is negligible
+    assert torch.allclose(oracle.rmsnorm(x, g, 0.0), oracle.rmsnorm(7.0 * x, g, 0.0), rtol=1e-14)
+    # eps sits inside the square root, added to the mean square
+    assert math.isclose(float(oracle.rmsnorm(torch.zeros(1, 4, dtype=F64) + 1e-3, g, 1.0)[0, 1]),
+                        2.0 * 1e-3 / math.sqrt(1e-6 + 1.0), rel_tol=1e-14)
+
+
+def test_rope_closed_forms():
+    torch.manual_seed(4)
+    u = torch.randn(5, 3, 8, dtype=F64)
+    pos = torch.tensor([0, 1, 7, 100, 8191])
+    y = oracle.rope_rotate(u, pos, 1e4)
+    assert torch.equal(y[0], u[0])                                            # position 0 is the identity
+    assert torch.allclose(y.norm(dim=-1), u.norm(dim=-1), rtol=1e-13)         # rotations keep the norm
+    # d = 2: a plain 2-D rotation by pos radians (theta**0 = 1)
+    v = torch.tensor([[[1.0, 0.0]], [[0.0, 1.0]]], dtype=F64)
+    r = oracle.rope_rotate(v, torch.tensor([2, 3]), 1e4)
+    assert torch.allclose(r[0, 0], torch.tensor([math.cos(2), math.sin(2)], dtype=F64), rtol=1e-14)
+    assert torch.allclose(r[1, 0], torch.tensor([-math.sin(3), math.cos(3)], dtype=F64), rtol=1e-14)
+    # half-split pairing with per-pair frequency theta**(-2i/d): element i pairs with i + d/2
+    d, theta, p = 8, 1e4, 5
+    e = torch.zeros(1, 1, d, dtype=F64)
+    e[0, 0, 1] = 1.0
+    z = oracle.rope_rotate(e, torch.tensor([p]), theta)[0, 0]
+    ang = p * theta ** (-2.0 * 1 / d)
+    expect = torch.zeros(d, dtype=F64)
+    expect[1], expect[1 + d // 2] = math.cos(ang), math.sin(ang)
+    assert torch.allclose(z, expect, rtol=1e-14, atol=1e-16)
+    # relative property: <R_p q, R_s k> depends on p - s only
+    q, k = torch.randn(1, 1, 8, dtype=F64), torch.randn(1, 1, 8, dtype=F64)
+    dot = lambda p_, s_: float((oracle.rope_rotate(q, torch.tensor([p_]), theta)
+                                * oracle.rope_rotate(k, torch.tensor([s_]), theta)).sum())
+    assert math.isclose(dot(9, 4), dot(105, 100), rel_tol=1e-10)
+    assert not math.isclose(dot(9, 4), dot(9, 5), rel_tol=1e-3)
+
+
+def test_positions_shift_leaves_fresh_prefill_unchanged_and_is_separate_from_ctx():
+    shape = small_shape()
+    layers = draw_layers(shape, 13, "fan_in")
+    hidden = synth.draw_hidden(shape, 11, seed=13)
+    mb0 = synth.make_microbatch([11], [0], seed=13)
+    mb1 = synth.make_microbatch([11], [0], seed=13, position_shift=37)
+    o0, s0, _ = run_oracle(shape, mb0, layers=layers, hidden=hidden)
+    o1, s1, _ = run_oracle(shape, mb1, layers=layers, hidden=hidden)
+    assert s0 == s1                                  # slots follow ctx + i, not positions
+    assert torch.allclose(o0, o1, rtol=1e-9, atol=1e-10)   # attention sees only position differences
+
+
+def test_silu_and_swiglu_limits():
+    z = torch.tensor([0.0, 40.0, -40.0, 1.0], dtype=F64)
+    s = oracle.silu(z)
+    assert s[0] == 0.0 and math.isclose(float(s[1]), 40.0, rel_tol=1e-15) and abs(float(s[2])) < 1e-15
+    assert math.isclose(float(s[3]), 1.0 / (1.0 + math.exp(-1.0)), rel_tol=1e-15)
+    shape = small_shape(num_layers=1)
+    mb = synth.make_microbatch([3], [0], seed=14)
+    layers = draw_layers(shape, 14, "fan_in")
+    layers[0]["wgate"] = torch.zeros_like(layers[0]["wgate"])
+    taps = []
+    out, _, _ = run_oracle(shape, mb, layers=layers, taps=taps)
+    assert torch.equal(taps[0]["m"], torch.zeros_like(taps[0]["m"])) and torch.equal(out, taps[0]["h"])
+
+
+def test_zero_output_projections_give_identity():
+    shape = small_shape()
+    mb = synth.make_microbatch([5, 1], [0, 9], seed=15)
+    layers = draw_layers(shape, 15, "fan_in")
+    for w in layers:
+        w["wo"] = torch.zeros_like(w["wo"])
+        w["wdown"] = torch.zeros_like(w["wdown"])
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=15)
+    out, _, _ = run_oracle(shape, mb, seed=15, layers=layers, hidden=hidden)
+    assert torch.equal(out, hidden.double())
+
+
+def test_single_token_layer_reduces_to_matmul_chain():
+    """One fresh token: attention returns its own value vector, so the layer is a chain of
+    matrix products; cross-check against numpy float64 written with explicit transposes."""
+    import numpy as np
+    shape = small_shape(num_layers=1)
+    mb = synth.make_microbatch([1], [0], seed=16)
+    layers = draw_layers(shape, 16, "fan_in")
+    hidden = synth.draw_hidden(shape, 1, seed=16)
+    out, _, _ = run_oracle(shape, mb, layers=layers, hidden=hidden)
+    w = {k: v.double().numpy() for k, v in layers[0].items()}
+    x = hidden.double().numpy()[0]
+    nq, nkv, d = shape.num_q_heads, shape.num_kv_heads, shape.head_dim
+    a = x * w["norm1"] / np.sqrt(np.mean(x * x) + shape.rms_eps)
+    v = (w["wqkv"][(nq + nkv) * d:] @ a).reshape(nkv, d)          # position 0: no rotation
+    o = np.concatenate([v[h // (nq // nkv)] for h in range(nq)])
+    h = x + w["wo"] @ o
+    b = h * w["norm2"] / np.sqrt(np.mean(h * h) + shape.rms_eps)
+    gate, up = w["wgate"] @ b, w["wup"] @ b
+    y = h + w["wdown"] @ (gate / (1 + np.exp(-gate)) * up)
+    assert np.allclose(out[0].numpy(), y, rtol=1e-12, atol=1e-13)
+
+
+def test_synthetic_generator_is_deterministic_and_sliceable():
+    a = synth.draw_normal_bf16(0, 5, 1000)
+    b = synth.draw_normal_bf16(0, 5, 400, offset=300)
+    assert torch.equal(a[300:700], b)
+    idx = torch.tensor([999, 0, 512], dtype=torch.int64)
+    assert torch.equal(synth.draw_normal_bf16_at(0, 5, idx), a[idx])
+    assert not torch.equal(a, synth.draw_normal_bf16(1, 5, 1000))
+    x = synth.draw_normal_bf16(0, 6, 200000).float()
+    assert abs(float(x.mean())) < 0.01 and abs(float(x.std()) - 1.0) < 0.01
