@@ -1,0 +1,210 @@
+/*
+ * molink_stage.h -- C ABI of one pipeline stage's decoder-layer forward pass on one MI355X.
+ *
+ * The serving system launches every inference engine with the run of consecutive decoder
+ * layers assigned to it (paper section 3.2.1) and feeds it micro-batches that mix prefill
+ * chunks and decode tokens; the engine's runtime holds the weights, runs the micro-batch through
+ * them and hands the resulting intermediate activations to the next stage (paper section
+ * 3.2.2, "Distributed Inference Engine").  That output is one hidden vector per processed
+ * token (section 4.2).  This library is that computation:
+ *   stage_init     -- bind the stage's layer weights, a paged KV pool and a workspace;
+ *   stage_forward  -- run all layers on one micro-batch and write the packed activations.
+ *
+ * Per layer (Llama-style pre-norm block, bf16 storage, fp32 accumulation):
+ *   a = RMSNorm(x; norm1)            q,k,v = a Wqkv^T        q,k <- RoPE(q,k; positions)
+ *   append k,v to the paged pool     o = causal GQA attention of q over the sequence's cache
+ *   h = x + o Wo^T                   b = RMSNorm(h; norm2)
+ *   x' = h + (silu(b Wgate^T) * (b Wup^T)) Wdown^T
+ *
+ * All device buffers (weights, KV pool, workspace, input, output) are allocated and owned by
+ * the caller and must stay valid until stage_destroy; the library allocates no device memory.
+ * Every entry point returns 0 on success or a negative STAGE_ERR_* code and never throws;
+ * stage_last_error() gives a message for the calling thread's last failure.
+ *
+ * The library targets gfx950 only and requires kv_block_size == 16, head_dim in {64, 128},
+ * hidden, ffn and num_q_heads*head_dim multiples of 8, num_q_heads a multiple of num_kv_heads
+ * with at most 16 query heads per KV head.
+ */
+#ifndef MOLINK_STAGE_H
+#define MOLINK_STAGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  STAGE_OK = 0,
+  STAGE_ERR_NULL = -1,        /* a required pointer is NULL */
+  STAGE_ERR_CONFIG = -2,      /* unsupported or inconsistent stage_config */
+  STAGE_ERR_SIZE = -3,        /* a caller buffer is too small */
+  STAGE_ERR_BATCH = -4,       /* micro-batch metadata invalid (lengths, counts, capacity) */
+  STAGE_ERR_BLOCK_TABLE = -5, /* block table too short, or a used block id out of range */
+  STAGE_ERR_HIP = -6,         /* a HIP runtime call failed (message has the HIP error string) */
+  STAGE_ERR_ALIAS = -7        /* hidden_out overlaps hidden_in */
+};
+
+/* Plain data, versioned by struct_size (= sizeof(stage_config) of the caller's header). */
+typedef struct {
+  uint32_t struct_size;
+  int32_t num_layers;          /* L: decoder layers hosted by this stage */
+  int32_t hidden;              /* H */
+  int32_t num_q_heads;         /* nq */
+  int32_t num_kv_heads;        /* nkv; query head h reads KV head h / (nq / nkv) */
+  int32_t head_dim;            /* d: 64 or 128 */
+  int32_t ffn;                 /* F: SwiGLU inner width */
+  float rms_eps;               /* added to the mean square inside the square root */
+  float rope_theta;            /* RoPE base; pair (i, i + d/2) turns by position * theta^(-2i/d) */
+  int32_t kv_block_size;       /* tokens per KV block; must be 16 */
+  int32_t num_kv_blocks;       /* blocks in each layer's pool */
+  int64_t kv_layer_stride_bytes; /* distance between consecutive layers' pools; >= stage_kv_layer_bytes,
+                                    or 0 to alias every layer onto one pool (timing experiments only:
+                                    values are then meaningless) */
+  int32_t max_tokens;          /* capacity: new tokens per micro-batch (T) */
+  int32_t max_seqs;            /* capacity: sequences per micro-batch (S) */
+  int32_t max_blocks_per_seq;  /* row length of block_tables */
+} stage_config;
+
+/* Device pointers to one layer's bf16 weights, row-major [out_features][in_features]. Borrowed, read-only. */
+typedef struct {
+  const void *norm1;  /* [H]  gain of the input RMSNorm */
+  const void *wqkv;   /* [(nq + 2 nkv) d][H]: q head rows, then k head rows, then v head rows */
+  const void *wo;     /* [H][nq d] */
+  const void *norm2;  /* [H]  gain of the post-attention RMSNorm */
+  const void *wgate;  /* [F][H] */
+  const void *wup;    /* [F][H] */
+  const void *wdown;  /* [H][F] */
+} stage_layer_weights;
+
+typedef struct stage_handle stage_handle;
+
+/*
+ * KV pool layout (part of the ABI: the caller pre-fills the cached context).
+ * Layer l starts at kv_pool + l * kv_layer_stride_bytes and holds two bf16 regions:
+ *   K: [num_kv_blocks][nkv][16 slots][d]      one cached key vector is d contiguous elements
+ *   V: [num_kv_blocks][nkv][d][16 slots]      values are stored transposed inside a block
+ * The V region starts stage_kv_layer_bytes/2 bytes after the K region.  Token j of a sequence
+ * lives in block block_table[j / 16] at slot j % 16.
+ * stage_kv_layer_bytes: bytes of one layer's pool (both regions).
+ */
+int stage_kv_layer_bytes(const stage_config *cfg, size_t *out_bytes);
+
+/*
+ * Element offset (in bf16 elements from the start of a layer's pool) of cached element
+ * (kv = 0 key / 1 value, block, kv_head, slot, dim).  Host-only helper for callers and tests.
+ */
+int stage_kv_element_offset(const stage_config *cfg, int32_t kv, int32_t block, int32_t kv_head,
+                            int32_t slot, int32_t dim, int64_t *out_offset);
+
+/*
+ * Host-only check of a micro-batch against a configuration: exactly the validation stage_forward
+ * performs before it enqueues anything (same arguments, same error codes), usable without a GPU.
+ * On success, and if slot_mapping_out is not NULL, writes the pool slot of every row as
+ * stage_forward would report it.
+ */
+int stage_check_batch(const stage_config *cfg, int32_t num_tokens, const int32_t *positions,
+                      int32_t num_seqs, const int32_t *q_lens, const int32_t *ctx_lens,
+                      const int32_t *block_tables, int64_t *slot_mapping_out);
+
+/* Bytes of device workspace stage_init needs for this config (activations, split-K and
+ * split-KV partial results, per-call metadata). */
+int stage_workspace_bytes(const stage_config *cfg, size_t *out_bytes);
+
+/*
+ * Create a stage.  layers: host array [num_layers] of device-pointer structs (copied).
+ * kv_pool / workspace: device memory, 256-byte aligned, of at least kv_pool_bytes >=
+ * (L-1)*stride + stage_kv_layer_bytes and stage_workspace_bytes.  device: HIP device ordinal
+ * that owns all buffers.  No kernel is launched and no device memory is touched.
+ * Errors: STAGE_ERR_NULL, STAGE_ERR_CONFIG, STAGE_ERR_SIZE, STAGE_ERR_HIP.
+ */
+int stage_init(const stage_config *cfg, const stage_layer_weights *layers, void *kv_pool,
+               size_t kv_pool_bytes, void *workspace, size_t workspace_bytes, int32_t device,
+               stage_handle **out);
+
+/*
+ * Run the stage's layers on one micro-batch, asynchronously on hip_stream (a hipStream_t;
+ * NULL = the default stream).
+ *   num_tokens T      rows of hidden_in / hidden_out; T == sum(q_lens), 0 < T <= max_tokens
+ *   hidden_in         device bf16 [T][H]; sequences packed one after another
+ *   positions         host int32 [T]; RoPE position of every row (>= 0)
+ *   num_seqs S        0 < S <= max_seqs
+ *   q_lens            host int32 [S]; new tokens of each sequence (1 = decode token, >1 = prefill chunk)
+ *   ctx_lens          host int32 [S]; tokens of the sequence already cached (>= 0)
+ *   block_tables      host int32 [S][max_blocks_per_seq]; entries beyond ceil((ctx+q)/16) are ignored
+ *   hidden_out        device bf16 [T][H]; row t is the output for input row t (the activation
+ *                     payload for the next stage).  Must not overlap hidden_in.
+ *   slot_mapping_out  host int64 [T] or NULL; receives, for every row, the pool slot
+ *                     block_table[j/16]*16 + j%16 (j = ctx + offset in the chunk) its K/V is written to
+ * Row i of a sequence attends to cached tokens 0..ctx-1 and to rows 0..i of its own chunk.
+ * All metadata is validated on the host before anything is enqueued: on error nothing was
+ * launched and the KV pool is unchanged.  The host arrays may be reused as soon as the call
+ * returns.  The call does not synchronise; asynchronous HIP failures surface at the caller's
+ * next synchronisation.  One handle must not be used from two threads at once, and calls on
+ * one handle must be issued to streams that execute them in order (the workspace is shared).
+ * Errors: STAGE_ERR_NULL, STAGE_ERR_BATCH, STAGE_ERR_BLOCK_TABLE, STAGE_ERR_ALIAS, STAGE_ERR_HIP.
+ */
+int stage_forward(stage_handle *st, void *hip_stream, int32_t num_tokens, const void *hidden_in,
+                  const int32_t *positions, int32_t num_seqs, const int32_t *q_lens,
+                  const int32_t *ctx_lens, const int32_t *block_tables, void *hidden_out,
+                  int64_t *slot_mapping_out);
+
+/*
+ * Debug taps (for parity tests).  Same as stage_forward, and additionally copies, for layer
+ * tap_layer, intermediate tensors into caller device buffers (any may be NULL to skip):
+ *   tap_norm1 bf16 [T][H]            RMSNorm output a
+ *   tap_qkv   bf16 [T][(nq+2nkv)d]   projection output with q and k already rotated
+ *   tap_attn  bf16 [T][nq d]         attention output
+ *   tap_h     f32  [T][H]            residual stream after the attention branch
+ *   tap_mlp   bf16 [T][F]            silu(gate) * up
+ *   tap_x     f32  [T][H]            residual stream after the layer
+ */
+typedef struct {
+  int32_t tap_layer;
+  void *tap_norm1, *tap_qkv, *tap_attn, *tap_h, *tap_mlp, *tap_x;
+} stage_taps;
+
+int stage_forward_taps(stage_handle *st, void *hip_stream, int32_t num_tokens, const void *hidden_in,
+                       const int32_t *positions, int32_t num_seqs, const int32_t *q_lens,
+                       const int32_t *ctx_lens, const int32_t *block_tables, void *hidden_out,
+                       int64_t *slot_mapping_out, const stage_taps *taps);
+
+/*
+ * Per-kernel timing with HIP events recorded on the stream the kernels are launched on.
+ * stage_profile_enable(st, mask): bit k of mask turns timing of kernel class k on (0 = off).
+ * stage_profile_read: synchronises the events recorded so far, adds up the elapsed time of
+ * class `kernel` and returns it with the number of timed launches, then forgets them.
+ * At most 8192 launches are kept between two reads; later ones are not timed.
+ */
+enum {
+  STAGE_K_RMSNORM = 0,
+  STAGE_K_GEMM_QKV = 1,
+  STAGE_K_ROPE_APPEND = 2,
+  STAGE_K_ATTN_PREFILL = 3,
+  STAGE_K_ATTN_DECODE = 4,
+  STAGE_K_ATTN_MERGE = 5,
+  STAGE_K_GEMM_O = 6,
+  STAGE_K_GEMM_GATEUP = 7,
+  STAGE_K_GEMM_DOWN = 8,
+  STAGE_K_SPLITK_REDUCE = 9,
+  STAGE_K_ROPE_TABLE = 10,
+  STAGE_K_COUNT = 11
+};
+int stage_profile_enable(stage_handle *st, uint32_t kernel_mask);
+int stage_profile_read(stage_handle *st, int32_t kernel, double *out_total_ms, int64_t *out_launches);
+
+/* Name of the device kernel (as a profiler lists it) that implements a kernel class for this stage's shapes
+ * at the given token count; for matching profiler output.  Returns NULL for an unknown class. */
+const char *stage_kernel_name(int32_t kernel);
+
+/* Release the handle (host memory, events, pinned staging).  Synchronises the device first. */
+void stage_destroy(stage_handle *st);
+
+/* Message describing the calling thread's most recent error ("" if none). */
+const char *stage_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOLINK_STAGE_H */

@@ -1,0 +1,53 @@
+// Shared device-side types and small helpers for the gfx950 stage kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace molink {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int kWave = 64;        // lanes per wavefront
+constexpr int kKvBlock = 16;     // tokens per KV block (fixed by the ABI)
+
+__device__ __forceinline__ float bf16_to_f32(__bf16 v) { return static_cast<float>(v); }
+__device__ __forceinline__ __bf16 f32_to_bf16(float v) { return static_cast<__bf16>(v); }
+
+// widen the low / high bf16 of a packed 32-bit word
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  bf16x2 p;
+  p[0] = static_cast<__bf16>(lo);
+  p[1] = static_cast<__bf16>(hi);
+  return __builtin_bit_cast(uint32_t, p);
+}
+
+// 16-byte global load / store of 8 bf16
+__device__ __forceinline__ bf16x8 load8(const __bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }
+__device__ __forceinline__ void store8(__bf16* p, bf16x8 v) { *reinterpret_cast<bf16x8*>(p) = v; }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// The 8 XCDs take workgroups round-robin.  Remap the hardware workgroup id so that ids that are
+// consecutive in the logical order run on the same XCD (and share its L2).
+// Returns the logical id, or -1 for a padding workgroup.  Launch with xcd_grid(total) workgroups.
+__host__ __device__ __forceinline__ int xcd_grid(int total) { return ((total + 7) / 8) * 8; }
+__device__ __forceinline__ int xcd_logical_id(int pid, int total) {
+  const int per = (total + 7) / 8;
+  const int lid = (pid % 8) * per + pid / 8;
+  return lid < total ? lid : -1;
+}
+
+}  // namespace molink

@@ -1,0 +1,147 @@
+// Bandwidth-bound row kernels of the decoder block: RMSNorm, the RoPE angle table, and the fused
+// RoPE + KV-cache append.  All global accesses are 16-byte vectors along the contiguous dimension,
+// except the transposed V writes of the append (2-byte elements, 32 bytes apart by construction of
+// the V block layout [d][16 slots]).
+#include "elementwise.hpp"
+#include "common.hpp"
+
+namespace molink {
+
+namespace {
+
+template <bool FROM_BF16>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const __bf16* __restrict__ in_bf16, float* __restrict__ x,
+                                                      const __bf16* __restrict__ gain, __bf16* __restrict__ out,
+                                                      int hidden, float eps) {
+  __shared__ float partial[4];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const int chunks = hidden / 8;
+  const __bf16* src_b = in_bf16 + (size_t)row * hidden;
+  float* xr = x + (size_t)row * hidden;
+  float ss = 0.f;
+  for (int c = tid; c < chunks; c += 256) {
+    float v[8];
+    if constexpr (FROM_BF16) {
+      const bf16x8 b = load8(src_b + c * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = bf16_to_f32(b[e]);
+      *reinterpret_cast<float4*>(xr + c * 8) = make_float4(v[0], v[1], v[2], v[3]);
+      *reinterpret_cast<float4*>(xr + c * 8 + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    } else {
+      const float4 p = *reinterpret_cast<const float4*>(xr + c * 8);
+      const float4 q = *reinterpret_cast<const float4*>(xr + c * 8 + 4);
+      v[0] = p.x; v[1] = p.y; v[2] = p.z; v[3] = p.w; v[4] = q.x; v[5] = q.y; v[6] = q.z; v[7] = q.w;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ss += v[e] * v[e];
+  }
+  ss = wave_sum(ss);
+  if ((tid & 63) == 0) partial[tid >> 6] = ss;
+  __syncthreads();
+  const float total = partial[0] + partial[1] + partial[2] + partial[3];
+  const float rs = 1.0f / sqrtf(total / (float)hidden + eps);
+  for (int c = tid; c < chunks; c += 256) {
+    float v[8];
+    if constexpr (FROM_BF16) {
+      const bf16x8 b = load8(src_b + c * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = bf16_to_f32(b[e]);
+    } else {
+      const float4 p = *reinterpret_cast<const float4*>(xr + c * 8);
+      const float4 q = *reinterpret_cast<const float4*>(xr + c * 8 + 4);
+      v[0] = p.x; v[1] = p.y; v[2] = p.z; v[3] = p.w; v[4] = q.x; v[5] = q.y; v[6] = q.z; v[7] = q.w;
+    }
+    const bf16x8 g = load8(gain + c * 8);
+    bf16x8 o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = f32_to_bf16(v[e] * rs * bf16_to_f32(g[e]));
+    store8(out + (size_t)row * hidden + c * 8, o);
+  }
+}
+
+__global__ __launch_bounds__(256) void rope_table_kernel(const int32_t* __restrict__ positions,
+                                                         float2* __restrict__ cos_sin, int rows, int half,
+                                                         double log2_theta) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= rows * half) return;
+  const int t = idx / half, i = idx % half;
+  const double inv_freq = exp2(-(double)i / (double)half * log2_theta);   // theta^(-2i/d), d = 2*half
+  const double ang = (double)positions[t] * inv_freq;
+  double s, c;
+  sincos(ang, &s, &c);
+  cos_sin[idx] = make_float2((float)c, (float)s);
+}
+
+// One workgroup per token row.  Work units of 8 elements:
+//   rotated heads (q then k): unit = (head, chunk of 8 pairs): reads lo/hi halves, rotates, writes back
+//   in place and, for k heads, also into the K pool row of the token's slot;
+//   v heads: unit = (head, chunk of 8 dims): scattered into the transposed V block.
+__global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs p) {
+  const int t = blockIdx.x, tid = threadIdx.x;
+  const int d = p.head_dim, half = d / 2, cpr = half / 8;       // chunks per rotated head
+  const int row_elems = (p.nq + 2 * p.nkv) * d;
+  __bf16* row = p.qkv + (size_t)t * row_elems;
+  const float2* cs = p.cos_sin + (size_t)t * half;
+  const int64_t slot = p.slots[t];
+  const int64_t blk = slot / kKvBlock;
+  const int s = (int)(slot % kKvBlock);
+  const int rot_units = (p.nq + p.nkv) * cpr;
+  const int v_units = p.nkv * (d / 8);
+  for (int u = tid; u < rot_units + v_units; u += 256) {
+    if (u < rot_units) {
+      const int head = u / cpr, c = u % cpr;
+      __bf16* base = row + head * d + c * 8;
+      const bf16x8 lo = load8(base), hi = load8(base + half);
+      bf16x8 olo, ohi;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float2 f = cs[c * 8 + e];
+        const float a = bf16_to_f32(lo[e]), b = bf16_to_f32(hi[e]);
+        olo[e] = f32_to_bf16(a * f.x - b * f.y);
+        ohi[e] = f32_to_bf16(b * f.x + a * f.y);
+      }
+      store8(base, olo);
+      store8(base + half, ohi);
+      if (head >= p.nq) {
+        const int r = head - p.nq;
+        __bf16* dst = p.k_pool + (((size_t)blk * p.nkv + r) * kKvBlock + s) * d + c * 8;
+        store8(dst, olo);
+        store8(dst + half, ohi);
+      }
+    } else {
+      const int w = u - rot_units;
+      const int r = w / (d / 8), c = w % (d / 8);
+      const bf16x8 v = load8(row + (p.nq + p.nkv + r) * d + c * 8);
+      __bf16* dst = p.v_pool + (((size_t)blk * p.nkv + r) * d + c * 8) * kKvBlock + s;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dst[e * kKvBlock] = v[e];
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_rmsnorm(const __bf16* in_bf16, float* x, const __bf16* gain, __bf16* out, int rows, int hidden,
+                          float eps, bool from_bf16, hipStream_t stream) {
+  if (from_bf16)
+    hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(rows), dim3(256), 0, stream, in_bf16, x, gain, out, hidden, eps);
+  else
+    hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(rows), dim3(256), 0, stream, in_bf16, x, gain, out, hidden, eps);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_table(const int32_t* positions, float2* cos_sin, int rows, int head_dim, float theta,
+                             hipStream_t stream) {
+  const int half = head_dim / 2;
+  const int total = rows * half;
+  hipLaunchKernelGGL(rope_table_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, positions, cos_sin, rows, half,
+                     log2((double)theta));
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_append(const RopeAppendArgs& args, hipStream_t stream) {
+  hipLaunchKernelGGL(rope_append_kernel, dim3(args.rows), dim3(256), 0, stream, args);
+  return hipGetLastError();
+}
+
+}  // namespace molink

@@ -1,0 +1,28 @@
+// RMSNorm, RoPE angle table and RoPE + paged KV append (host-side declarations).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace molink {
+
+// a[t][:] = x[t][:] * gain / sqrt(mean(x[t][:]^2) + eps), rounded to bf16.
+// from_bf16: the row source is in_bf16 (the stage input) and the fp32 residual stream x is also
+// initialised from it; otherwise the source is x.
+hipError_t launch_rmsnorm(const __bf16* in_bf16, float* x, const __bf16* gain, __bf16* out, int rows, int hidden,
+                          float eps, bool from_bf16, hipStream_t stream);
+
+// cos_sin[t][i] = (cos, sin)(positions[t] * theta^(-2i/d)), i < d/2, evaluated in fp64.
+hipError_t launch_rope_table(const int32_t* positions, float2* cos_sin, int rows, int head_dim, float theta,
+                             hipStream_t stream);
+
+struct RopeAppendArgs {
+  __bf16* qkv;             // [T][(nq + 2 nkv) d]; q and k heads are rotated in place
+  const float2* cos_sin;   // [T][d/2]
+  const int64_t* slots;    // [T] pool slot of every row
+  __bf16* k_pool;          // this layer's K region [blocks][nkv][16][d]
+  __bf16* v_pool;          // this layer's V region [blocks][nkv][d][16]
+  int rows, nq, nkv, head_dim;
+};
+hipError_t launch_rope_append(const RopeAppendArgs& args, hipStream_t stream);
+
+}  // namespace molink

@@ -1,0 +1,41 @@
+// bf16 MFMA GEMM  C[M][N] = A[M][K] * W[N][K]^T  with fused epilogues (host-side declarations).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace molink {
+
+enum GemmEpilogue : int {
+  kEpiStoreBf16 = 0,    // out_bf16[m][n] = acc
+  kEpiResidualF32 = 1,  // resid[m][n] += acc                      (fp32 residual stream, in place)
+  kEpiResidualOut = 2,  // out_bf16[m][n] = resid[m][n] + acc      (last layer: packed payload)
+  kEpiSwiGLU = 3,       // out_bf16[m][f] = silu(acc_gate[f]) * acc_up[f]
+};
+
+struct GemmArgs {
+  const __bf16* a;      // [M][lda]
+  const __bf16* w0;     // [N][K]; for SwiGLU the gate matrix [F][K]
+  const __bf16* w1;     // SwiGLU only: the up matrix [F][K]
+  __bf16* out_bf16;     // see GemmEpilogue
+  float* resid;         // fp32 residual stream [M][N]
+  float* partial;       // split-K scratch [splits][M][Nv] fp32
+  int m, n, k;          // n = output features (F for SwiGLU)
+  int lda, ldo;         // leading dimensions (elements) of a and out_bf16
+};
+
+struct GemmPlan {
+  int tile;             // 0: 128x128 workgroup tile, 1: 64x128
+  int splits;           // K splits (1 = epilogue fused into the GEMM kernel)
+  int k_tiles_per_split;
+  int nv;               // width of the column space the kernel iterates (2*ceil(F/32)*32 for SwiGLU, else N)
+};
+
+GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus);
+// Floats of split-K scratch that any GEMM with m <= max_m rows of this (n, k, epilogue) may need.
+size_t gemm_partial_floats(int max_m, int n, int k, GemmEpilogue epi, int num_cus);
+
+hipError_t launch_gemm_main(const GemmArgs& args, GemmEpilogue epi, const GemmPlan& plan, hipStream_t stream);
+// Only when plan.splits > 1: sums the partial results in split order and applies the epilogue.
+hipError_t launch_gemm_reduce(const GemmArgs& args, GemmEpilogue epi, const GemmPlan& plan, hipStream_t stream);
+
+}  // namespace molink

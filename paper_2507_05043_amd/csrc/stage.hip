@@ -1,0 +1,630 @@
+// C ABI of the stage library: configuration checks, workspace carving, per-call metadata (slot
+// mapping, work lists) and the launch sequence of one micro-batch.  See include/molink_stage.h.
+#include "../../include/molink_stage.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "attention.hpp"
+#include "elementwise.hpp"
+#include "gemm.hpp"
+
+using namespace molink;
+
+namespace {
+
+thread_local char g_error[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_error, sizeof(g_error), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                          \
+  do {                                                                                         \
+    hipError_t e_ = (expr);                                                                    \
+    if (e_ != hipSuccess) return fail(STAGE_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+constexpr int kStagingSlots = 4;
+constexpr int kMaxTimed = 8192;
+constexpr int kDecodeWavesPerCu = 32;   // decode work items aimed at per CU and KV head group (sets the key-range length)
+constexpr int kMinDecodeRange = 128;    // shortest key range worth a separate work item
+
+struct Dims {
+  int L, H, nq, nkv, d, F, qkv_out, g;
+};
+
+struct WorkspaceLayout {
+  size_t x, a, qkv, attn, mlp, cos_sin, splitk, part_o, part_ml, meta, total;
+  size_t meta_bytes;
+  int max_items, max_tiles;
+};
+
+int check_config(const stage_config* c) {
+  if (!c) return fail(STAGE_ERR_NULL, "stage_config is NULL");
+  if (c->struct_size != sizeof(stage_config))
+    return fail(STAGE_ERR_CONFIG, "stage_config.struct_size %u != %zu", c->struct_size, sizeof(stage_config));
+  if (c->num_layers < 1 || c->hidden < 8 || c->num_q_heads < 1 || c->num_kv_heads < 1 || c->ffn < 8)
+    return fail(STAGE_ERR_CONFIG, "non-positive dimension in stage_config");
+  if (c->kv_block_size != 16) return fail(STAGE_ERR_CONFIG, "kv_block_size must be 16, got %d", c->kv_block_size);
+  if (c->head_dim != 64 && c->head_dim != 128)
+    return fail(STAGE_ERR_CONFIG, "head_dim must be 64 or 128, got %d", c->head_dim);
+  if (c->hidden % 8 || c->ffn % 8) return fail(STAGE_ERR_CONFIG, "hidden and ffn must be multiples of 8");
+  if (c->num_q_heads % c->num_kv_heads) return fail(STAGE_ERR_CONFIG, "num_q_heads must be a multiple of num_kv_heads");
+  if (c->num_q_heads / c->num_kv_heads > 16)
+    return fail(STAGE_ERR_CONFIG, "at most 16 query heads per KV head are supported");
+  if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return fail(STAGE_ERR_CONFIG, "rms_eps must be > 0 and rope_theta > 1");
+  if (c->num_kv_blocks < 1 || c->max_tokens < 1 || c->max_seqs < 1 || c->max_blocks_per_seq < 1)
+    return fail(STAGE_ERR_CONFIG, "capacities must be positive");
+  const size_t layer_bytes = (size_t)c->num_kv_blocks * c->num_kv_heads * 16 * c->head_dim * 2 * 2;
+  if (c->kv_layer_stride_bytes != 0 &&
+      (c->kv_layer_stride_bytes < (int64_t)layer_bytes || c->kv_layer_stride_bytes % 256))
+    return fail(STAGE_ERR_CONFIG, "kv_layer_stride_bytes must be 0 or a multiple of 256 >= %zu", layer_bytes);
+  return STAGE_OK;
+}
+
+Dims dims_of(const stage_config& c) {
+  Dims d;
+  d.L = c.num_layers; d.H = c.hidden; d.nq = c.num_q_heads; d.nkv = c.num_kv_heads; d.d = c.head_dim; d.F = c.ffn;
+  d.qkv_out = (c.num_q_heads + 2 * c.num_kv_heads) * c.head_dim;
+  d.g = c.num_q_heads / c.num_kv_heads;
+  return d;
+}
+
+// Number of compute units the work decomposition is sized for.  The library targets MI355X only.
+constexpr int kNumCus = 256;
+
+int decode_target_items(const Dims& d) { return (kNumCus * kDecodeWavesPerCu + d.nkv - 1) / d.nkv; }
+
+WorkspaceLayout layout_of(const stage_config& c) {
+  const Dims d = dims_of(c);
+  WorkspaceLayout w;
+  const size_t T = (size_t)c.max_tokens;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+  w.x = take(T * d.H * 4);
+  w.a = take(T * d.H * 2);
+  w.qkv = take(T * d.qkv_out * 2);
+  w.attn = take(T * d.nq * d.d * 2);
+  w.mlp = take(T * d.F * 2);
+  w.cos_sin = take(T * (d.d / 2) * 8);
+  size_t pf = gemm_partial_floats(c.max_tokens, d.qkv_out, d.H, kEpiStoreBf16, kNumCus);
+  size_t v;
+  if ((v = gemm_partial_floats(c.max_tokens, d.H, d.nq * d.d, kEpiResidualF32, kNumCus)) > pf) pf = v;
+  if ((v = gemm_partial_floats(c.max_tokens, d.F, d.H, kEpiSwiGLU, kNumCus)) > pf) pf = v;
+  if ((v = gemm_partial_floats(c.max_tokens, d.H, d.F, kEpiResidualF32, kNumCus)) > pf) pf = v;
+  w.splitk = take(pf * 4 + 16);
+  w.max_items = decode_target_items(d) + c.max_seqs;
+  w.part_o = take((size_t)w.max_items * d.nq * d.d * 4);
+  w.part_ml = take((size_t)w.max_items * d.nq * 8);
+  w.max_tiles = (int)((T * d.g + 31) / 32) + c.max_seqs;
+  size_t mb = 0;
+  mb += align_up(T * 4);                                                    // positions
+  mb += align_up(T * 8);                                                    // slots
+  mb += align_up((size_t)c.max_seqs * c.max_blocks_per_seq * 4);            // flat block tables
+  mb += align_up((size_t)w.max_items * sizeof(DecodeItem));
+  mb += align_up((size_t)c.max_seqs * sizeof(DecodeToken));
+  mb += align_up((size_t)w.max_tiles * sizeof(PrefillTile));
+  w.meta_bytes = mb;
+  w.meta = take(mb);
+  w.total = off;
+  return w;
+}
+
+struct BatchCounts {
+  int64_t total_blocks, decode_keys;
+  int n_decode, n_tiles;
+};
+
+// Host-only checks of a micro-batch against the stage's capacities; also counts the work.
+int validate_batch(const stage_config& c, int32_t T, const int32_t* positions, int32_t S, const int32_t* q_lens,
+                   const int32_t* ctx_lens, const int32_t* block_tables, BatchCounts* out) {
+  if (!positions || !q_lens || !ctx_lens || !block_tables) return fail(STAGE_ERR_NULL, "a metadata array is NULL");
+  if (T < 1 || T > c.max_tokens) return fail(STAGE_ERR_BATCH, "num_tokens %d outside [1, max_tokens=%d]", T, c.max_tokens);
+  if (S < 1 || S > c.max_seqs) return fail(STAGE_ERR_BATCH, "num_seqs %d outside [1, max_seqs=%d]", S, c.max_seqs);
+  const int g = c.num_q_heads / c.num_kv_heads;
+  BatchCounts bc{0, 0, 0, 0};
+  int64_t sum_q = 0;
+  for (int s = 0; s < S; ++s) {
+    const int q = q_lens[s], cx = ctx_lens[s];
+    if (q < 1) return fail(STAGE_ERR_BATCH, "q_lens[%d] = %d must be >= 1", s, q);
+    if (cx < 0) return fail(STAGE_ERR_BATCH, "ctx_lens[%d] = %d must be >= 0", s, cx);
+    const int64_t tot = (int64_t)q + cx;
+    const int64_t nb = (tot + 15) / 16;
+    if (nb > c.max_blocks_per_seq)
+      return fail(STAGE_ERR_BLOCK_TABLE, "sequence %d needs %lld blocks, block table rows hold %d", s, (long long)nb,
+                  c.max_blocks_per_seq);
+    const int32_t* row = block_tables + (size_t)s * c.max_blocks_per_seq;
+    for (int b = 0; b < nb; ++b)
+      if (row[b] < 0 || row[b] >= c.num_kv_blocks)
+        return fail(STAGE_ERR_BLOCK_TABLE, "block_tables[%d][%d] = %d outside [0, %d)", s, b, row[b], c.num_kv_blocks);
+    sum_q += q;
+    bc.total_blocks += nb;
+    if (q == 1) { ++bc.n_decode; bc.decode_keys += tot; }
+    else bc.n_tiles += (int)(((int64_t)q * g + 31) / 32);
+  }
+  if (sum_q != T) return fail(STAGE_ERR_BATCH, "sum(q_lens) = %lld != num_tokens = %d", (long long)sum_q, T);
+  for (int t = 0; t < T; ++t)
+    if (positions[t] < 0) return fail(STAGE_ERR_BATCH, "positions[%d] = %d must be >= 0", t, positions[t]);
+  *out = bc;
+  return STAGE_OK;
+}
+
+void fill_slot_mapping(const stage_config& c, int32_t S, const int32_t* q_lens, const int32_t* ctx_lens,
+                       const int32_t* block_tables, int64_t* slots) {
+  int row = 0;
+  for (int s = 0; s < S; ++s) {
+    const int32_t* tab = block_tables + (size_t)s * c.max_blocks_per_seq;
+    for (int i = 0; i < q_lens[s]; ++i) {
+      const int j = ctx_lens[s] + i;
+      slots[row++] = (int64_t)tab[j / 16] * 16 + j % 16;
+    }
+  }
+}
+
+struct TimedLaunch {
+  hipEvent_t begin, end;
+  int kernel;
+};
+
+}  // namespace
+
+struct stage_handle {
+  stage_config cfg;
+  Dims dim;
+  WorkspaceLayout ws;
+  std::vector<stage_layer_weights> layers;
+  char* kv_pool;
+  char* workspace;
+  int device;
+  // pinned staging ring for the per-call metadata
+  char* staging[kStagingSlots];
+  hipEvent_t staging_done[kStagingSlots];
+  bool staging_used[kStagingSlots];
+  int next_slot;
+  // timing
+  uint32_t profile_mask;
+  std::vector<TimedLaunch> timed;       // recorded, not yet read
+  std::vector<TimedLaunch> free_events; // recycled event pairs
+};
+
+namespace {
+
+struct Timer {
+  stage_handle* st;
+  hipStream_t stream;
+  bool on;
+  TimedLaunch cur;
+  Timer(stage_handle* s, hipStream_t str, int kernel) : st(s), stream(str), on(false) {
+    if (!((s->profile_mask >> kernel) & 1u) || (int)s->timed.size() >= kMaxTimed) return;
+    if (!s->free_events.empty()) {
+      cur = s->free_events.back();
+      s->free_events.pop_back();
+    } else {
+      if (hipEventCreate(&cur.begin) != hipSuccess) return;
+      if (hipEventCreate(&cur.end) != hipSuccess) { (void)hipEventDestroy(cur.begin); return; }
+    }
+    cur.kernel = kernel;
+    on = hipEventRecord(cur.begin, stream) == hipSuccess;
+    if (!on) st->free_events.push_back(cur);
+  }
+  ~Timer() {
+    if (!on) return;
+    (void)hipEventRecord(cur.end, stream);
+    st->timed.push_back(cur);
+  }
+};
+
+__global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float* __restrict__ src, __bf16* __restrict__ dst, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = static_cast<__bf16>(src[i]);
+}
+
+int run_gemm(stage_handle* st, hipStream_t stream, int kernel_class, const GemmArgs& args, GemmEpilogue epi) {
+  const GemmPlan plan = plan_gemm(args.m, args.n, args.k, epi, kNumCus);
+  {
+    Timer t(st, stream, kernel_class);
+    HIP_TRY(launch_gemm_main(args, epi, plan, stream));
+  }
+  if (plan.splits > 1) {
+    Timer t(st, stream, STAGE_K_SPLITK_REDUCE);
+    HIP_TRY(launch_gemm_reduce(args, epi, plan, stream));
+  }
+  return STAGE_OK;
+}
+
+int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidden_in, const int32_t* positions,
+                 int32_t S, const int32_t* q_lens, const int32_t* ctx_lens, const int32_t* block_tables,
+                 void* hidden_out, int64_t* slot_mapping_out, const stage_taps* taps) {
+  if (!st) return fail(STAGE_ERR_NULL, "stage handle is NULL");
+  if (!hidden_in || !positions || !q_lens || !ctx_lens || !block_tables || !hidden_out)
+    return fail(STAGE_ERR_NULL, "a required argument of stage_forward is NULL");
+  const stage_config& c = st->cfg;
+  const Dims& d = st->dim;
+  if (taps && (taps->tap_layer < 0 || taps->tap_layer >= d.L))
+    return fail(STAGE_ERR_BATCH, "tap_layer %d outside [0, %d)", taps->tap_layer, d.L);
+  if (T >= 1) {
+    const char* in0 = (const char*)hidden_in;
+    const char* out0 = (const char*)hidden_out;
+    const size_t bytes = (size_t)T * d.H * 2;
+    if (in0 < out0 + bytes && out0 < in0 + bytes) return fail(STAGE_ERR_ALIAS, "hidden_out overlaps hidden_in");
+  }
+
+  // ---- validate the micro-batch and size the metadata (host only, nothing enqueued yet)
+  BatchCounts bc;
+  {
+    int rc = validate_batch(c, T, positions, S, q_lens, ctx_lens, block_tables, &bc);
+    if (rc) return rc;
+  }
+  const int64_t total_blocks = bc.total_blocks, decode_keys = bc.decode_keys;
+  const int n_decode = bc.n_decode, n_tiles = bc.n_tiles;
+
+  // key-range length of the decode work items: aim at a fixed number of items, never below the minimum
+  int range = kMinDecodeRange;
+  if (n_decode) {
+    const int64_t target = decode_target_items(d);
+    int64_t r = (decode_keys + target - 1) / target;
+    r = (r + 31) / 32 * 32;
+    if (r > range) range = (int)r;
+  }
+  int n_items = 0;
+  for (int s = 0; s < S; ++s)
+    if (q_lens[s] == 1) n_items += (ctx_lens[s] + 1 + range - 1) / range;
+  if (n_items > st->ws.max_items || n_tiles > st->ws.max_tiles)
+    return fail(STAGE_ERR_BATCH, "internal: work list larger than planned (%d items, %d tiles)", n_items, n_tiles);
+
+  HIP_TRY(hipSetDevice(st->device));
+  hipStream_t stream = (hipStream_t)hip_stream;
+
+  // ---- build the metadata blob in a pinned staging slot
+  const int slot_id = st->next_slot;
+  st->next_slot = (st->next_slot + 1) % kStagingSlots;
+  if (st->staging_used[slot_id]) HIP_TRY(hipEventSynchronize(st->staging_done[slot_id]));
+  char* blob = st->staging[slot_id];
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+  const size_t o_pos = take((size_t)T * 4), o_slots = take((size_t)T * 8), o_bt = take((size_t)total_blocks * 4);
+  const size_t o_items = take((size_t)n_items * sizeof(DecodeItem));
+  const size_t o_dtok = take((size_t)n_decode * sizeof(DecodeToken));
+  const size_t o_tiles = take((size_t)n_tiles * sizeof(PrefillTile));
+  if (off > st->ws.meta_bytes) return fail(STAGE_ERR_BATCH, "internal: metadata larger than planned");
+  int32_t* h_pos = (int32_t*)(blob + o_pos);
+  int64_t* h_slots = (int64_t*)(blob + o_slots);
+  int32_t* h_bt = (int32_t*)(blob + o_bt);
+  DecodeItem* h_items = (DecodeItem*)(blob + o_items);
+  DecodeToken* h_dtok = (DecodeToken*)(blob + o_dtok);
+  PrefillTile* h_tiles = (PrefillTile*)(blob + o_tiles);
+  memcpy(h_pos, positions, (size_t)T * 4);
+  {
+    int row = 0, bt_off = 0, it = 0, dt = 0, tl = 0;
+    for (int s = 0; s < S; ++s) {
+      const int q = q_lens[s], cx = ctx_lens[s];
+      const int nb = (q + cx + 15) / 16;
+      const int32_t* tab = block_tables + (size_t)s * c.max_blocks_per_seq;
+      memcpy(h_bt + bt_off, tab, (size_t)nb * 4);
+      for (int i = 0; i < q; ++i) {
+        const int j = cx + i;
+        h_slots[row + i] = (int64_t)tab[j / 16] * 16 + j % 16;
+      }
+      if (q == 1) {
+        const int keys = cx + 1;
+        const int n = (keys + range - 1) / range;
+        h_dtok[dt++] = DecodeToken{row, it, n, 0};
+        for (int k = 0; k < n; ++k) {
+          const int kb = k * range;
+          const int ke = kb + range < keys ? kb + range : keys;
+          h_items[it++] = DecodeItem{row, bt_off, kb, ke};
+        }
+      } else {
+        const int ncols = q * d.g;
+        for (int c0 = 0; c0 < ncols; c0 += 32) h_tiles[tl++] = PrefillTile{row, q, cx, bt_off, c0, {0, 0, 0}};
+      }
+      row += q;
+      bt_off += nb;
+    }
+  }
+  if (slot_mapping_out) memcpy(slot_mapping_out, h_slots, (size_t)T * 8);
+
+  // ---- enqueue
+  char* ws = st->workspace;
+  char* meta = ws + st->ws.meta;
+  HIP_TRY(hipMemcpyAsync(meta, blob, off, hipMemcpyHostToDevice, stream));
+  HIP_TRY(hipEventRecord(st->staging_done[slot_id], stream));
+  st->staging_used[slot_id] = true;
+
+  float* x = (float*)(ws + st->ws.x);
+  __bf16* a = (__bf16*)(ws + st->ws.a);
+  __bf16* qkv = (__bf16*)(ws + st->ws.qkv);
+  __bf16* attn = (__bf16*)(ws + st->ws.attn);
+  __bf16* mlp = (__bf16*)(ws + st->ws.mlp);
+  float2* cos_sin = (float2*)(ws + st->ws.cos_sin);
+  float* splitk = (float*)(ws + st->ws.splitk);
+  float* part_o = (float*)(ws + st->ws.part_o);
+  float2* part_ml = (float2*)(ws + st->ws.part_ml);
+  const int32_t* d_pos = (const int32_t*)(meta + o_pos);
+  const int64_t* d_slots = (const int64_t*)(meta + o_slots);
+  const int32_t* d_bt = (const int32_t*)(meta + o_bt);
+  const DecodeItem* d_items = (const DecodeItem*)(meta + o_items);
+  const DecodeToken* d_dtok = (const DecodeToken*)(meta + o_dtok);
+  const PrefillTile* d_tiles = (const PrefillTile*)(meta + o_tiles);
+
+  {
+    Timer t(st, stream, STAGE_K_ROPE_TABLE);
+    HIP_TRY(launch_rope_table(d_pos, cos_sin, T, d.d, c.rope_theta, stream));
+  }
+  const size_t kv_region = (size_t)c.num_kv_blocks * d.nkv * 16 * d.d;   // elements of one K (or V) region
+  for (int l = 0; l < d.L; ++l) {
+    const stage_layer_weights& w = st->layers[l];
+    const bool last = l == d.L - 1;
+    const bool tap = taps && taps->tap_layer == l;
+    __bf16* k_pool = (__bf16*)(st->kv_pool + (size_t)l * (size_t)c.kv_layer_stride_bytes);
+    __bf16* v_pool = k_pool + kv_region;
+    {
+      Timer t(st, stream, STAGE_K_RMSNORM);
+      HIP_TRY(launch_rmsnorm((const __bf16*)hidden_in, x, (const __bf16*)w.norm1, a, T, d.H, c.rms_eps, l == 0, stream));
+    }
+    if (tap && taps->tap_norm1)
+      HIP_TRY(hipMemcpyAsync(taps->tap_norm1, a, (size_t)T * d.H * 2, hipMemcpyDeviceToDevice, stream));
+    {
+      GemmArgs g{};
+      g.a = a; g.w0 = (const __bf16*)w.wqkv; g.out_bf16 = qkv; g.partial = splitk;
+      g.m = T; g.n = d.qkv_out; g.k = d.H; g.lda = d.H; g.ldo = d.qkv_out;
+      int rc = run_gemm(st, stream, STAGE_K_GEMM_QKV, g, kEpiStoreBf16);
+      if (rc) return rc;
+    }
+    {
+      Timer t(st, stream, STAGE_K_ROPE_APPEND);
+      RopeAppendArgs r{qkv, cos_sin, d_slots, k_pool, v_pool, T, d.nq, d.nkv, d.d};
+      HIP_TRY(launch_rope_append(r, stream));
+    }
+    if (tap && taps->tap_qkv)
+      HIP_TRY(hipMemcpyAsync(taps->tap_qkv, qkv, (size_t)T * d.qkv_out * 2, hipMemcpyDeviceToDevice, stream));
+    AttnArgs aa{qkv, k_pool, v_pool, d_bt, attn, d.nq, d.nkv, d.d, 1.4426950408889634f / sqrtf((float)d.d)};
+    if (n_tiles) {
+      Timer t(st, stream, STAGE_K_ATTN_PREFILL);
+      HIP_TRY(launch_attn_prefill(aa, d_tiles, n_tiles, stream));
+    }
+    if (n_items) {
+      {
+        Timer t(st, stream, STAGE_K_ATTN_DECODE);
+        HIP_TRY(launch_attn_decode(aa, d_items, n_items, part_o, part_ml, stream));
+      }
+      Timer t(st, stream, STAGE_K_ATTN_MERGE);
+      HIP_TRY(launch_attn_merge(aa, d_dtok, n_decode, part_o, part_ml, stream));
+    }
+    if (tap && taps->tap_attn)
+      HIP_TRY(hipMemcpyAsync(taps->tap_attn, attn, (size_t)T * d.nq * d.d * 2, hipMemcpyDeviceToDevice, stream));
+    {
+      GemmArgs g{};
+      g.a = attn; g.w0 = (const __bf16*)w.wo; g.resid = x; g.partial = splitk;
+      g.m = T; g.n = d.H; g.k = d.nq * d.d; g.lda = d.nq * d.d; g.ldo = d.H;
+      int rc = run_gemm(st, stream, STAGE_K_GEMM_O, g, kEpiResidualF32);
+      if (rc) return rc;
+    }
+    if (tap && taps->tap_h)
+      HIP_TRY(hipMemcpyAsync(taps->tap_h, x, (size_t)T * d.H * 4, hipMemcpyDeviceToDevice, stream));
+    {
+      Timer t(st, stream, STAGE_K_RMSNORM);
+      HIP_TRY(launch_rmsnorm(nullptr, x, (const __bf16*)w.norm2, a, T, d.H, c.rms_eps, false, stream));
+    }
+    {
+      GemmArgs g{};
+      g.a = a; g.w0 = (const __bf16*)w.wgate; g.w1 = (const __bf16*)w.wup; g.out_bf16 = mlp; g.partial = splitk;
+      g.m = T; g.n = d.F; g.k = d.H; g.lda = d.H; g.ldo = d.F;
+      int rc = run_gemm(st, stream, STAGE_K_GEMM_GATEUP, g, kEpiSwiGLU);
+      if (rc) return rc;
+    }
+    if (tap && taps->tap_mlp)
+      HIP_TRY(hipMemcpyAsync(taps->tap_mlp, mlp, (size_t)T * d.F * 2, hipMemcpyDeviceToDevice, stream));
+    {
+      // With a tap on the last layer the fp32 stream is completed first and rounded by a separate
+      // kernel, so the tap sees it; the sum and its rounding are the same as in the fused epilogue.
+      const bool fused_out = last && !(tap && taps->tap_x);
+      GemmArgs g{};
+      g.a = mlp; g.w0 = (const __bf16*)w.wdown; g.resid = x; g.out_bf16 = (__bf16*)hidden_out; g.partial = splitk;
+      g.m = T; g.n = d.H; g.k = d.F; g.lda = d.F; g.ldo = d.H;
+      int rc = run_gemm(st, stream, STAGE_K_GEMM_DOWN, g, fused_out ? kEpiResidualOut : kEpiResidualF32);
+      if (rc) return rc;
+      if (tap && taps->tap_x)
+        HIP_TRY(hipMemcpyAsync(taps->tap_x, x, (size_t)T * d.H * 4, hipMemcpyDeviceToDevice, stream));
+      if (last && !fused_out) {
+        const size_t n = (size_t)T * d.H;
+        hipLaunchKernelGGL(f32_to_bf16_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, x,
+                           (__bf16*)hidden_out, n);
+        HIP_TRY(hipGetLastError());
+      }
+    }
+  }
+  return STAGE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int stage_kv_layer_bytes(const stage_config* cfg, size_t* out_bytes) {
+  if (!out_bytes) return fail(STAGE_ERR_NULL, "out_bytes is NULL");
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  *out_bytes = (size_t)cfg->num_kv_blocks * cfg->num_kv_heads * 16 * cfg->head_dim * 2 * 2;
+  return STAGE_OK;
+}
+
+int stage_kv_element_offset(const stage_config* cfg, int32_t kv, int32_t block, int32_t kv_head, int32_t slot,
+                            int32_t dim, int64_t* out_offset) {
+  if (!out_offset) return fail(STAGE_ERR_NULL, "out_offset is NULL");
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  if (kv < 0 || kv > 1 || block < 0 || block >= cfg->num_kv_blocks || kv_head < 0 || kv_head >= cfg->num_kv_heads ||
+      slot < 0 || slot >= 16 || dim < 0 || dim >= cfg->head_dim)
+    return fail(STAGE_ERR_CONFIG, "KV coordinate out of range");
+  const int64_t d = cfg->head_dim, nkv = cfg->num_kv_heads;
+  const int64_t region = (int64_t)cfg->num_kv_blocks * nkv * 16 * d;
+  const int64_t base = ((int64_t)block * nkv + kv_head) * 16 * d;
+  *out_offset = kv == 0 ? base + (int64_t)slot * d + dim : region + base + (int64_t)dim * 16 + slot;
+  return STAGE_OK;
+}
+
+int stage_workspace_bytes(const stage_config* cfg, size_t* out_bytes) {
+  if (!out_bytes) return fail(STAGE_ERR_NULL, "out_bytes is NULL");
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  *out_bytes = layout_of(*cfg).total;
+  return STAGE_OK;
+}
+
+int stage_check_batch(const stage_config* cfg, int32_t num_tokens, const int32_t* positions, int32_t num_seqs,
+                      const int32_t* q_lens, const int32_t* ctx_lens, const int32_t* block_tables,
+                      int64_t* slot_mapping_out) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  BatchCounts bc;
+  rc = validate_batch(*cfg, num_tokens, positions, num_seqs, q_lens, ctx_lens, block_tables, &bc);
+  if (rc) return rc;
+  if (slot_mapping_out) fill_slot_mapping(*cfg, num_seqs, q_lens, ctx_lens, block_tables, slot_mapping_out);
+  return STAGE_OK;
+}
+
+int stage_init(const stage_config* cfg, const stage_layer_weights* layers, void* kv_pool, size_t kv_pool_bytes,
+               void* workspace, size_t workspace_bytes, int32_t device, stage_handle** out) {
+  if (!out) return fail(STAGE_ERR_NULL, "out handle pointer is NULL");
+  *out = nullptr;
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  if (!layers || !kv_pool || !workspace) return fail(STAGE_ERR_NULL, "layers, kv_pool or workspace is NULL");
+  for (int l = 0; l < cfg->num_layers; ++l) {
+    const stage_layer_weights& w = layers[l];
+    if (!w.norm1 || !w.wqkv || !w.wo || !w.norm2 || !w.wgate || !w.wup || !w.wdown)
+      return fail(STAGE_ERR_NULL, "layer %d has a NULL weight pointer", l);
+    const void* ptrs[7] = {w.norm1, w.wqkv, w.wo, w.norm2, w.wgate, w.wup, w.wdown};
+    for (const void* p : ptrs)
+      if ((uintptr_t)p % 16) return fail(STAGE_ERR_CONFIG, "layer %d has a weight pointer that is not 16-byte aligned", l);
+  }
+  if ((uintptr_t)kv_pool % 256 || (uintptr_t)workspace % 256)
+    return fail(STAGE_ERR_CONFIG, "kv_pool and workspace must be 256-byte aligned");
+  const size_t layer_bytes = (size_t)cfg->num_kv_blocks * cfg->num_kv_heads * 16 * cfg->head_dim * 2 * 2;
+  const size_t need_pool = (size_t)(cfg->num_layers - 1) * (size_t)cfg->kv_layer_stride_bytes + layer_bytes;
+  if (kv_pool_bytes < need_pool) return fail(STAGE_ERR_SIZE, "kv_pool_bytes %zu < %zu", kv_pool_bytes, need_pool);
+  const WorkspaceLayout ws = layout_of(*cfg);
+  if (workspace_bytes < ws.total) return fail(STAGE_ERR_SIZE, "workspace_bytes %zu < %zu", workspace_bytes, ws.total);
+  int ndev = 0;
+  HIP_TRY(hipGetDeviceCount(&ndev));
+  if (device < 0 || device >= ndev) return fail(STAGE_ERR_CONFIG, "device %d outside [0, %d)", device, ndev);
+  HIP_TRY(hipSetDevice(device));
+
+  stage_handle* st = new (std::nothrow) stage_handle();
+  if (!st) return fail(STAGE_ERR_SIZE, "out of host memory");
+  st->cfg = *cfg;
+  st->dim = dims_of(*cfg);
+  st->ws = ws;
+  st->layers.assign(layers, layers + cfg->num_layers);
+  st->kv_pool = (char*)kv_pool;
+  st->workspace = (char*)workspace;
+  st->device = device;
+  st->next_slot = 0;
+  st->profile_mask = 0;
+  for (int i = 0; i < kStagingSlots; ++i) { st->staging[i] = nullptr; st->staging_done[i] = nullptr; st->staging_used[i] = false; }
+  for (int i = 0; i < kStagingSlots; ++i) {
+    hipError_t e = hipHostMalloc((void**)&st->staging[i], ws.meta_bytes, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&st->staging_done[i], hipEventDisableTiming);
+    if (e != hipSuccess) {
+      stage_destroy(st);
+      return fail(STAGE_ERR_HIP, "allocating pinned staging: %s", hipGetErrorString(e));
+    }
+  }
+  *out = st;
+  return STAGE_OK;
+}
+
+int stage_forward(stage_handle* st, void* hip_stream, int32_t num_tokens, const void* hidden_in,
+                  const int32_t* positions, int32_t num_seqs, const int32_t* q_lens, const int32_t* ctx_lens,
+                  const int32_t* block_tables, void* hidden_out, int64_t* slot_mapping_out) {
+  return forward_impl(st, hip_stream, num_tokens, hidden_in, positions, num_seqs, q_lens, ctx_lens, block_tables,
+                      hidden_out, slot_mapping_out, nullptr);
+}
+
+int stage_forward_taps(stage_handle* st, void* hip_stream, int32_t num_tokens, const void* hidden_in,
+                       const int32_t* positions, int32_t num_seqs, const int32_t* q_lens, const int32_t* ctx_lens,
+                       const int32_t* block_tables, void* hidden_out, int64_t* slot_mapping_out,
+                       const stage_taps* taps) {
+  if (!taps) return fail(STAGE_ERR_NULL, "taps is NULL");
+  return forward_impl(st, hip_stream, num_tokens, hidden_in, positions, num_seqs, q_lens, ctx_lens, block_tables,
+                      hidden_out, slot_mapping_out, taps);
+}
+
+int stage_profile_enable(stage_handle* st, uint32_t kernel_mask) {
+  if (!st) return fail(STAGE_ERR_NULL, "stage handle is NULL");
+  st->profile_mask = kernel_mask;
+  return STAGE_OK;
+}
+
+int stage_profile_read(stage_handle* st, int32_t kernel, double* out_total_ms, int64_t* out_launches) {
+  if (!st || !out_total_ms || !out_launches) return fail(STAGE_ERR_NULL, "NULL argument");
+  if (kernel < 0 || kernel >= STAGE_K_COUNT) return fail(STAGE_ERR_CONFIG, "unknown kernel class %d", kernel);
+  double total = 0.0;
+  int64_t n = 0;
+  std::vector<TimedLaunch> keep;
+  for (const TimedLaunch& t : st->timed) {
+    if (t.kernel != kernel) { keep.push_back(t); continue; }
+    HIP_TRY(hipEventSynchronize(t.end));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, t.begin, t.end));
+    total += ms;
+    ++n;
+    st->free_events.push_back(t);
+  }
+  st->timed.swap(keep);
+  *out_total_ms = total;
+  *out_launches = n;
+  return STAGE_OK;
+}
+
+const char* stage_kernel_name(int32_t kernel) {
+  switch (kernel) {
+    case STAGE_K_RMSNORM: return "rmsnorm_kernel";
+    case STAGE_K_GEMM_QKV:
+    case STAGE_K_GEMM_O:
+    case STAGE_K_GEMM_GATEUP:
+    case STAGE_K_GEMM_DOWN: return "gemm_bf16_kernel";
+    case STAGE_K_ROPE_APPEND: return "rope_append_kernel";
+    case STAGE_K_ATTN_PREFILL: return "attn_prefill_kernel";
+    case STAGE_K_ATTN_DECODE: return "attn_decode_kernel";
+    case STAGE_K_ATTN_MERGE: return "attn_merge_kernel";
+    case STAGE_K_SPLITK_REDUCE: return "gemm_splitk_reduce_kernel";
+    case STAGE_K_ROPE_TABLE: return "rope_table_kernel";
+    default: return nullptr;
+  }
+}
+
+void stage_destroy(stage_handle* st) {
+  if (!st) return;
+  (void)hipSetDevice(st->device);
+  (void)hipDeviceSynchronize();
+  for (int i = 0; i < kStagingSlots; ++i) {
+    if (st->staging[i]) (void)hipHostFree(st->staging[i]);
+    if (st->staging_done[i]) (void)hipEventDestroy(st->staging_done[i]);
+  }
+  for (auto* list : {&st->timed, &st->free_events})
+    for (const TimedLaunch& t : *list) {
+      (void)hipEventDestroy(t.begin);
+      (void)hipEventDestroy(t.end);
+    }
+  delete st;
+}
+
+const char* stage_last_error(void) { return g_error; }
+
+}  // extern "C"

@@ -1,0 +1,268 @@
+"""ctypes binding of libmolink_stage.so: argument marshalling only.
+
+Every step of the forward pass runs in the library's HIP kernels; torch is used for device
+memory, the current stream handle and nothing else.  The library is loaded from the package
+directory and there is no fallback: without it every call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmolink_stage.so")
+
+KERNEL_CLASSES = {
+    "rmsnorm": 0, "gemm_qkv": 1, "rope_append": 2, "attn_prefill": 3, "attn_decode": 4, "attn_merge": 5,
+    "gemm_o": 6, "gemm_gateup": 7, "gemm_down": 8, "splitk_reduce": 9, "rope_table": 10,
+}
+
+
+class StageError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"stage error {code}: {message}")
+        self.code = code
+
+
+class StageConfig(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32),
+        ("num_layers", ctypes.c_int32), ("hidden", ctypes.c_int32), ("num_q_heads", ctypes.c_int32),
+        ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("ffn", ctypes.c_int32),
+        ("rms_eps", ctypes.c_float), ("rope_theta", ctypes.c_float),
+        ("kv_block_size", ctypes.c_int32), ("num_kv_blocks", ctypes.c_int32),
+        ("kv_layer_stride_bytes", ctypes.c_int64),
+        ("max_tokens", ctypes.c_int32), ("max_seqs", ctypes.c_int32), ("max_blocks_per_seq", ctypes.c_int32),
+    ]
+
+
+class StageLayerWeights(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("norm1", "wqkv", "wo", "norm2", "wgate", "wup", "wdown")]
+
+
+class StageTaps(ctypes.Structure):
+    _fields_ = [("tap_layer", ctypes.c_int32)] + [
+        (n, ctypes.c_void_p) for n in ("tap_norm1", "tap_qkv", "tap_attn", "tap_h", "tap_mlp", "tap_x")]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the built shared library (raises if it has not been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2507_05043_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    i32p, i64p = ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)
+    cfgp = ctypes.POINTER(StageConfig)
+    lib.stage_kv_layer_bytes.argtypes = [cfgp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.stage_kv_element_offset.argtypes = [cfgp] + [ctypes.c_int32] * 5 + [i64p]
+    lib.stage_check_batch.argtypes = [cfgp, ctypes.c_int32, i32p, ctypes.c_int32, i32p, i32p, i32p, i64p]
+    lib.stage_workspace_bytes.argtypes = [cfgp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.stage_init.argtypes = [cfgp, ctypes.POINTER(StageLayerWeights), ctypes.c_void_p, ctypes.c_size_t,
+                               ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.POINTER(ctypes.c_void_p)]
+    fwd = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, i32p, ctypes.c_int32, i32p, i32p,
+           i32p, ctypes.c_void_p, i64p]
+    lib.stage_forward.argtypes = fwd
+    lib.stage_forward_taps.argtypes = fwd + [ctypes.POINTER(StageTaps)]
+    lib.stage_profile_enable.argtypes = [ctypes.c_void_p, ctypes.c_uint32]
+    lib.stage_profile_read.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_double), i64p]
+    lib.stage_kernel_name.argtypes = [ctypes.c_int32]
+    lib.stage_kernel_name.restype = ctypes.c_char_p
+    lib.stage_destroy.argtypes = [ctypes.c_void_p]
+    lib.stage_destroy.restype = None
+    lib.stage_last_error.restype = ctypes.c_char_p
+    for name in ("stage_kv_layer_bytes", "stage_kv_element_offset", "stage_check_batch", "stage_workspace_bytes",
+                 "stage_init", "stage_forward", "stage_forward_taps", "stage_profile_enable", "stage_profile_read"):
+        getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise StageError(rc, load_library().stage_last_error().decode())
+
+
+def make_config(*, num_layers, hidden, num_q_heads, num_kv_heads, head_dim, ffn, rms_eps, rope_theta,
+                num_kv_blocks, max_tokens, max_seqs, max_blocks_per_seq, kv_block_size=16,
+                kv_layer_stride_bytes=None) -> StageConfig:
+    cfg = StageConfig(ctypes.sizeof(StageConfig), num_layers, hidden, num_q_heads, num_kv_heads, head_dim, ffn,
+                      rms_eps, rope_theta, kv_block_size, num_kv_blocks, 0, max_tokens, max_seqs, max_blocks_per_seq)
+    if kv_layer_stride_bytes is None:
+        kv_layer_stride_bytes = stage_kv_layer_bytes(cfg)
+    cfg.kv_layer_stride_bytes = kv_layer_stride_bytes
+    return cfg
+
+
+def stage_kv_layer_bytes(cfg: StageConfig) -> int:
+    out = ctypes.c_size_t()
+    _check(load_library().stage_kv_layer_bytes(ctypes.byref(cfg), ctypes.byref(out)))
+    return out.value
+
+
+def stage_workspace_bytes(cfg: StageConfig) -> int:
+    out = ctypes.c_size_t()
+    _check(load_library().stage_workspace_bytes(ctypes.byref(cfg), ctypes.byref(out)))
+    return out.value
+
+
+def stage_kv_element_offset(cfg: StageConfig, kv: int, block: int, kv_head: int, slot: int, dim: int) -> int:
+    out = ctypes.c_int64()
+    _check(load_library().stage_kv_element_offset(ctypes.byref(cfg), kv, block, kv_head, slot, dim, ctypes.byref(out)))
+    return out.value
+
+
+def stage_kernel_name(kernel: int) -> Optional[str]:
+    r = load_library().stage_kernel_name(kernel)
+    return r.decode() if r else None
+
+
+def _i32_array(values, count: Optional[int] = None):
+    t = torch.as_tensor(values, dtype=torch.int32).contiguous().cpu()
+    if count is not None and t.numel() != count:
+        raise ValueError(f"expected {count} int32 values, got {t.numel()}")
+    return t, ctypes.cast(t.data_ptr(), ctypes.POINTER(ctypes.c_int32))
+
+
+def stage_check_batch(cfg: StageConfig, positions, q_lens, ctx_lens, block_tables, num_tokens=None) -> List[int]:
+    """Host-only validation; returns the slot mapping."""
+    pos_t, pos_p = _i32_array(positions)
+    q_t, q_p = _i32_array(q_lens)
+    c_t, c_p = _i32_array(ctx_lens)
+    b_t, b_p = _i32_array(block_tables)
+    n = pos_t.numel() if num_tokens is None else num_tokens
+    slots = torch.empty(max(n, 1), dtype=torch.int64)
+    _check(load_library().stage_check_batch(ctypes.byref(cfg), n, pos_p, q_t.numel(), q_p, c_p, b_p,
+                                            ctypes.cast(slots.data_ptr(), ctypes.POINTER(ctypes.c_int64))))
+    return slots[:n].tolist()
+
+
+class Stage:
+    """One pipeline stage bound to its weights, KV pool and workspace (all torch CUDA tensors)."""
+
+    def __init__(self, cfg: StageConfig, layers: Sequence[Dict[str, torch.Tensor]], *, device="cuda:0",
+                 kv_pool: Optional[torch.Tensor] = None):
+        lib = load_library()
+        self.cfg = cfg
+        self.device = torch.device(device)
+        self.layers = [dict(l) for l in layers]          # keep the tensors alive
+        arr = (StageLayerWeights * cfg.num_layers)()
+        for l, w in enumerate(self.layers):
+            for name, _ in StageLayerWeights._fields_:
+                t = w[name]
+                if t.dtype != torch.bfloat16 or not t.is_contiguous() or t.device != self.device:
+                    raise ValueError(f"layer {l} {name}: need a contiguous bf16 tensor on {self.device}")
+                setattr(arr[l], name, t.data_ptr())
+        layer_bytes = stage_kv_layer_bytes(cfg)
+        pool_bytes = (cfg.num_layers - 1) * cfg.kv_layer_stride_bytes + layer_bytes
+        if kv_pool is None:
+            kv_pool = torch.empty(pool_bytes, dtype=torch.uint8, device=self.device)
+        self.kv_pool = kv_pool
+        self.workspace = torch.empty(stage_workspace_bytes(cfg), dtype=torch.uint8, device=self.device)
+        handle = ctypes.c_void_p()
+        _check(lib.stage_init(ctypes.byref(cfg), arr, kv_pool.data_ptr(), kv_pool.numel() * kv_pool.element_size(),
+                              self.workspace.data_ptr(), self.workspace.numel(), self.device.index or 0,
+                              ctypes.byref(handle)))
+        self._handle = handle
+
+    # ---- KV pool views (layout of the ABI: K [blocks][nkv][16][d], V [blocks][nkv][d][16])
+    def _region(self, layer: int, kv: int) -> torch.Tensor:
+        c = self.cfg
+        region_bytes = stage_kv_layer_bytes(c) // 2
+        start = layer * c.kv_layer_stride_bytes + kv * region_bytes
+        return self.kv_pool.view(torch.uint8)[start:start + region_bytes].view(torch.bfloat16)
+
+    def k_view(self, layer: int) -> torch.Tensor:
+        c = self.cfg
+        return self._region(layer, 0).view(c.num_kv_blocks, c.num_kv_heads, 16, c.head_dim)
+
+    def v_view(self, layer: int) -> torch.Tensor:
+        c = self.cfg
+        return self._region(layer, 1).view(c.num_kv_blocks, c.num_kv_heads, c.head_dim, 16)
+
+    def write_kv_blocks(self, layer: int, kv: int, blocks: torch.Tensor, values: torch.Tensor) -> None:
+        """Store values [n, 16 slots, nkv, d] (bf16, on the device) into the given physical blocks."""
+        if kv == 0:
+            self.k_view(layer)[blocks] = values.permute(0, 2, 1, 3)
+        else:
+            self.v_view(layer)[blocks] = values.permute(0, 2, 3, 1)
+
+    def read_kv_blocks(self, layer: int, kv: int, blocks: torch.Tensor) -> torch.Tensor:
+        """Inverse of write_kv_blocks: [n, 16 slots, nkv, d]."""
+        if kv == 0:
+            return self.k_view(layer)[blocks].permute(0, 2, 1, 3)
+        return self.v_view(layer)[blocks].permute(0, 3, 1, 2)
+
+    # ---- the forward pass
+    def forward(self, hidden: torch.Tensor, positions, q_lens, ctx_lens, block_tables, *,
+                out: Optional[torch.Tensor] = None, want_slots: bool = False, taps_layer: Optional[int] = None):
+        lib = load_library()
+        c = self.cfg
+        t = hidden.shape[0]
+        if hidden.dtype != torch.bfloat16 or not hidden.is_contiguous() or hidden.shape[1] != c.hidden:
+            raise ValueError("hidden must be a contiguous bf16 [T, hidden] tensor")
+        pos_t, pos_p = _i32_array(positions, t)
+        q_t, q_p = _i32_array(q_lens)
+        c_t, c_p = _i32_array(ctx_lens, q_t.numel())
+        b_t, b_p = _i32_array(block_tables, q_t.numel() * c.max_blocks_per_seq)
+        if out is None:
+            out = torch.empty_like(hidden)
+        slots = torch.empty(t, dtype=torch.int64) if want_slots else None
+        slots_p = ctypes.cast(slots.data_ptr(), ctypes.POINTER(ctypes.c_int64)) if want_slots else None
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        args = [self._handle, ctypes.c_void_p(stream), t, hidden.data_ptr(), pos_p, q_t.numel(), q_p, c_p, b_p,
+                out.data_ptr(), slots_p]
+        taps = None
+        if taps_layer is None:
+            _check(lib.stage_forward(*args))
+        else:
+            qkv_out = (c.num_q_heads + 2 * c.num_kv_heads) * c.head_dim
+            dev = self.device
+            taps = {
+                "a": torch.empty(t, c.hidden, dtype=torch.bfloat16, device=dev),
+                "qkv": torch.empty(t, qkv_out, dtype=torch.bfloat16, device=dev),
+                "attn": torch.empty(t, c.num_q_heads * c.head_dim, dtype=torch.bfloat16, device=dev),
+                "h": torch.empty(t, c.hidden, dtype=torch.float32, device=dev),
+                "m": torch.empty(t, c.ffn, dtype=torch.bfloat16, device=dev),
+                "x": torch.empty(t, c.hidden, dtype=torch.float32, device=dev),
+            }
+            st = StageTaps(taps_layer, taps["a"].data_ptr(), taps["qkv"].data_ptr(), taps["attn"].data_ptr(),
+                           taps["h"].data_ptr(), taps["m"].data_ptr(), taps["x"].data_ptr())
+            _check(lib.stage_forward_taps(*args, ctypes.byref(st)))
+        result = [out]
+        if want_slots:
+            result.append(slots.tolist())
+        if taps is not None:
+            result.append(taps)
+        return result[0] if len(result) == 1 else tuple(result)
+
+    # ---- per-kernel timing
+    def profile_enable(self, kernels: Sequence[str]) -> None:
+        mask = 0
+        for k in kernels:
+            mask |= 1 << KERNEL_CLASSES[k]
+        _check(load_library().stage_profile_enable(self._handle, mask))
+
+    def profile_read(self, kernel: str):
+        ms, n = ctypes.c_double(), ctypes.c_int64()
+        _check(load_library().stage_profile_read(self._handle, KERNEL_CLASSES[kernel], ctypes.byref(ms), ctypes.byref(n)))
+        return ms.value, n.value
+
+    def close(self) -> None:
+        if getattr(self, "_handle", None):
+            load_library().stage_destroy(self._handle)
+            self._handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
