@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark of one pipeline stage's forward pass on one MI355X.
+
+A step is one stage_forward (all layers, every kernel of the path) over one seeded synthetic
+micro-batch whose inputs are already resident in HBM.  Default workload: the Llama-2-7B-shaped stage
+(8 of 32 layers) on a pure-decode micro-batch of 64 sequences with contexts in [512, 2048].
+Prints one JSON line: stage tokens/s, latency per micro-batch, the roofline of the dominant kernel
+measured with HIP events on the launch stream, and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# HBM bytes per launch (reads + writes) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the
+# same counter reads for a plain 1 GiB copy (profiles/hbm_traffic_*.md).  A figure is only reported while the
+# kernel source it was taken on is unchanged.
+MEASURED_TRAFFIC = {
+    ("attn_decode", "llama2-7b", 0): {"bytes": 1.2978e9 + 4.6117e6, "source": "csrc/attention.hip",
+                                      "sha256_16": "21d7eea7feec8ae3"},
+}
+
+HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def algorithmic_work(shape, mb):
+    """Bytes and flops the method must move / compute per call (weights once, KV once per KV head)."""
+    kv_tok = 4 * shape.num_kv_heads * shape.head_dim                       # K+V bytes per token per layer
+    dec_keys = sum(c + 1 for q, c in zip(mb.q_lens, mb.ctx_lens) if q == 1)
+    pre_keys = sum(c + q for q, c in zip(mb.q_lens, mb.ctx_lens) if q > 1)
+    t = mb.num_tokens
+    attn_flops = 0
+    for q, c in zip(mb.q_lens, mb.ctx_lens):
+        attn_flops += 4 * shape.num_q_heads * shape.head_dim * sum(c + i + 1 for i in range(q))
+    per_layer_bytes = 2 * shape.params_per_layer + (dec_keys + pre_keys) * kv_tok + t * kv_tok
+    return {
+        "decode_attn_bytes_per_layer": dec_keys * kv_tok,
+        "weight_bytes_per_layer": 2 * shape.params_per_layer,
+        "bytes_per_call": shape.num_layers * per_layer_bytes + 2 * t * shape.hidden * 2,
+        "gemm_flops_per_layer": 2 * shape.params_per_layer * t,
+        "attn_flops_per_layer": attn_flops,
+        "flops_per_call": shape.num_layers * (2 * shape.params_per_layer * t + attn_flops),
+    }
+
+
+def measured_traffic(kernel, workload, seed):
+    import hashlib
+    rec = MEASURED_TRAFFIC.get((kernel, workload, seed))
+    if rec is None:
+        return None
+    path = os.path.join(ROOT, "paper_2507_05043_amd", rec["source"])
+    with open(path, "rb") as f:
+        if hashlib.sha256(f.read()).hexdigest()[:16] != rec["sha256_16"]:
+            return None
+    return rec["bytes"]
+
+
+def cpu_baseline(shape, mb, seed, sample_seqs):
+    """The oracle, as it stands, on a sample of whole sequences at full depth (rows of different
+    sequences are independent).  Returns tokens/s of the host cores."""
+    import torch
+    import oracle
+    from paper_2507_05043_amd import synth
+    from tests.gpu_harness import sub_problem
+    from tests.helpers import oracle_shape
+    seqs = list(range(0, mb.num_seqs, max(1, mb.num_seqs // sample_seqs)))[:sample_seqs]
+    sub, rows, pool = sub_problem(shape, mb, seqs, seed, dtype=torch.float32, draw_device="cuda:0")
+    layers = [{k: v.cpu() for k, v in synth.draw_layer_weights(shape, l, seed=seed, device="cuda:0").items()}
+              for l in range(shape.num_layers)]
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=seed)[rows]
+    t0 = time.perf_counter()
+    oracle.stage_forward(oracle_shape(shape), layers, hidden, sub.positions, sub.q_lens, sub.ctx_lens,
+                         sub.block_tables, pool, dtype=torch.float32)
+    dt = time.perf_counter() - t0
+    return {"value": sub.num_tokens / dt, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
+            "sample": f"{len(seqs)} of {mb.num_seqs} sequences ({sub.num_tokens} tokens) at full depth, fp32, "
+                      f"{dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llama2-7b", choices=["tiny", "llama2-7b", "qwen2-7b", "llama3-70b", "sweep"])
+    ap.add_argument("--budget", type=int, default=256, help="token budget of the sweep workload")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--breakdown", action="store_true", help="also time every kernel class (extra untimed steps)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run a plain 1 GiB device copy ten times and exit (reference for hardware counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (one pipeline stage = one GPU's share); use --gpus 1")
+
+    import torch
+    if args.copy_calibration:
+        src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda:0")      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4, "launches": 10}))
+        return
+    from paper_2507_05043_amd import KERNEL_CLASSES, synth
+    from paper_2507_05043_amd import stage as _stage
+    if not os.path.exists(_stage.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    from paper_2507_05043_amd.harness import make_stage
+
+    shape, mb = synth.workload(args.workload, seed=args.seed, budget=args.budget)
+    work = algorithmic_work(shape, mb)
+    kv_bytes = shape.num_layers * mb.num_kv_blocks * 16 * 4 * shape.num_kv_heads * shape.head_dim
+    alias = kv_bytes + 2 * shape.params_per_layer * shape.num_layers > 250e9     # timing only: layers share one pool
+    st = make_stage(shape, mb, args.seed, alias_layers=alias)
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=args.seed, device="cuda:0")
+    out = torch.empty_like(hidden)
+    n_dec = sum(1 for q in mb.q_lens if q == 1)
+    decode_bound = work["decode_attn_bytes_per_layer"] / (HBM_PEAK_GBS * 1e9) >= \
+        (work["gemm_flops_per_layer"] + work["attn_flops_per_layer"]) / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    dominant = "attn_decode" if (n_dec and decode_bound) else "gemm_gateup"
+
+    def step():
+        st.forward(hidden, mb.positions, mb.q_lens, mb.ctx_lens, mb.block_tables, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    st.profile_enable([dominant])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    dom_ms, dom_n = st.profile_read(dominant)
+    st.profile_enable([])
+    ms_per_step = elapsed / args.steps * 1e3
+    tokens_per_s = mb.num_tokens * args.steps / elapsed
+
+    avg_ms = dom_ms / max(dom_n, 1)
+    if dominant == "attn_decode":
+        achieved = work["decode_attn_bytes_per_layer"] / (avg_ms * 1e-3) / 1e9
+        roofline = {"kernel": _stage.stage_kernel_name(KERNEL_CLASSES[dominant]), "bound": "hbm",
+                    "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBS, 4),
+                    "traffic": measured_traffic(dominant, args.workload, args.seed),
+                    "avg_launch_ms": round(avg_ms, 5), "launches": dom_n,
+                    "algorithmic_bytes_per_launch": work["decode_attn_bytes_per_layer"]}
+    else:
+        flops = 2 * (2 * shape.hidden * shape.ffn) * mb.num_tokens
+        achieved = flops / (avg_ms * 1e-3) / 1e12
+        roofline = {"kernel": _stage.stage_kernel_name(KERNEL_CLASSES[dominant]), "bound": "mfma",
+                    "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                    "avg_launch_ms": round(avg_ms, 5), "launches": dom_n, "flops_per_launch": flops}
+
+    result = {
+        "metric": "stage_tokens_per_sec", "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{shape.name}: L={shape.num_layers} H={shape.hidden} nq={shape.num_q_heads} "
+                               f"nkv={shape.num_kv_heads} d={shape.head_dim} F={shape.ffn}; micro-batch T={mb.num_tokens} "
+                               f"S={mb.num_seqs} ({mb.num_seqs - n_dec} prefill chunks, {n_dec} decode tokens), KV block 16",
+                   "seed": args.seed, "kv_layers_aliased": bool(alias)},
+        "stage_latency_ms": round(ms_per_step, 4),
+        "ideal_ms": {"hbm": round(work["bytes_per_call"] / (HBM_PEAK_GBS * 1e9) * 1e3, 4),
+                     "mfma": round(work["flops_per_call"] / (MFMA_BF16_PEAK_TFLOPS * 1e12) * 1e3, 4)},
+        "roofline": roofline,
+    }
+
+    if args.breakdown:
+        names = list(KERNEL_CLASSES)
+        st.profile_enable(names)
+        reps = max(3, min(args.steps, 10))
+        for _ in range(reps):
+            step()
+        torch.cuda.synchronize()
+        result["breakdown_ms_per_step"] = {n: round(st.profile_read(n)[0] / reps, 5) for n in names}
+        st.profile_enable([])
+
+    if not args.no_cpu_baseline:
+        sample = {"tiny": mb.num_seqs, "llama2-7b": 64, "qwen2-7b": 8, "llama3-70b": 4, "sweep": 4}[args.workload]
+        result["cpu_baseline"] = cpu_baseline(shape, mb, args.seed, sample)
+    st.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -49,6 +49,7 @@ __device__ __forceinline__ bf16x8 pack8(const float* p) {
 template <int D>
 struct DecodeStepLoads {
   bf16x8 ka[D / 32], kb[D / 32];   // key tiles A and B, D/32 MFMA k-steps each
+  bf16x8 v[D / 16];                // V^T tiles, one per 16 output dims
 };
 
 template <int D>
@@ -58,14 +59,17 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, const Deco
   constexpr int KS = D / 32;   // MFMA k-steps of the QK product
   constexpr int DT = D / 16;   // 16-row tiles of O^T
   const int lane = threadIdx.x & 63;
-  const int item_id = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6));
-  if (item_id >= num_items) return;
-  const int r = blockIdx.y;                              // KV head
+  // the four waves of a workgroup take four neighbouring KV heads of the same key range: their
+  // blocks are adjacent in the pool, so the workgroup reads 16 KB runs
+  const int item_id = blockIdx.x;
+  const int r = __builtin_amdgcn_readfirstlane(blockIdx.y * 4 + (threadIdx.x >> 6));   // KV head
+  if (r >= a.nkv) return;
   const int g = a.nq / a.nkv;
   const int row = __builtin_amdgcn_readfirstlane(items[item_id].row);
   const int bt_off = __builtin_amdgcn_readfirstlane(items[item_id].bt_off);
   const int key_begin = __builtin_amdgcn_readfirstlane(items[item_id].key_begin);
   const int key_end = __builtin_amdgcn_readfirstlane(items[item_id].key_end);
+  const int part = __builtin_amdgcn_readfirstlane(items[item_id].part);
   const int32_t* bt = a.bt_flat + bt_off;
   const int last_block = (key_end - 1) / kKvBlock;
   const int nsteps = (key_end - key_begin + 31) / 32;
@@ -100,14 +104,20 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, const Deco
     lb = lb < last_block ? lb : last_block;
     return bt[lb];
   };
-  auto load_k = [&](DecodeStepLoads<D>& L, int b0, int b1) {
-    const int pb = k_bsel ? b1 : b0;
-    const __bf16* kp = a.k_pool + (size_t)pb * blk_stride + head_off + k_lane_off;
+  // all loads of one step: addresses are always in bounds (block indices are clamped), so a step can
+  // be fetched without asking whether it exists and the loop body stays free of branches
+  auto load_step = [&](DecodeStepLoads<D>& L, int b0, int b1) {
+    const int pbk = k_bsel ? b1 : b0;
+    const __bf16* kp = a.k_pool + (size_t)pbk * blk_stride + head_off + k_lane_off;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
       L.ka[kk] = load8(kp + kk * 32);
       L.kb[kk] = load8(kp + 4 * D + kk * 32);
     }
+    const int pbv = v_bsel ? b1 : b0;
+    const __bf16* vp = a.v_pool + (size_t)pbv * blk_stride + head_off + v_lane_off;
+#pragma unroll
+    for (int t = 0; t < DT; ++t) L.v[t] = load8(vp + (size_t)t * 16 * kKvBlock);
   };
 
   f32x4 acc[DT];
@@ -115,15 +125,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, const Deco
   for (int t = 0; t < DT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
   float m_run = -INFINITY, l_run = 0.f;
 
-  auto process = [&](const DecodeStepLoads<D>& L, int step, int b0, int b1) {
-    // V^T loads for this step first: their latency hides behind QK and the softmax
-    bf16x8 vf[DT];
-    {
-      const int pb = v_bsel ? b1 : b0;
-      const __bf16* vp = a.v_pool + (size_t)pb * blk_stride + head_off + v_lane_off;
-#pragma unroll
-      for (int t = 0; t < DT; ++t) vf[t] = load8(vp + (size_t)t * 16 * kKvBlock);
-    }
+  auto process = [&](const DecodeStepLoads<D>& L, int step) {
     f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
@@ -157,37 +159,41 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, const Deco
     const bool tail = key_begin + 32 * step + 32 > key_end;   // wave-uniform
 #pragma unroll
     for (int t = 0; t < DT; ++t) {
-      bf16x8 v = vf[t];
+      bf16x8 v = L.v[t];
       if (tail) v = zero_tail(v, nvalid < 0 ? 0 : nvalid);
       acc[t] = acc[t] * alpha;
       acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v, pf, acc[t], 0, 0, 0);
     }
   };
 
+  // Software pipeline: while step s is processed, all loads of step s+1 are in flight and the block
+  // ids of step s+2 are being fetched.  The loop body has no branches, so the waits count exactly the
+  // loads that must have landed.
   DecodeStepLoads<D> buf0, buf1;
-  int b0 = block_id(0, 0), b1 = block_id(0, 1);
-  int n0 = block_id(1, 0), n1 = block_id(1, 1);
-  load_k(buf0, b0, b1);
-  for (int step = 0; step < nsteps; step += 2) {
-    const bool has1 = step + 1 < nsteps;
-    if (has1) load_k(buf1, n0, n1);
-    const int f0 = block_id(step + 2, 0), f1 = block_id(step + 2, 1);
-    process(buf0, step, b0, b1);
-    if (has1) {
-      const bool has2 = step + 2 < nsteps;
-      if (has2) load_k(buf0, f0, f1);
-      const int h0 = block_id(step + 3, 0), h1 = block_id(step + 3, 1);
-      process(buf1, step + 1, n0, n1);
-      b0 = f0; b1 = f1;
-      n0 = h0; n1 = h1;
-    }
+  int c0 = block_id(1, 0), c1 = block_id(1, 1);          // ids of the step after the one in flight
+  load_step(buf0, block_id(0, 0), block_id(0, 1));
+  int step = 0;
+  for (; step + 2 < nsteps; step += 2) {
+    load_step(buf1, c0, c1);                              // step + 1
+    c0 = block_id(step + 2, 0); c1 = block_id(step + 2, 1);
+    process(buf0, step);
+    load_step(buf0, c0, c1);                              // step + 2
+    c0 = block_id(step + 3, 0); c1 = block_id(step + 3, 1);
+    process(buf1, step + 1);
+  }
+  if (step + 1 < nsteps) {
+    load_step(buf1, c0, c1);
+    process(buf0, step);
+    process(buf1, step + 1);
+  } else {
+    process(buf0, step);
   }
 
   // l_run holds this lane group's share of the row sum; combine the four groups
   float l_tot = l_run + __shfl_xor(l_run, 16, 64);
   l_tot += __shfl_xor(l_tot, 32, 64);
   if (col < g) {
-    const size_t slot = ((size_t)item_id * a.nkv + r) * g + col;
+    const size_t slot = ((size_t)part * a.nkv + r) * g + col;
     float* po = part_o + slot * D + 4 * grp;
 #pragma unroll
     for (int t = 0; t < DT; ++t) *reinterpret_cast<f32x4*>(po + t * 16) = acc[t];
@@ -403,7 +409,7 @@ hipError_t launch_attn_prefill(const AttnArgs& a, const PrefillTile* tiles, int 
 
 hipError_t launch_attn_decode(const AttnArgs& a, const DecodeItem* items, int num_items, float* part_o,
                               float2* part_ml, hipStream_t stream) {
-  dim3 grid((num_items + 3) / 4, a.nkv), block(256);
+  dim3 grid(num_items, (a.nkv + 3) / 4), block(256);
   if (a.head_dim == 128)
     hipLaunchKernelGGL(attn_decode_kernel<128>, grid, block, 0, stream, a, items, num_items, part_o, part_ml);
   else

@@ -11,6 +11,8 @@ struct DecodeItem {
   int32_t bt_off;     // offset of the sequence's first block in the flat block-table array
   int32_t key_begin;  // first key of the range (multiple of 32)
   int32_t key_end;    // one past the last key (<= ctx + 1)
+  int32_t part;       // index of this range's partial result (ranges of a token are consecutive)
+  int32_t pad[3];
 };
 
 // One decode token: where its partial results live.

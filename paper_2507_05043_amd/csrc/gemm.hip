@@ -223,6 +223,52 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(GemmArgs p, int
   }
 }
 
+// Sum of the split-K partial results + residual add + (RMSNorm | bf16 rounding), one workgroup per row.
+template <bool NORM>
+__global__ __launch_bounds__(1024) void reduce_residual_norm_kernel(const float* __restrict__ partial, int splits,
+                                                                   int m_rows, int n, float* __restrict__ x,
+                                                                   const __bf16* __restrict__ gain, float eps,
+                                                                   __bf16* __restrict__ out, int ldo) {
+  __shared__ float wsum[16];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const int stride = blockDim.x * 4, nwaves = blockDim.x >> 6;
+  const size_t plane = (size_t)m_rows * n;
+  float* xr = x + (size_t)row * n;
+  const float* pr = partial + (size_t)row * n;
+  float ss = 0.f;
+  for (int c = tid * 4; c < n; c += stride) {
+    f32x4 v = *reinterpret_cast<const f32x4*>(xr + c);
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    for (int k = 0; k < splits; ++k) s += *reinterpret_cast<const f32x4*>(pr + k * plane + c);
+    v += s;
+    if constexpr (NORM) {
+      *reinterpret_cast<f32x4*>(xr + c) = v;
+      ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+    } else {
+      bf16x4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16(v[e]);
+      *reinterpret_cast<bf16x4*>(out + (size_t)row * ldo + c) = o;
+    }
+  }
+  if constexpr (NORM) {
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) wsum[tid >> 6] = ss;
+    __syncthreads();
+    float tot = 0.f;
+    for (int w = 0; w < nwaves; ++w) tot += wsum[w];
+    const float rs = 1.0f / sqrtf(tot / (float)n + eps);
+    for (int c = tid * 4; c < n; c += stride) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(xr + c);     // written by this same thread above
+      const bf16x4 g = *reinterpret_cast<const bf16x4*>(gain + c);
+      bf16x4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16(v[e] * rs * bf16_to_f32(g[e]));
+      *reinterpret_cast<bf16x4*>(out + (size_t)row * ldo + c) = o;
+    }
+  }
+}
+
 template <int BM, int BN, int EPI>
 hipError_t launch_tile(const GemmArgs& a, const GemmPlan& plan, hipStream_t stream) {
   const int tiles_m = (a.m + BM - 1) / BM;
@@ -311,6 +357,19 @@ hipError_t launch_gemm_reduce(const GemmArgs& a, GemmEpilogue epi, const GemmPla
     case kEpiSwiGLU:
       hipLaunchKernelGGL((gemm_splitk_reduce_kernel<kEpiSwiGLU>), grid, block, 0, stream, a, plan.nv, plan.splits);
       break;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm_reduce_residual_norm(const GemmArgs& a, GemmEpilogue epi, const GemmPlan& plan,
+                                            const __bf16* gain, float eps, __bf16* norm_out, hipStream_t stream) {
+  const int threads = a.n >= 4096 ? 1024 : (a.n >= 2048 ? 512 : 256);
+  if (epi == kEpiResidualOut) {
+    hipLaunchKernelGGL(reduce_residual_norm_kernel<false>, dim3(a.m), dim3(threads), 0, stream, a.partial, plan.splits, a.m,
+                       a.n, a.resid, (const __bf16*)nullptr, eps, a.out_bf16, a.ldo);
+  } else {
+    hipLaunchKernelGGL(reduce_residual_norm_kernel<true>, dim3(a.m), dim3(threads), 0, stream, a.partial, plan.splits, a.m,
+                       a.n, a.resid, gain, eps, norm_out, a.n);
   }
   return hipGetLastError();
 }

@@ -25,9 +25,9 @@ struct GemmArgs {
 
 struct GemmPlan {
   int tile;             // 0: 128x128 workgroup tile, 1: 64x128
-  int splits;           // K splits (1 = epilogue fused into the GEMM kernel)
+  int splits;           // K splits across workgroups (1 = epilogue fused into the GEMM kernel)
   int k_tiles_per_split;
-  int nv;               // width of the column space the kernel iterates (2*ceil(F/32)*32 for SwiGLU, else N)
+  int nv;               // width of the column space the kernel iterates (gate/up interleaved for SwiGLU, else N)
 };
 
 GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus);
@@ -37,5 +37,12 @@ size_t gemm_partial_floats(int max_m, int n, int k, GemmEpilogue epi, int num_cu
 hipError_t launch_gemm_main(const GemmArgs& args, GemmEpilogue epi, const GemmPlan& plan, hipStream_t stream);
 // Only when plan.splits > 1: sums the partial results in split order and applies the epilogue.
 hipError_t launch_gemm_reduce(const GemmArgs& args, GemmEpilogue epi, const GemmPlan& plan, hipStream_t stream);
+
+// Only when plan.splits > 1 and the epilogue is a residual one: one kernel that sums the partial
+// results in split order, adds them to the fp32 residual stream x[m][n] (in place), and then either
+// writes RMSNorm(x; gain, eps) as bf16 to norm_out (gain != nullptr) or rounds x to bf16 into
+// args.out_bf16 (kEpiResidualOut).  Replaces launch_gemm_reduce plus the following RMSNorm.
+hipError_t launch_gemm_reduce_residual_norm(const GemmArgs& args, GemmEpilogue epi, const GemmPlan& plan,
+                                            const __bf16* gain, float eps, __bf16* norm_out, hipStream_t stream);
 
 }  // namespace molink

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <algorithm>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -246,6 +247,33 @@ int run_gemm(stage_handle* st, hipStream_t stream, int kernel_class, const GemmA
   return STAGE_OK;
 }
 
+// A projection whose result is added to the fp32 residual stream x, followed by what consumes x next:
+// an RMSNorm into `norm_out` (gain != nullptr), or nothing.  When the GEMM splits K across workgroups
+// the sum of the partial results, the residual add and the norm run as one kernel.
+int run_residual_gemm(stage_handle* st, hipStream_t stream, int kernel_class, const GemmArgs& args, GemmEpilogue epi,
+                      const __bf16* gain, __bf16* norm_out) {
+  const GemmPlan plan = plan_gemm(args.m, args.n, args.k, epi, kNumCus);
+  {
+    Timer t(st, stream, kernel_class);
+    HIP_TRY(launch_gemm_main(args, epi, plan, stream));
+  }
+  const bool fused = plan.splits > 1 && (gain != nullptr || epi == kEpiResidualOut);
+  if (fused) {
+    Timer t(st, stream, STAGE_K_SPLITK_REDUCE);
+    HIP_TRY(launch_gemm_reduce_residual_norm(args, epi, plan, gain, st->cfg.rms_eps, norm_out, stream));
+    return STAGE_OK;
+  }
+  if (plan.splits > 1) {
+    Timer t(st, stream, STAGE_K_SPLITK_REDUCE);
+    HIP_TRY(launch_gemm_reduce(args, epi, plan, stream));
+  }
+  if (gain) {
+    Timer t(st, stream, STAGE_K_RMSNORM);
+    HIP_TRY(launch_rmsnorm(nullptr, args.resid, gain, norm_out, args.m, args.n, st->cfg.rms_eps, false, stream));
+  }
+  return STAGE_OK;
+}
+
 int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidden_in, const int32_t* positions,
                  int32_t S, const int32_t* q_lens, const int32_t* ctx_lens, const int32_t* block_tables,
                  void* hidden_out, int64_t* slot_mapping_out, const stage_taps* taps) {
@@ -326,7 +354,8 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
         for (int k = 0; k < n; ++k) {
           const int kb = k * range;
           const int ke = kb + range < keys ? kb + range : keys;
-          h_items[it++] = DecodeItem{row, bt_off, kb, ke};
+          h_items[it] = DecodeItem{row, bt_off, kb, ke, it, {0, 0, 0}};
+          ++it;
         }
       } else {
         const int ncols = q * d.g;
@@ -336,6 +365,11 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       bt_off += nb;
     }
   }
+  // longest key ranges first, so the short ones fill the tail of the launch
+  if (n_items > 1)
+    std::stable_sort(h_items, h_items + n_items, [](const DecodeItem& x, const DecodeItem& y) {
+      return (x.key_end - x.key_begin) > (y.key_end - y.key_begin);
+    });
   if (slot_mapping_out) memcpy(slot_mapping_out, h_slots, (size_t)T * 8);
 
   // ---- enqueue
@@ -366,16 +400,19 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
     HIP_TRY(launch_rope_table(d_pos, cos_sin, T, d.d, c.rope_theta, stream));
   }
   const size_t kv_region = (size_t)c.num_kv_blocks * d.nkv * 16 * d.d;   // elements of one K (or V) region
+  {
+    // the first layer's input norm also initialises the fp32 residual stream from the bf16 input
+    Timer t(st, stream, STAGE_K_RMSNORM);
+    HIP_TRY(launch_rmsnorm((const __bf16*)hidden_in, x, (const __bf16*)st->layers[0].norm1, a, T, d.H, c.rms_eps, true,
+                           stream));
+  }
   for (int l = 0; l < d.L; ++l) {
     const stage_layer_weights& w = st->layers[l];
     const bool last = l == d.L - 1;
     const bool tap = taps && taps->tap_layer == l;
     __bf16* k_pool = (__bf16*)(st->kv_pool + (size_t)l * (size_t)c.kv_layer_stride_bytes);
     __bf16* v_pool = k_pool + kv_region;
-    {
-      Timer t(st, stream, STAGE_K_RMSNORM);
-      HIP_TRY(launch_rmsnorm((const __bf16*)hidden_in, x, (const __bf16*)w.norm1, a, T, d.H, c.rms_eps, l == 0, stream));
-    }
+    // `a` holds RMSNorm(x; norm1 of this layer) here
     if (tap && taps->tap_norm1)
       HIP_TRY(hipMemcpyAsync(taps->tap_norm1, a, (size_t)T * d.H * 2, hipMemcpyDeviceToDevice, stream));
     {
@@ -411,15 +448,11 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       GemmArgs g{};
       g.a = attn; g.w0 = (const __bf16*)w.wo; g.resid = x; g.partial = splitk;
       g.m = T; g.n = d.H; g.k = d.nq * d.d; g.lda = d.nq * d.d; g.ldo = d.H;
-      int rc = run_gemm(st, stream, STAGE_K_GEMM_O, g, kEpiResidualF32);
+      int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_O, g, kEpiResidualF32, (const __bf16*)w.norm2, a);
       if (rc) return rc;
     }
     if (tap && taps->tap_h)
       HIP_TRY(hipMemcpyAsync(taps->tap_h, x, (size_t)T * d.H * 4, hipMemcpyDeviceToDevice, stream));
-    {
-      Timer t(st, stream, STAGE_K_RMSNORM);
-      HIP_TRY(launch_rmsnorm(nullptr, x, (const __bf16*)w.norm2, a, T, d.H, c.rms_eps, false, stream));
-    }
     {
       GemmArgs g{};
       g.a = a; g.w0 = (const __bf16*)w.wgate; g.w1 = (const __bf16*)w.wup; g.out_bf16 = mlp; g.partial = splitk;
@@ -436,7 +469,9 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       GemmArgs g{};
       g.a = mlp; g.w0 = (const __bf16*)w.wdown; g.resid = x; g.out_bf16 = (__bf16*)hidden_out; g.partial = splitk;
       g.m = T; g.n = d.H; g.k = d.F; g.lda = d.F; g.ldo = d.H;
-      int rc = run_gemm(st, stream, STAGE_K_GEMM_DOWN, g, fused_out ? kEpiResidualOut : kEpiResidualF32);
+      const __bf16* next_gain = last ? nullptr : (const __bf16*)st->layers[l + 1].norm1;
+      int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_DOWN, g, fused_out ? kEpiResidualOut : kEpiResidualF32,
+                                 next_gain, a);
       if (rc) return rc;
       if (tap && taps->tap_x)
         HIP_TRY(hipMemcpyAsync(taps->tap_x, x, (size_t)T * d.H * 4, hipMemcpyDeviceToDevice, stream));

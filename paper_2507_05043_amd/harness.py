@@ -1,0 +1,48 @@
+"""Set a stage up on the GPU from the seeded synthetic draws (device memory plumbing only)."""
+from __future__ import annotations
+
+from typing import Optional
+
+import torch
+
+from . import synth
+from .stage import Stage, make_config
+
+
+def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_std=None,
+               max_tokens: Optional[int] = None, alias_layers: bool = False, fill_kv: bool = True,
+               device: str = "cuda:0") -> Stage:
+    """Draw the stage's weights on the device, size the pool and workspace for `mb`, fill the cache."""
+    layers = [synth.draw_layer_weights(shape, l, seed=seed, device=device, weight_std=weight_std)
+              for l in range(shape.num_layers)]
+    cfg = make_config(num_layers=shape.num_layers, hidden=shape.hidden, num_q_heads=shape.num_q_heads,
+                      num_kv_heads=shape.num_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn,
+                      rms_eps=shape.rms_eps, rope_theta=shape.rope_theta, num_kv_blocks=mb.num_kv_blocks,
+                      max_tokens=max_tokens or mb.num_tokens, max_seqs=mb.num_seqs,
+                      max_blocks_per_seq=mb.max_blocks_per_seq,
+                      kv_layer_stride_bytes=0 if alias_layers else None)
+    st = Stage(cfg, layers, device=device)
+    if fill_kv:
+        fill_pool(st, shape, mb, seed)
+    return st
+
+
+def fill_pool(st: Stage, shape: synth.StageShape, mb: synth.MicroBatch, seed: int) -> None:
+    """Cached context drawn into its slots; every other slot of the pool is NaN."""
+    st.kv_pool.view(torch.bfloat16).fill_(float("nan"))
+    valid = synth.valid_slot_mask(mb, shape.kv_block_size)
+    used = torch.nonzero(valid.any(dim=1)).flatten()
+    if used.numel() == 0:
+        return
+    used_dev = used.to(st.device)
+    m = valid[used].to(st.device).view(-1, shape.kv_block_size, 1, 1)
+    nan = torch.tensor(float("nan"), dtype=torch.bfloat16, device=st.device)
+    layers = 1 if st.cfg.kv_layer_stride_bytes == 0 else shape.num_layers
+    step = 4096
+    for l in range(layers):
+        for kv in (0, 1):
+            for i in range(0, used_dev.numel(), step):
+                blk = used_dev[i:i + step]
+                vals = synth.draw_kv_blocks(shape, mb.num_kv_blocks, l, kv, blk, seed=seed)
+                vals = torch.where(m[i:i + step], vals, nan)
+                st.write_kv_blocks(l, kv, blk, vals)
