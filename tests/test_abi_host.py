@@ -1,0 +1,138 @@
+"""Host-side checks that need no GPU: the library loads, exports what the header declares,
+validates micro-batches, and maps slots and KV coordinates exactly."""
+import ctypes
+import os
+import random
+import re
+
+import pytest
+import torch
+
+import oracle
+from paper_2507_05043_amd import StageError, stage as S, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(S.LIB_PATH):
+        from paper_2507_05043_amd import build
+        build.build()
+    return S.load_library()
+
+
+def tiny_cfg(**kw):
+    args = dict(num_layers=2, hidden=256, num_q_heads=4, num_kv_heads=2, head_dim=64, ffn=688, rms_eps=1e-5,
+                rope_theta=1e4, num_kv_blocks=40, max_tokens=128, max_seqs=8, max_blocks_per_seq=12)
+    args.update(kw)
+    return S.make_config(**args)
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "molink_stage.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(stage_[a-z_]+)\s*\(", header))
+    assert {"stage_init", "stage_forward", "stage_forward_taps", "stage_check_batch", "stage_destroy"} <= names
+    for n in sorted(names):
+        assert hasattr(lib, n), f"{n} is declared in the header but not exported"
+
+
+def test_config_struct_matches_header_size(lib):
+    # uint32 + 6 int32 + 2 float + 2 int32 (+ 4 pad) + int64 + 3 int32 (+ 4 pad)
+    assert ctypes.sizeof(S.StageConfig) == 72
+    assert S.stage_workspace_bytes(tiny_cfg()) > 0
+
+
+@pytest.mark.parametrize("bad", [dict(kv_block_size=32), dict(head_dim=96), dict(hidden=252), dict(num_q_heads=5),
+                                 dict(num_q_heads=34, num_kv_heads=2), dict(rms_eps=0.0), dict(num_layers=0)])
+def test_unsupported_configs_are_rejected(lib, bad):
+    with pytest.raises(StageError) as ei:
+        cfg = tiny_cfg(**bad)
+        S.stage_workspace_bytes(cfg)
+    assert ei.value.code == -2
+
+
+def test_struct_size_is_checked(lib):
+    cfg = tiny_cfg()
+    cfg.struct_size = 64
+    with pytest.raises(StageError) as ei:
+        S.stage_workspace_bytes(cfg)
+    assert ei.value.code == -2
+
+
+def test_slot_mapping_is_bit_exact_against_the_oracle(lib):
+    rng = random.Random(5)
+    for trial in range(20):
+        n_seq = rng.randint(1, 8)
+        q_lens = [rng.choice([1, 1, 1, 2, 7, 16, 17, 33]) for _ in range(n_seq)]
+        ctx_lens = [rng.choice([0, 1, 15, 16, 17, 31, 64, 100]) for _ in range(n_seq)]
+        mb = synth.make_microbatch(q_lens, ctx_lens, seed=trial, max_blocks_per_seq=12)
+        cfg = tiny_cfg(num_kv_blocks=mb.num_kv_blocks, max_tokens=max(128, mb.num_tokens))
+        got = S.stage_check_batch(cfg, mb.positions, mb.q_lens, mb.ctx_lens, mb.block_tables)
+        assert got == oracle.slot_mapping(q_lens, ctx_lens, mb.block_tables, 16)
+
+
+def test_batch_validation_errors(lib):
+    mb = synth.make_microbatch([5, 1, 1], [0, 20, 3], seed=1, max_blocks_per_seq=12)
+    cfg = tiny_cfg(num_kv_blocks=mb.num_kv_blocks)
+    ok = dict(positions=mb.positions, q_lens=mb.q_lens, ctx_lens=mb.ctx_lens, block_tables=mb.block_tables)
+    S.stage_check_batch(cfg, **ok)
+
+    def expect(code, **change):
+        args = dict(ok)
+        args.update(change)
+        with pytest.raises(StageError) as ei:
+            S.stage_check_batch(cfg, **args)
+        assert ei.value.code == code, ei.value
+
+    expect(-4, q_lens=[5, 0, 1])
+    expect(-4, q_lens=[4, 1, 1])                              # sum(q_lens) != T
+    expect(-4, ctx_lens=[0, -1, 3])
+    expect(-4, positions=torch.tensor([0, 1, 2, 3, -4, 20, 3], dtype=torch.int32))
+    bad = mb.block_tables.clone()
+    bad[1, 1] = mb.num_kv_blocks
+    expect(-5, block_tables=bad)
+    bad = mb.block_tables.clone()
+    bad[0, 0] = -1
+    expect(-5, block_tables=bad)
+    expect(-5, ctx_lens=[0, 16 * 12, 3])                      # needs 13 blocks, rows hold 12
+    small = tiny_cfg(num_kv_blocks=mb.num_kv_blocks, max_tokens=6)
+    with pytest.raises(StageError) as ei:
+        S.stage_check_batch(small, **ok)
+    assert ei.value.code == -4
+    few = tiny_cfg(num_kv_blocks=mb.num_kv_blocks, max_seqs=2)
+    with pytest.raises(StageError) as ei:
+        S.stage_check_batch(few, **ok)
+    assert ei.value.code == -4
+    # entries past a sequence's need are ignored, whatever they hold
+    junk = mb.block_tables.clone()
+    junk[2, 1:] = 10 ** 6
+    S.stage_check_batch(cfg, **dict(ok, block_tables=junk))
+
+
+def test_kv_element_offset_is_a_bijection_with_the_documented_layout(lib):
+    cfg = tiny_cfg(num_kv_blocks=3)
+    nb, nkv, d = 3, cfg.num_kv_heads, cfg.head_dim
+    layer_elems = S.stage_kv_layer_bytes(cfg) // 2
+    assert layer_elems == 2 * nb * nkv * 16 * d
+    seen = set()
+    for kv in (0, 1):
+        for b in range(nb):
+            for h in range(nkv):
+                for s in (0, 1, 15):
+                    for e in (0, 1, d - 1):
+                        off = S.stage_kv_element_offset(cfg, kv, b, h, s, e)
+                        assert 0 <= off < layer_elems and off not in seen
+                        seen.add(off)
+                        region = kv * (layer_elems // 2)
+                        base = (b * nkv + h) * 16 * d
+                        want = region + base + (s * d + e if kv == 0 else e * 16 + s)
+                        assert off == want
+    with pytest.raises(StageError):
+        S.stage_kv_element_offset(cfg, 0, 3, 0, 0, 0)
+
+
+def test_kernel_names(lib):
+    assert S.stage_kernel_name(S.KERNEL_CLASSES["attn_decode"]) == "attn_decode_kernel"
+    assert S.stage_kernel_name(99) is None
