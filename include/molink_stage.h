@@ -22,7 +22,7 @@
  * stage_last_error() gives a message for the calling thread's last failure.
  *
  * The library targets gfx950 only and requires kv_block_size == 16, head_dim in {64, 128},
- * hidden, ffn and num_q_heads*head_dim multiples of 8, num_q_heads a multiple of num_kv_heads
+ * hidden and ffn multiples of 8 and at least 64, num_q_heads a multiple of num_kv_heads
  * with at most 16 query heads per KV head.
  */
 #ifndef MOLINK_STAGE_H

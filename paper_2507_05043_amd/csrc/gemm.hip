@@ -22,36 +22,38 @@ namespace {
 constexpr int kBK = 64;               // K elements per tile
 constexpr int kLdsStride = kBK + 8;   // padded row stride in bf16 elements (144 bytes)
 
-template <int EPI>
-struct ColumnMap {
-  // Maps a column v of the iterated column space to (matrix, row).  For SwiGLU, columns come in
-  // groups of 64: 32 gate rows f..f+31 followed by the 32 up rows with the same f, so that one
-  // wave's two 32-wide MFMA column tiles hold gate and up of the same features.
-  __device__ static __forceinline__ const __bf16* row_ptr(const GemmArgs& p, int v) {
-    if constexpr (EPI == kEpiSwiGLU) {
-      int f = (v >> 6) * 32 + (v & 31);
-      f = f < p.n ? f : p.n - 1;
-      const __bf16* w = (v & 32) ? p.w1 : p.w0;
-      return w + (size_t)f * p.k;
-    } else {
-      const int n = v < p.n ? v : p.n - 1;
-      return p.w0 + (size_t)n * p.k;
-    }
+// Scheduling hint: NOPS memory operations of class OPMASK (0x100 LDS read, 0x200 LDS write) spread evenly
+// between NMFMA MFMAs.  The group sizes must be compile-time constants, hence the recursion.
+template <int R, int NOPS, int NMFMA, int OPMASK, bool OP_FIRST>
+__device__ __forceinline__ void sched_interleave() {
+  if constexpr (R < NOPS) {
+    constexpr int n = (R + 1) * NMFMA / NOPS - R * NMFMA / NOPS;
+    if constexpr (OP_FIRST) __builtin_amdgcn_sched_group_barrier(OPMASK, 1, 0);
+    if constexpr (n > 0) __builtin_amdgcn_sched_group_barrier(0x008, n, 0);
+    if constexpr (!OP_FIRST) __builtin_amdgcn_sched_group_barrier(OPMASK, 1, 0);
+    sched_interleave<R + 1, NOPS, NMFMA, OPMASK, OP_FIRST>();
   }
-};
+}
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, bool SPLIT>
-__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmArgs p, int nv, int tiles_m, int tiles_n,
-                                                                          int splits, int k_tiles_per_split) {
-  constexpr int NTHREADS = WAVES_M * WAVES_N * 64;
-  constexpr int TM = BM / WAVES_M, TN = BN / WAVES_N;
+// Workgroup of 4 waves (2 x 2); wave tile (BM/2) x (BN/2) made of 32x32 MFMA tiles.
+// PF = number of K tiles kept in flight in registers ahead of the one being multiplied.  Small tiles
+// finish a K tile faster than a load returns, so they look two tiles ahead; 256x256 needs only one.
+// Fetches are unconditional (the tile index is clamped at the end of the range, which re-reads the
+// last tile once or twice) so that the loop body has no branches and the waits on outstanding loads
+// count exactly the loads that must have landed.
+template <int BM, int BN, int PF, int EPI, bool SPLIT>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p, int nv, int tiles_m, int tiles_n, int splits,
+                                                        int k_tiles_per_split) {
+  constexpr int NTHREADS = 256;
+  constexpr int TM = BM / 2, TN = BN / 2;
   constexpr int MT = TM / 32, NT = TN / 32;
   constexpr int A_CHUNKS = BM * (kBK / 8) / NTHREADS;   // 16-byte chunks per thread per tile
   constexpr int B_CHUNKS = BN * (kBK / 8) / NTHREADS;
   static_assert(A_CHUNKS >= 1 && B_CHUNKS >= 1, "tile too small for the workgroup");
-  static_assert(EPI != kEpiSwiGLU || TN == 64, "SwiGLU pairs two 32-wide column tiles per wave");
+  static_assert(EPI != kEpiSwiGLU || TN % 64 == 0, "SwiGLU pairs two 32-wide column tiles per wave");
+  static_assert(PF == 1 || PF == 2, "one or two K tiles in flight");
 
   __shared__ __attribute__((aligned(16))) __bf16 lds_a[2][BM * kLdsStride];
   __shared__ __attribute__((aligned(16))) __bf16 lds_b[2][BN * kLdsStride];
@@ -65,55 +67,86 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int wm = wave >> 1, wn = wave & 1;
 
   const int k_tiles = (p.k + kBK - 1) / kBK;
   const int kt_begin = split * k_tiles_per_split;
   const int kt_end = min(kt_begin + k_tiles_per_split, k_tiles);
+  const int nkt = kt_end - kt_begin;
 
-  // per-thread source rows of the global->LDS copy (fixed across K tiles)
-  const __bf16* a_src[A_CHUNKS];
-  const __bf16* b_src[B_CHUNKS];
-  int a_dst[A_CHUNKS], b_dst[B_CHUNKS];
-  const int kc = (tid & 7) * 8;  // this thread's k offset inside a tile
+  // Global->LDS copy.  Chunk i of a thread is 16 bytes of row 32*i + tid/8 at k offset 8*(tid%8); the
+  // byte offsets from the (uniform) matrix bases are fixed across K tiles, so a load is one
+  // instruction with a scalar base that advances along K and a 32-bit per-thread offset.
+  const int kc = (tid & 7) * 8;
+  const int row_in_pass = tid >> 3;
+  uint32_t a_off[A_CHUNKS], b_off[B_CHUNKS];
 #pragma unroll
   for (int i = 0; i < A_CHUNKS; ++i) {
-    const int row = (i * NTHREADS + tid) >> 3;
-    int gm = m0 + row;
+    int gm = m0 + i * 32 + row_in_pass;
     gm = gm < p.m ? gm : p.m - 1;
-    a_src[i] = p.a + (size_t)gm * p.lda + kc;
-    a_dst[i] = row * kLdsStride + kc;
+    a_off[i] = ((uint32_t)gm * (uint32_t)p.lda + kc) * 2u;
   }
 #pragma unroll
   for (int i = 0; i < B_CHUNKS; ++i) {
-    const int row = (i * NTHREADS + tid) >> 3;
-    b_src[i] = ColumnMap<EPI>::row_ptr(p, n0 + row) + kc;
-    b_dst[i] = row * kLdsStride + kc;
+    int row;
+    if constexpr (EPI == kEpiSwiGLU) {
+      // 32 gate rows, then the 32 up rows of the same features: chunk i is gate for even i, up for odd i
+      row = ((n0 >> 6) + (i >> 1)) * 32 + row_in_pass;
+    } else {
+      row = n0 + i * 32 + row_in_pass;
+    }
+    row = row < p.n ? row : p.n - 1;
+    b_off[i] = ((uint32_t)row * (uint32_t)p.k + kc) * 2u;
   }
+  const int lds_dst = row_in_pass * kLdsStride + kc;
 
-  bf16x8 a_reg[A_CHUNKS], b_reg[B_CHUNKS];
-  auto fetch = [&](int kt) {
-    const int k0 = kt * kBK;
-    const bool in_k = (k0 + kc) < p.k;            // K is a multiple of 8: a chunk is all in or all out
-    const int koff = in_k ? k0 : 0;               // keep the address in bounds, zero the data below
+  bf16x8 a_reg[PF][A_CHUNKS], b_reg[PF][B_CHUNKS];
+  int zero_below[PF];   // leading k columns of the tile in a register set that repeat the previous tile
+  auto fetch = [&](int set, int idx) {
+    int kt = kt_begin + idx;
+    kt = kt < kt_end - 1 ? kt : kt_end - 1;
+    // The last tile of a K that is not a multiple of 64 is shifted back to end exactly at K (so every
+    // load stays inside its row); the columns it then shares with the previous tile are zeroed on
+    // their way into LDS.  All of this is uniform: nothing below depends on loaded data.
+    int k0 = kt * kBK;
+    const int k_last = p.k - kBK;
+    zero_below[set] = k0 > k_last ? k0 - k_last : 0;
+    k0 = k0 > k_last ? k_last : k0;
+    const char* abase = reinterpret_cast<const char*>(p.a + k0);
+    const char* w0base = reinterpret_cast<const char*>(p.w0 + k0);
 #pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) {
-      bf16x8 v = load8(a_src[i] + koff - (in_k ? 0 : kc));
-      if (!in_k) v = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-      a_reg[i] = v;
-    }
+    for (int i = 0; i < A_CHUNKS; ++i) a_reg[set][i] = *reinterpret_cast<const bf16x8*>(abase + a_off[i]);
+    if constexpr (EPI == kEpiSwiGLU) {
+      const char* w1base = reinterpret_cast<const char*>(p.w1 + k0);
 #pragma unroll
-    for (int i = 0; i < B_CHUNKS; ++i) {
-      bf16x8 v = load8(b_src[i] + koff - (in_k ? 0 : kc));
-      if (!in_k) v = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-      b_reg[i] = v;
+      for (int i = 0; i < B_CHUNKS; ++i)
+        b_reg[set][i] = *reinterpret_cast<const bf16x8*>(((i & 1) ? w1base : w0base) + b_off[i]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < B_CHUNKS; ++i) b_reg[set][i] = *reinterpret_cast<const bf16x8*>(w0base + b_off[i]);
     }
+    __builtin_amdgcn_sched_barrier(0);   // keep the loads here, ahead of the MFMAs they overlap with
   };
-  auto stash = [&](int buf) {
+  // LDS writes of one register set: plain copies, nothing is computed on the loaded data (any
+  // arithmetic on it would be scheduled early and stall on the loads that were just issued).
+  auto stash = [&](int set, int buf) {
 #pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<bf16x8*>(&lds_a[buf][a_dst[i]]) = a_reg[i];
+    for (int i = 0; i < A_CHUNKS; ++i)
+      *reinterpret_cast<bf16x8*>(&lds_a[buf][lds_dst + i * 32 * kLdsStride]) = a_reg[set][i];
 #pragma unroll
-    for (int i = 0; i < B_CHUNKS; ++i) *reinterpret_cast<bf16x8*>(&lds_b[buf][b_dst[i]]) = b_reg[i];
+    for (int i = 0; i < B_CHUNKS; ++i)
+      *reinterpret_cast<bf16x8*>(&lds_b[buf][lds_dst + i * 32 * kLdsStride]) = b_reg[set][i];
+  };
+  // The shifted last tile of a K that is not a multiple of 64: overwrite the columns it shares with
+  // the previous tile with zeros (after this thread's own copies; LDS operations of a wave are ordered).
+  auto patch_tail = [&](int set, int buf) {
+    if (zero_below[set] > 0 && kc < zero_below[set]) {
+      const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+      for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<bf16x8*>(&lds_a[buf][lds_dst + i * 32 * kLdsStride]) = zero;
+#pragma unroll
+      for (int i = 0; i < B_CHUNKS; ++i) *reinterpret_cast<bf16x8*>(&lds_b[buf][lds_dst + i * 32 * kLdsStride]) = zero;
+    }
   };
 
   f32x16 acc[MT][NT];
@@ -124,34 +157,73 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  if (kt_begin < kt_end) {
-    fetch(kt_begin);
-    stash(0);
-  }
-  __syncthreads();
-
   const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
-  for (int kt = kt_begin; kt < kt_end; ++kt) {
-    const int buf = (kt - kt_begin) & 1;
-    const bool more = kt + 1 < kt_end;
-    if (more) fetch(kt + 1);
+  // One K tile: 4 steps of 16 k.  The LDS reads of step kk+1 are issued under the MFMAs of step kk
+  // (fragments are double buffered in registers), and the LDS writes of the next tile (register set
+  // `st_set` into buffer `st_buf`, if st_set >= 0) are spread under the MFMAs of the last step.
+  auto multiply = [&](int buf, int st_set, int st_buf) {
     const __bf16* la = &lds_a[buf][(wm * TM + frag_row) * kLdsStride + frag_k];
     const __bf16* lb = &lds_b[buf][(wn * TN + frag_row) * kLdsStride + frag_k];
+    bf16x8 af[2][MT], bfr[2][NT];
+    auto read_frags = [&](int s, int kk) {
 #pragma unroll
-    for (int kk = 0; kk < kBK / 16; ++kk) {
-      bf16x8 af[MT], bfr[NT];
+      for (int i = 0; i < MT; ++i) af[s][i] = *reinterpret_cast<const bf16x8*>(la + i * 32 * kLdsStride + kk * 16);
 #pragma unroll
-      for (int i = 0; i < MT; ++i) af[i] = *reinterpret_cast<const bf16x8*>(la + i * 32 * kLdsStride + kk * 16);
+      for (int j = 0; j < NT; ++j) bfr[s][j] = *reinterpret_cast<const bf16x8*>(lb + j * 32 * kLdsStride + kk * 16);
+    };
+    constexpr int KSTEPS = kBK / 16, NMFMA = MT * NT, NREAD = MT + NT, NWRITE = A_CHUNKS + B_CHUNKS;
+    read_frags(0, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, NREAD, 0);   // the first step's fragments cannot overlap anything
 #pragma unroll
-      for (int j = 0; j < NT; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(lb + j * 32 * kLdsStride + kk * 16);
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+      if (kk + 1 < KSTEPS) read_frags((kk + 1) & 1, kk + 1);
+      if (kk + 1 == KSTEPS && st_set >= 0) stash(st_set, st_buf);
 #pragma unroll
       for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int j = 0; j < NT; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+      // scheduling pattern for this step: memory operations spread evenly between the MFMAs
+      if (kk + 1 < KSTEPS) {
+        sched_interleave<0, NREAD, NMFMA, 0x100, true>();
+      } else if (st_set >= 0) {
+        sched_interleave<0, NWRITE, NMFMA, 0x200, false>();
+      }
     }
-    if (more) stash(buf ^ 1);
-    __syncthreads();
+  };
+
+  if (nkt > 0) {
+    if constexpr (PF == 1) {
+      fetch(0, 0);
+      stash(0, 0);
+      patch_tail(0, 0);
+      __syncthreads();
+      for (int i = 0; i < nkt; ++i) {
+        fetch(0, i + 1);
+        multiply(i & 1, 0, (i & 1) ^ 1);
+        patch_tail(0, (i & 1) ^ 1);
+        __syncthreads();
+      }
+    } else {
+      // tile i is in LDS buffer i&1; register set (i+1)&1 holds tile i+1; set i&1 is free for tile i+2
+      fetch(0, 0);
+      fetch(1, 1);
+      stash(0, 0);
+      patch_tail(0, 0);
+      __syncthreads();
+      int i = 0;
+      for (; i + 2 <= nkt; i += 2) {
+        fetch(0, i + 2);
+        multiply(0, 1, 1);
+        patch_tail(1, 1);
+        __syncthreads();
+        fetch(1, i + 3);
+        multiply(1, 0, 0);
+        patch_tail(0, 0);
+        __syncthreads();
+      }
+      if (i < nkt) multiply(0, -1, 0);
+    }
   }
 
   // Epilogue.  Accumulator register r of lane l is C[row 8*(r/4) + 4*(l/32) + r%4][col l%32] of its tile.
@@ -170,9 +242,12 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
           if (v < nv) p.partial[((size_t)split * p.m + m) * nv + v] = acc[i][j][r];
         }
       } else if constexpr (EPI == kEpiSwiGLU) {
-        const int v = n0 + wn * TN + col_in_tile;          // gate column; up is 32 further
-        const int f = (v >> 6) * 32 + (v & 31);
-        if (f < p.n) p.out_bf16[(size_t)m * p.ldo + f] = f32_to_bf16(silu_f(acc[i][0][r]) * acc[i][1][r]);
+#pragma unroll
+        for (int j = 0; j < NT; j += 2) {
+          const int v = n0 + wn * TN + j * 32 + col_in_tile;   // gate column; its up column is 32 further
+          const int f = (v >> 6) * 32 + (v & 31);
+          if (f < p.n) p.out_bf16[(size_t)m * p.ldo + f] = f32_to_bf16(silu_f(acc[i][j][r]) * acc[i][j + 1][r]);
+        }
       } else {
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
@@ -269,39 +344,62 @@ __global__ __launch_bounds__(1024) void reduce_residual_norm_kernel(const float*
   }
 }
 
-template <int BM, int BN, int EPI>
+template <int BM, int BN, int PF, int EPI>
 hipError_t launch_tile(const GemmArgs& a, const GemmPlan& plan, hipStream_t stream) {
   const int tiles_m = (a.m + BM - 1) / BM;
   const int tiles_n = (plan.nv + BN - 1) / BN;
   const int total = tiles_m * tiles_n * plan.splits;
   dim3 grid(xcd_grid(total)), block(256);
   if (plan.splits > 1) {
-    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, 2, 2, EPI, true>), grid, block, 0, stream, a, plan.nv, tiles_m, tiles_n,
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, PF, EPI, true>), grid, block, 0, stream, a, plan.nv, tiles_m, tiles_n,
                        plan.splits, plan.k_tiles_per_split);
   } else {
-    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, 2, 2, EPI, false>), grid, block, 0, stream, a, plan.nv, tiles_m,
-                       tiles_n, 1, plan.k_tiles_per_split);
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, PF, EPI, false>), grid, block, 0, stream, a, plan.nv, tiles_m, tiles_n,
+                       1, plan.k_tiles_per_split);
   }
   return hipGetLastError();
 }
 
 template <int EPI>
 hipError_t launch_epi(const GemmArgs& a, const GemmPlan& plan, hipStream_t stream) {
-  return plan.tile == 0 ? launch_tile<128, 128, EPI>(a, plan, stream) : launch_tile<64, 128, EPI>(a, plan, stream);
+  switch (plan.tile) {
+    case kTile256x256: return launch_tile<256, 256, 1, EPI>(a, plan, stream);
+    case kTile256x128: return launch_tile<256, 128, 2, EPI>(a, plan, stream);
+    case kTile128x128: return launch_tile<128, 128, 2, EPI>(a, plan, stream);
+    default: return launch_tile<64, 128, 2, EPI>(a, plan, stream);
+  }
 }
 
 }  // namespace
 
 GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus) {
   GemmPlan plan;
-  plan.tile = m <= 64 ? 1 : 0;
-  const int bm = plan.tile == 0 ? 128 : 64, bn = 128;
   plan.nv = epi == kEpiSwiGLU ? ((n + 31) / 32) * 64 : n;
-  const int tiles = ((m + bm - 1) / bm) * ((plan.nv + bn - 1) / bn);
   const int k_tiles = (k + kBK - 1) / kBK;
+  struct Cand { int tile, bm, bn, wg_per_cu; float eff; };
+  // relative MFMA efficiency of a tile shape (LDS traffic per MFMA) and how many fit on a CU (LDS)
+  static const Cand cands[] = {{kTile256x256, 256, 256, 1, 1.0f}, {kTile256x128, 256, 128, 1, 0.85f},
+                               {kTile128x128, 128, 128, 2, 0.7f}};
+  if (m <= 64) {
+    plan.tile = kTile64x128;
+  } else {
+    float best = 0.f;
+    plan.tile = kTile128x128;
+    for (const Cand& c : cands) {
+      const long tiles = (long)((m + c.bm - 1) / c.bm) * ((plan.nv + c.bn - 1) / c.bn);
+      const long slots = (long)num_cus * c.wg_per_cu;
+      const long rounds = (tiles + slots - 1) / slots;
+      const float cost = (float)rounds * c.bm * c.bn * c.wg_per_cu / c.eff;
+      if (best == 0.f || cost < best) { best = cost; plan.tile = c.tile; }
+    }
+  }
+  const int bm = plan.tile == kTile64x128 ? 64 : (plan.tile == kTile128x128 ? 128 : 256);
+  const int bn = plan.tile == kTile256x256 ? 256 : 128;
+  const int wg_per_cu = (plan.tile == kTile128x128 || plan.tile == kTile64x128) ? 2 : 1;
+  const int tiles = ((m + bm - 1) / bm) * ((plan.nv + bn - 1) / bn);
   int splits = 1;
-  if (tiles < num_cus) {
-    splits = (2 * num_cus + tiles - 1) / tiles;
+  if (tiles * 2 <= num_cus * wg_per_cu) {
+    splits = (num_cus * wg_per_cu + tiles - 1) / tiles;
     const int max_by_k = k_tiles / 4 > 0 ? k_tiles / 4 : 1;   // at least 4 K tiles per split
     if (splits > max_by_k) splits = max_by_k;
     if (splits > 16) splits = 16;

@@ -23,8 +23,10 @@ struct GemmArgs {
   int lda, ldo;         // leading dimensions (elements) of a and out_bf16
 };
 
+enum GemmTile : int { kTile256x256 = 0, kTile256x128 = 1, kTile128x128 = 2, kTile64x128 = 3 };
+
 struct GemmPlan {
-  int tile;             // 0: 128x128 workgroup tile, 1: 64x128
+  int tile;             // GemmTile: workgroup tile shape
   int splits;           // K splits across workgroups (1 = epilogue fused into the GEMM kernel)
   int k_tiles_per_split;
   int nv;               // width of the column space the kernel iterates (gate/up interleaved for SwiGLU, else N)

@@ -58,8 +58,9 @@ int check_config(const stage_config* c) {
   if (!c) return fail(STAGE_ERR_NULL, "stage_config is NULL");
   if (c->struct_size != sizeof(stage_config))
     return fail(STAGE_ERR_CONFIG, "stage_config.struct_size %u != %zu", c->struct_size, sizeof(stage_config));
-  if (c->num_layers < 1 || c->hidden < 8 || c->num_q_heads < 1 || c->num_kv_heads < 1 || c->ffn < 8)
+  if (c->num_layers < 1 || c->num_q_heads < 1 || c->num_kv_heads < 1)
     return fail(STAGE_ERR_CONFIG, "non-positive dimension in stage_config");
+  if (c->hidden < 64 || c->ffn < 64) return fail(STAGE_ERR_CONFIG, "hidden and ffn must be at least 64");
   if (c->kv_block_size != 16) return fail(STAGE_ERR_CONFIG, "kv_block_size must be 16, got %d", c->kv_block_size);
   if (c->head_dim != 64 && c->head_dim != 128)
     return fail(STAGE_ERR_CONFIG, "head_dim must be 64 or 128, got %d", c->head_dim);
