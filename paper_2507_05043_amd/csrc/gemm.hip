@@ -1,10 +1,10 @@
 // bf16 MFMA GEMM for the stage's projections: C[M][N] = A[M][K] * W[N][K]^T, fp32 accumulate.
 //
 // Both operands are K-contiguous, which is the layout the 32x32x16 bf16 MFMA wants in its lanes
-// (lane l holds 8 consecutive k of row l%32).  Tiles travel HBM -> registers (16-byte coalesced
-// loads) -> LDS (row stride padded by 16 bytes, so 128-bit LDS reads of 8 consecutive rows cover all
-// banks) -> MFMA operands.  The next K tile is prefetched into registers while the current one is
-// multiplied; LDS is double buffered so one barrier per K tile suffices.
+// (lane l holds 8 consecutive k of row l%32).  Tiles travel HBM/L2 -> LDS directly (16 bytes per lane,
+// 8 rows x 128 bytes per wave instruction, XOR-swizzled so 128-bit LDS reads are conflict free) ->
+// MFMA operands.  Two to three K tiles are kept in flight in separate LDS stages; one barrier per K
+// tile; LDS reads and tile loads are interleaved with the MFMAs by explicit scheduling hints.
 //
 // Workgroup ids are remapped so that consecutive logical tiles share an XCD: the M tiles that reuse
 // one weight tile run next to each other on one L2.
@@ -15,6 +15,8 @@
 #include "gemm.hpp"
 #include "common.hpp"
 
+#include <type_traits>
+
 namespace molink {
 
 namespace {
@@ -22,41 +24,75 @@ namespace {
 constexpr int kBK = 64;               // K elements per tile
 constexpr int kLdsStride = kBK + 8;   // padded row stride in bf16 elements (144 bytes)
 
-// Scheduling hint: NOPS memory operations of class OPMASK (0x100 LDS read, 0x200 LDS write) spread evenly
-// between NMFMA MFMAs.  The group sizes must be compile-time constants, hence the recursion.
-template <int R, int NOPS, int NMFMA, int OPMASK, bool OP_FIRST>
-__device__ __forceinline__ void sched_interleave() {
-  if constexpr (R < NOPS) {
-    constexpr int n = (R + 1) * NMFMA / NOPS - R * NMFMA / NOPS;
-    if constexpr (OP_FIRST) __builtin_amdgcn_sched_group_barrier(OPMASK, 1, 0);
-    if constexpr (n > 0) __builtin_amdgcn_sched_group_barrier(0x008, n, 0);
-    if constexpr (!OP_FIRST) __builtin_amdgcn_sched_group_barrier(OPMASK, 1, 0);
-    sched_interleave<R + 1, NOPS, NMFMA, OPMASK, OP_FIRST>();
+// Scheduling hint for one MFMA step of NMFMA MFMAs.  After each MFMA come the memory operations that
+// run in its shadow: the NREAD LDS reads of the next step's fragments are placed behind the first
+// MFMAs (so they have landed when the step ends), and the step's NLOAD tile loads are spread evenly
+// over the whole step - a wave that issues its loads in one burst sits in the address unit's queue and
+// issues no MFMA meanwhile.  Group sizes must be compile-time constants, hence the recursion.
+template <int R, int NMFMA, int NREAD, int NLOAD>
+__device__ __forceinline__ void sched_step() {
+  if constexpr (R < NMFMA) {
+    constexpr int RSLOTS = NMFMA < NREAD ? NMFMA : (NREAD > 0 ? NREAD : 1);
+    constexpr int reads = R < RSLOTS ? (R + 1) * NREAD / RSLOTS - R * NREAD / RSLOTS : 0;
+    constexpr int loads = (R + 1) * NLOAD / NMFMA - R * NLOAD / NMFMA;
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if constexpr (reads > 0) __builtin_amdgcn_sched_group_barrier(0x100, reads, 0);
+    if constexpr (loads > 0) __builtin_amdgcn_sched_group_barrier(0x010, loads, 0);
+    sched_step<R + 1, NMFMA, NREAD, NLOAD>();
   }
 }
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 
-// Workgroup of 4 waves (2 x 2); wave tile (BM/2) x (BN/2) made of 32x32 MFMA tiles.
-// PF = number of K tiles kept in flight in registers ahead of the one being multiplied.  Small tiles
-// finish a K tile faster than a load returns, so they look two tiles ahead; 256x256 needs only one.
-// Fetches are unconditional (the tile index is clamped at the end of the range, which re-reads the
-// last tile once or twice) so that the loop body has no branches and the waits on outstanding loads
-// count exactly the loads that must have landed.
-template <int BM, int BN, int PF, int EPI, bool SPLIT>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p, int nv, int tiles_m, int tiles_n, int splits,
-                                                        int k_tiles_per_split) {
-  constexpr int NTHREADS = 256;
-  constexpr int TM = BM / 2, TN = BN / 2;
-  constexpr int MT = TM / 32, NT = TN / 32;
-  constexpr int A_CHUNKS = BM * (kBK / 8) / NTHREADS;   // 16-byte chunks per thread per tile
-  constexpr int B_CHUNKS = BN * (kBK / 8) / NTHREADS;
-  static_assert(A_CHUNKS >= 1 && B_CHUNKS >= 1, "tile too small for the workgroup");
-  static_assert(EPI != kEpiSwiGLU || TN % 64 == 0, "SwiGLU pairs two 32-wide column tiles per wave");
-  static_assert(PF == 1 || PF == 2, "one or two K tiles in flight");
+// LDS stages live in separate arrays so that the compiler can tell a stage being filled from the
+// stage being read (a single array indexed by the stage would force every LDS read to wait for all
+// loads in flight).
+template <int BYTES> struct LdsStages {
+  template <int S> static __device__ __forceinline__ char* get() {
+    __shared__ __attribute__((aligned(1024))) char stage[BYTES];
+    return stage;
+  }
+};
 
-  __shared__ __attribute__((aligned(16))) __bf16 lds_a[2][BM * kLdsStride];
-  __shared__ __attribute__((aligned(16))) __bf16 lds_b[2][BN * kLdsStride];
+// s_waitcnt on the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and 15:14).
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0070 | 0x0F00);
+}
+
+// Workgroup barrier without the memory fence of __syncthreads(): that fence would wait for every load
+// in flight, including the tiles being prefetched into other LDS stages.  The caller has already
+// waited for exactly the loads the other waves are about to read; this only drains the wave's own LDS
+// operations and keeps the compiler from moving memory accesses across the barrier.
+__device__ __forceinline__ void pipeline_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0), vmcnt and expcnt untouched
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+// Workgroup of 4 waves (2 x 2); wave tile (BM/2) x (BN/2) made of 32x32 MFMA tiles; K tile of 64.
+//
+// Tiles go from global memory straight into LDS (global_load_lds_dwordx4: each lane's 16 bytes land at
+// the wave's LDS base + 16*lane), so data in flight costs no registers and the pipeline depth is set
+// by how many stages fit in the 160 KB of LDS (NSTAGE-1 tiles in flight).  One wave instruction
+// fills 8 rows x 128 bytes.  Rows are unpadded; bank conflicts are avoided by an XOR swizzle applied
+// to the *global* address each lane fetches: slot p of row r holds the row's 16-byte chunk p ^ (r & 7),
+// so the 8 lanes of a 128-bit LDS read that hit rows r..r+7 at the same logical chunk touch 8
+// different slots.  LDS reads of MFMA step kk+1 are issued under the MFMAs of step kk.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int EPI, bool SPLIT>
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmArgs p, int nv, int tiles_m, int tiles_n, int splits,
+                                                        int k_tiles_per_split) {
+  constexpr int NWAVES = WAVES_M * WAVES_N;
+  constexpr int TM = BM / WAVES_M, TN = BN / WAVES_N;
+  constexpr int MT = TM / 32, NT = TN / 32;
+  constexpr int GROUPS = (BM + BN) / 8;        // 8-row groups per stage (A rows first, then B rows)
+  constexpr int NI = GROUPS / NWAVES;          // load instructions per wave per tile
+  static_assert(GROUPS % NWAVES == 0, "row groups must divide evenly among the waves");
+  constexpr int STAGE_BYTES = (BM + BN) * 128;
+  static_assert(EPI != kEpiSwiGLU || TN % 64 == 0, "SwiGLU pairs two 32-wide column tiles per wave");
+  static_assert(NSTAGE >= 2 && NSTAGE <= 4 && NSTAGE * STAGE_BYTES <= 160 * 1024, "stages must fit in LDS");
+  using Lds = LdsStages<STAGE_BYTES>;
 
   const int total = tiles_m * tiles_n * splits;
   const int lid = xcd_logical_id(blockIdx.x, total);
@@ -66,86 +102,72 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p, int nv, int 
   const int tile_n = lid / (tiles_m * splits);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
   const int k_tiles = (p.k + kBK - 1) / kBK;
   const int kt_begin = split * k_tiles_per_split;
   const int kt_end = min(kt_begin + k_tiles_per_split, k_tiles);
   const int nkt = kt_end - kt_begin;
 
-  // Global->LDS copy.  Chunk i of a thread is 16 bytes of row 32*i + tid/8 at k offset 8*(tid%8); the
-  // byte offsets from the (uniform) matrix bases are fixed across K tiles, so a load is one
-  // instruction with a scalar base that advances along K and a 32-bit per-thread offset.
-  const int kc = (tid & 7) * 8;
-  const int row_in_pass = tid >> 3;
-  uint32_t a_off[A_CHUNKS], b_off[B_CHUNKS];
+  // Load instruction j of this wave fills row group g = 4*j + wave.  This lane's slot in the group is
+  // (row 8*g + lane/8, position lane%8) and receives the row's chunk (lane%8) ^ (lane/8).
+  const int sw_chunk = (lane & 7) ^ (lane >> 3);
+  uint32_t g_off[NI];     // byte offset of this lane's chunk from the matrix base at k = 0
 #pragma unroll
-  for (int i = 0; i < A_CHUNKS; ++i) {
-    int gm = m0 + i * 32 + row_in_pass;
-    gm = gm < p.m ? gm : p.m - 1;
-    a_off[i] = ((uint32_t)gm * (uint32_t)p.lda + kc) * 2u;
-  }
-#pragma unroll
-  for (int i = 0; i < B_CHUNKS; ++i) {
-    int row;
-    if constexpr (EPI == kEpiSwiGLU) {
-      // 32 gate rows, then the 32 up rows of the same features: chunk i is gate for even i, up for odd i
-      row = ((n0 >> 6) + (i >> 1)) * 32 + row_in_pass;
+  for (int j = 0; j < NI; ++j) {
+    const int g = NWAVES * j + wave;
+    const int r = 8 * g + (lane >> 3);            // row inside the stage (A rows, then B rows)
+    if (r < BM) {
+      int gm = m0 + r;
+      gm = gm < p.m ? gm : p.m - 1;
+      g_off[j] = ((uint32_t)gm * (uint32_t)p.lda + sw_chunk * 8) * 2u;
     } else {
-      row = n0 + i * 32 + row_in_pass;
+      int row;
+      if constexpr (EPI == kEpiSwiGLU) {
+        // 32 gate rows, then the 32 up rows of the same features (which matrix is decided per 8-row group)
+        const int v = n0 + (r - BM);
+        row = (v >> 6) * 32 + (v & 31);
+      } else {
+        row = n0 + (r - BM);
+      }
+      row = row < p.n ? row : p.n - 1;
+      g_off[j] = ((uint32_t)row * (uint32_t)p.k + sw_chunk * 8) * 2u;
     }
-    row = row < p.n ? row : p.n - 1;
-    b_off[i] = ((uint32_t)row * (uint32_t)p.k + kc) * 2u;
   }
-  const int lds_dst = row_in_pass * kLdsStride + kc;
 
-  bf16x8 a_reg[PF][A_CHUNKS], b_reg[PF][B_CHUNKS];
-  int zero_below[PF];   // leading k columns of the tile in a register set that repeat the previous tile
-  auto fetch = [&](int set, int idx) {
+  int zero_below[NSTAGE];   // per stage: leading k columns that repeat the previous tile (shifted last tile)
+  auto fetch = [&](auto stage_c, int idx) {
+    constexpr int S = decltype(stage_c)::value;
     int kt = kt_begin + idx;
     kt = kt < kt_end - 1 ? kt : kt_end - 1;
-    // The last tile of a K that is not a multiple of 64 is shifted back to end exactly at K (so every
-    // load stays inside its row); the columns it then shares with the previous tile are zeroed on
-    // their way into LDS.  All of this is uniform: nothing below depends on loaded data.
+    // The last tile of a K that is not a multiple of 64 is shifted back to end exactly at K (every load
+    // stays inside its row); the columns it shares with the previous tile are zeroed in LDS afterwards.
     int k0 = kt * kBK;
     const int k_last = p.k - kBK;
-    zero_below[set] = k0 > k_last ? k0 - k_last : 0;
+    zero_below[S] = k0 > k_last ? k0 - k_last : 0;
     k0 = k0 > k_last ? k_last : k0;
     const char* abase = reinterpret_cast<const char*>(p.a + k0);
     const char* w0base = reinterpret_cast<const char*>(p.w0 + k0);
+    const char* w1base = EPI == kEpiSwiGLU ? reinterpret_cast<const char*>(p.w1 + k0) : w0base;
+    char* stage = Lds::template get<S>();
 #pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) a_reg[set][i] = *reinterpret_cast<const bf16x8*>(abase + a_off[i]);
-    if constexpr (EPI == kEpiSwiGLU) {
-      const char* w1base = reinterpret_cast<const char*>(p.w1 + k0);
-#pragma unroll
-      for (int i = 0; i < B_CHUNKS; ++i)
-        b_reg[set][i] = *reinterpret_cast<const bf16x8*>(((i & 1) ? w1base : w0base) + b_off[i]);
-    } else {
-#pragma unroll
-      for (int i = 0; i < B_CHUNKS; ++i) b_reg[set][i] = *reinterpret_cast<const bf16x8*>(w0base + b_off[i]);
+    for (int j = 0; j < NI; ++j) {
+      const int g = NWAVES * j + wave;                          // uniform
+      const char* base = g < BM / 8 ? abase : ((EPI == kEpiSwiGLU && ((g - BM / 8) & 4)) ? w1base : w0base);
+      __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(base + g_off[j]),
+                                       reinterpret_cast<uint32_t*>(stage + g * 1024), 16, 0, 0);
     }
-    __builtin_amdgcn_sched_barrier(0);   // keep the loads here, ahead of the MFMAs they overlap with
   };
-  // LDS writes of one register set: plain copies, nothing is computed on the loaded data (any
-  // arithmetic on it would be scheduled early and stall on the loads that were just issued).
-  auto stash = [&](int set, int buf) {
+  // Zero the duplicated columns of a shifted last tile: each lane patches the slots it loaded itself.
+  auto patch_tail = [&](auto stage_c) {
+    constexpr int S = decltype(stage_c)::value;
+    if (zero_below[S] > 0 && sw_chunk * 8 < zero_below[S]) {
+      char* stage = Lds::template get<S>();
+      const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i)
-      *reinterpret_cast<bf16x8*>(&lds_a[buf][lds_dst + i * 32 * kLdsStride]) = a_reg[set][i];
-#pragma unroll
-    for (int i = 0; i < B_CHUNKS; ++i)
-      *reinterpret_cast<bf16x8*>(&lds_b[buf][lds_dst + i * 32 * kLdsStride]) = b_reg[set][i];
-  };
-  // The shifted last tile of a K that is not a multiple of 64: overwrite the columns it shares with
-  // the previous tile with zeros (after this thread's own copies; LDS operations of a wave are ordered).
-  auto patch_tail = [&](int set, int buf) {
-    if (zero_below[set] > 0 && kc < zero_below[set]) {
-      const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-      for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<bf16x8*>(&lds_a[buf][lds_dst + i * 32 * kLdsStride]) = zero;
-#pragma unroll
-      for (int i = 0; i < B_CHUNKS; ++i) *reinterpret_cast<bf16x8*>(&lds_b[buf][lds_dst + i * 32 * kLdsStride]) = zero;
+      for (int j = 0; j < NI; ++j) *reinterpret_cast<u32x4*>(stage + (NWAVES * j + wave) * 1024 + lane * 16) = zero;
     }
   };
 
@@ -157,73 +179,80 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p, int nv, int 
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
-  // One K tile: 4 steps of 16 k.  The LDS reads of step kk+1 are issued under the MFMAs of step kk
-  // (fragments are double buffered in registers), and the LDS writes of the next tile (register set
-  // `st_set` into buffer `st_buf`, if st_set >= 0) are spread under the MFMAs of the last step.
-  auto multiply = [&](int buf, int st_set, int st_buf) {
-    const __bf16* la = &lds_a[buf][(wm * TM + frag_row) * kLdsStride + frag_k];
-    const __bf16* lb = &lds_b[buf][(wn * TN + frag_row) * kLdsStride + frag_k];
+  // fragment reads: lane (row l%32, k half l/32) of step kk wants chunk 2*kk + l/32 of its row, which
+  // sits at slot (2*kk + l/32) ^ (l % 8) since every fragment's first row is a multiple of 32
+  const int frag_row = lane & 31;
+  int frag_off[kBK / 16];
+#pragma unroll
+  for (int kk = 0; kk < kBK / 16; ++kk) frag_off[kk] = frag_row * 128 + (((2 * kk + (lane >> 5)) ^ (lane & 7)) * 16);
+
+  auto multiply = [&](auto stage_c) {
+    constexpr int S = decltype(stage_c)::value;
+    const char* la = Lds::template get<S>() + wm * TM * 128;
+    const char* lb = Lds::template get<S>() + (BM + wn * TN) * 128;
     bf16x8 af[2][MT], bfr[2][NT];
     auto read_frags = [&](int s, int kk) {
 #pragma unroll
-      for (int i = 0; i < MT; ++i) af[s][i] = *reinterpret_cast<const bf16x8*>(la + i * 32 * kLdsStride + kk * 16);
+      for (int i = 0; i < MT; ++i) af[s][i] = *reinterpret_cast<const bf16x8*>(la + i * 32 * 128 + frag_off[kk]);
 #pragma unroll
-      for (int j = 0; j < NT; ++j) bfr[s][j] = *reinterpret_cast<const bf16x8*>(lb + j * 32 * kLdsStride + kk * 16);
+      for (int j = 0; j < NT; ++j) bfr[s][j] = *reinterpret_cast<const bf16x8*>(lb + j * 32 * 128 + frag_off[kk]);
     };
-    constexpr int KSTEPS = kBK / 16, NMFMA = MT * NT, NREAD = MT + NT, NWRITE = A_CHUNKS + B_CHUNKS;
+    constexpr int KSTEPS = kBK / 16, NMFMA = MT * NT, NREAD = MT + NT, NLOADS = NI;
     read_frags(0, 0);
     __builtin_amdgcn_sched_group_barrier(0x100, NREAD, 0);   // the first step's fragments cannot overlap anything
-#pragma unroll
-    for (int kk = 0; kk < KSTEPS; ++kk) {
-      if (kk + 1 < KSTEPS) read_frags((kk + 1) & 1, kk + 1);
-      if (kk + 1 == KSTEPS && st_set >= 0) stash(st_set, st_buf);
+    auto mfma_step = [&](auto kk_c) {
+      constexpr int kk = decltype(kk_c)::value;
+      if constexpr (kk + 1 < KSTEPS) read_frags((kk + 1) & 1, kk + 1);
 #pragma unroll
       for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int j = 0; j < NT; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
-      // scheduling pattern for this step: memory operations spread evenly between the MFMAs
-      if (kk + 1 < KSTEPS) {
-        sched_interleave<0, NREAD, NMFMA, 0x100, true>();
-      } else if (st_set >= 0) {
-        sched_interleave<0, NWRITE, NMFMA, 0x200, false>();
-      }
-    }
+      // a quarter of this pipeline step's tile loads goes behind each MFMA step
+      constexpr int loads = (kk + 1) * NLOADS / KSTEPS - kk * NLOADS / KSTEPS;
+      sched_step<0, NMFMA, (kk + 1 < KSTEPS ? NREAD : 0), loads>();
+    };
+    static_assert(KSTEPS == 4, "four MFMA steps per K tile");
+    mfma_step(std::integral_constant<int, 0>{});
+    mfma_step(std::integral_constant<int, 1>{});
+    mfma_step(std::integral_constant<int, 2>{});
+    mfma_step(std::integral_constant<int, 3>{});
+  };
+
+  // One pipeline step: tile idx is in stage S.  Refill the stage that was read in the previous step with
+  // tile idx + NSTAGE - 1, multiply, then wait until tile idx + 1 has landed (newer tiles may still be
+  // in flight) and meet the other waves.
+  auto step = [&](auto stage_c, int idx) {
+    constexpr int S = decltype(stage_c)::value;
+    fetch(std::integral_constant<int, (S + NSTAGE - 1) % NSTAGE>{}, idx + NSTAGE - 1);
+    multiply(stage_c);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vmcnt<(NSTAGE - 2) * NI>();
+    patch_tail(std::integral_constant<int, (S + 1) % NSTAGE>{});
+    pipeline_barrier();
   };
 
   if (nkt > 0) {
-    if constexpr (PF == 1) {
-      fetch(0, 0);
-      stash(0, 0);
-      patch_tail(0, 0);
-      __syncthreads();
-      for (int i = 0; i < nkt; ++i) {
-        fetch(0, i + 1);
-        multiply(i & 1, 0, (i & 1) ^ 1);
-        patch_tail(0, (i & 1) ^ 1);
-        __syncthreads();
-      }
-    } else {
-      // tile i is in LDS buffer i&1; register set (i+1)&1 holds tile i+1; set i&1 is free for tile i+2
-      fetch(0, 0);
-      fetch(1, 1);
-      stash(0, 0);
-      patch_tail(0, 0);
-      __syncthreads();
-      int i = 0;
-      for (; i + 2 <= nkt; i += 2) {
-        fetch(0, i + 2);
-        multiply(0, 1, 1);
-        patch_tail(1, 1);
-        __syncthreads();
-        fetch(1, i + 3);
-        multiply(1, 0, 0);
-        patch_tail(0, 0);
-        __syncthreads();
-      }
-      if (i < nkt) multiply(0, -1, 0);
+    // prologue: tiles 0 .. NSTAGE-2 in flight, tile 0 landed
+    fetch(std::integral_constant<int, 0>{}, 0);
+    if constexpr (NSTAGE > 2) fetch(std::integral_constant<int, 1>{}, 1);
+    if constexpr (NSTAGE > 3) fetch(std::integral_constant<int, 2>{}, 2);
+    wait_vmcnt<(NSTAGE - 2) * NI>();
+    patch_tail(std::integral_constant<int, 0>{});
+    pipeline_barrier();
+    int i = 0;
+    for (; i + NSTAGE <= nkt; i += NSTAGE) {
+      step(std::integral_constant<int, 0>{}, i);
+      step(std::integral_constant<int, 1>{}, i + 1);
+      if constexpr (NSTAGE > 2) step(std::integral_constant<int, 2>{}, i + 2);
+      if constexpr (NSTAGE > 3) step(std::integral_constant<int, 3>{}, i + 3);
     }
+    if (i < nkt) step(std::integral_constant<int, 0>{}, i);
+    if (i + 1 < nkt) step(std::integral_constant<int, 1>{}, i + 1);
+    if constexpr (NSTAGE > 3) {
+      if (i + 2 < nkt) step(std::integral_constant<int, 2>{}, i + 2);
+    }
+    wait_vmcnt<0>();   // nothing may still be writing LDS when the workgroup ends
   }
 
   // Epilogue.  Accumulator register r of lane l is C[row 8*(r/4) + 4*(l/32) + r%4][col l%32] of its tile.
@@ -344,18 +373,18 @@ __global__ __launch_bounds__(1024) void reduce_residual_norm_kernel(const float*
   }
 }
 
-template <int BM, int BN, int PF, int EPI>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int EPI>
 hipError_t launch_tile(const GemmArgs& a, const GemmPlan& plan, hipStream_t stream) {
   const int tiles_m = (a.m + BM - 1) / BM;
   const int tiles_n = (plan.nv + BN - 1) / BN;
   const int total = tiles_m * tiles_n * plan.splits;
-  dim3 grid(xcd_grid(total)), block(256);
+  dim3 grid(xcd_grid(total)), block(WAVES_M * WAVES_N * 64);
   if (plan.splits > 1) {
-    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, PF, EPI, true>), grid, block, 0, stream, a, plan.nv, tiles_m, tiles_n,
-                       plan.splits, plan.k_tiles_per_split);
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, NSTAGE, EPI, true>), grid, block, 0, stream, a, plan.nv,
+                       tiles_m, tiles_n, plan.splits, plan.k_tiles_per_split);
   } else {
-    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, PF, EPI, false>), grid, block, 0, stream, a, plan.nv, tiles_m, tiles_n,
-                       1, plan.k_tiles_per_split);
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, NSTAGE, EPI, false>), grid, block, 0, stream, a,
+                       plan.nv, tiles_m, tiles_n, 1, plan.k_tiles_per_split);
   }
   return hipGetLastError();
 }
@@ -363,10 +392,10 @@ hipError_t launch_tile(const GemmArgs& a, const GemmPlan& plan, hipStream_t stre
 template <int EPI>
 hipError_t launch_epi(const GemmArgs& a, const GemmPlan& plan, hipStream_t stream) {
   switch (plan.tile) {
-    case kTile256x256: return launch_tile<256, 256, 1, EPI>(a, plan, stream);
-    case kTile256x128: return launch_tile<256, 128, 2, EPI>(a, plan, stream);
-    case kTile128x128: return launch_tile<128, 128, 2, EPI>(a, plan, stream);
-    default: return launch_tile<64, 128, 2, EPI>(a, plan, stream);
+    case kTile256x256: return launch_tile<256, 256, 2, 2, 2, EPI>(a, plan, stream);
+    case kTile256x128: return launch_tile<256, 128, 2, 2, 3, EPI>(a, plan, stream);
+    case kTile128x128: return launch_tile<128, 128, 2, 2, 2, EPI>(a, plan, stream);
+    default: return launch_tile<64, 128, 2, 2, 3, EPI>(a, plan, stream);
   }
 }
 
@@ -377,9 +406,9 @@ GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus) {
   plan.nv = epi == kEpiSwiGLU ? ((n + 31) / 32) * 64 : n;
   const int k_tiles = (k + kBK - 1) / kBK;
   struct Cand { int tile, bm, bn, wg_per_cu; float eff; };
-  // relative MFMA efficiency of a tile shape (LDS traffic per MFMA) and how many fit on a CU (LDS)
-  static const Cand cands[] = {{kTile256x256, 256, 256, 1, 1.0f}, {kTile256x128, 256, 128, 1, 0.85f},
-                               {kTile128x128, 128, 128, 2, 0.7f}};
+  // measured relative efficiency of the tile shapes and how many workgroups of each fit on a CU (LDS)
+  static const Cand cands[] = {{kTile256x256, 256, 256, 1, 0.9f}, {kTile256x128, 256, 128, 1, 1.0f},
+                               {kTile128x128, 128, 128, 2, 0.95f}};
   if (m <= 64) {
     plan.tile = kTile64x128;
   } else {
