@@ -12,7 +12,7 @@ namespace {
 template <bool FROM_BF16>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const __bf16* __restrict__ in_bf16, float* __restrict__ x,
                                                       const __bf16* __restrict__ gain, __bf16* __restrict__ out,
-                                                      int hidden, float eps) {
+                                                      __bf16* __restrict__ out_lo, int hidden, float eps) {
   __shared__ float partial[4];
   const int row = blockIdx.x, tid = threadIdx.x;
   const int chunks = hidden / 8;
@@ -52,10 +52,15 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const __bf16* __restrict__
       v[0] = p.x; v[1] = p.y; v[2] = p.z; v[3] = p.w; v[4] = q.x; v[5] = q.y; v[6] = q.z; v[7] = q.w;
     }
     const bf16x8 g = load8(gain + c * 8);
-    bf16x8 o;
+    bf16x8 o, lo;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = f32_to_bf16(v[e] * rs * bf16_to_f32(g[e]));
+    for (int e = 0; e < 8; ++e) {
+      const float val = v[e] * rs * bf16_to_f32(g[e]);
+      o[e] = f32_to_bf16(val);
+      lo[e] = f32_to_bf16(val - bf16_to_f32(o[e]));     // what the rounding dropped, for the two-plane GEMMs
+    }
     store8(out + (size_t)row * hidden + c * 8, o);
+    if (out_lo) store8(out_lo + (size_t)row * hidden + c * 8, lo);
   }
 }
 
@@ -121,12 +126,13 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs p) {
 
 }  // namespace
 
-hipError_t launch_rmsnorm(const __bf16* in_bf16, float* x, const __bf16* gain, __bf16* out, int rows, int hidden,
-                          float eps, bool from_bf16, hipStream_t stream) {
+hipError_t launch_rmsnorm(const __bf16* in_bf16, float* x, const __bf16* gain, __bf16* out, __bf16* out_lo, int rows,
+                          int hidden, float eps, bool from_bf16, hipStream_t stream) {
   if (from_bf16)
-    hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(rows), dim3(256), 0, stream, in_bf16, x, gain, out, hidden, eps);
+    hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(rows), dim3(256), 0, stream, in_bf16, x, gain, out, out_lo, hidden, eps);
   else
-    hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(rows), dim3(256), 0, stream, in_bf16, x, gain, out, hidden, eps);
+    hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(rows), dim3(256), 0, stream, in_bf16, x, gain, out, out_lo, hidden,
+                       eps);
   return hipGetLastError();
 }
 

@@ -8,8 +8,9 @@ namespace molink {
 // a[t][:] = x[t][:] * gain / sqrt(mean(x[t][:]^2) + eps), rounded to bf16.
 // from_bf16: the row source is in_bf16 (the stage input) and the fp32 residual stream x is also
 // initialised from it; otherwise the source is x.
-hipError_t launch_rmsnorm(const __bf16* in_bf16, float* x, const __bf16* gain, __bf16* out, int rows, int hidden,
-                          float eps, bool from_bf16, hipStream_t stream);
+// out_lo (optional): receives bf16(value - bf16(value)), the second activation plane of the two-plane GEMMs.
+hipError_t launch_rmsnorm(const __bf16* in_bf16, float* x, const __bf16* gain, __bf16* out, __bf16* out_lo, int rows,
+                          int hidden, float eps, bool from_bf16, hipStream_t stream);
 
 // cos_sin[t][i] = (cos, sin)(positions[t] * theta^(-2i/d)), i < d/2, evaluated in fp64.
 hipError_t launch_rope_table(const int32_t* positions, float2* cos_sin, int rows, int head_dim, float theta,

@@ -80,16 +80,17 @@ __device__ __forceinline__ void pipeline_barrier() {
 // to the *global* address each lane fetches: slot p of row r holds the row's 16-byte chunk p ^ (r & 7),
 // so the 8 lanes of a 128-bit LDS read that hit rows r..r+7 at the same logical chunk touch 8
 // different slots.  LDS reads of MFMA step kk+1 are issued under the MFMAs of step kk.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int EPI, bool SPLIT>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int EPI, bool SPLIT, bool SPLIT_A>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmArgs p, int nv, int tiles_m, int tiles_n, int splits,
                                                         int k_tiles_per_split) {
   constexpr int NWAVES = WAVES_M * WAVES_N;
   constexpr int TM = BM / WAVES_M, TN = BN / WAVES_N;
   constexpr int MT = TM / 32, NT = TN / 32;
-  constexpr int GROUPS = (BM + BN) / 8;        // 8-row groups per stage (A rows first, then B rows)
+  constexpr int AROWS = SPLIT_A ? 2 * BM : BM;  // activation rows per stage: the high plane, then the low plane
+  constexpr int GROUPS = (AROWS + BN) / 8;     // 8-row groups per stage (A rows first, then B rows)
   constexpr int NI = GROUPS / NWAVES;          // load instructions per wave per tile
   static_assert(GROUPS % NWAVES == 0, "row groups must divide evenly among the waves");
-  constexpr int STAGE_BYTES = (BM + BN) * 128;
+  constexpr int STAGE_BYTES = (AROWS + BN) * 128;
   static_assert(EPI != kEpiSwiGLU || TN % 64 == 0, "SwiGLU pairs two 32-wide column tiles per wave");
   static_assert(NSTAGE >= 2 && NSTAGE <= 4 && NSTAGE * STAGE_BYTES <= 160 * 1024, "stages must fit in LDS");
   using Lds = LdsStages<STAGE_BYTES>;
@@ -119,18 +120,18 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
   for (int j = 0; j < NI; ++j) {
     const int g = NWAVES * j + wave;
     const int r = 8 * g + (lane >> 3);            // row inside the stage (A rows, then B rows)
-    if (r < BM) {
-      int gm = m0 + r;
+    if (r < AROWS) {
+      int gm = m0 + (r < BM ? r : r - BM);         // the low plane has the same rows as the high plane
       gm = gm < p.m ? gm : p.m - 1;
       g_off[j] = ((uint32_t)gm * (uint32_t)p.lda + sw_chunk * 8) * 2u;
     } else {
       int row;
       if constexpr (EPI == kEpiSwiGLU) {
         // 32 gate rows, then the 32 up rows of the same features (which matrix is decided per 8-row group)
-        const int v = n0 + (r - BM);
+        const int v = n0 + (r - AROWS);
         row = (v >> 6) * 32 + (v & 31);
       } else {
-        row = n0 + (r - BM);
+        row = n0 + (r - AROWS);
       }
       row = row < p.n ? row : p.n - 1;
       g_off[j] = ((uint32_t)row * (uint32_t)p.k + sw_chunk * 8) * 2u;
@@ -149,13 +150,16 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
     zero_below[S] = k0 > k_last ? k0 - k_last : 0;
     k0 = k0 > k_last ? k_last : k0;
     const char* abase = reinterpret_cast<const char*>(p.a + k0);
+    const char* alobase = SPLIT_A ? reinterpret_cast<const char*>(p.a_lo + k0) : abase;
     const char* w0base = reinterpret_cast<const char*>(p.w0 + k0);
     const char* w1base = EPI == kEpiSwiGLU ? reinterpret_cast<const char*>(p.w1 + k0) : w0base;
     char* stage = Lds::template get<S>();
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
       const int g = NWAVES * j + wave;                          // uniform
-      const char* base = g < BM / 8 ? abase : ((EPI == kEpiSwiGLU && ((g - BM / 8) & 4)) ? w1base : w0base);
+      const char* base = g < BM / 8 ? abase
+                         : g < AROWS / 8 ? alobase
+                                         : ((EPI == kEpiSwiGLU && ((g - AROWS / 8) & 4)) ? w1base : w0base);
       __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(base + g_off[j]),
                                        reinterpret_cast<uint32_t*>(stage + g * 1024), 16, 0, 0);
     }
@@ -189,25 +193,31 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
   auto multiply = [&](auto stage_c) {
     constexpr int S = decltype(stage_c)::value;
     const char* la = Lds::template get<S>() + wm * TM * 128;
-    const char* lb = Lds::template get<S>() + (BM + wn * TN) * 128;
-    bf16x8 af[2][MT], bfr[2][NT];
+    const char* lb = Lds::template get<S>() + (AROWS + wn * TN) * 128;
+    constexpr int NPLANE = SPLIT_A ? 2 : 1;
+    bf16x8 af[2][NPLANE][MT], bfr[2][NT];
     auto read_frags = [&](int s, int kk) {
 #pragma unroll
-      for (int i = 0; i < MT; ++i) af[s][i] = *reinterpret_cast<const bf16x8*>(la + i * 32 * 128 + frag_off[kk]);
+      for (int pl = 0; pl < NPLANE; ++pl)
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+          af[s][pl][i] = *reinterpret_cast<const bf16x8*>(la + (pl * BM + i * 32) * 128 + frag_off[kk]);
 #pragma unroll
       for (int j = 0; j < NT; ++j) bfr[s][j] = *reinterpret_cast<const bf16x8*>(lb + j * 32 * 128 + frag_off[kk]);
     };
-    constexpr int KSTEPS = kBK / 16, NMFMA = MT * NT, NREAD = MT + NT, NLOADS = NI;
+    constexpr int KSTEPS = kBK / 16, NMFMA = NPLANE * MT * NT, NREAD = NPLANE * MT + NT, NLOADS = NI;
     read_frags(0, 0);
     __builtin_amdgcn_sched_group_barrier(0x100, NREAD, 0);   // the first step's fragments cannot overlap anything
     auto mfma_step = [&](auto kk_c) {
       constexpr int kk = decltype(kk_c)::value;
       if constexpr (kk + 1 < KSTEPS) read_frags((kk + 1) & 1, kk + 1);
 #pragma unroll
-      for (int i = 0; i < MT; ++i)
+      for (int pl = 0; pl < NPLANE; ++pl)
 #pragma unroll
-        for (int j = 0; j < NT; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+          for (int j = 0; j < NT; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][pl][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
       // a quarter of this pipeline step's tile loads goes behind each MFMA step
       constexpr int loads = (kk + 1) * NLOADS / KSTEPS - kk * NLOADS / KSTEPS;
       sched_step<0, NMFMA, (kk + 1 < KSTEPS ? NREAD : 0), loads>();
@@ -275,7 +285,12 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
         for (int j = 0; j < NT; j += 2) {
           const int v = n0 + wn * TN + j * 32 + col_in_tile;   // gate column; its up column is 32 further
           const int f = (v >> 6) * 32 + (v & 31);
-          if (f < p.n) p.out_bf16[(size_t)m * p.ldo + f] = f32_to_bf16(silu_f(acc[i][j][r]) * acc[i][j + 1][r]);
+          if (f < p.n) {
+            const float val = silu_f(acc[i][j][r]) * acc[i][j + 1][r];
+            const __bf16 hi = f32_to_bf16(val);
+            p.out_bf16[(size_t)m * p.ldo + f] = hi;
+            if (p.out_lo) p.out_lo[(size_t)m * p.ldo + f] = f32_to_bf16(val - bf16_to_f32(hi));
+          }
         }
       } else {
 #pragma unroll
@@ -312,7 +327,10 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(GemmArgs p, int
       g += src[s * plane];
       u += src[s * plane + 32];
     }
-    p.out_bf16[(size_t)m * p.ldo + n] = f32_to_bf16(silu_f(g) * u);
+    const float val = silu_f(g) * u;
+    const __bf16 hi = f32_to_bf16(val);
+    p.out_bf16[(size_t)m * p.ldo + n] = hi;
+    if (p.out_lo) p.out_lo[(size_t)m * p.ldo + n] = f32_to_bf16(val - bf16_to_f32(hi));
   } else {
     const float* src = p.partial + (size_t)m * nv + n;
     float c = 0.f;
@@ -332,7 +350,8 @@ template <bool NORM>
 __global__ __launch_bounds__(1024) void reduce_residual_norm_kernel(const float* __restrict__ partial, int splits,
                                                                    int m_rows, int n, float* __restrict__ x,
                                                                    const __bf16* __restrict__ gain, float eps,
-                                                                   __bf16* __restrict__ out, int ldo) {
+                                                                   __bf16* __restrict__ out, __bf16* __restrict__ out_lo,
+                                                                   int ldo) {
   __shared__ float wsum[16];
   const int row = blockIdx.x, tid = threadIdx.x;
   const int stride = blockDim.x * 4, nwaves = blockDim.x >> 6;
@@ -365,43 +384,56 @@ __global__ __launch_bounds__(1024) void reduce_residual_norm_kernel(const float*
     for (int c = tid * 4; c < n; c += stride) {
       const f32x4 v = *reinterpret_cast<const f32x4*>(xr + c);     // written by this same thread above
       const bf16x4 g = *reinterpret_cast<const bf16x4*>(gain + c);
-      bf16x4 o;
+      bf16x4 o, lo;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16(v[e] * rs * bf16_to_f32(g[e]));
+      for (int e = 0; e < 4; ++e) {
+        const float val = v[e] * rs * bf16_to_f32(g[e]);
+        o[e] = f32_to_bf16(val);
+        lo[e] = f32_to_bf16(val - bf16_to_f32(o[e]));
+      }
       *reinterpret_cast<bf16x4*>(out + (size_t)row * ldo + c) = o;
+      if (out_lo) *reinterpret_cast<bf16x4*>(out_lo + (size_t)row * ldo + c) = lo;
     }
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int EPI>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int EPI, bool SPLIT_A>
 hipError_t launch_tile(const GemmArgs& a, const GemmPlan& plan, hipStream_t stream) {
   const int tiles_m = (a.m + BM - 1) / BM;
   const int tiles_n = (plan.nv + BN - 1) / BN;
   const int total = tiles_m * tiles_n * plan.splits;
   dim3 grid(xcd_grid(total)), block(WAVES_M * WAVES_N * 64);
   if (plan.splits > 1) {
-    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, NSTAGE, EPI, true>), grid, block, 0, stream, a, plan.nv,
-                       tiles_m, tiles_n, plan.splits, plan.k_tiles_per_split);
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, NSTAGE, EPI, true, SPLIT_A>), grid, block, 0, stream, a,
+                       plan.nv, tiles_m, tiles_n, plan.splits, plan.k_tiles_per_split);
   } else {
-    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, NSTAGE, EPI, false>), grid, block, 0, stream, a,
-                       plan.nv, tiles_m, tiles_n, 1, plan.k_tiles_per_split);
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, NSTAGE, EPI, false, SPLIT_A>), grid, block, 0, stream,
+                       a, plan.nv, tiles_m, tiles_n, 1, plan.k_tiles_per_split);
   }
   return hipGetLastError();
 }
 
 template <int EPI>
 hipError_t launch_epi(const GemmArgs& a, const GemmPlan& plan, hipStream_t stream) {
+  if (a.a_lo) {
+    // two activation planes: only the MLP projections use them, and only the tiles whose stages still fit
+    if constexpr (EPI == kEpiSwiGLU || EPI == kEpiResidualF32 || EPI == kEpiResidualOut) {
+      if (plan.tile == kTile128x128) return launch_tile<128, 128, 2, 2, 3, EPI, true>(a, plan, stream);
+      if (plan.tile == kTile64x128) return launch_tile<64, 128, 2, 2, 2, EPI, true>(a, plan, stream);
+    }
+    return hipErrorInvalidValue;
+  }
   switch (plan.tile) {
-    case kTile256x256: return launch_tile<256, 256, 2, 2, 2, EPI>(a, plan, stream);
-    case kTile256x128: return launch_tile<256, 128, 2, 2, 3, EPI>(a, plan, stream);
-    case kTile128x128: return launch_tile<128, 128, 2, 2, 2, EPI>(a, plan, stream);
-    default: return launch_tile<64, 128, 2, 2, 3, EPI>(a, plan, stream);
+    case kTile256x256: return launch_tile<256, 256, 2, 2, 2, EPI, false>(a, plan, stream);
+    case kTile256x128: return launch_tile<256, 128, 2, 2, 3, EPI, false>(a, plan, stream);
+    case kTile128x128: return launch_tile<128, 128, 2, 2, 2, EPI, false>(a, plan, stream);
+    default: return launch_tile<64, 128, 2, 2, 3, EPI, false>(a, plan, stream);
   }
 }
 
 }  // namespace
 
-GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus) {
+GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool split_a) {
   GemmPlan plan;
   plan.nv = epi == kEpiSwiGLU ? ((n + 31) / 32) * 64 : n;
   const int k_tiles = (k + kBK - 1) / kBK;
@@ -415,6 +447,7 @@ GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus) {
     float best = 0.f;
     plan.tile = kTile128x128;
     for (const Cand& c : cands) {
+      if (split_a && c.tile != kTile128x128) continue;   // with two activation planes only this tile's stages fit
       const long tiles = (long)((m + c.bm - 1) / c.bm) * ((plan.nv + c.bn - 1) / c.bn);
       const long slots = (long)num_cus * c.wg_per_cu;
       const long rounds = (tiles + slots - 1) / slots;
@@ -424,7 +457,7 @@ GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus) {
   }
   const int bm = plan.tile == kTile64x128 ? 64 : (plan.tile == kTile128x128 ? 128 : 256);
   const int bn = plan.tile == kTile256x256 ? 256 : 128;
-  const int wg_per_cu = (plan.tile == kTile128x128 || plan.tile == kTile64x128) ? 2 : 1;
+  const int wg_per_cu = (!split_a && plan.tile == kTile128x128) || plan.tile == kTile64x128 ? 2 : 1;
   const int tiles = ((m + bm - 1) / bm) * ((plan.nv + bn - 1) / bn);
   int splits = 1;
   if (tiles * 2 <= num_cus * wg_per_cu) {
@@ -438,19 +471,19 @@ GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus) {
   return plan;
 }
 
-size_t gemm_partial_floats(int max_m, int n, int k, GemmEpilogue epi, int num_cus) {
+size_t gemm_partial_floats(int max_m, int n, int k, GemmEpilogue epi, int num_cus, bool split_a) {
   // Splitting only happens when there are fewer tiles than CUs; the scratch of any such shape is
   // bounded by 16 splits of the largest m that still splits.
   size_t worst = 0;
   for (int m = 1; m <= max_m; m = (m < 64 ? 64 : m + 64)) {
     const int mm = m > max_m ? max_m : m;
-    GemmPlan p = plan_gemm(mm, n, k, epi, num_cus);
+    GemmPlan p = plan_gemm(mm, n, k, epi, num_cus, split_a);
     if (p.splits > 1) {
       const size_t need = (size_t)p.splits * mm * p.nv;
       if (need > worst) worst = need;
     }
   }
-  GemmPlan p = plan_gemm(max_m, n, k, epi, num_cus);
+  GemmPlan p = plan_gemm(max_m, n, k, epi, num_cus, split_a);
   if (p.splits > 1) {
     const size_t need = (size_t)p.splits * max_m * p.nv;
     if (need > worst) worst = need;
@@ -489,14 +522,15 @@ hipError_t launch_gemm_reduce(const GemmArgs& a, GemmEpilogue epi, const GemmPla
 }
 
 hipError_t launch_gemm_reduce_residual_norm(const GemmArgs& a, GemmEpilogue epi, const GemmPlan& plan,
-                                            const __bf16* gain, float eps, __bf16* norm_out, hipStream_t stream) {
+                                            const __bf16* gain, float eps, __bf16* norm_out, __bf16* norm_out_lo,
+                                            hipStream_t stream) {
   const int threads = a.n >= 4096 ? 1024 : (a.n >= 2048 ? 512 : 256);
   if (epi == kEpiResidualOut) {
     hipLaunchKernelGGL(reduce_residual_norm_kernel<false>, dim3(a.m), dim3(threads), 0, stream, a.partial, plan.splits, a.m,
-                       a.n, a.resid, (const __bf16*)nullptr, eps, a.out_bf16, a.ldo);
+                       a.n, a.resid, (const __bf16*)nullptr, eps, a.out_bf16, (__bf16*)nullptr, a.ldo);
   } else {
     hipLaunchKernelGGL(reduce_residual_norm_kernel<true>, dim3(a.m), dim3(threads), 0, stream, a.partial, plan.splits, a.m,
-                       a.n, a.resid, gain, eps, norm_out, a.n);
+                       a.n, a.resid, gain, eps, norm_out, norm_out_lo, a.n);
   }
   return hipGetLastError();
 }

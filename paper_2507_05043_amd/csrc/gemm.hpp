@@ -14,6 +14,10 @@ enum GemmEpilogue : int {
 
 struct GemmArgs {
   const __bf16* a;      // [M][lda]
+  const __bf16* a_lo;   // optional second plane [M][lda]: the activations are a + a_lo (the part of the fp32
+                        // value that bf16 rounding dropped); both planes are multiplied into the same
+                        // accumulators.  nullptr = single plane.
+  __bf16* out_lo;       // SwiGLU epilogue only, optional: receives bf16(result - bf16(result)) [M][ldo]
   const __bf16* w0;     // [N][K]; for SwiGLU the gate matrix [F][K]
   const __bf16* w1;     // SwiGLU only: the up matrix [F][K]
   __bf16* out_bf16;     // see GemmEpilogue
@@ -32,9 +36,9 @@ struct GemmPlan {
   int nv;               // width of the column space the kernel iterates (gate/up interleaved for SwiGLU, else N)
 };
 
-GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus);
+GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool split_a = false);
 // Floats of split-K scratch that any GEMM with m <= max_m rows of this (n, k, epilogue) may need.
-size_t gemm_partial_floats(int max_m, int n, int k, GemmEpilogue epi, int num_cus);
+size_t gemm_partial_floats(int max_m, int n, int k, GemmEpilogue epi, int num_cus, bool split_a = false);
 
 hipError_t launch_gemm_main(const GemmArgs& args, GemmEpilogue epi, const GemmPlan& plan, hipStream_t stream);
 // Only when plan.splits > 1: sums the partial results in split order and applies the epilogue.
@@ -45,6 +49,7 @@ hipError_t launch_gemm_reduce(const GemmArgs& args, GemmEpilogue epi, const Gemm
 // writes RMSNorm(x; gain, eps) as bf16 to norm_out (gain != nullptr) or rounds x to bf16 into
 // args.out_bf16 (kEpiResidualOut).  Replaces launch_gemm_reduce plus the following RMSNorm.
 hipError_t launch_gemm_reduce_residual_norm(const GemmArgs& args, GemmEpilogue epi, const GemmPlan& plan,
-                                            const __bf16* gain, float eps, __bf16* norm_out, hipStream_t stream);
+                                            const __bf16* gain, float eps, __bf16* norm_out, __bf16* norm_out_lo,
+                                            hipStream_t stream);
 
 }  // namespace molink

@@ -49,7 +49,7 @@ struct Dims {
 };
 
 struct WorkspaceLayout {
-  size_t x, a, qkv, attn, mlp, cos_sin, splitk, part_o, part_ml, meta, total;
+  size_t x, a, a_lo, qkv, attn, mlp, mlp_lo, cos_sin, splitk, part_o, part_ml, meta, total;
   size_t meta_bytes;
   int max_items, max_tiles;
 };
@@ -89,6 +89,14 @@ Dims dims_of(const stage_config& c) {
 // Number of compute units the work decomposition is sized for.  The library targets MI355X only.
 constexpr int kNumCus = 256;
 
+// Deep stages carry the MLP's activations (the post-attention norm output and silu(gate)*up) as two
+// bf16 planes, value = hi + lo, and multiply both into the same accumulators.  One bf16 rounding per
+// GEMM input costs about 1.7e-3 relative error per layer on the residual stream; the errors of the
+// layers add in quadrature, and beyond about ten layers the single-plane path no longer meets the
+// 1e-2 relative-L2 budget on the stage output.  The second plane doubles the MFMA work of the gate/up
+// and down projections, so shallow stages do without it.
+bool split_mlp_of(const stage_config& c) { return c.num_layers > 10; }
+
 int decode_target_items(const Dims& d) { return (kNumCus * kDecodeWavesPerCu + d.nkv - 1) / d.nkv; }
 
 WorkspaceLayout layout_of(const stage_config& c) {
@@ -99,15 +107,18 @@ WorkspaceLayout layout_of(const stage_config& c) {
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
   w.x = take(T * d.H * 4);
   w.a = take(T * d.H * 2);
+  w.a_lo = take(split_mlp_of(c) ? T * d.H * 2 : 0);
   w.qkv = take(T * d.qkv_out * 2);
   w.attn = take(T * d.nq * d.d * 2);
   w.mlp = take(T * d.F * 2);
+  w.mlp_lo = take(split_mlp_of(c) ? T * d.F * 2 : 0);
   w.cos_sin = take(T * (d.d / 2) * 8);
   size_t pf = gemm_partial_floats(c.max_tokens, d.qkv_out, d.H, kEpiStoreBf16, kNumCus);
   size_t v;
   if ((v = gemm_partial_floats(c.max_tokens, d.H, d.nq * d.d, kEpiResidualF32, kNumCus)) > pf) pf = v;
-  if ((v = gemm_partial_floats(c.max_tokens, d.F, d.H, kEpiSwiGLU, kNumCus)) > pf) pf = v;
-  if ((v = gemm_partial_floats(c.max_tokens, d.H, d.F, kEpiResidualF32, kNumCus)) > pf) pf = v;
+  const bool sp = split_mlp_of(c);
+  if ((v = gemm_partial_floats(c.max_tokens, d.F, d.H, kEpiSwiGLU, kNumCus, sp)) > pf) pf = v;
+  if ((v = gemm_partial_floats(c.max_tokens, d.H, d.F, kEpiResidualF32, kNumCus, sp)) > pf) pf = v;
   w.splitk = take(pf * 4 + 16);
   w.max_items = decode_target_items(d) + c.max_seqs;
   w.part_o = take((size_t)w.max_items * d.nq * d.d * 4);
@@ -236,7 +247,7 @@ __global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float* __restric
 }
 
 int run_gemm(stage_handle* st, hipStream_t stream, int kernel_class, const GemmArgs& args, GemmEpilogue epi) {
-  const GemmPlan plan = plan_gemm(args.m, args.n, args.k, epi, kNumCus);
+  const GemmPlan plan = plan_gemm(args.m, args.n, args.k, epi, kNumCus, args.a_lo != nullptr);
   {
     Timer t(st, stream, kernel_class);
     HIP_TRY(launch_gemm_main(args, epi, plan, stream));
@@ -252,8 +263,8 @@ int run_gemm(stage_handle* st, hipStream_t stream, int kernel_class, const GemmA
 // an RMSNorm into `norm_out` (gain != nullptr), or nothing.  When the GEMM splits K across workgroups
 // the sum of the partial results, the residual add and the norm run as one kernel.
 int run_residual_gemm(stage_handle* st, hipStream_t stream, int kernel_class, const GemmArgs& args, GemmEpilogue epi,
-                      const __bf16* gain, __bf16* norm_out) {
-  const GemmPlan plan = plan_gemm(args.m, args.n, args.k, epi, kNumCus);
+                      const __bf16* gain, __bf16* norm_out, __bf16* norm_out_lo) {
+  const GemmPlan plan = plan_gemm(args.m, args.n, args.k, epi, kNumCus, args.a_lo != nullptr);
   {
     Timer t(st, stream, kernel_class);
     HIP_TRY(launch_gemm_main(args, epi, plan, stream));
@@ -261,7 +272,7 @@ int run_residual_gemm(stage_handle* st, hipStream_t stream, int kernel_class, co
   const bool fused = plan.splits > 1 && (gain != nullptr || epi == kEpiResidualOut);
   if (fused) {
     Timer t(st, stream, STAGE_K_SPLITK_REDUCE);
-    HIP_TRY(launch_gemm_reduce_residual_norm(args, epi, plan, gain, st->cfg.rms_eps, norm_out, stream));
+    HIP_TRY(launch_gemm_reduce_residual_norm(args, epi, plan, gain, st->cfg.rms_eps, norm_out, norm_out_lo, stream));
     return STAGE_OK;
   }
   if (plan.splits > 1) {
@@ -270,7 +281,8 @@ int run_residual_gemm(stage_handle* st, hipStream_t stream, int kernel_class, co
   }
   if (gain) {
     Timer t(st, stream, STAGE_K_RMSNORM);
-    HIP_TRY(launch_rmsnorm(nullptr, args.resid, gain, norm_out, args.m, args.n, st->cfg.rms_eps, false, stream));
+    HIP_TRY(launch_rmsnorm(nullptr, args.resid, gain, norm_out, norm_out_lo, args.m, args.n, st->cfg.rms_eps, false,
+                           stream));
   }
   return STAGE_OK;
 }
@@ -382,6 +394,9 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
 
   float* x = (float*)(ws + st->ws.x);
   __bf16* a = (__bf16*)(ws + st->ws.a);
+  const bool split_mlp = split_mlp_of(c);
+  __bf16* a_lo = split_mlp ? (__bf16*)(ws + st->ws.a_lo) : nullptr;
+  __bf16* mlp_lo = split_mlp ? (__bf16*)(ws + st->ws.mlp_lo) : nullptr;
   __bf16* qkv = (__bf16*)(ws + st->ws.qkv);
   __bf16* attn = (__bf16*)(ws + st->ws.attn);
   __bf16* mlp = (__bf16*)(ws + st->ws.mlp);
@@ -404,8 +419,8 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
   {
     // the first layer's input norm also initialises the fp32 residual stream from the bf16 input
     Timer t(st, stream, STAGE_K_RMSNORM);
-    HIP_TRY(launch_rmsnorm((const __bf16*)hidden_in, x, (const __bf16*)st->layers[0].norm1, a, T, d.H, c.rms_eps, true,
-                           stream));
+    HIP_TRY(launch_rmsnorm((const __bf16*)hidden_in, x, (const __bf16*)st->layers[0].norm1, a, nullptr, T, d.H, c.rms_eps,
+                           true, stream));
   }
   for (int l = 0; l < d.L; ++l) {
     const stage_layer_weights& w = st->layers[l];
@@ -449,14 +464,15 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       GemmArgs g{};
       g.a = attn; g.w0 = (const __bf16*)w.wo; g.resid = x; g.partial = splitk;
       g.m = T; g.n = d.H; g.k = d.nq * d.d; g.lda = d.nq * d.d; g.ldo = d.H;
-      int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_O, g, kEpiResidualF32, (const __bf16*)w.norm2, a);
+      int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_O, g, kEpiResidualF32, (const __bf16*)w.norm2, a, a_lo);
       if (rc) return rc;
     }
     if (tap && taps->tap_h)
       HIP_TRY(hipMemcpyAsync(taps->tap_h, x, (size_t)T * d.H * 4, hipMemcpyDeviceToDevice, stream));
     {
       GemmArgs g{};
-      g.a = a; g.w0 = (const __bf16*)w.wgate; g.w1 = (const __bf16*)w.wup; g.out_bf16 = mlp; g.partial = splitk;
+      g.a = a; g.a_lo = a_lo; g.w0 = (const __bf16*)w.wgate; g.w1 = (const __bf16*)w.wup; g.out_bf16 = mlp; g.out_lo = mlp_lo;
+      g.partial = splitk;
       g.m = T; g.n = d.F; g.k = d.H; g.lda = d.H; g.ldo = d.F;
       int rc = run_gemm(st, stream, STAGE_K_GEMM_GATEUP, g, kEpiSwiGLU);
       if (rc) return rc;
@@ -468,11 +484,12 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       // kernel, so the tap sees it; the sum and its rounding are the same as in the fused epilogue.
       const bool fused_out = last && !(tap && taps->tap_x);
       GemmArgs g{};
-      g.a = mlp; g.w0 = (const __bf16*)w.wdown; g.resid = x; g.out_bf16 = (__bf16*)hidden_out; g.partial = splitk;
+      g.a = mlp; g.a_lo = mlp_lo; g.w0 = (const __bf16*)w.wdown; g.resid = x; g.out_bf16 = (__bf16*)hidden_out;
+      g.partial = splitk;
       g.m = T; g.n = d.H; g.k = d.F; g.lda = d.F; g.ldo = d.H;
       const __bf16* next_gain = last ? nullptr : (const __bf16*)st->layers[l + 1].norm1;
       int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_DOWN, g, fused_out ? kEpiResidualOut : kEpiResidualF32,
-                                 next_gain, a);
+                                 next_gain, a, nullptr);
       if (rc) return rc;
       if (tap && taps->tap_x)
         HIP_TRY(hipMemcpyAsync(taps->tap_x, x, (size_t)T * d.H * 4, hipMemcpyDeviceToDevice, stream));

@@ -27,7 +27,7 @@ def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_
     return st
 
 
-def fill_pool(st: Stage, shape: synth.StageShape, mb: synth.MicroBatch, seed: int) -> None:
+def fill_pool(st: Stage, shape: synth.StageShape, mb: synth.MicroBatch, seed: int, progress: bool = False) -> None:
     """Cached context drawn into its slots; every other slot of the pool is NaN."""
     st.kv_pool.view(torch.bfloat16).fill_(float("nan"))
     valid = synth.valid_slot_mask(mb, shape.kv_block_size)
@@ -46,3 +46,5 @@ def fill_pool(st: Stage, shape: synth.StageShape, mb: synth.MicroBatch, seed: in
                 vals = synth.draw_kv_blocks(shape, mb.num_kv_blocks, l, kv, blk, seed=seed)
                 vals = torch.where(m[i:i + step], vals, nan)
                 st.write_kv_blocks(l, kv, blk, vals)
+        if progress:
+            print(f"  KV pool of layer {l} filled", flush=True)

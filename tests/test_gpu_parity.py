@@ -170,3 +170,109 @@ def test_llama2_7b_stage_sampled_rows_at_full_size():
     stats = H.check_output(out[rows.cuda()], ref, "llama2-7b sampled rows")
     print(f"  rel-L2 {stats['rel_l2']:.3e} max-abs {stats['max_abs']:.3e} rms {stats['rms']:.3f}", flush=True)
     st.close()
+
+
+def _layer0_reference(shape, layers0, hidden, mb):
+    """Oracle q/k/v (after RoPE) of layer 0 for every row, from the oracle's own building blocks."""
+    dt = torch.float32
+    w = layers0
+    a = oracle.rmsnorm(hidden.to(dt), w["norm1"].to(dt), shape.rms_eps)
+    qkv = a @ w["wqkv"].to(dt).T
+    nq, nkv, d = shape.num_q_heads, shape.num_kv_heads, shape.head_dim
+    t = hidden.shape[0]
+    pos = mb.positions.to(torch.int64)
+    q = oracle.rope_rotate(qkv[:, : nq * d].reshape(t, nq, d), pos, shape.rope_theta)
+    k = oracle.rope_rotate(qkv[:, nq * d:(nq + nkv) * d].reshape(t, nkv, d), pos, shape.rope_theta)
+    v = qkv[:, (nq + nkv) * d:].reshape(t, nkv, d)
+    return a, q, k, v
+
+
+def test_qwen2_7b_stage_at_full_size():
+    """Mixed micro-batch at its real shape (2048-token prefill chunk + 128 decode tokens, 7 layers).
+    Whole-stage output: the first 320 rows of the chunk (causal, so exact on their own) and 8 decode
+    sequences, row by row.  Layer 0 taps: q/k/v of every row, attention of late prefill rows."""
+    shape, mb = synth.workload("qwen2-7b", seed=0)
+    print(f"[case] {shape.name} T={mb.num_tokens} blocks={mb.num_kv_blocks}", flush=True)
+    st = H.make_stage(shape, mb, 0)
+    out, slots, taps = H.run_gpu(st, shape, mb, 0, taps_layer=0)
+    assert slots == oracle.slot_mapping(mb.q_lens, mb.ctx_lens, mb.block_tables, 16)
+    assert torch.isfinite(out.float()).all()
+    layers = [{k: v.cpu() for k, v in synth.draw_layer_weights(shape, l, seed=0, device="cuda:0").items()}
+              for l in range(shape.num_layers)]
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=0)
+    print("  inputs ready", flush=True)
+
+    # -- layer 0 taps on all rows
+    a, q, k, v = _layer0_reference(shape, layers[0], hidden, mb)
+    t = mb.num_tokens
+    ref_qkv = torch.cat([q.reshape(t, -1), k.reshape(t, -1), v.reshape(t, -1)], dim=1)
+    e_a = rel_l2(taps["a"].cpu(), a)
+    e_qkv = rel_l2(taps["qkv"].cpu(), ref_qkv)
+    print(f"  layer-0 norm rel-L2 {e_a:.2e}, qkv rel-L2 {e_qkv:.2e}", flush=True)
+    assert e_a <= H.REL_L2_TOL and e_qkv <= H.REL_L2_TOL
+    late = torch.tensor([0, 1, 31, 32, 777, 1500, 2016, 2047])
+    ref_attn = torch.stack([oracle.attention_rows(q[r:r + 1], k[: r + 1], v[: r + 1], int(r))[0] for r in late.tolist()])
+    e_attn = rel_l2(taps["attn"].cpu()[late], ref_attn.reshape(len(late), -1))
+    print(f"  layer-0 attention of rows {late.tolist()} rel-L2 {e_attn:.2e}", flush=True)
+    assert e_attn <= H.REL_L2_TOL
+
+    # -- whole stage on a sample: prefix of the chunk + 8 decode sequences
+    prefix = 320
+    dec = list(range(1, 129, 16))
+    sub_dec, rows_dec, pool_dec = H.sub_problem(shape, mb, dec, 0, dtype=torch.float32, draw_device="cuda:0")
+    osh = oracle_shape(shape)
+    ref_dec, _ = oracle.stage_forward(osh, layers, hidden[rows_dec], sub_dec.positions, sub_dec.q_lens, sub_dec.ctx_lens,
+                                      sub_dec.block_tables, pool_dec, dtype=torch.float32)
+    s1 = H.check_output(out[rows_dec.cuda()], ref_dec, "qwen2 decode rows")
+    mbp = synth.make_microbatch([prefix], [0], seed=1, paging="identity")
+    poolp = oracle.new_pool(osh, mbp.num_kv_blocks, dtype=torch.float32)
+    ref_pre, _ = oracle.stage_forward(osh, layers, hidden[:prefix], mbp.positions, [prefix], [0], mbp.block_tables,
+                                      poolp, dtype=torch.float32)
+    s2 = H.check_output(out[:prefix], ref_pre, "qwen2 prefill prefix")
+    print(f"  decode rows rel-L2 {s1['rel_l2']:.3e}; prefill prefix rel-L2 {s2['rel_l2']:.3e} max-abs {s2['max_abs']:.3e} "
+          f"rms {s2['rms']:.2f}", flush=True)
+    st.close()
+
+
+@pytest.mark.timeout(1100)
+def test_llama3_70b_stage_sampled_rows_at_full_size():
+    """256 decode tokens, contexts up to 8192, 20 layers, 8 query heads per KV head: 4 sequences row by row."""
+    shape, mb = synth.workload("llama3-70b", seed=0)
+    print(f"[case] {shape.name} T={mb.num_tokens} blocks={mb.num_kv_blocks}", flush=True)
+    layers_dev = []
+    for l in range(shape.num_layers):
+        layers_dev.append(synth.draw_layer_weights(shape, l, seed=0, device="cuda:0"))
+        print(f"  weights of layer {l} drawn", flush=True)
+    from paper_2507_05043_amd.stage import make_config, Stage
+    cfg = make_config(num_layers=shape.num_layers, hidden=shape.hidden, num_q_heads=shape.num_q_heads,
+                      num_kv_heads=shape.num_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn, rms_eps=shape.rms_eps,
+                      rope_theta=shape.rope_theta, num_kv_blocks=mb.num_kv_blocks, max_tokens=mb.num_tokens,
+                      max_seqs=mb.num_seqs, max_blocks_per_seq=mb.max_blocks_per_seq)
+    st = Stage(cfg, layers_dev, device="cuda:0")
+    H.fill_pool(st, shape, mb, 0, progress=True)
+    out, slots = H.run_gpu(st, shape, mb, 0)
+    assert slots == oracle.slot_mapping(mb.q_lens, mb.ctx_lens, mb.block_tables, 16)
+    assert torch.isfinite(out.float()).all()
+    print("  GPU forward done", flush=True)
+    seqs = [0, 85, 170, 255]
+    sub, rows, pool = H.sub_problem(shape, mb, seqs, 0, dtype=torch.float32, draw_device="cuda:0")
+    layers = []
+    for l in range(shape.num_layers):
+        layers.append({k: v.cpu() for k, v in layers_dev[l].items()})
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=0)[rows]
+    print("  oracle inputs ready", flush=True)
+    ref, _ = oracle.stage_forward(oracle_shape(shape), layers, hidden, sub.positions, sub.q_lens, sub.ctx_lens,
+                                  sub.block_tables, pool, dtype=torch.float32)
+    stats = H.check_output(out[rows.cuda()], ref, "llama3-70b sampled rows")
+    print(f"  rel-L2 {stats['rel_l2']:.3e} max-abs {stats['max_abs']:.3e} rms {stats['rms']:.3f}", flush=True)
+    st.close()
+
+
+@pytest.mark.parametrize("q,c", [([40, 1, 1, 9, 1], [0, 257, 33, 50, 700]), ([150, 61, 1, 1], [0, 20, 300, 5])])
+def test_deep_stage_two_plane_mlp(q, c):
+    """More than ten layers: the MLP activations travel as two bf16 planes (both GEMM tile paths)."""
+    shape = _shape("deep-12", 12, 520, 4, 2, 64, 1096)
+    mb = synth.make_microbatch(q, c, seed=26)
+    full_parity(shape, mb, 26, "fan_in", taps=False)
+    shape2 = _shape("deep-12-l", 12, 512, 8, 2, 128, 1024)
+    st = full_parity(shape2, mb, 27, None, taps=True, check_kv=False)
