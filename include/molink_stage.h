@@ -65,6 +65,12 @@ typedef struct {
   int32_t max_tokens;          /* capacity: new tokens per micro-batch (T) */
   int32_t max_seqs;            /* capacity: sequences per micro-batch (S) */
   int32_t max_blocks_per_seq;  /* row length of block_tables */
+  int32_t activation_planes;   /* 0 = automatic, 1 or 2.  With 2, every projection input (and the rotated
+                                  queries) is carried as two bf16 planes, value = hi + lo, both multiplied into
+                                  the same fp32 accumulators: twice the MFMA work of the projections for
+                                  activations that are effectively 16-bit.  Automatic = 2 for stages deeper than
+                                  10 layers, whose accumulated bf16 rounding error would otherwise exceed
+                                  1e-2 relative on the output, else 1. */
 } stage_config;
 
 /* Device pointers to one layer's bf16 weights, row-major [out_features][in_features]. Borrowed, read-only. */

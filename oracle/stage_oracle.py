@@ -124,8 +124,12 @@ def attention_rows(q: torch.Tensor, keys: torch.Tensor, values: torch.Tensor, ct
 
 def decoder_layer(shape: OracleShape, w: Dict[str, torch.Tensor], x: torch.Tensor, pos: torch.Tensor,
                   q_lens, ctx_lens, block_tables, pool_layer: torch.Tensor, slots: List[int],
-                  taps: Optional[Dict[str, torch.Tensor]] = None) -> torch.Tensor:
-    """One decoder layer on packed rows x [T, H]; appends to pool_layer [2, block, slot, nkv, d]."""
+                  taps: Optional[Dict[str, torch.Tensor]] = None, kv_store_dtype=None) -> torch.Tensor:
+    """One decoder layer on packed rows x [T, H]; appends to pool_layer [2, block, slot, nkv, d].
+
+    kv_store_dtype: None keeps the appended keys/values unrounded in the oracle's pool; a torch dtype
+    (the cache's storage type) rounds them once on their way into the pool, so that attention, in
+    this call and in later ones, reads what a cache of that type holds."""
     dt = x.dtype
     nq, nkv, d, blk = shape.num_q_heads, shape.num_kv_heads, shape.head_dim, shape.kv_block_size
     t = x.shape[0]
@@ -139,8 +143,10 @@ def decoder_layer(shape: OracleShape, w: Dict[str, torch.Tensor], x: torch.Tenso
     k = rope_rotate(k, pos, shape.rope_theta)
     # append the new tokens' keys (rotated) and values at their slots
     slot_t = torch.as_tensor(slots, dtype=torch.int64)
-    pool_layer[0, slot_t // blk, slot_t % blk] = k
-    pool_layer[1, slot_t // blk, slot_t % blk] = v
+    k_st = k if kv_store_dtype is None else k.to(kv_store_dtype).to(dt)
+    v_st = v if kv_store_dtype is None else v.to(kv_store_dtype).to(dt)
+    pool_layer[0, slot_t // blk, slot_t % blk] = k_st
+    pool_layer[1, slot_t // blk, slot_t % blk] = v_st
     o = torch.empty(t, nq, d, dtype=dt)
     row0 = 0
     for s, (n, c) in enumerate(zip(q_lens, ctx_lens)):
@@ -163,13 +169,14 @@ def decoder_layer(shape: OracleShape, w: Dict[str, torch.Tensor], x: torch.Tenso
 def stage_forward(shape: OracleShape, layers: Sequence[Dict[str, torch.Tensor]], hidden: torch.Tensor,
                   positions, q_lens: Sequence[int], ctx_lens: Sequence[int], block_tables,
                   pool: torch.Tensor, dtype=torch.float64,
-                  taps: Optional[List[Dict[str, torch.Tensor]]] = None):
+                  taps: Optional[List[Dict[str, torch.Tensor]]] = None, kv_store_dtype=None):
     """Run the stage's layers on one micro-batch.
 
     hidden [T, H] (any float dtype; widened exactly), positions [T], per-sequence q_lens
     (new tokens; 1 = decode) and ctx_lens (tokens already cached), block_tables [S][...],
     pool [L, 2, blocks, slot, nkv, d] holding the cached context at the logical positions
-    0 .. ctx-1 of every sequence; it is updated in place with the new tokens.
+    0 .. ctx-1 of every sequence; it is updated in place with the new tokens (unrounded, or rounded
+    once to kv_store_dtype if given: see decoder_layer).
     Returns (output [T, H] in `dtype`, slot list [T]).
     """
     assert pool.dtype == dtype
@@ -178,7 +185,7 @@ def stage_forward(shape: OracleShape, layers: Sequence[Dict[str, torch.Tensor]],
     slots = slot_mapping(q_lens, ctx_lens, block_tables, shape.kv_block_size)
     for l in range(shape.num_layers):
         tap = {} if taps is not None else None
-        x = decoder_layer(shape, layers[l], x, pos, q_lens, ctx_lens, block_tables, pool[l], slots, tap)
+        x = decoder_layer(shape, layers[l], x, pos, q_lens, ctx_lens, block_tables, pool[l], slots, tap, kv_store_dtype)
         if taps is not None:
             taps.append(tap)
     return x, slots

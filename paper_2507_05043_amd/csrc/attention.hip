@@ -52,8 +52,8 @@ struct DecodeStepLoads {
   bf16x8 v[D / 16];                // V^T tiles, one per 16 output dims
 };
 
-template <int D>
-__global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, const DecodeItem* __restrict__ items,
+template <int D, bool QLO>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void attn_decode_kernel(AttnArgs a, const DecodeItem* __restrict__ items,
                                                           int num_items, float* __restrict__ part_o,
                                                           float2* __restrict__ part_ml) {
   constexpr int KS = D / 32;   // MFMA k-steps of the QK product
@@ -78,15 +78,21 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, const Deco
   const int ldq = (a.nq + 2 * a.nkv) * D;
 
   // Q^T operand: column = query head of the group, lane group holds d = 32*kk + 8*grp .. +7
-  bf16x8 qf[KS];
+  bf16x8 qf[KS], qf_lo[QLO ? KS : 1];
   {
     const int head = r * g + (col < g ? col : 0);
     const __bf16* qp = a.qkv + (size_t)row * ldq + head * D + grp * 8;
+    const __bf16* ql = QLO ? a.q_lo + ((size_t)row * a.nq + head) * D + grp * 8 : qp;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
       bf16x8 v = load8(qp + kk * 32);
       if (col >= g) v = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
       qf[kk] = v;
+      if constexpr (QLO) {
+        bf16x8 w = load8(ql + kk * 32);
+        if (col >= g) w = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        qf_lo[kk] = w;
+      }
     }
   }
 
@@ -131,6 +137,10 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, const Deco
     for (int kk = 0; kk < KS; ++kk) {
       sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(L.ka[kk], qf[kk], sa, 0, 0, 0);
       sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(L.kb[kk], qf[kk], sb, 0, 0, 0);
+      if constexpr (QLO) {   // second query plane into the same scores
+        sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(L.ka[kk], qf_lo[kk], sa, 0, 0, 0);
+        sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(L.kb[kk], qf_lo[kk], sb, 0, 0, 0);
+      }
     }
     const int key0 = key_begin + 32 * step + 8 * grp;     // first of this lane's 8 keys
     const int nvalid = key_end - key0;                    // keys [0, nvalid) of the 8 are real
@@ -231,10 +241,16 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const Decod
     o += po * w;
   }
   const float inv = 1.0f / l;
-  bf16x4 ob;
+  bf16x4 ob, ol;
 #pragma unroll
-  for (int e = 0; e < 4; ++e) ob[e] = f32_to_bf16(o[e] * inv);
-  *reinterpret_cast<bf16x4*>(a.out + (size_t)t.row * a.nq * D + head * D + d4 * 4) = ob;
+  for (int e = 0; e < 4; ++e) {
+    const float val = o[e] * inv;
+    ob[e] = f32_to_bf16(val);
+    ol[e] = f32_to_bf16(val - bf16_to_f32(ob[e]));
+  }
+  const size_t at = (size_t)t.row * a.nq * D + head * D + d4 * 4;
+  *reinterpret_cast<bf16x4*>(a.out + at) = ob;
+  if (a.out_lo) *reinterpret_cast<bf16x4*>(a.out_lo + at) = ol;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -244,7 +260,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const Decod
 // 8*((m/4)%2) + 4*((m/8)%2) + m%4): accumulator registers 0..7 of lane group G = lane/32 are then
 // slots 8G..8G+7 of the first block, registers 8..15 the same slots of the second block.
 // ------------------------------------------------------------------------------------------------
-template <int D>
+template <int D, bool QLO>
 __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const PrefillTile* __restrict__ tiles,
                                                            int num_tiles) {
   constexpr int KS = D / 16;   // MFMA k-steps of the QK product
@@ -273,11 +289,16 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
   const int nsteps = max_limit / 32 + 1;
   const int ldq = (a.nq + 2 * a.nkv) * D;
 
-  bf16x8 qf[KS];
+  bf16x8 qf[KS], qf_lo[QLO ? KS : 1];
   {
     const __bf16* qp = a.qkv + (size_t)(row0 + tok) * ldq + (r * g + hg) * D + grp * 8;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) qf[kk] = load8(qp + kk * 16);
+    if constexpr (QLO) {
+      const __bf16* ql = a.q_lo + ((size_t)(row0 + tok) * a.nq + r * g + hg) * D + grp * 8;
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) qf_lo[kk] = load8(ql + kk * 16);
+    }
   }
 
   const int k_bsel = col >> 4;
@@ -321,7 +342,10 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
 #pragma unroll
     for (int e = 0; e < 16; ++e) s[e] = 0.f;
 #pragma unroll
-    for (int kk = 0; kk < KS; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s, 0, 0, 0);
+    for (int kk = 0; kk < KS; ++kk) {
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s, 0, 0, 0);
+      if constexpr (QLO) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf_lo[kk], s, 0, 0, 0);
+    }
     // register e of this lane is key 32*step + 16*(e/8) + 8*grp + e%8
     const int key_base = 32 * step + 8 * grp;
     float sv[16];
@@ -382,15 +406,20 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   if (col0 + col < ncols) {
     const float inv = 1.0f / l_tot;
-    __bf16* op = a.out + (size_t)(row0 + tok) * a.nq * D + (r * g + hg) * D + 4 * grp;
+    const size_t at = (size_t)(row0 + tok) * a.nq * D + (r * g + hg) * D + 4 * grp;
 #pragma unroll
     for (int t = 0; t < DT; ++t) {
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
-        bf16x4 ob;
+        bf16x4 ob, ol;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) ob[e] = f32_to_bf16(acc[t][q4 * 4 + e] * inv);
-        *reinterpret_cast<bf16x4*>(op + t * 32 + q4 * 8) = ob;
+        for (int e = 0; e < 4; ++e) {
+          const float val = acc[t][q4 * 4 + e] * inv;
+          ob[e] = f32_to_bf16(val);
+          ol[e] = f32_to_bf16(val - bf16_to_f32(ob[e]));
+        }
+        *reinterpret_cast<bf16x4*>(a.out + at + t * 32 + q4 * 8) = ob;
+        if (a.out_lo) *reinterpret_cast<bf16x4*>(a.out_lo + at + t * 32 + q4 * 8) = ol;
       }
     }
   }
@@ -400,20 +429,26 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
 
 hipError_t launch_attn_prefill(const AttnArgs& a, const PrefillTile* tiles, int num_tiles, hipStream_t stream) {
   dim3 grid((num_tiles + 3) / 4, a.nkv), block(256);
-  if (a.head_dim == 128)
-    hipLaunchKernelGGL(attn_prefill_kernel<128>, grid, block, 0, stream, a, tiles, num_tiles);
-  else
-    hipLaunchKernelGGL(attn_prefill_kernel<64>, grid, block, 0, stream, a, tiles, num_tiles);
+  if (a.head_dim == 128) {
+    if (a.q_lo) hipLaunchKernelGGL((attn_prefill_kernel<128, true>), grid, block, 0, stream, a, tiles, num_tiles);
+    else hipLaunchKernelGGL((attn_prefill_kernel<128, false>), grid, block, 0, stream, a, tiles, num_tiles);
+  } else {
+    if (a.q_lo) hipLaunchKernelGGL((attn_prefill_kernel<64, true>), grid, block, 0, stream, a, tiles, num_tiles);
+    else hipLaunchKernelGGL((attn_prefill_kernel<64, false>), grid, block, 0, stream, a, tiles, num_tiles);
+  }
   return hipGetLastError();
 }
 
 hipError_t launch_attn_decode(const AttnArgs& a, const DecodeItem* items, int num_items, float* part_o,
                               float2* part_ml, hipStream_t stream) {
   dim3 grid(num_items, (a.nkv + 3) / 4), block(256);
-  if (a.head_dim == 128)
-    hipLaunchKernelGGL(attn_decode_kernel<128>, grid, block, 0, stream, a, items, num_items, part_o, part_ml);
-  else
-    hipLaunchKernelGGL(attn_decode_kernel<64>, grid, block, 0, stream, a, items, num_items, part_o, part_ml);
+  if (a.head_dim == 128) {
+    if (a.q_lo) hipLaunchKernelGGL((attn_decode_kernel<128, true>), grid, block, 0, stream, a, items, num_items, part_o, part_ml);
+    else hipLaunchKernelGGL((attn_decode_kernel<128, false>), grid, block, 0, stream, a, items, num_items, part_o, part_ml);
+  } else {
+    if (a.q_lo) hipLaunchKernelGGL((attn_decode_kernel<64, true>), grid, block, 0, stream, a, items, num_items, part_o, part_ml);
+    else hipLaunchKernelGGL((attn_decode_kernel<64, false>), grid, block, 0, stream, a, items, num_items, part_o, part_ml);
+  }
   return hipGetLastError();
 }
 

@@ -78,13 +78,14 @@ __global__ __launch_bounds__(256) void rope_table_kernel(const int32_t* __restri
 }
 
 // One workgroup per token row.  Work units of 8 elements:
-//   rotated heads (q then k): unit = (head, chunk of 8 pairs): reads lo/hi halves, rotates, writes back
-//   in place and, for k heads, also into the K pool row of the token's slot;
-//   v heads: unit = (head, chunk of 8 dims): scattered into the transposed V block.
+//   rotated heads (q then k): unit = (head, chunk of 8 pairs): reads the fp32 halves, rotates, rounds to
+//   bf16 once, writes the bf16 row and, for k heads, also the K pool row of the token's slot;
+//   v heads: unit = (head, chunk of 8 dims): rounded once and scattered into the transposed V block.
 __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs p) {
   const int t = blockIdx.x, tid = threadIdx.x;
   const int d = p.head_dim, half = d / 2, cpr = half / 8;       // chunks per rotated head
   const int row_elems = (p.nq + 2 * p.nkv) * d;
+  const float* src = p.qkv_f32 + (size_t)t * row_elems;
   __bf16* row = p.qkv + (size_t)t * row_elems;
   const float2* cs = p.cos_sin + (size_t)t * half;
   const int64_t slot = p.slots[t];
@@ -92,22 +93,36 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs p) {
   const int s = (int)(slot % kKvBlock);
   const int rot_units = (p.nq + p.nkv) * cpr;
   const int v_units = p.nkv * (d / 8);
+  auto load8f = [](const float* q, float* v) {
+    const float4 a = *reinterpret_cast<const float4*>(q), b = *reinterpret_cast<const float4*>(q + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  };
   for (int u = tid; u < rot_units + v_units; u += 256) {
     if (u < rot_units) {
       const int head = u / cpr, c = u % cpr;
-      __bf16* base = row + head * d + c * 8;
-      const bf16x8 lo = load8(base), hi = load8(base + half);
-      bf16x8 olo, ohi;
+      float lo[8], hi[8];
+      load8f(src + head * d + c * 8, lo);
+      load8f(src + head * d + half + c * 8, hi);
+      bf16x8 olo, ohi, llo, lhi;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const float2 f = cs[c * 8 + e];
-        const float a = bf16_to_f32(lo[e]), b = bf16_to_f32(hi[e]);
-        olo[e] = f32_to_bf16(a * f.x - b * f.y);
-        ohi[e] = f32_to_bf16(b * f.x + a * f.y);
+        const float y0 = lo[e] * f.x - hi[e] * f.y, y1 = hi[e] * f.x + lo[e] * f.y;
+        olo[e] = f32_to_bf16(y0);
+        ohi[e] = f32_to_bf16(y1);
+        llo[e] = f32_to_bf16(y0 - bf16_to_f32(olo[e]));
+        lhi[e] = f32_to_bf16(y1 - bf16_to_f32(ohi[e]));
       }
+      __bf16* base = row + head * d + c * 8;
       store8(base, olo);
       store8(base + half, ohi);
-      if (head >= p.nq) {
+      if (head < p.nq) {
+        if (p.q_lo) {
+          __bf16* lb = p.q_lo + ((size_t)t * p.nq + head) * d + c * 8;
+          store8(lb, llo);
+          store8(lb + half, lhi);
+        }
+      } else {
         const int r = head - p.nq;
         __bf16* dst = p.k_pool + (((size_t)blk * p.nkv + r) * kKvBlock + s) * d + c * 8;
         store8(dst, olo);
@@ -116,10 +131,15 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs p) {
     } else {
       const int w = u - rot_units;
       const int r = w / (d / 8), c = w % (d / 8);
-      const bf16x8 v = load8(row + (p.nq + p.nkv + r) * d + c * 8);
+      float v[8];
+      load8f(src + (p.nq + p.nkv + r) * d + c * 8, v);
+      bf16x8 vb;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vb[e] = f32_to_bf16(v[e]);
+      store8(row + (p.nq + p.nkv + r) * d + c * 8, vb);
       __bf16* dst = p.v_pool + (((size_t)blk * p.nkv + r) * d + c * 8) * kKvBlock + s;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) dst[e * kKvBlock] = v[e];
+      for (int e = 0; e < 8; ++e) dst[e * kKvBlock] = vb[e];
     }
   }
 }

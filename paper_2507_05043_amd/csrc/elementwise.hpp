@@ -17,7 +17,9 @@ hipError_t launch_rope_table(const int32_t* positions, float2* cos_sin, int rows
                              hipStream_t stream);
 
 struct RopeAppendArgs {
-  __bf16* qkv;             // [T][(nq + 2 nkv) d]; q and k heads are rotated in place
+  const float* qkv_f32;    // [T][(nq + 2 nkv) d] projection output, fp32 (rounded to bf16 only after the rotation)
+  __bf16* qkv;             // [T][(nq + 2 nkv) d] bf16: rotated q heads, rotated k heads, v heads
+  __bf16* q_lo;            // optional [T][nq d]: bf16(q - bf16(q)), second plane of the rotated queries
   const float2* cos_sin;   // [T][d/2]
   const int64_t* slots;    // [T] pool slot of every row
   __bf16* k_pool;          // this layer's K region [blocks][nkv][16][d]

@@ -298,8 +298,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
           const int n = n0 + wn * TN + j * 32 + col_in_tile;
           if (n >= p.n) continue;
           const float c = acc[i][j][r];
-          if constexpr (EPI == kEpiStoreBf16) {
-            p.out_bf16[(size_t)m * p.ldo + n] = f32_to_bf16(c);
+          if constexpr (EPI == kEpiStoreF32) {
+            p.out_f32[(size_t)m * p.ldo + n] = c;
           } else if constexpr (EPI == kEpiResidualF32) {
             p.resid[(size_t)m * p.n + n] += c;
           } else {
@@ -335,8 +335,8 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(GemmArgs p, int
     const float* src = p.partial + (size_t)m * nv + n;
     float c = 0.f;
     for (int s = 0; s < splits; ++s) c += src[s * plane];
-    if constexpr (EPI == kEpiStoreBf16) {
-      p.out_bf16[(size_t)m * p.ldo + n] = f32_to_bf16(c);
+    if constexpr (EPI == kEpiStoreF32) {
+      p.out_f32[(size_t)m * p.ldo + n] = c;
     } else if constexpr (EPI == kEpiResidualF32) {
       p.resid[idx] += c;
     } else {
@@ -416,11 +416,9 @@ hipError_t launch_tile(const GemmArgs& a, const GemmPlan& plan, hipStream_t stre
 template <int EPI>
 hipError_t launch_epi(const GemmArgs& a, const GemmPlan& plan, hipStream_t stream) {
   if (a.a_lo) {
-    // two activation planes: only the MLP projections use them, and only the tiles whose stages still fit
-    if constexpr (EPI == kEpiSwiGLU || EPI == kEpiResidualF32 || EPI == kEpiResidualOut) {
-      if (plan.tile == kTile128x128) return launch_tile<128, 128, 2, 2, 3, EPI, true>(a, plan, stream);
-      if (plan.tile == kTile64x128) return launch_tile<64, 128, 2, 2, 2, EPI, true>(a, plan, stream);
-    }
+    // two activation planes: only the tiles whose stages still fit in LDS
+    if (plan.tile == kTile128x128) return launch_tile<128, 128, 2, 2, 3, EPI, true>(a, plan, stream);
+    if (plan.tile == kTile64x128) return launch_tile<64, 128, 2, 2, 2, EPI, true>(a, plan, stream);
     return hipErrorInvalidValue;
   }
   switch (plan.tile) {
@@ -493,7 +491,7 @@ size_t gemm_partial_floats(int max_m, int n, int k, GemmEpilogue epi, int num_cu
 
 hipError_t launch_gemm_main(const GemmArgs& a, GemmEpilogue epi, const GemmPlan& plan, hipStream_t stream) {
   switch (epi) {
-    case kEpiStoreBf16: return launch_epi<kEpiStoreBf16>(a, plan, stream);
+    case kEpiStoreF32: return launch_epi<kEpiStoreF32>(a, plan, stream);
     case kEpiResidualF32: return launch_epi<kEpiResidualF32>(a, plan, stream);
     case kEpiResidualOut: return launch_epi<kEpiResidualOut>(a, plan, stream);
     case kEpiSwiGLU: return launch_epi<kEpiSwiGLU>(a, plan, stream);
@@ -505,8 +503,8 @@ hipError_t launch_gemm_reduce(const GemmArgs& a, GemmEpilogue epi, const GemmPla
   const size_t count = (size_t)a.m * a.n;
   dim3 grid((unsigned)((count + 255) / 256)), block(256);
   switch (epi) {
-    case kEpiStoreBf16:
-      hipLaunchKernelGGL((gemm_splitk_reduce_kernel<kEpiStoreBf16>), grid, block, 0, stream, a, plan.nv, plan.splits);
+    case kEpiStoreF32:
+      hipLaunchKernelGGL((gemm_splitk_reduce_kernel<kEpiStoreF32>), grid, block, 0, stream, a, plan.nv, plan.splits);
       break;
     case kEpiResidualF32:
       hipLaunchKernelGGL((gemm_splitk_reduce_kernel<kEpiResidualF32>), grid, block, 0, stream, a, plan.nv, plan.splits);

@@ -6,7 +6,7 @@
 namespace molink {
 
 enum GemmEpilogue : int {
-  kEpiStoreBf16 = 0,    // out_bf16[m][n] = acc
+  kEpiStoreF32 = 0,     // out_f32[m][n] = acc                   (q/k/v before RoPE: rounded only once, after it)
   kEpiResidualF32 = 1,  // resid[m][n] += acc                      (fp32 residual stream, in place)
   kEpiResidualOut = 2,  // out_bf16[m][n] = resid[m][n] + acc      (last layer: packed payload)
   kEpiSwiGLU = 3,       // out_bf16[m][f] = silu(acc_gate[f]) * acc_up[f]
@@ -21,10 +21,11 @@ struct GemmArgs {
   const __bf16* w0;     // [N][K]; for SwiGLU the gate matrix [F][K]
   const __bf16* w1;     // SwiGLU only: the up matrix [F][K]
   __bf16* out_bf16;     // see GemmEpilogue
+  float* out_f32;       // kEpiStoreF32 output [M][ldo]
   float* resid;         // fp32 residual stream [M][N]
   float* partial;       // split-K scratch [splits][M][Nv] fp32
   int m, n, k;          // n = output features (F for SwiGLU)
-  int lda, ldo;         // leading dimensions (elements) of a and out_bf16
+  int lda, ldo;         // leading dimensions (elements) of a and of out_bf16 / out_f32
 };
 
 enum GemmTile : int { kTile256x256 = 0, kTile256x128 = 1, kTile128x128 = 2, kTile64x128 = 3 };

@@ -49,7 +49,7 @@ struct Dims {
 };
 
 struct WorkspaceLayout {
-  size_t x, a, a_lo, qkv, attn, mlp, mlp_lo, cos_sin, splitk, part_o, part_ml, meta, total;
+  size_t x, a, a_lo, qkv_f32, qkv, q_lo, attn, attn_lo, mlp, mlp_lo, cos_sin, splitk, part_o, part_ml, meta, total;
   size_t meta_bytes;
   int max_items, max_tiles;
 };
@@ -69,6 +69,8 @@ int check_config(const stage_config* c) {
   if (c->num_q_heads / c->num_kv_heads > 16)
     return fail(STAGE_ERR_CONFIG, "at most 16 query heads per KV head are supported");
   if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return fail(STAGE_ERR_CONFIG, "rms_eps must be > 0 and rope_theta > 1");
+  if (c->activation_planes < 0 || c->activation_planes > 2)
+    return fail(STAGE_ERR_CONFIG, "activation_planes must be 0 (automatic), 1 or 2");
   if (c->num_kv_blocks < 1 || c->max_tokens < 1 || c->max_seqs < 1 || c->max_blocks_per_seq < 1)
     return fail(STAGE_ERR_CONFIG, "capacities must be positive");
   const size_t layer_bytes = (size_t)c->num_kv_blocks * c->num_kv_heads * 16 * c->head_dim * 2 * 2;
@@ -89,13 +91,15 @@ Dims dims_of(const stage_config& c) {
 // Number of compute units the work decomposition is sized for.  The library targets MI355X only.
 constexpr int kNumCus = 256;
 
-// Deep stages carry the MLP's activations (the post-attention norm output and silu(gate)*up) as two
-// bf16 planes, value = hi + lo, and multiply both into the same accumulators.  One bf16 rounding per
-// GEMM input costs about 1.7e-3 relative error per layer on the residual stream; the errors of the
-// layers add in quadrature, and beyond about ten layers the single-plane path no longer meets the
-// 1e-2 relative-L2 budget on the stage output.  The second plane doubles the MFMA work of the gate/up
-// and down projections, so shallow stages do without it.
-bool split_mlp_of(const stage_config& c) { return c.num_layers > 10; }
+// Deep stages carry every GEMM input (both norm outputs, the attention output, silu(gate)*up) and the
+// rotated queries as two bf16 planes, value = hi + lo, and multiply both into the same accumulators.
+// One bf16 rounding per GEMM input costs about 1.7e-3 relative error per layer on the residual
+// stream; the errors of the layers add in quadrature, and beyond about ten layers the single-plane
+// path no longer meets the 1e-2 relative-L2 budget on the stage output.  The second plane doubles the
+// MFMA work of the projections, so shallow stages do without it.
+bool two_plane_of(const stage_config& c) {
+  return c.activation_planes == 0 ? c.num_layers > 10 : c.activation_planes == 2;
+}
 
 int decode_target_items(const Dims& d) { return (kNumCus * kDecodeWavesPerCu + d.nkv - 1) / d.nkv; }
 
@@ -107,16 +111,19 @@ WorkspaceLayout layout_of(const stage_config& c) {
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
   w.x = take(T * d.H * 4);
   w.a = take(T * d.H * 2);
-  w.a_lo = take(split_mlp_of(c) ? T * d.H * 2 : 0);
+  w.a_lo = take(two_plane_of(c) ? T * d.H * 2 : 0);
+  w.qkv_f32 = take(T * d.qkv_out * 4);
   w.qkv = take(T * d.qkv_out * 2);
+  w.q_lo = take(two_plane_of(c) ? T * d.nq * d.d * 2 : 0);
   w.attn = take(T * d.nq * d.d * 2);
+  w.attn_lo = take(two_plane_of(c) ? T * d.nq * d.d * 2 : 0);
   w.mlp = take(T * d.F * 2);
-  w.mlp_lo = take(split_mlp_of(c) ? T * d.F * 2 : 0);
+  w.mlp_lo = take(two_plane_of(c) ? T * d.F * 2 : 0);
   w.cos_sin = take(T * (d.d / 2) * 8);
-  size_t pf = gemm_partial_floats(c.max_tokens, d.qkv_out, d.H, kEpiStoreBf16, kNumCus);
+  const bool sp = two_plane_of(c);
+  size_t pf = gemm_partial_floats(c.max_tokens, d.qkv_out, d.H, kEpiStoreF32, kNumCus, sp);
   size_t v;
-  if ((v = gemm_partial_floats(c.max_tokens, d.H, d.nq * d.d, kEpiResidualF32, kNumCus)) > pf) pf = v;
-  const bool sp = split_mlp_of(c);
+  if ((v = gemm_partial_floats(c.max_tokens, d.H, d.nq * d.d, kEpiResidualF32, kNumCus, sp)) > pf) pf = v;
   if ((v = gemm_partial_floats(c.max_tokens, d.F, d.H, kEpiSwiGLU, kNumCus, sp)) > pf) pf = v;
   if ((v = gemm_partial_floats(c.max_tokens, d.H, d.F, kEpiResidualF32, kNumCus, sp)) > pf) pf = v;
   w.splitk = take(pf * 4 + 16);
@@ -394,9 +401,12 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
 
   float* x = (float*)(ws + st->ws.x);
   __bf16* a = (__bf16*)(ws + st->ws.a);
-  const bool split_mlp = split_mlp_of(c);
+  const bool split_mlp = two_plane_of(c);
   __bf16* a_lo = split_mlp ? (__bf16*)(ws + st->ws.a_lo) : nullptr;
   __bf16* mlp_lo = split_mlp ? (__bf16*)(ws + st->ws.mlp_lo) : nullptr;
+  __bf16* q_lo = split_mlp ? (__bf16*)(ws + st->ws.q_lo) : nullptr;
+  __bf16* attn_lo = split_mlp ? (__bf16*)(ws + st->ws.attn_lo) : nullptr;
+  float* qkv_f32 = (float*)(ws + st->ws.qkv_f32);
   __bf16* qkv = (__bf16*)(ws + st->ws.qkv);
   __bf16* attn = (__bf16*)(ws + st->ws.attn);
   __bf16* mlp = (__bf16*)(ws + st->ws.mlp);
@@ -419,7 +429,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
   {
     // the first layer's input norm also initialises the fp32 residual stream from the bf16 input
     Timer t(st, stream, STAGE_K_RMSNORM);
-    HIP_TRY(launch_rmsnorm((const __bf16*)hidden_in, x, (const __bf16*)st->layers[0].norm1, a, nullptr, T, d.H, c.rms_eps,
+    HIP_TRY(launch_rmsnorm((const __bf16*)hidden_in, x, (const __bf16*)st->layers[0].norm1, a, a_lo, T, d.H, c.rms_eps,
                            true, stream));
   }
   for (int l = 0; l < d.L; ++l) {
@@ -433,19 +443,19 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       HIP_TRY(hipMemcpyAsync(taps->tap_norm1, a, (size_t)T * d.H * 2, hipMemcpyDeviceToDevice, stream));
     {
       GemmArgs g{};
-      g.a = a; g.w0 = (const __bf16*)w.wqkv; g.out_bf16 = qkv; g.partial = splitk;
+      g.a = a; g.a_lo = a_lo; g.w0 = (const __bf16*)w.wqkv; g.out_f32 = qkv_f32; g.partial = splitk;
       g.m = T; g.n = d.qkv_out; g.k = d.H; g.lda = d.H; g.ldo = d.qkv_out;
-      int rc = run_gemm(st, stream, STAGE_K_GEMM_QKV, g, kEpiStoreBf16);
+      int rc = run_gemm(st, stream, STAGE_K_GEMM_QKV, g, kEpiStoreF32);
       if (rc) return rc;
     }
     {
       Timer t(st, stream, STAGE_K_ROPE_APPEND);
-      RopeAppendArgs r{qkv, cos_sin, d_slots, k_pool, v_pool, T, d.nq, d.nkv, d.d};
+      RopeAppendArgs r{qkv_f32, qkv, q_lo, cos_sin, d_slots, k_pool, v_pool, T, d.nq, d.nkv, d.d};
       HIP_TRY(launch_rope_append(r, stream));
     }
     if (tap && taps->tap_qkv)
       HIP_TRY(hipMemcpyAsync(taps->tap_qkv, qkv, (size_t)T * d.qkv_out * 2, hipMemcpyDeviceToDevice, stream));
-    AttnArgs aa{qkv, k_pool, v_pool, d_bt, attn, d.nq, d.nkv, d.d, 1.4426950408889634f / sqrtf((float)d.d)};
+    AttnArgs aa{qkv, q_lo, k_pool, v_pool, d_bt, attn, attn_lo, d.nq, d.nkv, d.d, 1.4426950408889634f / sqrtf((float)d.d)};
     if (n_tiles) {
       Timer t(st, stream, STAGE_K_ATTN_PREFILL);
       HIP_TRY(launch_attn_prefill(aa, d_tiles, n_tiles, stream));
@@ -462,7 +472,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       HIP_TRY(hipMemcpyAsync(taps->tap_attn, attn, (size_t)T * d.nq * d.d * 2, hipMemcpyDeviceToDevice, stream));
     {
       GemmArgs g{};
-      g.a = attn; g.w0 = (const __bf16*)w.wo; g.resid = x; g.partial = splitk;
+      g.a = attn; g.a_lo = attn_lo; g.w0 = (const __bf16*)w.wo; g.resid = x; g.partial = splitk;
       g.m = T; g.n = d.H; g.k = d.nq * d.d; g.lda = d.nq * d.d; g.ldo = d.H;
       int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_O, g, kEpiResidualF32, (const __bf16*)w.norm2, a, a_lo);
       if (rc) return rc;
@@ -489,7 +499,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       g.m = T; g.n = d.H; g.k = d.F; g.lda = d.F; g.ldo = d.H;
       const __bf16* next_gain = last ? nullptr : (const __bf16*)st->layers[l + 1].norm1;
       int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_DOWN, g, fused_out ? kEpiResidualOut : kEpiResidualF32,
-                                 next_gain, a, nullptr);
+                                 next_gain, a, a_lo);
       if (rc) return rc;
       if (tap && taps->tap_x)
         HIP_TRY(hipMemcpyAsync(taps->tap_x, x, (size_t)T * d.H * 4, hipMemcpyDeviceToDevice, stream));

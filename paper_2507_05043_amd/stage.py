@@ -36,6 +36,7 @@ class StageConfig(ctypes.Structure):
         ("kv_block_size", ctypes.c_int32), ("num_kv_blocks", ctypes.c_int32),
         ("kv_layer_stride_bytes", ctypes.c_int64),
         ("max_tokens", ctypes.c_int32), ("max_seqs", ctypes.c_int32), ("max_blocks_per_seq", ctypes.c_int32),
+        ("activation_planes", ctypes.c_int32),
     ]
 
 
@@ -93,9 +94,10 @@ def _check(rc: int) -> None:
 
 def make_config(*, num_layers, hidden, num_q_heads, num_kv_heads, head_dim, ffn, rms_eps, rope_theta,
                 num_kv_blocks, max_tokens, max_seqs, max_blocks_per_seq, kv_block_size=16,
-                kv_layer_stride_bytes=None) -> StageConfig:
+                kv_layer_stride_bytes=None, activation_planes=0) -> StageConfig:
     cfg = StageConfig(ctypes.sizeof(StageConfig), num_layers, hidden, num_q_heads, num_kv_heads, head_dim, ffn,
-                      rms_eps, rope_theta, kv_block_size, num_kv_blocks, 0, max_tokens, max_seqs, max_blocks_per_seq)
+                      rms_eps, rope_theta, kv_block_size, num_kv_blocks, 0, max_tokens, max_seqs, max_blocks_per_seq,
+                      activation_planes)
     if kv_layer_stride_bytes is None:
         kv_layer_stride_bytes = stage_kv_layer_bytes(cfg)
     cfg.kv_layer_stride_bytes = kv_layer_stride_bytes

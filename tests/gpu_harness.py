@@ -47,6 +47,36 @@ def check_output(gpu_out: torch.Tensor, ref: torch.Tensor, what: str = "output")
     return {"rel_l2": r, "max_abs": max_abs, "rms": rms}
 
 
+def check_output_stratified(gpu_out: torch.Tensor, ref: torch.Tensor, strata, what: str = "output",
+                            gate_max_abs: bool = True) -> Dict[str, float]:
+    """The whole-output metric estimated from a stratified sample of rows.
+
+    strata: list of (row_slice_into_the_sample, rows_in_the_population).  Every sampled row of a
+    stratum stands for population/sample rows, so the sums of squared error and of squared reference
+    are scaled per stratum before the ratio is taken (rows of a stratum are exact; only which
+    sequences were drawn is a sample).  Also reports every stratum on its own.
+    """
+    got = gpu_out.detach().cpu().double()
+    ref = ref.double()
+    assert torch.isfinite(got).all(), f"{what}: non-finite values"
+    num = den = 0.0
+    per = []
+    max_abs = 0.0
+    for sl, population in strata:
+        g, r = got[sl], ref[sl]
+        w = population / g.shape[0]
+        num += w * float((g - r).pow(2).sum())
+        den += w * float(r.pow(2).sum())
+        per.append(rel_l2(g, r))
+        max_abs = max(max_abs, float((g - r).abs().max()))
+    est = (num / den) ** 0.5
+    rms = float(ref.pow(2).mean().sqrt())
+    assert est <= REL_L2_TOL, f"{what}: estimated whole-output rel-L2 {est:.3e} > {REL_L2_TOL} (strata {per})"
+    if gate_max_abs:
+        assert max_abs <= MAX_ABS_TOL * max(1.0, rms), f"{what}: max-abs {max_abs:.3e} (rms {rms:.3f})"
+    return {"rel_l2": est, "per_stratum": per, "max_abs": max_abs, "rms": rms}
+
+
 def check_taps(gpu_taps: Dict[str, torch.Tensor], otap: Dict[str, torch.Tensor], x_in: torch.Tensor,
                x_in_gpu: torch.Tensor, label: str):
     """Every sub-layer output, and the two residual branches on their own, within the rel-L2 tolerance.

@@ -39,13 +39,14 @@ def test_library_exports_every_declared_symbol(lib):
 
 
 def test_config_struct_matches_header_size(lib):
-    # uint32 + 6 int32 + 2 float + 2 int32 (+ 4 pad) + int64 + 3 int32 (+ 4 pad)
+    # uint32 + 6 int32 + 2 float + 2 int32 (+ 4 pad) + int64 + 4 int32
     assert ctypes.sizeof(S.StageConfig) == 72
     assert S.stage_workspace_bytes(tiny_cfg()) > 0
 
 
 @pytest.mark.parametrize("bad", [dict(kv_block_size=32), dict(head_dim=96), dict(hidden=252), dict(num_q_heads=5),
-                                 dict(num_q_heads=34, num_kv_heads=2), dict(rms_eps=0.0), dict(num_layers=0)])
+                                 dict(num_q_heads=34, num_kv_heads=2), dict(rms_eps=0.0), dict(num_layers=0),
+                                 dict(activation_planes=3)])
 def test_unsupported_configs_are_rejected(lib, bad):
     with pytest.raises(StageError) as ei:
         cfg = tiny_cfg(**bad)
