@@ -397,6 +397,161 @@ __global__ __launch_bounds__(1024) void reduce_residual_norm_kernel(const float*
   }
 }
 
+// Weight-streaming GEMM for micro-batches of at most 64 rows (decode): the projection is bound by
+// reading W once from HBM, so the kernel is built around that stream.
+//
+// K is cut into slices of 1024; a workgroup keeps one slice for its whole life and walks over groups
+// of 16 weight rows.  A stage is 16 weight rows x 2 KB, filled by global_load_lds instructions that
+// each fetch 1 KB of ONE row (the longest run a wave instruction can ask for, and what the memory
+// system streams fastest); four stages, three in flight (96 KB per CU).  Chunk c (16 bytes) of row r is
+// stored at position c ^ (r & 7) of its 1 KB piece - done by choosing which chunk each lane fetches -
+// so that the 128-bit fragment reads of 16 rows at one k are conflict free.
+//
+// Eight waves with two roles.  Waves 4-7 only issue the loads: a wave that has filled the address
+// unit's queue stalls at its next load until older ones have drained, and a wave that also had to
+// multiply would do so only after that stall - load time and multiply time would add up.  Waves 0-3
+// multiply: wave w holds the activations of rows 16w..16w+15 for the whole slice in registers as MFMA
+// operands (loaded once), multiplies every stage with them (16x16x32 MFMA, weights as the row operand)
+// and writes its 16 x 16 block of the slice's partial sums; the split-K reduction kernels add the
+// slices in order and apply the epilogue.  One barrier per stage joins the two roles.
+constexpr int kSkinnyKS = 1024;     // K elements per slice
+constexpr int kSkinnyRows = 16;     // weight rows per stage
+constexpr int kSkinnyStages = 4;
+
+__global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs p, int nv, int splits, int groups, int swiglu) {
+  constexpr int KS = kSkinnyKS, ROWS = kSkinnyRows, NST = kSkinnyStages;
+  constexpr int STAGE_BYTES = ROWS * KS * 2;
+  constexpr int NI = ROWS * 2 / 4;             // load instructions per loading wave per stage (two 1 KB pieces per row)
+  constexpr int STEPS = KS / 32;               // MFMA steps per stage
+  using Lds = LdsStages<STAGE_BYTES>;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nwg = gridDim.x;
+  const int split = blockIdx.x % splits, slot = blockIdx.x / splits;
+  const int peers = (nwg - split + splits - 1) / splits;         // workgroups that share this slice
+  const int g_begin = (int)((long)groups * slot / peers);
+  const int g_end = (int)((long)groups * (slot + 1) / peers);
+  const int n_units = g_end - g_begin;
+  const int n_steps = (n_units + NST - 1) / NST * NST;           // both roles run the same number of barriers
+  const int kbase = split * KS;
+  if (n_units <= 0) return;
+
+  if (wave >= 4) {
+    // ---- loading waves ----
+    const int lw = wave - 4;
+    // byte offset inside a row of the chunk this lane fetches: position `lane` of a 1 KB piece receives
+    // chunk lane ^ (row & 7)
+    uint32_t koff[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int idx = NI * lw + i, row = idx >> 1, half = idx & 1;
+      int k = kbase + 8 * (64 * half + (lane ^ (row & 7)));
+      k = k < p.k - 8 ? k : p.k - 8;           // past the end of K: any finite value, the activations there are zero
+      koff[i] = (uint32_t)k * 2u;
+    }
+    // Every pipeline step issues the same number of loads, so that the wait count below holds without
+    // control flow around the loads (which the compiler would answer with full waits).  A fetch past the
+    // workgroup's last unit degenerates to one cache line: every lane reads the start of a row.
+    auto fetch = [&](auto stage_c, int unit) {
+      constexpr int S = decltype(stage_c)::value;
+      const bool real = unit < n_units;
+      unit = real ? unit : n_units - 1;
+      const int v0 = (g_begin + unit) * ROWS;    // first (virtual) row of the group
+      // SwiGLU: 32 gate rows, then the 32 up rows of the same features
+      const __bf16* w = (swiglu && (v0 & 32)) ? p.w1 : p.w0;
+      const int r0 = swiglu ? (v0 >> 6) * 32 + (v0 & 31) : v0;
+      const int last = p.n - 1 - r0;              // rows past the matrix repeat its last row (never stored)
+      char* stage = Lds::template get<S>();
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        const int idx = NI * lw + i;
+        int row = idx >> 1;
+        row = row < last ? row : last;
+        const char* base = reinterpret_cast<const char*>(w + (size_t)(r0 + row) * p.k);
+        __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(base + (real ? koff[i] : 0u)),
+                                         reinterpret_cast<uint32_t*>(stage + idx * 1024), 16, 0, 0);
+      }
+    };
+    // Step u: after the wait only the 2 * NI loads of the two younger stages can still be in flight, so
+    // this wave's part of stage u % 4 has landed; after the barrier everybody's has, and the multiplying
+    // waves are done with stage (u - 1) % 4, which is refilled next.
+    auto step = [&](auto stage_c, int u) {
+      constexpr int S = decltype(stage_c)::value;
+      wait_vmcnt<2 * NI>();
+      pipeline_barrier();
+      fetch(std::integral_constant<int, (S + NST - 1) % NST>{}, u + NST - 1);
+    };
+    fetch(std::integral_constant<int, 0>{}, 0);
+    fetch(std::integral_constant<int, 1>{}, 1);
+    fetch(std::integral_constant<int, 2>{}, 2);
+    for (int u = 0; u < n_steps; u += NST) {
+      step(std::integral_constant<int, 0>{}, u);
+      step(std::integral_constant<int, 1>{}, u + 1);
+      step(std::integral_constant<int, 2>{}, u + 2);
+      step(std::integral_constant<int, 3>{}, u + 3);
+    }
+    wait_vmcnt<0>();   // nothing may still be writing LDS when the workgroup ends
+    return;
+  }
+
+  // ---- multiplying waves ----
+  // activations: lane (row l%16, quarter l/16) holds k = 32 s + 8 (l/16) .. +7 of step s
+  const int a_row = 16 * wave + (lane & 15), quarter = lane >> 4;
+  const bool wave_active = 16 * wave < p.m;
+  bf16x8 act[STEPS];
+  {
+    const int m = a_row < p.m ? a_row : p.m - 1;
+    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+      const int k = kbase + 32 * s + 8 * quarter;
+      act[s] = wave_active && k < p.k ? load8(p.a + (size_t)m * p.lda + k) : zero;
+    }
+  }
+
+  // fragment of step s: lane (row n = l%16, quarter q) wants chunk 4s + q of row n, stored at position
+  // (4s + q) ^ (n & 7) = 4 (s ^ ((n >> 2) & 1)) + (q ^ (n & 3)) of the piece s / 16 of the row
+  const int n_in = lane & 15;
+  const int frag_base = n_in * 2048 + ((quarter ^ (n_in & 3)) * 16);
+  const int flip = (n_in >> 2) & 1;
+  const int frag_even = frag_base + flip * 64, frag_odd = frag_base - flip * 64;
+
+  auto compute = [&](auto stage_c, int unit) {
+    constexpr int S = decltype(stage_c)::value;
+    pipeline_barrier();
+    if (!wave_active || unit >= n_units) return;
+    const char* stage = Lds::template get<S>();
+    f32x4 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+      const int off = (s >> 4) * 1024 + (s & 15) * 64 + ((s & 1) ? frag_odd : frag_even);
+      const bf16x8 wf = *reinterpret_cast<const bf16x8*>(stage + off);
+      acc[s & 3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, act[s], acc[s & 3], 0, 0, 0);
+    }
+    // eight fragment reads run ahead of the MFMA that consumes the oldest of them
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+    for (int s = 0; s < STEPS - 8; ++s) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+    const f32x4 sum = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+    // accumulator register r of lane l is C[weight row 4 (l/16) + r][activation row l%16]
+    const int v = (g_begin + unit) * ROWS + 4 * quarter;
+    if (a_row < p.m && v < nv) *reinterpret_cast<f32x4*>(p.partial + ((size_t)split * p.m + a_row) * nv + v) = sum;
+  };
+  for (int u = 0; u < n_steps; u += NST) {
+    compute(std::integral_constant<int, 0>{}, u);
+    compute(std::integral_constant<int, 1>{}, u + 1);
+    compute(std::integral_constant<int, 2>{}, u + 2);
+    compute(std::integral_constant<int, 3>{}, u + 3);
+  }
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int EPI, bool SPLIT_A>
 hipError_t launch_tile(const GemmArgs& a, const GemmPlan& plan, hipStream_t stream) {
   const int tiles_m = (a.m + BM - 1) / BM;
@@ -439,19 +594,23 @@ GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool spli
   // measured relative efficiency of the tile shapes and how many workgroups of each fit on a CU (LDS)
   static const Cand cands[] = {{kTile256x256, 256, 256, 1, 0.9f}, {kTile256x128, 256, 128, 1, 1.0f},
                                {kTile128x128, 128, 128, 2, 0.95f}};
-  if (m <= 64) {
-    plan.tile = kTile64x128;
-  } else {
-    float best = 0.f;
-    plan.tile = kTile128x128;
-    for (const Cand& c : cands) {
-      if (split_a && c.tile != kTile128x128) continue;   // with two activation planes only this tile's stages fit
-      const long tiles = (long)((m + c.bm - 1) / c.bm) * ((plan.nv + c.bn - 1) / c.bn);
-      const long slots = (long)num_cus * c.wg_per_cu;
-      const long rounds = (tiles + slots - 1) / slots;
-      const float cost = (float)rounds * c.bm * c.bn * c.wg_per_cu / c.eff;
-      if (best == 0.f || cost < best) { best = cost; plan.tile = c.tile; }
-    }
+  if (m <= 64 && !split_a) {
+    plan.tile = kTileSkinny;
+    plan.splits = (k + kSkinnyKS - 1) / kSkinnyKS;
+    plan.k_tiles_per_split = kSkinnyKS / kBK;
+    plan.partials = true;
+    return plan;
+  }
+  float best = 0.f;
+  plan.tile = m <= 64 ? kTile64x128 : kTile128x128;
+  for (const Cand& c : cands) {
+    if (m <= 64) break;
+    if (split_a && c.tile != kTile128x128) continue;   // with two activation planes only this tile's stages fit
+    const long tiles = (long)((m + c.bm - 1) / c.bm) * ((plan.nv + c.bn - 1) / c.bn);
+    const long slots = (long)num_cus * c.wg_per_cu;
+    const long rounds = (tiles + slots - 1) / slots;
+    const float cost = (float)rounds * c.bm * c.bn * c.wg_per_cu / c.eff;
+    if (best == 0.f || cost < best) { best = cost; plan.tile = c.tile; }
   }
   const int bm = plan.tile == kTile64x128 ? 64 : (plan.tile == kTile128x128 ? 128 : 256);
   const int bn = plan.tile == kTile256x256 ? 256 : 128;
@@ -466,23 +625,24 @@ GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool spli
   }
   plan.k_tiles_per_split = (k_tiles + splits - 1) / splits;
   plan.splits = (k_tiles + plan.k_tiles_per_split - 1) / plan.k_tiles_per_split;
+  plan.partials = plan.splits > 1;
   return plan;
 }
 
 size_t gemm_partial_floats(int max_m, int n, int k, GemmEpilogue epi, int num_cus, bool split_a) {
-  // Splitting only happens when there are fewer tiles than CUs; the scratch of any such shape is
-  // bounded by 16 splits of the largest m that still splits.
+  // The scratch of a shape is splits * m * nv; the split count falls as m grows, so every m at which the
+  // plan can change (multiples of 64) is tried.
   size_t worst = 0;
   for (int m = 1; m <= max_m; m = (m < 64 ? 64 : m + 64)) {
-    const int mm = m > max_m ? max_m : m;
-    GemmPlan p = plan_gemm(mm, n, k, epi, num_cus, split_a);
-    if (p.splits > 1) {
+    const GemmPlan p = plan_gemm(m, n, k, epi, num_cus, split_a);
+    if (p.partials) {
+      const int mm = m < 64 ? (max_m < 64 ? max_m : 64) : m;   // the plan of m = 1 holds up to 64 rows
       const size_t need = (size_t)p.splits * mm * p.nv;
       if (need > worst) worst = need;
     }
   }
-  GemmPlan p = plan_gemm(max_m, n, k, epi, num_cus, split_a);
-  if (p.splits > 1) {
+  const GemmPlan p = plan_gemm(max_m, n, k, epi, num_cus, split_a);
+  if (p.partials) {
     const size_t need = (size_t)p.splits * max_m * p.nv;
     if (need > worst) worst = need;
   }
@@ -490,6 +650,17 @@ size_t gemm_partial_floats(int max_m, int n, int k, GemmEpilogue epi, int num_cu
 }
 
 hipError_t launch_gemm_main(const GemmArgs& a, GemmEpilogue epi, const GemmPlan& plan, hipStream_t stream) {
+  if (plan.tile == kTileSkinny) {
+    if (a.m > 64 || a.a_lo) return hipErrorInvalidValue;
+    const int groups = (plan.nv + kSkinnyRows - 1) / kSkinnyRows;
+    const long units = (long)groups * plan.splits;
+    const int cus = 256;
+    const int nwg = units < cus ? (int)units : (cus > plan.splits ? cus : plan.splits);
+    dim3 grid(nwg);
+    hipLaunchKernelGGL(gemm_skinny_kernel, grid, dim3(512), 0, stream, a, plan.nv, plan.splits, groups,
+                       epi == kEpiSwiGLU ? 1 : 0);
+    return hipGetLastError();
+  }
   switch (epi) {
     case kEpiStoreF32: return launch_epi<kEpiStoreF32>(a, plan, stream);
     case kEpiResidualF32: return launch_epi<kEpiResidualF32>(a, plan, stream);

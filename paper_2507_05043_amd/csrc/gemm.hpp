@@ -28,11 +28,14 @@ struct GemmArgs {
   int lda, ldo;         // leading dimensions (elements) of a and of out_bf16 / out_f32
 };
 
-enum GemmTile : int { kTile256x256 = 0, kTile256x128 = 1, kTile128x128 = 2, kTile64x128 = 3 };
+// kTileSkinny: at most 64 rows; K cut into slices of 1024, weights streamed in groups of 16 rows, always
+// through partial sums (the reduction applies the epilogue).
+enum GemmTile : int { kTile256x256 = 0, kTile256x128 = 1, kTile128x128 = 2, kTile64x128 = 3, kTileSkinny = 4 };
 
 struct GemmPlan {
   int tile;             // GemmTile: workgroup tile shape
-  int splits;           // K splits across workgroups (1 = epilogue fused into the GEMM kernel)
+  int splits;           // K splits across workgroups
+  bool partials;        // the GEMM kernel writes partial sums [splits][M][nv]; a reduction applies the epilogue
   int k_tiles_per_split;
   int nv;               // width of the column space the kernel iterates (gate/up interleaved for SwiGLU, else N)
 };
@@ -42,10 +45,10 @@ GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool spli
 size_t gemm_partial_floats(int max_m, int n, int k, GemmEpilogue epi, int num_cus, bool split_a = false);
 
 hipError_t launch_gemm_main(const GemmArgs& args, GemmEpilogue epi, const GemmPlan& plan, hipStream_t stream);
-// Only when plan.splits > 1: sums the partial results in split order and applies the epilogue.
+// Only when plan.partials: sums the partial results in split order and applies the epilogue.
 hipError_t launch_gemm_reduce(const GemmArgs& args, GemmEpilogue epi, const GemmPlan& plan, hipStream_t stream);
 
-// Only when plan.splits > 1 and the epilogue is a residual one: one kernel that sums the partial
+// Only when plan.partials and the epilogue is a residual one: one kernel that sums the partial
 // results in split order, adds them to the fp32 residual stream x[m][n] (in place), and then either
 // writes RMSNorm(x; gain, eps) as bf16 to norm_out (gain != nullptr) or rounds x to bf16 into
 // args.out_bf16 (kEpiResidualOut).  Replaces launch_gemm_reduce plus the following RMSNorm.

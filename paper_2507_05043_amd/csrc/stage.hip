@@ -259,7 +259,7 @@ int run_gemm(stage_handle* st, hipStream_t stream, int kernel_class, const GemmA
     Timer t(st, stream, kernel_class);
     HIP_TRY(launch_gemm_main(args, epi, plan, stream));
   }
-  if (plan.splits > 1) {
+  if (plan.partials) {
     Timer t(st, stream, STAGE_K_SPLITK_REDUCE);
     HIP_TRY(launch_gemm_reduce(args, epi, plan, stream));
   }
@@ -276,13 +276,13 @@ int run_residual_gemm(stage_handle* st, hipStream_t stream, int kernel_class, co
     Timer t(st, stream, kernel_class);
     HIP_TRY(launch_gemm_main(args, epi, plan, stream));
   }
-  const bool fused = plan.splits > 1 && (gain != nullptr || epi == kEpiResidualOut);
+  const bool fused = plan.partials && (gain != nullptr || epi == kEpiResidualOut);
   if (fused) {
     Timer t(st, stream, STAGE_K_SPLITK_REDUCE);
     HIP_TRY(launch_gemm_reduce_residual_norm(args, epi, plan, gain, st->cfg.rms_eps, norm_out, norm_out_lo, stream));
     return STAGE_OK;
   }
-  if (plan.splits > 1) {
+  if (plan.partials) {
     Timer t(st, stream, STAGE_K_SPLITK_REDUCE);
     HIP_TRY(launch_gemm_reduce(args, epi, plan, stream));
   }
