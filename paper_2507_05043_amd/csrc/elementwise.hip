@@ -82,65 +82,70 @@ __global__ __launch_bounds__(256) void rope_table_kernel(const int32_t* __restri
 //   bf16 once, writes the bf16 row and, for k heads, also the K pool row of the token's slot;
 //   v heads: unit = (head, chunk of 8 dims): rounded once and scattered into the transposed V block.
 __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs p) {
-  const int t = blockIdx.x, tid = threadIdx.x;
+  const int t = blockIdx.x;
+  const int u = blockIdx.y * 256 + threadIdx.x;                  // one unit of 8 (rotated: 8 pairs) per thread
   const int d = p.head_dim, half = d / 2, cpr = half / 8;       // chunks per rotated head
+  const int rot_units = (p.nq + p.nkv) * cpr;
+  const int v_units = p.nkv * (d / 8);
+  if (u >= rot_units + v_units) return;
   const int row_elems = (p.nq + 2 * p.nkv) * d;
   const float* src = p.qkv_f32 + (size_t)t * row_elems;
   __bf16* row = p.qkv + (size_t)t * row_elems;
-  const float2* cs = p.cos_sin + (size_t)t * half;
   const int64_t slot = p.slots[t];
   const int64_t blk = slot / kKvBlock;
   const int s = (int)(slot % kKvBlock);
-  const int rot_units = (p.nq + p.nkv) * cpr;
-  const int v_units = p.nkv * (d / 8);
-  auto load8f = [](const float* q, float* v) {
-    const float4 a = *reinterpret_cast<const float4*>(q), b = *reinterpret_cast<const float4*>(q + 4);
-    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  // 8 consecutive fp32 values, summed over the split-K planes in plane order
+  auto load8f = [&](const float* q, float* v) {
+    f32x4 a = *reinterpret_cast<const f32x4*>(q), b = *reinterpret_cast<const f32x4*>(q + 4);
+    for (int k = 1; k < p.planes; ++k) {
+      a += *reinterpret_cast<const f32x4*>(q + k * p.plane_stride);
+      b += *reinterpret_cast<const f32x4*>(q + k * p.plane_stride + 4);
+    }
+    v[0] = a[0]; v[1] = a[1]; v[2] = a[2]; v[3] = a[3]; v[4] = b[0]; v[5] = b[1]; v[6] = b[2]; v[7] = b[3];
   };
-  for (int u = tid; u < rot_units + v_units; u += 256) {
-    if (u < rot_units) {
-      const int head = u / cpr, c = u % cpr;
-      float lo[8], hi[8];
-      load8f(src + head * d + c * 8, lo);
-      load8f(src + head * d + half + c * 8, hi);
-      bf16x8 olo, ohi, llo, lhi;
+  if (u < rot_units) {
+    const int head = u / cpr, c = u % cpr;
+    const float2* cs = p.cos_sin + (size_t)t * half + c * 8;
+    float lo[8], hi[8];
+    load8f(src + head * d + c * 8, lo);
+    load8f(src + head * d + half + c * 8, hi);
+    bf16x8 olo, ohi, llo, lhi;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float2 f = cs[c * 8 + e];
-        const float y0 = lo[e] * f.x - hi[e] * f.y, y1 = hi[e] * f.x + lo[e] * f.y;
-        olo[e] = f32_to_bf16(y0);
-        ohi[e] = f32_to_bf16(y1);
-        llo[e] = f32_to_bf16(y0 - bf16_to_f32(olo[e]));
-        lhi[e] = f32_to_bf16(y1 - bf16_to_f32(ohi[e]));
-      }
-      __bf16* base = row + head * d + c * 8;
-      store8(base, olo);
-      store8(base + half, ohi);
-      if (head < p.nq) {
-        if (p.q_lo) {
-          __bf16* lb = p.q_lo + ((size_t)t * p.nq + head) * d + c * 8;
-          store8(lb, llo);
-          store8(lb + half, lhi);
-        }
-      } else {
-        const int r = head - p.nq;
-        __bf16* dst = p.k_pool + (((size_t)blk * p.nkv + r) * kKvBlock + s) * d + c * 8;
-        store8(dst, olo);
-        store8(dst + half, ohi);
+    for (int e = 0; e < 8; ++e) {
+      const float2 f = cs[e];
+      const float y0 = lo[e] * f.x - hi[e] * f.y, y1 = hi[e] * f.x + lo[e] * f.y;
+      olo[e] = f32_to_bf16(y0);
+      ohi[e] = f32_to_bf16(y1);
+      llo[e] = f32_to_bf16(y0 - bf16_to_f32(olo[e]));
+      lhi[e] = f32_to_bf16(y1 - bf16_to_f32(ohi[e]));
+    }
+    __bf16* base = row + head * d + c * 8;
+    store8(base, olo);
+    store8(base + half, ohi);
+    if (head < p.nq) {
+      if (p.q_lo) {
+        __bf16* lb = p.q_lo + ((size_t)t * p.nq + head) * d + c * 8;
+        store8(lb, llo);
+        store8(lb + half, lhi);
       }
     } else {
-      const int w = u - rot_units;
-      const int r = w / (d / 8), c = w % (d / 8);
-      float v[8];
-      load8f(src + (p.nq + p.nkv + r) * d + c * 8, v);
-      bf16x8 vb;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) vb[e] = f32_to_bf16(v[e]);
-      store8(row + (p.nq + p.nkv + r) * d + c * 8, vb);
-      __bf16* dst = p.v_pool + (((size_t)blk * p.nkv + r) * d + c * 8) * kKvBlock + s;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) dst[e * kKvBlock] = vb[e];
+      const int r = head - p.nq;
+      __bf16* dst = p.k_pool + (((size_t)blk * p.nkv + r) * kKvBlock + s) * d + c * 8;
+      store8(dst, olo);
+      store8(dst + half, ohi);
     }
+  } else {
+    const int w = u - rot_units;
+    const int r = w / (d / 8), c = w % (d / 8);
+    float v[8];
+    load8f(src + (p.nq + p.nkv + r) * d + c * 8, v);
+    bf16x8 vb;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) vb[e] = f32_to_bf16(v[e]);
+    store8(row + (p.nq + p.nkv + r) * d + c * 8, vb);
+    __bf16* dst = p.v_pool + (((size_t)blk * p.nkv + r) * d + c * 8) * kKvBlock + s;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dst[e * kKvBlock] = vb[e];
   }
 }
 
@@ -166,7 +171,8 @@ hipError_t launch_rope_table(const int32_t* positions, float2* cos_sin, int rows
 }
 
 hipError_t launch_rope_append(const RopeAppendArgs& args, hipStream_t stream) {
-  hipLaunchKernelGGL(rope_append_kernel, dim3(args.rows), dim3(256), 0, stream, args);
+  const int units = (args.nq + args.nkv) * (args.head_dim / 16) + args.nkv * (args.head_dim / 8);
+  hipLaunchKernelGGL(rope_append_kernel, dim3(args.rows, (units + 255) / 256), dim3(256), 0, stream, args);
   return hipGetLastError();
 }
 

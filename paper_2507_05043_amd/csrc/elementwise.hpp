@@ -17,7 +17,10 @@ hipError_t launch_rope_table(const int32_t* positions, float2* cos_sin, int rows
                              hipStream_t stream);
 
 struct RopeAppendArgs {
-  const float* qkv_f32;    // [T][(nq + 2 nkv) d] projection output, fp32 (rounded to bf16 only after the rotation)
+  const float* qkv_f32;    // [planes][T][(nq + 2 nkv) d] projection output, fp32 (rounded to bf16 only after the
+                           // rotation); with planes > 1 the split-K partial sums, added here in plane order
+  int planes;
+  size_t plane_stride;     // floats between planes
   __bf16* qkv;             // [T][(nq + 2 nkv) d] bf16: rotated q heads, rotated k heads, v heads
   __bf16* q_lo;            // optional [T][nq d]: bf16(q - bf16(q)), second plane of the rotated queries
   const float2* cos_sin;   // [T][d/2]

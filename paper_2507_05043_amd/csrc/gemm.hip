@@ -311,10 +311,11 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
   }
 }
 
-// Adds the split-K partial sums (split 0 first) and applies the epilogue.  One thread per output.
+// Adds the split-K partial sums (split 0 first) and applies the epilogue.  Four consecutive outputs per
+// thread (n is a multiple of 8, so a group of four never straddles a row or a gate/up block of 32).
 template <int EPI>
 __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(GemmArgs p, int nv, int splits) {
-  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t idx = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
   const size_t count = (size_t)p.m * p.n;
   if (idx >= count) return;
   const int m = (int)(idx / p.n), n = (int)(idx % p.n);
@@ -322,25 +323,34 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(GemmArgs p, int
   if constexpr (EPI == kEpiSwiGLU) {
     const int vg = (n >> 5) * 64 + (n & 31);
     const float* src = p.partial + (size_t)m * nv + vg;
-    float g = 0.f, u = 0.f;
+    f32x4 g = {0.f, 0.f, 0.f, 0.f}, u = {0.f, 0.f, 0.f, 0.f};
     for (int s = 0; s < splits; ++s) {
-      g += src[s * plane];
-      u += src[s * plane + 32];
+      g += *reinterpret_cast<const f32x4*>(src + s * plane);
+      u += *reinterpret_cast<const f32x4*>(src + s * plane + 32);
     }
-    const float val = silu_f(g) * u;
-    const __bf16 hi = f32_to_bf16(val);
-    p.out_bf16[(size_t)m * p.ldo + n] = hi;
-    if (p.out_lo) p.out_lo[(size_t)m * p.ldo + n] = f32_to_bf16(val - bf16_to_f32(hi));
+    bf16x4 hi, lo;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float val = silu_f(g[e]) * u[e];
+      hi[e] = f32_to_bf16(val);
+      lo[e] = f32_to_bf16(val - bf16_to_f32(hi[e]));
+    }
+    *reinterpret_cast<bf16x4*>(p.out_bf16 + (size_t)m * p.ldo + n) = hi;
+    if (p.out_lo) *reinterpret_cast<bf16x4*>(p.out_lo + (size_t)m * p.ldo + n) = lo;
   } else {
     const float* src = p.partial + (size_t)m * nv + n;
-    float c = 0.f;
-    for (int s = 0; s < splits; ++s) c += src[s * plane];
+    f32x4 c = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < splits; ++s) c += *reinterpret_cast<const f32x4*>(src + s * plane);
     if constexpr (EPI == kEpiStoreF32) {
-      p.out_f32[(size_t)m * p.ldo + n] = c;
+      *reinterpret_cast<f32x4*>(p.out_f32 + (size_t)m * p.ldo + n) = c;
     } else if constexpr (EPI == kEpiResidualF32) {
-      p.resid[idx] += c;
+      *reinterpret_cast<f32x4*>(p.resid + idx) += c;
     } else {
-      p.out_bf16[(size_t)m * p.ldo + n] = f32_to_bf16(p.resid[idx] + c);
+      const f32x4 r = *reinterpret_cast<const f32x4*>(p.resid + idx) + c;
+      bf16x4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16(r[e]);
+      *reinterpret_cast<bf16x4*>(p.out_bf16 + (size_t)m * p.ldo + n) = o;
     }
   }
 }
@@ -671,7 +681,7 @@ hipError_t launch_gemm_main(const GemmArgs& a, GemmEpilogue epi, const GemmPlan&
 }
 
 hipError_t launch_gemm_reduce(const GemmArgs& a, GemmEpilogue epi, const GemmPlan& plan, hipStream_t stream) {
-  const size_t count = (size_t)a.m * a.n;
+  const size_t count = (size_t)a.m * a.n / 4;
   dim3 grid((unsigned)((count + 255) / 256)), block(256);
   switch (epi) {
     case kEpiStoreF32:

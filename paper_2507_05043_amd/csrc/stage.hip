@@ -445,12 +445,15 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       GemmArgs g{};
       g.a = a; g.a_lo = a_lo; g.w0 = (const __bf16*)w.wqkv; g.out_f32 = qkv_f32; g.partial = splitk;
       g.m = T; g.n = d.qkv_out; g.k = d.H; g.lda = d.H; g.ldo = d.qkv_out;
-      int rc = run_gemm(st, stream, STAGE_K_GEMM_QKV, g, kEpiStoreF32);
-      if (rc) return rc;
-    }
-    {
+      // the rotation kernel adds the split-K partial sums itself: no separate reduction pass
+      const GemmPlan plan = plan_gemm(g.m, g.n, g.k, kEpiStoreF32, kNumCus, g.a_lo != nullptr);
+      {
+        Timer t(st, stream, STAGE_K_GEMM_QKV);
+        HIP_TRY(launch_gemm_main(g, kEpiStoreF32, plan, stream));
+      }
       Timer t(st, stream, STAGE_K_ROPE_APPEND);
-      RopeAppendArgs r{qkv_f32, qkv, q_lo, cos_sin, d_slots, k_pool, v_pool, T, d.nq, d.nkv, d.d};
+      RopeAppendArgs r{plan.partials ? splitk : qkv_f32, plan.partials ? plan.splits : 1, (size_t)T * d.qkv_out,
+                       qkv, q_lo, cos_sin, d_slots, k_pool, v_pool, T, d.nq, d.nkv, d.d};
       HIP_TRY(launch_rope_append(r, stream));
     }
     if (tap && taps->tap_qkv)
