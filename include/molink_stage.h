@@ -71,6 +71,8 @@ typedef struct {
                                   activations that are effectively 16-bit.  Automatic = 2 for stages deeper than
                                   10 layers, whose accumulated bf16 rounding error would otherwise exceed
                                   1e-2 relative on the output, else 1. */
+  int32_t vocab_size;          /* 0, or the vocabulary size (multiple of 8, >= 64) of the output head this
+                                  stage may run with stage_head (sizes the workspace for it) */
 } stage_config;
 
 /* Device pointers to one layer's bf16 weights, row-major [out_features][in_features]. Borrowed, read-only. */
@@ -177,6 +179,36 @@ int stage_forward_taps(stage_handle *st, void *hip_stream, int32_t num_tokens, c
                        int64_t *slot_mapping_out, const stage_taps *taps);
 
 /*
+ * The two ends of the pipeline.  The head engine turns requests into the first stage's input and
+ * the system's output is generated tokens (paper section 3.2.2 "Distributed Inference Engine";
+ * section 5 "Metrics"); the definitions are the Llama family's (section 5 "Models").
+ *
+ * stage_embed: hidden_out[t] = table[token_ids[t]], the input of the first stage.
+ *   table       device bf16 [vocab][H] (H = the handle's hidden size), borrowed for the call
+ *   token_ids   host int32 [T], each in [0, vocab); validated before anything is enqueued
+ *   hidden_out  device bf16 [T][H]
+ * Needs no vocab_size in the config.  Errors: STAGE_ERR_NULL, STAGE_ERR_BATCH, STAGE_ERR_HIP.
+ *
+ * stage_head: for every sequence s of a micro-batch, on its LAST row r(s) = q_lens[0] + .. + q_lens[s] - 1:
+ *   logits[s] = RMSNorm(hidden[r(s)]; final_norm, rms_eps) * lm_head^T,  next_tokens[s] = argmax_v logits[s][v]
+ * (the smallest index among equal maxima).  The norm is computed in fp32 and rounded to bf16 once, the
+ * projection accumulates in fp32, logits stay fp32.
+ *   hidden       device bf16 [T][H]: the last stage's hidden_out
+ *   q_lens       host int32 [S], sum == T
+ *   final_norm   device bf16 [H];  lm_head  device bf16 [vocab][H]; both borrowed for the call
+ *   vocab        must equal the config's vocab_size
+ *   logits_out   device f32 [S][vocab], or NULL when only the tokens are wanted
+ *   next_tokens  device int32 [S]
+ * Asynchronous on hip_stream like stage_forward, shares the handle's workspace with it (same ordering
+ * rule).  Errors: STAGE_ERR_NULL, STAGE_ERR_CONFIG (vocab mismatch), STAGE_ERR_BATCH, STAGE_ERR_HIP.
+ */
+int stage_embed(stage_handle *st, void *hip_stream, const void *table, int32_t vocab, int32_t num_tokens,
+                const int32_t *token_ids, void *hidden_out);
+int stage_head(stage_handle *st, void *hip_stream, int32_t num_tokens, const void *hidden, int32_t num_seqs,
+               const int32_t *q_lens, const void *final_norm, const void *lm_head, int32_t vocab,
+               void *logits_out, int32_t *next_tokens);
+
+/*
  * Per-kernel timing with HIP events recorded on the stream the kernels are launched on.
  * stage_profile_enable(st, mask): bit k of mask turns timing of kernel class k on (0 = off).
  * stage_profile_read: synchronises the events recorded so far, adds up the elapsed time of
@@ -195,7 +227,11 @@ enum {
   STAGE_K_GEMM_DOWN = 8,
   STAGE_K_SPLITK_REDUCE = 9,
   STAGE_K_ROPE_TABLE = 10,
-  STAGE_K_COUNT = 11
+  STAGE_K_EMBED = 11,
+  STAGE_K_HEAD_NORM = 12,
+  STAGE_K_GEMM_HEAD = 13,
+  STAGE_K_HEAD_ARGMAX = 14,
+  STAGE_K_COUNT = 15
 };
 int stage_profile_enable(stage_handle *st, uint32_t kernel_mask);
 int stage_profile_read(stage_handle *st, int32_t kernel, double *out_total_ms, int64_t *out_launches);

@@ -149,7 +149,96 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs p) {
   }
 }
 
+__global__ __launch_bounds__(256) void embed_gather_kernel(const __bf16* __restrict__ table, const int32_t* __restrict__ ids,
+                                                           __bf16* __restrict__ out, int hidden) {
+  const int t = blockIdx.x;
+  const __bf16* src = table + (size_t)ids[t] * hidden;
+  __bf16* dst = out + (size_t)t * hidden;
+  for (int c = threadIdx.x * 8; c < hidden; c += 256 * 8) store8(dst + c, load8(src + c));
+}
+
+__global__ __launch_bounds__(256) void gather_rmsnorm_kernel(const __bf16* __restrict__ in, const int32_t* __restrict__ rows,
+                                                             const __bf16* __restrict__ gain, __bf16* __restrict__ out,
+                                                             int hidden, float eps) {
+  __shared__ float wsum[4];
+  const int s = blockIdx.x, tid = threadIdx.x;
+  const __bf16* src = in + (size_t)rows[s] * hidden;
+  float ss = 0.f;
+  for (int c = tid * 8; c < hidden; c += 256 * 8) {
+    const bf16x8 v = load8(src + c);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { const float f = bf16_to_f32(v[e]); ss += f * f; }
+  }
+  ss = wave_sum(ss);
+  if ((tid & 63) == 0) wsum[tid >> 6] = ss;
+  __syncthreads();
+  const float tot = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+  const float rs = 1.0f / sqrtf(tot / (float)hidden + eps);
+  for (int c = tid * 8; c < hidden; c += 256 * 8) {
+    const bf16x8 v = load8(src + c), g = load8(gain + c);
+    bf16x8 o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = f32_to_bf16(bf16_to_f32(v[e]) * rs * bf16_to_f32(g[e]));
+    store8(out + (size_t)s * hidden + c, o);
+  }
+}
+
+// One workgroup per row.  Every thread keeps the best (value, index) of the columns it visits in
+// increasing order (so `>` keeps the earliest), then the pairs are combined preferring the larger
+// value and, among equal values, the smaller index.
+__global__ __launch_bounds__(1024) void argmax_rows_kernel(const float* __restrict__ src, int planes, size_t plane_stride,
+                                                           int vocab, float* __restrict__ logits_out,
+                                                           int32_t* __restrict__ tokens) {
+  __shared__ float bv[16];
+  __shared__ int bi[16];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const float* base = src + (size_t)row * vocab;
+  float best = -INFINITY;
+  int best_i = 0x7fffffff;
+  for (int c = tid * 4; c < vocab; c += 1024 * 4) {
+    f32x4 v = *reinterpret_cast<const f32x4*>(base + c);
+    for (int k = 1; k < planes; ++k) v += *reinterpret_cast<const f32x4*>(base + k * plane_stride + c);
+    if (logits_out) *reinterpret_cast<f32x4*>(logits_out + (size_t)row * vocab + c) = v;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (v[e] > best || best_i == 0x7fffffff) { best = v[e]; best_i = c + e; }
+  }
+  auto better = [](float v, int i, float w, int j) { return v > w || (v == w && i < j); };
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const float ov = __shfl_xor(best, off, 64);
+    const int oi = __shfl_xor(best_i, off, 64);
+    if (oi != 0x7fffffff && (best_i == 0x7fffffff || better(ov, oi, best, best_i))) { best = ov; best_i = oi; }
+  }
+  if ((tid & 63) == 0) { bv[tid >> 6] = best; bi[tid >> 6] = best_i; }
+  __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < 16; ++w)
+      if (bi[w] != 0x7fffffff && (best_i == 0x7fffffff || better(bv[w], bi[w], best, best_i))) { best = bv[w]; best_i = bi[w]; }
+    tokens[row] = best_i == 0x7fffffff ? 0 : best_i;
+  }
+}
+
 }  // namespace
+
+hipError_t launch_embed_gather(const __bf16* table, const int32_t* ids, __bf16* out, int rows, int hidden,
+                               hipStream_t stream) {
+  hipLaunchKernelGGL(embed_gather_kernel, dim3(rows), dim3(256), 0, stream, table, ids, out, hidden);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_rmsnorm(const __bf16* in, const int32_t* rows, const __bf16* gain, __bf16* out, int n_rows,
+                                 int hidden, float eps, hipStream_t stream) {
+  hipLaunchKernelGGL(gather_rmsnorm_kernel, dim3(n_rows), dim3(256), 0, stream, in, rows, gain, out, hidden, eps);
+  return hipGetLastError();
+}
+
+hipError_t launch_argmax_rows(const float* src, int planes, size_t plane_stride, int rows, int vocab, float* logits_out,
+                              int32_t* tokens, hipStream_t stream) {
+  hipLaunchKernelGGL(argmax_rows_kernel, dim3(rows), dim3(1024), 0, stream, src, planes, plane_stride, vocab, logits_out,
+                     tokens);
+  return hipGetLastError();
+}
 
 hipError_t launch_rmsnorm(const __bf16* in_bf16, float* x, const __bf16* gain, __bf16* out, __bf16* out_lo, int rows,
                           int hidden, float eps, bool from_bf16, hipStream_t stream) {

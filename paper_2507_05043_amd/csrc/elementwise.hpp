@@ -31,4 +31,17 @@ struct RopeAppendArgs {
 };
 hipError_t launch_rope_append(const RopeAppendArgs& args, hipStream_t stream);
 
+// out[t][:] = table[ids[t]][:]  (bf16 rows of `hidden` elements, hidden % 8 == 0)
+hipError_t launch_embed_gather(const __bf16* table, const int32_t* ids, __bf16* out, int rows, int hidden,
+                               hipStream_t stream);
+
+// out[s][:] = bf16(RMSNorm(in[rows[s]][:]; gain, eps)), norm in fp32
+hipError_t launch_gather_rmsnorm(const __bf16* in, const int32_t* rows, const __bf16* gain, __bf16* out, int n_rows,
+                                 int hidden, float eps, hipStream_t stream);
+
+// Per row: logits = sum over `planes` of src[plane][row][:] (in plane order), optionally stored, and the
+// index of their maximum (the smallest index among equals) written to tokens[row].
+hipError_t launch_argmax_rows(const float* src, int planes, size_t plane_stride, int rows, int vocab, float* logits_out,
+                              int32_t* tokens, hipStream_t stream);
+
 }  // namespace molink

@@ -50,6 +50,7 @@ struct Dims {
 
 struct WorkspaceLayout {
   size_t x, a, a_lo, qkv_f32, qkv, q_lo, attn, attn_lo, mlp, mlp_lo, cos_sin, splitk, part_o, part_ml, meta, total;
+  size_t head_a, head_logits, ends_meta;   // output head: normalised last rows, fp32 logits, token ids / row indices
   size_t meta_bytes;
   int max_items, max_tiles;
 };
@@ -71,6 +72,8 @@ int check_config(const stage_config* c) {
   if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return fail(STAGE_ERR_CONFIG, "rms_eps must be > 0 and rope_theta > 1");
   if (c->activation_planes < 0 || c->activation_planes > 2)
     return fail(STAGE_ERR_CONFIG, "activation_planes must be 0 (automatic), 1 or 2");
+  if (c->vocab_size != 0 && (c->vocab_size < 64 || c->vocab_size % 8))
+    return fail(STAGE_ERR_CONFIG, "vocab_size must be 0 or a multiple of 8 that is at least 64");
   if (c->num_kv_blocks < 1 || c->max_tokens < 1 || c->max_seqs < 1 || c->max_blocks_per_seq < 1)
     return fail(STAGE_ERR_CONFIG, "capacities must be positive");
   const size_t layer_bytes = (size_t)c->num_kv_blocks * c->num_kv_heads * 16 * c->head_dim * 2 * 2;
@@ -126,7 +129,11 @@ WorkspaceLayout layout_of(const stage_config& c) {
   if ((v = gemm_partial_floats(c.max_tokens, d.H, d.nq * d.d, kEpiResidualF32, kNumCus, sp)) > pf) pf = v;
   if ((v = gemm_partial_floats(c.max_tokens, d.F, d.H, kEpiSwiGLU, kNumCus, sp)) > pf) pf = v;
   if ((v = gemm_partial_floats(c.max_tokens, d.H, d.F, kEpiResidualF32, kNumCus, sp)) > pf) pf = v;
+  if (c.vocab_size > 0 && (v = gemm_partial_floats(c.max_seqs, c.vocab_size, d.H, kEpiStoreF32, kNumCus, false)) > pf) pf = v;
   w.splitk = take(pf * 4 + 16);
+  w.head_a = take(c.vocab_size > 0 ? (size_t)c.max_seqs * d.H * 2 : 0);
+  w.head_logits = take(c.vocab_size > 0 ? (size_t)c.max_seqs * c.vocab_size * 4 : 0);
+  w.ends_meta = take((T > (size_t)c.max_seqs ? T : (size_t)c.max_seqs) * 4 + 256);
   w.max_items = decode_target_items(d) + c.max_seqs;
   w.part_o = take((size_t)w.max_items * d.nq * d.d * 4);
   w.part_ml = take((size_t)w.max_items * d.nq * 8);
@@ -631,6 +638,94 @@ int stage_forward_taps(stage_handle* st, void* hip_stream, int32_t num_tokens, c
                       hidden_out, slot_mapping_out, taps);
 }
 
+// Copies a small host array to the device through a pinned staging slot (the caller may reuse the host
+// array as soon as the call returns).
+static int stage_small_h2d(stage_handle* st, hipStream_t stream, const void* host, size_t bytes, void* dev) {
+  const int slot_id = st->next_slot;
+  st->next_slot = (st->next_slot + 1) % kStagingSlots;
+  if (st->staging_used[slot_id]) HIP_TRY(hipEventSynchronize(st->staging_done[slot_id]));
+  memcpy(st->staging[slot_id], host, bytes);
+  HIP_TRY(hipMemcpyAsync(dev, st->staging[slot_id], bytes, hipMemcpyHostToDevice, stream));
+  HIP_TRY(hipEventRecord(st->staging_done[slot_id], stream));
+  st->staging_used[slot_id] = true;
+  return STAGE_OK;
+}
+
+int stage_embed(stage_handle* st, void* hip_stream, const void* table, int32_t vocab, int32_t num_tokens,
+                const int32_t* token_ids, void* hidden_out) {
+  if (!st) return fail(STAGE_ERR_NULL, "stage handle is NULL");
+  if (!table || !token_ids || !hidden_out) return fail(STAGE_ERR_NULL, "a required argument of stage_embed is NULL");
+  if (vocab < 1) return fail(STAGE_ERR_BATCH, "vocab %d must be positive", vocab);
+  if (num_tokens < 1 || num_tokens > st->cfg.max_tokens)
+    return fail(STAGE_ERR_BATCH, "num_tokens %d outside [1, max_tokens=%d]", num_tokens, st->cfg.max_tokens);
+  for (int t = 0; t < num_tokens; ++t)
+    if (token_ids[t] < 0 || token_ids[t] >= vocab)
+      return fail(STAGE_ERR_BATCH, "token_ids[%d] = %d outside [0, %d)", t, token_ids[t], vocab);
+  HIP_TRY(hipSetDevice(st->device));
+  hipStream_t stream = (hipStream_t)hip_stream;
+  int32_t* d_ids = (int32_t*)(st->workspace + st->ws.ends_meta);
+  int rc = stage_small_h2d(st, stream, token_ids, (size_t)num_tokens * 4, d_ids);
+  if (rc) return rc;
+  Timer t(st, stream, STAGE_K_EMBED);
+  HIP_TRY(launch_embed_gather((const __bf16*)table, d_ids, (__bf16*)hidden_out, num_tokens, st->dim.H, stream));
+  return STAGE_OK;
+}
+
+int stage_head(stage_handle* st, void* hip_stream, int32_t num_tokens, const void* hidden, int32_t num_seqs,
+               const int32_t* q_lens, const void* final_norm, const void* lm_head, int32_t vocab, void* logits_out,
+               int32_t* next_tokens) {
+  if (!st) return fail(STAGE_ERR_NULL, "stage handle is NULL");
+  if (!hidden || !q_lens || !final_norm || !lm_head || !next_tokens)
+    return fail(STAGE_ERR_NULL, "a required argument of stage_head is NULL");
+  const stage_config& c = st->cfg;
+  const Dims& d = st->dim;
+  if (c.vocab_size == 0 || vocab != c.vocab_size)
+    return fail(STAGE_ERR_CONFIG, "vocab %d does not match the stage's vocab_size %d", vocab, c.vocab_size);
+  if (num_tokens < 1 || num_tokens > c.max_tokens)
+    return fail(STAGE_ERR_BATCH, "num_tokens %d outside [1, max_tokens=%d]", num_tokens, c.max_tokens);
+  if (num_seqs < 1 || num_seqs > c.max_seqs)
+    return fail(STAGE_ERR_BATCH, "num_seqs %d outside [1, max_seqs=%d]", num_seqs, c.max_seqs);
+  std::vector<int32_t> rows((size_t)num_seqs);
+  int64_t sum_q = 0;
+  for (int s = 0; s < num_seqs; ++s) {
+    if (q_lens[s] < 1) return fail(STAGE_ERR_BATCH, "q_lens[%d] = %d must be >= 1", s, q_lens[s]);
+    sum_q += q_lens[s];
+    rows[(size_t)s] = (int32_t)(sum_q - 1);
+  }
+  if (sum_q != num_tokens)
+    return fail(STAGE_ERR_BATCH, "sum(q_lens) = %lld != num_tokens = %d", (long long)sum_q, num_tokens);
+  HIP_TRY(hipSetDevice(st->device));
+  hipStream_t stream = (hipStream_t)hip_stream;
+  char* ws = st->workspace;
+  int32_t* d_rows = (int32_t*)(ws + st->ws.ends_meta);
+  int rc = stage_small_h2d(st, stream, rows.data(), (size_t)num_seqs * 4, d_rows);
+  if (rc) return rc;
+  __bf16* head_a = (__bf16*)(ws + st->ws.head_a);
+  {
+    Timer t(st, stream, STAGE_K_HEAD_NORM);
+    HIP_TRY(launch_gather_rmsnorm((const __bf16*)hidden, d_rows, (const __bf16*)final_norm, head_a, num_seqs, d.H,
+                                  c.rms_eps, stream));
+  }
+  GemmArgs g{};
+  g.a = head_a; g.w0 = (const __bf16*)lm_head; g.partial = (float*)(ws + st->ws.splitk);
+  g.m = num_seqs; g.n = vocab; g.k = d.H; g.lda = d.H; g.ldo = vocab;
+  const GemmPlan plan = plan_gemm(g.m, g.n, g.k, kEpiStoreF32, kNumCus, false);
+  // without partial sums the GEMM writes the logits itself (to the caller's buffer if there is one)
+  float* direct = logits_out ? (float*)logits_out : (float*)(ws + st->ws.head_logits);
+  g.out_f32 = direct;
+  {
+    Timer t(st, stream, STAGE_K_GEMM_HEAD);
+    HIP_TRY(launch_gemm_main(g, kEpiStoreF32, plan, stream));
+  }
+  Timer t(st, stream, STAGE_K_HEAD_ARGMAX);
+  if (plan.partials)
+    HIP_TRY(launch_argmax_rows(g.partial, plan.splits, (size_t)num_seqs * vocab, num_seqs, vocab, (float*)logits_out,
+                               next_tokens, stream));
+  else
+    HIP_TRY(launch_argmax_rows(direct, 1, 0, num_seqs, vocab, nullptr, next_tokens, stream));
+  return STAGE_OK;
+}
+
 int stage_profile_enable(stage_handle* st, uint32_t kernel_mask) {
   if (!st) return fail(STAGE_ERR_NULL, "stage handle is NULL");
   st->profile_mask = kernel_mask;
@@ -671,6 +766,10 @@ const char* stage_kernel_name(int32_t kernel) {
     case STAGE_K_ATTN_MERGE: return "attn_merge_kernel";
     case STAGE_K_SPLITK_REDUCE: return "gemm_splitk_reduce_kernel";
     case STAGE_K_ROPE_TABLE: return "rope_table_kernel";
+    case STAGE_K_EMBED: return "embed_gather_kernel";
+    case STAGE_K_HEAD_NORM: return "gather_rmsnorm_kernel";
+    case STAGE_K_GEMM_HEAD: return "gemm_bf16_kernel";
+    case STAGE_K_HEAD_ARGMAX: return "argmax_rows_kernel";
     default: return nullptr;
   }
 }

@@ -11,7 +11,7 @@ from .stage import Stage, make_config
 
 def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_std=None,
                max_tokens: Optional[int] = None, alias_layers: bool = False, fill_kv: bool = True,
-               device: str = "cuda:0", activation_planes: int = 0) -> Stage:
+               device: str = "cuda:0", activation_planes: int = 0, vocab_size: int = 0) -> Stage:
     """Draw the stage's weights on the device, size the pool and workspace for `mb`, fill the cache."""
     layers = [synth.draw_layer_weights(shape, l, seed=seed, device=device, weight_std=weight_std)
               for l in range(shape.num_layers)]
@@ -20,7 +20,8 @@ def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_
                       rms_eps=shape.rms_eps, rope_theta=shape.rope_theta, num_kv_blocks=mb.num_kv_blocks,
                       max_tokens=max_tokens or mb.num_tokens, max_seqs=mb.num_seqs,
                       max_blocks_per_seq=mb.max_blocks_per_seq,
-                      kv_layer_stride_bytes=0 if alias_layers else None, activation_planes=activation_planes)
+                      kv_layer_stride_bytes=0 if alias_layers else None, activation_planes=activation_planes,
+                      vocab_size=vocab_size)
     st = Stage(cfg, layers, device=device)
     if fill_kv:
         fill_pool(st, shape, mb, seed)

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libmolink_stage.so")
 KERNEL_CLASSES = {
     "rmsnorm": 0, "gemm_qkv": 1, "rope_append": 2, "attn_prefill": 3, "attn_decode": 4, "attn_merge": 5,
     "gemm_o": 6, "gemm_gateup": 7, "gemm_down": 8, "splitk_reduce": 9, "rope_table": 10,
+    "embed": 11, "head_norm": 12, "gemm_head": 13, "head_argmax": 14,
 }
 
 
@@ -36,7 +37,7 @@ class StageConfig(ctypes.Structure):
         ("kv_block_size", ctypes.c_int32), ("num_kv_blocks", ctypes.c_int32),
         ("kv_layer_stride_bytes", ctypes.c_int64),
         ("max_tokens", ctypes.c_int32), ("max_seqs", ctypes.c_int32), ("max_blocks_per_seq", ctypes.c_int32),
-        ("activation_planes", ctypes.c_int32),
+        ("activation_planes", ctypes.c_int32), ("vocab_size", ctypes.c_int32),
     ]
 
 
@@ -73,6 +74,10 @@ def load_library() -> ctypes.CDLL:
            i32p, ctypes.c_void_p, i64p]
     lib.stage_forward.argtypes = fwd
     lib.stage_forward_taps.argtypes = fwd + [ctypes.POINTER(StageTaps)]
+    lib.stage_embed.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, i32p,
+                                ctypes.c_void_p]
+    lib.stage_head.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, i32p,
+                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
     lib.stage_profile_enable.argtypes = [ctypes.c_void_p, ctypes.c_uint32]
     lib.stage_profile_read.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_double), i64p]
     lib.stage_kernel_name.argtypes = [ctypes.c_int32]
@@ -81,7 +86,8 @@ def load_library() -> ctypes.CDLL:
     lib.stage_destroy.restype = None
     lib.stage_last_error.restype = ctypes.c_char_p
     for name in ("stage_kv_layer_bytes", "stage_kv_element_offset", "stage_check_batch", "stage_workspace_bytes",
-                 "stage_init", "stage_forward", "stage_forward_taps", "stage_profile_enable", "stage_profile_read"):
+                 "stage_init", "stage_forward", "stage_forward_taps", "stage_profile_enable", "stage_profile_read",
+                 "stage_embed", "stage_head"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -94,10 +100,10 @@ def _check(rc: int) -> None:
 
 def make_config(*, num_layers, hidden, num_q_heads, num_kv_heads, head_dim, ffn, rms_eps, rope_theta,
                 num_kv_blocks, max_tokens, max_seqs, max_blocks_per_seq, kv_block_size=16,
-                kv_layer_stride_bytes=None, activation_planes=0) -> StageConfig:
+                kv_layer_stride_bytes=None, activation_planes=0, vocab_size=0) -> StageConfig:
     cfg = StageConfig(ctypes.sizeof(StageConfig), num_layers, hidden, num_q_heads, num_kv_heads, head_dim, ffn,
                       rms_eps, rope_theta, kv_block_size, num_kv_blocks, 0, max_tokens, max_seqs, max_blocks_per_seq,
-                      activation_planes)
+                      activation_planes, vocab_size)
     if kv_layer_stride_bytes is None:
         kv_layer_stride_bytes = stage_kv_layer_bytes(cfg)
     cfg.kv_layer_stride_bytes = kv_layer_stride_bytes
@@ -245,6 +251,42 @@ class Stage:
         if taps is not None:
             result.append(taps)
         return result[0] if len(result) == 1 else tuple(result)
+
+    # ---- the two ends of the pipeline
+    def embed(self, table: torch.Tensor, token_ids, *, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        c = self.cfg
+        if table.dtype != torch.bfloat16 or not table.is_contiguous() or table.shape[1] != c.hidden:
+            raise ValueError("table must be a contiguous bf16 [vocab, hidden] tensor")
+        ids_t, ids_p = _i32_array(token_ids)
+        t = ids_t.numel()
+        if out is None:
+            out = torch.empty(t, c.hidden, dtype=torch.bfloat16, device=self.device)
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        _check(load_library().stage_embed(self._handle, ctypes.c_void_p(stream), table.data_ptr(), table.shape[0], t,
+                                          ids_p, out.data_ptr()))
+        return out
+
+    def head(self, hidden: torch.Tensor, q_lens, final_norm: torch.Tensor, lm_head: torch.Tensor, *,
+             want_logits: bool = True):
+        """(next_tokens int32 [S], logits f32 [S, vocab] or None) for the last row of every sequence."""
+        c = self.cfg
+        if hidden.dtype != torch.bfloat16 or not hidden.is_contiguous() or hidden.shape[1] != c.hidden:
+            raise ValueError("hidden must be a contiguous bf16 [T, hidden] tensor")
+        for w in (final_norm, lm_head):
+            if w.dtype != torch.bfloat16 or not w.is_contiguous():
+                raise ValueError("final_norm and lm_head must be contiguous bf16 tensors")
+        if lm_head.shape[1] != c.hidden or final_norm.numel() != c.hidden:
+            raise ValueError("final_norm must be [hidden] and lm_head [vocab, hidden]")
+        q_t, q_p = _i32_array(q_lens)
+        s = q_t.numel()
+        vocab = lm_head.shape[0]
+        logits = torch.empty(s, vocab, dtype=torch.float32, device=self.device) if want_logits else None
+        tokens = torch.empty(s, dtype=torch.int32, device=self.device)
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        _check(load_library().stage_head(self._handle, ctypes.c_void_p(stream), hidden.shape[0], hidden.data_ptr(), s, q_p,
+                                         final_norm.data_ptr(), lm_head.data_ptr(), vocab,
+                                         logits.data_ptr() if want_logits else None, tokens.data_ptr()))
+        return tokens, logits
 
     # ---- per-kernel timing
     def profile_enable(self, kernels: Sequence[str]) -> None:

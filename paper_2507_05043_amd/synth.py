@@ -134,6 +134,7 @@ class StageShape:
     rms_eps: float = 1e-5
     rope_theta: float = 1e4
     kv_block_size: int = 16
+    vocab: int = 0          # vocabulary size of the model the stage is cut from (embedding / output head)
 
     @property
     def qkv_out(self) -> int:
@@ -145,10 +146,10 @@ class StageShape:
         return h * self.qkv_out + self.num_q_heads * d * h + 3 * h * self.ffn
 
 
-TINY = StageShape("tiny-llama-style", 2, 256, 4, 2, 64, 688)
-LLAMA2_7B_STAGE = StageShape("llama2-7b-8of32", 8, 4096, 32, 32, 128, 11008)
-QWEN2_7B_STAGE = StageShape("qwen2-7b-7of28", 7, 3584, 28, 4, 128, 18944)
-LLAMA3_70B_STAGE = StageShape("llama3-70b-20of80", 20, 8192, 64, 8, 128, 28672, rope_theta=5e5)
+TINY = StageShape("tiny-llama-style", 2, 256, 4, 2, 64, 688, vocab=1000)
+LLAMA2_7B_STAGE = StageShape("llama2-7b-8of32", 8, 4096, 32, 32, 128, 11008, vocab=32000)
+QWEN2_7B_STAGE = StageShape("qwen2-7b-7of28", 7, 3584, 28, 4, 128, 18944, vocab=152064)
+LLAMA3_70B_STAGE = StageShape("llama3-70b-20of80", 20, 8192, 64, 8, 128, 28672, rope_theta=5e5, vocab=128256)
 
 
 @dataclasses.dataclass
@@ -251,6 +252,10 @@ def workload(name: str, seed: int = 0, budget: int = 256):
 # stream ids of the tensors of a stage (one per tensor kind; the layer index is added)
 STREAM_HIDDEN = 1
 STREAM_KV = 2
+STREAM_EMBED = 3
+STREAM_FINAL_NORM = 4
+STREAM_LM_HEAD = 5
+STREAM_TOKEN_IDS = 6
 STREAM_LAYER_BASE = 100   # + 10*layer + {0..6}
 _WEIGHT_KINDS = ("norm1", "wqkv", "wo", "norm2", "wgate", "wup", "wdown")
 
@@ -296,6 +301,22 @@ def draw_layer_weights(shape: StageShape, layer: int, *, seed: int, device="cpu"
 def draw_hidden(shape: StageShape, num_tokens: int, *, seed: int, device="cpu") -> torch.Tensor:
     return draw_normal_bf16(seed, STREAM_HIDDEN, num_tokens * shape.hidden, device=device).view(
         num_tokens, shape.hidden)
+
+
+def draw_ends_weights(shape: StageShape, *, seed: int, device="cpu", head_std: float = 0.02) -> Dict[str, torch.Tensor]:
+    """bf16 tensors of the pipeline's two ends: embedding table [vocab, hidden] ~ N(0, 1) (so the first
+    stage's input has the scale of `draw_hidden`), final norm gain ~ 1 + N(0, 0.02), output head
+    [vocab, hidden] ~ N(0, head_std)."""
+    v, h = shape.vocab, shape.hidden
+    return {
+        "embed": draw_normal_bf16(seed, STREAM_EMBED, v * h, device=device).view(v, h),
+        "final_norm": draw_normal_bf16(seed, STREAM_FINAL_NORM, h, std=0.02, mean=1.0, device=device),
+        "lm_head": draw_normal_bf16(seed, STREAM_LM_HEAD, v * h, std=head_std, device=device).view(v, h),
+    }
+
+
+def draw_token_ids(shape: StageShape, num_tokens: int, *, seed: int) -> List[int]:
+    return draw_int_uniform(seed, STREAM_TOKEN_IDS, num_tokens, 0, shape.vocab - 1)
 
 
 def kv_value_index(shape: StageShape, num_kv_blocks: int, layer, kv, block, slot, head, dim):

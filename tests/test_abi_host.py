@@ -39,14 +39,14 @@ def test_library_exports_every_declared_symbol(lib):
 
 
 def test_config_struct_matches_header_size(lib):
-    # uint32 + 6 int32 + 2 float + 2 int32 (+ 4 pad) + int64 + 4 int32
-    assert ctypes.sizeof(S.StageConfig) == 72
+    # uint32 + 6 int32 + 2 float + 2 int32 (+ 4 pad) + int64 + 5 int32 (+ 4 pad)
+    assert ctypes.sizeof(S.StageConfig) == 80
     assert S.stage_workspace_bytes(tiny_cfg()) > 0
 
 
 @pytest.mark.parametrize("bad", [dict(kv_block_size=32), dict(head_dim=96), dict(hidden=252), dict(num_q_heads=5),
                                  dict(num_q_heads=34, num_kv_heads=2), dict(rms_eps=0.0), dict(num_layers=0),
-                                 dict(activation_planes=3)])
+                                 dict(activation_planes=3), dict(vocab_size=1001), dict(vocab_size=32)])
 def test_unsupported_configs_are_rejected(lib, bad):
     with pytest.raises(StageError) as ei:
         cfg = tiny_cfg(**bad)
@@ -134,6 +134,15 @@ def test_kv_element_offset_is_a_bijection_with_the_documented_layout(lib):
         S.stage_kv_element_offset(cfg, 0, 3, 0, 0, 0)
 
 
+def test_output_head_adds_its_scratch_to_the_workspace(lib):
+    base = S.stage_workspace_bytes(tiny_cfg())
+    with_head = S.stage_workspace_bytes(tiny_cfg(vocab_size=1000))
+    # at least the normalised rows [S, H] bf16 and the fp32 logits [S, vocab]
+    assert with_head - base >= 8 * 256 * 2 + 8 * 1000 * 4
+
+
 def test_kernel_names(lib):
+    assert S.stage_kernel_name(S.KERNEL_CLASSES["gemm_head"]) == "gemm_bf16_kernel"
+    assert S.stage_kernel_name(S.KERNEL_CLASSES["head_argmax"]) == "argmax_rows_kernel"
     assert S.stage_kernel_name(S.KERNEL_CLASSES["attn_decode"]) == "attn_decode_kernel"
     assert S.stage_kernel_name(99) is None
