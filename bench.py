@@ -92,6 +92,8 @@ def main():
     ap.add_argument("--budget", type=int, default=256, help="token budget of the sweep workload")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--ends", action="store_true",
+                    help="also time the pipeline's two ends (embedding; final norm + output head + greedy choice)")
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel class (extra untimed steps)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy ten times and exit (reference for hardware counters)")
@@ -119,7 +121,7 @@ def main():
     work = algorithmic_work(shape, mb)
     kv_bytes = shape.num_layers * mb.num_kv_blocks * 16 * 4 * shape.num_kv_heads * shape.head_dim
     alias = kv_bytes + 2 * shape.params_per_layer * shape.num_layers > 250e9     # timing only: layers share one pool
-    st = make_stage(shape, mb, args.seed, alias_layers=alias)
+    st = make_stage(shape, mb, args.seed, alias_layers=alias, vocab_size=shape.vocab if args.ends else 0)
     hidden = synth.draw_hidden(shape, mb.num_tokens, seed=args.seed, device="cuda:0")
     out = torch.empty_like(hidden)
     n_dec = sum(1 for q in mb.q_lens if q == 1)
@@ -185,6 +187,27 @@ def main():
         torch.cuda.synchronize()
         result["breakdown_ms_per_step"] = {n: round(st.profile_read(n)[0] / reps, 5) for n in names}
         st.profile_enable([])
+
+    if args.ends:
+        # The pipeline's two ends, timed on their own after the stage (not part of `value`): token
+        # embedding of the micro-batch and final norm + vocabulary projection + greedy choice.
+        ends = synth.draw_ends_weights(shape, seed=args.seed, device="cuda:0")
+        ids = synth.draw_token_ids(shape, mb.num_tokens, seed=args.seed)
+        names = ["embed", "head_norm", "gemm_head", "head_argmax"]
+        reps = max(3, min(args.steps, 20))
+        for timed in (False, True):
+            if timed:
+                st.profile_enable(names)
+            for _ in range(reps):
+                st.embed(ends["embed"], ids, out=hidden)
+                st.head(out, mb.q_lens, ends["final_norm"], ends["lm_head"], want_logits=False)
+            torch.cuda.synchronize()
+        ms = {n: st.profile_read(n)[0] / reps for n in names}
+        st.profile_enable([])
+        head_bytes = 2 * shape.vocab * shape.hidden
+        result["ends"] = {"vocab": shape.vocab, "ms": {n: round(v, 5) for n, v in ms.items()},
+                          "head_gemm_GBps": round(head_bytes / (ms["gemm_head"] * 1e-3) / 1e9, 1),
+                          "head_gemm_algorithmic_bytes": head_bytes}
 
     if not args.no_cpu_baseline:
         sample = {"tiny": mb.num_seqs, "llama2-7b": 64, "qwen2-7b": 8, "llama3-70b": 4, "sweep": 4}[args.workload]
