@@ -6,3 +6,4 @@ from .stage_oracle import (  # noqa: F401
     decoder_layer, stage_forward, new_pool,
 )
 from .ends_oracle import embed_tokens, last_rows, head_logits, greedy_tokens  # noqa: F401
+from . import handoff_oracle  # noqa: F401
