@@ -38,6 +38,30 @@ def test_library_exports_every_declared_symbol(lib):
         assert hasattr(lib, n), f"{n} is declared in the header but not exported"
 
 
+def test_library_exports_every_handoff_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "molink_handoff.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(handoff_[a-z_]+)\s*\(", header))
+    assert {"handoff_plan", "handoff_sender_create", "handoff_sender_submit", "handoff_sender_destroy"} <= names
+    for n in sorted(names):
+        assert hasattr(lib, n), f"{n} is declared in the header but not exported"
+
+
+def test_handoff_plan_equals_the_model_on_random_layouts(lib):
+    from oracle import handoff_oracle as M
+    from paper_2507_05043_amd import handoff
+    rng = random.Random(0)
+    for _ in range(200):
+        q = [rng.choice([1, 1, 1, rng.randint(2, 50)]) for _ in range(rng.randint(1, 20))]
+        row, chunk = rng.choice([2, 512, 7168]), rng.choice([3, 100, 4096, 1 << 20])
+        d, p = M.split_payload(q, row, chunk)
+        assert handoff.plan(q, row, chunk) == d + p
+    with pytest.raises(handoff.HandoffError):
+        handoff.plan([3, 0], 8, 8)
+    with pytest.raises(handoff.HandoffError):
+        handoff.plan([3], 8, 0)
+
+
 def test_config_struct_matches_header_size(lib):
     # uint32 + 6 int32 + 2 float + 2 int32 (+ 4 pad) + int64 + 5 int32 (+ 4 pad)
     assert ctypes.sizeof(S.StageConfig) == 80
