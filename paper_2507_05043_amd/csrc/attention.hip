@@ -123,7 +123,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     const int pbv = v_bsel ? b1 : b0;
     const __bf16* vp = a.v_pool + (size_t)pbv * blk_stride + head_off + v_lane_off;
 #pragma unroll
-    for (int t = 0; t < DT; ++t) L.v[t] = load8(vp + (size_t)t * 16 * kKvBlock);
+    for (int t = 0; t < DT; ++t) L.v[t] = load8_stream(vp + (size_t)t * 16 * kKvBlock);
   };
 
   f32x4 acc[DT];

@@ -480,7 +480,7 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs p, int nv, in
         row = row < last ? row : last;
         const char* base = reinterpret_cast<const char*>(w + (size_t)(r0 + row) * p.k);
         __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(base + (real ? koff[i] : 0u)),
-                                         reinterpret_cast<uint32_t*>(stage + idx * 1024), 16, 0, 0);
+                                         reinterpret_cast<uint32_t*>(stage + idx * 1024), 16, 0, 2);   // aux 2 = nontemporal
       }
     };
     // Step u: after the wait only the 2 * NI loads of the two younger stages can still be in flight, so
