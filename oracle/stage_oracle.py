@@ -13,7 +13,9 @@ Llama-family models (section 5, "Models"), so the definition used here is the
 standard pre-norm Llama decoder block: RMSNorm, q/k/v projection, rotary
 embedding (half-split pairing), append to a paged KV cache, causal attention
 with grouped KV heads, output projection + residual, RMSNorm, SwiGLU MLP +
-residual.  No biases, no final norm.
+residual.  No biases, except an optional one on the q/k/v projection (the Qwen2
+family of the paper's model table has it; it is added before the rotation);
+no final norm.
 
 Numerics: every tensor is widened to `dtype` (float64 by default) on entry and
 nothing is rounded afterwards.  Library primitives used as steps: matmul,
@@ -136,6 +138,8 @@ def decoder_layer(shape: OracleShape, w: Dict[str, torch.Tensor], x: torch.Tenso
     wqkv = w["wqkv"].to(dt)
     a = rmsnorm(x, w["norm1"].to(dt), shape.rms_eps)
     qkv = a @ wqkv.T                                                  # weights are [out, in]
+    if w.get("bqkv") is not None:                                     # optional projection bias (Qwen2 family)
+        qkv = qkv + w["bqkv"].to(dt)
     q = qkv[:, : nq * d].reshape(t, nq, d)
     k = qkv[:, nq * d: (nq + nkv) * d].reshape(t, nkv, d)
     v = qkv[:, (nq + nkv) * d:].reshape(t, nkv, d)

@@ -256,7 +256,7 @@ STREAM_EMBED = 3
 STREAM_FINAL_NORM = 4
 STREAM_LM_HEAD = 5
 STREAM_TOKEN_IDS = 6
-STREAM_LAYER_BASE = 100   # + 10*layer + {0..6}
+STREAM_LAYER_BASE = 100   # + 10*layer + {0..6 weights, 7 q/k/v bias}
 _WEIGHT_KINDS = ("norm1", "wqkv", "wo", "norm2", "wgate", "wup", "wdown")
 
 
@@ -296,6 +296,11 @@ def draw_layer_weights(shape: StageShape, layer: int, *, seed: int, device="cpu"
             t = draw_normal_bf16(seed, stream, n, std=std, device=device)
         out[kind] = t.view(*shp)
     return out
+
+
+def draw_qkv_bias(shape: StageShape, layer: int, *, seed: int, device="cpu", std: float = 0.5) -> torch.Tensor:
+    """bf16 bias [qkv_out] of a layer's q/k/v projection ~ N(0, std) (for the stages that have one)."""
+    return draw_normal_bf16(seed, STREAM_LAYER_BASE + 10 * layer + 7, shape.qkv_out, std=std, device=device)
 
 
 def draw_hidden(shape: StageShape, num_tokens: int, *, seed: int, device="cpu") -> torch.Tensor:

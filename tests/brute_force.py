@@ -39,6 +39,8 @@ def layer_one_sequence(shape, w, rows, pos, cache_k, cache_v):
     for n, x in enumerate(rows):
         a = rmsnorm_row(x, w["norm1"], shape.rms_eps)
         qkv = matvec(w["wqkv"], a)
+        if w.get("bqkv") is not None:
+            qkv = [u + b for u, b in zip(qkv, w["bqkv"])]
         q = [rope_head(qkv[h * d:(h + 1) * d], pos[n], shape.rope_theta) for h in range(nq)]
         k = [rope_head(qkv[(nq + r) * d:(nq + r + 1) * d], pos[n], shape.rope_theta) for r in range(nkv)]
         v = [qkv[(nq + nkv + r) * d:(nq + nkv + r + 1) * d] for r in range(nkv)]

@@ -35,12 +35,15 @@ def run_oracle(shape, mb, seed=0, weight_std="fan_in", layers=None, hidden=None,
 
 # ---------------------------------------------------------------- brute force, whole block
 
-@pytest.mark.parametrize("nq,nkv", [(4, 2), (3, 3), (4, 1)])
-def test_whole_stage_matches_scalar_loops(nq, nkv):
+@pytest.mark.parametrize("nq,nkv,bias", [(4, 2, False), (3, 3, False), (4, 1, False), (4, 2, True)])
+def test_whole_stage_matches_scalar_loops(nq, nkv, bias):
     shape = small_shape(num_q_heads=nq, num_kv_heads=nkv, hidden=12, ffn=20, head_dim=4, kv_block_size=4)
     q_lens, ctx_lens = [5, 1, 3], [0, 6, 2]
     mb = synth.make_microbatch(q_lens, ctx_lens, seed=3, block=4)
     layers = draw_layers(shape, 3, "fan_in")
+    if bias:
+        for l, w in enumerate(layers):
+            w["bqkv"] = synth.draw_qkv_bias(shape, l, seed=3)
     hidden = synth.draw_hidden(shape, mb.num_tokens, seed=3)
     pool = oracle_pool(shape, mb, 3)
     pool0 = pool.clone()
@@ -64,6 +67,36 @@ def test_whole_stage_matches_scalar_loops(nq, nkv):
         row0 += q
     got = torch.tensor(got, dtype=F64)
     assert torch.allclose(out, got, rtol=1e-10, atol=1e-11), float((out - got).abs().max())
+
+
+def test_projection_bias_is_added_before_the_rotation():
+    """q, k, v of a biased layer are the rotation of (unbiased pre-rotation values + bias); v is not rotated."""
+    shape = small_shape(num_layers=1)
+    mb = synth.make_microbatch([4, 1], [0, 5], seed=2, block=shape.kv_block_size)
+    layers = draw_layers(shape, 2, "fan_in")
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=2)
+    bias = synth.draw_qkv_bias(shape, 0, seed=2).double()
+    nq, nkv, d = shape.num_q_heads, shape.num_kv_heads, shape.head_dim
+    osh = oracle_shape(shape)
+    taps0, taps1 = [], []
+    run_oracle(shape, mb, layers=layers, hidden=hidden, taps=taps0)
+    biased = [dict(layers[0], bqkv=bias)]
+    run_oracle(shape, mb, layers=biased, hidden=hidden, taps=taps1)
+    a = taps0[0]["a"]
+    assert torch.equal(a, taps1[0]["a"])
+    pre = a @ layers[0]["wqkv"].double().T + bias
+    pos = torch.as_tensor(mb.positions)
+    t = a.shape[0]
+    q = oracle.rope_rotate(pre[:, : nq * d].reshape(t, nq, d), pos, osh.rope_theta)
+    k = oracle.rope_rotate(pre[:, nq * d: (nq + nkv) * d].reshape(t, nkv, d), pos, osh.rope_theta)
+    assert torch.allclose(taps1[0]["q"], q, rtol=1e-12, atol=1e-12)
+    assert torch.allclose(taps1[0]["k"], k, rtol=1e-12, atol=1e-12)
+    assert torch.allclose(taps1[0]["v"], pre[:, (nq + nkv) * d:].reshape(t, nkv, d), rtol=1e-12, atol=1e-12)
+    assert not torch.allclose(taps1[0]["x"], taps0[0]["x"])
+    # a zero bias changes nothing, bit for bit
+    taps2 = []
+    run_oracle(shape, mb, layers=[dict(layers[0], bqkv=torch.zeros_like(bias))], hidden=hidden, taps=taps2)
+    assert torch.equal(taps2[0]["x"], taps0[0]["x"])
 
 
 # ---------------------------------------------------------------- attention
