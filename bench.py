@@ -121,7 +121,8 @@ def main():
     work = algorithmic_work(shape, mb)
     kv_bytes = shape.num_layers * mb.num_kv_blocks * 16 * 4 * shape.num_kv_heads * shape.head_dim
     alias = kv_bytes + 2 * shape.params_per_layer * shape.num_layers > 250e9     # timing only: layers share one pool
-    st = make_stage(shape, mb, args.seed, alias_layers=alias, vocab_size=shape.vocab if args.ends else 0)
+    st = make_stage(shape, mb, args.seed, alias_layers=alias, vocab_size=shape.vocab if args.ends else 0,
+                    qkv_bias=args.workload == "qwen2-7b")     # the Qwen2 family has a q/k/v bias
     hidden = synth.draw_hidden(shape, mb.num_tokens, seed=args.seed, device="cuda:0")
     out = torch.empty_like(hidden)
     n_dec = sum(1 for q in mb.q_lens if q == 1)

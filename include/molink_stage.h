@@ -84,6 +84,8 @@ typedef struct {
   const void *wgate;  /* [F][H] */
   const void *wup;    /* [F][H] */
   const void *wdown;  /* [H][F] */
+  const void *bqkv;   /* [(nq + 2 nkv) d] bias of the q/k/v projection, added before the rotation
+                         (the Qwen2 family has one), or NULL */
 } stage_layer_weights;
 
 typedef struct stage_handle stage_handle;

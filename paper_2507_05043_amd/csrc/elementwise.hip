@@ -102,6 +102,11 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs p) {
       b += *reinterpret_cast<const f32x4*>(q + k * p.plane_stride + 4);
     }
     v[0] = a[0]; v[1] = a[1]; v[2] = a[2]; v[3] = a[3]; v[4] = b[0]; v[5] = b[1]; v[6] = b[2]; v[7] = b[3];
+    if (p.bias) {
+      const bf16x8 bb = load8(p.bias + (q - src));
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] += bf16_to_f32(bb[e]);
+    }
   };
   if (u < rot_units) {
     const int head = u / cpr, c = u % cpr;

@@ -21,6 +21,7 @@ struct RopeAppendArgs {
                            // rotation); with planes > 1 the split-K partial sums, added here in plane order
   int planes;
   size_t plane_stride;     // floats between planes
+  const __bf16* bias;      // optional [(nq + 2 nkv) d] projection bias, added before the rotation
   __bf16* qkv;             // [T][(nq + 2 nkv) d] bf16: rotated q heads, rotated k heads, v heads
   __bf16* q_lo;            // optional [T][nq d]: bf16(q - bf16(q)), second plane of the rotated queries
   const float2* cos_sin;   // [T][d/2]

@@ -460,7 +460,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       }
       Timer t(st, stream, STAGE_K_ROPE_APPEND);
       RopeAppendArgs r{plan.partials ? splitk : qkv_f32, plan.partials ? plan.splits : 1, (size_t)T * d.qkv_out,
-                       qkv, q_lo, cos_sin, d_slots, k_pool, v_pool, T, d.nq, d.nkv, d.d};
+                       (const __bf16*)w.bqkv, qkv, q_lo, cos_sin, d_slots, k_pool, v_pool, T, d.nq, d.nkv, d.d};
       HIP_TRY(launch_rope_append(r, stream));
     }
     if (tap && taps->tap_qkv)
@@ -585,6 +585,7 @@ int stage_init(const stage_config* cfg, const stage_layer_weights* layers, void*
     const void* ptrs[7] = {w.norm1, w.wqkv, w.wo, w.norm2, w.wgate, w.wup, w.wdown};
     for (const void* p : ptrs)
       if ((uintptr_t)p % 16) return fail(STAGE_ERR_CONFIG, "layer %d has a weight pointer that is not 16-byte aligned", l);
+    if ((uintptr_t)w.bqkv % 16) return fail(STAGE_ERR_CONFIG, "layer %d: bqkv is not 16-byte aligned", l);
   }
   if ((uintptr_t)kv_pool % 256 || (uintptr_t)workspace % 256)
     return fail(STAGE_ERR_CONFIG, "kv_pool and workspace must be 256-byte aligned");

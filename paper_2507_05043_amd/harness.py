@@ -11,10 +11,14 @@ from .stage import Stage, make_config
 
 def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_std=None,
                max_tokens: Optional[int] = None, alias_layers: bool = False, fill_kv: bool = True,
-               device: str = "cuda:0", activation_planes: int = 0, vocab_size: int = 0) -> Stage:
+               device: str = "cuda:0", activation_planes: int = 0, vocab_size: int = 0,
+               qkv_bias: bool = False) -> Stage:
     """Draw the stage's weights on the device, size the pool and workspace for `mb`, fill the cache."""
     layers = [synth.draw_layer_weights(shape, l, seed=seed, device=device, weight_std=weight_std)
               for l in range(shape.num_layers)]
+    if qkv_bias:
+        for l, w in enumerate(layers):
+            w["bqkv"] = synth.draw_qkv_bias(shape, l, seed=seed, device=device)
     cfg = make_config(num_layers=shape.num_layers, hidden=shape.hidden, num_q_heads=shape.num_q_heads,
                       num_kv_heads=shape.num_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn,
                       rms_eps=shape.rms_eps, rope_theta=shape.rope_theta, num_kv_blocks=mb.num_kv_blocks,

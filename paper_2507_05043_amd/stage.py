@@ -42,7 +42,7 @@ class StageConfig(ctypes.Structure):
 
 
 class StageLayerWeights(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_void_p) for n in ("norm1", "wqkv", "wo", "norm2", "wgate", "wup", "wdown")]
+    _fields_ = [(n, ctypes.c_void_p) for n in ("norm1", "wqkv", "wo", "norm2", "wgate", "wup", "wdown", "bqkv")]
 
 
 class StageTaps(ctypes.Structure):
@@ -165,6 +165,8 @@ class Stage:
         arr = (StageLayerWeights * cfg.num_layers)()
         for l, w in enumerate(self.layers):
             for name, _ in StageLayerWeights._fields_:
+                if name == "bqkv" and w.get(name) is None:     # the only optional tensor
+                    continue
                 t = w[name]
                 if t.dtype != torch.bfloat16 or not t.is_contiguous() or t.device != self.device:
                     raise ValueError(f"layer {l} {name}: need a contiguous bf16 tensor on {self.device}")

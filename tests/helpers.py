@@ -15,9 +15,14 @@ def oracle_shape(shape: synth.StageShape) -> oracle.OracleShape:
                               shape.kv_block_size)
 
 
-def draw_layers(shape: synth.StageShape, seed: int, weight_std=None, device="cpu") -> List[Dict[str, torch.Tensor]]:
-    return [synth.draw_layer_weights(shape, l, seed=seed, device=device, weight_std=weight_std)
-            for l in range(shape.num_layers)]
+def draw_layers(shape: synth.StageShape, seed: int, weight_std=None, device="cpu",
+                qkv_bias: bool = False) -> List[Dict[str, torch.Tensor]]:
+    layers = [synth.draw_layer_weights(shape, l, seed=seed, device=device, weight_std=weight_std)
+              for l in range(shape.num_layers)]
+    if qkv_bias:
+        for l, w in enumerate(layers):
+            w["bqkv"] = synth.draw_qkv_bias(shape, l, seed=seed, device=device)
+    return layers
 
 
 def oracle_pool(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, dtype=torch.float64) -> torch.Tensor:

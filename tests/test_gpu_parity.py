@@ -14,12 +14,13 @@ def _shape(name, L, H_, nq, nkv, d, F, theta=1e4):
     return synth.StageShape(name, L, H_, nq, nkv, d, F, rope_theta=theta)
 
 
-def full_parity(shape, mb, seed, weight_std, taps=True, check_kv=True):
+def full_parity(shape, mb, seed, weight_std, taps=True, check_kv=True, qkv_bias=False, activation_planes=0):
     print(f"[case] {shape.name} T={mb.num_tokens} S={mb.num_seqs} q={mb.q_lens[:6]} ctx={mb.ctx_lens[:6]} "
-          f"std={weight_std} seed={seed}", flush=True)
-    st = H.make_stage(shape, mb, seed, weight_std)
+          f"std={weight_std} seed={seed} bias={qkv_bias} planes={activation_planes}", flush=True)
+    st = H.make_stage(shape, mb, seed, weight_std, qkv_bias=qkv_bias, activation_planes=activation_planes)
     before = H.snapshot_pool(st, shape, mb) if check_kv else None
-    ref, ref_slots, ref_pool, otaps = H.run_oracle(shape, mb, seed, weight_std, want_taps=True)
+    ref, ref_slots, ref_pool, otaps = H.run_oracle(shape, mb, seed, weight_std, want_taps=True,
+                                                   layers=draw_layers(shape, seed, weight_std, qkv_bias=qkv_bias))
     out, slots = H.run_gpu(st, shape, mb, seed)
     assert slots == ref_slots                                   # bit-exact slot indexing
     stats = H.check_output(out, ref)
@@ -55,6 +56,16 @@ def test_generator_same_bits_on_gpu_and_cpu():
 def test_tiny_stage(weight_std):
     shape, mb = synth.workload("tiny", seed=0)
     full_parity(shape, mb, 0, weight_std)
+
+
+@pytest.mark.parametrize("planes", [1, 2])
+def test_projection_bias(planes):
+    """Optional q/k/v bias (Qwen2 family), in both activation modes, small and grouped-head d=128 shapes."""
+    shape, mb = synth.workload("tiny", seed=0)
+    full_parity(shape, mb, 0, "fan_in", qkv_bias=True, activation_planes=planes)
+    gqa = _shape("gqa-d128-bias", 2, 512, 8, 2, 128, 1024)
+    mb2 = synth.make_microbatch([70, 1, 1, 1, 9], [0, 33, 200, 15, 40], seed=7)
+    full_parity(gqa, mb2, 7, "fan_in", qkv_bias=True, activation_planes=planes)
 
 
 @pytest.mark.parametrize("case", [
@@ -178,6 +189,8 @@ def _layer0_reference(shape, layers0, hidden, mb):
     w = layers0
     a = oracle.rmsnorm(hidden.to(dt), w["norm1"].to(dt), shape.rms_eps)
     qkv = a @ w["wqkv"].to(dt).T
+    if w.get("bqkv") is not None:
+        qkv = qkv + w["bqkv"].to(dt)
     nq, nkv, d = shape.num_q_heads, shape.num_kv_heads, shape.head_dim
     t = hidden.shape[0]
     pos = mb.positions.to(torch.int64)
@@ -190,15 +203,18 @@ def _layer0_reference(shape, layers0, hidden, mb):
 def test_qwen2_7b_stage_at_full_size():
     """Mixed micro-batch at its real shape (2048-token prefill chunk + 128 decode tokens, 7 layers).
     Whole-stage output: the first 320 rows of the chunk (causal, so exact on their own) and 8 decode
-    sequences, row by row.  Layer 0 taps: q/k/v of every row, attention of late prefill rows."""
+    sequences, row by row.  Layer 0 taps: q/k/v of every row, attention of late prefill rows.
+    The q/k/v projections carry a bias, as in the Qwen2 family."""
     shape, mb = synth.workload("qwen2-7b", seed=0)
     print(f"[case] {shape.name} T={mb.num_tokens} blocks={mb.num_kv_blocks}", flush=True)
-    st = H.make_stage(shape, mb, 0)
+    st = H.make_stage(shape, mb, 0, qkv_bias=True)
     out, slots, taps = H.run_gpu(st, shape, mb, 0, taps_layer=0)
     assert slots == oracle.slot_mapping(mb.q_lens, mb.ctx_lens, mb.block_tables, 16)
     assert torch.isfinite(out.float()).all()
     layers = [{k: v.cpu() for k, v in synth.draw_layer_weights(shape, l, seed=0, device="cuda:0").items()}
               for l in range(shape.num_layers)]
+    for l, w in enumerate(layers):
+        w["bqkv"] = synth.draw_qkv_bias(shape, l, seed=0)
     hidden = synth.draw_hidden(shape, mb.num_tokens, seed=0)
     print("  inputs ready", flush=True)
 
