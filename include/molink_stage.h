@@ -69,8 +69,8 @@ typedef struct {
                                   queries) is carried as two bf16 planes, value = hi + lo, both multiplied into
                                   the same fp32 accumulators: twice the MFMA work of the projections for
                                   activations that are effectively 16-bit.  Automatic = 2 for stages deeper than
-                                  10 layers, whose accumulated bf16 rounding error would otherwise exceed
-                                  1e-2 relative on the output, else 1. */
+                                  8 layers, whose accumulated bf16 rounding error would otherwise come close
+                                  to or exceed 1e-2 relative on the output, else 1. */
   int32_t vocab_size;          /* 0, or the vocabulary size (multiple of 8, >= 64) of the output head this
                                   stage may run with stage_head (sizes the workspace for it) */
 } stage_config;
