@@ -134,6 +134,52 @@ def test_two_runs_are_bitwise_identical():
     st.close()
 
 
+def test_one_handle_serves_different_micro_batches_in_turn():
+    """A serving loop reuses one stage for micro-batches of different sizes and mixes: nothing of a
+    previous call (workspace, metadata, split counts) may leak into the next."""
+    shape = _shape("reuse-d64", 2, 256, 4, 2, 64, 688)
+    batches = [
+        synth.make_microbatch([40, 1, 1, 1, 1, 1], [0, 77, 20, 130, 5, 64], seed=11),      # mixed
+        synth.make_microbatch([1] * 70, [17 + 3 * i for i in range(70)], seed=12),          # decode only, > 64 rows
+        synth.make_microbatch([1, 1], [300, 2], seed=13),                                    # two rows
+        synth.make_microbatch([150], [16], seed=14),                                         # one long chunk with a prefix
+    ]
+    for i, mb in enumerate(batches):
+        st = H.make_stage(shape, mb, 20 + i, "fan_in")
+        out, _ = H.run_gpu(st, shape, mb, 20 + i)
+        ref, _, _, _ = H.run_oracle(shape, mb, 20 + i, "fan_in")
+        H.check_output(out, ref, f"batch {i} on a fresh stage")
+        st.close()
+    big_tokens = max(mb.num_tokens for mb in batches)
+    # one handle, one set of weights (seed 20), the batches in turn: every output equals, bit for bit, that of
+    # a fresh stage with the same weights
+    seed = 20
+    cap = synth.make_microbatch([1] * 70, [300] * 70, seed=99)      # capacity: 70 sequences, 19 blocks each
+    one = H.make_stage(shape, cap, seed, "fan_in", max_tokens=big_tokens, fill_kv=False)
+    for i in [0, 1, 2, 3, 1, 0]:
+        mb = batches[i]
+        if mb.num_kv_blocks > cap.num_kv_blocks or mb.max_blocks_per_seq > cap.max_blocks_per_seq:
+            continue
+        ref_stage = H.make_stage(shape, mb, seed, "fan_in")
+        want, _ = H.run_gpu(ref_stage, shape, mb, seed)
+        ref_stage.close()
+        # same cached values at the same physical blocks: copy the reference pool's drawing into the big pool
+        one.kv_pool.view(torch.bfloat16).fill_(float("nan"))
+        blocks = torch.arange(mb.num_kv_blocks, device="cuda:0")
+        tmp = H.make_stage(shape, mb, seed, "fan_in")
+        for l in range(shape.num_layers):
+            for kv in (0, 1):
+                one.write_kv_blocks(l, kv, blocks, tmp.read_kv_blocks(l, kv, blocks))
+        tmp.close()
+        tables = torch.full((mb.num_seqs, cap.max_blocks_per_seq), -1, dtype=torch.int32)
+        tables[:, : mb.block_tables.shape[1]] = mb.block_tables
+        hidden = synth.draw_hidden(shape, mb.num_tokens, seed=seed, device="cuda:0")
+        got = one.forward(hidden, mb.positions, mb.q_lens, mb.ctx_lens, tables)
+        torch.cuda.synchronize()
+        assert torch.equal(got.view(torch.int16), want.view(torch.int16)), f"batch {i} on the shared handle"
+    one.close()
+
+
 def test_invalid_batches_are_rejected_and_leave_the_pool_untouched():
     shape, mb = synth.workload("tiny", seed=0)
     st = H.make_stage(shape, mb, 0)
