@@ -14,6 +14,8 @@
 #include "attention.hpp"
 #include "common.hpp"
 
+#include <type_traits>
+
 namespace molink {
 
 namespace {
@@ -254,39 +256,62 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const Decod
 }
 
 // ------------------------------------------------------------------------------------------------
-// Prefill: one wave per 32 query columns of one (sequence, KV head); a column is a (token, head in
-// group) pair, column = token * g + head_in_group, so grouped heads share every K/V read.  32x32x16
-// MFMA; a step is 32 keys (two blocks).  Row m of the key tile is (block m/16, slot
+// Prefill: a workgroup of four waves takes 128 consecutive query columns of one (sequence, KV head);
+// a column is a (token, head in group) pair, column = token * g + head_in_group, so grouped heads
+// share every K/V read; wave w owns columns 32w .. 32w+31.  The four waves need the same keys, so a
+// step's K and V tiles (32 keys = two blocks) are fetched once per workgroup, straight into LDS
+// (global_load_lds), four stages deep: three steps are in flight while one is multiplied, which is
+// what hides the memory latency (a wave that loads its own operands into registers can only run one
+// step ahead).  32x32x16 MFMA.  Row m of the key tile is (block m/16, slot
 // 8*((m/4)%2) + 4*((m/8)%2) + m%4): accumulator registers 0..7 of lane group G = lane/32 are then
-// slots 8G..8G+7 of the first block, registers 8..15 the same slots of the second block.
+// slots 8G..8G+7 of the first block, registers 8..15 the same slots of the second block, i.e. the
+// S^T accumulators are the P^T operand of the PV product as they stand.
+//
+// LDS stage: K tile, 32 rows of 2D bytes in MFMA row order, 16-byte chunk c of row m stored at
+// position c ^ (m & 7) (128-bit fragment reads of 8 consecutive rows then hit 8 different bank
+// groups); then the V^T tiles as [block][slot half][d][16 bytes], so that the lanes of a fragment
+// read (32 consecutive d, one half) are contiguous.  Both arrangements are made by choosing which 16
+// bytes each lane of a load instruction fetches.
 // ------------------------------------------------------------------------------------------------
 template <int D, bool QLO>
 __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const PrefillTile* __restrict__ tiles,
                                                            int num_tiles) {
-  constexpr int KS = D / 16;   // MFMA k-steps of the QK product
-  constexpr int DT = D / 32;   // 32-row tiles of O^T
+  constexpr int KS = D / 16;                 // MFMA k-steps of the QK product
+  constexpr int DT = D / 32;                 // 32-row tiles of O^T
+  constexpr int NST = 4;                     // LDS stages
+  constexpr int K_BYTES = 32 * D * 2;        // K tile
+  constexpr int STAGE_BYTES = 2 * K_BYTES;   // + V^T tiles of the same size
+  constexpr int NI = STAGE_BYTES / 1024 / 4; // load instructions per wave per stage
+  constexpr int CPR = D / 8;                 // 16-byte chunks per K row
+  using Lds = LdsStages<STAGE_BYTES>;
+
   const int lane = threadIdx.x & 63;
-  const int tile_id = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6));
-  if (tile_id >= num_tiles) return;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int tile_id = blockIdx.x;
   const int r = blockIdx.y;
   const int g = a.nq / a.nkv;
   const int row0 = __builtin_amdgcn_readfirstlane(tiles[tile_id].row0);
   const int q_len = __builtin_amdgcn_readfirstlane(tiles[tile_id].q_len);
   const int ctx = __builtin_amdgcn_readfirstlane(tiles[tile_id].ctx);
   const int bt_off = __builtin_amdgcn_readfirstlane(tiles[tile_id].bt_off);
-  const int col0 = __builtin_amdgcn_readfirstlane(tiles[tile_id].col0);
-  const int32_t* bt = a.bt_flat + bt_off;
+  const int tile_col0 = __builtin_amdgcn_readfirstlane(tiles[tile_id].col0);
+  // The block table is read through the constant address space (nothing writes it during the kernel): the
+  // reads become scalar loads, which do not queue behind the tile loads in flight.
+  typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+  const const_i32_ptr bt = (const_i32_ptr)(a.bt_flat + bt_off);
   const int total_keys = ctx + q_len;
   const int last_block = (total_keys - 1) / kKvBlock;
   const int ncols = q_len * g;
 
   const int col = lane & 31, grp = lane >> 5;
-  const int my_col = min(col0 + col, ncols - 1);           // padding columns repeat the last real one
+  const int col0 = tile_col0 + 32 * wave;                      // this wave's first column
+  const bool wave_active = col0 < ncols;
+  const int my_col = min(col0 + col, ncols - 1);               // padding columns repeat the last real one
   const int tok = my_col / g, hg = my_col % g;
-  const int limit = ctx + tok;                              // last key this column may see
-  const int last_col = min(col0 + 31, ncols - 1);
-  const int max_limit = ctx + last_col / g;                 // wave-uniform loop bound
-  const int nsteps = max_limit / 32 + 1;
+  const int limit = ctx + tok;                                  // last key this column may see
+  const int wave_steps = (ctx + min(col0 + 31, ncols - 1) / g) / 32 + 1;   // steps with a key visible to this wave
+  const int wave_min_limit = ctx + min(col0, ncols - 1) / g;               // smallest limit among this wave's columns
+  const int nsteps = (ctx + min(tile_col0 + 127, ncols - 1) / g) / 32 + 1; // ... to the workgroup
   const int ldq = (a.nq + 2 * a.nkv) * D;
 
   bf16x8 qf[KS], qf_lo[QLO ? KS : 1];
@@ -301,23 +326,47 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
     }
   }
 
-  const int k_bsel = col >> 4;
-  const int k_slot = 8 * ((col >> 2) & 1) + 4 * ((col >> 3) & 1) + (col & 3);
-  const size_t k_lane_off = (size_t)k_slot * D + grp * 8;
-  const size_t v_lane_off = (size_t)col * kKvBlock + 8 * grp;
-  const size_t blk_stride = (size_t)a.nkv * kKvBlock * D;
+  // ---- what this lane fetches for load instruction i of its wave (instruction id j = 4 i + wave;
+  // the first K_BYTES / 1024 instructions fill the K tile, the rest the V^T tiles)
+  const size_t blk_stride = (size_t)a.nkv * kKvBlock * D;     // elements per block (all heads)
   const size_t head_off = (size_t)r * kKvBlock * D;
-
-  auto block_id = [&](int step, int sel) -> int {
-    int lb = 2 * step + sel;
-    lb = lb < last_block ? lb : last_block;
-    return bt[lb];
-  };
-  auto load_k = [&](bf16x8* kf, int b0, int b1) {
-    const int pb = k_bsel ? b1 : b0;
-    const __bf16* kp = a.k_pool + (size_t)pb * blk_stride + head_off + k_lane_off;
+  // An instruction never straddles two blocks (4 or 8 K rows, 64 of the 2 D positions of a V block), so
+  // the block is chosen per instruction (scalar) and only the offset inside the block is per lane.
+  uint32_t ld_off[NI];     // byte offset of this lane's 16 bytes inside the (block, head) region
 #pragma unroll
-    for (int kk = 0; kk < KS; ++kk) kf[kk] = load8(kp + kk * 16);
+  for (int i = 0; i < NI; ++i) {
+    const int j = 4 * i + wave;
+    if (j < K_BYTES / 1024) {
+      const int pos = j * 64 + lane;                 // 16-byte position in the K tile
+      const int m = pos / CPR, p = pos % CPR;        // tile row, position in the row
+      const int chunk = p ^ (m & 7);
+      const int slot = 8 * ((m >> 2) & 1) + 4 * ((m >> 3) & 1) + (m & 3);
+      ld_off[i] = (uint32_t)(slot * D + chunk * 8) * 2u;
+    } else {
+      const int pos = (j - K_BYTES / 1024) * 64 + lane;   // 16-byte position in the V part: [block][half][d]
+      const int d = pos % D, half = (pos / D) & 1;
+      ld_off[i] = (uint32_t)(d * kKvBlock + half * 8) * 2u;
+    }
+  }
+  // Every step issues the same loads (block indices past the sequence are clamped to its last block),
+  // so the wait counts below hold without control flow around the loads.
+  auto fetch = [&](auto stage_c, int step) {
+    constexpr int S = decltype(stage_c)::value;
+    int lb0 = 2 * step, lb1 = 2 * step + 1;
+    lb0 = lb0 < last_block ? lb0 : last_block;
+    lb1 = lb1 < last_block ? lb1 : last_block;
+    const int b0 = bt[lb0], b1 = bt[lb1];
+    char* stage = Lds::template get<S>();
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int j = 4 * i + wave;                                    // uniform
+      const bool is_k = j < K_BYTES / 1024;
+      const int second = is_k ? (j * 64 / CPR) >> 4 : ((j - K_BYTES / 1024) * 64) / (2 * D);
+      const int pb = second ? b1 : b0;
+      const char* base = reinterpret_cast<const char*>((is_k ? a.k_pool : a.v_pool) + (size_t)pb * blk_stride + head_off);
+      __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(base + ld_off[i]),
+                                       reinterpret_cast<uint32_t*>(stage + j * 1024), 16, 0, 0);
+    }
   };
 
   f32x16 acc[DT];
@@ -327,81 +376,100 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
     for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  auto process = [&](const bf16x8* kf, int step, int b0, int b1) {
-    bf16x8 vf[DT][2];
-    {
-      const __bf16* vp0 = a.v_pool + (size_t)b0 * blk_stride + head_off + v_lane_off;
-      const __bf16* vp1 = a.v_pool + (size_t)b1 * blk_stride + head_off + v_lane_off;
-#pragma unroll
-      for (int t = 0; t < DT; ++t) {
-        vf[t][0] = load8(vp0 + (size_t)t * 32 * kKvBlock);
-        vf[t][1] = load8(vp1 + (size_t)t * 32 * kKvBlock);
-      }
-    }
-    f32x16 s;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) s[e] = 0.f;
+  // fragment addresses: K row m = lane % 32, chunk 2 kk + grp at position (2 kk + grp) ^ (m & 7);
+  // V^T row d = 32 t + lane % 32 of half grp of block b
+  const int k_row_off = col * (2 * D);
+  const int v_frag_off = K_BYTES + (grp * D + col) * 16;
+
+  auto process = [&](auto stage_c, int step) {
+    constexpr int S = decltype(stage_c)::value;
+    if (!wave_active || step >= wave_steps) return;          // nothing visible to this wave's columns
+    const char* stage = Lds::template get<S>();
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f32x16 s = zero16;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s, 0, 0, 0);
-      if constexpr (QLO) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf_lo[kk], s, 0, 0, 0);
+      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(stage + k_row_off + (((2 * kk + grp) ^ (col & 7)) * 16));
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
+      if constexpr (QLO) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf_lo[kk], s, 0, 0, 0);
     }
     // register e of this lane is key 32*step + 16*(e/8) + 8*grp + e%8
     const int key_base = 32 * step + 8 * grp;
     float sv[16];
-    float m_tile = -INFINITY;
+    float raw_max = -INFINITY;                               // maximum of the unscaled scores (the scale is positive)
+    if (32 * step + 31 <= wave_min_limit) {                  // wave-uniform: every key of the step is visible to every column
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const int key = key_base + 16 * (e / 8) + (e % 8);
-      sv[e] = (key <= limit) ? s[e] * a.scale_log2e : -INFINITY;
-      m_tile = fmaxf(m_tile, sv[e]);
+      for (int e = 0; e < 16; ++e) {
+        sv[e] = s[e];
+        raw_max = fmaxf(raw_max, sv[e]);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int key = key_base + 16 * (e / 8) + (e % 8);
+        sv[e] = (key <= limit) ? s[e] : -INFINITY;
+        raw_max = fmaxf(raw_max, sv[e]);
+      }
     }
-    m_tile = fmaxf(m_tile, __shfl_xor(m_tile, 32, 64));
-    const float m_new = fmaxf(m_run, m_tile);               // finite from step 0 on: key 0 is visible to all
-    const float alpha = fast_exp2(m_run - m_new);
+    raw_max = fmaxf(raw_max, __shfl_xor(raw_max, 32, 64));
+    const float m_new = fmaxf(m_run, raw_max * a.scale_log2e);   // finite from step 0 on: key 0 is visible to all
+    // The reference m_run of the exponentials need not be the exact running maximum: softmax does not
+    // depend on it, it only has to keep exp2(score - m_run) in range.  It is moved (and the accumulators
+    // rescaled, 16 DT multiplications per lane) only when some column's maximum has grown by more than
+    // 2^8 since; until then probabilities up to 256 are accumulated as they are.
+    const bool rescale = __builtin_amdgcn_ballot_w64(m_new > m_run + 8.0f) != 0;
+    if (rescale) {
+      const float alpha = fast_exp2(m_run - m_new);
+      l_run *= alpha;
+#pragma unroll
+      for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[t][e] *= alpha;
+      m_run = m_new;
+    }
     float psum = 0.f;
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-      sv[e] = fast_exp2(sv[e] - m_new);
+      sv[e] = fast_exp2(__builtin_fmaf(sv[e], a.scale_log2e, -m_run));    // (-inf) * scale - m = -inf -> 0
       psum += sv[e];
     }
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
+    l_run += psum;
     const bf16x8 p0 = pack8(sv), p1 = pack8(sv + 8);
     const bool tail = 32 * step + 32 > total_keys;            // wave-uniform: slots past the sequence end
     const int nv0 = total_keys - key_base, nv1 = nv0 - 16;
 #pragma unroll
     for (int t = 0; t < DT; ++t) {
-      bf16x8 v0 = vf[t][0], v1 = vf[t][1];
+      bf16x8 v0 = *reinterpret_cast<const bf16x8*>(stage + v_frag_off + t * 512);
+      bf16x8 v1 = *reinterpret_cast<const bf16x8*>(stage + v_frag_off + 2 * D * 16 + t * 512);
       if (tail) {
         v0 = zero_tail(v0, nv0 < 0 ? 0 : nv0);
         v1 = zero_tail(v1, nv1 < 0 ? 0 : nv1);
       }
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[t][e] *= alpha;
       acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0, p0, acc[t], 0, 0, 0);
       acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1, p1, acc[t], 0, 0, 0);
     }
   };
 
-  bf16x8 kbuf0[KS], kbuf1[KS];
-  int b0 = block_id(0, 0), b1 = block_id(0, 1);
-  int n0 = block_id(1, 0), n1 = block_id(1, 1);
-  load_k(kbuf0, b0, b1);
-  for (int step = 0; step < nsteps; step += 2) {
-    const bool has1 = step + 1 < nsteps;
-    if (has1) load_k(kbuf1, n0, n1);
-    const int f0 = block_id(step + 2, 0), f1 = block_id(step + 2, 1);
-    process(kbuf0, step, b0, b1);
-    if (has1) {
-      const bool has2 = step + 2 < nsteps;
-      if (has2) load_k(kbuf0, f0, f1);
-      const int h0 = block_id(step + 3, 0), h1 = block_id(step + 3, 1);
-      process(kbuf1, step + 1, n0, n1);
-      b0 = f0; b1 = f1;
-      n0 = h0; n1 = h1;
-    }
+  // Step u: after the wait only the loads of the two younger stages can still be in flight, so this
+  // wave's part of stage u % 4 has landed; after the barrier everybody's has, and everybody is done with
+  // stage (u - 1) % 4, which is refilled with step u + 3.
+  auto step_fn = [&](auto stage_c, int u) {
+    constexpr int S = decltype(stage_c)::value;
+    wait_vmcnt<2 * NI>();
+    pipeline_barrier();
+    fetch(std::integral_constant<int, (S + NST - 1) % NST>{}, u + NST - 1);
+    process(stage_c, u);
+  };
+  fetch(std::integral_constant<int, 0>{}, 0);
+  fetch(std::integral_constant<int, 1>{}, 1);
+  fetch(std::integral_constant<int, 2>{}, 2);
+  for (int u = 0; u < nsteps; u += NST) {
+    step_fn(std::integral_constant<int, 0>{}, u);
+    step_fn(std::integral_constant<int, 1>{}, u + 1);
+    step_fn(std::integral_constant<int, 2>{}, u + 2);
+    step_fn(std::integral_constant<int, 3>{}, u + 3);
   }
+  wait_vmcnt<0>();   // nothing may still be writing LDS when the workgroup ends
 
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   if (col0 + col < ncols) {
@@ -428,7 +496,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
 }  // namespace
 
 hipError_t launch_attn_prefill(const AttnArgs& a, const PrefillTile* tiles, int num_tiles, hipStream_t stream) {
-  dim3 grid((num_tiles + 3) / 4, a.nkv), block(256);
+  dim3 grid(num_tiles, a.nkv), block(256);
   if (a.head_dim == 128) {
     if (a.q_lo) hipLaunchKernelGGL((attn_prefill_kernel<128, true>), grid, block, 0, stream, a, tiles, num_tiles);
     else hipLaunchKernelGGL((attn_prefill_kernel<128, false>), grid, block, 0, stream, a, tiles, num_tiles);

@@ -23,7 +23,7 @@ struct DecodeToken {
   int32_t pad;
 };
 
-// One unit of prefill work: 32 query columns (token, head-in-group pairs) of one sequence.
+// One unit of prefill work (one workgroup): 128 query columns (token, head-in-group pairs) of one sequence.
 struct PrefillTile {
   int32_t row0;       // row of the chunk's first token
   int32_t q_len;      // tokens in the chunk

@@ -44,33 +44,6 @@ __device__ __forceinline__ void sched_step() {
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 
-// LDS stages live in separate arrays so that the compiler can tell a stage being filled from the
-// stage being read (a single array indexed by the stage would force every LDS read to wait for all
-// loads in flight).
-template <int BYTES> struct LdsStages {
-  template <int S> static __device__ __forceinline__ char* get() {
-    __shared__ __attribute__((aligned(1024))) char stage[BYTES];
-    return stage;
-  }
-};
-
-// s_waitcnt on the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and 15:14).
-template <int N> __device__ __forceinline__ void wait_vmcnt() {
-  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-  __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0070 | 0x0F00);
-}
-
-// Workgroup barrier without the memory fence of __syncthreads(): that fence would wait for every load
-// in flight, including the tiles being prefetched into other LDS stages.  The caller has already
-// waited for exactly the loads the other waves are about to read; this only drains the wave's own LDS
-// operations and keeps the compiler from moving memory accesses across the barrier.
-__device__ __forceinline__ void pipeline_barrier() {
-  asm volatile("" ::: "memory");
-  __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0), vmcnt and expcnt untouched
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
-}
-
 // Workgroup of 4 waves (2 x 2); wave tile (BM/2) x (BN/2) made of 32x32 MFMA tiles; K tile of 64.
 //
 // Tiles go from global memory straight into LDS (global_load_lds_dwordx4: each lane's 16 bytes land at

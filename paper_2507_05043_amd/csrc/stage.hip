@@ -182,7 +182,7 @@ int validate_batch(const stage_config& c, int32_t T, const int32_t* positions, i
     sum_q += q;
     bc.total_blocks += nb;
     if (q == 1) { ++bc.n_decode; bc.decode_keys += tot; }
-    else bc.n_tiles += (int)(((int64_t)q * g + 31) / 32);
+    else bc.n_tiles += (int)(((int64_t)q * g + 127) / 128);
   }
   if (sum_q != T) return fail(STAGE_ERR_BATCH, "sum(q_lens) = %lld != num_tokens = %d", (long long)sum_q, T);
   for (int t = 0; t < T; ++t)
@@ -387,7 +387,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
         }
       } else {
         const int ncols = q * d.g;
-        for (int c0 = 0; c0 < ncols; c0 += 32) h_tiles[tl++] = PrefillTile{row, q, cx, bt_off, c0, {0, 0, 0}};
+        for (int c0 = 0; c0 < ncols; c0 += 128) h_tiles[tl++] = PrefillTile{row, q, cx, bt_off, c0, {0, 0, 0}};
       }
       row += q;
       bt_off += nb;
@@ -398,6 +398,13 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
     std::stable_sort(h_items, h_items + n_items, [](const DecodeItem& x, const DecodeItem& y) {
       return (x.key_end - x.key_begin) > (y.key_end - y.key_begin);
     });
+  // prefill tiles that see the most keys first (a late tile of a long chunk runs twice as long as an early one)
+  if (n_tiles > 1) {
+    const int gq = d.g;
+    std::stable_sort(h_tiles, h_tiles + n_tiles, [gq](const PrefillTile& x, const PrefillTile& y) {
+      return x.ctx + (x.col0 + 127) / gq > y.ctx + (y.col0 + 127) / gq;
+    });
+  }
   if (slot_mapping_out) memcpy(slot_mapping_out, h_slots, (size_t)T * 8);
 
   // ---- enqueue
