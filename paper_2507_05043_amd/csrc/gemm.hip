@@ -9,9 +9,10 @@
 // Workgroup ids are remapped so that consecutive logical tiles share an XCD: the M tiles that reuse
 // one weight tile run next to each other on one L2.
 //
-// Small-M shapes (decode micro-batches) do not have enough output tiles to fill 256 CUs, so the K
-// dimension is split across workgroups; the partial sums go to fp32 scratch and a second kernel adds
-// them in a fixed order (deterministic) and applies the epilogue.
+// Shapes without enough output tiles to fill 256 CUs split the K dimension across workgroups; the
+// partial sums go to fp32 scratch and a second kernel adds them in a fixed order (deterministic) and
+// applies the epilogue.  Micro-batches of at most 64 rows (decode) have a kernel of their own,
+// gemm_skinny_kernel below, built around streaming the weights.
 #include "gemm.hpp"
 #include "common.hpp"
 
@@ -22,7 +23,6 @@ namespace molink {
 namespace {
 
 constexpr int kBK = 64;               // K elements per tile
-constexpr int kLdsStride = kBK + 8;   // padded row stride in bf16 elements (144 bytes)
 
 // Scheduling hint for one MFMA step of NMFMA MFMAs.  After each MFMA come the memory operations that
 // run in its shadow: the NREAD LDS reads of the next step's fragments are placed behind the first
@@ -563,7 +563,7 @@ hipError_t launch_epi(const GemmArgs& a, const GemmPlan& plan, hipStream_t strea
     case kTile256x256: return launch_tile<256, 256, 2, 2, 2, EPI, false>(a, plan, stream);
     case kTile256x128: return launch_tile<256, 128, 2, 2, 3, EPI, false>(a, plan, stream);
     case kTile128x128: return launch_tile<128, 128, 2, 2, 2, EPI, false>(a, plan, stream);
-    default: return launch_tile<64, 128, 2, 2, 3, EPI, false>(a, plan, stream);
+    default: return hipErrorInvalidValue;   // 64x128 exists only for two activation planes; single-plane M <= 64 is kTileSkinny
   }
 }
 

@@ -416,11 +416,11 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
 
   float* x = (float*)(ws + st->ws.x);
   __bf16* a = (__bf16*)(ws + st->ws.a);
-  const bool split_mlp = two_plane_of(c);
-  __bf16* a_lo = split_mlp ? (__bf16*)(ws + st->ws.a_lo) : nullptr;
-  __bf16* mlp_lo = split_mlp ? (__bf16*)(ws + st->ws.mlp_lo) : nullptr;
-  __bf16* q_lo = split_mlp ? (__bf16*)(ws + st->ws.q_lo) : nullptr;
-  __bf16* attn_lo = split_mlp ? (__bf16*)(ws + st->ws.attn_lo) : nullptr;
+  const bool two_plane = two_plane_of(c);
+  __bf16* a_lo = two_plane ? (__bf16*)(ws + st->ws.a_lo) : nullptr;
+  __bf16* mlp_lo = two_plane ? (__bf16*)(ws + st->ws.mlp_lo) : nullptr;
+  __bf16* q_lo = two_plane ? (__bf16*)(ws + st->ws.q_lo) : nullptr;
+  __bf16* attn_lo = two_plane ? (__bf16*)(ws + st->ws.attn_lo) : nullptr;
   float* qkv_f32 = (float*)(ws + st->ws.qkv_f32);
   __bf16* qkv = (__bf16*)(ws + st->ws.qkv);
   __bf16* attn = (__bf16*)(ws + st->ws.attn);
