@@ -82,6 +82,9 @@ int handoff_sender_wait(handoff_sender *s, int64_t ticket, int32_t kind);
 /* How many transfers the sender had chosen when it first saw the ticket complete (-1: not seen yet). */
 int handoff_sender_visible_pick(handoff_sender *s, int64_t ticket, int64_t *out_pick);
 
+/* How many transfers the sender has chosen so far (its position in the order of transfers). */
+int handoff_sender_picks(handoff_sender *s, int64_t *out_picks);
+
 /* Copy out (and forget) the records of the transfers finished so far, in the order they were chosen. */
 int handoff_sender_log(handoff_sender *s, handoff_record *out, int32_t capacity, int32_t *out_count);
 

@@ -267,6 +267,13 @@ int handoff_sender_visible_pick(handoff_sender* s, int64_t ticket, int64_t* out_
   return HANDOFF_OK;
 }
 
+int handoff_sender_picks(handoff_sender* s, int64_t* out_picks) {
+  if (!s || !out_picks) return fail(HANDOFF_ERR_NULL, "a required pointer is NULL");
+  std::lock_guard<std::mutex> lk(s->mu);
+  *out_picks = s->picks;
+  return HANDOFF_OK;
+}
+
 int handoff_sender_log(handoff_sender* s, handoff_record* out, int32_t capacity, int32_t* out_count) {
   if (!s || !out_count || (!out && capacity > 0)) return fail(HANDOFF_ERR_NULL, "a required pointer is NULL");
   std::lock_guard<std::mutex> lk(s->mu);

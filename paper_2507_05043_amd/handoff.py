@@ -41,12 +41,13 @@ def _lib():
                                               ctypes.c_int32, i32p, ctypes.c_int64, i64p]
         lib.handoff_sender_wait.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32]
         lib.handoff_sender_visible_pick.argtypes = [ctypes.c_void_p, ctypes.c_int64, i64p]
+        lib.handoff_sender_picks.argtypes = [ctypes.c_void_p, i64p]
         lib.handoff_sender_log.argtypes = [ctypes.c_void_p, recp, ctypes.c_int32, i32p]
         lib.handoff_sender_destroy.argtypes = [ctypes.c_void_p]
         lib.handoff_sender_destroy.restype = None
         lib.handoff_last_error.restype = ctypes.c_char_p
         for n in ("handoff_plan", "handoff_sender_create", "handoff_sender_submit", "handoff_sender_wait",
-                  "handoff_sender_visible_pick", "handoff_sender_log"):
+                  "handoff_sender_visible_pick", "handoff_sender_picks", "handoff_sender_log"):
             getattr(lib, n).restype = ctypes.c_int
         _ready = True
     return lib
@@ -102,6 +103,11 @@ class Sender:
     def visible_pick(self, ticket: int) -> int:
         out = ctypes.c_int64()
         _check(_lib().handoff_sender_visible_pick(self._h, ticket, ctypes.byref(out)))
+        return out.value
+
+    def picks(self) -> int:
+        out = ctypes.c_int64()
+        _check(_lib().handoff_sender_picks(self._h, ctypes.byref(out)))
         return out.value
 
     def log(self) -> List[HandoffRecord]:
