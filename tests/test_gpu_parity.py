@@ -134,6 +134,17 @@ def test_two_runs_are_bitwise_identical():
     st.close()
 
 
+def test_two_planes_on_small_micro_batches():
+    """Two activation planes with at most 64 rows (the weight-streaming kernel handles one plane only, so
+    this takes the tiled kernel's 64-row two-plane variant), decode only and mixed."""
+    shape = _shape("planes2-small", 2, 512, 8, 2, 128, 1024)
+    full_parity(shape, synth.make_microbatch([1] * 20, [5 + 9 * i for i in range(20)], seed=31), 31, "fan_in",
+                activation_planes=2)
+    full_parity(shape, synth.make_microbatch([30, 1, 1, 1], [0, 40, 100, 7], seed=32), 32, "fan_in", activation_planes=2)
+    small = _shape("planes2-d64", 2, 256, 4, 2, 64, 688)
+    full_parity(small, synth.make_microbatch([1], [0], seed=33), 33, "fan_in", activation_planes=2)
+
+
 def test_one_handle_serves_different_micro_batches_in_turn():
     """A serving loop reuses one stage for micro-batches of different sizes and mixes: nothing of a
     previous call (workspace, metadata, split counts) may leak into the next."""
