@@ -93,8 +93,12 @@ typedef struct stage_handle stage_handle;
 /*
  * KV pool layout (part of the ABI: the caller pre-fills the cached context).
  * Layer l starts at kv_pool + l * kv_layer_stride_bytes and holds two bf16 regions:
- *   K: [num_kv_blocks][nkv][16 slots][d]      one cached key vector is d contiguous elements
- *   V: [num_kv_blocks][nkv][d][16 slots]      values are stored transposed inside a block
+ *   K: [num_kv_blocks][nkv][d/32][16 positions][32]   a key vector is cut into pieces of 32 elements; the
+ *                                                      key of slot s sits at position s with bits 2 and 3
+ *                                                      exchanged (slots 0-3, 8-11, 4-7, 12-15)
+ *   V: [num_kv_blocks][nkv][d][16 slots]               values are stored transposed inside a block
+ * (the orders in which the attention kernels' matrix-core tiles take their rows, so that every load
+ * instruction reads runs of 512 bytes or more; stage_kv_element_offset is the map)
  * The V region starts stage_kv_layer_bytes/2 bytes after the K region.  Token j of a sequence
  * lives in block block_table[j / 16] at slot j % 16.
  * stage_kv_layer_bytes: bytes of one layer's pool (both regions).

@@ -1,9 +1,9 @@
 // Attention over the paged KV pool, both phases, on MFMA with operands read straight from HBM/L2.
 //
 // Formulation.  Everything is computed transposed: S^T = K Q^T and O^T = V^T P^T.  With the pool
-// layout K [block][head][16 slots][d] and V [block][head][d][16 slots], both left operands then have
-// their contraction index contiguous in memory (d for K rows, slots for V^T rows), which is exactly
-// what an MFMA lane holds (8 consecutive k of one row).  The right operand of the second product,
+// layout K [block][head][d/32][16 positions][32] and V [block][head][d][16 slots], both left operands
+// then have their contraction index contiguous in memory (d for K rows, slots for V^T rows), which is
+// exactly what an MFMA lane holds (8 consecutive k of one row).  The right operand of the second product,
 // P^T, is the accumulator of the first one: the row order of a key tile is a free choice (each lane
 // loads its own K row), and choosing it so that a lane's accumulator registers are 8 consecutive slots
 // of one block makes the registers of S^T the B operand of the PV product with no data movement
@@ -100,9 +100,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
 
   // per-lane constants of the K and V^T operand loads
   const int k_bsel = (lane & 15) >> 3;                                  // which block of the pair this lane's K row is in
-  const int k_slot = 8 * (((lane & 15) >> 2) & 1) + (lane & 3);         // tile A slot; tile B is +4
   const int v_bsel = grp >> 1;
-  const size_t k_lane_off = (size_t)k_slot * D + grp * 8;
+  // tile A takes positions 0..7 of the block this lane's key row is in (slots 0-3 and 8-11), tile B the
+  // next eight: per instruction two runs of 512 bytes
+  const size_t k_lane_off = (size_t)(lane & 7) * 32 + grp * 8;
   const size_t v_lane_off = (size_t)(lane & 15) * kKvBlock + 8 * (grp & 1);
   const size_t blk_stride = (size_t)a.nkv * kKvBlock * D;               // elements per block (all heads)
   const size_t head_off = (size_t)r * kKvBlock * D;
@@ -119,8 +120,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     const __bf16* kp = a.k_pool + (size_t)pbk * blk_stride + head_off + k_lane_off;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
-      L.ka[kk] = load8(kp + kk * 32);
-      L.kb[kk] = load8(kp + 4 * D + kk * 32);
+      L.ka[kk] = load8_stream(kp + kk * (kKvBlock * 32));
+      L.kb[kk] = load8_stream(kp + 8 * 32 + kk * (kKvBlock * 32));
     }
     const int pbv = v_bsel ? b1 : b0;
     const __bf16* vp = a.v_pool + (size_t)pbv * blk_stride + head_off + v_lane_off;
@@ -267,11 +268,12 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const Decod
 // slots 8G..8G+7 of the first block, registers 8..15 the same slots of the second block, i.e. the
 // S^T accumulators are the P^T operand of the PV product as they stand.
 //
-// LDS stage: K tile, 32 rows of 2D bytes in MFMA row order, 16-byte chunk c of row m stored at
-// position c ^ (m & 7) (128-bit fragment reads of 8 consecutive rows then hit 8 different bank
-// groups); then the V^T tiles as [block][slot half][d][16 bytes], so that the lanes of a fragment
-// read (32 consecutive d, one half) are contiguous.  Both arrangements are made by choosing which 16
-// bytes each lane of a load instruction fetches.
+// LDS stage: the K tile as it lies in the pool, [block][d/32][16 positions][64 bytes] (MFMA row m of the
+// tile is position m % 16 of block m / 16; every load instruction copies one 1 KB run), with the four
+// 16-byte chunks of a 64-byte piece exchanged by (position / 2) % 4 so that the 128-bit fragment reads
+// of 8 consecutive rows hit 8 different bank groups; then the V^T tiles as [block][slot half][d][16
+// bytes], so that the lanes of a fragment read (32 consecutive d, one half) are contiguous.  Both
+// arrangements are made by choosing which 16 bytes each lane of a load instruction fetches.
 // ------------------------------------------------------------------------------------------------
 template <int D, bool QLO>
 __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const PrefillTile* __restrict__ tiles,
@@ -282,7 +284,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
   constexpr int K_BYTES = 32 * D * 2;        // K tile
   constexpr int STAGE_BYTES = 2 * K_BYTES;   // + V^T tiles of the same size
   constexpr int NI = STAGE_BYTES / 1024 / 4; // load instructions per wave per stage
-  constexpr int CPR = D / 8;                 // 16-byte chunks per K row
+  constexpr int NP = D / 32;                 // 32-element pieces per K row
   using Lds = LdsStages<STAGE_BYTES>;
 
   const int lane = threadIdx.x & 63;
@@ -337,11 +339,9 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
   for (int i = 0; i < NI; ++i) {
     const int j = 4 * i + wave;
     if (j < K_BYTES / 1024) {
-      const int pos = j * 64 + lane;                 // 16-byte position in the K tile
-      const int m = pos / CPR, p = pos % CPR;        // tile row, position in the row
-      const int chunk = p ^ (m & 7);
-      const int slot = 8 * ((m >> 2) & 1) + 4 * ((m >> 3) & 1) + (m & 3);
-      ld_off[i] = (uint32_t)(slot * D + chunk * 8) * 2u;
+      // instruction j copies piece j % NP of block j / NP: 16 positions x 64 bytes, one run in the pool
+      const int piece = j % NP, pos = lane >> 2, c = lane & 3;
+      ld_off[i] = (uint32_t)((piece * kKvBlock + pos) * 32 + ((c ^ ((pos >> 1) & 3)) * 8)) * 2u;
     } else {
       const int pos = (j - K_BYTES / 1024) * 64 + lane;   // 16-byte position in the V part: [block][half][d]
       const int d = pos % D, half = (pos / D) & 1;
@@ -361,7 +361,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
     for (int i = 0; i < NI; ++i) {
       const int j = 4 * i + wave;                                    // uniform
       const bool is_k = j < K_BYTES / 1024;
-      const int second = is_k ? (j * 64 / CPR) >> 4 : ((j - K_BYTES / 1024) * 64) / (2 * D);
+      const int second = is_k ? j / NP : ((j - K_BYTES / 1024) * 64) / (2 * D);
       const int pb = second ? b1 : b0;
       const char* base = reinterpret_cast<const char*>((is_k ? a.k_pool : a.v_pool) + (size_t)pb * blk_stride + head_off);
       __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(base + ld_off[i]),
@@ -376,9 +376,11 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
     for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  // fragment addresses: K row m = lane % 32, chunk 2 kk + grp at position (2 kk + grp) ^ (m & 7);
-  // V^T row d = 32 t + lane % 32 of half grp of block b
-  const int k_row_off = col * (2 * D);
+  // fragment addresses: K row m = lane % 32 is position m % 16 of block m / 16; MFMA step kk wants chunk
+  // 2 (kk % 2) + grp of piece kk / 2;  V^T row d = 32 t + lane % 32 of half grp of block b
+  const int k_pos = col & 15;
+  const int k_row_off = ((col >> 4) * NP * kKvBlock + k_pos) * 64;
+  const int k_swz = (k_pos >> 1) & 3;
   const int v_frag_off = K_BYTES + (grp * D + col) * 16;
 
   auto process = [&](auto stage_c, int step) {
@@ -389,7 +391,8 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
     f32x16 s = zero16;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
-      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(stage + k_row_off + (((2 * kk + grp) ^ (col & 7)) * 16));
+      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(stage + k_row_off + (kk >> 1) * (kKvBlock * 64) +
+                                                         (((2 * (kk & 1) + grp) ^ k_swz) * 16));
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
       if constexpr (QLO) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf_lo[kk], s, 0, 0, 0);
     }

@@ -16,6 +16,18 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 constexpr int kWave = 64;        // lanes per wavefront
 constexpr int kKvBlock = 16;     // tokens per KV block (fixed by the ABI)
 
+// K layout inside one (block, KV head): [d / 32][16 positions][32 elements]; the key of slot s sits at
+// position s with bits 2 and 3 exchanged (slots 0-3, 8-11, 4-7, 12-15).  In that order the key rows an
+// MFMA key tile takes (whose accumulator registers must come out as 8 consecutive slots per lane group)
+// are consecutive, so that one load instruction reads a 512-byte or 1 KB run instead of 64-byte pieces.
+__host__ __device__ __forceinline__ int k_position_of_slot(int slot) {
+  return (slot & 3) | ((slot & 8) >> 1) | ((slot & 4) << 1);
+}
+// element offset of (slot, dim) inside a (block, KV head) region of K
+__host__ __device__ __forceinline__ int k_offset_in_block(int slot, int dim) {
+  return ((dim >> 5) * kKvBlock + k_position_of_slot(slot)) * 32 + (dim & 31);
+}
+
 __device__ __forceinline__ float bf16_to_f32(__bf16 v) { return static_cast<float>(v); }
 __device__ __forceinline__ __bf16 f32_to_bf16(float v) { return static_cast<__bf16>(v); }
 

@@ -135,9 +135,9 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs p) {
       }
     } else {
       const int r = head - p.nq;
-      __bf16* dst = p.k_pool + (((size_t)blk * p.nkv + r) * kKvBlock + s) * d + c * 8;
-      store8(dst, olo);
-      store8(dst + half, ohi);
+      __bf16* dst = p.k_pool + ((size_t)blk * p.nkv + r) * kKvBlock * d;
+      store8(dst + k_offset_in_block(s, c * 8), olo);
+      store8(dst + k_offset_in_block(s, half + c * 8), ohi);
     }
   } else {
     const int w = u - rot_units;

@@ -14,6 +14,7 @@
 
 #include "attention.hpp"
 #include "elementwise.hpp"
+#include "common.hpp"
 #include "gemm.hpp"
 
 using namespace molink;
@@ -555,7 +556,7 @@ int stage_kv_element_offset(const stage_config* cfg, int32_t kv, int32_t block, 
   const int64_t d = cfg->head_dim, nkv = cfg->num_kv_heads;
   const int64_t region = (int64_t)cfg->num_kv_blocks * nkv * 16 * d;
   const int64_t base = ((int64_t)block * nkv + kv_head) * 16 * d;
-  *out_offset = kv == 0 ? base + (int64_t)slot * d + dim : region + base + (int64_t)dim * 16 + slot;
+  *out_offset = kv == 0 ? base + k_offset_in_block(slot, dim) : region + base + (int64_t)dim * 16 + slot;
   return STAGE_OK;
 }
 

@@ -183,7 +183,10 @@ class Stage:
                               ctypes.byref(handle)))
         self._handle = handle
 
-    # ---- KV pool views (layout of the ABI: K [blocks][nkv][16][d], V [blocks][nkv][d][16])
+    # ---- KV pool views (layout of the ABI: K [blocks][nkv][d/32][16 positions][32], V [blocks][nkv][d][16])
+    # position of slot s = s with bits 2 and 3 exchanged; the exchange is its own inverse
+    _K_SLOT_OF_POSITION = [0, 1, 2, 3, 8, 9, 10, 11, 4, 5, 6, 7, 12, 13, 14, 15]
+
     def _region(self, layer: int, kv: int) -> torch.Tensor:
         c = self.cfg
         region_bytes = stage_kv_layer_bytes(c) // 2
@@ -192,7 +195,7 @@ class Stage:
 
     def k_view(self, layer: int) -> torch.Tensor:
         c = self.cfg
-        return self._region(layer, 0).view(c.num_kv_blocks, c.num_kv_heads, 16, c.head_dim)
+        return self._region(layer, 0).view(c.num_kv_blocks, c.num_kv_heads, c.head_dim // 32, 16, 32)
 
     def v_view(self, layer: int) -> torch.Tensor:
         c = self.cfg
@@ -201,14 +204,20 @@ class Stage:
     def write_kv_blocks(self, layer: int, kv: int, blocks: torch.Tensor, values: torch.Tensor) -> None:
         """Store values [n, 16 slots, nkv, d] (bf16, on the device) into the given physical blocks."""
         if kv == 0:
-            self.k_view(layer)[blocks] = values.permute(0, 2, 1, 3)
+            n, _, nkv, d = values.shape
+            order = torch.tensor(self._K_SLOT_OF_POSITION, device=values.device)
+            v = values[:, order].reshape(n, 16, nkv, d // 32, 32)          # [n, position, nkv, piece, 32]
+            self.k_view(layer)[blocks] = v.permute(0, 2, 3, 1, 4)
         else:
             self.v_view(layer)[blocks] = values.permute(0, 2, 3, 1)
 
     def read_kv_blocks(self, layer: int, kv: int, blocks: torch.Tensor) -> torch.Tensor:
         """Inverse of write_kv_blocks: [n, 16 slots, nkv, d]."""
         if kv == 0:
-            return self.k_view(layer)[blocks].permute(0, 2, 1, 3)
+            v = self.k_view(layer)[blocks].permute(0, 3, 1, 2, 4)             # [n, position, nkv, piece, 32]
+            n, _, nkv, pieces, _ = v.shape
+            order = torch.tensor(self._K_SLOT_OF_POSITION, device=v.device)  # slot of position == position of slot
+            return v.reshape(n, 16, nkv, pieces * 32)[:, order]
         return self.v_view(layer)[blocks].permute(0, 3, 1, 2)
 
     # ---- the forward pass

@@ -152,7 +152,8 @@ def test_kv_element_offset_is_a_bijection_with_the_documented_layout(lib):
                         seen.add(off)
                         region = kv * (layer_elems // 2)
                         base = (b * nkv + h) * 16 * d
-                        want = region + base + (s * d + e if kv == 0 else e * 16 + s)
+                        pos = (s & 3) | ((s & 8) >> 1) | ((s & 4) << 1)     # bits 2 and 3 of the slot exchanged
+                        want = region + base + (((e // 32) * 16 + pos) * 32 + e % 32 if kv == 0 else e * 16 + s)
                         assert off == want
     with pytest.raises(StageError):
         S.stage_kv_element_offset(cfg, 0, 3, 0, 0, 0)
