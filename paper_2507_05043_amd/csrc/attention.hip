@@ -72,7 +72,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
   const int key_begin = __builtin_amdgcn_readfirstlane(items[item_id].key_begin);
   const int key_end = __builtin_amdgcn_readfirstlane(items[item_id].key_end);
   const int part = __builtin_amdgcn_readfirstlane(items[item_id].part);
-  const int32_t* bt = a.bt_flat + bt_off;
+  // block ids are read through the constant address space (nothing writes the table during the kernel):
+  // scalar loads, which do not queue behind the K/V loads in flight
+  typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+  const const_i32_ptr bt = (const_i32_ptr)(a.bt_flat + bt_off);
   const int last_block = (key_end - 1) / kKvBlock;
   const int nsteps = (key_end - key_begin + 31) / 32;
 
