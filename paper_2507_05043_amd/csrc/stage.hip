@@ -380,9 +380,12 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
         const int keys = cx + 1;
         const int n = (keys + range - 1) / range;
         h_dtok[dt++] = DecodeToken{row, it, n, 0};
+        // the sequence's ranges get equal lengths (a multiple of 32 keys) instead of n - 1 full ones and a
+        // short remainder: less spread between the work items
+        const int len = ((keys + n - 1) / n + 31) / 32 * 32;
         for (int k = 0; k < n; ++k) {
-          const int kb = k * range;
-          const int ke = kb + range < keys ? kb + range : keys;
+          const int kb = k * len;
+          const int ke = kb + len < keys ? kb + len : keys;
           h_items[it] = DecodeItem{row, bt_off, kb, ke, it, {0, 0, 0}};
           ++it;
         }
