@@ -99,7 +99,7 @@ def main():
                     help="run a plain 1 GiB device copy ten times and exit (reference for hardware counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (one pipeline stage = one GPU's share); use --gpus 1")
+        sys.exit("bench.py: one pipeline stage is one GPU's share and this benchmark measures exactly that; use --gpus 1")
 
     import torch
     if args.copy_calibration:
