@@ -575,8 +575,8 @@ GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool spli
   const int k_tiles = (k + kBK - 1) / kBK;
   struct Cand { int tile, bm, bn, wg_per_cu; float eff; };
   // measured relative efficiency of the tile shapes and how many workgroups of each fit on a CU (LDS)
-  static const Cand cands[] = {{kTile256x256, 256, 256, 1, 0.9f}, {kTile256x128, 256, 128, 1, 1.0f},
-                               {kTile128x128, 128, 128, 2, 0.95f}};
+  static const Cand cands[] = {{kTile256x256, 256, 256, 1, 0.94f}, {kTile256x128, 256, 128, 1, 1.0f},
+                               {kTile128x128, 128, 128, 2, 0.8f}};
   if (m <= 64 && !split_a) {
     plan.tile = kTileSkinny;
     plan.splits = (k + kSkinnyKS - 1) / kSkinnyKS;
