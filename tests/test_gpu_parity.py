@@ -145,6 +145,27 @@ def test_two_planes_on_small_micro_batches():
     full_parity(small, synth.make_microbatch([1], [0], seed=33), 33, "fan_in", activation_planes=2)
 
 
+def test_startup_profile_table():
+    """The latency table a stage measures at start-up: positive, reproducible to the same order of magnitude,
+    and growing with the work (4x the sequences at 8x the context must take longer)."""
+    from paper_2507_05043_amd import profiler
+    shape = _shape("profile-d128", 2, 1024, 8, 8, 128, 2048)
+    cap = synth.make_microbatch([1] * 64, [4096] * 64, seed=0)
+    st = H.make_stage(shape, cap, 0, max_tokens=512, fill_kv=False)
+    st.kv_pool.zero_()
+    dec = profiler.profile_decode(st, [1, 16, 64], [512, 4096])
+    pre = profiler.profile_prefill(st, [64, 512], [0, 1024])
+    for line in profiler.format_table(dec, "sequences", "context") + profiler.format_table(pre, "chunk", "context"):
+        print("  " + line, flush=True)
+    assert all(v > 0 for v in dec.values()) and all(v > 0 for v in pre.values())
+    assert dec[(64, 4096)] > dec[(16, 512)] and pre[(512, 1024)] > pre[(64, 0)]
+    with pytest.raises(ValueError):
+        profiler.profile_decode(st, [65], [512])
+    with pytest.raises(ValueError):
+        profiler.profile_decode(st, [64], [8192])
+    st.close()
+
+
 def test_one_handle_serves_different_micro_batches_in_turn():
     """A serving loop reuses one stage for micro-batches of different sizes and mixes: nothing of a
     previous call (workspace, metadata, split counts) may leak into the next."""
