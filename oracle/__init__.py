@@ -7,3 +7,4 @@ from .stage_oracle import (  # noqa: F401
 )
 from .ends_oracle import embed_tokens, last_rows, head_logits, greedy_tokens  # noqa: F401
 from . import handoff_oracle  # noqa: F401
+from . import pipeline_oracle  # noqa: F401
