@@ -145,6 +145,28 @@ def test_two_planes_on_small_micro_batches():
     full_parity(small, synth.make_microbatch([1], [0], seed=33), 33, "fan_in", activation_planes=2)
 
 
+def test_forward_on_a_side_stream_while_the_default_stream_is_busy():
+    """Everything is enqueued on the caller's stream: a forward pass on a side stream gives the same bits
+    while unrelated work runs on the default stream, and the default stream is not waited for."""
+    shape, mb = synth.workload("tiny", seed=0)
+    st = H.make_stage(shape, mb, 0, "fan_in")
+    want, _ = H.run_gpu(st, shape, mb, 0)
+    want = want.clone()
+    H.fill_pool(st, shape, mb, 0)
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=0, device="cuda:0")
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream(device="cuda:0")
+    busy = torch.ones(4096, 4096, device="cuda:0")
+    for _ in range(20):                       # keeps the default stream occupied for a while
+        busy = (busy @ busy).clamp_(max=1.0)
+    with torch.cuda.stream(side):
+        got = st.forward(hidden, mb.positions, mb.q_lens, mb.ctx_lens, mb.block_tables)
+    side.synchronize()
+    assert torch.equal(got.view(torch.int16), want.view(torch.int16))
+    torch.cuda.synchronize()
+    st.close()
+
+
 def test_startup_profile_table():
     """The latency table a stage measures at start-up: positive, reproducible to the same order of magnitude,
     and growing with the work (4x the sequences at 8x the context must take longer)."""
