@@ -1,4 +1,5 @@
-"""CPU oracle of one pipeline stage's forward pass and of the pipeline's two ends.  Test infrastructure only:
+"""CPU oracles: one pipeline stage's forward pass, the pipeline's two ends, and the models of the payload
+hand-off and of the pipeline's iteration time.  Test infrastructure only:
 imported by tests/, by the smoke check and by the CPU-baseline leg of the
 benchmark; never by the product package."""
 from .stage_oracle import (  # noqa: F401
