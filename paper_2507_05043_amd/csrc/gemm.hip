@@ -4,10 +4,12 @@
 // (lane l holds 8 consecutive k of row l%32).  Tiles travel HBM/L2 -> LDS directly (16 bytes per lane,
 // 8 rows x 128 bytes per wave instruction, XOR-swizzled so 128-bit LDS reads are conflict free) ->
 // MFMA operands.  Two to three K tiles are kept in flight in separate LDS stages; one barrier per K
-// tile; LDS reads and tile loads are interleaved with the MFMAs by explicit scheduling hints.
+// tile, placed before the tile's last MFMA step so that the matrix pipe does not drain at it; LDS reads
+// and tile loads are interleaved with the MFMAs by explicit scheduling hints.
 //
-// Workgroup ids are remapped so that consecutive logical tiles share an XCD: the M tiles that reuse
-// one weight tile run next to each other on one L2.
+// Workgroup ids are remapped so that consecutive logical tiles share an XCD, and tiles are walked in
+// bands of eight tile rows: the workgroups that run together on one XCD form a compact block of the
+// output, so each operand tile that enters the XCD's L2 is used by several of them.
 //
 // Shapes without enough output tiles to fill 256 CUs split the K dimension across workgroups; the
 // partial sums go to fp32 scratch and a second kernel adds them in a fixed order (deterministic) and
@@ -23,6 +25,7 @@ namespace molink {
 namespace {
 
 constexpr int kBK = 64;               // K elements per tile
+constexpr int kBandRows = 8;          // tile rows per band of the tile order
 
 // Scheduling hint for one MFMA step of NMFMA MFMAs.  After each MFMA come the memory operations that
 // run in its shadow: the NREAD LDS reads of the next step's fragments are placed behind the first
@@ -52,7 +55,8 @@ __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)
 // fills 8 rows x 128 bytes.  Rows are unpadded; bank conflicts are avoided by an XOR swizzle applied
 // to the *global* address each lane fetches: slot p of row r holds the row's 16-byte chunk p ^ (r & 7),
 // so the 8 lanes of a 128-bit LDS read that hit rows r..r+7 at the same logical chunk touch 8
-// different slots.  LDS reads of MFMA step kk+1 are issued under the MFMAs of step kk.
+// different slots.  LDS reads of MFMA step kk+1 are issued under the MFMAs of step kk, across tile
+// boundaries too.
 template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int EPI, bool SPLIT, bool SPLIT_A>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmArgs p, int nv, int tiles_m, int tiles_n, int splits,
                                                         int k_tiles_per_split) {
@@ -65,15 +69,26 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
   static_assert(GROUPS % NWAVES == 0, "row groups must divide evenly among the waves");
   constexpr int STAGE_BYTES = (AROWS + BN) * 128;
   static_assert(EPI != kEpiSwiGLU || TN % 64 == 0, "SwiGLU pairs two 32-wide column tiles per wave");
-  static_assert(NSTAGE >= 2 && NSTAGE <= 4 && NSTAGE * STAGE_BYTES <= 160 * 1024, "stages must fit in LDS");
+  static_assert(NSTAGE >= 2 && NSTAGE <= 3 && NSTAGE * STAGE_BYTES <= 160 * 1024, "stages must fit in LDS");
   using Lds = LdsStages<STAGE_BYTES>;
 
   const int total = tiles_m * tiles_n * splits;
   const int lid = xcd_logical_id(blockIdx.x, total);
   if (lid < 0) return;
-  const int tile_m = lid % tiles_m;
-  const int split = (lid / tiles_m) % splits;
-  const int tile_n = lid / (tiles_m * splits);
+  int tile_m, tile_n, split;
+  if (splits == 1 && tiles_m > kBandRows) {
+    // bands of kBandRows tile rows, each walked column by column
+    const int band_size = kBandRows * tiles_n;
+    const int band = lid / band_size, rem = lid % band_size;
+    const int rows_in_band = min(kBandRows, tiles_m - band * kBandRows);
+    tile_m = band * kBandRows + rem % rows_in_band;
+    tile_n = rem / rows_in_band;
+    split = 0;
+  } else {
+    tile_m = lid % tiles_m;
+    split = (lid / tiles_m) % splits;
+    tile_n = lid / (tiles_m * splits);
+  }
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -163,77 +178,90 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
 #pragma unroll
   for (int kk = 0; kk < kBK / 16; ++kk) frag_off[kk] = frag_row * 128 + (((2 * kk + (lane >> 5)) ^ (lane & 7)) * 16);
 
-  auto multiply = [&](auto stage_c) {
+  constexpr int NPLANE = SPLIT_A ? 2 : 1;
+  constexpr int KSTEPS = kBK / 16, NMFMA = NPLANE * MT * NT, NREAD = NPLANE * MT + NT;
+  static_assert(KSTEPS == 4, "four MFMA steps per K tile");
+  bf16x8 af[2][NPLANE][MT], bfr[2][NT];
+  // fragments of MFMA step kk of the tile in stage S into register set s
+  auto read_frags = [&](auto stage_c, int s, int kk) {
     constexpr int S = decltype(stage_c)::value;
     const char* la = Lds::template get<S>() + wm * TM * 128;
     const char* lb = Lds::template get<S>() + (AROWS + wn * TN) * 128;
-    constexpr int NPLANE = SPLIT_A ? 2 : 1;
-    bf16x8 af[2][NPLANE][MT], bfr[2][NT];
-    auto read_frags = [&](int s, int kk) {
 #pragma unroll
-      for (int pl = 0; pl < NPLANE; ++pl)
+    for (int pl = 0; pl < NPLANE; ++pl)
 #pragma unroll
-        for (int i = 0; i < MT; ++i)
-          af[s][pl][i] = *reinterpret_cast<const bf16x8*>(la + (pl * BM + i * 32) * 128 + frag_off[kk]);
+      for (int i = 0; i < MT; ++i)
+        af[s][pl][i] = *reinterpret_cast<const bf16x8*>(la + (pl * BM + i * 32) * 128 + frag_off[kk]);
 #pragma unroll
-      for (int j = 0; j < NT; ++j) bfr[s][j] = *reinterpret_cast<const bf16x8*>(lb + j * 32 * 128 + frag_off[kk]);
-    };
-    constexpr int KSTEPS = kBK / 16, NMFMA = NPLANE * MT * NT, NREAD = NPLANE * MT + NT, NLOADS = NI;
-    read_frags(0, 0);
-    __builtin_amdgcn_sched_group_barrier(0x100, NREAD, 0);   // the first step's fragments cannot overlap anything
-    auto mfma_step = [&](auto kk_c) {
-      constexpr int kk = decltype(kk_c)::value;
-      if constexpr (kk + 1 < KSTEPS) read_frags((kk + 1) & 1, kk + 1);
+    for (int j = 0; j < NT; ++j) bfr[s][j] = *reinterpret_cast<const bf16x8*>(lb + j * 32 * 128 + frag_off[kk]);
+  };
+  auto mfmas = [&](int s) {
 #pragma unroll
-      for (int pl = 0; pl < NPLANE; ++pl)
+    for (int pl = 0; pl < NPLANE; ++pl)
 #pragma unroll
-        for (int i = 0; i < MT; ++i)
+      for (int i = 0; i < MT; ++i)
 #pragma unroll
-          for (int j = 0; j < NT; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][pl][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
-      // a quarter of this pipeline step's tile loads goes behind each MFMA step
-      constexpr int loads = (kk + 1) * NLOADS / KSTEPS - kk * NLOADS / KSTEPS;
-      sched_step<0, NMFMA, (kk + 1 < KSTEPS ? NREAD : 0), loads>();
-    };
-    static_assert(KSTEPS == 4, "four MFMA steps per K tile");
-    mfma_step(std::integral_constant<int, 0>{});
-    mfma_step(std::integral_constant<int, 1>{});
-    mfma_step(std::integral_constant<int, 2>{});
-    mfma_step(std::integral_constant<int, 3>{});
+        for (int j = 0; j < NT; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s][pl][i], bfr[s][j], acc[i][j], 0, 0, 0);
   };
 
-  // One pipeline step: tile idx is in stage S.  Refill the stage that was read in the previous step with
-  // tile idx + NSTAGE - 1, multiply, then wait until tile idx + 1 has landed (newer tiles may still be
-  // in flight) and meet the other waves.
+  // One pipeline step: tile idx is in stage S and the fragments of its first MFMA step are already in
+  // registers (two register sets alternate).  The wait for tile idx + 1 and the barrier come BEFORE the
+  // last MFMA step: by then every fragment of tile idx has been read, so the barrier also frees stage S,
+  // and the fragment reads of tile idx + 1 run under the MFMAs of the last step - the matrix pipe does
+  // not drain at the barrier.  Where the next tile's loads go depends on the depth:
+  //  - three stages: the stage read in the previous step takes tile idx + 2, its loads spread evenly over
+  //    the first three MFMA steps (a wave that issues loads faster than the address unit takes them sits
+  //    in its queue and issues no MFMA meanwhile; at this tile size the even spread is just that rate);
+  //  - two stages: stage S takes tile idx + 2 right after the barrier, under the last MFMA step, which
+  //    gives the loads the longest lead a double buffer allows.
+  constexpr bool kRefillAfterBarrier = NSTAGE == 2;
+  constexpr int L0 = kRefillAfterBarrier ? 0 : NI / 3, L1 = kRefillAfterBarrier ? 0 : (2 * NI) / 3 - NI / 3,
+                L2 = kRefillAfterBarrier ? 0 : NI - (2 * NI) / 3, L3 = kRefillAfterBarrier ? NI : 0;
+  constexpr int kInFlight = kRefillAfterBarrier ? NSTAGE : NSTAGE - 1;   // tiles requested ahead of the one multiplied
   auto step = [&](auto stage_c, int idx) {
     constexpr int S = decltype(stage_c)::value;
-    fetch(std::integral_constant<int, (S + NSTAGE - 1) % NSTAGE>{}, idx + NSTAGE - 1);
-    multiply(stage_c);
+    using Next = std::integral_constant<int, (S + 1) % NSTAGE>;
+    if constexpr (!kRefillAfterBarrier) fetch(std::integral_constant<int, (S + NSTAGE - 1) % NSTAGE>{}, idx + NSTAGE - 1);
+    read_frags(stage_c, 1, 1);
+    mfmas(0);
+    sched_step<0, NMFMA, NREAD, L0>();
+    read_frags(stage_c, 0, 2);
+    mfmas(1);
+    sched_step<0, NMFMA, NREAD, L1>();
+    read_frags(stage_c, 1, 3);
+    mfmas(0);
+    sched_step<0, NMFMA, NREAD, L2>();
     __builtin_amdgcn_sched_barrier(0);
     wait_vmcnt<(NSTAGE - 2) * NI>();
-    patch_tail(std::integral_constant<int, (S + 1) % NSTAGE>{});
+    patch_tail(Next{});
     pipeline_barrier();
+    if constexpr (kRefillAfterBarrier) fetch(stage_c, idx + NSTAGE);
+    read_frags(Next{}, 0, 0);
+    mfmas(1);
+    sched_step<0, NMFMA, NREAD, L3>();
+    __builtin_amdgcn_sched_barrier(0);
   };
 
   if (nkt > 0) {
-    // prologue: tiles 0 .. NSTAGE-2 in flight, tile 0 landed
+    // prologue: the first tiles in flight, tile 0 landed, its first fragments read
     fetch(std::integral_constant<int, 0>{}, 0);
-    if constexpr (NSTAGE > 2) fetch(std::integral_constant<int, 1>{}, 1);
-    if constexpr (NSTAGE > 3) fetch(std::integral_constant<int, 2>{}, 2);
-    wait_vmcnt<(NSTAGE - 2) * NI>();
+    if constexpr (kInFlight > 1) fetch(std::integral_constant<int, 1>{}, 1);
+    if constexpr (kInFlight > 2) fetch(std::integral_constant<int, 2>{}, 2);
+    wait_vmcnt<(kInFlight - 1) * NI>();
     patch_tail(std::integral_constant<int, 0>{});
     pipeline_barrier();
+    read_frags(std::integral_constant<int, 0>{}, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
     int i = 0;
     for (; i + NSTAGE <= nkt; i += NSTAGE) {
       step(std::integral_constant<int, 0>{}, i);
       step(std::integral_constant<int, 1>{}, i + 1);
       if constexpr (NSTAGE > 2) step(std::integral_constant<int, 2>{}, i + 2);
-      if constexpr (NSTAGE > 3) step(std::integral_constant<int, 3>{}, i + 3);
     }
     if (i < nkt) step(std::integral_constant<int, 0>{}, i);
-    if (i + 1 < nkt) step(std::integral_constant<int, 1>{}, i + 1);
-    if constexpr (NSTAGE > 3) {
-      if (i + 2 < nkt) step(std::integral_constant<int, 2>{}, i + 2);
+    if constexpr (NSTAGE > 2) {
+      if (i + 1 < nkt) step(std::integral_constant<int, 1>{}, i + 1);
     }
     wait_vmcnt<0>();   // nothing may still be writing LDS when the workgroup ends
   }
@@ -563,6 +591,7 @@ hipError_t launch_epi(const GemmArgs& a, const GemmPlan& plan, hipStream_t strea
     case kTile256x256: return launch_tile<256, 256, 2, 2, 2, EPI, false>(a, plan, stream);
     case kTile256x128: return launch_tile<256, 128, 2, 2, 3, EPI, false>(a, plan, stream);
     case kTile128x128: return launch_tile<128, 128, 2, 2, 2, EPI, false>(a, plan, stream);
+    case kTile128x256: return launch_tile<128, 256, 2, 2, 3, EPI, false>(a, plan, stream);
     default: return hipErrorInvalidValue;   // 64x128 exists only for two activation planes; single-plane M <= 64 is kTileSkinny
   }
 }
@@ -575,8 +604,8 @@ GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool spli
   const int k_tiles = (k + kBK - 1) / kBK;
   struct Cand { int tile, bm, bn, wg_per_cu; float eff; };
   // measured relative efficiency of the tile shapes and how many workgroups of each fit on a CU (LDS)
-  static const Cand cands[] = {{kTile256x256, 256, 256, 1, 0.94f}, {kTile256x128, 256, 128, 1, 1.0f},
-                               {kTile128x128, 128, 128, 2, 0.8f}};
+  static const Cand cands[] = {{kTile128x256, 128, 256, 1, 1.0f}, {kTile256x128, 256, 128, 1, 0.99f},
+                               {kTile256x256, 256, 256, 1, 0.97f}, {kTile128x128, 128, 128, 2, 0.86f}};
   if (m <= 64 && !split_a) {
     plan.tile = kTileSkinny;
     plan.splits = (k + kSkinnyKS - 1) / kSkinnyKS;
@@ -585,19 +614,22 @@ GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool spli
     return plan;
   }
   float best = 0.f;
+  int bm = m <= 64 ? 64 : 128, bn = 128, wg_per_cu = m <= 64 ? 2 : (split_a ? 1 : 2);
   plan.tile = m <= 64 ? kTile64x128 : kTile128x128;
   for (const Cand& c : cands) {
     if (m <= 64) break;
     if (split_a && c.tile != kTile128x128) continue;   // with two activation planes only this tile's stages fit
+    const int per_cu = split_a ? 1 : c.wg_per_cu;
     const long tiles = (long)((m + c.bm - 1) / c.bm) * ((plan.nv + c.bn - 1) / c.bn);
-    const long slots = (long)num_cus * c.wg_per_cu;
+    const long slots = (long)num_cus * per_cu;
     const long rounds = (tiles + slots - 1) / slots;
-    const float cost = (float)rounds * c.bm * c.bn * c.wg_per_cu / c.eff;
-    if (best == 0.f || cost < best) { best = cost; plan.tile = c.tile; }
+    const float cost = (float)rounds * c.bm * c.bn * per_cu / c.eff;
+    if (best == 0.f || cost < best) {
+      best = cost;
+      plan.tile = c.tile;
+      bm = c.bm; bn = c.bn; wg_per_cu = per_cu;
+    }
   }
-  const int bm = plan.tile == kTile64x128 ? 64 : (plan.tile == kTile128x128 ? 128 : 256);
-  const int bn = plan.tile == kTile256x256 ? 256 : 128;
-  const int wg_per_cu = (!split_a && plan.tile == kTile128x128) || plan.tile == kTile64x128 ? 2 : 1;
   const int tiles = ((m + bm - 1) / bm) * ((plan.nv + bn - 1) / bn);
   int splits = 1;
   if (tiles * 2 <= num_cus * wg_per_cu) {

@@ -30,7 +30,7 @@ struct GemmArgs {
 
 // kTileSkinny: at most 64 rows; K cut into slices of 1024, weights streamed in groups of 16 rows, always
 // through partial sums (the reduction applies the epilogue).
-enum GemmTile : int { kTile256x256 = 0, kTile256x128 = 1, kTile128x128 = 2, kTile64x128 = 3, kTileSkinny = 4 };
+enum GemmTile : int { kTile256x256 = 0, kTile256x128 = 1, kTile128x128 = 2, kTile64x128 = 3, kTileSkinny = 4, kTile128x256 = 5 };
 
 struct GemmPlan {
   int tile;             // GemmTile: workgroup tile shape
