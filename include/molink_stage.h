@@ -73,9 +73,16 @@ typedef struct {
                                   to or exceed 1e-2 relative on the output, else 1. */
   int32_t vocab_size;          /* 0, or the vocabulary size (multiple of 8, >= 64) of the output head this
                                   stage may run with stage_head (sizes the workspace for it) */
+  int32_t weight_bits;         /* 0 or 16: the five projection matrices of a layer are bf16.  4: they are
+                                  group-quantised to 4 bits (see stage_layer_weights); the paper runs its 70B
+                                  model that way (section 5 "Models") */
+  int32_t weight_group_size;   /* weight_bits == 4 only: 32, 64 or 128 consecutive input features share one
+                                  scale and one zero point; hidden, num_q_heads*head_dim and ffn must be
+                                  multiples of it.  Otherwise 0. */
 } stage_config;
 
-/* Device pointers to one layer's bf16 weights, row-major [out_features][in_features]. Borrowed, read-only. */
+/* Device pointers to one layer's weights, row-major [out_features][in_features], bf16 unless
+ * stage_config.weight_bits says otherwise. Borrowed, read-only. */
 typedef struct {
   const void *norm1;  /* [H]  gain of the input RMSNorm */
   const void *wqkv;   /* [(nq + 2 nkv) d][H]: q head rows, then k head rows, then v head rows */
@@ -86,6 +93,19 @@ typedef struct {
   const void *wdown;  /* [H][F] */
   const void *bqkv;   /* [(nq + 2 nkv) d] bias of the q/k/v projection, added before the rotation
                          (the Qwen2 family has one), or NULL */
+  /*
+   * weight_bits == 4 only (ignored otherwise).  Each projection matrix W [N][K] (wqkv, wo, wgate, wup,
+   * wdown above) is then given as
+   *   codes        uint32 [N][K/8], in the w* pointer: element k of row n is the 4-bit field at bits
+   *                4*(k%8) .. 4*(k%8)+3 of word [n][k/8]
+   *   scales       bf16 [N][K/group]   (s* below)
+   *   zero points  bf16 [N][K/group]   (z* below; in code units, usually an integer in 0..15)
+   * and stands for   W[n][k] = (code[n][k] - zero[n][k/group]) * scale[n][k/group].
+   * The product is formed in fp32 (it is exact for integer zero points); kernels that materialise W
+   * round it to bf16 once.  Norm gains, the bias and the output head stay bf16.
+   */
+  const void *sqkv, *so, *sgate, *sup, *sdown;
+  const void *zqkv, *zo, *zgate, *zup, *zdown;
 } stage_layer_weights;
 
 typedef struct stage_handle stage_handle;
@@ -237,7 +257,8 @@ enum {
   STAGE_K_HEAD_NORM = 12,
   STAGE_K_GEMM_HEAD = 13,
   STAGE_K_HEAD_ARGMAX = 14,
-  STAGE_K_COUNT = 15
+  STAGE_K_DEQUANT = 15,      /* 4-bit weights expanded to bf16 ahead of a GEMM */
+  STAGE_K_COUNT = 16
 };
 int stage_profile_enable(stage_handle *st, uint32_t kernel_mask);
 int stage_profile_read(stage_handle *st, int32_t kernel, double *out_total_ms, int64_t *out_launches);

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libmolink_stage.so")
-SOURCES = ("gemm.hip", "elementwise.hip", "attention.hip", "stage.hip", "handoff.hip", "controller.hip")
+SOURCES = ("gemm.hip", "w4.hip", "elementwise.hip", "attention.hip", "stage.hip", "handoff.hip", "controller.hip")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed fp32 instructions are switched off for every kernel of the library
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -16,6 +16,7 @@
 #include "elementwise.hpp"
 #include "common.hpp"
 #include "gemm.hpp"
+#include "w4.hpp"
 
 using namespace molink;
 
@@ -52,6 +53,7 @@ struct Dims {
 struct WorkspaceLayout {
   size_t x, a, a_lo, qkv_f32, qkv, q_lo, attn, attn_lo, mlp, mlp_lo, cos_sin, splitk, part_o, part_ml, meta, total;
   size_t head_a, head_logits, ends_meta;   // output head: normalised last rows, fp32 logits, token ids / row indices
+  size_t wexp;                             // 4-bit weights: one projection's matrices expanded to bf16
   size_t meta_bytes;
   int max_items, max_tiles;
 };
@@ -75,6 +77,16 @@ int check_config(const stage_config* c) {
     return fail(STAGE_ERR_CONFIG, "activation_planes must be 0 (automatic), 1 or 2");
   if (c->vocab_size != 0 && (c->vocab_size < 64 || c->vocab_size % 8))
     return fail(STAGE_ERR_CONFIG, "vocab_size must be 0 or a multiple of 8 that is at least 64");
+  if (c->weight_bits != 0 && c->weight_bits != 16 && c->weight_bits != 4)
+    return fail(STAGE_ERR_CONFIG, "weight_bits must be 0, 16 or 4, got %d", c->weight_bits);
+  if (c->weight_bits == 4) {
+    const int g = c->weight_group_size;
+    if (g != 32 && g != 64 && g != 128) return fail(STAGE_ERR_CONFIG, "weight_group_size must be 32, 64 or 128, got %d", g);
+    if (c->hidden % g || c->ffn % g || (c->num_q_heads * c->head_dim) % g)
+      return fail(STAGE_ERR_CONFIG, "hidden, num_q_heads*head_dim and ffn must be multiples of weight_group_size %d", g);
+  } else if (c->weight_group_size != 0) {
+    return fail(STAGE_ERR_CONFIG, "weight_group_size must be 0 unless weight_bits is 4");
+  }
   if (c->num_kv_blocks < 1 || c->max_tokens < 1 || c->max_seqs < 1 || c->max_blocks_per_seq < 1)
     return fail(STAGE_ERR_CONFIG, "capacities must be positive");
   const size_t layer_bytes = (size_t)c->num_kv_blocks * c->num_kv_heads * 16 * c->head_dim * 2 * 2;
@@ -133,6 +145,12 @@ WorkspaceLayout layout_of(const stage_config& c) {
   if ((v = gemm_partial_floats(c.max_tokens, d.H, d.F, kEpiResidualF32, kNumCus, sp)) > pf) pf = v;
   if (c.vocab_size > 0 && (v = gemm_partial_floats(c.max_seqs, c.vocab_size, d.H, kEpiStoreF32, kNumCus, false)) > pf) pf = v;
   w.splitk = take(pf * 4 + 16);
+  // 4-bit weights: room for the largest projection (gate and up together) expanded to bf16
+  {
+    size_t elems = (size_t)d.qkv_out * d.H;
+    if ((size_t)2 * d.F * d.H > elems) elems = (size_t)2 * d.F * d.H;
+    w.wexp = take(c.weight_bits == 4 ? elems * 2 : 0);
+  }
   w.head_a = take(c.vocab_size > 0 ? (size_t)c.max_seqs * d.H * 2 : 0);
   w.head_logits = take(c.vocab_size > 0 ? (size_t)c.max_seqs * c.vocab_size * 4 : 0);
   w.ends_meta = take((T > (size_t)c.max_seqs ? T : (size_t)c.max_seqs) * 4 + 256);
@@ -260,6 +278,30 @@ struct Timer {
 __global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float* __restrict__ src, __bf16* __restrict__ dst, size_t n) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i < n) dst[i] = static_cast<__bf16>(src[i]);
+}
+
+// Points a projection's GEMM at its weights.  bf16 weights are used where they lie.  4-bit weights are
+// expanded to bf16 in the workspace first (one projection at a time; `w1` is the second matrix of the
+// gate/up pair or NULL) and the GEMM reads the expanded copy.
+int bind_weights(stage_handle* st, hipStream_t stream, GemmArgs& g, const void* w0, const void* s0, const void* z0,
+                 const void* w1, const void* s1, const void* z1) {
+  if (st->cfg.weight_bits != 4) {
+    g.w0 = (const __bf16*)w0;
+    g.w1 = (const __bf16*)w1;
+    return STAGE_OK;
+  }
+  __bf16* exp0 = (__bf16*)(st->workspace + st->ws.wexp);
+  Timer t(st, stream, STAGE_K_DEQUANT);
+  const W4Matrix m0{(const uint32_t*)w0, (const __bf16*)s0, (const __bf16*)z0};
+  HIP_TRY(launch_dequant_w4(m0, g.n, g.k, st->cfg.weight_group_size, exp0, stream));
+  g.w0 = exp0;
+  if (w1) {
+    __bf16* exp1 = exp0 + (size_t)g.n * g.k;
+    const W4Matrix m1{(const uint32_t*)w1, (const __bf16*)s1, (const __bf16*)z1};
+    HIP_TRY(launch_dequant_w4(m1, g.n, g.k, st->cfg.weight_group_size, exp1, stream));
+    g.w1 = exp1;
+  }
+  return STAGE_OK;
 }
 
 int run_gemm(stage_handle* st, hipStream_t stream, int kernel_class, const GemmArgs& args, GemmEpilogue epi) {
@@ -462,8 +504,9 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       HIP_TRY(hipMemcpyAsync(taps->tap_norm1, a, (size_t)T * d.H * 2, hipMemcpyDeviceToDevice, stream));
     {
       GemmArgs g{};
-      g.a = a; g.a_lo = a_lo; g.w0 = (const __bf16*)w.wqkv; g.out_f32 = qkv_f32; g.partial = splitk;
+      g.a = a; g.a_lo = a_lo; g.out_f32 = qkv_f32; g.partial = splitk;
       g.m = T; g.n = d.qkv_out; g.k = d.H; g.lda = d.H; g.ldo = d.qkv_out;
+      if (int rc = bind_weights(st, stream, g, w.wqkv, w.sqkv, w.zqkv, nullptr, nullptr, nullptr)) return rc;
       // the rotation kernel adds the split-K partial sums itself: no separate reduction pass
       const GemmPlan plan = plan_gemm(g.m, g.n, g.k, kEpiStoreF32, kNumCus, g.a_lo != nullptr);
       {
@@ -494,8 +537,9 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       HIP_TRY(hipMemcpyAsync(taps->tap_attn, attn, (size_t)T * d.nq * d.d * 2, hipMemcpyDeviceToDevice, stream));
     {
       GemmArgs g{};
-      g.a = attn; g.a_lo = attn_lo; g.w0 = (const __bf16*)w.wo; g.resid = x; g.partial = splitk;
+      g.a = attn; g.a_lo = attn_lo; g.resid = x; g.partial = splitk;
       g.m = T; g.n = d.H; g.k = d.nq * d.d; g.lda = d.nq * d.d; g.ldo = d.H;
+      if (int rc = bind_weights(st, stream, g, w.wo, w.so, w.zo, nullptr, nullptr, nullptr)) return rc;
       int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_O, g, kEpiResidualF32, (const __bf16*)w.norm2, a, a_lo);
       if (rc) return rc;
     }
@@ -503,9 +547,10 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       HIP_TRY(hipMemcpyAsync(taps->tap_h, x, (size_t)T * d.H * 4, hipMemcpyDeviceToDevice, stream));
     {
       GemmArgs g{};
-      g.a = a; g.a_lo = a_lo; g.w0 = (const __bf16*)w.wgate; g.w1 = (const __bf16*)w.wup; g.out_bf16 = mlp; g.out_lo = mlp_lo;
+      g.a = a; g.a_lo = a_lo; g.out_bf16 = mlp; g.out_lo = mlp_lo;
       g.partial = splitk;
       g.m = T; g.n = d.F; g.k = d.H; g.lda = d.H; g.ldo = d.F;
+      if (int rc = bind_weights(st, stream, g, w.wgate, w.sgate, w.zgate, w.wup, w.sup, w.zup)) return rc;
       int rc = run_gemm(st, stream, STAGE_K_GEMM_GATEUP, g, kEpiSwiGLU);
       if (rc) return rc;
     }
@@ -516,9 +561,10 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       // kernel, so the tap sees it; the sum and its rounding are the same as in the fused epilogue.
       const bool fused_out = last && !(tap && taps->tap_x);
       GemmArgs g{};
-      g.a = mlp; g.a_lo = mlp_lo; g.w0 = (const __bf16*)w.wdown; g.resid = x; g.out_bf16 = (__bf16*)hidden_out;
+      g.a = mlp; g.a_lo = mlp_lo; g.resid = x; g.out_bf16 = (__bf16*)hidden_out;
       g.partial = splitk;
       g.m = T; g.n = d.H; g.k = d.F; g.lda = d.F; g.ldo = d.H;
+      if (int rc = bind_weights(st, stream, g, w.wdown, w.sdown, w.zdown, nullptr, nullptr, nullptr)) return rc;
       const __bf16* next_gain = last ? nullptr : (const __bf16*)st->layers[l + 1].norm1;
       int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_DOWN, g, fused_out ? kEpiResidualOut : kEpiResidualF32,
                                  next_gain, a, a_lo);
@@ -598,6 +644,13 @@ int stage_init(const stage_config* cfg, const stage_layer_weights* layers, void*
     for (const void* p : ptrs)
       if ((uintptr_t)p % 16) return fail(STAGE_ERR_CONFIG, "layer %d has a weight pointer that is not 16-byte aligned", l);
     if ((uintptr_t)w.bqkv % 16) return fail(STAGE_ERR_CONFIG, "layer %d: bqkv is not 16-byte aligned", l);
+    if (cfg->weight_bits == 4) {
+      const void* q[10] = {w.sqkv, w.so, w.sgate, w.sup, w.sdown, w.zqkv, w.zo, w.zgate, w.zup, w.zdown};
+      for (const void* p : q) {
+        if (!p) return fail(STAGE_ERR_NULL, "layer %d has a NULL scale or zero-point pointer", l);
+        if ((uintptr_t)p % 16) return fail(STAGE_ERR_CONFIG, "layer %d has a scale or zero-point pointer that is not 16-byte aligned", l);
+      }
+    }
   }
   if ((uintptr_t)kv_pool % 256 || (uintptr_t)workspace % 256)
     return fail(STAGE_ERR_CONFIG, "kv_pool and workspace must be 256-byte aligned");
@@ -783,6 +836,7 @@ const char* stage_kernel_name(int32_t kernel) {
     case STAGE_K_HEAD_NORM: return "gather_rmsnorm_kernel";
     case STAGE_K_GEMM_HEAD: return "gemm_bf16_kernel";
     case STAGE_K_HEAD_ARGMAX: return "argmax_rows_kernel";
+    case STAGE_K_DEQUANT: return "dequant_w4_kernel";
     default: return nullptr;
   }
 }

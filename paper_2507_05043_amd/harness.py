@@ -12,10 +12,16 @@ from .stage import Stage, make_config
 def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_std=None,
                max_tokens: Optional[int] = None, alias_layers: bool = False, fill_kv: bool = True,
                device: str = "cuda:0", activation_planes: int = 0, vocab_size: int = 0,
-               qkv_bias: bool = False) -> Stage:
-    """Draw the stage's weights on the device, size the pool and workspace for `mb`, fill the cache."""
-    layers = [synth.draw_layer_weights(shape, l, seed=seed, device=device, weight_std=weight_std)
-              for l in range(shape.num_layers)]
+               qkv_bias: bool = False, weight_group_size: int = 0) -> Stage:
+    """Draw the stage's weights on the device, size the pool and workspace for `mb`, fill the cache.
+    weight_group_size > 0: 4-bit group-quantised projection weights with that group size."""
+    if weight_group_size:
+        layers = [synth.draw_w4_layer(shape, l, seed=seed, group=weight_group_size, device=device,
+                                      weight_std=0.02 if weight_std is None else float(weight_std))
+                  for l in range(shape.num_layers)]
+    else:
+        layers = [synth.draw_layer_weights(shape, l, seed=seed, device=device, weight_std=weight_std)
+                  for l in range(shape.num_layers)]
     if qkv_bias:
         for l, w in enumerate(layers):
             w["bqkv"] = synth.draw_qkv_bias(shape, l, seed=seed, device=device)
@@ -25,7 +31,8 @@ def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_
                       max_tokens=max_tokens or mb.num_tokens, max_seqs=mb.num_seqs,
                       max_blocks_per_seq=mb.max_blocks_per_seq,
                       kv_layer_stride_bytes=0 if alias_layers else None, activation_planes=activation_planes,
-                      vocab_size=vocab_size)
+                      vocab_size=vocab_size, weight_bits=4 if weight_group_size else 0,
+                      weight_group_size=weight_group_size)
     st = Stage(cfg, layers, device=device)
     if fill_kv:
         fill_pool(st, shape, mb, seed)

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libmolink_stage.so")
 KERNEL_CLASSES = {
     "rmsnorm": 0, "gemm_qkv": 1, "rope_append": 2, "attn_prefill": 3, "attn_decode": 4, "attn_merge": 5,
     "gemm_o": 6, "gemm_gateup": 7, "gemm_down": 8, "splitk_reduce": 9, "rope_table": 10,
-    "embed": 11, "head_norm": 12, "gemm_head": 13, "head_argmax": 14,
+    "embed": 11, "head_norm": 12, "gemm_head": 13, "head_argmax": 14, "dequant": 15,
 }
 
 
@@ -38,11 +38,18 @@ class StageConfig(ctypes.Structure):
         ("kv_layer_stride_bytes", ctypes.c_int64),
         ("max_tokens", ctypes.c_int32), ("max_seqs", ctypes.c_int32), ("max_blocks_per_seq", ctypes.c_int32),
         ("activation_planes", ctypes.c_int32), ("vocab_size", ctypes.c_int32),
+        ("weight_bits", ctypes.c_int32), ("weight_group_size", ctypes.c_int32),
     ]
 
 
+W4_MATRICES = ("wqkv", "wo", "wgate", "wup", "wdown")
+W4_SCALES = ("sqkv", "so", "sgate", "sup", "sdown")
+W4_ZEROS = ("zqkv", "zo", "zgate", "zup", "zdown")
+
+
 class StageLayerWeights(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_void_p) for n in ("norm1", "wqkv", "wo", "norm2", "wgate", "wup", "wdown", "bqkv")]
+    _fields_ = [(n, ctypes.c_void_p) for n in ("norm1", "wqkv", "wo", "norm2", "wgate", "wup", "wdown", "bqkv")
+                + W4_SCALES + W4_ZEROS]
 
 
 class StageTaps(ctypes.Structure):
@@ -100,10 +107,11 @@ def _check(rc: int) -> None:
 
 def make_config(*, num_layers, hidden, num_q_heads, num_kv_heads, head_dim, ffn, rms_eps, rope_theta,
                 num_kv_blocks, max_tokens, max_seqs, max_blocks_per_seq, kv_block_size=16,
-                kv_layer_stride_bytes=None, activation_planes=0, vocab_size=0) -> StageConfig:
+                kv_layer_stride_bytes=None, activation_planes=0, vocab_size=0, weight_bits=0,
+                weight_group_size=0) -> StageConfig:
     cfg = StageConfig(ctypes.sizeof(StageConfig), num_layers, hidden, num_q_heads, num_kv_heads, head_dim, ffn,
                       rms_eps, rope_theta, kv_block_size, num_kv_blocks, 0, max_tokens, max_seqs, max_blocks_per_seq,
-                      activation_planes, vocab_size)
+                      activation_planes, vocab_size, weight_bits, weight_group_size)
     if kv_layer_stride_bytes is None:
         kv_layer_stride_bytes = stage_kv_layer_bytes(cfg)
     cfg.kv_layer_stride_bytes = kv_layer_stride_bytes
@@ -164,12 +172,16 @@ class Stage:
         self.layers = [dict(l) for l in layers]          # keep the tensors alive
         arr = (StageLayerWeights * cfg.num_layers)()
         for l, w in enumerate(self.layers):
+            four_bit = cfg.weight_bits == 4
             for name, _ in StageLayerWeights._fields_:
                 if name == "bqkv" and w.get(name) is None:     # the only optional tensor
                     continue
+                if not four_bit and (name in W4_SCALES or name in W4_ZEROS):
+                    continue
                 t = w[name]
-                if t.dtype != torch.bfloat16 or not t.is_contiguous() or t.device != self.device:
-                    raise ValueError(f"layer {l} {name}: need a contiguous bf16 tensor on {self.device}")
+                want = torch.int32 if four_bit and name in W4_MATRICES else torch.bfloat16   # code words / bf16
+                if t.dtype != want or not t.is_contiguous() or t.device != self.device:
+                    raise ValueError(f"layer {l} {name}: need a contiguous {want} tensor on {self.device}")
                 setattr(arr[l], name, t.data_ptr())
         layer_bytes = stage_kv_layer_bytes(cfg)
         pool_bytes = (cfg.num_layers - 1) * cfg.kv_layer_stride_bytes + layer_bytes

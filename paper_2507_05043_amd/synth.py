@@ -298,6 +298,50 @@ def draw_layer_weights(shape: StageShape, layer: int, *, seed: int, device="cpu"
     return out
 
 
+STREAM_W4_BASE = 100000   # + 20*layer + {0..4 code words, 5..9 scales, 10..14 zero points} of the five matrices
+_W4_MATRICES = ("wqkv", "wo", "wgate", "wup", "wdown")
+
+
+def draw_w4_layer(shape: StageShape, layer: int, *, seed: int, group: int, device="cpu",
+                  weight_std: float = 0.02) -> Dict[str, torch.Tensor]:
+    """One layer with 4-bit group-quantised projection matrices, drawn directly in their stored form:
+    code words int32 [N, K/8] of uniformly random bits (every 4-bit code is uniform in 0..15), zero points
+    bf16 [N, K/group], integers uniform in 6..9, scales bf16 [N, K/group] = weight_std/4.74 * u with u uniform
+    in [0.75, 1.25) (code - zero has standard deviation 4.74, so the weights they stand for have about
+    `weight_std`; integer arithmetic and one float32 multiplication, so CPU and GPU draws are bit-identical).
+    Keys: the matrix names hold the code words, "s"/"z" + {qkv,o,gate,up,down} the scales and zero points;
+    the norm gains are those of `draw_layer_weights`."""
+    device = torch.device(device)
+    out = {}
+    for k, kind in enumerate(_WEIGHT_KINDS):
+        if kind.startswith("norm"):
+            out[kind] = draw_normal_bf16(seed, STREAM_LAYER_BASE + 10 * layer + k, shape.hidden, std=0.02, mean=1.0,
+                                         device=device)
+    shapes = weight_shapes(shape)
+    for m, kind in enumerate(_W4_MATRICES):
+        n, kk = shapes[kind]
+        if kk % group or kk % 8:
+            raise ValueError(f"{kind}: {kk} input features are not a multiple of the group size {group}")
+        base = STREAM_W4_BASE + 20 * layer
+        words = n * (kk // 8)
+        code = torch.empty(words, dtype=torch.int32, device=device)
+        chunk = 1 << 24
+        for start in range(0, words, chunk):
+            idx = torch.arange(start, min(words, start + chunk), dtype=torch.int64, device=device)
+            h = hash_u32(seed, base + m, idx)
+            code[start:start + idx.numel()] = (h - ((h >> 31) << 32)).to(torch.int32)   # the same 32 bits, signed
+        groups = n * (kk // group)
+        gi = torch.arange(groups, dtype=torch.int64, device=device)
+        scale = (768 + hash_u32(seed, base + 5 + m, gi) % 512).to(torch.float32) * \
+            torch.tensor(weight_std / 4.74 / 1024.0, dtype=torch.float32, device=device)
+        zero = 6 + hash_u32(seed, base + 10 + m, gi) % 4
+        suffix = kind[1:]
+        out[kind] = code.view(n, kk // 8)
+        out["s" + suffix] = scale.to(torch.bfloat16).view(n, kk // group)
+        out["z" + suffix] = zero.to(torch.bfloat16).view(n, kk // group)
+    return out
+
+
 def draw_qkv_bias(shape: StageShape, layer: int, *, seed: int, device="cpu", std: float = 0.5) -> torch.Tensor:
     """bf16 bias [qkv_out] of a layer's q/k/v projection ~ N(0, std) (for the stages that have one)."""
     return draw_normal_bf16(seed, STREAM_LAYER_BASE + 10 * layer + 7, shape.qkv_out, std=std, device=device)

@@ -63,14 +63,18 @@ def test_handoff_plan_equals_the_model_on_random_layouts(lib):
 
 
 def test_config_struct_matches_header_size(lib):
-    # uint32 + 6 int32 + 2 float + 2 int32 (+ 4 pad) + int64 + 5 int32 (+ 4 pad)
-    assert ctypes.sizeof(S.StageConfig) == 80
+    # uint32 + 6 int32 + 2 float + 2 int32 (+ 4 pad) + int64 + 7 int32 (+ 4 pad)
+    assert ctypes.sizeof(S.StageConfig) == 88
+    assert ctypes.sizeof(S.StageLayerWeights) == 18 * ctypes.sizeof(ctypes.c_void_p)
     assert S.stage_workspace_bytes(tiny_cfg()) > 0
 
 
 @pytest.mark.parametrize("bad", [dict(kv_block_size=32), dict(head_dim=96), dict(hidden=252), dict(num_q_heads=5),
                                  dict(num_q_heads=34, num_kv_heads=2), dict(rms_eps=0.0), dict(num_layers=0),
-                                 dict(activation_planes=3), dict(vocab_size=1001), dict(vocab_size=32)])
+                                 dict(activation_planes=3), dict(vocab_size=1001), dict(vocab_size=32),
+                                 dict(weight_bits=3), dict(weight_group_size=128), dict(weight_bits=4, weight_group_size=48),
+                                 dict(weight_bits=4, weight_group_size=128, ffn=768 + 64),
+                                 dict(weight_bits=4, weight_group_size=128)])   # ffn 688 is no multiple of 128
 def test_unsupported_configs_are_rejected(lib, bad):
     with pytest.raises(StageError) as ei:
         cfg = tiny_cfg(**bad)
@@ -166,8 +170,15 @@ def test_output_head_adds_its_scratch_to_the_workspace(lib):
     assert with_head - base >= 8 * 256 * 2 + 8 * 1000 * 4
 
 
+def test_four_bit_weights_add_room_for_one_expanded_projection(lib):
+    base = S.stage_workspace_bytes(tiny_cfg(ffn=768))
+    w4 = S.stage_workspace_bytes(tiny_cfg(ffn=768, weight_bits=4, weight_group_size=128))
+    assert w4 - base >= 2 * 768 * 256 * 2          # gate and up [F][H] as bf16
+
+
 def test_kernel_names(lib):
     assert S.stage_kernel_name(S.KERNEL_CLASSES["gemm_head"]) == "gemm_bf16_kernel"
     assert S.stage_kernel_name(S.KERNEL_CLASSES["head_argmax"]) == "argmax_rows_kernel"
     assert S.stage_kernel_name(S.KERNEL_CLASSES["attn_decode"]) == "attn_decode_kernel"
+    assert S.stage_kernel_name(S.KERNEL_CLASSES["dequant"]) == "dequant_w4_kernel"
     assert S.stage_kernel_name(99) is None

@@ -1,0 +1,76 @@
+"""GPU parity of stages with 4-bit group-quantised weights: the HIP library (through its C ABI) against the
+CPU oracle run on the matrices the stored form stands for (oracle/w4_oracle.py), same seeded inputs."""
+import pytest
+import torch
+
+from oracle import w4_oracle
+from paper_2507_05043_amd import synth
+from tests import gpu_harness as H
+
+pytestmark = pytest.mark.gpu
+
+# the tiny stage with an inner width that every supported group size divides
+W4_TINY = synth.StageShape("tiny-w4", 2, 256, 4, 2, 64, 768)
+
+
+def w4_parity(shape, mb, seed, group, activation_planes=0, check_kv=True):
+    print(f"[case] {shape.name} 4-bit group={group} T={mb.num_tokens} S={mb.num_seqs} q={mb.q_lens[:6]} "
+          f"ctx={mb.ctx_lens[:6]} seed={seed} planes={activation_planes}", flush=True)
+    st = H.make_stage(shape, mb, seed, weight_group_size=group, activation_planes=activation_planes)
+    before = H.snapshot_pool(st, shape, mb) if check_kv else None
+    stored = [synth.draw_w4_layer(shape, l, seed=seed, group=group) for l in range(shape.num_layers)]
+    for l, lw in enumerate(stored):          # the GPU stage was built from the same stored form, bit for bit
+        for k, v in lw.items():
+            assert torch.equal(st.layers[l][k].cpu().view(torch.int16 if v.dtype == torch.bfloat16 else v.dtype),
+                               v.view(torch.int16 if v.dtype == torch.bfloat16 else v.dtype)), (l, k)
+    layers = [w4_oracle.dequantize_layer(lw, group) for lw in stored]
+    ref, ref_slots, ref_pool, _ = H.run_oracle(shape, mb, seed, layers=layers)
+    out, slots = H.run_gpu(st, shape, mb, seed)
+    assert slots == ref_slots
+    stats = H.check_output(out, ref)
+    if check_kv:
+        H.check_pool(st, shape, mb, ref_pool, before, slots)
+    print(f"  output rel-L2 {stats['rel_l2']:.3e} max-abs {stats['max_abs']:.3e} rms {stats['rms']:.3f}", flush=True)
+    st.close()
+    return stats
+
+
+@pytest.mark.parametrize("group", [32, 64, 128])
+def test_tiny_mixed_batch(group):
+    mb = synth.make_microbatch([32, 32, 1, 1, 1, 1, 1, 1], [0, 0, 16, 37, 52, 64, 81, 100], seed=0, max_blocks_per_seq=12)
+    w4_parity(W4_TINY, mb, 0, group)
+
+
+@pytest.mark.parametrize("n_decode", [1, 7, 64])
+def test_decode_micro_batches(n_decode):
+    ctx = [17 + 13 * i % 90 for i in range(n_decode)]
+    mb = synth.make_microbatch([1] * n_decode, ctx, seed=1, max_blocks_per_seq=8)
+    w4_parity(W4_TINY, mb, 1, 128)
+
+
+def test_two_activation_planes():
+    mb = synth.make_microbatch([40, 1, 1, 1], [0, 30, 5, 66], seed=2, max_blocks_per_seq=8)
+    w4_parity(W4_TINY, mb, 2, 128, activation_planes=2)
+
+
+def test_ragged_rows_and_longer_k():
+    # 200 rows (not a multiple of any tile), hidden 1024, inner width 2816 = 22 groups of 128
+    shape = synth.StageShape("w4-mid", 2, 1024, 8, 2, 128, 2816)
+    mb = synth.make_microbatch([130, 61, 1, 1, 1, 1, 1, 1, 1, 1, 1], [0, 40] + [20 + 9 * i for i in range(9)], seed=3,
+                               max_blocks_per_seq=16)
+    w4_parity(shape, mb, 3, 128)
+
+
+def test_missing_scales_are_rejected():
+    from paper_2507_05043_amd import StageError
+    from paper_2507_05043_amd.stage import Stage, make_config
+    mb = synth.make_microbatch([4], [0], seed=0, max_blocks_per_seq=2)
+    layers = [synth.draw_w4_layer(W4_TINY, l, seed=0, group=128, device="cuda:0") for l in range(2)]
+    cfg = make_config(num_layers=2, hidden=256, num_q_heads=4, num_kv_heads=2, head_dim=64, ffn=768, rms_eps=1e-5,
+                      rope_theta=1e4, num_kv_blocks=mb.num_kv_blocks, max_tokens=8, max_seqs=2, max_blocks_per_seq=2,
+                      weight_bits=4, weight_group_size=128)
+    st = Stage(cfg, layers)
+    st.close()
+    del layers[1]["zdown"]
+    with pytest.raises(KeyError):
+        Stage(cfg, layers)
