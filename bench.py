@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
-def algorithmic_work(shape, mb):
+def algorithmic_work(shape, mb, weight_bytes_per_param=2.0):
     """Bytes and flops the method must move / compute per call (weights once, KV once per KV head)."""
     kv_tok = 4 * shape.num_kv_heads * shape.head_dim                       # K+V bytes per token per layer
     dec_keys = sum(c + 1 for q, c in zip(mb.q_lens, mb.ctx_lens) if q == 1)
@@ -38,10 +38,11 @@ def algorithmic_work(shape, mb):
     attn_flops = 0
     for q, c in zip(mb.q_lens, mb.ctx_lens):
         attn_flops += 4 * shape.num_q_heads * shape.head_dim * sum(c + i + 1 for i in range(q))
-    per_layer_bytes = 2 * shape.params_per_layer + (dec_keys + pre_keys) * kv_tok + t * kv_tok
+    weight_bytes = int(weight_bytes_per_param * shape.params_per_layer)
+    per_layer_bytes = weight_bytes + (dec_keys + pre_keys) * kv_tok + t * kv_tok
     return {
         "decode_attn_bytes_per_layer": dec_keys * kv_tok,
-        "weight_bytes_per_layer": 2 * shape.params_per_layer,
+        "weight_bytes_per_layer": weight_bytes,
         "bytes_per_call": shape.num_layers * per_layer_bytes + 2 * t * shape.hidden * 2,
         "gemm_flops_per_layer": 2 * shape.params_per_layer * t,
         "attn_flops_per_layer": attn_flops,
@@ -91,6 +92,8 @@ def main():
     ap.add_argument("--workload", default="llama2-7b", choices=["tiny", "llama2-7b", "qwen2-7b", "llama3-70b", "sweep"])
     ap.add_argument("--budget", type=int, default=256, help="token budget of the sweep workload")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--weights", default="bf16", choices=["bf16", "w4"],
+                    help="w4: 4-bit projection weights in groups of 128 (a variant, not the benchmark configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ends", action="store_true",
                     help="also time the pipeline's two ends (embedding; final norm + output head + greedy choice)")
@@ -118,11 +121,14 @@ def main():
     from paper_2507_05043_amd.harness import make_stage
 
     shape, mb = synth.workload(args.workload, seed=args.seed, budget=args.budget)
-    work = algorithmic_work(shape, mb)
+    w4 = args.weights == "w4"
+    # 4 bits per weight plus a bf16 scale and a bf16 zero point per 128 weights
+    work = algorithmic_work(shape, mb, 0.5 + 4.0 / 128 if w4 else 2.0)
     kv_bytes = shape.num_layers * mb.num_kv_blocks * 16 * 4 * shape.num_kv_heads * shape.head_dim
-    alias = kv_bytes + 2 * shape.params_per_layer * shape.num_layers > 250e9     # timing only: layers share one pool
+    alias = kv_bytes + work["weight_bytes_per_layer"] * shape.num_layers > 250e9     # timing only: layers share one pool
     st = make_stage(shape, mb, args.seed, alias_layers=alias, vocab_size=shape.vocab if args.ends else 0,
-                    qkv_bias=args.workload == "qwen2-7b")     # the Qwen2 family has a q/k/v bias
+                    qkv_bias=args.workload == "qwen2-7b",     # the Qwen2 family has a q/k/v bias
+                    weight_group_size=128 if w4 else 0)
     hidden = synth.draw_hidden(shape, mb.num_tokens, seed=args.seed, device="cuda:0")
     out = torch.empty_like(hidden)
     n_dec = sum(1 for q in mb.q_lens if q == 1)
@@ -172,7 +178,8 @@ def main():
         "config": {"workload": f"{shape.name}: L={shape.num_layers} H={shape.hidden} nq={shape.num_q_heads} "
                                f"nkv={shape.num_kv_heads} d={shape.head_dim} F={shape.ffn}; micro-batch T={mb.num_tokens} "
                                f"S={mb.num_seqs} ({mb.num_seqs - n_dec} prefill chunks, {n_dec} decode tokens), KV block 16",
-                   "seed": args.seed, "kv_layers_aliased": bool(alias)},
+                   "seed": args.seed, "kv_layers_aliased": bool(alias),
+                   "weights": "4-bit codes, bf16 scale and zero point per 128 input features" if w4 else "bf16"},
         "stage_latency_ms": round(ms_per_step, 4),
         "ideal_ms": {"hbm": round(work["bytes_per_call"] / (HBM_PEAK_GBS * 1e9) * 1e3, 4),
                      "mfma": round(work["flops_per_call"] / (MFMA_BF16_PEAK_TFLOPS * 1e12) * 1e3, 4)},
@@ -188,6 +195,10 @@ def main():
         torch.cuda.synchronize()
         result["breakdown_ms_per_step"] = {n: round(st.profile_read(n)[0] / reps, 5) for n in names}
         st.profile_enable([])
+        proj_ms = sum(result["breakdown_ms_per_step"][n] for n in ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down", "dequant"))
+        result["projections"] = {"ms_per_step": round(proj_ms, 5),
+                                 "weight_bytes_per_step": work["weight_bytes_per_layer"] * shape.num_layers,
+                                 "weight_stream_GBps": round(work["weight_bytes_per_layer"] * shape.num_layers / (proj_ms * 1e-3) / 1e9, 1)}
 
     if args.ends:
         # The pipeline's two ends, timed on their own after the stage (not part of `value`): token
@@ -210,7 +221,7 @@ def main():
                           "head_gemm_GBps": round(head_bytes / (ms["gemm_head"] * 1e-3) / 1e9, 1),
                           "head_gemm_algorithmic_bytes": head_bytes}
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not w4:     # the oracle baseline is timed on the benchmark configuration (bf16 weights)
         sample = {"tiny": mb.num_seqs, "llama2-7b": 64, "qwen2-7b": 8, "llama3-70b": 4, "sweep": 4}[args.workload]
         result["cpu_baseline"] = cpu_baseline(shape, mb, args.seed, sample)
     st.close()

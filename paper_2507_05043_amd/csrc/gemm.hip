@@ -16,6 +16,7 @@
 // applies the epilogue.  Micro-batches of at most 64 rows (decode) have a kernel of their own,
 // gemm_skinny_kernel below, built around streaming the weights.
 #include "gemm.hpp"
+#include "w4.hpp"
 #include "common.hpp"
 
 #include <type_traits>
@@ -667,6 +668,7 @@ size_t gemm_partial_floats(int max_m, int n, int k, GemmEpilogue epi, int num_cu
 hipError_t launch_gemm_main(const GemmArgs& a, GemmEpilogue epi, const GemmPlan& plan, hipStream_t stream) {
   if (plan.tile == kTileSkinny) {
     if (a.m > 64 || a.a_lo) return hipErrorInvalidValue;
+    if (a.q0.codes) return launch_gemm_skinny_w4(a, plan.nv, plan.splits, epi == kEpiSwiGLU ? 1 : 0, stream);
     const int groups = (plan.nv + kSkinnyRows - 1) / kSkinnyRows;
     const long units = (long)groups * plan.splits;
     const int cus = 256;
@@ -676,6 +678,7 @@ hipError_t launch_gemm_main(const GemmArgs& a, GemmEpilogue epi, const GemmPlan&
                        epi == kEpiSwiGLU ? 1 : 0);
     return hipGetLastError();
   }
+  if (a.q0.codes) return hipErrorInvalidValue;   // the tiled kernels take bf16 weights only
   switch (epi) {
     case kEpiStoreF32: return launch_epi<kEpiStoreF32>(a, plan, stream);
     case kEpiResidualF32: return launch_epi<kEpiResidualF32>(a, plan, stream);

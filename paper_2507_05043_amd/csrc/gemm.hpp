@@ -12,6 +12,14 @@ enum GemmEpilogue : int {
   kEpiSwiGLU = 3,       // out_bf16[m][f] = silu(acc_gate[f]) * acc_up[f]
 };
 
+// One 4-bit group-quantised matrix [n][k]: codes uint32 [n][k/8] (element k in bits 4*(k%8).. of word k/8),
+// scales and zero points bf16 [n][k/group];  W[n][k] = (code - zero) * scale.
+struct W4Matrix {
+  const uint32_t* codes;
+  const __bf16* scales;
+  const __bf16* zeros;
+};
+
 struct GemmArgs {
   const __bf16* a;      // [M][lda]
   const __bf16* a_lo;   // optional second plane [M][lda]: the activations are a + a_lo (the part of the fp32
@@ -20,6 +28,8 @@ struct GemmArgs {
   __bf16* out_lo;       // SwiGLU epilogue only, optional: receives bf16(result - bf16(result)) [M][ldo]
   const __bf16* w0;     // [N][K]; for SwiGLU the gate matrix [F][K]
   const __bf16* w1;     // SwiGLU only: the up matrix [F][K]
+  W4Matrix q0, q1;      // q0.codes != nullptr: the weights are 4-bit (groups of 128) and w0 / w1 are unused;
+                        // only plans of the weight-streaming kind (at most 64 rows) take them
   __bf16* out_bf16;     // see GemmEpilogue
   float* out_f32;       // kEpiStoreF32 output [M][ldo]
   float* resid;         // fp32 residual stream [M][N]

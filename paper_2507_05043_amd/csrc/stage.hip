@@ -280,7 +280,8 @@ __global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float* __restric
   if (i < n) dst[i] = static_cast<__bf16>(src[i]);
 }
 
-// Points a projection's GEMM at its weights.  bf16 weights are used where they lie.  4-bit weights are
+// Points a projection's GEMM at its weights.  bf16 weights are used where they lie.  4-bit weights go to
+// the weight-streaming kernel as they are stored when the micro-batch is decode-sized; otherwise they are
 // expanded to bf16 in the workspace first (one projection at a time; `w1` is the second matrix of the
 // gate/up pair or NULL) and the GEMM reads the expanded copy.
 int bind_weights(stage_handle* st, hipStream_t stream, GemmArgs& g, const void* w0, const void* s0, const void* z0,
@@ -290,9 +291,15 @@ int bind_weights(stage_handle* st, hipStream_t stream, GemmArgs& g, const void* 
     g.w1 = (const __bf16*)w1;
     return STAGE_OK;
   }
+  const W4Matrix m0{(const uint32_t*)w0, (const __bf16*)s0, (const __bf16*)z0};
+  if (skinny_w4_supports(g.m, g.k, st->cfg.weight_group_size, g.a_lo != nullptr)) {
+    // decode-sized micro-batch: the weight-streaming kernel reads the stored form itself
+    g.q0 = m0;
+    if (w1) g.q1 = W4Matrix{(const uint32_t*)w1, (const __bf16*)s1, (const __bf16*)z1};
+    return STAGE_OK;
+  }
   __bf16* exp0 = (__bf16*)(st->workspace + st->ws.wexp);
   Timer t(st, stream, STAGE_K_DEQUANT);
-  const W4Matrix m0{(const uint32_t*)w0, (const __bf16*)s0, (const __bf16*)z0};
   HIP_TRY(launch_dequant_w4(m0, g.n, g.k, st->cfg.weight_group_size, exp0, stream));
   g.w0 = exp0;
   if (w1) {

@@ -4,17 +4,21 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-namespace molink {
+#include "gemm.hpp"
 
-// One quantised matrix [n][k]: codes uint32 [n][k/8] (element k in bits 4*(k%8).. of word k/8), scales and
-// zero points bf16 [n][k/group].
-struct W4Matrix {
-  const uint32_t* codes;
-  const __bf16* scales;
-  const __bf16* zeros;
-};
+namespace molink {
 
 // Writes the matrix as bf16 [n][k] (the product formed in fp32, rounded once).  k % group == 0, group % 8 == 0.
 hipError_t launch_dequant_w4(const W4Matrix& w, int n, int k, int group, __bf16* out, hipStream_t stream);
+
+// Whether the weight-streaming kernel below takes this shape as it is stored (otherwise the caller expands
+// the matrix with launch_dequant_w4 and runs a bf16 GEMM): at most 64 rows, one activation plane, groups
+// of 128, an even number of groups per row.
+bool skinny_w4_supports(int m, int k, int group, bool two_planes);
+
+// Decode-sized GEMM on 4-bit weights, args.q0 (and args.q1 for the gate/up pair) in place of w0 / w1.
+// Same decomposition and output as the bf16 weight-streaming kernel: fp32 partial sums
+// [splits][m][nv] in args.partial, to be added by the reduction kernels.
+hipError_t launch_gemm_skinny_w4(const GemmArgs& args, int nv, int splits, int swiglu, hipStream_t stream);
 
 }  // namespace molink

@@ -48,6 +48,24 @@ def test_decode_micro_batches(n_decode):
     w4_parity(W4_TINY, mb, 1, 128)
 
 
+@pytest.mark.parametrize("n_decode", [11, 20, 40, 64])
+def test_decode_streams_the_stored_form_with_a_ragged_last_slice(n_decode):
+    # inner width 2816 = 2.75 slices of 1024: the down projection's last slice is partly empty; 1..4 blocks of rows
+    shape = synth.StageShape("w4-mid", 2, 1024, 8, 2, 128, 2816)
+    ctx = [5 + 17 * i % 120 for i in range(n_decode)]
+    mb = synth.make_microbatch([1] * n_decode, ctx, seed=4, max_blocks_per_seq=10)
+    st = H.make_stage(shape, mb, 4, weight_group_size=128)
+    st.profile_enable(["dequant", "gemm_qkv", "gemm_down"])
+    out1, _ = H.run_gpu(st, shape, mb, 4)
+    assert st.profile_read("dequant")[1] == 0          # nothing was expanded: the GEMMs read the codes
+    assert st.profile_read("gemm_down")[1] == shape.num_layers
+    H.fill_pool(st, shape, mb, 4)
+    out2, _ = H.run_gpu(st, shape, mb, 4)
+    assert torch.equal(out1, out2)                     # fixed summation order
+    st.close()
+    w4_parity(shape, mb, 4, 128)
+
+
 def test_two_activation_planes():
     mb = synth.make_microbatch([40, 1, 1, 1], [0, 30, 5, 66], seed=2, max_blocks_per_seq=8)
     w4_parity(W4_TINY, mb, 2, 128, activation_planes=2)
