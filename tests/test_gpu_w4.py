@@ -48,7 +48,7 @@ def test_decode_micro_batches(n_decode):
     w4_parity(W4_TINY, mb, 1, 128)
 
 
-@pytest.mark.parametrize("n_decode", [11, 20, 40, 64])
+@pytest.mark.parametrize("n_decode", [11, 20, 32, 40, 48, 64])
 def test_decode_streams_the_stored_form_with_a_ragged_last_slice(n_decode):
     # inner width 2816 = 2.75 slices of 1024: the down projection's last slice is partly empty; 1..4 blocks of rows
     shape = synth.StageShape("w4-mid", 2, 1024, 8, 2, 128, 2816)
