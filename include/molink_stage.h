@@ -235,6 +235,22 @@ int stage_head(stage_handle *st, void *hip_stream, int32_t num_tokens, const voi
                void *logits_out, int32_t *next_tokens);
 
 /*
+ * Start-up profiling (paper section 4.1: "each engine measures computation latency across batch sizes and
+ * sequence lengths" when it starts; the scheduler sizes its micro-batches from that table).  One point of
+ * the table: the stage's latency for a micro-batch of num_seqs sequences, each with q_len new tokens
+ * (1 = decode, > 1 = a prefill chunk) after ctx_len cached ones.  Runs stage_forward on such a micro-batch
+ * `warmup` times untimed and `iters` times timed (HIP events on hip_stream), synchronises, and writes
+ * milliseconds per micro-batch to out_ms.  Sequence s is paged onto blocks s*B .. s*B+B-1 (B = blocks of
+ * ctx_len + q_len tokens): the runs append to those blocks and read whatever the pool holds there, so
+ * this belongs before the pool holds live sequences.  The values in hidden_in do not matter for the time.
+ *   hidden_in / hidden_out   device bf16 [num_seqs * q_len][H], not overlapping
+ * Errors: STAGE_ERR_NULL, STAGE_ERR_BATCH (counts outside the stage's capacities), STAGE_ERR_BLOCK_TABLE
+ * (the sequences do not fit the block tables or the pool), STAGE_ERR_ALIAS, STAGE_ERR_HIP.
+ */
+int stage_profile(stage_handle *st, void *hip_stream, int32_t num_seqs, int32_t q_len, int32_t ctx_len,
+                  int32_t warmup, int32_t iters, const void *hidden_in, void *hidden_out, double *out_ms);
+
+/*
  * Per-kernel timing with HIP events recorded on the stream the kernels are launched on.
  * stage_profile_enable(st, mask): bit k of mask turns timing of kernel class k on (0 = off).
  * stage_profile_read: synchronises the events recorded so far, adds up the elapsed time of

@@ -711,6 +711,56 @@ int stage_forward_taps(stage_handle* st, void* hip_stream, int32_t num_tokens, c
                       hidden_out, slot_mapping_out, taps);
 }
 
+// Start-up profiling: one point of the latency table (see the header).  Identity paging: sequence s owns the
+// blocks s * B .. s * B + B - 1, B = blocks of ctx_len + q_len tokens.
+int stage_profile(stage_handle* st, void* hip_stream, int32_t num_seqs, int32_t q_len, int32_t ctx_len, int32_t warmup,
+                  int32_t iters, const void* hidden_in, void* hidden_out, double* out_ms) {
+  if (!st || !out_ms) return fail(STAGE_ERR_NULL, "stage handle or out_ms is NULL");
+  const stage_config& c = st->cfg;
+  if (num_seqs < 1 || q_len < 1 || ctx_len < 0 || warmup < 0 || iters < 1)
+    return fail(STAGE_ERR_BATCH, "stage_profile: need num_seqs, q_len, iters >= 1 and ctx_len, warmup >= 0");
+  const int64_t T = (int64_t)num_seqs * q_len;
+  const int64_t blocks = ((int64_t)ctx_len + q_len + 15) / 16;
+  if (num_seqs > c.max_seqs || T > c.max_tokens)
+    return fail(STAGE_ERR_BATCH, "stage_profile: %d sequences of %d new tokens exceed max_seqs %d / max_tokens %d", num_seqs,
+                q_len, c.max_seqs, c.max_tokens);
+  if (blocks > c.max_blocks_per_seq || blocks * num_seqs > c.num_kv_blocks)
+    return fail(STAGE_ERR_BLOCK_TABLE, "stage_profile: %d sequences of %lld blocks exceed the block tables or the pool",
+                num_seqs, (long long)blocks);
+  std::vector<int32_t> positions((size_t)T), q_lens((size_t)num_seqs, q_len), ctx_lens((size_t)num_seqs, ctx_len);
+  std::vector<int32_t> tables((size_t)num_seqs * c.max_blocks_per_seq, -1);
+  for (int s = 0; s < num_seqs; ++s) {
+    for (int i = 0; i < q_len; ++i) positions[(size_t)s * q_len + i] = ctx_len + i;
+    for (int b = 0; b < blocks; ++b) tables[(size_t)s * c.max_blocks_per_seq + b] = (int32_t)(s * blocks + b);
+  }
+  hipStream_t stream = (hipStream_t)hip_stream;
+  HIP_TRY(hipSetDevice(st->device));
+  hipEvent_t begin, end;
+  HIP_TRY(hipEventCreate(&begin));
+  if (hipEventCreate(&end) != hipSuccess) {
+    (void)hipEventDestroy(begin);
+    return fail(STAGE_ERR_HIP, "hipEventCreate failed");
+  }
+  int rc = STAGE_OK;
+  for (int i = 0; i < warmup + iters && rc == STAGE_OK; ++i) {
+    if (i == warmup && hipEventRecord(begin, stream) != hipSuccess) rc = fail(STAGE_ERR_HIP, "hipEventRecord failed");
+    if (rc == STAGE_OK)
+      rc = forward_impl(st, hip_stream, (int32_t)T, hidden_in, positions.data(), num_seqs, q_lens.data(), ctx_lens.data(),
+                        tables.data(), hidden_out, nullptr, nullptr);
+  }
+  if (rc == STAGE_OK) {
+    float ms = 0.f;
+    if (hipEventRecord(end, stream) != hipSuccess || hipEventSynchronize(end) != hipSuccess ||
+        hipEventElapsedTime(&ms, begin, end) != hipSuccess)
+      rc = fail(STAGE_ERR_HIP, "timing the profiled runs failed: %s", hipGetErrorString(hipGetLastError()));
+    else
+      *out_ms = (double)ms / iters;
+  }
+  (void)hipEventDestroy(begin);
+  (void)hipEventDestroy(end);
+  return rc;
+}
+
 // Copies a small host array to the device through a pinned staging slot (the caller may reuse the host
 // array as soon as the call returns).
 static int stage_small_h2d(stage_handle* st, hipStream_t stream, const void* host, size_t bytes, void* dev) {

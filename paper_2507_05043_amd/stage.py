@@ -85,6 +85,8 @@ def load_library() -> ctypes.CDLL:
                                 ctypes.c_void_p]
     lib.stage_head.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, i32p,
                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+    lib.stage_profile.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int32] * 5 + [
+        ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double)]
     lib.stage_profile_enable.argtypes = [ctypes.c_void_p, ctypes.c_uint32]
     lib.stage_profile_read.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_double), i64p]
     lib.stage_kernel_name.argtypes = [ctypes.c_int32]
@@ -93,8 +95,8 @@ def load_library() -> ctypes.CDLL:
     lib.stage_destroy.restype = None
     lib.stage_last_error.restype = ctypes.c_char_p
     for name in ("stage_kv_layer_bytes", "stage_kv_element_offset", "stage_check_batch", "stage_workspace_bytes",
-                 "stage_init", "stage_forward", "stage_forward_taps", "stage_profile_enable", "stage_profile_read",
-                 "stage_embed", "stage_head"):
+                 "stage_init", "stage_forward", "stage_forward_taps", "stage_profile", "stage_profile_enable",
+                 "stage_profile_read", "stage_embed", "stage_head"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -231,6 +233,19 @@ class Stage:
             order = torch.tensor(self._K_SLOT_OF_POSITION, device=v.device)  # slot of position == position of slot
             return v.reshape(n, 16, nkv, pieces * 32)[:, order]
         return self.v_view(layer)[blocks].permute(0, 3, 1, 2)
+
+    # ---- start-up profiling: one point of the latency table, timed by the library
+    def profile(self, num_seqs: int, q_len: int, ctx_len: int, *, warmup: int = 2, iters: int = 5) -> float:
+        """Milliseconds per micro-batch of `num_seqs` sequences with `q_len` new tokens after `ctx_len` cached ones."""
+        t = num_seqs * q_len
+        hidden = torch.zeros(max(t, 1), self.cfg.hidden, dtype=torch.bfloat16, device=self.device)
+        out = torch.empty_like(hidden)
+        ms = ctypes.c_double()
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        _check(load_library().stage_profile(self._handle, ctypes.c_void_p(stream), num_seqs, q_len, ctx_len, warmup, iters,
+                                            ctypes.c_void_p(hidden.data_ptr()), ctypes.c_void_p(out.data_ptr()),
+                                            ctypes.byref(ms)))
+        return ms.value
 
     # ---- the forward pass
     def forward(self, hidden: torch.Tensor, positions, q_lens, ctx_lens, block_tables, *,

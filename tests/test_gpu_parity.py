@@ -181,10 +181,30 @@ def test_startup_profile_table():
         print("  " + line, flush=True)
     assert all(v > 0 for v in dec.values()) and all(v > 0 for v in pre.values())
     assert dec[(64, 4096)] > dec[(16, 512)] and pre[(512, 1024)] > pre[(64, 0)]
-    with pytest.raises(ValueError):
-        profiler.profile_decode(st, [65], [512])
-    with pytest.raises(ValueError):
-        profiler.profile_decode(st, [64], [8192])
+    with pytest.raises(StageError) as ei:
+        profiler.profile_decode(st, [65], [512])            # more sequences than max_seqs
+    assert ei.value.code == -4
+    with pytest.raises(StageError) as ei:
+        profiler.profile_decode(st, [64], [8192])           # does not fit the block tables
+    assert ei.value.code == -5
+    # the library's timing agrees with timing the same micro-batch from outside (same order of magnitude),
+    # and the profiled run really is a forward pass: it appended the 16 new tokens' keys to block 0
+    import time
+    st.kv_pool.view(torch.bfloat16).fill_(7.0)
+    ms = st.profile(1, 16, 0, warmup=1, iters=3)
+    head0 = st.kv_pool.view(torch.bfloat16)[:16 * 128].float()     # block 0, KV head 0: all 16 slots were appended
+    assert (head0 == 0).all()                                       # keys of an all-zero input are zero, not the 7s
+    assert (st.kv_pool.view(torch.bfloat16)[8 * 16 * 128:8 * 16 * 128 + 2048].float() == 7).all()   # block 1 untouched
+    hidden = torch.zeros(16, 1024, dtype=torch.bfloat16, device="cuda:0")
+    tables = torch.full((1, st.cfg.max_blocks_per_seq), -1, dtype=torch.int32)
+    tables[0, 0] = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(3):
+        st.forward(hidden, list(range(16)), [16], [0], tables)
+    torch.cuda.synchronize()
+    outside = (time.perf_counter() - t0) / 3 * 1e3
+    assert 0.2 * ms < outside < 20 * ms + 1.0, (ms, outside)
     st.close()
 
 
