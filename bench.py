@@ -94,6 +94,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--weights", default="bf16", choices=["bf16", "w4"],
                     help="w4: 4-bit projection weights in groups of 128 (a variant, not the benchmark configuration)")
+    ap.add_argument("--dtype", default="bf16", choices=["bf16", "f16"],
+                    help="f16: the IEEE-half library (a variant, not the benchmark configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ends", action="store_true",
                     help="also time the pipeline's two ends (embedding; final norm + output head + greedy choice)")
@@ -115,21 +117,22 @@ def main():
         return
     from paper_2507_05043_amd import KERNEL_CLASSES, synth
     from paper_2507_05043_amd import stage as _stage
-    if not os.path.exists(_stage.LIB_PATH):
+    if not all(os.path.exists(p) for p in _stage.LIB_PATHS.values()):
         import __graft_entry__
         __graft_entry__.build()
     from paper_2507_05043_amd.harness import make_stage
 
     shape, mb = synth.workload(args.workload, seed=args.seed, budget=args.budget)
     w4 = args.weights == "w4"
+    elem = torch.float16 if args.dtype == "f16" else torch.bfloat16
     # 4 bits per weight plus a bf16 scale and a bf16 zero point per 128 weights
     work = algorithmic_work(shape, mb, 0.5 + 4.0 / 128 if w4 else 2.0)
     kv_bytes = shape.num_layers * mb.num_kv_blocks * 16 * 4 * shape.num_kv_heads * shape.head_dim
     alias = kv_bytes + work["weight_bytes_per_layer"] * shape.num_layers > 250e9     # timing only: layers share one pool
     st = make_stage(shape, mb, args.seed, alias_layers=alias, vocab_size=shape.vocab if args.ends else 0,
                     qkv_bias=args.workload == "qwen2-7b",     # the Qwen2 family has a q/k/v bias
-                    weight_group_size=128 if w4 else 0)
-    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=args.seed, device="cuda:0")
+                    weight_group_size=128 if w4 else 0, dtype=elem)
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=args.seed, device="cuda:0", dtype=elem)
     out = torch.empty_like(hidden)
     n_dec = sum(1 for q in mb.q_lens if q == 1)
     decode_bound = work["decode_attn_bytes_per_layer"] / (HBM_PEAK_GBS * 1e9) >= \
@@ -160,7 +163,7 @@ def main():
         roofline = {"kernel": _stage.stage_kernel_name(KERNEL_CLASSES[dominant]), "bound": "hbm",
                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBS, 4),
-                    "traffic": measured_traffic(dominant, args.workload, args.seed),
+                    "traffic": measured_traffic(dominant, args.workload, args.seed) if args.dtype == "bf16" and not w4 else None,
                     "avg_launch_ms": round(avg_ms, 5), "launches": dom_n,
                     "algorithmic_bytes_per_launch": work["decode_attn_bytes_per_layer"]}
     else:
@@ -174,12 +177,12 @@ def main():
     result = {
         "metric": "stage_tokens_per_sec", "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": f"{shape.name}: L={shape.num_layers} H={shape.hidden} nq={shape.num_q_heads} "
                                f"nkv={shape.num_kv_heads} d={shape.head_dim} F={shape.ffn}; micro-batch T={mb.num_tokens} "
                                f"S={mb.num_seqs} ({mb.num_seqs - n_dec} prefill chunks, {n_dec} decode tokens), KV block 16",
                    "seed": args.seed, "kv_layers_aliased": bool(alias),
-                   "weights": "4-bit codes, bf16 scale and zero point per 128 input features" if w4 else "bf16"},
+                   "weights": f"4-bit codes, {args.dtype} scale and zero point per 128 input features" if w4 else args.dtype},
         "stage_latency_ms": round(ms_per_step, 4),
         "ideal_ms": {"hbm": round(work["bytes_per_call"] / (HBM_PEAK_GBS * 1e9) * 1e3, 4),
                      "mfma": round(work["flops_per_call"] / (MFMA_BF16_PEAK_TFLOPS * 1e12) * 1e3, 4)},
@@ -203,7 +206,7 @@ def main():
     if args.ends:
         # The pipeline's two ends, timed on their own after the stage (not part of `value`): token
         # embedding of the micro-batch and final norm + vocabulary projection + greedy choice.
-        ends = synth.draw_ends_weights(shape, seed=args.seed, device="cuda:0")
+        ends = synth.draw_ends_weights(shape, seed=args.seed, device="cuda:0", dtype=elem)
         ids = synth.draw_token_ids(shape, mb.num_tokens, seed=args.seed)
         names = ["embed", "head_norm", "gemm_head", "head_argmax"]
         reps = max(3, min(args.steps, 20))
@@ -221,7 +224,7 @@ def main():
                           "head_gemm_GBps": round(head_bytes / (ms["gemm_head"] * 1e-3) / 1e9, 1),
                           "head_gemm_algorithmic_bytes": head_bytes}
 
-    if not args.no_cpu_baseline and not w4:     # the oracle baseline is timed on the benchmark configuration (bf16 weights)
+    if not args.no_cpu_baseline and not w4 and args.dtype == "bf16":     # the oracle baseline is timed on the benchmark configuration
         sample = {"tiny": mb.num_seqs, "llama2-7b": 64, "qwen2-7b": 8, "llama3-70b": 4, "sweep": 4}[args.workload]
         result["cpu_baseline"] = cpu_baseline(shape, mb, args.seed, sample)
     st.close()

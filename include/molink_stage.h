@@ -21,6 +21,13 @@
  * Every entry point returns 0 on success or a negative STAGE_ERR_* code and never throws;
  * stage_last_error() gives a message for the calling thread's last failure.
  *
+ * Element type.  The same sources build two libraries with this one ABI: libmolink_stage.so stores
+ * every 16-bit tensor (weights, activations, KV cache, payload, 4-bit scales and zero points) as
+ * bfloat16, libmolink_stage_f16.so as IEEE half, the precision the paper serves its 7B model in
+ * (section 5, "Models").  Wherever this header says bf16 it means the loaded library's element type;
+ * stage_elem_type() tells which one that is.  Accumulation, softmax, norms and the residual stream are
+ * fp32 in both.
+ *
  * The library targets gfx950 only and requires kv_block_size == 16, head_dim in {64, 128},
  * hidden and ffn multiples of 8 and at least 64, num_q_heads a multiple of num_kv_heads
  * with at most 16 query heads per KV head.
@@ -288,6 +295,11 @@ void stage_destroy(stage_handle *st);
 
 /* Message describing the calling thread's most recent error ("" if none). */
 const char *stage_last_error(void);
+
+/* The 16-bit element type this library was built for (see "Element type" at the top): which of the two
+ * builds of the half-precision serving configuration of paper section 5 the caller has loaded. */
+enum { STAGE_ELEM_BF16 = 0, STAGE_ELEM_F16 = 1 };
+int32_t stage_elem_type(void);
 
 #ifdef __cplusplus
 }

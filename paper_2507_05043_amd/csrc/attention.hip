@@ -22,7 +22,7 @@ namespace {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-__device__ __forceinline__ bf16x8 zero_tail(bf16x8 v, int nvalid) {
+__device__ __forceinline__ e16x8 zero_tail(e16x8 v, int nvalid) {
   // keep elements [0, nvalid), zero the rest (bitwise, so NaNs vanish)
   u32x4 w = __builtin_bit_cast(u32x4, v);
 #pragma unroll
@@ -31,13 +31,13 @@ __device__ __forceinline__ bf16x8 zero_tail(bf16x8 v, int nvalid) {
     const uint32_t hi = (2 * i + 1 < nvalid) ? 0xffff0000u : 0u;
     w[i] &= (lo | hi);
   }
-  return __builtin_bit_cast(bf16x8, w);
+  return __builtin_bit_cast(e16x8, w);
 }
 
-__device__ __forceinline__ bf16x8 pack8(const float* p) {
-  bf16x8 o;
+__device__ __forceinline__ e16x8 pack8(const float* p) {
+  e16x8 o;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) o[e] = f32_to_bf16(p[e]);
+  for (int e = 0; e < 8; ++e) o[e] = f32_to_e16(p[e]);
   return o;
 }
 
@@ -50,8 +50,8 @@ __device__ __forceinline__ bf16x8 pack8(const float* p) {
 // ------------------------------------------------------------------------------------------------
 template <int D>
 struct DecodeStepLoads {
-  bf16x8 ka[D / 32], kb[D / 32];   // key tiles A and B, D/32 MFMA k-steps each
-  bf16x8 v[D / 16];                // V^T tiles, one per 16 output dims
+  e16x8 ka[D / 32], kb[D / 32];   // key tiles A and B, D/32 MFMA k-steps each
+  e16x8 v[D / 16];                // V^T tiles, one per 16 output dims
 };
 
 template <int D, bool QLO>
@@ -83,19 +83,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
   const int ldq = (a.nq + 2 * a.nkv) * D;
 
   // Q^T operand: column = query head of the group, lane group holds d = 32*kk + 8*grp .. +7
-  bf16x8 qf[KS], qf_lo[QLO ? KS : 1];
+  e16x8 qf[KS], qf_lo[QLO ? KS : 1];
   {
     const int head = r * g + (col < g ? col : 0);
-    const __bf16* qp = a.qkv + (size_t)row * ldq + head * D + grp * 8;
-    const __bf16* ql = QLO ? a.q_lo + ((size_t)row * a.nq + head) * D + grp * 8 : qp;
+    const e16* qp = a.qkv + (size_t)row * ldq + head * D + grp * 8;
+    const e16* ql = QLO ? a.q_lo + ((size_t)row * a.nq + head) * D + grp * 8 : qp;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
-      bf16x8 v = load8(qp + kk * 32);
-      if (col >= g) v = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+      e16x8 v = load8(qp + kk * 32);
+      if (col >= g) v = e16x8{0, 0, 0, 0, 0, 0, 0, 0};
       qf[kk] = v;
       if constexpr (QLO) {
-        bf16x8 w = load8(ql + kk * 32);
-        if (col >= g) w = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        e16x8 w = load8(ql + kk * 32);
+        if (col >= g) w = e16x8{0, 0, 0, 0, 0, 0, 0, 0};
         qf_lo[kk] = w;
       }
     }
@@ -120,14 +120,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
   // be fetched without asking whether it exists and the loop body stays free of branches
   auto load_step = [&](DecodeStepLoads<D>& L, int b0, int b1) {
     const int pbk = k_bsel ? b1 : b0;
-    const __bf16* kp = a.k_pool + (size_t)pbk * blk_stride + head_off + k_lane_off;
+    const e16* kp = a.k_pool + (size_t)pbk * blk_stride + head_off + k_lane_off;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
       L.ka[kk] = load8_stream(kp + kk * (kKvBlock * 32));
       L.kb[kk] = load8_stream(kp + 8 * 32 + kk * (kKvBlock * 32));
     }
     const int pbv = v_bsel ? b1 : b0;
-    const __bf16* vp = a.v_pool + (size_t)pbv * blk_stride + head_off + v_lane_off;
+    const e16* vp = a.v_pool + (size_t)pbv * blk_stride + head_off + v_lane_off;
 #pragma unroll
     for (int t = 0; t < DT; ++t) L.v[t] = load8_stream(vp + (size_t)t * 16 * kKvBlock);
   };
@@ -141,11 +141,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
-      sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(L.ka[kk], qf[kk], sa, 0, 0, 0);
-      sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(L.kb[kk], qf[kk], sb, 0, 0, 0);
+      sa = mfma_16x16x32(L.ka[kk], qf[kk], sa);
+      sb = mfma_16x16x32(L.kb[kk], qf[kk], sb);
       if constexpr (QLO) {   // second query plane into the same scores
-        sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(L.ka[kk], qf_lo[kk], sa, 0, 0, 0);
-        sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(L.kb[kk], qf_lo[kk], sb, 0, 0, 0);
+        sa = mfma_16x16x32(L.ka[kk], qf_lo[kk], sa);
+        sb = mfma_16x16x32(L.kb[kk], qf_lo[kk], sb);
       }
     }
     const int key0 = key_begin + 32 * step + 8 * grp;     // first of this lane's 8 keys
@@ -171,14 +171,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     }
     l_run = l_run * alpha + psum;
     m_run = m_new;
-    const bf16x8 pf = pack8(p);
+    const e16x8 pf = pack8(p);
     const bool tail = key_begin + 32 * step + 32 > key_end;   // wave-uniform
 #pragma unroll
     for (int t = 0; t < DT; ++t) {
-      bf16x8 v = L.v[t];
+      e16x8 v = L.v[t];
       if (tail) v = zero_tail(v, nvalid < 0 ? 0 : nvalid);
       acc[t] = acc[t] * alpha;
-      acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v, pf, acc[t], 0, 0, 0);
+      acc[t] = mfma_16x16x32(v, pf, acc[t]);
     }
   };
 
@@ -247,16 +247,16 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const Decod
     o += po * w;
   }
   const float inv = 1.0f / l;
-  bf16x4 ob, ol;
+  e16x4 ob, ol;
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const float val = o[e] * inv;
-    ob[e] = f32_to_bf16(val);
-    ol[e] = f32_to_bf16(val - bf16_to_f32(ob[e]));
+    ob[e] = f32_to_e16(val);
+    ol[e] = f32_to_e16(val - e16_to_f32(ob[e]));
   }
   const size_t at = (size_t)t.row * a.nq * D + head * D + d4 * 4;
-  *reinterpret_cast<bf16x4*>(a.out + at) = ob;
-  if (a.out_lo) *reinterpret_cast<bf16x4*>(a.out_lo + at) = ol;
+  *reinterpret_cast<e16x4*>(a.out + at) = ob;
+  if (a.out_lo) *reinterpret_cast<e16x4*>(a.out_lo + at) = ol;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -319,13 +319,13 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
   const int nsteps = (ctx + min(tile_col0 + 127, ncols - 1) / g) / 32 + 1; // ... to the workgroup
   const int ldq = (a.nq + 2 * a.nkv) * D;
 
-  bf16x8 qf[KS], qf_lo[QLO ? KS : 1];
+  e16x8 qf[KS], qf_lo[QLO ? KS : 1];
   {
-    const __bf16* qp = a.qkv + (size_t)(row0 + tok) * ldq + (r * g + hg) * D + grp * 8;
+    const e16* qp = a.qkv + (size_t)(row0 + tok) * ldq + (r * g + hg) * D + grp * 8;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) qf[kk] = load8(qp + kk * 16);
     if constexpr (QLO) {
-      const __bf16* ql = a.q_lo + ((size_t)(row0 + tok) * a.nq + r * g + hg) * D + grp * 8;
+      const e16* ql = a.q_lo + ((size_t)(row0 + tok) * a.nq + r * g + hg) * D + grp * 8;
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk) qf_lo[kk] = load8(ql + kk * 16);
     }
@@ -394,10 +394,10 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
     f32x16 s = zero16;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
-      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(stage + k_row_off + (kk >> 1) * (kKvBlock * 64) +
+      const e16x8 kf = *reinterpret_cast<const e16x8*>(stage + k_row_off + (kk >> 1) * (kKvBlock * 64) +
                                                          (((2 * (kk & 1) + grp) ^ k_swz) * 16));
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
-      if constexpr (QLO) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf_lo[kk], s, 0, 0, 0);
+      s = mfma_32x32x16(kf, qf[kk], s);
+      if constexpr (QLO) s = mfma_32x32x16(kf, qf_lo[kk], s);
     }
     // register e of this lane is key 32*step + 16*(e/8) + 8*grp + e%8
     const int key_base = 32 * step + 8 * grp;
@@ -440,19 +440,19 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
       psum += sv[e];
     }
     l_run += psum;
-    const bf16x8 p0 = pack8(sv), p1 = pack8(sv + 8);
+    const e16x8 p0 = pack8(sv), p1 = pack8(sv + 8);
     const bool tail = 32 * step + 32 > total_keys;            // wave-uniform: slots past the sequence end
     const int nv0 = total_keys - key_base, nv1 = nv0 - 16;
 #pragma unroll
     for (int t = 0; t < DT; ++t) {
-      bf16x8 v0 = *reinterpret_cast<const bf16x8*>(stage + v_frag_off + t * 512);
-      bf16x8 v1 = *reinterpret_cast<const bf16x8*>(stage + v_frag_off + 2 * D * 16 + t * 512);
+      e16x8 v0 = *reinterpret_cast<const e16x8*>(stage + v_frag_off + t * 512);
+      e16x8 v1 = *reinterpret_cast<const e16x8*>(stage + v_frag_off + 2 * D * 16 + t * 512);
       if (tail) {
         v0 = zero_tail(v0, nv0 < 0 ? 0 : nv0);
         v1 = zero_tail(v1, nv1 < 0 ? 0 : nv1);
       }
-      acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0, p0, acc[t], 0, 0, 0);
-      acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1, p1, acc[t], 0, 0, 0);
+      acc[t] = mfma_32x32x16(v0, p0, acc[t]);
+      acc[t] = mfma_32x32x16(v1, p1, acc[t]);
     }
   };
 
@@ -485,15 +485,15 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
     for (int t = 0; t < DT; ++t) {
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
-        bf16x4 ob, ol;
+        e16x4 ob, ol;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const float val = acc[t][q4 * 4 + e] * inv;
-          ob[e] = f32_to_bf16(val);
-          ol[e] = f32_to_bf16(val - bf16_to_f32(ob[e]));
+          ob[e] = f32_to_e16(val);
+          ol[e] = f32_to_e16(val - e16_to_f32(ob[e]));
         }
-        *reinterpret_cast<bf16x4*>(a.out + at + t * 32 + q4 * 8) = ob;
-        if (a.out_lo) *reinterpret_cast<bf16x4*>(a.out_lo + at + t * 32 + q4 * 8) = ol;
+        *reinterpret_cast<e16x4*>(a.out + at + t * 32 + q4 * 8) = ob;
+        if (a.out_lo) *reinterpret_cast<e16x4*>(a.out_lo + at + t * 32 + q4 * 8) = ol;
       }
     }
   }

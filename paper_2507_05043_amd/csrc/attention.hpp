@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "elem.hpp"
+
 namespace molink {
 
 // One unit of decode work: a contiguous key range of one decode token's sequence.
@@ -34,13 +36,13 @@ struct PrefillTile {
 };
 
 struct AttnArgs {
-  const __bf16* qkv;        // [T][(nq + 2 nkv) d], q already rotated
-  const __bf16* q_lo;       // optional [T][nq d]: second plane of the rotated queries (q = hi + lo); nullptr = none
-  const __bf16* k_pool;     // this layer's K region
-  const __bf16* v_pool;     // this layer's V region
+  const e16* qkv;        // [T][(nq + 2 nkv) d], q already rotated
+  const e16* q_lo;       // optional [T][nq d]: second plane of the rotated queries (q = hi + lo); nullptr = none
+  const e16* k_pool;     // this layer's K region
+  const e16* v_pool;     // this layer's V region
   const int32_t* bt_flat;   // flat block tables
-  __bf16* out;              // [T][nq d]
-  __bf16* out_lo;           // optional [T][nq d]: bf16(result - bf16(result)) for the two-plane output projection
+  e16* out;              // [T][nq d]
+  e16* out_lo;           // optional [T][nq d]: e16(result - e16(result)) for the two-plane output projection
   int nq, nkv, head_dim;
   float scale_log2e;        // log2(e) / sqrt(d)
 };

@@ -3,11 +3,13 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "elem.hpp"
+
 namespace molink {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(8))) e16 e16x8;
+typedef __attribute__((ext_vector_type(4))) e16 e16x4;
+typedef __attribute__((ext_vector_type(2))) e16 e16x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
@@ -28,28 +30,49 @@ __host__ __device__ __forceinline__ int k_offset_in_block(int slot, int dim) {
   return ((dim >> 5) * kKvBlock + k_position_of_slot(slot)) * 32 + (dim & 31);
 }
 
-__device__ __forceinline__ float bf16_to_f32(__bf16 v) { return static_cast<float>(v); }
-__device__ __forceinline__ __bf16 f32_to_bf16(float v) { return static_cast<__bf16>(v); }
+__device__ __forceinline__ float e16_to_f32(e16 v) { return static_cast<float>(v); }
+__device__ __forceinline__ e16 f32_to_e16(float v) { return static_cast<e16>(v); }
 
-// widen the low / high bf16 of a packed 32-bit word
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+// widen the low / high e16 of a packed 32-bit word
+#ifdef MOLINK_F16
+__device__ __forceinline__ float e16_lo(uint32_t w) { return static_cast<float>(__builtin_bit_cast(e16x2, w)[0]); }
+__device__ __forceinline__ float e16_hi(uint32_t w) { return static_cast<float>(__builtin_bit_cast(e16x2, w)[1]); }
+#else
+__device__ __forceinline__ float e16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float e16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+#endif
 
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  bf16x2 p;
-  p[0] = static_cast<__bf16>(lo);
-  p[1] = static_cast<__bf16>(hi);
+// matrix instructions on e16 operands, fp32 accumulators
+__device__ __forceinline__ f32x4 mfma_16x16x32(e16x8 a, e16x8 b, f32x4 c) {
+#ifdef MOLINK_F16
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+#else
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+#endif
+}
+__device__ __forceinline__ f32x16 mfma_32x32x16(e16x8 a, e16x8 b, f32x16 c) {
+#ifdef MOLINK_F16
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+#else
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+#endif
+}
+
+__device__ __forceinline__ uint32_t pack_e16(float lo, float hi) {
+  e16x2 p;
+  p[0] = static_cast<e16>(lo);
+  p[1] = static_cast<e16>(hi);
   return __builtin_bit_cast(uint32_t, p);
 }
 
-// 16-byte global load / store of 8 bf16
-__device__ __forceinline__ bf16x8 load8(const __bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }
+// 16-byte global load / store of 8 e16
+__device__ __forceinline__ e16x8 load8(const e16* p) { return *reinterpret_cast<const e16x8*>(p); }
 // The same load for data that is read exactly once (cached KV, streamed weights): marked nontemporal,
 // so it does not displace what the caches hold; measured about 15 % more read bandwidth on long streams.
-__device__ __forceinline__ bf16x8 load8_stream(const __bf16* p) {
-  return __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(p));
+__device__ __forceinline__ e16x8 load8_stream(const e16* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const e16x8*>(p));
 }
-__device__ __forceinline__ void store8(__bf16* p, bf16x8 v) { *reinterpret_cast<bf16x8*>(p) = v; }
+__device__ __forceinline__ void store8(e16* p, e16x8 v) { *reinterpret_cast<e16x8*>(p) = v; }
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

@@ -10,21 +10,21 @@ namespace molink {
 namespace {
 
 template <bool FROM_BF16>
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const __bf16* __restrict__ in_bf16, float* __restrict__ x,
-                                                      const __bf16* __restrict__ gain, __bf16* __restrict__ out,
-                                                      __bf16* __restrict__ out_lo, int hidden, float eps) {
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const e16* __restrict__ in_e16, float* __restrict__ x,
+                                                      const e16* __restrict__ gain, e16* __restrict__ out,
+                                                      e16* __restrict__ out_lo, int hidden, float eps) {
   __shared__ float partial[4];
   const int row = blockIdx.x, tid = threadIdx.x;
   const int chunks = hidden / 8;
-  const __bf16* src_b = in_bf16 + (size_t)row * hidden;
+  const e16* src_b = in_e16 + (size_t)row * hidden;
   float* xr = x + (size_t)row * hidden;
   float ss = 0.f;
   for (int c = tid; c < chunks; c += 256) {
     float v[8];
     if constexpr (FROM_BF16) {
-      const bf16x8 b = load8(src_b + c * 8);
+      const e16x8 b = load8(src_b + c * 8);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = bf16_to_f32(b[e]);
+      for (int e = 0; e < 8; ++e) v[e] = e16_to_f32(b[e]);
       *reinterpret_cast<float4*>(xr + c * 8) = make_float4(v[0], v[1], v[2], v[3]);
       *reinterpret_cast<float4*>(xr + c * 8 + 4) = make_float4(v[4], v[5], v[6], v[7]);
     } else {
@@ -43,21 +43,21 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const __bf16* __restrict__
   for (int c = tid; c < chunks; c += 256) {
     float v[8];
     if constexpr (FROM_BF16) {
-      const bf16x8 b = load8(src_b + c * 8);
+      const e16x8 b = load8(src_b + c * 8);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = bf16_to_f32(b[e]);
+      for (int e = 0; e < 8; ++e) v[e] = e16_to_f32(b[e]);
     } else {
       const float4 p = *reinterpret_cast<const float4*>(xr + c * 8);
       const float4 q = *reinterpret_cast<const float4*>(xr + c * 8 + 4);
       v[0] = p.x; v[1] = p.y; v[2] = p.z; v[3] = p.w; v[4] = q.x; v[5] = q.y; v[6] = q.z; v[7] = q.w;
     }
-    const bf16x8 g = load8(gain + c * 8);
-    bf16x8 o, lo;
+    const e16x8 g = load8(gain + c * 8);
+    e16x8 o, lo;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const float val = v[e] * rs * bf16_to_f32(g[e]);
-      o[e] = f32_to_bf16(val);
-      lo[e] = f32_to_bf16(val - bf16_to_f32(o[e]));     // what the rounding dropped, for the two-plane GEMMs
+      const float val = v[e] * rs * e16_to_f32(g[e]);
+      o[e] = f32_to_e16(val);
+      lo[e] = f32_to_e16(val - e16_to_f32(o[e]));     // what the rounding dropped, for the two-plane GEMMs
     }
     store8(out + (size_t)row * hidden + c * 8, o);
     if (out_lo) store8(out_lo + (size_t)row * hidden + c * 8, lo);
@@ -79,7 +79,7 @@ __global__ __launch_bounds__(256) void rope_table_kernel(const int32_t* __restri
 
 // One workgroup per token row.  Work units of 8 elements:
 //   rotated heads (q then k): unit = (head, chunk of 8 pairs): reads the fp32 halves, rotates, rounds to
-//   bf16 once, writes the bf16 row and, for k heads, also the K pool row of the token's slot;
+//   e16 once, writes the e16 row and, for k heads, also the K pool row of the token's slot;
 //   v heads: unit = (head, chunk of 8 dims): rounded once and scattered into the transposed V block.
 __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs p) {
   const int t = blockIdx.x;
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs p) {
   if (u >= rot_units + v_units) return;
   const int row_elems = (p.nq + 2 * p.nkv) * d;
   const float* src = p.qkv_f32 + (size_t)t * row_elems;
-  __bf16* row = p.qkv + (size_t)t * row_elems;
+  e16* row = p.qkv + (size_t)t * row_elems;
   const int64_t slot = p.slots[t];
   const int64_t blk = slot / kKvBlock;
   const int s = (int)(slot % kKvBlock);
@@ -103,9 +103,9 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs p) {
     }
     v[0] = a[0]; v[1] = a[1]; v[2] = a[2]; v[3] = a[3]; v[4] = b[0]; v[5] = b[1]; v[6] = b[2]; v[7] = b[3];
     if (p.bias) {
-      const bf16x8 bb = load8(p.bias + (q - src));
+      const e16x8 bb = load8(p.bias + (q - src));
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] += bf16_to_f32(bb[e]);
+      for (int e = 0; e < 8; ++e) v[e] += e16_to_f32(bb[e]);
     }
   };
   if (u < rot_units) {
@@ -114,28 +114,28 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs p) {
     float lo[8], hi[8];
     load8f(src + head * d + c * 8, lo);
     load8f(src + head * d + half + c * 8, hi);
-    bf16x8 olo, ohi, llo, lhi;
+    e16x8 olo, ohi, llo, lhi;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const float2 f = cs[e];
       const float y0 = lo[e] * f.x - hi[e] * f.y, y1 = hi[e] * f.x + lo[e] * f.y;
-      olo[e] = f32_to_bf16(y0);
-      ohi[e] = f32_to_bf16(y1);
-      llo[e] = f32_to_bf16(y0 - bf16_to_f32(olo[e]));
-      lhi[e] = f32_to_bf16(y1 - bf16_to_f32(ohi[e]));
+      olo[e] = f32_to_e16(y0);
+      ohi[e] = f32_to_e16(y1);
+      llo[e] = f32_to_e16(y0 - e16_to_f32(olo[e]));
+      lhi[e] = f32_to_e16(y1 - e16_to_f32(ohi[e]));
     }
-    __bf16* base = row + head * d + c * 8;
+    e16* base = row + head * d + c * 8;
     store8(base, olo);
     store8(base + half, ohi);
     if (head < p.nq) {
       if (p.q_lo) {
-        __bf16* lb = p.q_lo + ((size_t)t * p.nq + head) * d + c * 8;
+        e16* lb = p.q_lo + ((size_t)t * p.nq + head) * d + c * 8;
         store8(lb, llo);
         store8(lb + half, lhi);
       }
     } else {
       const int r = head - p.nq;
-      __bf16* dst = p.k_pool + ((size_t)blk * p.nkv + r) * kKvBlock * d;
+      e16* dst = p.k_pool + ((size_t)blk * p.nkv + r) * kKvBlock * d;
       store8(dst + k_offset_in_block(s, c * 8), olo);
       store8(dst + k_offset_in_block(s, half + c * 8), ohi);
     }
@@ -144,35 +144,35 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs p) {
     const int r = w / (d / 8), c = w % (d / 8);
     float v[8];
     load8f(src + (p.nq + p.nkv + r) * d + c * 8, v);
-    bf16x8 vb;
+    e16x8 vb;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) vb[e] = f32_to_bf16(v[e]);
+    for (int e = 0; e < 8; ++e) vb[e] = f32_to_e16(v[e]);
     store8(row + (p.nq + p.nkv + r) * d + c * 8, vb);
-    __bf16* dst = p.v_pool + (((size_t)blk * p.nkv + r) * d + c * 8) * kKvBlock + s;
+    e16* dst = p.v_pool + (((size_t)blk * p.nkv + r) * d + c * 8) * kKvBlock + s;
 #pragma unroll
     for (int e = 0; e < 8; ++e) dst[e * kKvBlock] = vb[e];
   }
 }
 
-__global__ __launch_bounds__(256) void embed_gather_kernel(const __bf16* __restrict__ table, const int32_t* __restrict__ ids,
-                                                           __bf16* __restrict__ out, int hidden) {
+__global__ __launch_bounds__(256) void embed_gather_kernel(const e16* __restrict__ table, const int32_t* __restrict__ ids,
+                                                           e16* __restrict__ out, int hidden) {
   const int t = blockIdx.x;
-  const __bf16* src = table + (size_t)ids[t] * hidden;
-  __bf16* dst = out + (size_t)t * hidden;
+  const e16* src = table + (size_t)ids[t] * hidden;
+  e16* dst = out + (size_t)t * hidden;
   for (int c = threadIdx.x * 8; c < hidden; c += 256 * 8) store8(dst + c, load8(src + c));
 }
 
-__global__ __launch_bounds__(256) void gather_rmsnorm_kernel(const __bf16* __restrict__ in, const int32_t* __restrict__ rows,
-                                                             const __bf16* __restrict__ gain, __bf16* __restrict__ out,
+__global__ __launch_bounds__(256) void gather_rmsnorm_kernel(const e16* __restrict__ in, const int32_t* __restrict__ rows,
+                                                             const e16* __restrict__ gain, e16* __restrict__ out,
                                                              int hidden, float eps) {
   __shared__ float wsum[4];
   const int s = blockIdx.x, tid = threadIdx.x;
-  const __bf16* src = in + (size_t)rows[s] * hidden;
+  const e16* src = in + (size_t)rows[s] * hidden;
   float ss = 0.f;
   for (int c = tid * 8; c < hidden; c += 256 * 8) {
-    const bf16x8 v = load8(src + c);
+    const e16x8 v = load8(src + c);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { const float f = bf16_to_f32(v[e]); ss += f * f; }
+    for (int e = 0; e < 8; ++e) { const float f = e16_to_f32(v[e]); ss += f * f; }
   }
   ss = wave_sum(ss);
   if ((tid & 63) == 0) wsum[tid >> 6] = ss;
@@ -180,10 +180,10 @@ __global__ __launch_bounds__(256) void gather_rmsnorm_kernel(const __bf16* __res
   const float tot = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
   const float rs = 1.0f / sqrtf(tot / (float)hidden + eps);
   for (int c = tid * 8; c < hidden; c += 256 * 8) {
-    const bf16x8 v = load8(src + c), g = load8(gain + c);
-    bf16x8 o;
+    const e16x8 v = load8(src + c), g = load8(gain + c);
+    e16x8 o;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = f32_to_bf16(bf16_to_f32(v[e]) * rs * bf16_to_f32(g[e]));
+    for (int e = 0; e < 8; ++e) o[e] = f32_to_e16(e16_to_f32(v[e]) * rs * e16_to_f32(g[e]));
     store8(out + (size_t)s * hidden + c, o);
   }
 }
@@ -226,13 +226,13 @@ __global__ __launch_bounds__(1024) void argmax_rows_kernel(const float* __restri
 
 }  // namespace
 
-hipError_t launch_embed_gather(const __bf16* table, const int32_t* ids, __bf16* out, int rows, int hidden,
+hipError_t launch_embed_gather(const e16* table, const int32_t* ids, e16* out, int rows, int hidden,
                                hipStream_t stream) {
   hipLaunchKernelGGL(embed_gather_kernel, dim3(rows), dim3(256), 0, stream, table, ids, out, hidden);
   return hipGetLastError();
 }
 
-hipError_t launch_gather_rmsnorm(const __bf16* in, const int32_t* rows, const __bf16* gain, __bf16* out, int n_rows,
+hipError_t launch_gather_rmsnorm(const e16* in, const int32_t* rows, const e16* gain, e16* out, int n_rows,
                                  int hidden, float eps, hipStream_t stream) {
   hipLaunchKernelGGL(gather_rmsnorm_kernel, dim3(n_rows), dim3(256), 0, stream, in, rows, gain, out, hidden, eps);
   return hipGetLastError();
@@ -245,12 +245,12 @@ hipError_t launch_argmax_rows(const float* src, int planes, size_t plane_stride,
   return hipGetLastError();
 }
 
-hipError_t launch_rmsnorm(const __bf16* in_bf16, float* x, const __bf16* gain, __bf16* out, __bf16* out_lo, int rows,
-                          int hidden, float eps, bool from_bf16, hipStream_t stream) {
-  if (from_bf16)
-    hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(rows), dim3(256), 0, stream, in_bf16, x, gain, out, out_lo, hidden, eps);
+hipError_t launch_rmsnorm(const e16* in_e16, float* x, const e16* gain, e16* out, e16* out_lo, int rows,
+                          int hidden, float eps, bool from_e16, hipStream_t stream) {
+  if (from_e16)
+    hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(rows), dim3(256), 0, stream, in_e16, x, gain, out, out_lo, hidden, eps);
   else
-    hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(rows), dim3(256), 0, stream, in_bf16, x, gain, out, out_lo, hidden,
+    hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(rows), dim3(256), 0, stream, in_e16, x, gain, out, out_lo, hidden,
                        eps);
   return hipGetLastError();
 }

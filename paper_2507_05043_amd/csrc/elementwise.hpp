@@ -3,41 +3,43 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "elem.hpp"
+
 namespace molink {
 
-// a[t][:] = x[t][:] * gain / sqrt(mean(x[t][:]^2) + eps), rounded to bf16.
-// from_bf16: the row source is in_bf16 (the stage input) and the fp32 residual stream x is also
+// a[t][:] = x[t][:] * gain / sqrt(mean(x[t][:]^2) + eps), rounded to e16.
+// from_e16: the row source is in_e16 (the stage input) and the fp32 residual stream x is also
 // initialised from it; otherwise the source is x.
-// out_lo (optional): receives bf16(value - bf16(value)), the second activation plane of the two-plane GEMMs.
-hipError_t launch_rmsnorm(const __bf16* in_bf16, float* x, const __bf16* gain, __bf16* out, __bf16* out_lo, int rows,
-                          int hidden, float eps, bool from_bf16, hipStream_t stream);
+// out_lo (optional): receives e16(value - e16(value)), the second activation plane of the two-plane GEMMs.
+hipError_t launch_rmsnorm(const e16* in_e16, float* x, const e16* gain, e16* out, e16* out_lo, int rows,
+                          int hidden, float eps, bool from_e16, hipStream_t stream);
 
 // cos_sin[t][i] = (cos, sin)(positions[t] * theta^(-2i/d)), i < d/2, evaluated in fp64.
 hipError_t launch_rope_table(const int32_t* positions, float2* cos_sin, int rows, int head_dim, float theta,
                              hipStream_t stream);
 
 struct RopeAppendArgs {
-  const float* qkv_f32;    // [planes][T][(nq + 2 nkv) d] projection output, fp32 (rounded to bf16 only after the
+  const float* qkv_f32;    // [planes][T][(nq + 2 nkv) d] projection output, fp32 (rounded to e16 only after the
                            // rotation); with planes > 1 the split-K partial sums, added here in plane order
   int planes;
   size_t plane_stride;     // floats between planes
-  const __bf16* bias;      // optional [(nq + 2 nkv) d] projection bias, added before the rotation
-  __bf16* qkv;             // [T][(nq + 2 nkv) d] bf16: rotated q heads, rotated k heads, v heads
-  __bf16* q_lo;            // optional [T][nq d]: bf16(q - bf16(q)), second plane of the rotated queries
+  const e16* bias;      // optional [(nq + 2 nkv) d] projection bias, added before the rotation
+  e16* qkv;             // [T][(nq + 2 nkv) d] e16: rotated q heads, rotated k heads, v heads
+  e16* q_lo;            // optional [T][nq d]: e16(q - e16(q)), second plane of the rotated queries
   const float2* cos_sin;   // [T][d/2]
   const int64_t* slots;    // [T] pool slot of every row
-  __bf16* k_pool;          // this layer's K region [blocks][nkv][16][d]
-  __bf16* v_pool;          // this layer's V region [blocks][nkv][d][16]
+  e16* k_pool;          // this layer's K region [blocks][nkv][16][d]
+  e16* v_pool;          // this layer's V region [blocks][nkv][d][16]
   int rows, nq, nkv, head_dim;
 };
 hipError_t launch_rope_append(const RopeAppendArgs& args, hipStream_t stream);
 
-// out[t][:] = table[ids[t]][:]  (bf16 rows of `hidden` elements, hidden % 8 == 0)
-hipError_t launch_embed_gather(const __bf16* table, const int32_t* ids, __bf16* out, int rows, int hidden,
+// out[t][:] = table[ids[t]][:]  (e16 rows of `hidden` elements, hidden % 8 == 0)
+hipError_t launch_embed_gather(const e16* table, const int32_t* ids, e16* out, int rows, int hidden,
                                hipStream_t stream);
 
-// out[s][:] = bf16(RMSNorm(in[rows[s]][:]; gain, eps)), norm in fp32
-hipError_t launch_gather_rmsnorm(const __bf16* in, const int32_t* rows, const __bf16* gain, __bf16* out, int n_rows,
+// out[s][:] = e16(RMSNorm(in[rows[s]][:]; gain, eps)), norm in fp32
+hipError_t launch_gather_rmsnorm(const e16* in, const int32_t* rows, const e16* gain, e16* out, int n_rows,
                                  int hidden, float eps, hipStream_t stream);
 
 // Per row: logits = sum over `planes` of src[plane][row][:] (in plane order), optionally stored, and the

@@ -1,6 +1,6 @@
-// bf16 MFMA GEMM for the stage's projections: C[M][N] = A[M][K] * W[N][K]^T, fp32 accumulate.
+// e16 MFMA GEMM for the stage's projections: C[M][N] = A[M][K] * W[N][K]^T, fp32 accumulate.
 //
-// Both operands are K-contiguous, which is the layout the 32x32x16 bf16 MFMA wants in its lanes
+// Both operands are K-contiguous, which is the layout the 32x32x16 e16 MFMA wants in its lanes
 // (lane l holds 8 consecutive k of row l%32).  Tiles travel HBM/L2 -> LDS directly (16 bytes per lane,
 // 8 rows x 128 bytes per wave instruction, XOR-swizzled so 128-bit LDS reads are conflict free) ->
 // MFMA operands.  Two to three K tiles are kept in flight in separate LDS stages; one barrier per K
@@ -59,7 +59,7 @@ __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)
 // different slots.  LDS reads of MFMA step kk+1 are issued under the MFMAs of step kk, across tile
 // boundaries too.
 template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int EPI, bool SPLIT, bool SPLIT_A>
-__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmArgs p, int nv, int tiles_m, int tiles_n, int splits,
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(GemmArgs p, int nv, int tiles_m, int tiles_n, int splits,
                                                         int k_tiles_per_split) {
   constexpr int NWAVES = WAVES_M * WAVES_N;
   constexpr int TM = BM / WAVES_M, TN = BN / WAVES_N;
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
   constexpr int NPLANE = SPLIT_A ? 2 : 1;
   constexpr int KSTEPS = kBK / 16, NMFMA = NPLANE * MT * NT, NREAD = NPLANE * MT + NT;
   static_assert(KSTEPS == 4, "four MFMA steps per K tile");
-  bf16x8 af[2][NPLANE][MT], bfr[2][NT];
+  e16x8 af[2][NPLANE][MT], bfr[2][NT];
   // fragments of MFMA step kk of the tile in stage S into register set s
   auto read_frags = [&](auto stage_c, int s, int kk) {
     constexpr int S = decltype(stage_c)::value;
@@ -192,9 +192,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
     for (int pl = 0; pl < NPLANE; ++pl)
 #pragma unroll
       for (int i = 0; i < MT; ++i)
-        af[s][pl][i] = *reinterpret_cast<const bf16x8*>(la + (pl * BM + i * 32) * 128 + frag_off[kk]);
+        af[s][pl][i] = *reinterpret_cast<const e16x8*>(la + (pl * BM + i * 32) * 128 + frag_off[kk]);
 #pragma unroll
-    for (int j = 0; j < NT; ++j) bfr[s][j] = *reinterpret_cast<const bf16x8*>(lb + j * 32 * 128 + frag_off[kk]);
+    for (int j = 0; j < NT; ++j) bfr[s][j] = *reinterpret_cast<const e16x8*>(lb + j * 32 * 128 + frag_off[kk]);
   };
   auto mfmas = [&](int s) {
 #pragma unroll
@@ -203,7 +203,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
       for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int j = 0; j < NT; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s][pl][i], bfr[s][j], acc[i][j], 0, 0, 0);
+          acc[i][j] = mfma_32x32x16(af[s][pl][i], bfr[s][j], acc[i][j]);
   };
 
   // One pipeline step: tile idx is in stage S and the fragments of its first MFMA step are already in
@@ -289,9 +289,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
           const int f = (v >> 6) * 32 + (v & 31);
           if (f < p.n) {
             const float val = silu_f(acc[i][j][r]) * acc[i][j + 1][r];
-            const __bf16 hi = f32_to_bf16(val);
-            p.out_bf16[(size_t)m * p.ldo + f] = hi;
-            if (p.out_lo) p.out_lo[(size_t)m * p.ldo + f] = f32_to_bf16(val - bf16_to_f32(hi));
+            const e16 hi = f32_to_e16(val);
+            p.out_e16[(size_t)m * p.ldo + f] = hi;
+            if (p.out_lo) p.out_lo[(size_t)m * p.ldo + f] = f32_to_e16(val - e16_to_f32(hi));
           }
         }
       } else {
@@ -305,7 +305,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_bf16_kernel(GemmAr
           } else if constexpr (EPI == kEpiResidualF32) {
             p.resid[(size_t)m * p.n + n] += c;
           } else {
-            p.out_bf16[(size_t)m * p.ldo + n] = f32_to_bf16(p.resid[(size_t)m * p.n + n] + c);
+            p.out_e16[(size_t)m * p.ldo + n] = f32_to_e16(p.resid[(size_t)m * p.n + n] + c);
           }
         }
       }
@@ -330,15 +330,15 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(GemmArgs p, int
       g += *reinterpret_cast<const f32x4*>(src + s * plane);
       u += *reinterpret_cast<const f32x4*>(src + s * plane + 32);
     }
-    bf16x4 hi, lo;
+    e16x4 hi, lo;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const float val = silu_f(g[e]) * u[e];
-      hi[e] = f32_to_bf16(val);
-      lo[e] = f32_to_bf16(val - bf16_to_f32(hi[e]));
+      hi[e] = f32_to_e16(val);
+      lo[e] = f32_to_e16(val - e16_to_f32(hi[e]));
     }
-    *reinterpret_cast<bf16x4*>(p.out_bf16 + (size_t)m * p.ldo + n) = hi;
-    if (p.out_lo) *reinterpret_cast<bf16x4*>(p.out_lo + (size_t)m * p.ldo + n) = lo;
+    *reinterpret_cast<e16x4*>(p.out_e16 + (size_t)m * p.ldo + n) = hi;
+    if (p.out_lo) *reinterpret_cast<e16x4*>(p.out_lo + (size_t)m * p.ldo + n) = lo;
   } else {
     const float* src = p.partial + (size_t)m * nv + n;
     f32x4 c = {0.f, 0.f, 0.f, 0.f};
@@ -349,20 +349,20 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(GemmArgs p, int
       *reinterpret_cast<f32x4*>(p.resid + idx) += c;
     } else {
       const f32x4 r = *reinterpret_cast<const f32x4*>(p.resid + idx) + c;
-      bf16x4 o;
+      e16x4 o;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16(r[e]);
-      *reinterpret_cast<bf16x4*>(p.out_bf16 + (size_t)m * p.ldo + n) = o;
+      for (int e = 0; e < 4; ++e) o[e] = f32_to_e16(r[e]);
+      *reinterpret_cast<e16x4*>(p.out_e16 + (size_t)m * p.ldo + n) = o;
     }
   }
 }
 
-// Sum of the split-K partial results + residual add + (RMSNorm | bf16 rounding), one workgroup per row.
+// Sum of the split-K partial results + residual add + (RMSNorm | e16 rounding), one workgroup per row.
 template <bool NORM>
 __global__ __launch_bounds__(1024) void reduce_residual_norm_kernel(const float* __restrict__ partial, int splits,
                                                                    int m_rows, int n, float* __restrict__ x,
-                                                                   const __bf16* __restrict__ gain, float eps,
-                                                                   __bf16* __restrict__ out, __bf16* __restrict__ out_lo,
+                                                                   const e16* __restrict__ gain, float eps,
+                                                                   e16* __restrict__ out, e16* __restrict__ out_lo,
                                                                    int ldo) {
   __shared__ float wsum[16];
   const int row = blockIdx.x, tid = threadIdx.x;
@@ -380,10 +380,10 @@ __global__ __launch_bounds__(1024) void reduce_residual_norm_kernel(const float*
       *reinterpret_cast<f32x4*>(xr + c) = v;
       ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
     } else {
-      bf16x4 o;
+      e16x4 o;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16(v[e]);
-      *reinterpret_cast<bf16x4*>(out + (size_t)row * ldo + c) = o;
+      for (int e = 0; e < 4; ++e) o[e] = f32_to_e16(v[e]);
+      *reinterpret_cast<e16x4*>(out + (size_t)row * ldo + c) = o;
     }
   }
   if constexpr (NORM) {
@@ -395,16 +395,16 @@ __global__ __launch_bounds__(1024) void reduce_residual_norm_kernel(const float*
     const float rs = 1.0f / sqrtf(tot / (float)n + eps);
     for (int c = tid * 4; c < n; c += stride) {
       const f32x4 v = *reinterpret_cast<const f32x4*>(xr + c);     // written by this same thread above
-      const bf16x4 g = *reinterpret_cast<const bf16x4*>(gain + c);
-      bf16x4 o, lo;
+      const e16x4 g = *reinterpret_cast<const e16x4*>(gain + c);
+      e16x4 o, lo;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const float val = v[e] * rs * bf16_to_f32(g[e]);
-        o[e] = f32_to_bf16(val);
-        lo[e] = f32_to_bf16(val - bf16_to_f32(o[e]));
+        const float val = v[e] * rs * e16_to_f32(g[e]);
+        o[e] = f32_to_e16(val);
+        lo[e] = f32_to_e16(val - e16_to_f32(o[e]));
       }
-      *reinterpret_cast<bf16x4*>(out + (size_t)row * ldo + c) = o;
-      if (out_lo) *reinterpret_cast<bf16x4*>(out_lo + (size_t)row * ldo + c) = lo;
+      *reinterpret_cast<e16x4*>(out + (size_t)row * ldo + c) = o;
+      if (out_lo) *reinterpret_cast<e16x4*>(out_lo + (size_t)row * ldo + c) = lo;
     }
   }
 }
@@ -471,7 +471,7 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs p, int nv, in
       unit = real ? unit : n_units - 1;
       const int v0 = (g_begin + unit) * ROWS;    // first (virtual) row of the group
       // SwiGLU: 32 gate rows, then the 32 up rows of the same features
-      const __bf16* w = (swiglu && (v0 & 32)) ? p.w1 : p.w0;
+      const e16* w = (swiglu && (v0 & 32)) ? p.w1 : p.w0;
       const int r0 = swiglu ? (v0 >> 6) * 32 + (v0 & 31) : v0;
       const int last = p.n - 1 - r0;              // rows past the matrix repeat its last row (never stored)
       char* stage = Lds::template get<S>();
@@ -511,10 +511,10 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs p, int nv, in
   // activations: lane (row l%16, quarter l/16) holds k = 32 s + 8 (l/16) .. +7 of step s
   const int a_row = 16 * wave + (lane & 15), quarter = lane >> 4;
   const bool wave_active = 16 * wave < p.m;
-  bf16x8 act[STEPS];
+  e16x8 act[STEPS];
   {
     const int m = a_row < p.m ? a_row : p.m - 1;
-    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    const e16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
     for (int s = 0; s < STEPS; ++s) {
       const int k = kbase + 32 * s + 8 * quarter;
@@ -540,8 +540,8 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs p, int nv, in
 #pragma unroll
     for (int s = 0; s < STEPS; ++s) {
       const int off = (s >> 4) * 1024 + (s & 15) * 64 + ((s & 1) ? frag_odd : frag_even);
-      const bf16x8 wf = *reinterpret_cast<const bf16x8*>(stage + off);
-      acc[s & 3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, act[s], acc[s & 3], 0, 0, 0);
+      const e16x8 wf = *reinterpret_cast<const e16x8*>(stage + off);
+      acc[s & 3] = mfma_16x16x32(wf, act[s], acc[s & 3]);
     }
     // eight fragment reads run ahead of the MFMA that consumes the oldest of them
     __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
@@ -571,10 +571,10 @@ hipError_t launch_tile(const GemmArgs& a, const GemmPlan& plan, hipStream_t stre
   const int total = tiles_m * tiles_n * plan.splits;
   dim3 grid(xcd_grid(total)), block(WAVES_M * WAVES_N * 64);
   if (plan.splits > 1) {
-    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, NSTAGE, EPI, true, SPLIT_A>), grid, block, 0, stream, a,
+    hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, NSTAGE, EPI, true, SPLIT_A>), grid, block, 0, stream, a,
                        plan.nv, tiles_m, tiles_n, plan.splits, plan.k_tiles_per_split);
   } else {
-    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, NSTAGE, EPI, false, SPLIT_A>), grid, block, 0, stream,
+    hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, NSTAGE, EPI, false, SPLIT_A>), grid, block, 0, stream,
                        a, plan.nv, tiles_m, tiles_n, 1, plan.k_tiles_per_split);
   }
   return hipGetLastError();
@@ -678,7 +678,7 @@ hipError_t launch_gemm_main(const GemmArgs& a, GemmEpilogue epi, const GemmPlan&
                        epi == kEpiSwiGLU ? 1 : 0);
     return hipGetLastError();
   }
-  if (a.q0.codes) return hipErrorInvalidValue;   // the tiled kernels take bf16 weights only
+  if (a.q0.codes) return hipErrorInvalidValue;   // the tiled kernels take e16 weights only
   switch (epi) {
     case kEpiStoreF32: return launch_epi<kEpiStoreF32>(a, plan, stream);
     case kEpiResidualF32: return launch_epi<kEpiResidualF32>(a, plan, stream);
@@ -709,12 +709,12 @@ hipError_t launch_gemm_reduce(const GemmArgs& a, GemmEpilogue epi, const GemmPla
 }
 
 hipError_t launch_gemm_reduce_residual_norm(const GemmArgs& a, GemmEpilogue epi, const GemmPlan& plan,
-                                            const __bf16* gain, float eps, __bf16* norm_out, __bf16* norm_out_lo,
+                                            const e16* gain, float eps, e16* norm_out, e16* norm_out_lo,
                                             hipStream_t stream) {
   const int threads = a.n >= 4096 ? 1024 : (a.n >= 2048 ? 512 : 256);
   if (epi == kEpiResidualOut) {
     hipLaunchKernelGGL(reduce_residual_norm_kernel<false>, dim3(a.m), dim3(threads), 0, stream, a.partial, plan.splits, a.m,
-                       a.n, a.resid, (const __bf16*)nullptr, eps, a.out_bf16, (__bf16*)nullptr, a.ldo);
+                       a.n, a.resid, (const e16*)nullptr, eps, a.out_e16, (e16*)nullptr, a.ldo);
   } else {
     hipLaunchKernelGGL(reduce_residual_norm_kernel<true>, dim3(a.m), dim3(threads), 0, stream, a.partial, plan.splits, a.m,
                        a.n, a.resid, gain, eps, norm_out, norm_out_lo, a.n);

@@ -1,41 +1,43 @@
-// bf16 MFMA GEMM  C[M][N] = A[M][K] * W[N][K]^T  with fused epilogues (host-side declarations).
+// e16 MFMA GEMM  C[M][N] = A[M][K] * W[N][K]^T  with fused epilogues (host-side declarations).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include "elem.hpp"
 
 namespace molink {
 
 enum GemmEpilogue : int {
   kEpiStoreF32 = 0,     // out_f32[m][n] = acc                   (q/k/v before RoPE: rounded only once, after it)
   kEpiResidualF32 = 1,  // resid[m][n] += acc                      (fp32 residual stream, in place)
-  kEpiResidualOut = 2,  // out_bf16[m][n] = resid[m][n] + acc      (last layer: packed payload)
-  kEpiSwiGLU = 3,       // out_bf16[m][f] = silu(acc_gate[f]) * acc_up[f]
+  kEpiResidualOut = 2,  // out_e16[m][n] = resid[m][n] + acc      (last layer: packed payload)
+  kEpiSwiGLU = 3,       // out_e16[m][f] = silu(acc_gate[f]) * acc_up[f]
 };
 
 // One 4-bit group-quantised matrix [n][k]: codes uint32 [n][k/8] (element k in bits 4*(k%8).. of word k/8),
-// scales and zero points bf16 [n][k/group];  W[n][k] = (code - zero) * scale.
+// scales and zero points e16 [n][k/group];  W[n][k] = (code - zero) * scale.
 struct W4Matrix {
   const uint32_t* codes;
-  const __bf16* scales;
-  const __bf16* zeros;
+  const e16* scales;
+  const e16* zeros;
 };
 
 struct GemmArgs {
-  const __bf16* a;      // [M][lda]
-  const __bf16* a_lo;   // optional second plane [M][lda]: the activations are a + a_lo (the part of the fp32
-                        // value that bf16 rounding dropped); both planes are multiplied into the same
+  const e16* a;      // [M][lda]
+  const e16* a_lo;   // optional second plane [M][lda]: the activations are a + a_lo (the part of the fp32
+                        // value that e16 rounding dropped); both planes are multiplied into the same
                         // accumulators.  nullptr = single plane.
-  __bf16* out_lo;       // SwiGLU epilogue only, optional: receives bf16(result - bf16(result)) [M][ldo]
-  const __bf16* w0;     // [N][K]; for SwiGLU the gate matrix [F][K]
-  const __bf16* w1;     // SwiGLU only: the up matrix [F][K]
+  e16* out_lo;       // SwiGLU epilogue only, optional: receives e16(result - e16(result)) [M][ldo]
+  const e16* w0;     // [N][K]; for SwiGLU the gate matrix [F][K]
+  const e16* w1;     // SwiGLU only: the up matrix [F][K]
   W4Matrix q0, q1;      // q0.codes != nullptr: the weights are 4-bit (groups of 128) and w0 / w1 are unused;
                         // only plans of the weight-streaming kind (at most 64 rows) take them
-  __bf16* out_bf16;     // see GemmEpilogue
+  e16* out_e16;     // see GemmEpilogue
   float* out_f32;       // kEpiStoreF32 output [M][ldo]
   float* resid;         // fp32 residual stream [M][N]
   float* partial;       // split-K scratch [splits][M][Nv] fp32
   int m, n, k;          // n = output features (F for SwiGLU)
-  int lda, ldo;         // leading dimensions (elements) of a and of out_bf16 / out_f32
+  int lda, ldo;         // leading dimensions (elements) of a and of out_e16 / out_f32
 };
 
 // kTileSkinny: at most 64 rows; K cut into slices of 1024, weights streamed in groups of 16 rows, always
@@ -60,10 +62,10 @@ hipError_t launch_gemm_reduce(const GemmArgs& args, GemmEpilogue epi, const Gemm
 
 // Only when plan.partials and the epilogue is a residual one: one kernel that sums the partial
 // results in split order, adds them to the fp32 residual stream x[m][n] (in place), and then either
-// writes RMSNorm(x; gain, eps) as bf16 to norm_out (gain != nullptr) or rounds x to bf16 into
-// args.out_bf16 (kEpiResidualOut).  Replaces launch_gemm_reduce plus the following RMSNorm.
+// writes RMSNorm(x; gain, eps) as e16 to norm_out (gain != nullptr) or rounds x to e16 into
+// args.out_e16 (kEpiResidualOut).  Replaces launch_gemm_reduce plus the following RMSNorm.
 hipError_t launch_gemm_reduce_residual_norm(const GemmArgs& args, GemmEpilogue epi, const GemmPlan& plan,
-                                            const __bf16* gain, float eps, __bf16* norm_out, __bf16* norm_out_lo,
+                                            const e16* gain, float eps, e16* norm_out, e16* norm_out_lo,
                                             hipStream_t stream);
 
 }  // namespace molink

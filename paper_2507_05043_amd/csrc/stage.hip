@@ -53,7 +53,7 @@ struct Dims {
 struct WorkspaceLayout {
   size_t x, a, a_lo, qkv_f32, qkv, q_lo, attn, attn_lo, mlp, mlp_lo, cos_sin, splitk, part_o, part_ml, meta, total;
   size_t head_a, head_logits, ends_meta;   // output head: normalised last rows, fp32 logits, token ids / row indices
-  size_t wexp;                             // 4-bit weights: one projection's matrices expanded to bf16
+  size_t wexp;                             // 4-bit weights: one projection's matrices expanded to e16
   size_t meta_bytes;
   int max_items, max_tiles;
 };
@@ -108,14 +108,15 @@ Dims dims_of(const stage_config& c) {
 constexpr int kNumCus = 256;
 
 // Deep stages carry every GEMM input (both norm outputs, the attention output, silu(gate)*up) and the
-// rotated queries as two bf16 planes, value = hi + lo, and multiply both into the same accumulators.
-// One bf16 rounding per GEMM input costs about 1.7e-3 relative error per layer on the residual
+// rotated queries as two e16 planes, value = hi + lo, and multiply both into the same accumulators.
+// One bfloat16 rounding per GEMM input costs about 1.7e-3 relative error per layer on the residual
 // stream; the errors of the layers add in quadrature (8.0e-3 measured at eight layers), and beyond
 // eight layers the single-plane path no longer keeps a margin to the 1e-2 relative-L2 budget on the
 // stage output.  The second plane doubles the
-// MFMA work of the projections, so shallow stages do without it.
+// MFMA work of the projections, so shallow stages do without it.  IEEE half keeps three more mantissa bits
+// (an eighth of the rounding error), so the half-precision library never chooses it by itself.
 bool two_plane_of(const stage_config& c) {
-  return c.activation_planes == 0 ? c.num_layers > 8 : c.activation_planes == 2;
+  return c.activation_planes == 0 ? (!kElemIsF16 && c.num_layers > 8) : c.activation_planes == 2;
 }
 
 int decode_target_items(const Dims& d) { return (kNumCus * kDecodeWavesPerCu + d.nkv - 1) / d.nkv; }
@@ -145,7 +146,7 @@ WorkspaceLayout layout_of(const stage_config& c) {
   if ((v = gemm_partial_floats(c.max_tokens, d.H, d.F, kEpiResidualF32, kNumCus, sp)) > pf) pf = v;
   if (c.vocab_size > 0 && (v = gemm_partial_floats(c.max_seqs, c.vocab_size, d.H, kEpiStoreF32, kNumCus, false)) > pf) pf = v;
   w.splitk = take(pf * 4 + 16);
-  // 4-bit weights: room for the largest projection (gate and up together) expanded to bf16
+  // 4-bit weights: room for the largest projection (gate and up together) expanded to e16
   {
     size_t elems = (size_t)d.qkv_out * d.H;
     if ((size_t)2 * d.F * d.H > elems) elems = (size_t)2 * d.F * d.H;
@@ -275,36 +276,36 @@ struct Timer {
   }
 };
 
-__global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float* __restrict__ src, __bf16* __restrict__ dst, size_t n) {
+__global__ __launch_bounds__(256) void f32_to_e16_kernel(const float* __restrict__ src, e16* __restrict__ dst, size_t n) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (i < n) dst[i] = static_cast<__bf16>(src[i]);
+  if (i < n) dst[i] = static_cast<e16>(src[i]);
 }
 
-// Points a projection's GEMM at its weights.  bf16 weights are used where they lie.  4-bit weights go to
+// Points a projection's GEMM at its weights.  e16 weights are used where they lie.  4-bit weights go to
 // the weight-streaming kernel as they are stored when the micro-batch is decode-sized; otherwise they are
-// expanded to bf16 in the workspace first (one projection at a time; `w1` is the second matrix of the
+// expanded to e16 in the workspace first (one projection at a time; `w1` is the second matrix of the
 // gate/up pair or NULL) and the GEMM reads the expanded copy.
 int bind_weights(stage_handle* st, hipStream_t stream, GemmArgs& g, const void* w0, const void* s0, const void* z0,
                  const void* w1, const void* s1, const void* z1) {
   if (st->cfg.weight_bits != 4) {
-    g.w0 = (const __bf16*)w0;
-    g.w1 = (const __bf16*)w1;
+    g.w0 = (const e16*)w0;
+    g.w1 = (const e16*)w1;
     return STAGE_OK;
   }
-  const W4Matrix m0{(const uint32_t*)w0, (const __bf16*)s0, (const __bf16*)z0};
+  const W4Matrix m0{(const uint32_t*)w0, (const e16*)s0, (const e16*)z0};
   if (skinny_w4_supports(g.m, g.k, st->cfg.weight_group_size, g.a_lo != nullptr)) {
     // decode-sized micro-batch: the weight-streaming kernel reads the stored form itself
     g.q0 = m0;
-    if (w1) g.q1 = W4Matrix{(const uint32_t*)w1, (const __bf16*)s1, (const __bf16*)z1};
+    if (w1) g.q1 = W4Matrix{(const uint32_t*)w1, (const e16*)s1, (const e16*)z1};
     return STAGE_OK;
   }
-  __bf16* exp0 = (__bf16*)(st->workspace + st->ws.wexp);
+  e16* exp0 = (e16*)(st->workspace + st->ws.wexp);
   Timer t(st, stream, STAGE_K_DEQUANT);
   HIP_TRY(launch_dequant_w4(m0, g.n, g.k, st->cfg.weight_group_size, exp0, stream));
   g.w0 = exp0;
   if (w1) {
-    __bf16* exp1 = exp0 + (size_t)g.n * g.k;
-    const W4Matrix m1{(const uint32_t*)w1, (const __bf16*)s1, (const __bf16*)z1};
+    e16* exp1 = exp0 + (size_t)g.n * g.k;
+    const W4Matrix m1{(const uint32_t*)w1, (const e16*)s1, (const e16*)z1};
     HIP_TRY(launch_dequant_w4(m1, g.n, g.k, st->cfg.weight_group_size, exp1, stream));
     g.w1 = exp1;
   }
@@ -328,7 +329,7 @@ int run_gemm(stage_handle* st, hipStream_t stream, int kernel_class, const GemmA
 // an RMSNorm into `norm_out` (gain != nullptr), or nothing.  When the GEMM splits K across workgroups
 // the sum of the partial results, the residual add and the norm run as one kernel.
 int run_residual_gemm(stage_handle* st, hipStream_t stream, int kernel_class, const GemmArgs& args, GemmEpilogue epi,
-                      const __bf16* gain, __bf16* norm_out, __bf16* norm_out_lo) {
+                      const e16* gain, e16* norm_out, e16* norm_out_lo) {
   const GemmPlan plan = plan_gemm(args.m, args.n, args.k, epi, kNumCus, args.a_lo != nullptr);
   {
     Timer t(st, stream, kernel_class);
@@ -468,16 +469,16 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
   st->staging_used[slot_id] = true;
 
   float* x = (float*)(ws + st->ws.x);
-  __bf16* a = (__bf16*)(ws + st->ws.a);
+  e16* a = (e16*)(ws + st->ws.a);
   const bool two_plane = two_plane_of(c);
-  __bf16* a_lo = two_plane ? (__bf16*)(ws + st->ws.a_lo) : nullptr;
-  __bf16* mlp_lo = two_plane ? (__bf16*)(ws + st->ws.mlp_lo) : nullptr;
-  __bf16* q_lo = two_plane ? (__bf16*)(ws + st->ws.q_lo) : nullptr;
-  __bf16* attn_lo = two_plane ? (__bf16*)(ws + st->ws.attn_lo) : nullptr;
+  e16* a_lo = two_plane ? (e16*)(ws + st->ws.a_lo) : nullptr;
+  e16* mlp_lo = two_plane ? (e16*)(ws + st->ws.mlp_lo) : nullptr;
+  e16* q_lo = two_plane ? (e16*)(ws + st->ws.q_lo) : nullptr;
+  e16* attn_lo = two_plane ? (e16*)(ws + st->ws.attn_lo) : nullptr;
   float* qkv_f32 = (float*)(ws + st->ws.qkv_f32);
-  __bf16* qkv = (__bf16*)(ws + st->ws.qkv);
-  __bf16* attn = (__bf16*)(ws + st->ws.attn);
-  __bf16* mlp = (__bf16*)(ws + st->ws.mlp);
+  e16* qkv = (e16*)(ws + st->ws.qkv);
+  e16* attn = (e16*)(ws + st->ws.attn);
+  e16* mlp = (e16*)(ws + st->ws.mlp);
   float2* cos_sin = (float2*)(ws + st->ws.cos_sin);
   float* splitk = (float*)(ws + st->ws.splitk);
   float* part_o = (float*)(ws + st->ws.part_o);
@@ -495,17 +496,17 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
   }
   const size_t kv_region = (size_t)c.num_kv_blocks * d.nkv * 16 * d.d;   // elements of one K (or V) region
   {
-    // the first layer's input norm also initialises the fp32 residual stream from the bf16 input
+    // the first layer's input norm also initialises the fp32 residual stream from the e16 input
     Timer t(st, stream, STAGE_K_RMSNORM);
-    HIP_TRY(launch_rmsnorm((const __bf16*)hidden_in, x, (const __bf16*)st->layers[0].norm1, a, a_lo, T, d.H, c.rms_eps,
+    HIP_TRY(launch_rmsnorm((const e16*)hidden_in, x, (const e16*)st->layers[0].norm1, a, a_lo, T, d.H, c.rms_eps,
                            true, stream));
   }
   for (int l = 0; l < d.L; ++l) {
     const stage_layer_weights& w = st->layers[l];
     const bool last = l == d.L - 1;
     const bool tap = taps && taps->tap_layer == l;
-    __bf16* k_pool = (__bf16*)(st->kv_pool + (size_t)l * (size_t)c.kv_layer_stride_bytes);
-    __bf16* v_pool = k_pool + kv_region;
+    e16* k_pool = (e16*)(st->kv_pool + (size_t)l * (size_t)c.kv_layer_stride_bytes);
+    e16* v_pool = k_pool + kv_region;
     // `a` holds RMSNorm(x; norm1 of this layer) here
     if (tap && taps->tap_norm1)
       HIP_TRY(hipMemcpyAsync(taps->tap_norm1, a, (size_t)T * d.H * 2, hipMemcpyDeviceToDevice, stream));
@@ -522,7 +523,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       }
       Timer t(st, stream, STAGE_K_ROPE_APPEND);
       RopeAppendArgs r{plan.partials ? splitk : qkv_f32, plan.partials ? plan.splits : 1, (size_t)T * d.qkv_out,
-                       (const __bf16*)w.bqkv, qkv, q_lo, cos_sin, d_slots, k_pool, v_pool, T, d.nq, d.nkv, d.d};
+                       (const e16*)w.bqkv, qkv, q_lo, cos_sin, d_slots, k_pool, v_pool, T, d.nq, d.nkv, d.d};
       HIP_TRY(launch_rope_append(r, stream));
     }
     if (tap && taps->tap_qkv)
@@ -547,14 +548,14 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       g.a = attn; g.a_lo = attn_lo; g.resid = x; g.partial = splitk;
       g.m = T; g.n = d.H; g.k = d.nq * d.d; g.lda = d.nq * d.d; g.ldo = d.H;
       if (int rc = bind_weights(st, stream, g, w.wo, w.so, w.zo, nullptr, nullptr, nullptr)) return rc;
-      int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_O, g, kEpiResidualF32, (const __bf16*)w.norm2, a, a_lo);
+      int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_O, g, kEpiResidualF32, (const e16*)w.norm2, a, a_lo);
       if (rc) return rc;
     }
     if (tap && taps->tap_h)
       HIP_TRY(hipMemcpyAsync(taps->tap_h, x, (size_t)T * d.H * 4, hipMemcpyDeviceToDevice, stream));
     {
       GemmArgs g{};
-      g.a = a; g.a_lo = a_lo; g.out_bf16 = mlp; g.out_lo = mlp_lo;
+      g.a = a; g.a_lo = a_lo; g.out_e16 = mlp; g.out_lo = mlp_lo;
       g.partial = splitk;
       g.m = T; g.n = d.F; g.k = d.H; g.lda = d.H; g.ldo = d.F;
       if (int rc = bind_weights(st, stream, g, w.wgate, w.sgate, w.zgate, w.wup, w.sup, w.zup)) return rc;
@@ -568,11 +569,11 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       // kernel, so the tap sees it; the sum and its rounding are the same as in the fused epilogue.
       const bool fused_out = last && !(tap && taps->tap_x);
       GemmArgs g{};
-      g.a = mlp; g.a_lo = mlp_lo; g.resid = x; g.out_bf16 = (__bf16*)hidden_out;
+      g.a = mlp; g.a_lo = mlp_lo; g.resid = x; g.out_e16 = (e16*)hidden_out;
       g.partial = splitk;
       g.m = T; g.n = d.H; g.k = d.F; g.lda = d.F; g.ldo = d.H;
       if (int rc = bind_weights(st, stream, g, w.wdown, w.sdown, w.zdown, nullptr, nullptr, nullptr)) return rc;
-      const __bf16* next_gain = last ? nullptr : (const __bf16*)st->layers[l + 1].norm1;
+      const e16* next_gain = last ? nullptr : (const e16*)st->layers[l + 1].norm1;
       int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_DOWN, g, fused_out ? kEpiResidualOut : kEpiResidualF32,
                                  next_gain, a, a_lo);
       if (rc) return rc;
@@ -580,8 +581,8 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
         HIP_TRY(hipMemcpyAsync(taps->tap_x, x, (size_t)T * d.H * 4, hipMemcpyDeviceToDevice, stream));
       if (last && !fused_out) {
         const size_t n = (size_t)T * d.H;
-        hipLaunchKernelGGL(f32_to_bf16_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, x,
-                           (__bf16*)hidden_out, n);
+        hipLaunchKernelGGL(f32_to_e16_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, x,
+                           (e16*)hidden_out, n);
         HIP_TRY(hipGetLastError());
       }
     }
@@ -790,7 +791,7 @@ int stage_embed(stage_handle* st, void* hip_stream, const void* table, int32_t v
   int rc = stage_small_h2d(st, stream, token_ids, (size_t)num_tokens * 4, d_ids);
   if (rc) return rc;
   Timer t(st, stream, STAGE_K_EMBED);
-  HIP_TRY(launch_embed_gather((const __bf16*)table, d_ids, (__bf16*)hidden_out, num_tokens, st->dim.H, stream));
+  HIP_TRY(launch_embed_gather((const e16*)table, d_ids, (e16*)hidden_out, num_tokens, st->dim.H, stream));
   return STAGE_OK;
 }
 
@@ -823,14 +824,14 @@ int stage_head(stage_handle* st, void* hip_stream, int32_t num_tokens, const voi
   int32_t* d_rows = (int32_t*)(ws + st->ws.ends_meta);
   int rc = stage_small_h2d(st, stream, rows.data(), (size_t)num_seqs * 4, d_rows);
   if (rc) return rc;
-  __bf16* head_a = (__bf16*)(ws + st->ws.head_a);
+  e16* head_a = (e16*)(ws + st->ws.head_a);
   {
     Timer t(st, stream, STAGE_K_HEAD_NORM);
-    HIP_TRY(launch_gather_rmsnorm((const __bf16*)hidden, d_rows, (const __bf16*)final_norm, head_a, num_seqs, d.H,
+    HIP_TRY(launch_gather_rmsnorm((const e16*)hidden, d_rows, (const e16*)final_norm, head_a, num_seqs, d.H,
                                   c.rms_eps, stream));
   }
   GemmArgs g{};
-  g.a = head_a; g.w0 = (const __bf16*)lm_head; g.partial = (float*)(ws + st->ws.splitk);
+  g.a = head_a; g.w0 = (const e16*)lm_head; g.partial = (float*)(ws + st->ws.splitk);
   g.m = num_seqs; g.n = vocab; g.k = d.H; g.lda = d.H; g.ldo = vocab;
   const GemmPlan plan = plan_gemm(g.m, g.n, g.k, kEpiStoreF32, kNumCus, false);
   // without partial sums the GEMM writes the logits itself (to the caller's buffer if there is one)
@@ -882,7 +883,7 @@ const char* stage_kernel_name(int32_t kernel) {
     case STAGE_K_GEMM_QKV:
     case STAGE_K_GEMM_O:
     case STAGE_K_GEMM_GATEUP:
-    case STAGE_K_GEMM_DOWN: return "gemm_bf16_kernel";
+    case STAGE_K_GEMM_DOWN: return "gemm_tile_kernel";
     case STAGE_K_ROPE_APPEND: return "rope_append_kernel";
     case STAGE_K_ATTN_PREFILL: return "attn_prefill_kernel";
     case STAGE_K_ATTN_DECODE: return "attn_decode_kernel";
@@ -891,7 +892,7 @@ const char* stage_kernel_name(int32_t kernel) {
     case STAGE_K_ROPE_TABLE: return "rope_table_kernel";
     case STAGE_K_EMBED: return "embed_gather_kernel";
     case STAGE_K_HEAD_NORM: return "gather_rmsnorm_kernel";
-    case STAGE_K_GEMM_HEAD: return "gemm_bf16_kernel";
+    case STAGE_K_GEMM_HEAD: return "gemm_tile_kernel";
     case STAGE_K_HEAD_ARGMAX: return "argmax_rows_kernel";
     case STAGE_K_DEQUANT: return "dequant_w4_kernel";
     default: return nullptr;
@@ -915,5 +916,7 @@ void stage_destroy(stage_handle* st) {
 }
 
 const char* stage_last_error(void) { return g_error; }
+
+int32_t stage_elem_type(void) { return kElemIsF16 ? STAGE_ELEM_F16 : STAGE_ELEM_BF16; }
 
 }  // extern "C"

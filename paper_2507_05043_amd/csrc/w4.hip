@@ -1,6 +1,6 @@
 // 4-bit group-quantised projection weights (the precision the paper runs its 70B model at, section 5
 // "Models").  Format: codes uint32 [N][K/8], element k of a row in bits 4*(k%8)..4*(k%8)+3 of word k/8;
-// scales and zero points bf16 [N][K/group];  W[n][k] = (code - zero) * scale.
+// scales and zero points e16 [N][K/group];  W[n][k] = (code - zero) * scale.
 #include "w4.hpp"
 #include "common.hpp"
 
@@ -10,28 +10,28 @@ namespace molink {
 
 namespace {
 
-// One thread expands one word (8 consecutive k of one row) into 16 bytes of bf16.
-__global__ __launch_bounds__(256) void dequant_w4_kernel(const uint32_t* __restrict__ codes, const __bf16* __restrict__ scales,
-                                                        const __bf16* __restrict__ zeros, int words_per_row, int group,
-                                                        size_t total_words, __bf16* __restrict__ out) {
+// One thread expands one word (8 consecutive k of one row) into 16 bytes of e16.
+__global__ __launch_bounds__(256) void dequant_w4_kernel(const uint32_t* __restrict__ codes, const e16* __restrict__ scales,
+                                                        const e16* __restrict__ zeros, int words_per_row, int group,
+                                                        size_t total_words, e16* __restrict__ out) {
   const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total_words) return;
   const size_t row = idx / words_per_row;
   const int word = (int)(idx % words_per_row);
   const int groups_per_row = words_per_row * 8 / group;
   const size_t g = row * groups_per_row + (size_t)(word * 8 / group);
-  const float s = bf16_to_f32(scales[g]), z = bf16_to_f32(zeros[g]);
+  const float s = e16_to_f32(scales[g]), z = e16_to_f32(zeros[g]);
   const uint32_t x = codes[idx];
-  bf16x8 o;
+  e16x8 o;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) o[i] = f32_to_bf16(((float)((x >> (4 * i)) & 15u) - z) * s);
-  *reinterpret_cast<bf16x8*>(out + idx * 8) = o;
+  for (int i = 0; i < 8; ++i) o[i] = f32_to_e16(((float)((x >> (4 * i)) & 15u) - z) * s);
+  *reinterpret_cast<e16x8*>(out + idx * 8) = o;
 }
 
 // ------------------------------------------------------------------------------------------------
 // Weight-streaming GEMM on the stored 4-bit form, for micro-batches of at most 64 rows (decode).
 //
-// Decomposition as in the bf16 weight-streaming kernel: K is cut into slices of 1024, a workgroup (one
+// Decomposition as in the e16 weight-streaming kernel: K is cut into slices of 1024, a workgroup (one
 // per CU, eight waves) keeps one slice and walks over units of 16 weight rows; the slices' partial
 // sums are added by the reduction kernels.  A quarter of the bytes per weight changes what is scarce:
 //  - Every weight is expanded exactly once.  Wave w owns the k range [128 w, 128 w + 128) of the slice -
@@ -39,14 +39,15 @@ __global__ __launch_bounds__(256) void dequant_w4_kernel(const uint32_t* __restr
 //    as MFMA operands), so no two waves read the same code.  The eight waves' sums over their k ranges
 //    meet in LDS: waves 0-3 each own one block of activation rows, take the eight contributions to it
 //    after a barrier, add them in wave order and write the block's partial sums.
-//  - Expansion is folded into the contraction.  A code c becomes the bf16 number 128 + c by or-ing its
-//    four bits into 0x4300 (two codes per 32-bit operation; the word's fields k and k+4 land in one
+//  - Expansion is folded into the contraction.  A code c becomes the e16 number 128 + c by or-ing its
+//    four bits into 0x4300 (bfloat16; IEEE half: 1024 + c, into 0x6400; "128" below stands for either
+//    offset; two codes per 32-bit operation; the word's fields k and k+4 land in one
 //    register, and the activation operands are permuted once to the same order).  The MFMAs give
 //    T = sum (128 + c) a over the wave's group; scale and zero point enter once per accumulator register:
 //    s * (T - (128 + z) * sum a), with sum a from one MFMA against ones per slice.  The weights are the
 //    MFMA's row operand, so a lane ends up with four consecutive weight rows of one activation row:
 //    16-byte stores, and one activation sum per lane.  Products and sums are fp32, so nothing but the
-//    activations is ever rounded to bf16.
+//    activations is ever rounded to e16.
 //  - Two waves per SIMD and two units between barriers: a unit is a chain of LDS reads, expansion, MFMAs,
 //    scaling and exchange whose latencies a wave can only hide behind another such chain.
 // Waves 4-7 also issue the loads (global_load_lds) and no stores, waves 0-3 the stores and no loads, so
@@ -54,20 +55,29 @@ __global__ __launch_bounds__(256) void dequant_w4_kernel(const uint32_t* __restr
 // weight rows x 512 bytes of codes, laid out so that the 4-byte fragment reads of 16 rows fall into 64
 // different banks, plus the rows' scales and zero points of the slice; four stages, up to four in flight.
 // ------------------------------------------------------------------------------------------------
-constexpr int kW4KS = 1024;            // K elements per slice (must equal the bf16 streaming kernel's)
+constexpr int kW4KS = 1024;            // K elements per slice (must equal the e16 streaming kernel's)
 constexpr int kW4Rows = 16;            // weight rows per unit
 constexpr int kW4UnitsPerStage = 2;
 constexpr int kW4Stages = 4;
 constexpr int kW4StageBytes = 32 * 512 + 512 + 512;   // codes, scales [4 pairs][32 rows] dwords, zero points likewise
 constexpr int kW4Group = 128;
 
-// Two 4-bit codes (bits 0-3 and 16-19 of x) as two bf16 numbers 128 + code.  Plain C on purpose: written as an
+// The offset whose e16 pattern has its four lowest mantissa bits worth 1, 2, 4, 8, and 1.0 as a pair.
+#ifdef MOLINK_F16
+constexpr uint32_t kCodeBasePair = 0x64006400u, kOnesPair = 0x3C003C00u;
+constexpr float kCodeBase = 1024.f;
+#else
+constexpr uint32_t kCodeBasePair = 0x43004300u, kOnesPair = 0x3F803F80u;
+constexpr float kCodeBase = 128.f;
+#endif
+
+// Two 4-bit codes (bits 0-3 and 16-19 of x) as two e16 numbers offset + code.  Plain C on purpose: written as an
 // inline-assembly v_and_or_b32 the result fed the next MFMA without the wait states the compiler inserts
 // between a vector write and a matrix read (it does not look inside assembly), and results were wrong.
-__device__ __forceinline__ uint32_t expand_pair(uint32_t x) { return (x & 0x000F000Fu) | 0x43004300u; }
+__device__ __forceinline__ uint32_t expand_pair(uint32_t x) { return (x & 0x000F000Fu) | kCodeBasePair; }
 
-__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+__device__ __forceinline__ f32x4 mfma16(e16x8 a, e16x8 b, f32x4 c) {
+  return mfma_16x16x32(a, b, c);
 }
 
 // NBLK: blocks of 16 activation rows in use (1..4); wave j < NBLK owns block j.
@@ -78,15 +88,15 @@ __global__ __launch_bounds__(512) void gemm_skinny_w4_kernel(GemmArgs p, int nv,
   __shared__ __attribute__((aligned(16))) char red[2][4][8][1024];   // [unit of the stage][owner block][source wave][lane x 16 B]
 
   // the arguments as plain values (the lambdas below capture these, not the struct)
-  const __bf16* const arg_a = p.a;
+  const e16* const arg_a = p.a;
   float* const arg_partial = p.partial;
   const int arg_m = p.m, arg_n = p.n, arg_k = p.k, arg_lda = p.lda;
   const uint32_t* const codes0 = p.q0.codes;
   const uint32_t* const codes1 = swiglu ? p.q1.codes : p.q0.codes;
-  const __bf16* const scales0 = p.q0.scales;
-  const __bf16* const scales1 = swiglu ? p.q1.scales : p.q0.scales;
-  const __bf16* const zeros0 = p.q0.zeros;
-  const __bf16* const zeros1 = swiglu ? p.q1.zeros : p.q0.zeros;
+  const e16* const scales0 = p.q0.scales;
+  const e16* const scales1 = swiglu ? p.q1.scales : p.q0.scales;
+  const e16* const zeros0 = p.q0.zeros;
+  const e16* const zeros1 = swiglu ? p.q1.zeros : p.q0.zeros;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -161,7 +171,7 @@ __global__ __launch_bounds__(512) void gemm_skinny_w4_kernel(GemmArgs p, int nv,
   const int kw = kbase + 128 * wave;                // this wave's k range: one group
   // activations as MFMA column operands: lane (row col of block j, quarter) holds k = kw + 32 t + 8 quarter .. +7 of
   // MFMA step t, in the order (k0 k4 k1 k5 k2 k6 k3 k7) the expanded weights come out in
-  bf16x8 act[NBLK][4];
+  e16x8 act[NBLK][4];
 #pragma unroll
   for (int j = 0; j < NBLK; ++j) {
     int m = 16 * j + col;
@@ -173,14 +183,14 @@ __global__ __launch_bounds__(512) void gemm_skinny_w4_kernel(GemmArgs p, int nv,
       if (k < arg_k) x = __builtin_bit_cast(u32x4, load8(arg_a + (size_t)m * arg_lda + k));
       const u32x4 y = {(x[0] & 0xFFFFu) | (x[2] << 16), (x[0] >> 16) | (x[2] & 0xFFFF0000u),
                        (x[1] & 0xFFFFu) | (x[3] << 16), (x[1] >> 16) | (x[3] & 0xFFFF0000u)};
-      act[j][t] = __builtin_bit_cast(bf16x8, y);
+      act[j][t] = __builtin_bit_cast(e16x8, y);
     }
   }
   // sum of this lane's activation row (row col of block j) over the wave's group
   float asum[NBLK];
   {
-    const u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
-    const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
+    const u32x4 ones_bits = {kOnesPair, kOnesPair, kOnesPair, kOnesPair};
+    const e16x8 ones = __builtin_bit_cast(e16x8, ones_bits);
 #pragma unroll
     for (int j = 0; j < NBLK; ++j) {
       f32x4 s = {0.f, 0.f, 0.f, 0.f};
@@ -230,15 +240,15 @@ __global__ __launch_bounds__(512) void gemm_skinny_w4_kernel(GemmArgs p, int nv,
     for (int t = 0; t < 4; ++t) {
       const uint32_t x = xs[t];
       const u32x4 wbits = {expand_pair(x), expand_pair(x >> 4), expand_pair(x >> 8), expand_pair(x >> 12)};
-      const bf16x8 wf = __builtin_bit_cast(bf16x8, wbits);
+      const e16x8 wf = __builtin_bit_cast(e16x8, wbits);
 #pragma unroll
       for (int j = 0; j < NBLK; ++j) tmp[j] = mfma16(wf, act[j][t], tmp[j]);
     }
     f32x4 s, zc;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      s[r] = __uint_as_float((wave & 1) ? sc[r] & 0xFFFF0000u : sc[r] << 16);
-      zc[r] = 128.f + __uint_as_float((wave & 1) ? zp[r] & 0xFFFF0000u : zp[r] << 16);
+      s[r] = (wave & 1) ? e16_hi(sc[r]) : e16_lo(sc[r]);
+      zc[r] = kCodeBase + ((wave & 1) ? e16_hi(zp[r]) : e16_lo(zp[r]));
     }
     // hand every block's contribution to its owner
 #pragma unroll
@@ -280,7 +290,7 @@ __global__ __launch_bounds__(512) void gemm_skinny_w4_kernel(GemmArgs p, int nv,
 
 }  // namespace
 
-hipError_t launch_dequant_w4(const W4Matrix& w, int n, int k, int group, __bf16* out, hipStream_t stream) {
+hipError_t launch_dequant_w4(const W4Matrix& w, int n, int k, int group, e16* out, hipStream_t stream) {
   if (k % 8 || group % 8 || k % group) return hipErrorInvalidValue;
   const size_t total = (size_t)n * (k / 8);
   hipLaunchKernelGGL(dequant_w4_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, w.codes, w.scales,

@@ -12,19 +12,20 @@ from .stage import Stage, make_config
 def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_std=None,
                max_tokens: Optional[int] = None, alias_layers: bool = False, fill_kv: bool = True,
                device: str = "cuda:0", activation_planes: int = 0, vocab_size: int = 0,
-               qkv_bias: bool = False, weight_group_size: int = 0) -> Stage:
+               qkv_bias: bool = False, weight_group_size: int = 0, dtype: torch.dtype = torch.bfloat16) -> Stage:
     """Draw the stage's weights on the device, size the pool and workspace for `mb`, fill the cache.
-    weight_group_size > 0: 4-bit group-quantised projection weights with that group size."""
+    weight_group_size > 0: 4-bit group-quantised projection weights with that group size.
+    dtype: the 16-bit element type (bfloat16, or float16 for the half-precision library)."""
     if weight_group_size:
         layers = [synth.draw_w4_layer(shape, l, seed=seed, group=weight_group_size, device=device,
-                                      weight_std=0.02 if weight_std is None else float(weight_std))
+                                      weight_std=0.02 if weight_std is None else float(weight_std), dtype=dtype)
                   for l in range(shape.num_layers)]
     else:
-        layers = [synth.draw_layer_weights(shape, l, seed=seed, device=device, weight_std=weight_std)
+        layers = [synth.draw_layer_weights(shape, l, seed=seed, device=device, weight_std=weight_std, dtype=dtype)
                   for l in range(shape.num_layers)]
     if qkv_bias:
         for l, w in enumerate(layers):
-            w["bqkv"] = synth.draw_qkv_bias(shape, l, seed=seed, device=device)
+            w["bqkv"] = synth.draw_qkv_bias(shape, l, seed=seed, device=device, dtype=dtype)
     cfg = make_config(num_layers=shape.num_layers, hidden=shape.hidden, num_q_heads=shape.num_q_heads,
                       num_kv_heads=shape.num_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn,
                       rms_eps=shape.rms_eps, rope_theta=shape.rope_theta, num_kv_blocks=mb.num_kv_blocks,
@@ -33,7 +34,7 @@ def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_
                       kv_layer_stride_bytes=0 if alias_layers else None, activation_planes=activation_planes,
                       vocab_size=vocab_size, weight_bits=4 if weight_group_size else 0,
                       weight_group_size=weight_group_size)
-    st = Stage(cfg, layers, device=device)
+    st = Stage(cfg, layers, device=device, dtype=dtype)
     if fill_kv:
         fill_pool(st, shape, mb, seed)
     return st
@@ -41,21 +42,21 @@ def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_
 
 def fill_pool(st: Stage, shape: synth.StageShape, mb: synth.MicroBatch, seed: int, progress: bool = False) -> None:
     """Cached context drawn into its slots; every other slot of the pool is NaN."""
-    st.kv_pool.view(torch.bfloat16).fill_(float("nan"))
+    st.kv_pool.view(st.dtype).fill_(float("nan"))
     valid = synth.valid_slot_mask(mb, shape.kv_block_size)
     used = torch.nonzero(valid.any(dim=1)).flatten()
     if used.numel() == 0:
         return
     used_dev = used.to(st.device)
     m = valid[used].to(st.device).view(-1, shape.kv_block_size, 1, 1)
-    nan = torch.tensor(float("nan"), dtype=torch.bfloat16, device=st.device)
+    nan = torch.tensor(float("nan"), dtype=st.dtype, device=st.device)
     layers = 1 if st.cfg.kv_layer_stride_bytes == 0 else shape.num_layers
     step = 4096
     for l in range(layers):
         for kv in (0, 1):
             for i in range(0, used_dev.numel(), step):
                 blk = used_dev[i:i + step]
-                vals = synth.draw_kv_blocks(shape, mb.num_kv_blocks, l, kv, blk, seed=seed)
+                vals = synth.draw_kv_blocks(shape, mb.num_kv_blocks, l, kv, blk, seed=seed, dtype=st.dtype)
                 vals = torch.where(m[i:i + step], vals, nan)
                 st.write_kv_blocks(l, kv, blk, vals)
         if progress:

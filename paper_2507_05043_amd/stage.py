@@ -1,4 +1,5 @@
-"""ctypes binding of libmolink_stage.so: argument marshalling only.
+"""ctypes binding of libmolink_stage.so (bfloat16 elements) and libmolink_stage_f16.so (IEEE half
+elements, the same sources and ABI): argument marshalling only.
 
 Every step of the forward pass runs in the library's HIP kernels; torch is used for device
 memory, the current stream handle and nothing else.  The library is loaded from the package
@@ -14,6 +15,8 @@ import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmolink_stage.so")
+LIB_PATHS = {torch.bfloat16: LIB_PATH, torch.float16: os.path.join(_HERE, "libmolink_stage_f16.so")}
+ELEM_TYPES = {torch.bfloat16: 0, torch.float16: 1}      # what stage_elem_type() of each library returns
 
 KERNEL_CLASSES = {
     "rmsnorm": 0, "gemm_qkv": 1, "rope_append": 2, "attn_prefill": 3, "attn_decode": 4, "attn_merge": 5,
@@ -57,18 +60,20 @@ class StageTaps(ctypes.Structure):
         (n, ctypes.c_void_p) for n in ("tap_norm1", "tap_qkv", "tap_attn", "tap_h", "tap_mlp", "tap_x")]
 
 
-_lib = None
+_libs: Dict[torch.dtype, ctypes.CDLL] = {}
 
 
-def load_library() -> ctypes.CDLL:
-    """Load the built shared library (raises if it has not been built)."""
-    global _lib
-    if _lib is not None:
-        return _lib
-    if not os.path.exists(LIB_PATH):
+def load_library(dtype: torch.dtype = torch.bfloat16) -> ctypes.CDLL:
+    """Load the built shared library for a 16-bit element type (raises if it has not been built)."""
+    if dtype in _libs:
+        return _libs[dtype]
+    if dtype not in LIB_PATHS:
+        raise ValueError(f"no library for element type {dtype}: bfloat16 and float16 are built")
+    path = LIB_PATHS[dtype]
+    if not os.path.exists(path):
         raise FileNotFoundError(
-            f"{LIB_PATH} is missing: build it with `python -m paper_2507_05043_amd.build`")
-    lib = ctypes.CDLL(LIB_PATH)
+            f"{path} is missing: build it with `python -m paper_2507_05043_amd.build`")
+    lib = ctypes.CDLL(path)
     i32p, i64p = ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)
     cfgp = ctypes.POINTER(StageConfig)
     lib.stage_kv_layer_bytes.argtypes = [cfgp, ctypes.POINTER(ctypes.c_size_t)]
@@ -98,13 +103,16 @@ def load_library() -> ctypes.CDLL:
                  "stage_init", "stage_forward", "stage_forward_taps", "stage_profile", "stage_profile_enable",
                  "stage_profile_read", "stage_embed", "stage_head"):
         getattr(lib, name).restype = ctypes.c_int
-    _lib = lib
+    lib.stage_elem_type.restype = ctypes.c_int32
+    if lib.stage_elem_type() != ELEM_TYPES[dtype]:
+        raise RuntimeError(f"{path} was not built for {dtype}")
+    _libs[dtype] = lib
     return lib
 
 
-def _check(rc: int) -> None:
+def _check(rc: int, lib: Optional[ctypes.CDLL] = None) -> None:
     if rc != 0:
-        raise StageError(rc, load_library().stage_last_error().decode())
+        raise StageError(rc, (lib or load_library()).stage_last_error().decode())
 
 
 def make_config(*, num_layers, hidden, num_q_heads, num_kv_heads, head_dim, ffn, rms_eps, rope_theta,
@@ -126,9 +134,12 @@ def stage_kv_layer_bytes(cfg: StageConfig) -> int:
     return out.value
 
 
-def stage_workspace_bytes(cfg: StageConfig) -> int:
+def stage_workspace_bytes(cfg: StageConfig, dtype: torch.dtype = torch.bfloat16) -> int:
+    """Workspace the library for `dtype` needs (the half-precision one never adds a second activation
+    plane by itself, so deep stages need less there)."""
     out = ctypes.c_size_t()
-    _check(load_library().stage_workspace_bytes(ctypes.byref(cfg), ctypes.byref(out)))
+    lib = load_library(dtype)
+    _check(lib.stage_workspace_bytes(ctypes.byref(cfg), ctypes.byref(out)), lib)
     return out.value
 
 
@@ -167,8 +178,10 @@ class Stage:
     """One pipeline stage bound to its weights, KV pool and workspace (all torch CUDA tensors)."""
 
     def __init__(self, cfg: StageConfig, layers: Sequence[Dict[str, torch.Tensor]], *, device="cuda:0",
-                 kv_pool: Optional[torch.Tensor] = None):
-        lib = load_library()
+                 kv_pool: Optional[torch.Tensor] = None, dtype: torch.dtype = torch.bfloat16):
+        lib = load_library(dtype)
+        self._lib = lib
+        self.dtype = dtype            # the 16-bit element type of weights, activations and the KV pool
         self.cfg = cfg
         self.device = torch.device(device)
         self.layers = [dict(l) for l in layers]          # keep the tensors alive
@@ -181,7 +194,7 @@ class Stage:
                 if not four_bit and (name in W4_SCALES or name in W4_ZEROS):
                     continue
                 t = w[name]
-                want = torch.int32 if four_bit and name in W4_MATRICES else torch.bfloat16   # code words / bf16
+                want = torch.int32 if four_bit and name in W4_MATRICES else dtype   # code words / elements
                 if t.dtype != want or not t.is_contiguous() or t.device != self.device:
                     raise ValueError(f"layer {l} {name}: need a contiguous {want} tensor on {self.device}")
                 setattr(arr[l], name, t.data_ptr())
@@ -190,12 +203,15 @@ class Stage:
         if kv_pool is None:
             kv_pool = torch.empty(pool_bytes, dtype=torch.uint8, device=self.device)
         self.kv_pool = kv_pool
-        self.workspace = torch.empty(stage_workspace_bytes(cfg), dtype=torch.uint8, device=self.device)
+        self.workspace = torch.empty(stage_workspace_bytes(cfg, dtype), dtype=torch.uint8, device=self.device)
         handle = ctypes.c_void_p()
-        _check(lib.stage_init(ctypes.byref(cfg), arr, kv_pool.data_ptr(), kv_pool.numel() * kv_pool.element_size(),
+        self._check(lib.stage_init(ctypes.byref(cfg), arr, kv_pool.data_ptr(), kv_pool.numel() * kv_pool.element_size(),
                               self.workspace.data_ptr(), self.workspace.numel(), self.device.index or 0,
                               ctypes.byref(handle)))
         self._handle = handle
+
+    def _check(self, rc: int) -> None:
+        _check(rc, self._lib)
 
     # ---- KV pool views (layout of the ABI: K [blocks][nkv][d/32][16 positions][32], V [blocks][nkv][d][16])
     # position of slot s = s with bits 2 and 3 exchanged; the exchange is its own inverse
@@ -205,7 +221,7 @@ class Stage:
         c = self.cfg
         region_bytes = stage_kv_layer_bytes(c) // 2
         start = layer * c.kv_layer_stride_bytes + kv * region_bytes
-        return self.kv_pool.view(torch.uint8)[start:start + region_bytes].view(torch.bfloat16)
+        return self.kv_pool.view(torch.uint8)[start:start + region_bytes].view(self.dtype)
 
     def k_view(self, layer: int) -> torch.Tensor:
         c = self.cfg
@@ -238,11 +254,11 @@ class Stage:
     def profile(self, num_seqs: int, q_len: int, ctx_len: int, *, warmup: int = 2, iters: int = 5) -> float:
         """Milliseconds per micro-batch of `num_seqs` sequences with `q_len` new tokens after `ctx_len` cached ones."""
         t = num_seqs * q_len
-        hidden = torch.zeros(max(t, 1), self.cfg.hidden, dtype=torch.bfloat16, device=self.device)
+        hidden = torch.zeros(max(t, 1), self.cfg.hidden, dtype=self.dtype, device=self.device)
         out = torch.empty_like(hidden)
         ms = ctypes.c_double()
         stream = torch.cuda.current_stream(self.device).cuda_stream
-        _check(load_library().stage_profile(self._handle, ctypes.c_void_p(stream), num_seqs, q_len, ctx_len, warmup, iters,
+        self._check(self._lib.stage_profile(self._handle, ctypes.c_void_p(stream), num_seqs, q_len, ctx_len, warmup, iters,
                                             ctypes.c_void_p(hidden.data_ptr()), ctypes.c_void_p(out.data_ptr()),
                                             ctypes.byref(ms)))
         return ms.value
@@ -250,11 +266,11 @@ class Stage:
     # ---- the forward pass
     def forward(self, hidden: torch.Tensor, positions, q_lens, ctx_lens, block_tables, *,
                 out: Optional[torch.Tensor] = None, want_slots: bool = False, taps_layer: Optional[int] = None):
-        lib = load_library()
+        lib = self._lib
         c = self.cfg
         t = hidden.shape[0]
-        if hidden.dtype != torch.bfloat16 or not hidden.is_contiguous() or hidden.shape[1] != c.hidden:
-            raise ValueError("hidden must be a contiguous bf16 [T, hidden] tensor")
+        if hidden.dtype != self.dtype or not hidden.is_contiguous() or hidden.shape[1] != c.hidden:
+            raise ValueError("hidden must be a contiguous 16-bit [T, hidden] tensor")
         pos_t, pos_p = _i32_array(positions, t)
         q_t, q_p = _i32_array(q_lens)
         c_t, c_p = _i32_array(ctx_lens, q_t.numel())
@@ -268,21 +284,21 @@ class Stage:
                 out.data_ptr(), slots_p]
         taps = None
         if taps_layer is None:
-            _check(lib.stage_forward(*args))
+            self._check(lib.stage_forward(*args))
         else:
             qkv_out = (c.num_q_heads + 2 * c.num_kv_heads) * c.head_dim
             dev = self.device
             taps = {
-                "a": torch.empty(t, c.hidden, dtype=torch.bfloat16, device=dev),
-                "qkv": torch.empty(t, qkv_out, dtype=torch.bfloat16, device=dev),
-                "attn": torch.empty(t, c.num_q_heads * c.head_dim, dtype=torch.bfloat16, device=dev),
+                "a": torch.empty(t, c.hidden, dtype=self.dtype, device=dev),
+                "qkv": torch.empty(t, qkv_out, dtype=self.dtype, device=dev),
+                "attn": torch.empty(t, c.num_q_heads * c.head_dim, dtype=self.dtype, device=dev),
                 "h": torch.empty(t, c.hidden, dtype=torch.float32, device=dev),
-                "m": torch.empty(t, c.ffn, dtype=torch.bfloat16, device=dev),
+                "m": torch.empty(t, c.ffn, dtype=self.dtype, device=dev),
                 "x": torch.empty(t, c.hidden, dtype=torch.float32, device=dev),
             }
             st = StageTaps(taps_layer, taps["a"].data_ptr(), taps["qkv"].data_ptr(), taps["attn"].data_ptr(),
                            taps["h"].data_ptr(), taps["m"].data_ptr(), taps["x"].data_ptr())
-            _check(lib.stage_forward_taps(*args, ctypes.byref(st)))
+            self._check(lib.stage_forward_taps(*args, ctypes.byref(st)))
         result = [out]
         if want_slots:
             result.append(slots.tolist())
@@ -293,14 +309,14 @@ class Stage:
     # ---- the two ends of the pipeline
     def embed(self, table: torch.Tensor, token_ids, *, out: Optional[torch.Tensor] = None) -> torch.Tensor:
         c = self.cfg
-        if table.dtype != torch.bfloat16 or not table.is_contiguous() or table.shape[1] != c.hidden:
-            raise ValueError("table must be a contiguous bf16 [vocab, hidden] tensor")
+        if table.dtype != self.dtype or not table.is_contiguous() or table.shape[1] != c.hidden:
+            raise ValueError("table must be a contiguous 16-bit [vocab, hidden] tensor")
         ids_t, ids_p = _i32_array(token_ids)
         t = ids_t.numel()
         if out is None:
-            out = torch.empty(t, c.hidden, dtype=torch.bfloat16, device=self.device)
+            out = torch.empty(t, c.hidden, dtype=self.dtype, device=self.device)
         stream = torch.cuda.current_stream(self.device).cuda_stream
-        _check(load_library().stage_embed(self._handle, ctypes.c_void_p(stream), table.data_ptr(), table.shape[0], t,
+        self._check(self._lib.stage_embed(self._handle, ctypes.c_void_p(stream), table.data_ptr(), table.shape[0], t,
                                           ids_p, out.data_ptr()))
         return out
 
@@ -308,11 +324,11 @@ class Stage:
              want_logits: bool = True):
         """(next_tokens int32 [S], logits f32 [S, vocab] or None) for the last row of every sequence."""
         c = self.cfg
-        if hidden.dtype != torch.bfloat16 or not hidden.is_contiguous() or hidden.shape[1] != c.hidden:
-            raise ValueError("hidden must be a contiguous bf16 [T, hidden] tensor")
+        if hidden.dtype != self.dtype or not hidden.is_contiguous() or hidden.shape[1] != c.hidden:
+            raise ValueError("hidden must be a contiguous 16-bit [T, hidden] tensor")
         for w in (final_norm, lm_head):
-            if w.dtype != torch.bfloat16 or not w.is_contiguous():
-                raise ValueError("final_norm and lm_head must be contiguous bf16 tensors")
+            if w.dtype != self.dtype or not w.is_contiguous():
+                raise ValueError("final_norm and lm_head must be contiguous 16-bit tensors")
         if lm_head.shape[1] != c.hidden or final_norm.numel() != c.hidden:
             raise ValueError("final_norm must be [hidden] and lm_head [vocab, hidden]")
         q_t, q_p = _i32_array(q_lens)
@@ -321,7 +337,7 @@ class Stage:
         logits = torch.empty(s, vocab, dtype=torch.float32, device=self.device) if want_logits else None
         tokens = torch.empty(s, dtype=torch.int32, device=self.device)
         stream = torch.cuda.current_stream(self.device).cuda_stream
-        _check(load_library().stage_head(self._handle, ctypes.c_void_p(stream), hidden.shape[0], hidden.data_ptr(), s, q_p,
+        self._check(self._lib.stage_head(self._handle, ctypes.c_void_p(stream), hidden.shape[0], hidden.data_ptr(), s, q_p,
                                          final_norm.data_ptr(), lm_head.data_ptr(), vocab,
                                          logits.data_ptr() if want_logits else None, tokens.data_ptr()))
         return tokens, logits
@@ -331,16 +347,16 @@ class Stage:
         mask = 0
         for k in kernels:
             mask |= 1 << KERNEL_CLASSES[k]
-        _check(load_library().stage_profile_enable(self._handle, mask))
+        self._check(self._lib.stage_profile_enable(self._handle, mask))
 
     def profile_read(self, kernel: str):
         ms, n = ctypes.c_double(), ctypes.c_int64()
-        _check(load_library().stage_profile_read(self._handle, KERNEL_CLASSES[kernel], ctypes.byref(ms), ctypes.byref(n)))
+        self._check(self._lib.stage_profile_read(self._handle, KERNEL_CLASSES[kernel], ctypes.byref(ms), ctypes.byref(n)))
         return ms.value, n.value
 
     def close(self) -> None:
         if getattr(self, "_handle", None):
-            load_library().stage_destroy(self._handle)
+            self._lib.stage_destroy(self._handle)
             self._handle = None
 
     def __del__(self):

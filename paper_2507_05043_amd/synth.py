@@ -84,12 +84,13 @@ def normal_from_index(seed: int, stream: int, idx: torch.Tensor) -> torch.Tensor
 
 def draw_normal_bf16(seed: int, stream: int, numel: int, *, std: float = 1.0, mean: float = 0.0,
                      device: str | torch.device = "cpu", offset: int = 0,
-                     chunk: Optional[int] = None) -> torch.Tensor:
-    """`numel` values mean + std*N(0,1), rounded to bf16, for indices offset..offset+numel-1."""
+                     chunk: Optional[int] = None, dtype: torch.dtype = torch.bfloat16) -> torch.Tensor:
+    """`numel` values mean + std*N(0,1), rounded to bf16 (or to `dtype`: the same fp32 values rounded to
+    the half-precision library's float16), for indices offset..offset+numel-1."""
     device = torch.device(device)
     if chunk is None:
         chunk = (1 << 26) if device.type == "cuda" else (1 << 22)
-    out = torch.empty(numel, dtype=torch.bfloat16, device=device)
+    out = torch.empty(numel, dtype=dtype, device=device)
     std32 = torch.tensor(std, dtype=torch.float32, device=device)
     for start in range(0, numel, chunk):
         stop = min(numel, start + chunk)
@@ -97,17 +98,17 @@ def draw_normal_bf16(seed: int, stream: int, numel: int, *, std: float = 1.0, me
         v = normal_from_index(seed, stream, idx) * std32
         if mean != 0.0:
             v = v + torch.tensor(mean, dtype=torch.float32, device=device)
-        out[start:stop] = v.to(torch.bfloat16)
+        out[start:stop] = v.to(dtype)
     return out
 
 
 def draw_normal_bf16_at(seed: int, stream: int, idx: torch.Tensor, *, std: float = 1.0,
-                        mean: float = 0.0) -> torch.Tensor:
+                        mean: float = 0.0, dtype: torch.dtype = torch.bfloat16) -> torch.Tensor:
     """Same values as `draw_normal_bf16`, at arbitrary int64 indices."""
     v = normal_from_index(seed, stream, idx) * torch.tensor(std, dtype=torch.float32, device=idx.device)
     if mean != 0.0:
         v = v + torch.tensor(mean, dtype=torch.float32, device=idx.device)
-    return v.to(torch.bfloat16)
+    return v.to(dtype)
 
 
 def draw_int_uniform(seed: int, stream: int, n: int, lo: int, hi: int) -> List[int]:
@@ -274,8 +275,8 @@ def weight_shapes(shape: StageShape) -> Dict[str, tuple]:
 
 
 def draw_layer_weights(shape: StageShape, layer: int, *, seed: int, device="cpu",
-                       weight_std: Optional[float] = None) -> Dict[str, torch.Tensor]:
-    """bf16 weights of one layer: matrices ~ N(0, std 0.02) (or std = `weight_std`, or
+                       weight_std: Optional[float] = None, dtype: torch.dtype = torch.bfloat16) -> Dict[str, torch.Tensor]:
+    """bf16 (or `dtype`) weights of one layer: matrices ~ N(0, std 0.02) (or std = `weight_std`, or
     1/sqrt(fan_in) when weight_std == "fan_in"), norm gains ~ 1 + N(0, 0.02)."""
     out = {}
     for k, kind in enumerate(_WEIGHT_KINDS):
@@ -285,7 +286,7 @@ def draw_layer_weights(shape: StageShape, layer: int, *, seed: int, device="cpu"
             n *= s
         stream = STREAM_LAYER_BASE + 10 * layer + k
         if kind.startswith("norm"):
-            t = draw_normal_bf16(seed, stream, n, std=0.02, mean=1.0, device=device)
+            t = draw_normal_bf16(seed, stream, n, std=0.02, mean=1.0, device=device, dtype=dtype)
         else:
             if weight_std is None:
                 std = 0.02
@@ -293,7 +294,7 @@ def draw_layer_weights(shape: StageShape, layer: int, *, seed: int, device="cpu"
                 std = 1.0 / math.sqrt(shp[1])
             else:
                 std = float(weight_std)
-            t = draw_normal_bf16(seed, stream, n, std=std, device=device)
+            t = draw_normal_bf16(seed, stream, n, std=std, device=device, dtype=dtype)
         out[kind] = t.view(*shp)
     return out
 
@@ -303,12 +304,12 @@ _W4_MATRICES = ("wqkv", "wo", "wgate", "wup", "wdown")
 
 
 def draw_w4_layer(shape: StageShape, layer: int, *, seed: int, group: int, device="cpu",
-                  weight_std: float = 0.02) -> Dict[str, torch.Tensor]:
+                  weight_std: float = 0.02, dtype: torch.dtype = torch.bfloat16) -> Dict[str, torch.Tensor]:
     """One layer with 4-bit group-quantised projection matrices, drawn directly in their stored form:
     code words int32 [N, K/8] of uniformly random bits (every 4-bit code is uniform in 0..15), zero points
     bf16 [N, K/group], integers uniform in 6..9, scales bf16 [N, K/group] = weight_std/4.74 * u with u uniform
     in [0.75, 1.25) (code - zero has standard deviation 4.74, so the weights they stand for have about
-    `weight_std`; integer arithmetic and one float32 multiplication, so CPU and GPU draws are bit-identical).
+    `weight_std`; `dtype` replaces bf16 for scales, zero points and gains; integer arithmetic and one float32 multiplication, so CPU and GPU draws are bit-identical).
     Keys: the matrix names hold the code words, "s"/"z" + {qkv,o,gate,up,down} the scales and zero points;
     the norm gains are those of `draw_layer_weights`."""
     device = torch.device(device)
@@ -316,7 +317,7 @@ def draw_w4_layer(shape: StageShape, layer: int, *, seed: int, group: int, devic
     for k, kind in enumerate(_WEIGHT_KINDS):
         if kind.startswith("norm"):
             out[kind] = draw_normal_bf16(seed, STREAM_LAYER_BASE + 10 * layer + k, shape.hidden, std=0.02, mean=1.0,
-                                         device=device)
+                                         device=device, dtype=dtype)
     shapes = weight_shapes(shape)
     for m, kind in enumerate(_W4_MATRICES):
         n, kk = shapes[kind]
@@ -337,30 +338,33 @@ def draw_w4_layer(shape: StageShape, layer: int, *, seed: int, group: int, devic
         zero = 6 + hash_u32(seed, base + 10 + m, gi) % 4
         suffix = kind[1:]
         out[kind] = code.view(n, kk // 8)
-        out["s" + suffix] = scale.to(torch.bfloat16).view(n, kk // group)
-        out["z" + suffix] = zero.to(torch.bfloat16).view(n, kk // group)
+        out["s" + suffix] = scale.to(dtype).view(n, kk // group)
+        out["z" + suffix] = zero.to(dtype).view(n, kk // group)
     return out
 
 
-def draw_qkv_bias(shape: StageShape, layer: int, *, seed: int, device="cpu", std: float = 0.5) -> torch.Tensor:
+def draw_qkv_bias(shape: StageShape, layer: int, *, seed: int, device="cpu", std: float = 0.5,
+                  dtype: torch.dtype = torch.bfloat16) -> torch.Tensor:
     """bf16 bias [qkv_out] of a layer's q/k/v projection ~ N(0, std) (for the stages that have one)."""
-    return draw_normal_bf16(seed, STREAM_LAYER_BASE + 10 * layer + 7, shape.qkv_out, std=std, device=device)
+    return draw_normal_bf16(seed, STREAM_LAYER_BASE + 10 * layer + 7, shape.qkv_out, std=std, device=device, dtype=dtype)
 
 
-def draw_hidden(shape: StageShape, num_tokens: int, *, seed: int, device="cpu") -> torch.Tensor:
-    return draw_normal_bf16(seed, STREAM_HIDDEN, num_tokens * shape.hidden, device=device).view(
+def draw_hidden(shape: StageShape, num_tokens: int, *, seed: int, device="cpu",
+                dtype: torch.dtype = torch.bfloat16) -> torch.Tensor:
+    return draw_normal_bf16(seed, STREAM_HIDDEN, num_tokens * shape.hidden, device=device, dtype=dtype).view(
         num_tokens, shape.hidden)
 
 
-def draw_ends_weights(shape: StageShape, *, seed: int, device="cpu", head_std: float = 0.02) -> Dict[str, torch.Tensor]:
+def draw_ends_weights(shape: StageShape, *, seed: int, device="cpu", head_std: float = 0.02,
+                      dtype: torch.dtype = torch.bfloat16) -> Dict[str, torch.Tensor]:
     """bf16 tensors of the pipeline's two ends: embedding table [vocab, hidden] ~ N(0, 1) (so the first
     stage's input has the scale of `draw_hidden`), final norm gain ~ 1 + N(0, 0.02), output head
     [vocab, hidden] ~ N(0, head_std)."""
     v, h = shape.vocab, shape.hidden
     return {
-        "embed": draw_normal_bf16(seed, STREAM_EMBED, v * h, device=device).view(v, h),
-        "final_norm": draw_normal_bf16(seed, STREAM_FINAL_NORM, h, std=0.02, mean=1.0, device=device),
-        "lm_head": draw_normal_bf16(seed, STREAM_LM_HEAD, v * h, std=head_std, device=device).view(v, h),
+        "embed": draw_normal_bf16(seed, STREAM_EMBED, v * h, device=device, dtype=dtype).view(v, h),
+        "final_norm": draw_normal_bf16(seed, STREAM_FINAL_NORM, h, std=0.02, mean=1.0, device=device, dtype=dtype),
+        "lm_head": draw_normal_bf16(seed, STREAM_LM_HEAD, v * h, std=head_std, device=device, dtype=dtype).view(v, h),
     }
 
 
@@ -380,7 +384,7 @@ def kv_value_index(shape: StageShape, num_kv_blocks: int, layer, kv, block, slot
 
 
 def draw_kv_blocks(shape: StageShape, num_kv_blocks: int, layer: int, kv: int, blocks: torch.Tensor,
-                   *, seed: int) -> torch.Tensor:
+                   *, seed: int, dtype: torch.dtype = torch.bfloat16) -> torch.Tensor:
     """Cached values of the given physical blocks: bf16 [len(blocks), block, nkv, d] ~ N(0,1)."""
     dev = blocks.device
     b, nkv, d = shape.kv_block_size, shape.num_kv_heads, shape.head_dim
@@ -389,7 +393,7 @@ def draw_kv_blocks(shape: StageShape, num_kv_blocks: int, layer: int, kv: int, b
     head = torch.arange(nkv, dtype=torch.int64, device=dev).view(1, 1, nkv, 1)
     dim = torch.arange(d, dtype=torch.int64, device=dev).view(1, 1, 1, d)
     idx = kv_value_index(shape, num_kv_blocks, layer, kv, blk, slot, head, dim)
-    return draw_normal_bf16_at(seed, STREAM_KV, idx)
+    return draw_normal_bf16_at(seed, STREAM_KV, idx, dtype=dtype)
 
 
 def valid_slot_mask(mb: MicroBatch, block: int = 16, *, include_new: bool = False) -> torch.Tensor:

@@ -17,17 +17,20 @@ MAX_ABS_TOL = 5e-2     # stated max-abs tolerance, scaled by max(1, rms(oracle))
 
 
 def run_gpu(st: Stage, shape, mb, seed, taps_layer=None, hidden=None):
-    hidden = hidden if hidden is not None else synth.draw_hidden(shape, mb.num_tokens, seed=seed, device=st.device)
+    hidden = hidden if hidden is not None else synth.draw_hidden(shape, mb.num_tokens, seed=seed, device=st.device,
+                                                                 dtype=st.dtype)
     res = st.forward(hidden, mb.positions, mb.q_lens, mb.ctx_lens, mb.block_tables, want_slots=True,
                      taps_layer=taps_layer)
     torch.cuda.synchronize()
     return res
 
 
-def run_oracle(shape, mb, seed, weight_std=None, dtype=torch.float64, want_taps=False, layers=None):
-    layers = layers if layers is not None else draw_layers(shape, seed, weight_std)
-    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=seed)
-    pool = oracle_pool(shape, mb, seed, dtype=dtype)
+def run_oracle(shape, mb, seed, weight_std=None, dtype=torch.float64, want_taps=False, layers=None,
+               elem=torch.bfloat16):
+    """`elem`: the 16-bit type the inputs are drawn in (the oracle widens them exactly and computes in `dtype`)."""
+    layers = layers if layers is not None else draw_layers(shape, seed, weight_std, elem=elem)
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=seed, dtype=elem)
+    pool = oracle_pool(shape, mb, seed, dtype=dtype, elem=elem)
     taps = [] if want_taps else None
     out, slots = oracle.stage_forward(oracle_shape(shape), layers, hidden, mb.positions, mb.q_lens, mb.ctx_lens,
                                       mb.block_tables, pool, dtype=dtype, taps=taps)
@@ -126,7 +129,7 @@ def snapshot_pool(st: Stage, shape, mb) -> List[List[torch.Tensor]]:
 
 
 def sub_problem(shape: synth.StageShape, mb: synth.MicroBatch, seqs: Sequence[int], seed: int, dtype=torch.float64,
-                draw_device="cpu"):
+                draw_device="cpu", elem=torch.bfloat16):
     """The oracle's view of a subset of sequences: their rows, a compact re-paged pool holding the
     same cached values (drawn by their original physical block numbers), compact block tables."""
     b = shape.kv_block_size
@@ -153,6 +156,7 @@ def sub_problem(shape: synth.StageShape, mb: synth.MicroBatch, seqs: Sequence[in
     for l in range(shape.num_layers):
         for kv in (0, 1):
             # the generator gives the same bits on either device; drawing on the GPU is only faster
-            vals = synth.draw_kv_blocks(shape, mb.num_kv_blocks, l, kv, orig.to(draw_device), seed=seed).cpu().to(dtype)
+            vals = synth.draw_kv_blocks(shape, mb.num_kv_blocks, l, kv, orig.to(draw_device), seed=seed,
+                                        dtype=elem).cpu().to(dtype)
             pool[l, kv] = torch.where(valid, vals, torch.full_like(vals, float("nan")))
     return sub, rows, pool

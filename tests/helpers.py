@@ -16,17 +16,19 @@ def oracle_shape(shape: synth.StageShape) -> oracle.OracleShape:
 
 
 def draw_layers(shape: synth.StageShape, seed: int, weight_std=None, device="cpu",
-                qkv_bias: bool = False) -> List[Dict[str, torch.Tensor]]:
-    layers = [synth.draw_layer_weights(shape, l, seed=seed, device=device, weight_std=weight_std)
+                qkv_bias: bool = False, elem: torch.dtype = torch.bfloat16) -> List[Dict[str, torch.Tensor]]:
+    layers = [synth.draw_layer_weights(shape, l, seed=seed, device=device, weight_std=weight_std, dtype=elem)
               for l in range(shape.num_layers)]
     if qkv_bias:
         for l, w in enumerate(layers):
-            w["bqkv"] = synth.draw_qkv_bias(shape, l, seed=seed, device=device)
+            w["bqkv"] = synth.draw_qkv_bias(shape, l, seed=seed, device=device, dtype=elem)
     return layers
 
 
-def oracle_pool(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, dtype=torch.float64) -> torch.Tensor:
-    """Oracle-layout pool [L, 2, blocks, slot, nkv, d]: cached context drawn, everything else NaN."""
+def oracle_pool(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, dtype=torch.float64,
+                elem: torch.dtype = torch.bfloat16) -> torch.Tensor:
+    """Oracle-layout pool [L, 2, blocks, slot, nkv, d]: cached context drawn (as 16-bit `elem` values, widened to
+    `dtype`), everything else NaN."""
     osh = oracle_shape(shape)
     pool = oracle.new_pool(osh, mb.num_kv_blocks, dtype=dtype)
     valid = synth.valid_slot_mask(mb, shape.kv_block_size)                 # [blocks, slot]
@@ -35,7 +37,7 @@ def oracle_pool(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, dtype=
         return pool
     for l in range(shape.num_layers):
         for kv in (0, 1):
-            vals = synth.draw_kv_blocks(shape, mb.num_kv_blocks, l, kv, used_blocks, seed=seed).to(dtype)
+            vals = synth.draw_kv_blocks(shape, mb.num_kv_blocks, l, kv, used_blocks, seed=seed, dtype=elem).to(dtype)
             m = valid[used_blocks].view(-1, shape.kv_block_size, 1, 1)
             vals = torch.where(m, vals, torch.full_like(vals, float("nan")))
             pool[l, kv, used_blocks] = vals

@@ -16,10 +16,15 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 @pytest.fixture(scope="module")
 def lib():
-    if not os.path.exists(S.LIB_PATH):
+    if not all(os.path.exists(p) for p in S.LIB_PATHS.values()):
         from paper_2507_05043_amd import build
         build.build()
     return S.load_library()
+
+
+@pytest.fixture(scope="module", params=[torch.bfloat16, torch.float16], ids=["bf16", "f16"])
+def each_lib(request, lib):
+    return S.load_library(request.param)
 
 
 def tiny_cfg(**kw):
@@ -29,7 +34,8 @@ def tiny_cfg(**kw):
     return S.make_config(**args)
 
 
-def test_library_exports_every_declared_symbol(lib):
+def test_library_exports_every_declared_symbol(each_lib):
+    lib = each_lib
     header = open(os.path.join(ROOT, "include", "molink_stage.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(stage_[a-z_]+)\s*\(", header))
@@ -38,7 +44,8 @@ def test_library_exports_every_declared_symbol(lib):
         assert hasattr(lib, n), f"{n} is declared in the header but not exported"
 
 
-def test_library_exports_every_handoff_symbol(lib):
+def test_library_exports_every_handoff_symbol(each_lib):
+    lib = each_lib
     header = open(os.path.join(ROOT, "include", "molink_handoff.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(handoff_[a-z_]+)\s*\(", header))
@@ -60,6 +67,19 @@ def test_handoff_plan_equals_the_model_on_random_layouts(lib):
         handoff.plan([3, 0], 8, 8)
     with pytest.raises(handoff.HandoffError):
         handoff.plan([3], 8, 0)
+
+
+def test_each_library_reports_its_element_type_and_the_same_host_answers(lib):
+    f16 = S.load_library(torch.float16)
+    assert lib.stage_elem_type() == 0 and f16.stage_elem_type() == 1
+    cfg = tiny_cfg(vocab_size=1000)
+    for fn in ("stage_kv_layer_bytes", "stage_workspace_bytes"):       # sizes do not depend on the 16-bit format
+        a, b = ctypes.c_size_t(), ctypes.c_size_t()
+        assert getattr(lib, fn)(ctypes.byref(cfg), ctypes.byref(a)) == 0
+        assert getattr(f16, fn)(ctypes.byref(cfg), ctypes.byref(b)) == 0
+        assert a.value == b.value > 0
+    with pytest.raises(ValueError):
+        S.load_library(torch.float32)
 
 
 def test_config_struct_matches_header_size(lib):
@@ -177,7 +197,7 @@ def test_four_bit_weights_add_room_for_one_expanded_projection(lib):
 
 
 def test_kernel_names(lib):
-    assert S.stage_kernel_name(S.KERNEL_CLASSES["gemm_head"]) == "gemm_bf16_kernel"
+    assert S.stage_kernel_name(S.KERNEL_CLASSES["gemm_head"]) == "gemm_tile_kernel"
     assert S.stage_kernel_name(S.KERNEL_CLASSES["head_argmax"]) == "argmax_rows_kernel"
     assert S.stage_kernel_name(S.KERNEL_CLASSES["attn_decode"]) == "attn_decode_kernel"
     assert S.stage_kernel_name(S.KERNEL_CLASSES["dequant"]) == "dequant_w4_kernel"
