@@ -137,6 +137,42 @@ def test_llama2_7b_stage_in_half_precision_sampled_rows_at_full_size():
     st.close()
 
 
+@pytest.mark.timeout(600)
+def test_llama3_70b_stage_in_half_precision_keeps_one_activation_plane():
+    """20 layers at the real shape, 256 decode tokens, contexts up to 8192.  The half-precision library does not
+    add the second activation plane that the bfloat16 one chooses beyond 8 layers; 4 sequences row by row show
+    that one plane stays within the tolerance at this depth."""
+    shape, mb = synth.workload("llama3-70b", seed=0)
+    print(f"[case] f16 {shape.name} T={mb.num_tokens} blocks={mb.num_kv_blocks}", flush=True)
+    from paper_2507_05043_amd.stage import make_config, stage_workspace_bytes
+    ws = {}
+    for planes in (0, 1, 2):
+        cfg = make_config(num_layers=shape.num_layers, hidden=shape.hidden, num_q_heads=shape.num_q_heads,
+                          num_kv_heads=shape.num_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn, rms_eps=shape.rms_eps,
+                          rope_theta=shape.rope_theta, num_kv_blocks=mb.num_kv_blocks, max_tokens=mb.num_tokens,
+                          max_seqs=mb.num_seqs, max_blocks_per_seq=mb.max_blocks_per_seq, activation_planes=planes)
+        ws[planes] = (stage_workspace_bytes(cfg, F16), stage_workspace_bytes(cfg, torch.bfloat16))
+    # left to the library (0), the half-precision one lays its workspace out for one plane, the bfloat16 one for two
+    assert ws[0][0] == ws[1][0] != ws[2][0] and ws[0][1] == ws[2][1] != ws[1][1]
+    st = H.make_stage(shape, mb, 0, dtype=F16)
+    print("  stage ready", flush=True)
+    out, slots = H.run_gpu(st, shape, mb, 0)
+    assert slots == oracle.slot_mapping(mb.q_lens, mb.ctx_lens, mb.block_tables, 16)
+    assert torch.isfinite(out.float()).all()
+    seqs = [0, 85, 170, 255]
+    sub, rows, pool = H.sub_problem(shape, mb, seqs, 0, dtype=torch.float32, draw_device="cuda:0", elem=F16)
+    layers = [{k: v.cpu() for k, v in st.layers[l].items()} for l in range(shape.num_layers)]
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=0, dtype=F16)[rows]
+    print("  oracle inputs ready", flush=True)
+    ref, _ = oracle.stage_forward(oracle_shape(shape), layers, hidden, sub.positions, sub.q_lens, sub.ctx_lens,
+                                  sub.block_tables, pool, dtype=torch.float32)
+    stats = H.check_output(out[rows.cuda()], ref, "f16 llama3-70b sampled rows")
+    print(f"  rel-L2 {stats['rel_l2']:.3e} max-abs {stats['max_abs']:.3e} rms {stats['rms']:.3f}", flush=True)
+    st.close()
+    del st
+    torch.cuda.empty_cache()
+
+
 def test_the_pipeline_ends_in_half_precision():
     shape = synth.TINY
     q_lens = [3, 1, 1, 5, 1, 1, 2]
