@@ -14,8 +14,11 @@ standard pre-norm Llama decoder block: RMSNorm, q/k/v projection, rotary
 embedding (half-split pairing), append to a paged KV cache, causal attention
 with grouped KV heads, output projection + residual, RMSNorm, SwiGLU MLP +
 residual.  No biases, except an optional one on the q/k/v projection (the Qwen2
-family of the paper's model table has it; it is added before the rotation);
-no final norm.
+family of the paper's model table has it; it is added before the rotation),
+and an optional RMSNorm over each query head and each key head (gains "qnorm",
+"knorm" of head_dim elements, the stage's eps) between the bias and the
+rotation, which is how the Qwen3 family of the same table (section 3.1.3)
+defines its block; no final norm.
 
 Numerics: every tensor is widened to `dtype` (float64 by default) on entry and
 nothing is rounded afterwards.  Library primitives used as steps: matmul,
@@ -143,6 +146,9 @@ def decoder_layer(shape: OracleShape, w: Dict[str, torch.Tensor], x: torch.Tenso
     q = qkv[:, : nq * d].reshape(t, nq, d)
     k = qkv[:, nq * d: (nq + nkv) * d].reshape(t, nkv, d)
     v = qkv[:, (nq + nkv) * d:].reshape(t, nkv, d)
+    if w.get("qnorm") is not None:                                    # optional per-head norm (Qwen3 family)
+        q = rmsnorm(q, w["qnorm"].to(dt), shape.rms_eps)              # over the d elements of each head
+        k = rmsnorm(k, w["knorm"].to(dt), shape.rms_eps)
     q = rope_rotate(q, pos, shape.rope_theta)
     k = rope_rotate(k, pos, shape.rope_theta)
     # append the new tokens' keys (rotated) and values at their slots

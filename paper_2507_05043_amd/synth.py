@@ -257,7 +257,7 @@ STREAM_EMBED = 3
 STREAM_FINAL_NORM = 4
 STREAM_LM_HEAD = 5
 STREAM_TOKEN_IDS = 6
-STREAM_LAYER_BASE = 100   # + 10*layer + {0..6 weights, 7 q/k/v bias}
+STREAM_LAYER_BASE = 100   # + 10*layer + {0..6 weights, 7 q/k/v bias, 8 query-head norm gain, 9 key-head norm gain}
 _WEIGHT_KINDS = ("norm1", "wqkv", "wo", "norm2", "wgate", "wup", "wdown")
 
 
@@ -347,6 +347,14 @@ def draw_qkv_bias(shape: StageShape, layer: int, *, seed: int, device="cpu", std
                   dtype: torch.dtype = torch.bfloat16) -> torch.Tensor:
     """bf16 bias [qkv_out] of a layer's q/k/v projection ~ N(0, std) (for the stages that have one)."""
     return draw_normal_bf16(seed, STREAM_LAYER_BASE + 10 * layer + 7, shape.qkv_out, std=std, device=device, dtype=dtype)
+
+
+def draw_qk_norm(shape: StageShape, layer: int, *, seed: int, device="cpu", std: float = 0.25,
+                 dtype: torch.dtype = torch.bfloat16) -> Dict[str, torch.Tensor]:
+    """Gains [head_dim] ~ 1 + N(0, std) of a layer's per-head query and key norms (for the stages that have them)."""
+    return {name: draw_normal_bf16(seed, STREAM_LAYER_BASE + 10 * layer + k, shape.head_dim, std=std, mean=1.0,
+                                   device=device, dtype=dtype)
+            for name, k in (("qnorm", 8), ("knorm", 9))}
 
 
 def draw_hidden(shape: StageShape, num_tokens: int, *, seed: int, device="cpu",

@@ -41,8 +41,13 @@ def layer_one_sequence(shape, w, rows, pos, cache_k, cache_v):
         qkv = matvec(w["wqkv"], a)
         if w.get("bqkv") is not None:
             qkv = [u + b for u, b in zip(qkv, w["bqkv"])]
-        q = [rope_head(qkv[h * d:(h + 1) * d], pos[n], shape.rope_theta) for h in range(nq)]
-        k = [rope_head(qkv[(nq + r) * d:(nq + r + 1) * d], pos[n], shape.rope_theta) for r in range(nkv)]
+        qh = [qkv[h * d:(h + 1) * d] for h in range(nq)]
+        kh = [qkv[(nq + r) * d:(nq + r + 1) * d] for r in range(nkv)]
+        if w.get("qnorm") is not None:            # per-head norm of queries and keys, before the rotation
+            qh = [rmsnorm_row(u, w["qnorm"], shape.rms_eps) for u in qh]
+            kh = [rmsnorm_row(u, w["knorm"], shape.rms_eps) for u in kh]
+        q = [rope_head(u, pos[n], shape.rope_theta) for u in qh]
+        k = [rope_head(u, pos[n], shape.rope_theta) for u in kh]
         v = [qkv[(nq + nkv + r) * d:(nq + nkv + r + 1) * d] for r in range(nkv)]
         cache_k.append(k)
         cache_v.append(v)

@@ -16,12 +16,16 @@ def oracle_shape(shape: synth.StageShape) -> oracle.OracleShape:
 
 
 def draw_layers(shape: synth.StageShape, seed: int, weight_std=None, device="cpu",
-                qkv_bias: bool = False, elem: torch.dtype = torch.bfloat16) -> List[Dict[str, torch.Tensor]]:
+                qkv_bias: bool = False, elem: torch.dtype = torch.bfloat16,
+                qk_norm: bool = False) -> List[Dict[str, torch.Tensor]]:
     layers = [synth.draw_layer_weights(shape, l, seed=seed, device=device, weight_std=weight_std, dtype=elem)
               for l in range(shape.num_layers)]
     if qkv_bias:
         for l, w in enumerate(layers):
             w["bqkv"] = synth.draw_qkv_bias(shape, l, seed=seed, device=device, dtype=elem)
+    if qk_norm:
+        for l, w in enumerate(layers):
+            w.update(synth.draw_qk_norm(shape, l, seed=seed, device=device, dtype=elem))
     return layers
 
 

@@ -35,8 +35,9 @@ def run_oracle(shape, mb, seed=0, weight_std="fan_in", layers=None, hidden=None,
 
 # ---------------------------------------------------------------- brute force, whole block
 
-@pytest.mark.parametrize("nq,nkv,bias", [(4, 2, False), (3, 3, False), (4, 1, False), (4, 2, True)])
-def test_whole_stage_matches_scalar_loops(nq, nkv, bias):
+@pytest.mark.parametrize("nq,nkv,bias,qk_norm", [(4, 2, False, False), (3, 3, False, False), (4, 1, False, False),
+                                                 (4, 2, True, False), (4, 2, False, True), (4, 1, True, True)])
+def test_whole_stage_matches_scalar_loops(nq, nkv, bias, qk_norm):
     shape = small_shape(num_q_heads=nq, num_kv_heads=nkv, hidden=12, ffn=20, head_dim=4, kv_block_size=4)
     q_lens, ctx_lens = [5, 1, 3], [0, 6, 2]
     mb = synth.make_microbatch(q_lens, ctx_lens, seed=3, block=4)
@@ -44,6 +45,9 @@ def test_whole_stage_matches_scalar_loops(nq, nkv, bias):
     if bias:
         for l, w in enumerate(layers):
             w["bqkv"] = synth.draw_qkv_bias(shape, l, seed=3)
+    if qk_norm:
+        for l, w in enumerate(layers):
+            w.update(synth.draw_qk_norm(shape, l, seed=3))
     hidden = synth.draw_hidden(shape, mb.num_tokens, seed=3)
     pool = oracle_pool(shape, mb, 3)
     pool0 = pool.clone()
@@ -97,6 +101,48 @@ def test_projection_bias_is_added_before_the_rotation():
     taps2 = []
     run_oracle(shape, mb, layers=[dict(layers[0], bqkv=torch.zeros_like(bias))], hidden=hidden, taps=taps2)
     assert torch.equal(taps2[0]["x"], taps0[0]["x"])
+
+
+def test_head_norm_of_queries_and_keys():
+    """The per-head norm sits between the bias and the rotation, acts on q and k heads only, makes the
+    block blind to the scale of the q and k projection rows, and with unit gains leaves heads of rms 1."""
+    shape = small_shape(num_layers=1, rms_eps=1e-12)
+    mb = synth.make_microbatch([4, 1], [0, 5], seed=4, block=shape.kv_block_size)
+    layers = draw_layers(shape, 4, "fan_in")
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=4)
+    nq, nkv, d = shape.num_q_heads, shape.num_kv_heads, shape.head_dim
+    gains = {k: v.double() for k, v in synth.draw_qk_norm(shape, 0, seed=4).items()}
+    assert gains["qnorm"].shape == (d,) and not torch.equal(gains["qnorm"], gains["knorm"])
+    plain, normed, unit = [], [], []
+    run_oracle(shape, mb, seed=4, layers=layers, hidden=hidden, taps=plain)
+    run_oracle(shape, mb, seed=4, layers=[dict(layers[0], **gains)], hidden=hidden, taps=normed)
+    ones = {"qnorm": torch.ones(d, dtype=F64), "knorm": torch.ones(d, dtype=F64)}
+    run_oracle(shape, mb, seed=4, layers=[dict(layers[0], **ones)], hidden=hidden, taps=unit)
+    # values untouched; queries and keys = rotation of (pre-rotation head * gain / its rms), retyped here
+    assert torch.equal(normed[0]["v"], plain[0]["v"])
+    pre = plain[0]["a"] @ layers[0]["wqkv"].double().T
+    pos = torch.as_tensor(mb.positions)
+    t = pre.shape[0]
+    for name, lo, n, gain in (("q", 0, nq, "qnorm"), ("k", nq * d, nkv, "knorm")):
+        u = pre[:, lo: lo + n * d].reshape(t, n, d)
+        u = u / u.pow(2).mean(dim=-1, keepdim=True).sqrt() * gains[gain]
+        want = oracle.rope_rotate(u, pos, shape.rope_theta)
+        assert torch.allclose(normed[0][name], want, rtol=1e-9, atol=1e-10), name
+        # unit gains: every head has rms 1 (the rotation keeps lengths)
+        rms = unit[0][name].pow(2).mean(dim=-1).sqrt()
+        assert torch.allclose(rms, torch.ones_like(rms), rtol=1e-9)
+    assert not torch.allclose(normed[0]["x"], plain[0]["x"], rtol=1e-3)
+    # scaling the q rows by 7 and the k rows by 0.3 changes nothing once heads are normalised ...
+    scaled = layers[0]["wqkv"].double().clone()
+    scaled[: nq * d] *= 7.0
+    scaled[nq * d: (nq + nkv) * d] *= 0.3
+    again = []
+    run_oracle(shape, mb, seed=4, layers=[dict(layers[0], wqkv=scaled, **gains)], hidden=hidden, taps=again)
+    assert torch.allclose(again[0]["x"], normed[0]["x"], rtol=1e-9, atol=1e-10)
+    # ... and does change the plain block
+    again_plain = []
+    run_oracle(shape, mb, seed=4, layers=[dict(layers[0], wqkv=scaled)], hidden=hidden, taps=again_plain)
+    assert not torch.allclose(again_plain[0]["x"], plain[0]["x"], rtol=1e-3)
 
 
 # ---------------------------------------------------------------- attention
