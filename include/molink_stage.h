@@ -113,6 +113,14 @@ typedef struct {
    */
   const void *sqkv, *so, *sgate, *sup, *sdown;
   const void *zqkv, *zo, *zgate, *zup, *zdown;
+  /*
+   * Both NULL, or both set: gains [d] of a per-head RMSNorm (same rms_eps) applied to every query head
+   * (qnorm) and every key head (knorm) of the projection output, after the bias and before the rotation:
+   *   u <- u * gain / sqrt(mean(u^2) + rms_eps)   over the d elements of one head.
+   * The Qwen3 family of the paper's model table (section 3.1.3) normalises its queries and keys this way;
+   * values are not normalised.
+   */
+  const void *qnorm, *knorm;
 } stage_layer_weights;
 
 typedef struct stage_handle stage_handle;

@@ -114,6 +114,22 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs p) {
     float lo[8], hi[8];
     load8f(src + head * d + c * 8, lo);
     load8f(src + head * d + half + c * 8, hi);
+    if (p.q_gain) {
+      // per-head RMSNorm: the head's d values sit in cpr consecutive lanes (cpr = 4 or 8, heads start at
+      // multiples of cpr), all of them in this branch
+      float ss = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss += lo[e] * lo[e] + hi[e] * hi[e];
+      for (int off = 1; off < cpr; off <<= 1) ss += __shfl_xor(ss, off, 64);
+      const float inv = 1.0f / sqrtf(ss / (float)d + p.head_eps);
+      const e16* gain = head < p.nq ? p.q_gain : p.k_gain;
+      const e16x8 gl = load8(gain + c * 8), gh = load8(gain + half + c * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        lo[e] = lo[e] * inv * e16_to_f32(gl[e]);
+        hi[e] = hi[e] * inv * e16_to_f32(gh[e]);
+      }
+    }
     e16x8 olo, ohi, llo, lhi;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {

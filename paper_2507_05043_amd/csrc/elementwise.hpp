@@ -24,6 +24,9 @@ struct RopeAppendArgs {
   int planes;
   size_t plane_stride;     // floats between planes
   const e16* bias;      // optional [(nq + 2 nkv) d] projection bias, added before the rotation
+  const e16* q_gain;    // optional [d] (with k_gain): per-head RMSNorm of every query head / key head after the
+  const e16* k_gain;    // bias and before the rotation, u * gain / sqrt(mean(u^2) + head_eps)
+  float head_eps;
   e16* qkv;             // [T][(nq + 2 nkv) d] e16: rotated q heads, rotated k heads, v heads
   e16* q_lo;            // optional [T][nq d]: e16(q - e16(q)), second plane of the rotated queries
   const float2* cos_sin;   // [T][d/2]

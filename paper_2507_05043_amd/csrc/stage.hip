@@ -523,7 +523,8 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       }
       Timer t(st, stream, STAGE_K_ROPE_APPEND);
       RopeAppendArgs r{plan.partials ? splitk : qkv_f32, plan.partials ? plan.splits : 1, (size_t)T * d.qkv_out,
-                       (const e16*)w.bqkv, qkv, q_lo, cos_sin, d_slots, k_pool, v_pool, T, d.nq, d.nkv, d.d};
+                       (const e16*)w.bqkv, (const e16*)w.qnorm, (const e16*)w.knorm, c.rms_eps,
+                       qkv, q_lo, cos_sin, d_slots, k_pool, v_pool, T, d.nq, d.nkv, d.d};
       HIP_TRY(launch_rope_append(r, stream));
     }
     if (tap && taps->tap_qkv)
@@ -652,6 +653,10 @@ int stage_init(const stage_config* cfg, const stage_layer_weights* layers, void*
     for (const void* p : ptrs)
       if ((uintptr_t)p % 16) return fail(STAGE_ERR_CONFIG, "layer %d has a weight pointer that is not 16-byte aligned", l);
     if ((uintptr_t)w.bqkv % 16) return fail(STAGE_ERR_CONFIG, "layer %d: bqkv is not 16-byte aligned", l);
+    if ((w.qnorm == nullptr) != (w.knorm == nullptr))
+      return fail(STAGE_ERR_NULL, "layer %d: qnorm and knorm must both be set or both be NULL", l);
+    if ((uintptr_t)w.qnorm % 16 || (uintptr_t)w.knorm % 16)
+      return fail(STAGE_ERR_CONFIG, "layer %d: qnorm or knorm is not 16-byte aligned", l);
     if (cfg->weight_bits == 4) {
       const void* q[10] = {w.sqkv, w.so, w.sgate, w.sup, w.sdown, w.zqkv, w.zo, w.zgate, w.zup, w.zdown};
       for (const void* p : q) {

@@ -52,7 +52,7 @@ W4_ZEROS = ("zqkv", "zo", "zgate", "zup", "zdown")
 
 class StageLayerWeights(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in ("norm1", "wqkv", "wo", "norm2", "wgate", "wup", "wdown", "bqkv")
-                + W4_SCALES + W4_ZEROS]
+                + W4_SCALES + W4_ZEROS + ("qnorm", "knorm")]
 
 
 class StageTaps(ctypes.Structure):
@@ -189,7 +189,7 @@ class Stage:
         for l, w in enumerate(self.layers):
             four_bit = cfg.weight_bits == 4
             for name, _ in StageLayerWeights._fields_:
-                if name == "bqkv" and w.get(name) is None:     # the only optional tensor
+                if name in ("bqkv", "qnorm", "knorm") and w.get(name) is None:     # the optional tensors
                     continue
                 if not four_bit and (name in W4_SCALES or name in W4_ZEROS):
                     continue

@@ -14,20 +14,23 @@ def _shape(name, L, H_, nq, nkv, d, F, theta=1e4):
     return synth.StageShape(name, L, H_, nq, nkv, d, F, rope_theta=theta)
 
 
-def full_parity(shape, mb, seed, weight_std, taps=True, check_kv=True, qkv_bias=False, activation_planes=0):
+def full_parity(shape, mb, seed, weight_std, taps=True, check_kv=True, qkv_bias=False, activation_planes=0,
+                qk_norm=False, elem=torch.bfloat16):
     print(f"[case] {shape.name} T={mb.num_tokens} S={mb.num_seqs} q={mb.q_lens[:6]} ctx={mb.ctx_lens[:6]} "
-          f"std={weight_std} seed={seed} bias={qkv_bias} planes={activation_planes}", flush=True)
-    st = H.make_stage(shape, mb, seed, weight_std, qkv_bias=qkv_bias, activation_planes=activation_planes)
+          f"std={weight_std} seed={seed} bias={qkv_bias} planes={activation_planes} qk_norm={qk_norm} {elem}", flush=True)
+    st = H.make_stage(shape, mb, seed, weight_std, qkv_bias=qkv_bias, activation_planes=activation_planes,
+                      qk_norm=qk_norm, dtype=elem)
     before = H.snapshot_pool(st, shape, mb) if check_kv else None
-    ref, ref_slots, ref_pool, otaps = H.run_oracle(shape, mb, seed, weight_std, want_taps=True,
-                                                   layers=draw_layers(shape, seed, weight_std, qkv_bias=qkv_bias))
+    ref, ref_slots, ref_pool, otaps = H.run_oracle(
+        shape, mb, seed, weight_std, want_taps=True, elem=elem,
+        layers=draw_layers(shape, seed, weight_std, qkv_bias=qkv_bias, qk_norm=qk_norm, elem=elem))
     out, slots = H.run_gpu(st, shape, mb, seed)
     assert slots == ref_slots                                   # bit-exact slot indexing
     stats = H.check_output(out, ref)
     if check_kv:
         H.check_pool(st, shape, mb, ref_pool, before, slots)
     if taps:
-        hidden = synth.draw_hidden(shape, mb.num_tokens, seed=seed)
+        hidden = synth.draw_hidden(shape, mb.num_tokens, seed=seed, dtype=elem)
         x_in_gpu = hidden
         for l in range(shape.num_layers):
             H.fill_pool(st, shape, mb, seed)
@@ -66,6 +69,39 @@ def test_projection_bias(planes):
     gqa = _shape("gqa-d128-bias", 2, 512, 8, 2, 128, 1024)
     mb2 = synth.make_microbatch([70, 1, 1, 1, 9], [0, 33, 200, 15, 40], seed=7)
     full_parity(gqa, mb2, 7, "fan_in", qkv_bias=True, activation_planes=planes)
+
+
+@pytest.mark.parametrize("elem", [torch.bfloat16, torch.float16], ids=["bf16", "f16"])
+@pytest.mark.parametrize("d,planes,bias", [(64, 1, False), (128, 1, True), (128, 2, False)])
+def test_head_norm_of_queries_and_keys(d, planes, bias, elem):
+    """The Qwen3 family's block: every query head and key head normalised (gain of d elements) between the
+    projection and the rotation.  Head sizes 64 and 128 (four and eight lanes share a head's sum), with the
+    bias, with the second plane of the rotated queries; prefill chunks, one after a cached prefix, and decode."""
+    shape = _shape(f"qk-norm-d{d}", 2, 512, 8, 2, d, 1408)
+    mb = synth.make_microbatch([70, 33, 1, 1, 1, 1, 1], [0, 21, 9, 40, 77, 100, 130], seed=9, max_blocks_per_seq=12)
+    stats = full_parity(shape, mb, 9, "fan_in", qkv_bias=bias, activation_planes=planes, qk_norm=True, elem=elem)
+    # the same stage without the norm gives another output: the gains were used
+    st = H.make_stage(shape, mb, 9, "fan_in", qkv_bias=bias, activation_planes=planes, dtype=elem)
+    plain, _ = H.run_gpu(st, shape, mb, 9)
+    st.close()
+    st = H.make_stage(shape, mb, 9, "fan_in", qkv_bias=bias, activation_planes=planes, qk_norm=True, dtype=elem)
+    normed, _ = H.run_gpu(st, shape, mb, 9)
+    st.close()
+    assert rel_l2(normed.cpu(), plain.cpu()) > 10 * max(stats["rel_l2"], 1e-3)
+
+
+def test_one_head_norm_gain_without_the_other_is_rejected():
+    shape, mb = synth.workload("tiny", seed=0)
+    from paper_2507_05043_amd.stage import Stage, make_config
+    layers = draw_layers(shape, 0, device="cuda:0", qk_norm=True)
+    del layers[1]["knorm"]
+    cfg = make_config(num_layers=shape.num_layers, hidden=shape.hidden, num_q_heads=shape.num_q_heads,
+                      num_kv_heads=shape.num_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn, rms_eps=shape.rms_eps,
+                      rope_theta=shape.rope_theta, num_kv_blocks=mb.num_kv_blocks, max_tokens=mb.num_tokens,
+                      max_seqs=mb.num_seqs, max_blocks_per_seq=mb.max_blocks_per_seq)
+    with pytest.raises(StageError) as ei:
+        Stage(cfg, layers)
+    assert ei.value.code == -1
 
 
 @pytest.mark.parametrize("case", [
