@@ -238,8 +238,28 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const Decod
   }
   float l = 0.f;
   f32x4 o = {0.f, 0.f, 0.f, 0.f};
-  for (int i = 0; i < t.num_items; ++i) {
-    const size_t slot = ((size_t)(t.first_item + i) * a.nkv + r) * g + col;
+  // four ranges per trip: their loads are issued together, the sums stay in range order
+  const size_t slot_step = (size_t)a.nkv * g;
+  const size_t slot0 = ((size_t)t.first_item * a.nkv + r) * g + col;
+  int i = 0;
+  for (; i + 4 <= t.num_items; i += 4) {
+    float2 ml[4];
+    f32x4 po[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const size_t slot = slot0 + (size_t)(i + u) * slot_step;
+      ml[u] = part_ml[slot];
+      po[u] = *reinterpret_cast<const f32x4*>(part_o + slot * D + d4 * 4);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float w = fast_exp2(ml[u].x - m_max);
+      l += w * ml[u].y;
+      o += po[u] * w;
+    }
+  }
+  for (; i < t.num_items; ++i) {
+    const size_t slot = slot0 + (size_t)i * slot_step;
     const float2 ml = part_ml[slot];
     const float w = fast_exp2(ml.x - m_max);
     l += w * ml.y;
