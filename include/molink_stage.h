@@ -72,12 +72,20 @@ typedef struct {
   int32_t max_tokens;          /* capacity: new tokens per micro-batch (T) */
   int32_t max_seqs;            /* capacity: sequences per micro-batch (S) */
   int32_t max_blocks_per_seq;  /* row length of block_tables */
-  int32_t activation_planes;   /* 0 = automatic, 1 or 2.  With 2, every projection input (and the rotated
-                                  queries) is carried as two bf16 planes, value = hi + lo, both multiplied into
-                                  the same fp32 accumulators: twice the MFMA work of the projections for
-                                  activations that are effectively 16-bit.  Automatic = 2 for stages deeper than
-                                  8 layers, whose accumulated bf16 rounding error would otherwise come close
-                                  to or exceed 1e-2 relative on the output, else 1. */
+  int32_t activation_planes;   /* How the inputs of the projections are carried between kernels:
+                                  1  one plane of the element type;
+                                  2  two planes (also of the rotated queries), value = hi + lo, both multiplied
+                                     into the same fp32 accumulators: activations that are effectively 16-bit, at
+                                     twice the MFMA work of the projections;
+                                  3  (bfloat16 library only) one plane of IEEE half - eleven significant bits
+                                     instead of eight - with the bfloat16 weights converted to half, exactly, on
+                                     their way into the matrix instruction; the rotated queries keep a second
+                                     bfloat16 plane for the attention kernels;
+                                  0  automatic: 1, except that a bfloat16 stage deeper than 8 layers, whose
+                                     accumulated bfloat16 rounding error would otherwise come close to or exceed
+                                     1e-2 relative on the output, takes 3 for micro-batches of decode tokens only
+                                     and 2 for micro-batches with prefill chunks (rows that attend to few keys
+                                     amplify input rounding; see the error figures in the design notes). */
   int32_t vocab_size;          /* 0, or the vocabulary size (multiple of 8, >= 64) of the output head this
                                   stage may run with stage_head (sizes the workspace for it) */
   int32_t weight_bits;         /* 0 or 16: the five projection matrices of a layer are bf16.  4: they are

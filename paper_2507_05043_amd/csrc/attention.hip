@@ -271,7 +271,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const Decod
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const float val = o[e] * inv;
-    ob[e] = f32_to_e16(val);
+    ob[e] = f32_to_act(val, a.out_half);
     ol[e] = f32_to_e16(val - e16_to_f32(ob[e]));
   }
   const size_t at = (size_t)t.row * a.nq * D + head * D + d4 * 4;
@@ -509,7 +509,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const float val = acc[t][q4 * 4 + e] * inv;
-          ob[e] = f32_to_e16(val);
+          ob[e] = f32_to_act(val, a.out_half);
           ol[e] = f32_to_e16(val - e16_to_f32(ob[e]));
         }
         *reinterpret_cast<e16x4*>(a.out + at + t * 32 + q4 * 8) = ob;

@@ -45,6 +45,7 @@ struct AttnArgs {
   e16* out_lo;           // optional [T][nq d]: e16(result - e16(result)) for the two-plane output projection
   int nq, nkv, head_dim;
   float scale_log2e;        // log2(e) / sqrt(d)
+  bool out_half;            // bfloat16 library only: `out` receives IEEE half bits (for a projection that takes half activations)
 };
 
 hipError_t launch_attn_prefill(const AttnArgs& a, const PrefillTile* tiles, int num_tiles, hipStream_t stream);

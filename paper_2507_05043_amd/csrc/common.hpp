@@ -65,6 +65,48 @@ __device__ __forceinline__ uint32_t pack_e16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, p);
 }
 
+// ---- half-precision activations inside the bfloat16 library ----
+// Deep stages keep the inputs of their projections (norm outputs, attention output, silu(gate)*up) as IEEE
+// half - eleven significant bits instead of eight - in the same 16-bit buffers, and the GEMMs convert the
+// bfloat16 weight fragments to half on their way into the matrix instruction (exact: a bfloat16 number has
+// eight significant bits; only magnitudes below 2^-17 lose bits, toward zero, by less than 2^-24).  In the
+// half-precision library the element type is half already and none of this is used.
+typedef _Float16 h16;
+typedef __attribute__((ext_vector_type(8))) h16 h16x8;
+typedef __attribute__((ext_vector_type(4))) h16 h16x4;
+typedef __attribute__((ext_vector_type(2))) h16 h16x2;
+
+// a value as the 16 bits of an activation: half (clamped to its finite range) when as_half, else e16
+__device__ __forceinline__ e16 f32_to_act(float v, bool as_half) {
+#ifdef MOLINK_F16
+  (void)as_half;
+  return static_cast<e16>(v);
+#else
+  if (as_half) return __builtin_bit_cast(e16, static_cast<h16>(fminf(fmaxf(v, -65504.f), 65504.f)));
+  return static_cast<e16>(v);
+#endif
+}
+
+// eight bfloat16 numbers as eight halves (round toward zero: exact wherever half has the range)
+__device__ __forceinline__ h16x8 bf16x8_to_half(e16x8 v) {
+#ifdef MOLINK_F16
+  return v;
+#else
+  const u32x4 w = __builtin_bit_cast(u32x4, v);
+  u32x4 o;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    o[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(__uint_as_float(w[i] << 16), __uint_as_float(w[i] & 0xffff0000u)));
+  return __builtin_bit_cast(h16x8, o);
+#endif
+}
+__device__ __forceinline__ f32x4 mfma_16x16x32_half(h16x8 a, h16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x16 mfma_32x32x16_half(h16x8 a, h16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
+
 // 16-byte global load / store of 8 e16
 __device__ __forceinline__ e16x8 load8(const e16* p) { return *reinterpret_cast<const e16x8*>(p); }
 // The same load for data that is read exactly once (cached KV, streamed weights): marked nontemporal,

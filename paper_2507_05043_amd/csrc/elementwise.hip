@@ -12,7 +12,7 @@ namespace {
 template <bool FROM_BF16>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const e16* __restrict__ in_e16, float* __restrict__ x,
                                                       const e16* __restrict__ gain, e16* __restrict__ out,
-                                                      e16* __restrict__ out_lo, int hidden, float eps) {
+                                                      e16* __restrict__ out_lo, int hidden, float eps, bool out_half) {
   __shared__ float partial[4];
   const int row = blockIdx.x, tid = threadIdx.x;
   const int chunks = hidden / 8;
@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const e16* __restrict__ in
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const float val = v[e] * rs * e16_to_f32(g[e]);
-      o[e] = f32_to_e16(val);
+      o[e] = f32_to_act(val, out_half);
       lo[e] = f32_to_e16(val - e16_to_f32(o[e]));     // what the rounding dropped, for the two-plane GEMMs
     }
     store8(out + (size_t)row * hidden + c * 8, o);
@@ -262,12 +262,13 @@ hipError_t launch_argmax_rows(const float* src, int planes, size_t plane_stride,
 }
 
 hipError_t launch_rmsnorm(const e16* in_e16, float* x, const e16* gain, e16* out, e16* out_lo, int rows,
-                          int hidden, float eps, bool from_e16, hipStream_t stream) {
+                          int hidden, float eps, bool from_e16, bool out_half, hipStream_t stream) {
   if (from_e16)
-    hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(rows), dim3(256), 0, stream, in_e16, x, gain, out, out_lo, hidden, eps);
+    hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(rows), dim3(256), 0, stream, in_e16, x, gain, out, out_lo, hidden, eps,
+                       out_half);
   else
     hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(rows), dim3(256), 0, stream, in_e16, x, gain, out, out_lo, hidden,
-                       eps);
+                       eps, out_half);
   return hipGetLastError();
 }
 

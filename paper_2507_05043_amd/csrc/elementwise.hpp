@@ -11,8 +11,9 @@ namespace molink {
 // from_e16: the row source is in_e16 (the stage input) and the fp32 residual stream x is also
 // initialised from it; otherwise the source is x.
 // out_lo (optional): receives e16(value - e16(value)), the second activation plane of the two-plane GEMMs.
+// out_half (bfloat16 library only): the output is written as IEEE half bits, for GEMMs that take half activations.
 hipError_t launch_rmsnorm(const e16* in_e16, float* x, const e16* gain, e16* out, e16* out_lo, int rows,
-                          int hidden, float eps, bool from_e16, hipStream_t stream);
+                          int hidden, float eps, bool from_e16, bool out_half, hipStream_t stream);
 
 // cos_sin[t][i] = (cos, sin)(positions[t] * theta^(-2i/d)), i < d/2, evaluated in fp64.
 hipError_t launch_rope_table(const int32_t* positions, float2* cos_sin, int rows, int head_dim, float theta,

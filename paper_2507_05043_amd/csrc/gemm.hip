@@ -58,7 +58,7 @@ __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)
 // so the 8 lanes of a 128-bit LDS read that hit rows r..r+7 at the same logical chunk touch 8
 // different slots.  LDS reads of MFMA step kk+1 are issued under the MFMAs of step kk, across tile
 // boundaries too.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int EPI, bool SPLIT, bool SPLIT_A>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int EPI, bool SPLIT, bool SPLIT_A, bool A_HALF>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(GemmArgs p, int nv, int tiles_m, int tiles_n, int splits,
                                                         int k_tiles_per_split) {
   constexpr int NWAVES = WAVES_M * WAVES_N;
@@ -71,6 +71,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(GemmAr
   constexpr int STAGE_BYTES = (AROWS + BN) * 128;
   static_assert(EPI != kEpiSwiGLU || TN % 64 == 0, "SwiGLU pairs two 32-wide column tiles per wave");
   static_assert(NSTAGE >= 2 && NSTAGE <= 3 && NSTAGE * STAGE_BYTES <= 160 * 1024, "stages must fit in LDS");
+  static_assert(!(A_HALF && SPLIT_A), "half activations come as one plane");
   using Lds = LdsStages<STAGE_BYTES>;
 
   const int total = tiles_m * tiles_n * splits;
@@ -194,7 +195,11 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(GemmAr
       for (int i = 0; i < MT; ++i)
         af[s][pl][i] = *reinterpret_cast<const e16x8*>(la + (pl * BM + i * 32) * 128 + frag_off[kk]);
 #pragma unroll
-    for (int j = 0; j < NT; ++j) bfr[s][j] = *reinterpret_cast<const e16x8*>(lb + j * 32 * 128 + frag_off[kk]);
+    for (int j = 0; j < NT; ++j) {
+      const e16x8 w = *reinterpret_cast<const e16x8*>(lb + j * 32 * 128 + frag_off[kk]);
+      // half activations: the weight fragment becomes half here, once per read
+      bfr[s][j] = A_HALF ? __builtin_bit_cast(e16x8, bf16x8_to_half(w)) : w;
+    }
   };
   auto mfmas = [&](int s) {
 #pragma unroll
@@ -203,7 +208,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(GemmAr
       for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int j = 0; j < NT; ++j)
-          acc[i][j] = mfma_32x32x16(af[s][pl][i], bfr[s][j], acc[i][j]);
+          acc[i][j] = A_HALF ? mfma_32x32x16_half(__builtin_bit_cast(h16x8, af[s][pl][i]), __builtin_bit_cast(h16x8, bfr[s][j]), acc[i][j])
+                             : mfma_32x32x16(af[s][pl][i], bfr[s][j], acc[i][j]);
   };
 
   // One pipeline step: tile idx is in stage S and the fragments of its first MFMA step are already in
@@ -289,7 +295,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(GemmAr
           const int f = (v >> 6) * 32 + (v & 31);
           if (f < p.n) {
             const float val = silu_f(acc[i][j][r]) * acc[i][j + 1][r];
-            const e16 hi = f32_to_e16(val);
+            const e16 hi = f32_to_act(val, p.out_half);
             p.out_e16[(size_t)m * p.ldo + f] = hi;
             if (p.out_lo) p.out_lo[(size_t)m * p.ldo + f] = f32_to_e16(val - e16_to_f32(hi));
           }
@@ -334,8 +340,8 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(GemmArgs p, int
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const float val = silu_f(g[e]) * u[e];
-      hi[e] = f32_to_e16(val);
-      lo[e] = f32_to_e16(val - e16_to_f32(hi[e]));
+      hi[e] = f32_to_act(val, p.out_half);
+      lo[e] = f32_to_e16(val - e16_to_f32(hi[e]));     // only stored with a second plane, never with half
     }
     *reinterpret_cast<e16x4*>(p.out_e16 + (size_t)m * p.ldo + n) = hi;
     if (p.out_lo) *reinterpret_cast<e16x4*>(p.out_lo + (size_t)m * p.ldo + n) = lo;
@@ -363,7 +369,7 @@ __global__ __launch_bounds__(1024) void reduce_residual_norm_kernel(const float*
                                                                    int m_rows, int n, float* __restrict__ x,
                                                                    const e16* __restrict__ gain, float eps,
                                                                    e16* __restrict__ out, e16* __restrict__ out_lo,
-                                                                   int ldo) {
+                                                                   int ldo, bool out_half) {
   __shared__ float wsum[16];
   const int row = blockIdx.x, tid = threadIdx.x;
   const int stride = blockDim.x * 4, nwaves = blockDim.x >> 6;
@@ -400,7 +406,7 @@ __global__ __launch_bounds__(1024) void reduce_residual_norm_kernel(const float*
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const float val = v[e] * rs * e16_to_f32(g[e]);
-        o[e] = f32_to_e16(val);
+        o[e] = f32_to_act(val, out_half);
         lo[e] = f32_to_e16(val - e16_to_f32(o[e]));
       }
       *reinterpret_cast<e16x4*>(out + (size_t)row * ldo + c) = o;
@@ -430,6 +436,7 @@ constexpr int kSkinnyKS = 1024;     // K elements per slice
 constexpr int kSkinnyRows = 16;     // weight rows per stage
 constexpr int kSkinnyStages = 4;
 
+template <bool A_HALF>
 __global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs p, int nv, int splits, int groups, int swiglu) {
   constexpr int KS = kSkinnyKS, ROWS = kSkinnyRows, NST = kSkinnyStages;
   constexpr int STAGE_BYTES = ROWS * KS * 2;
@@ -541,7 +548,8 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs p, int nv, in
     for (int s = 0; s < STEPS; ++s) {
       const int off = (s >> 4) * 1024 + (s & 15) * 64 + ((s & 1) ? frag_odd : frag_even);
       const e16x8 wf = *reinterpret_cast<const e16x8*>(stage + off);
-      acc[s & 3] = mfma_16x16x32(wf, act[s], acc[s & 3]);
+      acc[s & 3] = A_HALF ? mfma_16x16x32_half(bf16x8_to_half(wf), __builtin_bit_cast(h16x8, act[s]), acc[s & 3])
+                          : mfma_16x16x32(wf, act[s], acc[s & 3]);
     }
     // eight fragment reads run ahead of the MFMA that consumes the oldest of them
     __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
@@ -564,17 +572,17 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs p, int nv, in
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int EPI, bool SPLIT_A>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int EPI, bool SPLIT_A, bool A_HALF = false>
 hipError_t launch_tile(const GemmArgs& a, const GemmPlan& plan, hipStream_t stream) {
   const int tiles_m = (a.m + BM - 1) / BM;
   const int tiles_n = (plan.nv + BN - 1) / BN;
   const int total = tiles_m * tiles_n * plan.splits;
   dim3 grid(xcd_grid(total)), block(WAVES_M * WAVES_N * 64);
   if (plan.splits > 1) {
-    hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, NSTAGE, EPI, true, SPLIT_A>), grid, block, 0, stream, a,
+    hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, NSTAGE, EPI, true, SPLIT_A, A_HALF>), grid, block, 0, stream, a,
                        plan.nv, tiles_m, tiles_n, plan.splits, plan.k_tiles_per_split);
   } else {
-    hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, NSTAGE, EPI, false, SPLIT_A>), grid, block, 0, stream,
+    hipLaunchKernelGGL((gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, NSTAGE, EPI, false, SPLIT_A, A_HALF>), grid, block, 0, stream,
                        a, plan.nv, tiles_m, tiles_n, 1, plan.k_tiles_per_split);
   }
   return hipGetLastError();
@@ -587,6 +595,21 @@ hipError_t launch_epi(const GemmArgs& a, const GemmPlan& plan, hipStream_t strea
     if (plan.tile == kTile128x128) return launch_tile<128, 128, 2, 2, 3, EPI, true>(a, plan, stream);
     if (plan.tile == kTile64x128) return launch_tile<64, 128, 2, 2, 2, EPI, true>(a, plan, stream);
     return hipErrorInvalidValue;
+  }
+  if (a.a_half) {
+#ifdef MOLINK_F16
+    return hipErrorInvalidValue;   // the element type is half already
+#else
+    switch (plan.tile) {
+      // (the 256x256 tile has no registers left for the converted fragments: its plans run on 128x256 tiles,
+      // twice as many workgroups over the same splits)
+      case kTile256x256: return launch_tile<128, 256, 2, 2, 3, EPI, false, true>(a, plan, stream);
+      case kTile256x128: return launch_tile<256, 128, 2, 2, 3, EPI, false, true>(a, plan, stream);
+      case kTile128x128: return launch_tile<128, 128, 2, 2, 2, EPI, false, true>(a, plan, stream);
+      case kTile128x256: return launch_tile<128, 256, 2, 2, 3, EPI, false, true>(a, plan, stream);
+      default: return hipErrorInvalidValue;
+    }
+#endif
   }
   switch (plan.tile) {
     case kTile256x256: return launch_tile<256, 256, 2, 2, 2, EPI, false>(a, plan, stream);
@@ -679,14 +702,26 @@ size_t gemm_partial_floats(int max_m, int n, int k, GemmEpilogue epi, int num_cu
 hipError_t launch_gemm_main(const GemmArgs& a, GemmEpilogue epi, const GemmPlan& plan, hipStream_t stream) {
   if (plan.tile == kTileSkinny) {
     if (a.m > 64 || a.a_lo) return hipErrorInvalidValue;
-    if (a.q0.codes) return launch_gemm_skinny_w4(a, plan.nv, plan.splits, epi == kEpiSwiGLU ? 1 : 0, stream);
+    if (a.q0.codes) {
+      if (a.a_half) return hipErrorInvalidValue;   // the 4-bit streaming kernel takes e16 activations
+      return launch_gemm_skinny_w4(a, plan.nv, plan.splits, epi == kEpiSwiGLU ? 1 : 0, stream);
+    }
     const int groups = (plan.nv + kSkinnyRows - 1) / kSkinnyRows;
     const long units = (long)groups * plan.splits;
     const int cus = 256;
     const int nwg = units < cus ? (int)units : (cus > plan.splits ? cus : plan.splits);
     dim3 grid(nwg);
-    hipLaunchKernelGGL(gemm_skinny_kernel, grid, dim3(512), 0, stream, a, plan.nv, plan.splits, groups,
-                       epi == kEpiSwiGLU ? 1 : 0);
+    if (a.a_half) {
+#ifdef MOLINK_F16
+      return hipErrorInvalidValue;
+#else
+      hipLaunchKernelGGL(gemm_skinny_kernel<true>, grid, dim3(512), 0, stream, a, plan.nv, plan.splits, groups,
+                         epi == kEpiSwiGLU ? 1 : 0);
+#endif
+    } else {
+      hipLaunchKernelGGL(gemm_skinny_kernel<false>, grid, dim3(512), 0, stream, a, plan.nv, plan.splits, groups,
+                         epi == kEpiSwiGLU ? 1 : 0);
+    }
     return hipGetLastError();
   }
   if (a.q0.codes) return hipErrorInvalidValue;   // the tiled kernels take e16 weights only
@@ -721,14 +756,14 @@ hipError_t launch_gemm_reduce(const GemmArgs& a, GemmEpilogue epi, const GemmPla
 
 hipError_t launch_gemm_reduce_residual_norm(const GemmArgs& a, GemmEpilogue epi, const GemmPlan& plan,
                                             const e16* gain, float eps, e16* norm_out, e16* norm_out_lo,
-                                            hipStream_t stream) {
+                                            bool norm_out_half, hipStream_t stream) {
   const int threads = a.n >= 4096 ? 1024 : (a.n >= 2048 ? 512 : 256);
   if (epi == kEpiResidualOut) {
     hipLaunchKernelGGL(reduce_residual_norm_kernel<false>, dim3(a.m), dim3(threads), 0, stream, a.partial, plan.splits, a.m,
-                       a.n, a.resid, (const e16*)nullptr, eps, a.out_e16, (e16*)nullptr, a.ldo);
+                       a.n, a.resid, (const e16*)nullptr, eps, a.out_e16, (e16*)nullptr, a.ldo, false);
   } else {
     hipLaunchKernelGGL(reduce_residual_norm_kernel<true>, dim3(a.m), dim3(threads), 0, stream, a.partial, plan.splits, a.m,
-                       a.n, a.resid, gain, eps, norm_out, norm_out_lo, a.n);
+                       a.n, a.resid, gain, eps, norm_out, norm_out_lo, a.n, norm_out_half);
   }
   return hipGetLastError();
 }

@@ -38,6 +38,9 @@ struct GemmArgs {
   float* partial;       // split-K scratch [splits][M][Nv] fp32
   int m, n, k;          // n = output features (F for SwiGLU)
   int lda, ldo;         // leading dimensions (elements) of a and of out_e16 / out_f32
+  bool a_half;          // bfloat16 library only: `a` holds IEEE half bits (one plane); the weight fragments are
+                        // converted to half on their way into the matrix instruction
+  bool out_half;        // bfloat16 library only: the SwiGLU epilogue writes IEEE half bits (no out_lo then)
 };
 
 // kTileSkinny: at most 64 rows; K cut into slices of 1024, weights streamed in groups of 16 rows, always
@@ -66,6 +69,6 @@ hipError_t launch_gemm_reduce(const GemmArgs& args, GemmEpilogue epi, const Gemm
 // args.out_e16 (kEpiResidualOut).  Replaces launch_gemm_reduce plus the following RMSNorm.
 hipError_t launch_gemm_reduce_residual_norm(const GemmArgs& args, GemmEpilogue epi, const GemmPlan& plan,
                                             const e16* gain, float eps, e16* norm_out, e16* norm_out_lo,
-                                            hipStream_t stream);
+                                            bool norm_out_half, hipStream_t stream);
 
 }  // namespace molink

@@ -73,8 +73,10 @@ int check_config(const stage_config* c) {
   if (c->num_q_heads / c->num_kv_heads > 16)
     return fail(STAGE_ERR_CONFIG, "at most 16 query heads per KV head are supported");
   if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return fail(STAGE_ERR_CONFIG, "rms_eps must be > 0 and rope_theta > 1");
-  if (c->activation_planes < 0 || c->activation_planes > 2)
-    return fail(STAGE_ERR_CONFIG, "activation_planes must be 0 (automatic), 1 or 2");
+  if (c->activation_planes < 0 || c->activation_planes > 3)
+    return fail(STAGE_ERR_CONFIG, "activation_planes must be 0 (automatic), 1, 2 or 3 (half activations)");
+  if (c->activation_planes == 3 && kElemIsF16)
+    return fail(STAGE_ERR_CONFIG, "activation_planes 3 (half activations) is a mode of the bfloat16 library; this one stores half already");
   if (c->vocab_size != 0 && (c->vocab_size < 64 || c->vocab_size % 8))
     return fail(STAGE_ERR_CONFIG, "vocab_size must be 0 or a multiple of 8 that is at least 64");
   if (c->weight_bits != 0 && c->weight_bits != 16 && c->weight_bits != 4)
@@ -107,16 +109,33 @@ Dims dims_of(const stage_config& c) {
 // Number of compute units the work decomposition is sized for.  The library targets MI355X only.
 constexpr int kNumCus = 256;
 
-// Deep stages carry every GEMM input (both norm outputs, the attention output, silu(gate)*up) and the
-// rotated queries as two e16 planes, value = hi + lo, and multiply both into the same accumulators.
 // One bfloat16 rounding per GEMM input costs about 1.7e-3 relative error per layer on the residual
 // stream; the errors of the layers add in quadrature (8.0e-3 measured at eight layers), and beyond
-// eight layers the single-plane path no longer keeps a margin to the 1e-2 relative-L2 budget on the
-// stage output.  The second plane doubles the
-// MFMA work of the projections, so shallow stages do without it.  IEEE half keeps three more mantissa bits
-// (an eighth of the rounding error), so the half-precision library never chooses it by itself.
-bool two_plane_of(const stage_config& c) {
-  return c.activation_planes == 0 ? (!kElemIsF16 && c.num_layers > 8) : c.activation_planes == 2;
+// eight layers bfloat16 activations no longer keep a margin to the 1e-2 relative-L2 budget on the
+// stage output.  Two ways to carry more bits (stage_config.activation_planes):
+//  - two planes (2): every GEMM input - both norm outputs, the attention output, silu(gate)*up - and the
+//    rotated queries as two e16 planes, value = hi + lo, both multiplied into the same accumulators:
+//    sixteen bits at twice the matrix work of the projections.
+//  - half activations (3, bfloat16 library): every GEMM input is kept as IEEE half (eleven significant
+//    bits) in the same buffers and the GEMMs convert the bfloat16 weight fragments to half in registers,
+//    which is exact; the matrix work stays what it is.  The rotated queries keep a second bfloat16 plane
+//    for the attention kernels, whose cache operands are bfloat16.
+// Left to the library (0), a bfloat16 stage deeper than eight layers decides per micro-batch: decode-only
+// micro-batches take half activations (measured on 20 layers: 3.0e-3 on decode rows against 1.9e-3 with two
+// planes and 1.4e-2 with one bfloat16 plane), micro-batches with prefill chunks take two planes, because the
+// rows of a chunk that attend to few keys amplify input rounding about ninefold and half leaves their
+// largest error above the max-abs bar.  The half-precision library keeps three more mantissa bits in e16
+// itself and chooses neither.
+bool deep_auto_of(const stage_config& c) { return !kElemIsF16 && c.activation_planes == 0 && c.num_layers > 8; }
+// workspace: are the second planes of the GEMM inputs / of the rotated queries laid out?
+bool lo_planes_of(const stage_config& c) { return c.activation_planes == 2 || deep_auto_of(c); }
+bool q_lo_plane_of(const stage_config& c) { return lo_planes_of(c) || c.activation_planes == 3; }
+// per micro-batch
+bool half_act_of(const stage_config& c, bool has_prefill) {
+  return !kElemIsF16 && (c.activation_planes == 3 || (deep_auto_of(c) && !has_prefill));
+}
+bool two_plane_of(const stage_config& c, bool has_prefill) {
+  return c.activation_planes == 2 || (deep_auto_of(c) && has_prefill);
 }
 
 int decode_target_items(const Dims& d) { return (kNumCus * kDecodeWavesPerCu + d.nkv - 1) / d.nkv; }
@@ -129,21 +148,26 @@ WorkspaceLayout layout_of(const stage_config& c) {
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
   w.x = take(T * d.H * 4);
   w.a = take(T * d.H * 2);
-  w.a_lo = take(two_plane_of(c) ? T * d.H * 2 : 0);
+  w.a_lo = take(lo_planes_of(c) ? T * d.H * 2 : 0);
   w.qkv_f32 = take(T * d.qkv_out * 4);
   w.qkv = take(T * d.qkv_out * 2);
-  w.q_lo = take(two_plane_of(c) ? T * d.nq * d.d * 2 : 0);
+  w.q_lo = take(q_lo_plane_of(c) ? T * d.nq * d.d * 2 : 0);
   w.attn = take(T * d.nq * d.d * 2);
-  w.attn_lo = take(two_plane_of(c) ? T * d.nq * d.d * 2 : 0);
+  w.attn_lo = take(lo_planes_of(c) ? T * d.nq * d.d * 2 : 0);
   w.mlp = take(T * d.F * 2);
-  w.mlp_lo = take(two_plane_of(c) ? T * d.F * 2 : 0);
+  w.mlp_lo = take(lo_planes_of(c) ? T * d.F * 2 : 0);
   w.cos_sin = take(T * (d.d / 2) * 8);
-  const bool sp = two_plane_of(c);
-  size_t pf = gemm_partial_floats(c.max_tokens, d.qkv_out, d.H, kEpiStoreF32, kNumCus, sp);
-  size_t v;
-  if ((v = gemm_partial_floats(c.max_tokens, d.H, d.nq * d.d, kEpiResidualF32, kNumCus, sp)) > pf) pf = v;
-  if ((v = gemm_partial_floats(c.max_tokens, d.F, d.H, kEpiSwiGLU, kNumCus, sp)) > pf) pf = v;
-  if ((v = gemm_partial_floats(c.max_tokens, d.H, d.F, kEpiResidualF32, kNumCus, sp)) > pf) pf = v;
+  // split-K scratch for every way the projections may be planned: with two activation planes, with one, or
+  // (deep stages left to the library) either, depending on the micro-batch
+  size_t pf = 0, v;
+  for (int sp = 0; sp < 2; ++sp) {
+    if (sp == 1 && !lo_planes_of(c)) continue;
+    if (sp == 0 && c.activation_planes == 2) continue;
+    if ((v = gemm_partial_floats(c.max_tokens, d.qkv_out, d.H, kEpiStoreF32, kNumCus, sp)) > pf) pf = v;
+    if ((v = gemm_partial_floats(c.max_tokens, d.H, d.nq * d.d, kEpiResidualF32, kNumCus, sp)) > pf) pf = v;
+    if ((v = gemm_partial_floats(c.max_tokens, d.F, d.H, kEpiSwiGLU, kNumCus, sp)) > pf) pf = v;
+    if ((v = gemm_partial_floats(c.max_tokens, d.H, d.F, kEpiResidualF32, kNumCus, sp)) > pf) pf = v;
+  }
   if (c.vocab_size > 0 && (v = gemm_partial_floats(c.max_seqs, c.vocab_size, d.H, kEpiStoreF32, kNumCus, false)) > pf) pf = v;
   w.splitk = take(pf * 4 + 16);
   // 4-bit weights: room for the largest projection (gate and up together) expanded to e16
@@ -281,6 +305,19 @@ __global__ __launch_bounds__(256) void f32_to_e16_kernel(const float* __restrict
   if (i < n) dst[i] = static_cast<e16>(src[i]);
 }
 
+// IEEE half bits -> e16, for the taps of a stage that keeps its GEMM inputs as half
+__global__ __launch_bounds__(256) void half_bits_to_e16_kernel(const e16* __restrict__ src, e16* __restrict__ dst, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = f32_to_e16(static_cast<float>(__builtin_bit_cast(h16, src[i])));
+}
+
+// A tap of a GEMM input: a plain copy, or a conversion when the stage holds it as half.
+hipError_t copy_activation_tap(void* dst, const e16* src, size_t n, bool src_half, hipStream_t stream) {
+  if (!src_half) return hipMemcpyAsync(dst, src, n * 2, hipMemcpyDeviceToDevice, stream);
+  hipLaunchKernelGGL(half_bits_to_e16_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, src, (e16*)dst, n);
+  return hipGetLastError();
+}
+
 // Points a projection's GEMM at its weights.  e16 weights are used where they lie.  4-bit weights go to
 // the weight-streaming kernel as they are stored when the micro-batch is decode-sized; otherwise they are
 // expanded to e16 in the workspace first (one projection at a time; `w1` is the second matrix of the
@@ -293,7 +330,7 @@ int bind_weights(stage_handle* st, hipStream_t stream, GemmArgs& g, const void* 
     return STAGE_OK;
   }
   const W4Matrix m0{(const uint32_t*)w0, (const e16*)s0, (const e16*)z0};
-  if (skinny_w4_supports(g.m, g.k, st->cfg.weight_group_size, g.a_lo != nullptr)) {
+  if (!g.a_half && skinny_w4_supports(g.m, g.k, st->cfg.weight_group_size, g.a_lo != nullptr)) {
     // decode-sized micro-batch: the weight-streaming kernel reads the stored form itself
     g.q0 = m0;
     if (w1) g.q1 = W4Matrix{(const uint32_t*)w1, (const e16*)s1, (const e16*)z1};
@@ -329,7 +366,7 @@ int run_gemm(stage_handle* st, hipStream_t stream, int kernel_class, const GemmA
 // an RMSNorm into `norm_out` (gain != nullptr), or nothing.  When the GEMM splits K across workgroups
 // the sum of the partial results, the residual add and the norm run as one kernel.
 int run_residual_gemm(stage_handle* st, hipStream_t stream, int kernel_class, const GemmArgs& args, GemmEpilogue epi,
-                      const e16* gain, e16* norm_out, e16* norm_out_lo) {
+                      const e16* gain, e16* norm_out, e16* norm_out_lo, bool norm_out_half) {
   const GemmPlan plan = plan_gemm(args.m, args.n, args.k, epi, kNumCus, args.a_lo != nullptr);
   {
     Timer t(st, stream, kernel_class);
@@ -338,7 +375,8 @@ int run_residual_gemm(stage_handle* st, hipStream_t stream, int kernel_class, co
   const bool fused = plan.partials && (gain != nullptr || epi == kEpiResidualOut);
   if (fused) {
     Timer t(st, stream, STAGE_K_SPLITK_REDUCE);
-    HIP_TRY(launch_gemm_reduce_residual_norm(args, epi, plan, gain, st->cfg.rms_eps, norm_out, norm_out_lo, stream));
+    HIP_TRY(launch_gemm_reduce_residual_norm(args, epi, plan, gain, st->cfg.rms_eps, norm_out, norm_out_lo, norm_out_half,
+                                             stream));
     return STAGE_OK;
   }
   if (plan.partials) {
@@ -348,7 +386,7 @@ int run_residual_gemm(stage_handle* st, hipStream_t stream, int kernel_class, co
   if (gain) {
     Timer t(st, stream, STAGE_K_RMSNORM);
     HIP_TRY(launch_rmsnorm(nullptr, args.resid, gain, norm_out, norm_out_lo, args.m, args.n, st->cfg.rms_eps, false,
-                           stream));
+                           norm_out_half, stream));
   }
   return STAGE_OK;
 }
@@ -470,10 +508,11 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
 
   float* x = (float*)(ws + st->ws.x);
   e16* a = (e16*)(ws + st->ws.a);
-  const bool two_plane = two_plane_of(c);
+  const bool two_plane = two_plane_of(c, n_tiles > 0);
+  const bool half_act = half_act_of(c, n_tiles > 0);   // GEMM inputs as IEEE half bits (bfloat16 library)
   e16* a_lo = two_plane ? (e16*)(ws + st->ws.a_lo) : nullptr;
   e16* mlp_lo = two_plane ? (e16*)(ws + st->ws.mlp_lo) : nullptr;
-  e16* q_lo = two_plane ? (e16*)(ws + st->ws.q_lo) : nullptr;
+  e16* q_lo = (two_plane || half_act) ? (e16*)(ws + st->ws.q_lo) : nullptr;
   e16* attn_lo = two_plane ? (e16*)(ws + st->ws.attn_lo) : nullptr;
   float* qkv_f32 = (float*)(ws + st->ws.qkv_f32);
   e16* qkv = (e16*)(ws + st->ws.qkv);
@@ -499,7 +538,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
     // the first layer's input norm also initialises the fp32 residual stream from the e16 input
     Timer t(st, stream, STAGE_K_RMSNORM);
     HIP_TRY(launch_rmsnorm((const e16*)hidden_in, x, (const e16*)st->layers[0].norm1, a, a_lo, T, d.H, c.rms_eps,
-                           true, stream));
+                           true, half_act, stream));
   }
   for (int l = 0; l < d.L; ++l) {
     const stage_layer_weights& w = st->layers[l];
@@ -508,11 +547,10 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
     e16* k_pool = (e16*)(st->kv_pool + (size_t)l * (size_t)c.kv_layer_stride_bytes);
     e16* v_pool = k_pool + kv_region;
     // `a` holds RMSNorm(x; norm1 of this layer) here
-    if (tap && taps->tap_norm1)
-      HIP_TRY(hipMemcpyAsync(taps->tap_norm1, a, (size_t)T * d.H * 2, hipMemcpyDeviceToDevice, stream));
+    if (tap && taps->tap_norm1) HIP_TRY(copy_activation_tap(taps->tap_norm1, a, (size_t)T * d.H, half_act, stream));
     {
       GemmArgs g{};
-      g.a = a; g.a_lo = a_lo; g.out_f32 = qkv_f32; g.partial = splitk;
+      g.a = a; g.a_lo = a_lo; g.a_half = half_act; g.out_f32 = qkv_f32; g.partial = splitk;
       g.m = T; g.n = d.qkv_out; g.k = d.H; g.lda = d.H; g.ldo = d.qkv_out;
       if (int rc = bind_weights(st, stream, g, w.wqkv, w.sqkv, w.zqkv, nullptr, nullptr, nullptr)) return rc;
       // the rotation kernel adds the split-K partial sums itself: no separate reduction pass
@@ -529,7 +567,8 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
     }
     if (tap && taps->tap_qkv)
       HIP_TRY(hipMemcpyAsync(taps->tap_qkv, qkv, (size_t)T * d.qkv_out * 2, hipMemcpyDeviceToDevice, stream));
-    AttnArgs aa{qkv, q_lo, k_pool, v_pool, d_bt, attn, attn_lo, d.nq, d.nkv, d.d, 1.4426950408889634f / sqrtf((float)d.d)};
+    AttnArgs aa{qkv, q_lo, k_pool, v_pool, d_bt, attn, attn_lo, d.nq, d.nkv, d.d, 1.4426950408889634f / sqrtf((float)d.d),
+                half_act};
     if (n_tiles) {
       Timer t(st, stream, STAGE_K_ATTN_PREFILL);
       HIP_TRY(launch_attn_prefill(aa, d_tiles, n_tiles, stream));
@@ -542,41 +581,39 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       Timer t(st, stream, STAGE_K_ATTN_MERGE);
       HIP_TRY(launch_attn_merge(aa, d_dtok, n_decode, part_o, part_ml, stream));
     }
-    if (tap && taps->tap_attn)
-      HIP_TRY(hipMemcpyAsync(taps->tap_attn, attn, (size_t)T * d.nq * d.d * 2, hipMemcpyDeviceToDevice, stream));
+    if (tap && taps->tap_attn) HIP_TRY(copy_activation_tap(taps->tap_attn, attn, (size_t)T * d.nq * d.d, half_act, stream));
     {
       GemmArgs g{};
-      g.a = attn; g.a_lo = attn_lo; g.resid = x; g.partial = splitk;
+      g.a = attn; g.a_lo = attn_lo; g.a_half = half_act; g.resid = x; g.partial = splitk;
       g.m = T; g.n = d.H; g.k = d.nq * d.d; g.lda = d.nq * d.d; g.ldo = d.H;
       if (int rc = bind_weights(st, stream, g, w.wo, w.so, w.zo, nullptr, nullptr, nullptr)) return rc;
-      int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_O, g, kEpiResidualF32, (const e16*)w.norm2, a, a_lo);
+      int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_O, g, kEpiResidualF32, (const e16*)w.norm2, a, a_lo, half_act);
       if (rc) return rc;
     }
     if (tap && taps->tap_h)
       HIP_TRY(hipMemcpyAsync(taps->tap_h, x, (size_t)T * d.H * 4, hipMemcpyDeviceToDevice, stream));
     {
       GemmArgs g{};
-      g.a = a; g.a_lo = a_lo; g.out_e16 = mlp; g.out_lo = mlp_lo;
+      g.a = a; g.a_lo = a_lo; g.a_half = half_act; g.out_e16 = mlp; g.out_lo = mlp_lo; g.out_half = half_act;
       g.partial = splitk;
       g.m = T; g.n = d.F; g.k = d.H; g.lda = d.H; g.ldo = d.F;
       if (int rc = bind_weights(st, stream, g, w.wgate, w.sgate, w.zgate, w.wup, w.sup, w.zup)) return rc;
       int rc = run_gemm(st, stream, STAGE_K_GEMM_GATEUP, g, kEpiSwiGLU);
       if (rc) return rc;
     }
-    if (tap && taps->tap_mlp)
-      HIP_TRY(hipMemcpyAsync(taps->tap_mlp, mlp, (size_t)T * d.F * 2, hipMemcpyDeviceToDevice, stream));
+    if (tap && taps->tap_mlp) HIP_TRY(copy_activation_tap(taps->tap_mlp, mlp, (size_t)T * d.F, half_act, stream));
     {
       // With a tap on the last layer the fp32 stream is completed first and rounded by a separate
       // kernel, so the tap sees it; the sum and its rounding are the same as in the fused epilogue.
       const bool fused_out = last && !(tap && taps->tap_x);
       GemmArgs g{};
-      g.a = mlp; g.a_lo = mlp_lo; g.resid = x; g.out_e16 = (e16*)hidden_out;
+      g.a = mlp; g.a_lo = mlp_lo; g.a_half = half_act; g.resid = x; g.out_e16 = (e16*)hidden_out;
       g.partial = splitk;
       g.m = T; g.n = d.H; g.k = d.F; g.lda = d.F; g.ldo = d.H;
       if (int rc = bind_weights(st, stream, g, w.wdown, w.sdown, w.zdown, nullptr, nullptr, nullptr)) return rc;
       const e16* next_gain = last ? nullptr : (const e16*)st->layers[l + 1].norm1;
       int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_DOWN, g, fused_out ? kEpiResidualOut : kEpiResidualF32,
-                                 next_gain, a, a_lo);
+                                 next_gain, a, a_lo, half_act);
       if (rc) return rc;
       if (tap && taps->tap_x)
         HIP_TRY(hipMemcpyAsync(taps->tap_x, x, (size_t)T * d.H * 4, hipMemcpyDeviceToDevice, stream));

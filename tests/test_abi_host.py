@@ -82,6 +82,17 @@ def test_each_library_reports_its_element_type_and_the_same_host_answers(lib):
         S.load_library(torch.float32)
 
 
+def test_half_activations_are_a_mode_of_the_bfloat16_library_only(lib):
+    cfg = tiny_cfg(activation_planes=3)
+    out = ctypes.c_size_t()
+    assert lib.stage_workspace_bytes(ctypes.byref(cfg), ctypes.byref(out)) == 0
+    one = ctypes.c_size_t()
+    cfg1 = tiny_cfg(activation_planes=1)
+    assert lib.stage_workspace_bytes(ctypes.byref(cfg1), ctypes.byref(one)) == 0
+    assert out.value > one.value                       # the second plane of the rotated queries
+    assert S.load_library(torch.float16).stage_workspace_bytes(ctypes.byref(cfg), ctypes.byref(out)) == -2
+
+
 def test_config_struct_matches_header_size(lib):
     # uint32 + 6 int32 + 2 float + 2 int32 (+ 4 pad) + int64 + 7 int32 (+ 4 pad)
     assert ctypes.sizeof(S.StageConfig) == 88
@@ -91,7 +102,7 @@ def test_config_struct_matches_header_size(lib):
 
 @pytest.mark.parametrize("bad", [dict(kv_block_size=32), dict(head_dim=96), dict(hidden=252), dict(num_q_heads=5),
                                  dict(num_q_heads=34, num_kv_heads=2), dict(rms_eps=0.0), dict(num_layers=0),
-                                 dict(activation_planes=3), dict(vocab_size=1001), dict(vocab_size=32),
+                                 dict(activation_planes=4), dict(vocab_size=1001), dict(vocab_size=32),
                                  dict(weight_bits=3), dict(weight_group_size=128), dict(weight_bits=4, weight_group_size=48),
                                  dict(weight_bits=4, weight_group_size=128, ffn=768 + 64),
                                  dict(weight_bits=4, weight_group_size=128)])   # ffn 688 is no multiple of 128
