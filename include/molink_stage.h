@@ -83,9 +83,9 @@ typedef struct {
                                      bfloat16 plane for the attention kernels;
                                   0  automatic: 1, except that a bfloat16 stage deeper than 8 layers, whose
                                      accumulated bfloat16 rounding error would otherwise come close to or exceed
-                                     1e-2 relative on the output, takes 3 for micro-batches of decode tokens only
-                                     and 2 for micro-batches with prefill chunks (rows that attend to few keys
-                                     amplify input rounding; see the error figures in the design notes). */
+                                     1e-2 relative on the output, takes 3, and for micro-batches with prefill
+                                     chunks also gives the input of the q/k/v projection a second half plane
+                                     (rows that attend to few keys amplify the rounding of that input). */
   int32_t vocab_size;          /* 0, or the vocabulary size (multiple of 8, >= 64) of the output head this
                                   stage may run with stage_head (sizes the workspace for it) */
   int32_t weight_bits;         /* 0 or 16: the five projection matrices of a layer are bf16.  4: they are

@@ -87,6 +87,16 @@ __device__ __forceinline__ e16 f32_to_act(float v, bool as_half) {
 #endif
 }
 
+// the value of an activation stored by f32_to_act
+__device__ __forceinline__ float act_to_f32(e16 v, bool as_half) {
+#ifdef MOLINK_F16
+  (void)as_half;
+  return static_cast<float>(v);
+#else
+  return as_half ? static_cast<float>(__builtin_bit_cast(h16, v)) : static_cast<float>(v);
+#endif
+}
+
 // eight bfloat16 numbers as eight halves (round toward zero: exact wherever half has the range)
 __device__ __forceinline__ h16x8 bf16x8_to_half(e16x8 v) {
 #ifdef MOLINK_F16

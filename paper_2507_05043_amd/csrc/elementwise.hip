@@ -57,7 +57,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const e16* __restrict__ in
     for (int e = 0; e < 8; ++e) {
       const float val = v[e] * rs * e16_to_f32(g[e]);
       o[e] = f32_to_act(val, out_half);
-      lo[e] = f32_to_e16(val - e16_to_f32(o[e]));     // what the rounding dropped, for the two-plane GEMMs
+      lo[e] = f32_to_act(val - act_to_f32(o[e], out_half), out_half);     // what the rounding dropped, for two-plane GEMMs
     }
     store8(out + (size_t)row * hidden + c * 8, o);
     if (out_lo) store8(out_lo + (size_t)row * hidden + c * 8, lo);

@@ -71,7 +71,6 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(GemmAr
   constexpr int STAGE_BYTES = (AROWS + BN) * 128;
   static_assert(EPI != kEpiSwiGLU || TN % 64 == 0, "SwiGLU pairs two 32-wide column tiles per wave");
   static_assert(NSTAGE >= 2 && NSTAGE <= 3 && NSTAGE * STAGE_BYTES <= 160 * 1024, "stages must fit in LDS");
-  static_assert(!(A_HALF && SPLIT_A), "half activations come as one plane");
   using Lds = LdsStages<STAGE_BYTES>;
 
   const int total = tiles_m * tiles_n * splits;
@@ -407,7 +406,7 @@ __global__ __launch_bounds__(1024) void reduce_residual_norm_kernel(const float*
       for (int e = 0; e < 4; ++e) {
         const float val = v[e] * rs * e16_to_f32(g[e]);
         o[e] = f32_to_act(val, out_half);
-        lo[e] = f32_to_e16(val - e16_to_f32(o[e]));
+        lo[e] = f32_to_act(val - act_to_f32(o[e], out_half), out_half);
       }
       *reinterpret_cast<e16x4*>(out + (size_t)row * ldo + c) = o;
       if (out_lo) *reinterpret_cast<e16x4*>(out_lo + (size_t)row * ldo + c) = lo;
@@ -592,6 +591,15 @@ template <int EPI>
 hipError_t launch_epi(const GemmArgs& a, const GemmPlan& plan, hipStream_t stream) {
   if (a.a_lo) {
     // two activation planes: only the tiles whose stages still fit in LDS
+    if (a.a_half) {
+#ifdef MOLINK_F16
+      return hipErrorInvalidValue;
+#else
+      if (plan.tile == kTile128x128) return launch_tile<128, 128, 2, 2, 3, EPI, true, true>(a, plan, stream);
+      if (plan.tile == kTile64x128) return launch_tile<64, 128, 2, 2, 2, EPI, true, true>(a, plan, stream);
+      return hipErrorInvalidValue;
+#endif
+    }
     if (plan.tile == kTile128x128) return launch_tile<128, 128, 2, 2, 3, EPI, true>(a, plan, stream);
     if (plan.tile == kTile64x128) return launch_tile<64, 128, 2, 2, 2, EPI, true>(a, plan, stream);
     return hipErrorInvalidValue;

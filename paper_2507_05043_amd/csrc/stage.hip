@@ -120,23 +120,23 @@ constexpr int kNumCus = 256;
 //    bits) in the same buffers and the GEMMs convert the bfloat16 weight fragments to half in registers,
 //    which is exact; the matrix work stays what it is.  The rotated queries keep a second bfloat16 plane
 //    for the attention kernels, whose cache operands are bfloat16.
-// Left to the library (0), a bfloat16 stage deeper than eight layers decides per micro-batch: decode-only
-// micro-batches take half activations (measured on 20 layers: 3.0e-3 on decode rows against 1.9e-3 with two
-// planes and 1.4e-2 with one bfloat16 plane), micro-batches with prefill chunks take two planes, because the
-// rows of a chunk that attend to few keys amplify input rounding about ninefold and half leaves their
-// largest error above the max-abs bar.  The half-precision library keeps three more mantissa bits in e16
-// itself and chooses neither.
+// Left to the library (0), a bfloat16 stage deeper than eight layers takes half activations, and for
+// micro-batches with prefill chunks it also gives the q/k/v projection's input - the first norm's output -
+// a second half plane: the rows of a chunk that attend to few keys amplify input rounding about ninefold,
+// mostly through keys and values that land on the other side of a rounding boundary of the bfloat16 cache
+// (measured on 20 layers, a chunk with a short cached prefix: relative error of its rows 1.2e-2 with one
+// half plane everywhere, its largest error above the max-abs bar; decode rows 3.0e-3).  The half-precision
+// library keeps three more mantissa bits in e16 itself and chooses none of this.
 bool deep_auto_of(const stage_config& c) { return !kElemIsF16 && c.activation_planes == 0 && c.num_layers > 8; }
 // workspace: are the second planes of the GEMM inputs / of the rotated queries laid out?
-bool lo_planes_of(const stage_config& c) { return c.activation_planes == 2 || deep_auto_of(c); }
-bool q_lo_plane_of(const stage_config& c) { return lo_planes_of(c) || c.activation_planes == 3; }
+bool lo_planes_of(const stage_config& c) { return c.activation_planes == 2; }
+bool norm1_lo_plane_of(const stage_config& c) { return lo_planes_of(c) || deep_auto_of(c); }
+bool q_lo_plane_of(const stage_config& c) { return lo_planes_of(c) || deep_auto_of(c) || c.activation_planes == 3; }
 // per micro-batch
-bool half_act_of(const stage_config& c, bool has_prefill) {
-  return !kElemIsF16 && (c.activation_planes == 3 || (deep_auto_of(c) && !has_prefill));
-}
-bool two_plane_of(const stage_config& c, bool has_prefill) {
-  return c.activation_planes == 2 || (deep_auto_of(c) && has_prefill);
-}
+bool half_act_of(const stage_config& c) { return !kElemIsF16 && (c.activation_planes == 3 || deep_auto_of(c)); }
+bool two_plane_of(const stage_config& c) { return c.activation_planes == 2; }
+// half activations: does the q/k/v projection's input get a second (half) plane?
+bool qkv_lo_of(const stage_config& c, bool has_prefill) { return deep_auto_of(c) && has_prefill; }
 
 int decode_target_items(const Dims& d) { return (kNumCus * kDecodeWavesPerCu + d.nkv - 1) / d.nkv; }
 
@@ -148,7 +148,7 @@ WorkspaceLayout layout_of(const stage_config& c) {
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
   w.x = take(T * d.H * 4);
   w.a = take(T * d.H * 2);
-  w.a_lo = take(lo_planes_of(c) ? T * d.H * 2 : 0);
+  w.a_lo = take(norm1_lo_plane_of(c) ? T * d.H * 2 : 0);
   w.qkv_f32 = take(T * d.qkv_out * 4);
   w.qkv = take(T * d.qkv_out * 2);
   w.q_lo = take(q_lo_plane_of(c) ? T * d.nq * d.d * 2 : 0);
@@ -161,9 +161,10 @@ WorkspaceLayout layout_of(const stage_config& c) {
   // (deep stages left to the library) either, depending on the micro-batch
   size_t pf = 0, v;
   for (int sp = 0; sp < 2; ++sp) {
-    if (sp == 1 && !lo_planes_of(c)) continue;
+    if (sp == 1 && !norm1_lo_plane_of(c)) continue;
     if (sp == 0 && c.activation_planes == 2) continue;
     if ((v = gemm_partial_floats(c.max_tokens, d.qkv_out, d.H, kEpiStoreF32, kNumCus, sp)) > pf) pf = v;
+    if (sp == 1 && !lo_planes_of(c)) continue;      // only the q/k/v projection ever gets the second plane then
     if ((v = gemm_partial_floats(c.max_tokens, d.H, d.nq * d.d, kEpiResidualF32, kNumCus, sp)) > pf) pf = v;
     if ((v = gemm_partial_floats(c.max_tokens, d.F, d.H, kEpiSwiGLU, kNumCus, sp)) > pf) pf = v;
     if ((v = gemm_partial_floats(c.max_tokens, d.H, d.F, kEpiResidualF32, kNumCus, sp)) > pf) pf = v;
@@ -508,9 +509,11 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
 
   float* x = (float*)(ws + st->ws.x);
   e16* a = (e16*)(ws + st->ws.a);
-  const bool two_plane = two_plane_of(c, n_tiles > 0);
-  const bool half_act = half_act_of(c, n_tiles > 0);   // GEMM inputs as IEEE half bits (bfloat16 library)
+  const bool two_plane = two_plane_of(c);
+  const bool half_act = half_act_of(c);                // GEMM inputs as IEEE half bits (bfloat16 library)
+  const bool qkv_lo = half_act && qkv_lo_of(c, n_tiles > 0);
   e16* a_lo = two_plane ? (e16*)(ws + st->ws.a_lo) : nullptr;
+  e16* norm1_lo = (two_plane || qkv_lo) ? (e16*)(ws + st->ws.a_lo) : nullptr;   // second plane of the first norm's output
   e16* mlp_lo = two_plane ? (e16*)(ws + st->ws.mlp_lo) : nullptr;
   e16* q_lo = (two_plane || half_act) ? (e16*)(ws + st->ws.q_lo) : nullptr;
   e16* attn_lo = two_plane ? (e16*)(ws + st->ws.attn_lo) : nullptr;
@@ -537,7 +540,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
   {
     // the first layer's input norm also initialises the fp32 residual stream from the e16 input
     Timer t(st, stream, STAGE_K_RMSNORM);
-    HIP_TRY(launch_rmsnorm((const e16*)hidden_in, x, (const e16*)st->layers[0].norm1, a, a_lo, T, d.H, c.rms_eps,
+    HIP_TRY(launch_rmsnorm((const e16*)hidden_in, x, (const e16*)st->layers[0].norm1, a, norm1_lo, T, d.H, c.rms_eps,
                            true, half_act, stream));
   }
   for (int l = 0; l < d.L; ++l) {
@@ -550,7 +553,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
     if (tap && taps->tap_norm1) HIP_TRY(copy_activation_tap(taps->tap_norm1, a, (size_t)T * d.H, half_act, stream));
     {
       GemmArgs g{};
-      g.a = a; g.a_lo = a_lo; g.a_half = half_act; g.out_f32 = qkv_f32; g.partial = splitk;
+      g.a = a; g.a_lo = norm1_lo; g.a_half = half_act; g.out_f32 = qkv_f32; g.partial = splitk;
       g.m = T; g.n = d.qkv_out; g.k = d.H; g.lda = d.H; g.ldo = d.qkv_out;
       if (int rc = bind_weights(st, stream, g, w.wqkv, w.sqkv, w.zqkv, nullptr, nullptr, nullptr)) return rc;
       // the rotation kernel adds the split-K partial sums itself: no separate reduction pass
@@ -613,7 +616,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       if (int rc = bind_weights(st, stream, g, w.wdown, w.sdown, w.zdown, nullptr, nullptr, nullptr)) return rc;
       const e16* next_gain = last ? nullptr : (const e16*)st->layers[l + 1].norm1;
       int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_DOWN, g, fused_out ? kEpiResidualOut : kEpiResidualF32,
-                                 next_gain, a, a_lo, half_act);
+                                 next_gain, a, norm1_lo, half_act);
       if (rc) return rc;
       if (tap && taps->tap_x)
         HIP_TRY(hipMemcpyAsync(taps->tap_x, x, (size_t)T * d.H * 4, hipMemcpyDeviceToDevice, stream));
