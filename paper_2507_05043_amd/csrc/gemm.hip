@@ -435,7 +435,6 @@ constexpr int kSkinnyKS = 1024;     // K elements per slice
 constexpr int kSkinnyRows = 16;     // weight rows per stage
 constexpr int kSkinnyStages = 4;
 
-template <bool A_HALF>
 __global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs p, int nv, int splits, int groups, int swiglu) {
   constexpr int KS = kSkinnyKS, ROWS = kSkinnyRows, NST = kSkinnyStages;
   constexpr int STAGE_BYTES = ROWS * KS * 2;
@@ -547,8 +546,7 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs p, int nv, in
     for (int s = 0; s < STEPS; ++s) {
       const int off = (s >> 4) * 1024 + (s & 15) * 64 + ((s & 1) ? frag_odd : frag_even);
       const e16x8 wf = *reinterpret_cast<const e16x8*>(stage + off);
-      acc[s & 3] = A_HALF ? mfma_16x16x32_half(bf16x8_to_half(wf), __builtin_bit_cast(h16x8, act[s]), acc[s & 3])
-                          : mfma_16x16x32(wf, act[s], acc[s & 3]);
+      acc[s & 3] = mfma_16x16x32(wf, act[s], acc[s & 3]);
     }
     // eight fragment reads run ahead of the MFMA that consumes the oldest of them
     __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
@@ -608,6 +606,7 @@ hipError_t launch_epi(const GemmArgs& a, const GemmPlan& plan, hipStream_t strea
 #ifdef MOLINK_F16
     return hipErrorInvalidValue;   // the element type is half already
 #else
+    if (plan.tile == kTile64x128) return launch_tile<64, 128, 2, 2, 2, EPI, false, true>(a, plan, stream);
     switch (plan.tile) {
       // (the 256x256 tile has no registers left for the converted fragments: its plans run on 128x256 tiles,
       // twice as many workgroups over the same splits)
@@ -719,17 +718,9 @@ hipError_t launch_gemm_main(const GemmArgs& a, GemmEpilogue epi, const GemmPlan&
     const int cus = 256;
     const int nwg = units < cus ? (int)units : (cus > plan.splits ? cus : plan.splits);
     dim3 grid(nwg);
-    if (a.a_half) {
-#ifdef MOLINK_F16
-      return hipErrorInvalidValue;
-#else
-      hipLaunchKernelGGL(gemm_skinny_kernel<true>, grid, dim3(512), 0, stream, a, plan.nv, plan.splits, groups,
-                         epi == kEpiSwiGLU ? 1 : 0);
-#endif
-    } else {
-      hipLaunchKernelGGL(gemm_skinny_kernel<false>, grid, dim3(512), 0, stream, a, plan.nv, plan.splits, groups,
-                         epi == kEpiSwiGLU ? 1 : 0);
-    }
+    if (a.a_half) return hipErrorInvalidValue;     // half activations are planned onto the 64-row tiles
+    hipLaunchKernelGGL(gemm_skinny_kernel, grid, dim3(512), 0, stream, a, plan.nv, plan.splits, groups,
+                       epi == kEpiSwiGLU ? 1 : 0);
     return hipGetLastError();
   }
   if (a.q0.codes) return hipErrorInvalidValue;   // the tiled kernels take e16 weights only
