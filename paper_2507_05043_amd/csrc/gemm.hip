@@ -663,8 +663,9 @@ GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool spli
   }
   // One round of one workgroup per CU leaves a tile's prologue and epilogue exposed: nothing else runs on the CU
   // meanwhile.  If the 128x128 tiles (two per CU) also fit in one round they overlap each other's ends
-  // (measured on 2176 x 3584 x 3584: 75 us against 87).
-  if (!split_a && m > 64 && wg_per_cu == 1 && best > 0.f) {
+  // (measured on 2176 x 3584 x 3584: 75 us against 87).  Only for short K: with 296 K tiles instead of 56 the ends
+  // no longer count and the larger tile's lower traffic per flop wins again (277 us against 295).
+  if (!split_a && m > 64 && wg_per_cu == 1 && best > 0.f && k_tiles <= 96) {
     const long t_big = (long)((m + bm - 1) / bm) * ((plan.nv + bn - 1) / bn);
     const long t_small = (long)((m + 127) / 128) * ((plan.nv + 127) / 128);
     if (t_big <= num_cus && t_big * 2 > num_cus && t_small <= 2L * num_cus) {
