@@ -182,6 +182,9 @@ def main():
                                f"nkv={shape.num_kv_heads} d={shape.head_dim} F={shape.ffn}; micro-batch T={mb.num_tokens} "
                                f"S={mb.num_seqs} ({mb.num_seqs - n_dec} prefill chunks, {n_dec} decode tokens), KV block 16",
                    "seed": args.seed, "kv_layers_aliased": bool(alias),
+                   # what the library does by itself beyond 8 layers (see stage_config.activation_planes)
+                   "projection_inputs": ("IEEE half, bf16 weights converted in the GEMMs"
+                                         if args.dtype == "bf16" and shape.num_layers > 8 else args.dtype),
                    "weights": f"4-bit codes, {args.dtype} scale and zero point per 128 input features" if w4 else args.dtype},
         "stage_latency_ms": round(ms_per_step, 4),
         "ideal_ms": {"hbm": round(work["bytes_per_call"] / (HBM_PEAK_GBS * 1e9) * 1e3, 4),
