@@ -52,6 +52,7 @@ struct Dims {
 
 struct WorkspaceLayout {
   size_t x, a, a_lo, qkv_f32, qkv, q_lo, attn, attn_lo, mlp, mlp_lo, cos_sin, splitk, part_o, part_ml, meta, total;
+  size_t splitk_floats;                    // capacity of the split-K scratch
   size_t head_a, head_logits, ends_meta;   // output head: normalised last rows, fp32 logits, token ids / row indices
   size_t wexp;                             // 4-bit weights: one projection's matrices expanded to e16
   size_t meta_bytes;
@@ -157,20 +158,21 @@ WorkspaceLayout layout_of(const stage_config& c) {
   w.mlp = take(T * d.F * 2);
   w.mlp_lo = take(lo_planes_of(c) ? T * d.F * 2 : 0);
   w.cos_sin = take(T * (d.d / 2) * 8);
-  // split-K scratch for every way the projections may be planned: with two activation planes, with one, or
-  // (deep stages left to the library) either, depending on the micro-batch
+  // split-K scratch for every way the projections may be planned: as for one activation plane, and - with two
+  // planes, or with half activations, whose decode-sized projections take the two-plane plans' 64-row tiles -
+  // as for two
   size_t pf = 0, v;
   for (int sp = 0; sp < 2; ++sp) {
-    if (sp == 1 && !norm1_lo_plane_of(c)) continue;
+    if (sp == 1 && !(lo_planes_of(c) || half_act_of(c))) continue;
     if (sp == 0 && c.activation_planes == 2) continue;
     if ((v = gemm_partial_floats(c.max_tokens, d.qkv_out, d.H, kEpiStoreF32, kNumCus, sp)) > pf) pf = v;
-    if (sp == 1 && !lo_planes_of(c)) continue;      // only the q/k/v projection ever gets the second plane then
     if ((v = gemm_partial_floats(c.max_tokens, d.H, d.nq * d.d, kEpiResidualF32, kNumCus, sp)) > pf) pf = v;
     if ((v = gemm_partial_floats(c.max_tokens, d.F, d.H, kEpiSwiGLU, kNumCus, sp)) > pf) pf = v;
     if ((v = gemm_partial_floats(c.max_tokens, d.H, d.F, kEpiResidualF32, kNumCus, sp)) > pf) pf = v;
   }
   if (c.vocab_size > 0 && (v = gemm_partial_floats(c.max_seqs, c.vocab_size, d.H, kEpiStoreF32, kNumCus, false)) > pf) pf = v;
   w.splitk = take(pf * 4 + 16);
+  w.splitk_floats = pf;
   // 4-bit weights: room for the largest projection (gate and up together) expanded to e16
   {
     size_t elems = (size_t)d.qkv_out * d.H;
@@ -360,8 +362,19 @@ GemmPlan plan_for(const GemmArgs& g, GemmEpilogue epi) {
   return plan_gemm(g.m, g.n, g.k, epi, kNumCus, g.a_lo != nullptr || tiles_for_few_rows);
 }
 
+// The partial sums a plan writes must fit the scratch the workspace was laid out with.
+int check_plan(const stage_handle* st, const GemmArgs& g, const GemmPlan& plan) {
+  if (!plan.partials) return STAGE_OK;
+  const size_t need = (size_t)plan.splits * g.m * plan.nv;
+  if (need > st->ws.splitk_floats)
+    return fail(STAGE_ERR_SIZE, "internal: a projection's plan needs %zu floats of split-K scratch, the workspace holds %zu",
+                need, st->ws.splitk_floats);
+  return STAGE_OK;
+}
+
 int run_gemm(stage_handle* st, hipStream_t stream, int kernel_class, const GemmArgs& args, GemmEpilogue epi) {
   const GemmPlan plan = plan_for(args, epi);
+  if (int rc = check_plan(st, args, plan)) return rc;
   {
     Timer t(st, stream, kernel_class);
     HIP_TRY(launch_gemm_main(args, epi, plan, stream));
@@ -379,6 +392,7 @@ int run_gemm(stage_handle* st, hipStream_t stream, int kernel_class, const GemmA
 int run_residual_gemm(stage_handle* st, hipStream_t stream, int kernel_class, const GemmArgs& args, GemmEpilogue epi,
                       const e16* gain, e16* norm_out, e16* norm_out_lo, bool norm_out_half) {
   const GemmPlan plan = plan_for(args, epi);
+  if (int rc = check_plan(st, args, plan)) return rc;
   {
     Timer t(st, stream, kernel_class);
     HIP_TRY(launch_gemm_main(args, epi, plan, stream));
@@ -568,6 +582,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       if (int rc = bind_weights(st, stream, g, w.wqkv, w.sqkv, w.zqkv, nullptr, nullptr, nullptr)) return rc;
       // the rotation kernel adds the split-K partial sums itself: no separate reduction pass
       const GemmPlan plan = plan_for(g, kEpiStoreF32);
+      if (int rc = check_plan(st, g, plan)) return rc;
       {
         Timer t(st, stream, STAGE_K_GEMM_QKV);
         HIP_TRY(launch_gemm_main(g, kEpiStoreF32, plan, stream));
@@ -889,6 +904,7 @@ int stage_head(stage_handle* st, void* hip_stream, int32_t num_tokens, const voi
   g.a = head_a; g.w0 = (const e16*)lm_head; g.partial = (float*)(ws + st->ws.splitk);
   g.m = num_seqs; g.n = vocab; g.k = d.H; g.lda = d.H; g.ldo = vocab;
   const GemmPlan plan = plan_gemm(g.m, g.n, g.k, kEpiStoreF32, kNumCus, false);
+  if (int rc2 = check_plan(st, g, plan)) return rc2;
   // without partial sums the GEMM writes the logits itself (to the caller's buffer if there is one)
   float* direct = logits_out ? (float*)logits_out : (float*)(ws + st->ws.head_logits);
   g.out_f32 = direct;
