@@ -610,10 +610,12 @@ hipError_t launch_epi(const GemmArgs& a, const GemmPlan& plan, hipStream_t strea
     switch (plan.tile) {
       // (the 256x256 tile has no registers left for the converted fragments: its plans run on 128x256 tiles,
       // twice as many workgroups over the same splits)
-      case kTile256x256: return launch_tile<128, 256, 2, 2, 3, EPI, false, true>(a, plan, stream);
+      // The 128x256 tile is cut 1 x 4 among the waves here (each wave all 128 rows of a 64-column strip): every
+      // weight fragment is then converted by one wave instead of two, half the conversion work per MFMA.
+      case kTile256x256: return launch_tile<128, 256, 1, 4, 3, EPI, false, true>(a, plan, stream);
       case kTile256x128: return launch_tile<256, 128, 2, 2, 3, EPI, false, true>(a, plan, stream);
       case kTile128x128: return launch_tile<128, 128, 2, 2, 2, EPI, false, true>(a, plan, stream);
-      case kTile128x256: return launch_tile<128, 256, 2, 2, 3, EPI, false, true>(a, plan, stream);
+      case kTile128x256: return launch_tile<128, 256, 1, 4, 3, EPI, false, true>(a, plan, stream);
       default: return hipErrorInvalidValue;
     }
 #endif
