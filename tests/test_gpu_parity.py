@@ -528,14 +528,16 @@ def test_sweep_budget_256_at_full_depth(llama3_layers):
 
 
 @pytest.mark.timeout(1100)
-def test_sweep_budget_2048_depth_reduced(llama3_layers):
-    """Token budget 2048 needs more KV than one GPU holds at 20 layers; parity runs on the first 4 layers,
-    in the two-plane activation mode the 20-layer stage runs in."""
+@pytest.mark.parametrize("planes", [2, 3])
+def test_sweep_budget_2048_depth_reduced(llama3_layers, planes):
+    """Token budget 2048 needs more KV than one GPU holds at 20 layers; parity runs on the first 4 layers, in
+    the two modes that carry more than a bfloat16 plane: two planes, and half activations (what the 20-layer
+    stage takes; its second plane on the q/k/v input is covered at full depth by the budget-256 case)."""
     import dataclasses
     shape, mb = synth.workload("sweep", seed=0, budget=2048)
     shape = dataclasses.replace(shape, num_layers=4, name=shape.name + "-4layers")
     print(f"[case] sweep-2048 {shape.name} T={mb.num_tokens} q0={mb.q_lens[0]} ctx0={mb.ctx_lens[0]} blocks={mb.num_kv_blocks}",
           flush=True)
-    st = _stage_70b(shape, mb, llama3_layers, activation_planes=2)
-    _check_sampled(shape, mb, st, llama3_layers, [0, 1, 800, 1638], "sweep-2048 (4 layers)", stratified=True)
+    st = _stage_70b(shape, mb, llama3_layers, activation_planes=planes)
+    _check_sampled(shape, mb, st, llama3_layers, [0, 1, 800, 1638], f"sweep-2048 (4 layers, mode {planes})", stratified=True)
     st.close()
