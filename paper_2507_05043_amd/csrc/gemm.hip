@@ -712,10 +712,7 @@ size_t gemm_partial_floats(int max_m, int n, int k, GemmEpilogue epi, int num_cu
 hipError_t launch_gemm_main(const GemmArgs& a, GemmEpilogue epi, const GemmPlan& plan, hipStream_t stream) {
   if (plan.tile == kTileSkinny) {
     if (a.m > 64 || a.a_lo) return hipErrorInvalidValue;
-    if (a.q0.codes) {
-      if (a.a_half) return hipErrorInvalidValue;   // the 4-bit streaming kernel takes e16 activations
-      return launch_gemm_skinny_w4(a, plan.nv, plan.splits, epi == kEpiSwiGLU ? 1 : 0, stream);
-    }
+    if (a.q0.codes) return launch_gemm_skinny_w4(a, plan.nv, plan.splits, epi == kEpiSwiGLU ? 1 : 0, stream);
     const int groups = (plan.nv + kSkinnyRows - 1) / kSkinnyRows;
     const long units = (long)groups * plan.splits;
     const int cus = 256;

@@ -333,7 +333,7 @@ int bind_weights(stage_handle* st, hipStream_t stream, GemmArgs& g, const void* 
     return STAGE_OK;
   }
   const W4Matrix m0{(const uint32_t*)w0, (const e16*)s0, (const e16*)z0};
-  if (!g.a_half && skinny_w4_supports(g.m, g.k, st->cfg.weight_group_size, g.a_lo != nullptr)) {
+  if (skinny_w4_supports(g.m, g.k, st->cfg.weight_group_size, g.a_lo != nullptr)) {
     // decode-sized micro-batch: the weight-streaming kernel reads the stored form itself
     g.q0 = m0;
     if (w1) g.q1 = W4Matrix{(const uint32_t*)w1, (const e16*)s1, (const e16*)z1};

@@ -62,26 +62,32 @@ constexpr int kW4Stages = 4;
 constexpr int kW4StageBytes = 32 * 512 + 512 + 512;   // codes, scales [4 pairs][32 rows] dwords, zero points likewise
 constexpr int kW4Group = 128;
 
-// The offset whose e16 pattern has its four lowest mantissa bits worth 1, 2, 4, 8, and 1.0 as a pair.
-#ifdef MOLINK_F16
-constexpr uint32_t kCodeBasePair = 0x64006400u, kOnesPair = 0x3C003C00u;
-constexpr float kCodeBase = 1024.f;
-#else
-constexpr uint32_t kCodeBasePair = 0x43004300u, kOnesPair = 0x3F803F80u;
-constexpr float kCodeBase = 128.f;
-#endif
+// The 16-bit format of the MFMA operands: e16, or IEEE half when a bfloat16 stage keeps its activations as half
+// (HALF_ACT).  Per format: the offset whose pattern has its four lowest mantissa bits worth 1, 2, 4, 8 (as a
+// pair), 1.0 as a pair, and the offset as a number.  Scales and zero points are e16 in either case.
+template <bool HALF_ACT> struct OperandFormat {
+  static constexpr bool kHalf = HALF_ACT || kElemIsF16 != 0;
+  static constexpr uint32_t kCodeBasePair = kHalf ? 0x64006400u : 0x43004300u;
+  static constexpr uint32_t kOnesPair = kHalf ? 0x3C003C00u : 0x3F803F80u;
+  static constexpr float kCodeBase = kHalf ? 1024.f : 128.f;
+};
 
-// Two 4-bit codes (bits 0-3 and 16-19 of x) as two e16 numbers offset + code.  Plain C on purpose: written as an
+// Two 4-bit codes (bits 0-3 and 16-19 of x) as two 16-bit numbers offset + code.  Plain C on purpose: written as an
 // inline-assembly v_and_or_b32 the result fed the next MFMA without the wait states the compiler inserts
 // between a vector write and a matrix read (it does not look inside assembly), and results were wrong.
-__device__ __forceinline__ uint32_t expand_pair(uint32_t x) { return (x & 0x000F000Fu) | kCodeBasePair; }
+template <bool HALF_ACT> __device__ __forceinline__ uint32_t expand_pair(uint32_t x) {
+  return (x & 0x000F000Fu) | OperandFormat<HALF_ACT>::kCodeBasePair;
+}
 
-__device__ __forceinline__ f32x4 mfma16(e16x8 a, e16x8 b, f32x4 c) {
-  return mfma_16x16x32(a, b, c);
+template <bool HALF_ACT> __device__ __forceinline__ f32x4 mfma16(e16x8 a, e16x8 b, f32x4 c) {
+  if constexpr (OperandFormat<HALF_ACT>::kHalf)
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h16x8, a), __builtin_bit_cast(h16x8, b), c, 0, 0, 0);
+  else
+    return mfma_16x16x32(a, b, c);
 }
 
 // NBLK: blocks of 16 activation rows in use (1..4); wave j < NBLK owns block j.
-template <int NBLK>
+template <int NBLK, bool HALF_ACT>
 __global__ __launch_bounds__(512) void gemm_skinny_w4_kernel(GemmArgs p, int nv, int splits, int groups, int swiglu) {
   constexpr int NI = 5;                    // load instructions per loading wave per stage (4 of codes, 1 of scales or zero points)
   using Lds = LdsStages<kW4StageBytes>;
@@ -189,13 +195,14 @@ __global__ __launch_bounds__(512) void gemm_skinny_w4_kernel(GemmArgs p, int nv,
   // sum of this lane's activation row (row col of block j) over the wave's group
   float asum[NBLK];
   {
+    constexpr uint32_t kOnesPair = OperandFormat<HALF_ACT>::kOnesPair;
     const u32x4 ones_bits = {kOnesPair, kOnesPair, kOnesPair, kOnesPair};
     const e16x8 ones = __builtin_bit_cast(e16x8, ones_bits);
 #pragma unroll
     for (int j = 0; j < NBLK; ++j) {
       f32x4 s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int t = 0; t < 4; ++t) s = mfma16(ones, act[j][t], s);   // every row of the result is the sum
+      for (int t = 0; t < 4; ++t) s = mfma16<HALF_ACT>(ones, act[j][t], s);   // every row of the result is the sum
       asum[j] = s[0];
     }
   }
@@ -239,16 +246,17 @@ __global__ __launch_bounds__(512) void gemm_skinny_w4_kernel(GemmArgs p, int nv,
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       const uint32_t x = xs[t];
-      const u32x4 wbits = {expand_pair(x), expand_pair(x >> 4), expand_pair(x >> 8), expand_pair(x >> 12)};
+      const u32x4 wbits = {expand_pair<HALF_ACT>(x), expand_pair<HALF_ACT>(x >> 4), expand_pair<HALF_ACT>(x >> 8),
+                           expand_pair<HALF_ACT>(x >> 12)};
       const e16x8 wf = __builtin_bit_cast(e16x8, wbits);
 #pragma unroll
-      for (int j = 0; j < NBLK; ++j) tmp[j] = mfma16(wf, act[j][t], tmp[j]);
+      for (int j = 0; j < NBLK; ++j) tmp[j] = mfma16<HALF_ACT>(wf, act[j][t], tmp[j]);
     }
     f32x4 s, zc;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       s[r] = (wave & 1) ? e16_hi(sc[r]) : e16_lo(sc[r]);
-      zc[r] = kCodeBase + ((wave & 1) ? e16_hi(zp[r]) : e16_lo(zp[r]));
+      zc[r] = OperandFormat<HALF_ACT>::kCodeBase + ((wave & 1) ? e16_hi(zp[r]) : e16_lo(zp[r]));
     }
     // hand every block's contribution to its owner
 #pragma unroll
@@ -313,12 +321,29 @@ hipError_t launch_gemm_skinny_w4(const GemmArgs& a, int nv, int splits, int swig
   const long units = (long)groups * splits;
   const int cus = 256;
   const int nwg = units < cus ? (int)units : (cus > splits ? cus : splits);
-  switch ((a.m + 15) / 16) {
-    case 1: hipLaunchKernelGGL(gemm_skinny_w4_kernel<1>, dim3(nwg), dim3(512), 0, stream, a, nv, splits, groups, swiglu); break;
-    case 2: hipLaunchKernelGGL(gemm_skinny_w4_kernel<2>, dim3(nwg), dim3(512), 0, stream, a, nv, splits, groups, swiglu); break;
-    case 3: hipLaunchKernelGGL(gemm_skinny_w4_kernel<3>, dim3(nwg), dim3(512), 0, stream, a, nv, splits, groups, swiglu); break;
-    default: hipLaunchKernelGGL(gemm_skinny_w4_kernel<4>, dim3(nwg), dim3(512), 0, stream, a, nv, splits, groups, swiglu); break;
+  const int blocks = (a.m + 15) / 16;
+#define MOLINK_W4_LAUNCH(NB, HALF) \
+  hipLaunchKernelGGL((gemm_skinny_w4_kernel<NB, HALF>), dim3(nwg), dim3(512), 0, stream, a, nv, splits, groups, swiglu)
+  if (a.a_half) {
+#ifdef MOLINK_F16
+    return hipErrorInvalidValue;   // the element type is half already
+#else
+    switch (blocks) {
+      case 1: MOLINK_W4_LAUNCH(1, true); break;
+      case 2: MOLINK_W4_LAUNCH(2, true); break;
+      case 3: MOLINK_W4_LAUNCH(3, true); break;
+      default: MOLINK_W4_LAUNCH(4, true); break;
+    }
+#endif
+  } else {
+    switch (blocks) {
+      case 1: MOLINK_W4_LAUNCH(1, false); break;
+      case 2: MOLINK_W4_LAUNCH(2, false); break;
+      case 3: MOLINK_W4_LAUNCH(3, false); break;
+      default: MOLINK_W4_LAUNCH(4, false); break;
+    }
   }
+#undef MOLINK_W4_LAUNCH
   return hipGetLastError();
 }
 
