@@ -621,25 +621,28 @@ hipError_t launch_epi(const GemmArgs& a, const GemmPlan& plan, hipStream_t strea
 #endif
   }
   switch (plan.tile) {
+    case kTile64x128: return launch_tile<64, 128, 2, 2, 2, EPI, false>(a, plan, stream);
     case kTile256x256: return launch_tile<256, 256, 2, 2, 2, EPI, false>(a, plan, stream);
     case kTile256x128: return launch_tile<256, 128, 2, 2, 3, EPI, false>(a, plan, stream);
     case kTile128x128: return launch_tile<128, 128, 2, 2, 2, EPI, false>(a, plan, stream);
     case kTile128x256: return launch_tile<128, 256, 2, 2, 3, EPI, false>(a, plan, stream);
-    default: return hipErrorInvalidValue;   // 64x128 exists only for two activation planes; single-plane M <= 64 is kTileSkinny
+    default: return hipErrorInvalidValue;
   }
 }
 
 }  // namespace
 
-GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool split_a) {
+GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool split_a, GemmFewRows few_rows) {
   GemmPlan plan;
   plan.nv = epi == kEpiSwiGLU ? ((n + 31) / 32) * 64 : n;
+  const bool wide = k >= 8192 && (long)plan.nv * k >= (64L << 20);
+  const bool streaming = few_rows == kFewRowsStreaming || (few_rows == kFewRowsByShape && !wide);
   const int k_tiles = (k + kBK - 1) / kBK;
   struct Cand { int tile, bm, bn, wg_per_cu; float eff; };
   // measured relative efficiency of the tile shapes and how many workgroups of each fit on a CU (LDS)
   static const Cand cands[] = {{kTile128x256, 128, 256, 1, 1.0f}, {kTile256x128, 256, 128, 1, 0.99f},
                                {kTile256x256, 256, 256, 1, 0.97f}, {kTile128x128, 128, 128, 2, 0.86f}};
-  if (m <= 64 && !split_a) {
+  if (m <= 64 && !split_a && streaming) {
     plan.tile = kTileSkinny;
     plan.splits = (k + kSkinnyKS - 1) / kSkinnyKS;
     plan.k_tiles_per_split = kSkinnyKS / kBK;
@@ -694,11 +697,14 @@ size_t gemm_partial_floats(int max_m, int n, int k, GemmEpilogue epi, int num_cu
   // plan can change (multiples of 64) is tried.
   size_t worst = 0;
   for (int m = 1; m <= max_m; m = (m < 64 ? 64 : m + 64)) {
-    const GemmPlan p = plan_gemm(m, n, k, epi, num_cus, split_a);
-    if (p.partials) {
-      const int mm = m < 64 ? (max_m < 64 ? max_m : 64) : m;   // the plan of m = 1 holds up to 64 rows
-      const size_t need = (size_t)p.splits * mm * p.nv;
-      if (need > worst) worst = need;
+    for (GemmFewRows few : {kFewRowsStreaming, kFewRowsTiles}) {
+      if (m > 64 && few == kFewRowsTiles) continue;            // above 64 rows there is one plan
+      const GemmPlan p = plan_gemm(m, n, k, epi, num_cus, split_a, few);
+      if (p.partials) {
+        const int mm = m < 64 ? (max_m < 64 ? max_m : 64) : m;   // the plan of m = 1 holds up to 64 rows
+        const size_t need = (size_t)p.splits * mm * p.nv;
+        if (need > worst) worst = need;
+      }
     }
   }
   const GemmPlan p = plan_gemm(max_m, n, k, epi, num_cus, split_a);

@@ -55,8 +55,18 @@ struct GemmPlan {
   int nv;               // width of the column space the kernel iterates (gate/up interleaved for SwiGLU, else N)
 };
 
-GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool split_a = false);
-// Floats of split-K scratch that any GEMM with m <= max_m rows of this (n, k, epilogue) may need.
+// How a product of at most 64 rows (one activation plane) is planned: on the weight-streaming kernel, on 64-row
+// tiles, or by shape.  Wide projections (K of 8192 and more, 64 M weights and more) do better on the tiles: the
+// streaming kernel cuts K into slices of 1024 and writes one plane of partial sums per slice, and with 8 to 28
+// slices its reductions cost more than the tiles' few K splits (70B-shaped stage, 52 sequences: 8.5 ms of
+// projections and reductions per micro-batch against 7.2); at 7B shapes the streaming kernel is ahead (2.86 ms per
+// micro-batch against 3.00).
+enum GemmFewRows : int { kFewRowsByShape = 0, kFewRowsStreaming = 1, kFewRowsTiles = 2 };
+
+GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool split_a = false,
+                   GemmFewRows few_rows = kFewRowsByShape);
+// Floats of split-K scratch that any GEMM with m <= max_m rows of this (n, k, epilogue) may need, however its
+// products of at most 64 rows are planned.
 size_t gemm_partial_floats(int max_m, int n, int k, GemmEpilogue epi, int num_cus, bool split_a = false);
 
 hipError_t launch_gemm_main(const GemmArgs& args, GemmEpilogue epi, const GemmPlan& plan, hipStream_t stream);

@@ -352,14 +352,11 @@ int bind_weights(stage_handle* st, hipStream_t stream, GemmArgs& g, const void* 
   return STAGE_OK;
 }
 
-// The plan of a projection.  Decode-sized micro-batches with half activations take the 64-row tiles that the
-// two-plane mode uses, not the weight-streaming kernel: deep stages are wide (K of 8192 and more means eight and
-// more K slices of partial sums per output in the streaming kernel), and on those shapes the tiles, two
-// workgroups per CU with few or no K splits, stream the weights faster (measured on the 70B-shaped stage at 64
-// rows: 7.6 ms per micro-batch against 9.1 including the reductions).
+// The plan of a projection.  At most 64 rows: 4-bit weights in their stored form need the streaming kernel; half
+// activations run on the 64-row tiles (the bf16 streaming kernel takes e16 activations); otherwise the shape decides.
 GemmPlan plan_for(const GemmArgs& g, GemmEpilogue epi) {
-  const bool tiles_for_few_rows = g.a_half && g.m <= 64 && !g.q0.codes;
-  return plan_gemm(g.m, g.n, g.k, epi, kNumCus, g.a_lo != nullptr || tiles_for_few_rows);
+  const GemmFewRows few = g.q0.codes ? kFewRowsStreaming : (g.a_half ? kFewRowsTiles : kFewRowsByShape);
+  return plan_gemm(g.m, g.n, g.k, epi, kNumCus, g.a_lo != nullptr, few);
 }
 
 // The partial sums a plan writes must fit the scratch the workspace was laid out with.
@@ -903,7 +900,8 @@ int stage_head(stage_handle* st, void* hip_stream, int32_t num_tokens, const voi
   GemmArgs g{};
   g.a = head_a; g.w0 = (const e16*)lm_head; g.partial = (float*)(ws + st->ws.splitk);
   g.m = num_seqs; g.n = vocab; g.k = d.H; g.lda = d.H; g.ldo = vocab;
-  const GemmPlan plan = plan_gemm(g.m, g.n, g.k, kEpiStoreF32, kNumCus, false);
+  // the output head stays on the weight-streaming kernel at few rows: its reduction is the argmax kernel's pass
+  const GemmPlan plan = plan_gemm(g.m, g.n, g.k, kEpiStoreF32, kNumCus, false, kFewRowsStreaming);
   if (int rc2 = check_plan(st, g, plan)) return rc2;
   // without partial sums the GEMM writes the logits itself (to the caller's buffer if there is one)
   float* direct = logits_out ? (float*)logits_out : (float*)(ws + st->ws.head_logits);

@@ -130,6 +130,17 @@ def test_half_activations_in_the_bfloat16_library(case):
         assert stats3["rel_l2"] <= 1.05 * stats1["rel_l2"]
 
 
+@pytest.mark.parametrize("n_decode,elem", [(1, torch.bfloat16), (40, torch.float16), (64, torch.bfloat16)],
+                         ids=["1-bf16", "40-f16", "64-bf16"])
+def test_wide_projections_at_few_rows(n_decode, elem):
+    """70B-class widths (K = 8192, 64 M weights and more per projection) with at most 64 rows: these products are
+    planned onto 64-row tiles with K splits instead of the weight-streaming kernel; one plane of the element type."""
+    shape = _shape("wide", 1, 8192, 64, 8, 128, 8192)
+    ctx = [30 + 41 * i % 500 for i in range(n_decode)]
+    mb = synth.make_microbatch([1] * n_decode, ctx, seed=12, max_blocks_per_seq=40)
+    full_parity(shape, mb, 12, "fan_in", taps=(n_decode == 40), activation_planes=1, elem=elem)
+
+
 def test_one_head_norm_gain_without_the_other_is_rejected():
     shape, mb = synth.workload("tiny", seed=0)
     from paper_2507_05043_amd.stage import Stage, make_config
