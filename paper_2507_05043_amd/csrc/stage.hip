@@ -900,8 +900,7 @@ int stage_head(stage_handle* st, void* hip_stream, int32_t num_tokens, const voi
   GemmArgs g{};
   g.a = head_a; g.w0 = (const e16*)lm_head; g.partial = (float*)(ws + st->ws.splitk);
   g.m = num_seqs; g.n = vocab; g.k = d.H; g.lda = d.H; g.ldo = vocab;
-  // the output head stays on the weight-streaming kernel at few rows: its reduction is the argmax kernel's pass
-  const GemmPlan plan = plan_gemm(g.m, g.n, g.k, kEpiStoreF32, kNumCus, false, kFewRowsStreaming);
+  const GemmPlan plan = plan_gemm(g.m, g.n, g.k, kEpiStoreF32, kNumCus, false);
   if (int rc2 = check_plan(st, g, plan)) return rc2;
   // without partial sums the GEMM writes the logits itself (to the caller's buffer if there is one)
   float* direct = logits_out ? (float*)logits_out : (float*)(ws + st->ws.head_logits);
