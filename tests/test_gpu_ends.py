@@ -104,6 +104,11 @@ def test_head_llama3_70b_full_size():
     _head_case(synth.LLAMA3_70B_STAGE, 256, seed=0, sample=list(range(0, 256, 16)))
 
 
+def test_head_llama3_70b_few_sequences():
+    # at most 64 rows on a wide head (K = 8192): planned onto 64-row tiles, the logits written by the GEMM itself
+    _head_case(synth.LLAMA3_70B_STAGE, 40, seed=2, sample=list(range(0, 40, 5)))
+
+
 def test_equal_logits_resolve_to_the_smallest_index():
     shape = synth.TINY
     st = _head_stage(shape, 4, 4, 1)
