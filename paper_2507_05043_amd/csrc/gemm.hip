@@ -681,7 +681,9 @@ GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool spli
   const int tiles = ((m + bm - 1) / bm) * ((plan.nv + bn - 1) / bn);
   int splits = 1;
   if (tiles * 2 <= num_cus * wg_per_cu) {
-    splits = (num_cus * wg_per_cu + tiles - 1) / tiles;
+    // as many splits as still fit one round of workgroups: one more would start a second, nearly empty round
+    // that takes as long as the first
+    splits = (num_cus * wg_per_cu) / tiles;
     const int max_by_k = k_tiles / 4 > 0 ? k_tiles / 4 : 1;   // at least 4 K tiles per split
     if (splits > max_by_k) splits = max_by_k;
     if (splits > 16) splits = 16;
