@@ -14,7 +14,12 @@
 // Shapes without enough output tiles to fill 256 CUs split the K dimension across workgroups; the
 // partial sums go to fp32 scratch and a second kernel adds them in a fixed order (deterministic) and
 // applies the epilogue.  Micro-batches of at most 64 rows (decode) have a kernel of their own,
-// gemm_skinny_kernel below, built around streaming the weights.
+// gemm_skinny_kernel below, built around streaming the weights; the widest projections (K of 8192 and more)
+// run on 64-row tiles instead (see GemmFewRows).
+//
+// Half activations (bfloat16 library, deep stages): with A_HALF the A operand holds IEEE half bits, every weight
+// fragment read from LDS is converted from bfloat16 to half in registers (exact) and the f16 MFMA is used; the
+// tiles, their pipeline and their epilogues are otherwise the same code.
 #include "gemm.hpp"
 #include "w4.hpp"
 #include "common.hpp"
