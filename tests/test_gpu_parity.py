@@ -166,6 +166,7 @@ def test_edge_batches_d64(case):
     shape = _shape("edge-d64-g2", 2, 256, 4, 2, 64, 688)
     mb = synth.make_microbatch(case["q"], case["c"], seed=21)
     full_parity(shape, mb, 21, "fan_in")
+    full_parity(shape, mb, 21, "fan_in", activation_planes=3)      # the same edges with half activations
 
 
 @pytest.mark.parametrize("nq,nkv", [(4, 4), (8, 2), (14, 2), (16, 1)])
@@ -181,6 +182,8 @@ def test_large_m_tiles_and_k_tails():
     mb = synth.make_microbatch([150, 61, 1, 1], [0, 20, 300, 5], seed=23)
     full_parity(shape, mb, 23, "fan_in")
     full_parity(shape, mb, 23, None, taps=False)
+    full_parity(shape, mb, 23, "fan_in", activation_planes=3)      # the tails with half activations
+    full_parity(shape, mb, 23, "fan_in", activation_planes=3, elem=torch.bfloat16, qkv_bias=True, taps=False)
 
 
 def test_chunked_prefill_equals_unsplit_on_gpu():
