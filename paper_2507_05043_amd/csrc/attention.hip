@@ -231,17 +231,21 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const Decod
   const int g = a.nq / a.nkv;
   const int r = head / g, col = head % g;
   const DecodeToken t = tokens[tok];
-  float m_max = -INFINITY;
-  for (int i = 0; i < t.num_items; ++i) {
-    const size_t slot = ((size_t)(t.first_item + i) * a.nkv + r) * g + col;
-    m_max = fmaxf(m_max, part_ml[slot].x);
-  }
-  float l = 0.f;
-  f32x4 o = {0.f, 0.f, 0.f, 0.f};
-  // four ranges per trip: their loads are issued together, the sums stay in range order
+  // four ranges per trip in both passes: their loads are issued together, the sums stay in range order
   const size_t slot_step = (size_t)a.nkv * g;
   const size_t slot0 = ((size_t)t.first_item * a.nkv + r) * g + col;
+  float m_max = -INFINITY;
   int i = 0;
+  for (; i + 4 <= t.num_items; i += 4) {
+    float mx[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) mx[u] = part_ml[slot0 + (size_t)(i + u) * slot_step].x;
+    m_max = fmaxf(fmaxf(m_max, fmaxf(mx[0], mx[1])), fmaxf(mx[2], mx[3]));
+  }
+  for (; i < t.num_items; ++i) m_max = fmaxf(m_max, part_ml[slot0 + (size_t)i * slot_step].x);
+  float l = 0.f;
+  f32x4 o = {0.f, 0.f, 0.f, 0.f};
+  i = 0;
   for (; i + 4 <= t.num_items; i += 4) {
     float2 ml[4];
     f32x4 po[4];
