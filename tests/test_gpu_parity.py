@@ -141,6 +141,29 @@ def test_wide_projections_at_few_rows(n_decode, elem):
     full_parity(shape, mb, 12, "fan_in", taps=(n_decode == 40), activation_planes=1, elem=elem)
 
 
+@pytest.mark.parametrize("case", range(10))
+def test_seeded_random_small_stages(case):
+    """Ten seeded draws of stage shape, micro-batch composition, activation mode, element type and block variant:
+    combinations no hand-written case names."""
+    import random
+    rng = random.Random(1000 + case)
+    d = rng.choice([64, 128])
+    nkv = rng.choice([1, 2, 4])
+    nq = nkv * rng.choice([1, 2, 3, 7, 8])
+    hidden = 8 * rng.randint(16, 90)
+    ffn = 8 * rng.randint(16, 200)
+    layers = rng.randint(1, 3)
+    shape = _shape(f"random-{case}", layers, hidden, nq, nkv, d, ffn, theta=rng.choice([1e4, 5e5]))
+    n_seq = rng.randint(1, 9)
+    q_lens = [rng.choice([1, 1, 1, rng.randint(2, 90)]) for _ in range(n_seq)]
+    ctx = [rng.choice([0, rng.randint(1, 400)]) if q > 1 else rng.randint(0, 900) for q in q_lens]
+    mb = synth.make_microbatch(q_lens, ctx, seed=case)
+    elem = rng.choice([torch.bfloat16, torch.float16])
+    planes = rng.choice([1, 2, 3]) if elem == torch.bfloat16 else rng.choice([1, 2])
+    full_parity(shape, mb, 2000 + case, rng.choice([None, "fan_in"]), qkv_bias=rng.random() < 0.4,
+                qk_norm=rng.random() < 0.4, activation_planes=planes, elem=elem)
+
+
 def test_one_head_norm_gain_without_the_other_is_rejected():
     shape, mb = synth.workload("tiny", seed=0)
     from paper_2507_05043_amd.stage import Stage, make_config
