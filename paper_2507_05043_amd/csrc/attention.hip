@@ -316,8 +316,17 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int tile_id = blockIdx.x;
-  const int r = blockIdx.y;
+  // Work order.  The tile list is sorted by keys seen, longest first, and every tile exists once per KV head.  Two
+  // workgroups fit on a CU; when the launch is between one and two workgroups per CU, all of them are resident at
+  // once and a CU's time is the sum of its two.  The first 256 workgroups (one per CU) take the longest tiles in
+  // order, the rest take the remaining ones shortest first, so that the longest tile shares its CU with the
+  // shortest, the second longest with the second shortest, and so on.  Larger launches keep longest-first.
+  const int total = num_tiles * a.nkv;
+  constexpr int kFirstPass = 256;
+  int pos = blockIdx.x;
+  if (total > kFirstPass && total <= 2 * kFirstPass && pos >= kFirstPass) pos = total - 1 - (pos - kFirstPass);
+  const int tile_id = pos / a.nkv;
+  const int r = pos % a.nkv;
   const int g = a.nq / a.nkv;
   const int row0 = __builtin_amdgcn_readfirstlane(tiles[tile_id].row0);
   const int q_len = __builtin_amdgcn_readfirstlane(tiles[tile_id].q_len);
@@ -526,7 +535,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
 }  // namespace
 
 hipError_t launch_attn_prefill(const AttnArgs& a, const PrefillTile* tiles, int num_tiles, hipStream_t stream) {
-  dim3 grid(num_tiles, a.nkv), block(256);
+  dim3 grid(num_tiles * a.nkv), block(256);
   if (a.head_dim == 128) {
     if (a.q_lo) hipLaunchKernelGGL((attn_prefill_kernel<128, true>), grid, block, 0, stream, a, tiles, num_tiles);
     else hipLaunchKernelGGL((attn_prefill_kernel<128, false>), grid, block, 0, stream, a, tiles, num_tiles);
