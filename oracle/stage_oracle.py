@@ -32,7 +32,10 @@ tiny shapes; dense masked attention; paged == contiguous (bitwise); chunked ==
 unsplit; decode == last prefill row; batch-order independence; closed forms for
 RMSNorm, RoPE, softmax degenerate cases; GQA == MHA with replicated heads;
 zero output projections give the identity; library cross-checks (fp64 matmul
-chain, torch scaled_dot_product_attention).  The paper prints no numeric values
+chain, torch scaled_dot_product_attention); the cache-as-a-narrower-store
+switch (kv_store_dtype): a store as wide as the arithmetic changes nothing bit
+for bit, a bfloat16 store rounds exactly the appended slots once, scalar loops
+that read back what they stored, chunked == unsplit under it.  The paper prints no numeric values
 for this path, so parity against printed values is unpinned; parity is against
 the definition.
 """

@@ -72,3 +72,53 @@ def layer_one_sequence(shape, w, rows, pos, cache_k, cache_v):
         dn = matvec(w["wdown"], m)
         outs.append([hrow[j] + dn[j] for j in range(hdim)])
     return outs
+
+
+def round_to_bfloat16(x):
+    """A Python float rounded to the nearest bfloat16 (ties to even), by way of float32 - the route a
+    float64 tensor takes when it is stored into a bfloat16 cache."""
+    import struct
+    bits = struct.unpack("<I", struct.pack("<f", x))[0]
+    if (bits & 0x7F800000) == 0x7F800000:                 # inf / nan: keep the top half
+        return struct.unpack("<f", struct.pack("<I", bits & 0xFFFF0000))[0]
+    bits += 0x7FFF + ((bits >> 16) & 1)
+    return struct.unpack("<f", struct.pack("<I", bits & 0xFFFF0000))[0]
+
+
+def layer_one_sequence_rounded_cache(shape, w, rows, pos, cache_k, cache_v, store=round_to_bfloat16):
+    """The same block when the cache is a store of a narrower type: every new key (after the rotation)
+    and value passes through `store` on its way into the cache, and attention - of the chunk that
+    wrote them too - reads the cache."""
+    nq, nkv, d, hdim = shape.num_q_heads, shape.num_kv_heads, shape.head_dim, shape.hidden
+    g = nq // nkv
+    ctx = len(cache_k)
+    qs = []
+    for n, x in enumerate(rows):
+        a = rmsnorm_row(x, w["norm1"], shape.rms_eps)
+        qkv = matvec(w["wqkv"], a)
+        q = [rope_head(qkv[h * d:(h + 1) * d], pos[n], shape.rope_theta) for h in range(nq)]
+        k = [rope_head(qkv[(nq + r) * d:(nq + r + 1) * d], pos[n], shape.rope_theta) for r in range(nkv)]
+        v = [qkv[(nq + nkv + r) * d:(nq + nkv + r + 1) * d] for r in range(nkv)]
+        cache_k.append([[store(e) for e in head] for head in k])
+        cache_v.append([[store(e) for e in head] for head in v])
+        qs.append(q)
+    outs = []
+    for n, x in enumerate(rows):
+        o = []
+        for h in range(nq):
+            r = h // g
+            last = ctx + n
+            e = [sum(qs[n][h][c] * cache_k[j][r][c] for c in range(d)) / math.sqrt(d) for j in range(last + 1)]
+            mx = max(e)
+            wts = [math.exp(v_ - mx) for v_ in e]
+            z = sum(wts)
+            o.extend(sum(wts[j] / z * cache_v[j][r][c] for j in range(last + 1)) for c in range(d))
+        proj = matvec(w["wo"], o)
+        hrow = [x[j] + proj[j] for j in range(hdim)]
+        b = rmsnorm_row(hrow, w["norm2"], shape.rms_eps)
+        gate = matvec(w["wgate"], b)
+        up = matvec(w["wup"], b)
+        m = [gate[f] / (1.0 + math.exp(-gate[f])) * up[f] for f in range(len(gate))]
+        dn = matvec(w["wdown"], m)
+        outs.append([hrow[j] + dn[j] for j in range(hdim)])
+    return outs

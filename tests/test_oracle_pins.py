@@ -24,12 +24,13 @@ def small_shape(**kw):
     return synth.StageShape(**base)
 
 
-def run_oracle(shape, mb, seed=0, weight_std="fan_in", layers=None, hidden=None, pool=None, taps=None):
+def run_oracle(shape, mb, seed=0, weight_std="fan_in", layers=None, hidden=None, pool=None, taps=None,
+               kv_store_dtype=None):
     layers = layers if layers is not None else draw_layers(shape, seed, weight_std)
     hidden = hidden if hidden is not None else synth.draw_hidden(shape, mb.num_tokens, seed=seed)
     pool = pool if pool is not None else oracle_pool(shape, mb, seed)
     out, slots = oracle.stage_forward(oracle_shape(shape), layers, hidden, mb.positions, mb.q_lens,
-                                      mb.ctx_lens, mb.block_tables, pool, taps=taps)
+                                      mb.ctx_lens, mb.block_tables, pool, taps=taps, kv_store_dtype=kv_store_dtype)
     return out, slots, pool
 
 
@@ -240,8 +241,15 @@ def test_gqa_equals_mha_with_replicated_kv_heads():
     out_m, _ = oracle.stage_forward(oracle_shape(mha), [w], synth.draw_hidden(shape, mb.num_tokens, seed=1),
                                     mb.positions, mb.q_lens, mb.ctx_lens, mb.block_tables, pool_m)
     assert torch.allclose(out, out_m, rtol=1e-12, atol=1e-13)
-    # and the mapping is h // g, not h % nkv: permuting kv heads the other way changes the result
+    # and the mapping is h // g, not h % nkv: replicating the KV heads the other way round (head h takes KV head
+    # h % nkv) is a different block
     assert g > 1
+    til = lambda m: m.view(nkv, d, -1).repeat(g, 1, 1).reshape(nq * d, -1)
+    w_mod = dict(w, wqkv=torch.cat([wq, til(wk), til(wv)], dim=0))
+    pool_mod = pool_g.repeat(1, 1, 1, 1, g, 1)
+    out_mod, _ = oracle.stage_forward(oracle_shape(mha), [w_mod], synth.draw_hidden(shape, mb.num_tokens, seed=1),
+                                      mb.positions, mb.q_lens, mb.ctx_lens, mb.block_tables, pool_mod)
+    assert not torch.allclose(out, out_mod, rtol=1e-3, atol=1e-4)
 
 
 # ---------------------------------------------------------------- paging, chunking, batching
@@ -335,6 +343,105 @@ def test_rows_independent_of_batch_composition_and_order():
                             mb.positions[cu[s]:cu[s + 1]], mb.num_kv_blocks)
     out_1, _, _ = run_oracle(shape, mb_1, layers=layers, hidden=hidden[cu[s]:cu[s + 1]], pool=pool.clone())
     assert torch.allclose(out_1, out[cu[s]:cu[s + 1]], rtol=1e-12, atol=1e-13)
+
+
+# ---------------------------------------------------------------- the cache as a store of a narrower type
+
+def test_cache_store_type_as_wide_as_the_arithmetic_changes_nothing():
+    """kv_store_dtype = the oracle's own float64: a rounding that rounds nothing; output and pool bit for bit."""
+    shape = small_shape()
+    mb = synth.make_microbatch([9, 1, 1, 20], [3, 33, 0, 11], seed=31)
+    out0, slots0, pool0 = run_oracle(shape, mb, seed=31)
+    out1, slots1, pool1 = run_oracle(shape, mb, seed=31, kv_store_dtype=F64)
+    assert slots0 == slots1 and torch.equal(out0, out1)
+    assert torch.equal(pool0.nan_to_num(nan=-7.0), pool1.nan_to_num(nan=-7.0))
+
+
+def test_cache_store_rounds_exactly_the_appended_slots_once():
+    """With a bfloat16 store, what a layer appends is what the unrounded reading appends, rounded once to
+    bfloat16, at exactly the mapped slots (first layer: its input does not depend on the reading), everything
+    else in the pool stays bit for bit; the new values are bfloat16 numbers."""
+    shape = small_shape(num_layers=2)
+    q_lens, ctx_lens = [18, 1, 1], [15, 16, 31]
+    mb = synth.make_microbatch(q_lens, ctx_lens, seed=32)
+    before = oracle_pool(shape, mb, 32)
+    _, slots, pool_plain = run_oracle(shape, mb, seed=32, pool=before.clone())
+    _, slots_r, pool_round = run_oracle(shape, mb, seed=32, pool=before.clone(), kv_store_dtype=torch.bfloat16)
+    assert slots == slots_r
+    flat = lambda p: p.view(shape.num_layers, 2, -1, shape.num_kv_heads, shape.head_dim)
+    want = torch.zeros(mb.num_kv_blocks * 16, dtype=torch.bool)
+    want[slots] = True
+    b, p, r = flat(before), flat(pool_plain), flat(pool_round)
+    assert torch.equal(r[:, :, ~want].nan_to_num(nan=-7.0), b[:, :, ~want].nan_to_num(nan=-7.0))
+    assert torch.equal(r[0][:, want], p[0][:, want].to(torch.bfloat16).to(F64))
+    assert not torch.equal(r[0][:, want], p[0][:, want])                   # the rounding did something
+    new = r[:, :, want]
+    assert torch.equal(new, new.to(torch.bfloat16).to(F64))                # every appended value is a bfloat16 number
+    # the second layer's appends differ from the rounded plain ones only through the first layer's attention
+    assert torch.allclose(r[1][:, want], p[1][:, want], rtol=0, atol=0.05)
+
+
+@pytest.mark.parametrize("nq,nkv", [(4, 2), (3, 3), (4, 1)])
+def test_rounded_cache_matches_scalar_loops_that_read_back_what_they_stored(nq, nkv):
+    """Scalar loops in which every new key and value is rounded to bfloat16 on its way into the cache and the
+    chunk that wrote them attends to the stored values."""
+    shape = small_shape(num_q_heads=nq, num_kv_heads=nkv, hidden=12, ffn=20, head_dim=4, kv_block_size=4)
+    q_lens, ctx_lens = [5, 1, 3], [0, 6, 2]
+    mb = synth.make_microbatch(q_lens, ctx_lens, seed=3, block=4)
+    layers = draw_layers(shape, 3, "fan_in")
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=3)
+    pool = oracle_pool(shape, mb, 3)
+    pool0 = pool.clone()
+    out, _, _ = run_oracle(shape, mb, layers=layers, hidden=hidden, pool=pool, kv_store_dtype=torch.bfloat16)
+    plain, _, _ = run_oracle(shape, mb, layers=layers, hidden=hidden, pool=pool0.clone())
+    got, row0 = [], 0
+    x_rows = hidden.double().tolist()
+    for s, (q, c) in enumerate(zip(q_lens, ctx_lens)):
+        rows = x_rows[row0:row0 + q]
+        for l in range(shape.num_layers):
+            w = {k: v.double().tolist() for k, v in layers[l].items()}
+            ck, cv = [], []
+            for j in range(c):
+                blk = int(mb.block_tables[s][j // 4])
+                ck.append(pool0[l, 0, blk, j % 4].tolist())
+                cv.append(pool0[l, 1, blk, j % 4].tolist())
+            rows = brute_force.layer_one_sequence_rounded_cache(shape, w, rows, list(range(c, c + q)), ck, cv)
+        got.extend(rows)
+        row0 += q
+    got = torch.tensor(got, dtype=F64)
+    assert torch.allclose(out, got, rtol=1e-10, atol=1e-11), float((out - got).abs().max())
+    assert float((out - plain).abs().max()) > 1e-5           # and it is not the unrounded reading
+    # the rounding helper of the scalar loops against literal bfloat16 facts: 1 + 2^-8 is a tie and goes to even
+    assert brute_force.round_to_bfloat16(1.0 + 2.0 ** -8) == 1.0
+    assert brute_force.round_to_bfloat16(1.0 + 3 * 2.0 ** -8) == 1.0 + 2.0 ** -6
+    assert brute_force.round_to_bfloat16(-0.3) == -0.30078125
+
+
+@pytest.mark.parametrize("chunks", [[5, 11, 16], [31, 1], [1] * 6 + [26]])
+def test_chunked_prefill_equals_unsplit_with_a_rounded_cache(chunks):
+    """Under the stored-value reading a later chunk and the writing chunk see the same keys and values, so a
+    prefill cut into chunks equals the unsplit one as closely as with the unrounded pool."""
+    shape = small_shape()
+    n = sum(chunks)
+    layers = draw_layers(shape, 7, "fan_in")
+    hidden = synth.draw_hidden(shape, n, seed=7)
+    mb = synth.make_microbatch([n], [0], seed=7)
+    full, _, pool_full = run_oracle(shape, mb, layers=layers, hidden=hidden, kv_store_dtype=torch.bfloat16)
+    pool = oracle.new_pool(oracle_shape(shape), mb.num_kv_blocks)
+    outs, done = [], 0
+    for c in chunks:
+        pos = torch.arange(done, done + c, dtype=torch.int32)
+        o, _ = oracle.stage_forward(oracle_shape(shape), layers, hidden[done:done + c], pos, [c], [done],
+                                    mb.block_tables, pool, kv_store_dtype=torch.bfloat16)
+        outs.append(o)
+        done += c
+    got = torch.cat(outs)
+    assert torch.allclose(got, full, rtol=1e-11, atol=1e-12)
+    used = synth.valid_slot_mask(mb, 16, include_new=True)
+    assert torch.equal(pool[:, :, used], pool_full[:, :, used])
+    # whereas under the unrounded reading a chunked run that stores bfloat16 between calls would differ from it
+    plain, _, _ = run_oracle(shape, mb, layers=layers, hidden=hidden)
+    assert float((plain - full).abs().max()) > 1e-6
 
 
 # ---------------------------------------------------------------- slots and pool writes
