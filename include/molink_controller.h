@@ -8,7 +8,7 @@
  * engine's controller therefore combines (1) the latency table every engine measured at start-up
  * (computation latency over micro-batch sizes) with (2) the monitored latency and bandwidth of every
  * link, caps the micro-batch size, and searches the micro-batch count N upwards from the smallest
- * admissible one, stopping when one more micro-batch no longer shortens the iteration.
+ * admissible one for as long as bubbles remain in which a further micro-batch's computation can hide.
  *
  * The model behind the search: all N micro-batches hold b = ceil(num_seqs / N) sequences; stage p
  * needs c_p(b) per micro-batch (linear interpolation in the profile, constant below its first point,
@@ -65,8 +65,11 @@ int mbc_evaluate(int32_t num_stages, const mbc_stage_profile *stages, const mbc_
 
 /*
  * The controller's choice: N runs upwards from ceil(num_seqs / max_batch_per_microbatch) (the cap on
- * the micro-batch size; <= 0 = no cap, N starts at 1) and the search stops at the first N for which
- * N + 1 does not shorten the iteration, or at min(max_microbatches, num_seqs).
+ * the micro-batch size; <= 0 = no cap, N starts at 1) for as long as bubbles remain at N, i.e. while
+ * N * max_p max(c_p, s_p) < round trip, and stops at the first N whose busiest stage or link has no idle
+ * time left, or at min(max_microbatches, num_seqs).  The choice is the visited N with the shortest modelled
+ * iteration, the smallest such N among equals (counts that give the same micro-batch size also give the same
+ * round trip, so a step from N to N + 1 alone says nothing while bubbles remain).
  */
 int mbc_choose(int32_t num_stages, const mbc_stage_profile *stages, const mbc_link *links, int32_t num_seqs,
                double activation_bytes_per_seq, double token_bytes_per_seq, int32_t max_batch_per_microbatch,

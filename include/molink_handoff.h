@@ -79,13 +79,16 @@ int handoff_sender_submit(handoff_sender *s, void *producer_stream, const void *
  * (HANDOFF_PREFILL) have finished. */
 int handoff_sender_wait(handoff_sender *s, int64_t ticket, int32_t kind);
 
-/* How many transfers the sender had chosen when it first saw the ticket complete (-1: not seen yet). */
+/* How many transfers the sender had chosen when it first saw the ticket complete (-1: not seen yet).
+ * The sender remembers the 4096 most recent tickets; an older, finished one is HANDOFF_ERR_ARG here and
+ * reads as complete in handoff_sender_wait. */
 int handoff_sender_visible_pick(handoff_sender *s, int64_t ticket, int64_t *out_pick);
 
 /* How many transfers the sender has chosen so far (its position in the order of transfers). */
 int handoff_sender_picks(handoff_sender *s, int64_t *out_picks);
 
-/* Copy out (and forget) the records of the transfers finished so far, in the order they were chosen. */
+/* Copy out (and forget) the records of the transfers finished so far, in the order they were chosen.
+ * The sender keeps at most the 65536 most recent records between two calls; older ones are dropped. */
 int handoff_sender_log(handoff_sender *s, handoff_record *out, int32_t capacity, int32_t *out_count);
 
 /* Finish the queued transfers, stop the worker, release the stream. */

@@ -258,8 +258,8 @@ int stage_head(stage_handle *st, void *hip_stream, int32_t num_tokens, const voi
                void *logits_out, int32_t *next_tokens);
 
 /*
- * Start-up profiling (paper section 4.1: "each engine measures computation latency across batch sizes and
- * sequence lengths" when it starts; the scheduler sizes its micro-batches from that table).  One point of
+ * Start-up profiling (paper section 4.1: every engine times its own stage over a grid of batch sizes and
+ * sequence lengths when it starts, and the scheduler sizes its micro-batches from that table).  One point of
  * the table: the stage's latency for a micro-batch of num_seqs sequences, each with q_len new tokens
  * (1 = decode, > 1 = a prefill chunk) after ctx_len cached ones.  Runs stage_forward on such a micro-batch
  * `warmup` times untimed and `iters` times timed (HIP events on hip_stream), synchronises, and writes

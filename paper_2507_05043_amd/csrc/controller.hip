@@ -94,14 +94,19 @@ int mbc_choose(int32_t num_stages, const mbc_stage_profile* stages, const mbc_li
   if (n > n_max)
     return fail(MBC_ERR_ARG, "%d sequences in micro-batches of at most %d need %d micro-batches, more than %d allowed",
                 num_seqs, max_batch_per_microbatch, n, n_max);
+  // The search goes on for as long as bubbles remain - the busiest stage or link still idles between micro-batches,
+  // N * busiest < round trip - because a further micro-batch's work can then be hidden in them.  Comparing N + 1
+  // with N alone would stall on the plateaus of ceil(num_seqs / N): from about sqrt(num_seqs) on, consecutive
+  // counts give the same micro-batch size and the same round trip while bubbles are still there.  Among the counts
+  // visited the shortest modelled iteration wins, the smallest count among equals.
   mbc_choice cur = evaluate(num_stages, stages, links, num_seqs, activation_bytes_per_seq, token_bytes_per_seq, n);
-  while (n < n_max) {
-    const mbc_choice next = evaluate(num_stages, stages, links, num_seqs, activation_bytes_per_seq, token_bytes_per_seq, n + 1);
-    if (!(next.period_ms < cur.period_ms)) break;   // one more micro-batch no longer shortens the iteration
-    cur = next;
+  mbc_choice best = cur;
+  while (n < n_max && cur.busiest_ms < cur.round_trip_ms) {
     ++n;
+    cur = evaluate(num_stages, stages, links, num_seqs, activation_bytes_per_seq, token_bytes_per_seq, n);
+    if (cur.period_ms < best.period_ms) best = cur;
   }
-  *out = cur;
+  *out = best;
   return MBC_OK;
 }
 

@@ -56,8 +56,15 @@ int split_payload(int32_t S, const int32_t* q_lens, int64_t row_bytes, int64_t c
   return HANDOFF_OK;
 }
 
+// A serving loop submits one payload per micro-batch for as long as it runs, so nothing here may grow with
+// the number of payloads: a ticket's event and transfer lists are released as soon as its transfers are in the
+// queues, finished tickets beyond the most recent kKeepTickets are forgotten (they read as complete), and the
+// log keeps the most recent kMaxLog records.
+constexpr size_t kKeepTickets = 4096;
+constexpr size_t kMaxLog = 1 << 16;
+
 struct Ticket {
-  hipEvent_t ready;
+  hipEvent_t ready;                     // nullptr once the ticket's transfers have been queued
   const char* dev;
   char* host;
   std::vector<Item> decode, prefill;
@@ -75,10 +82,11 @@ struct handoff_sender {
   std::thread worker;
   std::mutex mu;
   std::condition_variable cv_work, cv_done;
-  std::vector<Ticket> tickets;          // index = ticket id
-  size_t next_unqueued;                 // first ticket whose transfers are not in the queues yet
+  std::deque<Ticket> tickets;           // tickets first_id, first_id + 1, ...
+  int64_t first_id;                     // id of tickets.front(); older ones have completed and were forgotten
+  size_t next_unqueued;                 // index in `tickets` of the first one whose transfers are not queued yet
   std::deque<Item> decode_q, prefill_q;
-  std::vector<handoff_record> log;
+  std::deque<handoff_record> log;
   int64_t picks;
   bool stop, failed;
   char fail_msg[256];
@@ -98,9 +106,29 @@ struct handoff_sender {
       for (const Item& it : t.prefill) prefill_q.push_back(it);
       t.visible_pick = picks;
       t.queued = true;
+      (void)hipEventDestroy(t.ready);
+      t.ready = nullptr;
+      std::vector<Item>().swap(t.decode);
+      std::vector<Item>().swap(t.prefill);
       ++next_unqueued;
-      if (t.left_total == 0) cv_done.notify_all();
+      cv_done.notify_all();             // a waiter on a kind this payload has no transfers of is done now
     }
+  }
+
+  Ticket& ticket_of(int64_t id) { return tickets[(size_t)(id - first_id)]; }
+
+  // Forget finished tickets at the front beyond the ones kept for late queries.  Called with the lock held.
+  void retire_old() {
+    while (tickets.size() > kKeepTickets && next_unqueued > 0 && tickets.front().queued && tickets.front().left_total == 0) {
+      tickets.pop_front();
+      ++first_id;
+      --next_unqueued;
+    }
+  }
+
+  void record(const handoff_record& r) {
+    if (log.size() >= kMaxLog) log.pop_front();
+    log.push_back(r);
   }
 
   void run() {
@@ -127,7 +155,7 @@ struct handoff_sender {
       if (!decode_q.empty()) { it = decode_q.front(); decode_q.pop_front(); }
       else { it = prefill_q.front(); prefill_q.pop_front(); }
       const int64_t pick = picks++;
-      const Ticket& t = tickets[(size_t)it.ticket];
+      const Ticket& t = ticket_of(it.ticket);
       const char* src = t.dev + it.offset;
       char* dst = t.host + it.offset;
       lk.unlock();
@@ -137,10 +165,11 @@ struct handoff_sender {
       const double end = now_ms();
       lk.lock();
       if (e != hipSuccess) set_failed("device to host copy", e);
-      log.push_back(handoff_record{it.ticket, it.kind, 0, it.offset, it.bytes, pick, begin, end});
-      Ticket& tt = tickets[(size_t)it.ticket];
+      record(handoff_record{it.ticket, it.kind, 0, it.offset, it.bytes, pick, begin, end});
+      Ticket& tt = ticket_of(it.ticket);
       if (it.kind == HANDOFF_DECODE) --tt.left_decode;
       --tt.left_total;
+      retire_old();
       cv_done.notify_all();
       if (failed) drop_everything();
     }
@@ -155,7 +184,10 @@ struct handoff_sender {
   void drop_everything() {
     decode_q.clear();
     prefill_q.clear();
-    for (Ticket& t : tickets) { t.left_decode = 0; t.left_total = 0; t.queued = true; }
+    for (Ticket& t : tickets) {
+      t.left_decode = 0; t.left_total = 0; t.queued = true;
+      if (t.ready) { (void)hipEventDestroy(t.ready); t.ready = nullptr; }
+    }
     next_unqueued = tickets.size();
     cv_done.notify_all();
   }
@@ -196,6 +228,7 @@ int handoff_sender_create(int32_t device, int64_t chunk_bytes, handoff_sender** 
   s->device = device;
   s->chunk_bytes = chunk_bytes;
   s->next_unqueued = 0;
+  s->first_id = 0;
   s->picks = 0;
   s->stop = s->failed = false;
   s->fail_msg[0] = 0;
@@ -236,7 +269,7 @@ int handoff_sender_submit(handoff_sender* s, void* producer_stream, const void* 
       (void)hipEventDestroy(t.ready);
       return fail(HANDOFF_ERR_HIP, "the sender has failed: %s", s->fail_msg);
     }
-    const int64_t id = (int64_t)s->tickets.size();
+    const int64_t id = s->first_id + (int64_t)s->tickets.size();
     for (Item& it : t.decode) it.ticket = id;
     for (Item& it : t.prefill) it.ticket = id;
     s->tickets.push_back(std::move(t));
@@ -250,9 +283,11 @@ int handoff_sender_wait(handoff_sender* s, int64_t ticket, int32_t kind) {
   if (!s) return fail(HANDOFF_ERR_NULL, "sender is NULL");
   if (kind != HANDOFF_DECODE && kind != HANDOFF_PREFILL) return fail(HANDOFF_ERR_ARG, "unknown kind %d", kind);
   std::unique_lock<std::mutex> lk(s->mu);
-  if (ticket < 0 || ticket >= (int64_t)s->tickets.size()) return fail(HANDOFF_ERR_ARG, "unknown ticket %lld", (long long)ticket);
+  if (ticket < 0 || ticket >= s->first_id + (int64_t)s->tickets.size())
+    return fail(HANDOFF_ERR_ARG, "unknown ticket %lld", (long long)ticket);
   s->cv_done.wait(lk, [&] {
-    const Ticket& t = s->tickets[(size_t)ticket];
+    if (ticket < s->first_id) return true;          // finished long ago and forgotten
+    const Ticket& t = s->ticket_of(ticket);
     return t.queued && (kind == HANDOFF_DECODE ? t.left_decode == 0 : t.left_total == 0);
   });
   if (s->failed) return fail(HANDOFF_ERR_HIP, "%s", s->fail_msg);
@@ -262,8 +297,10 @@ int handoff_sender_wait(handoff_sender* s, int64_t ticket, int32_t kind) {
 int handoff_sender_visible_pick(handoff_sender* s, int64_t ticket, int64_t* out_pick) {
   if (!s || !out_pick) return fail(HANDOFF_ERR_NULL, "a required pointer is NULL");
   std::lock_guard<std::mutex> lk(s->mu);
-  if (ticket < 0 || ticket >= (int64_t)s->tickets.size()) return fail(HANDOFF_ERR_ARG, "unknown ticket %lld", (long long)ticket);
-  *out_pick = s->tickets[(size_t)ticket].visible_pick;
+  if (ticket < 0 || ticket >= s->first_id + (int64_t)s->tickets.size())
+    return fail(HANDOFF_ERR_ARG, "unknown ticket %lld", (long long)ticket);
+  if (ticket < s->first_id) return fail(HANDOFF_ERR_ARG, "ticket %lld finished too long ago to be remembered", (long long)ticket);
+  *out_pick = s->ticket_of(ticket).visible_pick;
   return HANDOFF_OK;
 }
 
@@ -294,7 +331,8 @@ void handoff_sender_destroy(handoff_sender* s) {
   s->cv_work.notify_all();
   if (s->worker.joinable()) s->worker.join();
   (void)hipSetDevice(s->device);
-  for (Ticket& t : s->tickets) (void)hipEventDestroy(t.ready);
+  for (Ticket& t : s->tickets)
+    if (t.ready) (void)hipEventDestroy(t.ready);
   (void)hipStreamDestroy(s->stream);
   delete s;
 }

@@ -61,19 +61,63 @@ def test_modelled_iteration_time_equals_the_simulation():
         assert got.period_ms == max(got.round_trip_ms, got.busiest_ms)
 
 
-def test_the_search_stops_where_the_simulation_says_one_more_micro_batch_stops_helping():
+def _resource_times(profiles, links, num_seqs, act_bytes, tok_bytes, n):
+    """Per micro-batch: how long every stage and every link is occupied (the simulation's inputs)."""
+    b = -(-num_seqs // n)
+    last = len(profiles) - 1
+    return [dict(p)[b] for p in profiles] + [(tok_bytes if i == last else act_bytes) * b / links[i][1]
+                                             for i in range(len(links))]
+
+
+def _expected_choice(profiles, links, num_seqs, act, tok, n0, n_max):
+    """The search read off the simulation: counts are visited upwards while the simulated pipeline still has
+    bubbles (its period exceeds what the busiest stage or link needs for its n micro-batches); the first
+    shortest simulated period among the visited counts wins."""
+    sim = {}
+    n = n0
+    while True:
+        sim[n] = _simulated(profiles, links, num_seqs, act, tok, n)
+        saturated = sim[n] <= n * max(_resource_times(profiles, links, num_seqs, act, tok, n)) * (1 + 1e-9)
+        if saturated or n >= n_max:
+            break
+        n += 1
+    best = min(sim.values())
+    return min(k for k, v in sim.items() if v <= best * (1 + 1e-9)), sim
+
+
+def test_the_search_runs_while_the_simulated_pipeline_has_bubbles():
     rng = random.Random(1)
     for _ in range(60):
         profiles, links, num_seqs, act, tok = _scenario(rng, rng.randint(2, 5))
         cap = rng.choice([0, 0, 8, 16])
-        n = max(1, -(-num_seqs // cap)) if cap else 1
-        sim = {k: _simulated(profiles, links, num_seqs, act, tok, k) for k in range(1, num_seqs + 1)}
-        while n < num_seqs and sim[n + 1] < sim[n] * (1 - 1e-9):
-            n += 1
+        n0 = max(1, -(-num_seqs // cap)) if cap else 1
+        want, sim = _expected_choice(profiles, links, num_seqs, act, tok, n0, num_seqs)
         got = C.choose(profiles, links, num_seqs, act, tok, max_batch_per_microbatch=cap)
-        assert got.num_microbatches == n, (got.num_microbatches, n, [round(sim[k], 3) for k in sorted(sim)])
+        assert got.num_microbatches == want, (got.num_microbatches, want, [round(sim[k], 3) for k in sorted(sim)])
+        assert got.period_ms == pytest.approx(sim[want], rel=1e-6)
         if cap:
             assert got.batch_per_microbatch <= cap
+
+
+def test_the_best_count_lies_past_a_plateau_of_equal_micro_batch_sizes():
+    """96 sequences over slow links: from 10 micro-batches on, consecutive counts share a micro-batch size
+    (ceil(96/10) == ceil(96/11) == 9 ... ) and with it the round trip, while the stages still idle.  A search
+    that compared N + 1 with N alone would stop at the first such pair; the shortest iteration of the whole
+    simulated range lies beyond it and is what the controller returns."""
+    num_seqs = 96
+    profiles = [[(b, 3.0 + 0.05 * b) for b in range(1, num_seqs + 1)]] * 4
+    links = [(40.0, 1.25e6)] * 4
+    act, tok = 16384.0, 4.0
+    sim = {k: _simulated(profiles, links, num_seqs, act, tok, k) for k in range(1, num_seqs + 1)}
+    best = min(sim.values())
+    first_best = min(k for k, v in sim.items() if v <= best * (1 + 1e-9))
+    plateau = next(k for k in range(1, num_seqs) if -(-num_seqs // k) == -(-num_seqs // (k + 1)))
+    assert first_best > plateau + 1, (first_best, plateau)
+    assert sim[plateau + 1] >= sim[plateau] * (1 - 1e-9)            # the step a pairwise search would stop at
+    got = C.choose(profiles, links, num_seqs, act, tok)
+    assert got.num_microbatches == first_best, (got.num_microbatches, first_best)
+    assert got.period_ms == pytest.approx(best, rel=1e-6)
+    assert got.period_ms < sim[plateau] * (1 - 1e-3)             # and it is shorter than where that search stops
 
 
 def test_interpolation_in_the_profile():
