@@ -195,8 +195,10 @@ int stage_init(const stage_config *cfg, const stage_layer_weights *layers, void 
  *   slot_mapping_out  host int64 [T] or NULL; receives, for every row, the pool slot
  *                     block_table[j/16]*16 + j%16 (j = ctx + offset in the chunk) its K/V is written to
  * Row i of a sequence attends to cached tokens 0..ctx-1 and to rows 0..i of its own chunk.
- * All metadata is validated on the host before anything is enqueued: on error nothing was
- * launched and the KV pool is unchanged.  The host arrays may be reused as soon as the call
+ * All metadata, and the fit of every kernel's scratch into the workspace, is checked on the host before
+ * anything is enqueued: on STAGE_ERR_NULL / BATCH / BLOCK_TABLE / ALIAS / SIZE nothing was launched and the
+ * KV pool is unchanged.  STAGE_ERR_HIP reports a failing HIP runtime call (a copy or a launch itself), which
+ * can come after earlier kernels of the call were enqueued.  The host arrays may be reused as soon as the call
  * returns.  The call does not synchronise; asynchronous HIP failures surface at the caller's
  * next synchronisation.  One handle must not be used from two threads at once, and calls on
  * one handle must be issued to streams that execute them in order (the workspace is shared).

@@ -109,7 +109,11 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(GemmAr
   // Load instruction j of this wave fills row group g = 4*j + wave.  This lane's slot in the group is
   // (row 8*g + lane/8, position lane%8) and receives the row's chunk (lane%8) ^ (lane/8).
   const int sw_chunk = (lane & 7) ^ (lane >> 3);
-  uint32_t g_off[NI];     // byte offset of this lane's chunk from the matrix base at k = 0
+  // Byte offset of this lane's chunk from the first row of the workgroup's tile at k = 0.  Offsets are taken from
+  // the tile's own first row (a 64-bit base per workgroup), so 32 bits hold them for any matrix size: a tile spans
+  // at most 256 rows.
+  uint32_t g_off[NI];
+  const int b_row0 = EPI == kEpiSwiGLU ? (n0 >> 6) * 32 : n0;   // first weight row of the tile (gate/up: per matrix)
 #pragma unroll
   for (int j = 0; j < NI; ++j) {
     const int g = NWAVES * j + wave;
@@ -117,7 +121,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(GemmAr
     if (r < AROWS) {
       int gm = m0 + (r < BM ? r : r - BM);         // the low plane has the same rows as the high plane
       gm = gm < p.m ? gm : p.m - 1;
-      g_off[j] = ((uint32_t)gm * (uint32_t)p.lda + sw_chunk * 8) * 2u;
+      g_off[j] = ((uint32_t)(gm - m0) * (uint32_t)p.lda + sw_chunk * 8) * 2u;
     } else {
       int row;
       if constexpr (EPI == kEpiSwiGLU) {
@@ -128,9 +132,10 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(GemmAr
         row = n0 + (r - AROWS);
       }
       row = row < p.n ? row : p.n - 1;
-      g_off[j] = ((uint32_t)row * (uint32_t)p.k + sw_chunk * 8) * 2u;
+      g_off[j] = ((uint32_t)(row - b_row0) * (uint32_t)p.k + sw_chunk * 8) * 2u;
     }
   }
+  const size_t a_tile0 = (size_t)m0 * p.lda, b_tile0 = (size_t)b_row0 * p.k;   // elements
 
   int zero_below[NSTAGE];   // per stage: leading k columns that repeat the previous tile (shifted last tile)
   auto fetch = [&](auto stage_c, int idx) {
@@ -143,10 +148,10 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(GemmAr
     const int k_last = p.k - kBK;
     zero_below[S] = k0 > k_last ? k0 - k_last : 0;
     k0 = k0 > k_last ? k_last : k0;
-    const char* abase = reinterpret_cast<const char*>(p.a + k0);
-    const char* alobase = SPLIT_A ? reinterpret_cast<const char*>(p.a_lo + k0) : abase;
-    const char* w0base = reinterpret_cast<const char*>(p.w0 + k0);
-    const char* w1base = EPI == kEpiSwiGLU ? reinterpret_cast<const char*>(p.w1 + k0) : w0base;
+    const char* abase = reinterpret_cast<const char*>(p.a + a_tile0 + k0);
+    const char* alobase = SPLIT_A ? reinterpret_cast<const char*>(p.a_lo + a_tile0 + k0) : abase;
+    const char* w0base = reinterpret_cast<const char*>(p.w0 + b_tile0 + k0);
+    const char* w1base = EPI == kEpiSwiGLU ? reinterpret_cast<const char*>(p.w1 + b_tile0 + k0) : w0base;
     char* stage = Lds::template get<S>();
 #pragma unroll
     for (int j = 0; j < NI; ++j) {

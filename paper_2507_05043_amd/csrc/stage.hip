@@ -354,24 +354,43 @@ int bind_weights(stage_handle* st, hipStream_t stream, GemmArgs& g, const void* 
 
 // The plan of a projection.  At most 64 rows: 4-bit weights in their stored form need the streaming kernel; half
 // activations run on the 64-row tiles (the bf16 streaming kernel takes e16 activations); otherwise the shape decides.
-GemmPlan plan_for(const GemmArgs& g, GemmEpilogue epi) {
-  const GemmFewRows few = g.q0.codes ? kFewRowsStreaming : (g.a_half ? kFewRowsTiles : kFewRowsByShape);
-  return plan_gemm(g.m, g.n, g.k, epi, kNumCus, g.a_lo != nullptr, few);
+GemmPlan plan_projection(const stage_config& c, int m, int n, int k, GemmEpilogue epi, bool two_planes, bool a_half) {
+  const bool stored_w4 = c.weight_bits == 4 && skinny_w4_supports(m, k, c.weight_group_size, two_planes);
+  const GemmFewRows few = stored_w4 ? kFewRowsStreaming : (a_half ? kFewRowsTiles : kFewRowsByShape);
+  return plan_gemm(m, n, k, epi, kNumCus, two_planes, few);
 }
 
+// The plans of a layer's four projections for one micro-batch; they depend on the shapes only, so they are made -
+// and checked against the workspace - once per call, before anything is enqueued.
+struct LayerPlans {
+  GemmPlan qkv, o, gateup, down, down_out;   // down_out: the last layer's down projection writing the payload
+};
+
 // The partial sums a plan writes must fit the scratch the workspace was laid out with.
-int check_plan(const stage_handle* st, const GemmArgs& g, const GemmPlan& plan) {
+int check_plan(const stage_handle* st, int m, const GemmPlan& plan) {
   if (!plan.partials) return STAGE_OK;
-  const size_t need = (size_t)plan.splits * g.m * plan.nv;
+  const size_t need = (size_t)plan.splits * m * plan.nv;
   if (need > st->ws.splitk_floats)
     return fail(STAGE_ERR_SIZE, "internal: a projection's plan needs %zu floats of split-K scratch, the workspace holds %zu",
                 need, st->ws.splitk_floats);
   return STAGE_OK;
 }
 
-int run_gemm(stage_handle* st, hipStream_t stream, int kernel_class, const GemmArgs& args, GemmEpilogue epi) {
-  const GemmPlan plan = plan_for(args, epi);
-  if (int rc = check_plan(st, args, plan)) return rc;
+int plan_layer(const stage_handle* st, int T, bool qkv_two_planes, bool two_planes, bool a_half, LayerPlans* out) {
+  const stage_config& c = st->cfg;
+  const Dims& d = st->dim;
+  out->qkv = plan_projection(c, T, d.qkv_out, d.H, kEpiStoreF32, qkv_two_planes, a_half);
+  out->o = plan_projection(c, T, d.H, d.nq * d.d, kEpiResidualF32, two_planes, a_half);
+  out->gateup = plan_projection(c, T, d.F, d.H, kEpiSwiGLU, two_planes, a_half);
+  out->down = plan_projection(c, T, d.H, d.F, kEpiResidualF32, two_planes, a_half);
+  out->down_out = plan_projection(c, T, d.H, d.F, kEpiResidualOut, two_planes, a_half);
+  for (const GemmPlan* p : {&out->qkv, &out->o, &out->gateup, &out->down, &out->down_out})
+    if (int rc = check_plan(st, T, *p)) return rc;
+  return STAGE_OK;
+}
+
+int run_gemm(stage_handle* st, hipStream_t stream, int kernel_class, const GemmArgs& args, GemmEpilogue epi,
+             const GemmPlan& plan) {
   {
     Timer t(st, stream, kernel_class);
     HIP_TRY(launch_gemm_main(args, epi, plan, stream));
@@ -387,9 +406,7 @@ int run_gemm(stage_handle* st, hipStream_t stream, int kernel_class, const GemmA
 // an RMSNorm into `norm_out` (gain != nullptr), or nothing.  When the GEMM splits K across workgroups
 // the sum of the partial results, the residual add and the norm run as one kernel.
 int run_residual_gemm(stage_handle* st, hipStream_t stream, int kernel_class, const GemmArgs& args, GemmEpilogue epi,
-                      const e16* gain, e16* norm_out, e16* norm_out_lo, bool norm_out_half) {
-  const GemmPlan plan = plan_for(args, epi);
-  if (int rc = check_plan(st, args, plan)) return rc;
+                      const GemmPlan& plan, const e16* gain, e16* norm_out, e16* norm_out_lo, bool norm_out_half) {
   {
     Timer t(st, stream, kernel_class);
     HIP_TRY(launch_gemm_main(args, epi, plan, stream));
@@ -439,6 +456,8 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
   const int64_t total_blocks = bc.total_blocks, decode_keys = bc.decode_keys;
   const int n_decode = bc.n_decode, n_tiles = bc.n_tiles;
 
+  const WorkspaceLayout& wl = st->ws;
+
   // key-range length of the decode work items: aim at a fixed number of items, never below the minimum
   int range = kMinDecodeRange;
   if (n_decode) {
@@ -450,8 +469,15 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
   int n_items = 0;
   for (int s = 0; s < S; ++s)
     if (q_lens[s] == 1) n_items += (ctx_lens[s] + 1 + range - 1) / range;
-  if (n_items > st->ws.max_items || n_tiles > st->ws.max_tiles)
+  if (n_items > wl.max_items || n_tiles > wl.max_tiles)
     return fail(STAGE_ERR_BATCH, "internal: work list larger than planned (%d items, %d tiles)", n_items, n_tiles);
+
+  // the projections' plans (they depend on the shapes only) and their fit into the workspace
+  const bool two_plane = two_plane_of(c);
+  const bool half_act = half_act_of(c);                // GEMM inputs as IEEE half bits (bfloat16 library)
+  const bool qkv_lo = half_act && qkv_lo_of(c, n_tiles > 0);
+  LayerPlans plans;
+  if (int rc = plan_layer(st, T, two_plane || qkv_lo, two_plane, half_act, &plans)) return rc;
 
   HIP_TRY(hipSetDevice(st->device));
   hipStream_t stream = (hipStream_t)hip_stream;
@@ -467,7 +493,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
   const size_t o_items = take((size_t)n_items * sizeof(DecodeItem));
   const size_t o_dtok = take((size_t)n_decode * sizeof(DecodeToken));
   const size_t o_tiles = take((size_t)n_tiles * sizeof(PrefillTile));
-  if (off > st->ws.meta_bytes) return fail(STAGE_ERR_BATCH, "internal: metadata larger than planned");
+  if (off > wl.meta_bytes) return fail(STAGE_ERR_BATCH, "internal: metadata larger than planned");
   int32_t* h_pos = (int32_t*)(blob + o_pos);
   int64_t* h_slots = (int64_t*)(blob + o_slots);
   int32_t* h_bt = (int32_t*)(blob + o_bt);
@@ -523,29 +549,26 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
 
   // ---- enqueue
   char* ws = st->workspace;
-  char* meta = ws + st->ws.meta;
+  char* meta = ws + wl.meta;
   HIP_TRY(hipMemcpyAsync(meta, blob, off, hipMemcpyHostToDevice, stream));
   HIP_TRY(hipEventRecord(st->staging_done[slot_id], stream));
   st->staging_used[slot_id] = true;
 
-  float* x = (float*)(ws + st->ws.x);
-  e16* a = (e16*)(ws + st->ws.a);
-  const bool two_plane = two_plane_of(c);
-  const bool half_act = half_act_of(c);                // GEMM inputs as IEEE half bits (bfloat16 library)
-  const bool qkv_lo = half_act && qkv_lo_of(c, n_tiles > 0);
-  e16* a_lo = two_plane ? (e16*)(ws + st->ws.a_lo) : nullptr;
-  e16* norm1_lo = (two_plane || qkv_lo) ? (e16*)(ws + st->ws.a_lo) : nullptr;   // second plane of the first norm's output
-  e16* mlp_lo = two_plane ? (e16*)(ws + st->ws.mlp_lo) : nullptr;
-  e16* q_lo = (two_plane || half_act) ? (e16*)(ws + st->ws.q_lo) : nullptr;
-  e16* attn_lo = two_plane ? (e16*)(ws + st->ws.attn_lo) : nullptr;
-  float* qkv_f32 = (float*)(ws + st->ws.qkv_f32);
-  e16* qkv = (e16*)(ws + st->ws.qkv);
-  e16* attn = (e16*)(ws + st->ws.attn);
-  e16* mlp = (e16*)(ws + st->ws.mlp);
-  float2* cos_sin = (float2*)(ws + st->ws.cos_sin);
-  float* splitk = (float*)(ws + st->ws.splitk);
-  float* part_o = (float*)(ws + st->ws.part_o);
-  float2* part_ml = (float2*)(ws + st->ws.part_ml);
+  float* x = (float*)(ws + wl.x);
+  e16* a = (e16*)(ws + wl.a);
+  e16* a_lo = two_plane ? (e16*)(ws + wl.a_lo) : nullptr;
+  e16* norm1_lo = (two_plane || qkv_lo) ? (e16*)(ws + wl.a_lo) : nullptr;   // second plane of the first norm's output
+  e16* mlp_lo = two_plane ? (e16*)(ws + wl.mlp_lo) : nullptr;
+  e16* q_lo = (two_plane || half_act) ? (e16*)(ws + wl.q_lo) : nullptr;
+  e16* attn_lo = two_plane ? (e16*)(ws + wl.attn_lo) : nullptr;
+  float* qkv_f32 = (float*)(ws + wl.qkv_f32);
+  e16* qkv = (e16*)(ws + wl.qkv);
+  e16* attn = (e16*)(ws + wl.attn);
+  e16* mlp = (e16*)(ws + wl.mlp);
+  float2* cos_sin = (float2*)(ws + wl.cos_sin);
+  float* splitk = (float*)(ws + wl.splitk);
+  float* part_o = (float*)(ws + wl.part_o);
+  float2* part_ml = (float2*)(ws + wl.part_ml);
   const int32_t* d_pos = (const int32_t*)(meta + o_pos);
   const int64_t* d_slots = (const int64_t*)(meta + o_slots);
   const int32_t* d_bt = (const int32_t*)(meta + o_bt);
@@ -578,8 +601,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       g.m = T; g.n = d.qkv_out; g.k = d.H; g.lda = d.H; g.ldo = d.qkv_out;
       if (int rc = bind_weights(st, stream, g, w.wqkv, w.sqkv, w.zqkv, nullptr, nullptr, nullptr)) return rc;
       // the rotation kernel adds the split-K partial sums itself: no separate reduction pass
-      const GemmPlan plan = plan_for(g, kEpiStoreF32);
-      if (int rc = check_plan(st, g, plan)) return rc;
+      const GemmPlan& plan = plans.qkv;
       {
         Timer t(st, stream, STAGE_K_GEMM_QKV);
         HIP_TRY(launch_gemm_main(g, kEpiStoreF32, plan, stream));
@@ -612,7 +634,8 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       g.a = attn; g.a_lo = attn_lo; g.a_half = half_act; g.resid = x; g.partial = splitk;
       g.m = T; g.n = d.H; g.k = d.nq * d.d; g.lda = d.nq * d.d; g.ldo = d.H;
       if (int rc = bind_weights(st, stream, g, w.wo, w.so, w.zo, nullptr, nullptr, nullptr)) return rc;
-      int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_O, g, kEpiResidualF32, (const e16*)w.norm2, a, a_lo, half_act);
+      int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_O, g, kEpiResidualF32, plans.o, (const e16*)w.norm2, a, a_lo,
+                                 half_act);
       if (rc) return rc;
     }
     if (tap && taps->tap_h)
@@ -623,7 +646,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       g.partial = splitk;
       g.m = T; g.n = d.F; g.k = d.H; g.lda = d.H; g.ldo = d.F;
       if (int rc = bind_weights(st, stream, g, w.wgate, w.sgate, w.zgate, w.wup, w.sup, w.zup)) return rc;
-      int rc = run_gemm(st, stream, STAGE_K_GEMM_GATEUP, g, kEpiSwiGLU);
+      int rc = run_gemm(st, stream, STAGE_K_GEMM_GATEUP, g, kEpiSwiGLU, plans.gateup);
       if (rc) return rc;
     }
     if (tap && taps->tap_mlp) HIP_TRY(copy_activation_tap(taps->tap_mlp, mlp, (size_t)T * d.F, half_act, stream));
@@ -638,7 +661,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       if (int rc = bind_weights(st, stream, g, w.wdown, w.sdown, w.zdown, nullptr, nullptr, nullptr)) return rc;
       const e16* next_gain = last ? nullptr : (const e16*)st->layers[l + 1].norm1;
       int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_DOWN, g, fused_out ? kEpiResidualOut : kEpiResidualF32,
-                                 next_gain, a, norm1_lo, half_act);
+                                 fused_out ? plans.down_out : plans.down, next_gain, a, norm1_lo, half_act);
       if (rc) return rc;
       if (tap && taps->tap_x)
         HIP_TRY(hipMemcpyAsync(taps->tap_x, x, (size_t)T * d.H * 4, hipMemcpyDeviceToDevice, stream));
@@ -885,6 +908,8 @@ int stage_head(stage_handle* st, void* hip_stream, int32_t num_tokens, const voi
   }
   if (sum_q != num_tokens)
     return fail(STAGE_ERR_BATCH, "sum(q_lens) = %lld != num_tokens = %d", (long long)sum_q, num_tokens);
+  const GemmPlan plan = plan_gemm(num_seqs, vocab, d.H, kEpiStoreF32, kNumCus, false);
+  if (int rc2 = check_plan(st, num_seqs, plan)) return rc2;
   HIP_TRY(hipSetDevice(st->device));
   hipStream_t stream = (hipStream_t)hip_stream;
   char* ws = st->workspace;
@@ -900,8 +925,6 @@ int stage_head(stage_handle* st, void* hip_stream, int32_t num_tokens, const voi
   GemmArgs g{};
   g.a = head_a; g.w0 = (const e16*)lm_head; g.partial = (float*)(ws + st->ws.splitk);
   g.m = num_seqs; g.n = vocab; g.k = d.H; g.lda = d.H; g.ldo = vocab;
-  const GemmPlan plan = plan_gemm(g.m, g.n, g.k, kEpiStoreF32, kNumCus, false);
-  if (int rc2 = check_plan(st, g, plan)) return rc2;
   // without partial sums the GEMM writes the logits itself (to the caller's buffer if there is one)
   float* direct = logits_out ? (float*)logits_out : (float*)(ws + st->ws.head_logits);
   g.out_f32 = direct;
