@@ -210,6 +210,27 @@ int stage_forward(stage_handle *st, void *hip_stream, int32_t num_tokens, const 
                   int64_t *slot_mapping_out);
 
 /*
+ * stage_forward for callers that cannot allocate device memory and so cannot bring a workspace sized for
+ * the stage's capacities: code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same result (bit for bit) and same errors as stage_forward, but every
+ * intermediate of the call - activations between kernels, split-K and split-KV partial results, the per-call
+ * metadata - lives in a scratch array of STAGE_STATIC_SCRATCH_BYTES that is part of the library's device
+ * image (each GPU the library runs on holds one copy until the process ends); the workspace given to
+ * stage_init is not touched.  The array is carved for exactly this micro-batch (num_tokens rows, num_seqs
+ * sequences); a micro-batch that needs more is rejected with STAGE_ERR_SIZE before anything is enqueued.
+ * The call allocates nothing, on the device or through the HIP runtime (no hipMalloc, hipFree, event or
+ * stream creation; per-kernel timing is off for the call), and nothing in the array has to start at zero:
+ * every buffer carved from it is written by the call before it is read.  All calls on one GPU, from any
+ * handle, share that GPU's array: calls that overlap on one GPU race; issue them to streams that run them
+ * in order.  Additional error: STAGE_ERR_SIZE.
+ */
+#define STAGE_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+int stage_forward_static(stage_handle *st, void *hip_stream, int32_t num_tokens, const void *hidden_in,
+                         const int32_t *positions, int32_t num_seqs, const int32_t *q_lens,
+                         const int32_t *ctx_lens, const int32_t *block_tables, void *hidden_out,
+                         int64_t *slot_mapping_out);
+
+/*
  * Debug taps (for parity tests).  Same as stage_forward, and additionally copies, for layer
  * tap_layer, intermediate tensors into caller device buffers (any may be NULL to skip):
  *   tap_norm1 bf16 [T][H]            RMSNorm output a

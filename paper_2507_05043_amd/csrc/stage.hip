@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -19,6 +20,13 @@
 #include "w4.hpp"
 
 using namespace molink;
+
+// Scratch of stage_forward_static: the workspace of callers that cannot bring one.  One copy per GPU the library
+// runs on, held until the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress;
+// the device address of each GPU's copy is looked up once per device (static_scratch_of) and kernels only ever
+// see that pointer.
+static constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -40,6 +48,24 @@ int fail(int code, const char* fmt, ...) {
 
 constexpr size_t kAlign = 256;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+char* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of this device's copy of `scratch`; `device` must be the current device.
+int static_scratch_of(int device, char** out) {
+  if (device < 0 || device >= kMaxDevices) return fail(STAGE_ERR_CONFIG, "device %d: at most %d devices are supported", device, kMaxDevices);
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[device]) {
+    void* ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr || (uintptr_t)ptr % kAlign) return fail(STAGE_ERR_HIP, "the static scratch array has no usable device address");
+    g_scratch_ptr[device] = (char*)ptr;
+  }
+  *out = g_scratch_ptr[device];
+  return STAGE_OK;
+}
 
 constexpr int kStagingSlots = 4;
 constexpr int kMaxTimed = 8192;
@@ -264,6 +290,10 @@ struct stage_handle {
   std::vector<stage_layer_weights> layers;
   char* kv_pool;
   char* workspace;
+  char* static_scratch;                 // this device's copy of the library's static scratch array
+  // workspace and layout of the call being enqueued (the handle's own, or the static scratch carved for the call)
+  char* call_ws;
+  const WorkspaceLayout* call_layout;
   int device;
   // pinned staging ring for the per-call metadata
   char* staging[kStagingSlots];
@@ -339,7 +369,7 @@ int bind_weights(stage_handle* st, hipStream_t stream, GemmArgs& g, const void* 
     if (w1) g.q1 = W4Matrix{(const uint32_t*)w1, (const e16*)s1, (const e16*)z1};
     return STAGE_OK;
   }
-  e16* exp0 = (e16*)(st->workspace + st->ws.wexp);
+  e16* exp0 = (e16*)(st->call_ws + st->call_layout->wexp);
   Timer t(st, stream, STAGE_K_DEQUANT);
   HIP_TRY(launch_dequant_w4(m0, g.n, g.k, st->cfg.weight_group_size, exp0, stream));
   g.w0 = exp0;
@@ -370,9 +400,9 @@ struct LayerPlans {
 int check_plan(const stage_handle* st, int m, const GemmPlan& plan) {
   if (!plan.partials) return STAGE_OK;
   const size_t need = (size_t)plan.splits * m * plan.nv;
-  if (need > st->ws.splitk_floats)
+  if (need > st->call_layout->splitk_floats)
     return fail(STAGE_ERR_SIZE, "internal: a projection's plan needs %zu floats of split-K scratch, the workspace holds %zu",
-                need, st->ws.splitk_floats);
+                need, st->call_layout->splitk_floats);
   return STAGE_OK;
 }
 
@@ -432,10 +462,15 @@ int run_residual_gemm(stage_handle* st, hipStream_t stream, int kernel_class, co
 
 int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidden_in, const int32_t* positions,
                  int32_t S, const int32_t* q_lens, const int32_t* ctx_lens, const int32_t* block_tables,
-                 void* hidden_out, int64_t* slot_mapping_out, const stage_taps* taps) {
+                 void* hidden_out, int64_t* slot_mapping_out, const stage_taps* taps, bool use_static_scratch = false) {
   if (!st) return fail(STAGE_ERR_NULL, "stage handle is NULL");
   if (!hidden_in || !positions || !q_lens || !ctx_lens || !block_tables || !hidden_out)
     return fail(STAGE_ERR_NULL, "a required argument of stage_forward is NULL");
+  // whatever workspace this call uses, the handle points at its own again when the call returns
+  struct CallWorkspaceReset {
+    stage_handle* st;
+    ~CallWorkspaceReset() { st->call_ws = st->workspace; st->call_layout = &st->ws; }
+  } reset_call_workspace{st};
   const stage_config& c = st->cfg;
   const Dims& d = st->dim;
   if (taps && (taps->tap_layer < 0 || taps->tap_layer >= d.L))
@@ -456,7 +491,24 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
   const int64_t total_blocks = bc.total_blocks, decode_keys = bc.decode_keys;
   const int n_decode = bc.n_decode, n_tiles = bc.n_tiles;
 
-  const WorkspaceLayout& wl = st->ws;
+  // ---- the workspace of this call: the handle's, or the static scratch carved for exactly this micro-batch
+  WorkspaceLayout carved;
+  st->call_ws = st->workspace;
+  st->call_layout = &st->ws;
+  if (use_static_scratch) {
+    stage_config rc = c;
+    rc.max_tokens = T;
+    rc.max_seqs = S;
+    rc.vocab_size = 0;
+    carved = layout_of(rc);
+    if (carved.total > kStaticScratchBytes)
+      return fail(STAGE_ERR_SIZE, "this micro-batch needs %zu bytes of scratch; the static scratch holds %zu", carved.total,
+                  kStaticScratchBytes);
+    if (carved.meta_bytes > st->ws.meta_bytes) return fail(STAGE_ERR_SIZE, "internal: metadata staging too small");
+    st->call_ws = st->static_scratch;
+    st->call_layout = &carved;
+  }
+  const WorkspaceLayout& wl = *st->call_layout;
 
   // key-range length of the decode work items: aim at a fixed number of items, never below the minimum
   int range = kMinDecodeRange;
@@ -548,7 +600,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
   if (slot_mapping_out) memcpy(slot_mapping_out, h_slots, (size_t)T * 8);
 
   // ---- enqueue
-  char* ws = st->workspace;
+  char* ws = st->call_ws;
   char* meta = ws + wl.meta;
   HIP_TRY(hipMemcpyAsync(meta, blob, off, hipMemcpyHostToDevice, stream));
   HIP_TRY(hipEventRecord(st->staging_done[slot_id], stream));
@@ -770,6 +822,9 @@ int stage_init(const stage_config* cfg, const stage_layer_weights* layers, void*
   st->layers.assign(layers, layers + cfg->num_layers);
   st->kv_pool = (char*)kv_pool;
   st->workspace = (char*)workspace;
+  st->static_scratch = nullptr;
+  st->call_ws = (char*)workspace;
+  st->call_layout = &st->ws;
   st->device = device;
   st->next_slot = 0;
   st->profile_mask = 0;
@@ -782,8 +837,25 @@ int stage_init(const stage_config* cfg, const stage_layer_weights* layers, void*
       return fail(STAGE_ERR_HIP, "allocating pinned staging: %s", hipGetErrorString(e));
     }
   }
+  if (int rc2 = static_scratch_of(device, &st->static_scratch)) {
+    stage_destroy(st);
+    return rc2;
+  }
   *out = st;
   return STAGE_OK;
+}
+
+int stage_forward_static(stage_handle* st, void* hip_stream, int32_t num_tokens, const void* hidden_in,
+                         const int32_t* positions, int32_t num_seqs, const int32_t* q_lens, const int32_t* ctx_lens,
+                         const int32_t* block_tables, void* hidden_out, int64_t* slot_mapping_out) {
+  if (!st) return fail(STAGE_ERR_NULL, "stage handle is NULL");
+  // per-kernel timing creates events on demand; this entry point creates nothing
+  const uint32_t mask = st->profile_mask;
+  st->profile_mask = 0;
+  const int rc = forward_impl(st, hip_stream, num_tokens, hidden_in, positions, num_seqs, q_lens, ctx_lens, block_tables,
+                              hidden_out, slot_mapping_out, nullptr, true);
+  st->profile_mask = mask;
+  return rc;
 }
 
 int stage_forward(stage_handle* st, void* hip_stream, int32_t num_tokens, const void* hidden_in,

@@ -85,6 +85,7 @@ def load_library(dtype: torch.dtype = torch.bfloat16) -> ctypes.CDLL:
     fwd = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, i32p, ctypes.c_int32, i32p, i32p,
            i32p, ctypes.c_void_p, i64p]
     lib.stage_forward.argtypes = fwd
+    lib.stage_forward_static.argtypes = fwd
     lib.stage_forward_taps.argtypes = fwd + [ctypes.POINTER(StageTaps)]
     lib.stage_embed.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, i32p,
                                 ctypes.c_void_p]
@@ -100,7 +101,7 @@ def load_library(dtype: torch.dtype = torch.bfloat16) -> ctypes.CDLL:
     lib.stage_destroy.restype = None
     lib.stage_last_error.restype = ctypes.c_char_p
     for name in ("stage_kv_layer_bytes", "stage_kv_element_offset", "stage_check_batch", "stage_workspace_bytes",
-                 "stage_init", "stage_forward", "stage_forward_taps", "stage_profile", "stage_profile_enable",
+                 "stage_init", "stage_forward", "stage_forward_static", "stage_forward_taps", "stage_profile", "stage_profile_enable",
                  "stage_profile_read", "stage_embed", "stage_head"):
         getattr(lib, name).restype = ctypes.c_int
     lib.stage_elem_type.restype = ctypes.c_int32
@@ -265,7 +266,9 @@ class Stage:
 
     # ---- the forward pass
     def forward(self, hidden: torch.Tensor, positions, q_lens, ctx_lens, block_tables, *,
-                out: Optional[torch.Tensor] = None, want_slots: bool = False, taps_layer: Optional[int] = None):
+                out: Optional[torch.Tensor] = None, want_slots: bool = False, taps_layer: Optional[int] = None,
+                static_scratch: bool = False):
+        """static_scratch: call stage_forward_static (the library's own scratch array instead of the workspace)."""
         lib = self._lib
         c = self.cfg
         t = hidden.shape[0]
@@ -283,7 +286,11 @@ class Stage:
         args = [self._handle, ctypes.c_void_p(stream), t, hidden.data_ptr(), pos_p, q_t.numel(), q_p, c_p, b_p,
                 out.data_ptr(), slots_p]
         taps = None
-        if taps_layer is None:
+        if static_scratch:
+            if taps_layer is not None:
+                raise ValueError("the static-scratch entry point has no taps")
+            self._check(lib.stage_forward_static(*args))
+        elif taps_layer is None:
             self._check(lib.stage_forward(*args))
         else:
             qkv_out = (c.num_q_heads + 2 * c.num_kv_heads) * c.head_dim
