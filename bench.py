@@ -2,10 +2,13 @@
 """Benchmark of one pipeline stage's forward pass on one MI355X.
 
 A step is one stage_forward (all layers, every kernel of the path) over one seeded synthetic
-micro-batch whose inputs are already resident in HBM.  Default workload: the Llama-2-7B-shaped stage
-(8 of 32 layers) on a pure-decode micro-batch of 64 sequences with contexts in [512, 2048].
-Prints one JSON line: stage tokens/s, latency per micro-batch, the roofline of the dominant kernel
-measured with HIP events on the launch stream, and the CPU oracle timed on a bounded sample.
+micro-batch whose inputs are already resident in HBM.  Headline workload: the largest single-GPU
+configuration, the Llama-3-70B-shaped stage (20 of 80 layers) on a pure-decode micro-batch of 256
+sequences with contexts in [1024, 8192].  Prints one JSON line: stage tokens/s, latency per micro-batch,
+the roofline of the dominant kernel measured with HIP events on the launch stream, the CPU oracle
+timed on a bounded sample, and - unless a single workload was asked for - one entry per other
+configuration (Llama-2-7B-shaped decode, Qwen2-7B-shaped mixed, token-budget sweep) with its own
+latency and roofline line.
 """
 import argparse
 import json
@@ -27,6 +30,9 @@ MEASURED_TRAFFIC = {
 
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+HEADLINE = "llama3-70b"
+# (workload, sweep budget) of the per-configuration entries; the headline's own entry is the headline run itself
+PER_CONFIG = [("llama2-7b", None), ("qwen2-7b", None), ("llama3-70b", None), ("sweep", 64), ("sweep", 256), ("sweep", 2048)]
 
 
 def algorithmic_work(shape, mb, weight_bytes_per_param=2.0):
@@ -80,16 +86,141 @@ def cpu_baseline(shape, mb, seed, sample_seqs):
                          sub.block_tables, pool, dtype=torch.float32)
     dt = time.perf_counter() - t0
     return {"value": sub.num_tokens / dt, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
-            "sample": f"{len(seqs)} of {mb.num_seqs} sequences ({sub.num_tokens} tokens) at full depth, fp32, "
-                      f"{dt:.1f} s"}
+            "sample": f"{len(seqs)} of {mb.num_seqs} sequences ({sub.num_tokens} tokens) of the {shape.name} workload at "
+                      f"full depth, fp32, {dt:.1f} s"}
+
+
+def run_workload(args, workload, budget, steps, warmup, extras):
+    """Time `steps` forward passes of one workload; returns the result fields of that workload."""
+    import torch
+    from paper_2507_05043_amd import KERNEL_CLASSES, synth
+    from paper_2507_05043_amd import stage as _stage
+    from paper_2507_05043_amd.harness import make_stage
+
+    shape, mb = synth.workload(workload, seed=args.seed, budget=budget or 256)
+    w4 = args.weights == "w4"
+    elem = torch.float16 if args.dtype == "f16" else torch.bfloat16
+    # 4 bits per weight plus a bf16 scale and a bf16 zero point per 128 weights
+    work = algorithmic_work(shape, mb, 0.5 + 4.0 / 128 if w4 else 2.0)
+    kv_bytes = shape.num_layers * mb.num_kv_blocks * 16 * 4 * shape.num_kv_heads * shape.head_dim
+    alias = kv_bytes + work["weight_bytes_per_layer"] * shape.num_layers > 250e9     # timing only: layers share one pool
+    want_ends = extras and args.ends
+    st = make_stage(shape, mb, args.seed, alias_layers=alias, vocab_size=shape.vocab if want_ends else 0,
+                    qkv_bias=workload == "qwen2-7b",     # the Qwen2 family has a q/k/v bias
+                    weight_group_size=128 if w4 else 0, dtype=elem)
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=args.seed, device="cuda:0", dtype=elem)
+    out = torch.empty_like(hidden)
+    n_dec = sum(1 for q in mb.q_lens if q == 1)
+    decode_bound = work["decode_attn_bytes_per_layer"] / (HBM_PEAK_GBS * 1e9) >= \
+        (work["gemm_flops_per_layer"] + work["attn_flops_per_layer"]) / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    dominant = "attn_decode" if (n_dec and decode_bound) else "gemm_gateup"
+
+    def step():
+        st.forward(hidden, mb.positions, mb.q_lens, mb.ctx_lens, mb.block_tables, out=out)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    st.profile_enable([dominant])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    dom_ms, dom_n = st.profile_read(dominant)
+    st.profile_enable([])
+    ms_per_step = elapsed / steps * 1e3
+    tokens_per_s = mb.num_tokens * steps / elapsed
+
+    avg_ms = dom_ms / max(dom_n, 1)
+    if dominant == "attn_decode":
+        achieved = work["decode_attn_bytes_per_layer"] / (avg_ms * 1e-3) / 1e9
+        roofline = {"kernel": _stage.stage_kernel_name(KERNEL_CLASSES[dominant]), "bound": "hbm",
+                    "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBS, 4),
+                    "traffic": measured_traffic(dominant, workload, args.seed) if args.dtype == "bf16" and not w4 else None,
+                    "avg_launch_ms": round(avg_ms, 5), "launches": dom_n,
+                    "algorithmic_bytes_per_launch": work["decode_attn_bytes_per_layer"]}
+    else:
+        flops = 2 * (2 * shape.hidden * shape.ffn) * mb.num_tokens
+        achieved = flops / (avg_ms * 1e-3) / 1e12
+        roofline = {"kernel": _stage.stage_kernel_name(KERNEL_CLASSES[dominant]), "bound": "mfma",
+                    "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                    "avg_launch_ms": round(avg_ms, 5), "launches": dom_n, "flops_per_launch": flops}
+
+    # what the library does by itself by depth (see stage_config.activation_planes)
+    if args.dtype != "bf16" or shape.num_layers < 5:
+        inputs = args.dtype
+    else:
+        inputs = "IEEE half, bf16 weights converted in the GEMMs"
+    tag = f"sweep budget {budget}: " if workload == "sweep" else ""
+    result = {
+        "value": round(tokens_per_s, 1), "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 4),
+        "config": {"workload": f"{tag}{shape.name}: L={shape.num_layers} H={shape.hidden} nq={shape.num_q_heads} "
+                               f"nkv={shape.num_kv_heads} d={shape.head_dim} F={shape.ffn}; micro-batch T={mb.num_tokens} "
+                               f"S={mb.num_seqs} ({mb.num_seqs - n_dec} prefill chunks, {n_dec} decode tokens), KV block 16",
+                   "seed": args.seed, "kv_layers_aliased": bool(alias), "projection_inputs": inputs,
+                   "weights": f"4-bit codes, {args.dtype} scale and zero point per 128 input features" if w4 else args.dtype},
+        "stage_latency_ms": round(ms_per_step, 4),
+        "ideal_ms": {"hbm": round(work["bytes_per_call"] / (HBM_PEAK_GBS * 1e9) * 1e3, 4),
+                     "mfma": round(work["flops_per_call"] / (MFMA_BF16_PEAK_TFLOPS * 1e12) * 1e3, 4)},
+        "roofline": roofline,
+    }
+
+    if extras and args.breakdown:
+        names = list(KERNEL_CLASSES)
+        st.profile_enable(names)
+        reps = max(3, min(steps, 10))
+        for _ in range(reps):
+            step()
+        torch.cuda.synchronize()
+        result["breakdown_ms_per_step"] = {n: round(st.profile_read(n)[0] / reps, 5) for n in names}
+        st.profile_enable([])
+        proj_ms = sum(result["breakdown_ms_per_step"][n] for n in ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down", "dequant"))
+        result["projections"] = {"ms_per_step": round(proj_ms, 5),
+                                 "weight_bytes_per_step": work["weight_bytes_per_layer"] * shape.num_layers,
+                                 "weight_stream_GBps": round(work["weight_bytes_per_layer"] * shape.num_layers / (proj_ms * 1e-3) / 1e9, 1)}
+
+    if want_ends:
+        # The pipeline's two ends, timed on their own after the stage (not part of `value`): token
+        # embedding of the micro-batch and final norm + vocabulary projection + greedy choice.
+        ends = synth.draw_ends_weights(shape, seed=args.seed, device="cuda:0", dtype=elem)
+        ids = synth.draw_token_ids(shape, mb.num_tokens, seed=args.seed)
+        names = ["embed", "head_norm", "gemm_head", "head_argmax"]
+        reps = max(3, min(steps, 20))
+        for timed in (False, True):
+            if timed:
+                st.profile_enable(names)
+            for _ in range(reps):
+                st.embed(ends["embed"], ids, out=hidden)
+                st.head(out, mb.q_lens, ends["final_norm"], ends["lm_head"], want_logits=False)
+            torch.cuda.synchronize()
+        ms = {n: st.profile_read(n)[0] / reps for n in names}
+        st.profile_enable([])
+        head_bytes = 2 * shape.vocab * shape.hidden
+        result["ends"] = {"vocab": shape.vocab, "ms": {n: round(v, 5) for n, v in ms.items()},
+                          "head_gemm_GBps": round(head_bytes / (ms["gemm_head"] * 1e-3) / 1e9, 1),
+                          "head_gemm_algorithmic_bytes": head_bytes}
+
+    # the oracle baseline is timed on the benchmark configuration
+    if extras and not args.no_cpu_baseline and not w4 and args.dtype == "bf16":
+        sample = {"tiny": mb.num_seqs, "llama2-7b": 64, "qwen2-7b": 8, "llama3-70b": 4, "sweep": 4}[workload]
+        result["cpu_baseline"] = cpu_baseline(shape, mb, args.seed, sample)
+    st.close()
+    del st, hidden, out
+    torch.cuda.empty_cache()
+    return result
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="llama2-7b", choices=["tiny", "llama2-7b", "qwen2-7b", "llama3-70b", "sweep"])
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default=None, choices=["tiny", "llama2-7b", "qwen2-7b", "llama3-70b", "sweep"],
+                    help="time this workload alone (default: the headline workload plus one entry per configuration)")
     ap.add_argument("--budget", type=int, default=256, help="token budget of the sweep workload")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--weights", default="bf16", choices=["bf16", "w4"],
@@ -97,6 +228,7 @@ def main():
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "f16"],
                     help="f16: the IEEE-half library (a variant, not the benchmark configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true", help="headline workload only")
     ap.add_argument("--ends", action="store_true",
                     help="also time the pipeline's two ends (embedding; final norm + output head + greedy choice)")
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel class (extra untimed steps)")
@@ -115,122 +247,32 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4, "launches": 10}))
         return
-    from paper_2507_05043_amd import KERNEL_CLASSES, synth
     from paper_2507_05043_amd import stage as _stage
     if not all(os.path.exists(p) for p in _stage.LIB_PATHS.values()):
         import __graft_entry__
         __graft_entry__.build()
-    from paper_2507_05043_amd.harness import make_stage
 
-    shape, mb = synth.workload(args.workload, seed=args.seed, budget=args.budget)
-    w4 = args.weights == "w4"
-    elem = torch.float16 if args.dtype == "f16" else torch.bfloat16
-    # 4 bits per weight plus a bf16 scale and a bf16 zero point per 128 weights
-    work = algorithmic_work(shape, mb, 0.5 + 4.0 / 128 if w4 else 2.0)
-    kv_bytes = shape.num_layers * mb.num_kv_blocks * 16 * 4 * shape.num_kv_heads * shape.head_dim
-    alias = kv_bytes + work["weight_bytes_per_layer"] * shape.num_layers > 250e9     # timing only: layers share one pool
-    st = make_stage(shape, mb, args.seed, alias_layers=alias, vocab_size=shape.vocab if args.ends else 0,
-                    qkv_bias=args.workload == "qwen2-7b",     # the Qwen2 family has a q/k/v bias
-                    weight_group_size=128 if w4 else 0, dtype=elem)
-    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=args.seed, device="cuda:0", dtype=elem)
-    out = torch.empty_like(hidden)
-    n_dec = sum(1 for q in mb.q_lens if q == 1)
-    decode_bound = work["decode_attn_bytes_per_layer"] / (HBM_PEAK_GBS * 1e9) >= \
-        (work["gemm_flops_per_layer"] + work["attn_flops_per_layer"]) / (MFMA_BF16_PEAK_TFLOPS * 1e12)
-    dominant = "attn_decode" if (n_dec and decode_bound) else "gemm_gateup"
+    headline = args.workload or HEADLINE
+    head = run_workload(args, headline, args.budget if headline == "sweep" else None, args.steps, args.warmup, extras=True)
+    result = {"metric": "stage_tokens_per_sec", "value": head.pop("value"), "unit": "tokens/s", "n_gpus": 1,
+              "steps": head.pop("steps"), "warmup": head.pop("warmup"), "ms_per_step": head.pop("ms_per_step"),
+              "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic"}
+    result.update(head)
 
-    def step():
-        st.forward(hidden, mb.positions, mb.q_lens, mb.ctx_lens, mb.block_tables, out=out)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    st.profile_enable([dominant])
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    dom_ms, dom_n = st.profile_read(dominant)
-    st.profile_enable([])
-    ms_per_step = elapsed / args.steps * 1e3
-    tokens_per_s = mb.num_tokens * args.steps / elapsed
-
-    avg_ms = dom_ms / max(dom_n, 1)
-    if dominant == "attn_decode":
-        achieved = work["decode_attn_bytes_per_layer"] / (avg_ms * 1e-3) / 1e9
-        roofline = {"kernel": _stage.stage_kernel_name(KERNEL_CLASSES[dominant]), "bound": "hbm",
-                    "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(achieved / HBM_PEAK_GBS, 4),
-                    "traffic": measured_traffic(dominant, args.workload, args.seed) if args.dtype == "bf16" and not w4 else None,
-                    "avg_launch_ms": round(avg_ms, 5), "launches": dom_n,
-                    "algorithmic_bytes_per_launch": work["decode_attn_bytes_per_layer"]}
-    else:
-        flops = 2 * (2 * shape.hidden * shape.ffn) * mb.num_tokens
-        achieved = flops / (avg_ms * 1e-3) / 1e12
-        roofline = {"kernel": _stage.stage_kernel_name(KERNEL_CLASSES[dominant]), "bound": "mfma",
-                    "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
-                    "avg_launch_ms": round(avg_ms, 5), "launches": dom_n, "flops_per_launch": flops}
-
-    result = {
-        "metric": "stage_tokens_per_sec", "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": f"{shape.name}: L={shape.num_layers} H={shape.hidden} nq={shape.num_q_heads} "
-                               f"nkv={shape.num_kv_heads} d={shape.head_dim} F={shape.ffn}; micro-batch T={mb.num_tokens} "
-                               f"S={mb.num_seqs} ({mb.num_seqs - n_dec} prefill chunks, {n_dec} decode tokens), KV block 16",
-                   "seed": args.seed, "kv_layers_aliased": bool(alias),
-                   # what the library does by itself beyond 8 layers (see stage_config.activation_planes)
-                   "projection_inputs": ("IEEE half, bf16 weights converted in the GEMMs"
-                                         if args.dtype == "bf16" and shape.num_layers > 8 else args.dtype),
-                   "weights": f"4-bit codes, {args.dtype} scale and zero point per 128 input features" if w4 else args.dtype},
-        "stage_latency_ms": round(ms_per_step, 4),
-        "ideal_ms": {"hbm": round(work["bytes_per_call"] / (HBM_PEAK_GBS * 1e9) * 1e3, 4),
-                     "mfma": round(work["flops_per_call"] / (MFMA_BF16_PEAK_TFLOPS * 1e12) * 1e3, 4)},
-        "roofline": roofline,
-    }
-
-    if args.breakdown:
-        names = list(KERNEL_CLASSES)
-        st.profile_enable(names)
-        reps = max(3, min(args.steps, 10))
-        for _ in range(reps):
-            step()
-        torch.cuda.synchronize()
-        result["breakdown_ms_per_step"] = {n: round(st.profile_read(n)[0] / reps, 5) for n in names}
-        st.profile_enable([])
-        proj_ms = sum(result["breakdown_ms_per_step"][n] for n in ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down", "dequant"))
-        result["projections"] = {"ms_per_step": round(proj_ms, 5),
-                                 "weight_bytes_per_step": work["weight_bytes_per_layer"] * shape.num_layers,
-                                 "weight_stream_GBps": round(work["weight_bytes_per_layer"] * shape.num_layers / (proj_ms * 1e-3) / 1e9, 1)}
-
-    if args.ends:
-        # The pipeline's two ends, timed on their own after the stage (not part of `value`): token
-        # embedding of the micro-batch and final norm + vocabulary projection + greedy choice.
-        ends = synth.draw_ends_weights(shape, seed=args.seed, device="cuda:0", dtype=elem)
-        ids = synth.draw_token_ids(shape, mb.num_tokens, seed=args.seed)
-        names = ["embed", "head_norm", "gemm_head", "head_argmax"]
-        reps = max(3, min(args.steps, 20))
-        for timed in (False, True):
-            if timed:
-                st.profile_enable(names)
-            for _ in range(reps):
-                st.embed(ends["embed"], ids, out=hidden)
-                st.head(out, mb.q_lens, ends["final_norm"], ends["lm_head"], want_logits=False)
-            torch.cuda.synchronize()
-        ms = {n: st.profile_read(n)[0] / reps for n in names}
-        st.profile_enable([])
-        head_bytes = 2 * shape.vocab * shape.hidden
-        result["ends"] = {"vocab": shape.vocab, "ms": {n: round(v, 5) for n, v in ms.items()},
-                          "head_gemm_GBps": round(head_bytes / (ms["gemm_head"] * 1e-3) / 1e9, 1),
-                          "head_gemm_algorithmic_bytes": head_bytes}
-
-    if not args.no_cpu_baseline and not w4 and args.dtype == "bf16":     # the oracle baseline is timed on the benchmark configuration
-        sample = {"tiny": mb.num_seqs, "llama2-7b": 64, "qwen2-7b": 8, "llama3-70b": 4, "sweep": 4}[args.workload]
-        result["cpu_baseline"] = cpu_baseline(shape, mb, args.seed, sample)
-    st.close()
+    if args.workload is None and not args.no_per_config:
+        # One entry per configuration, each timed like the headline (same seed, same measurement) with fewer steps
+        # for the long ones so that the whole run stays within a few minutes.
+        entries = []
+        for workload, budget in PER_CONFIG:
+            if workload == headline:
+                r = {k: result[k] for k in ("value", "steps", "warmup", "ms_per_step", "config", "ideal_ms", "roofline")}
+            else:
+                steps = max(3, min(args.steps, 10)) if (workload == "sweep" and budget >= 1024) else args.steps
+                r = run_workload(args, workload, budget, steps, args.warmup, extras=False)
+                r.pop("stage_latency_ms")
+            r["unit"] = "tokens/s"
+            entries.append(r)
+        result["per_config"] = entries
     print(json.dumps(result))
 
 

@@ -80,12 +80,17 @@ typedef struct {
                                   3  (bfloat16 library only) one plane of IEEE half - eleven significant bits
                                      instead of eight - with the bfloat16 weights converted to half, exactly, on
                                      their way into the matrix instruction; the rotated queries keep a second
-                                     bfloat16 plane for the attention kernels;
-                                  0  automatic: 1, except that a bfloat16 stage deeper than 8 layers, whose
-                                     accumulated bfloat16 rounding error would otherwise come close to or exceed
-                                     1e-2 relative on the output, takes 3, and for micro-batches with prefill
-                                     chunks also gives the input of the q/k/v projection a second half plane
-                                     (rows that attend to few keys amplify the rounding of that input). */
+                                     bfloat16 plane for the attention kernels.  Values beyond the half range
+                                     saturate: a projection input larger than 65504 in magnitude is carried as
+                                     +-65504 (finite, no longer the unclamped result; activations of that size
+                                     do not occur behind an RMSNorm with gains of order one);
+                                  4  (bfloat16 library only) as 3, and for micro-batches with prefill chunks the
+                                     input of the q/k/v projection gets a second half plane (rows that attend to
+                                     few keys amplify the rounding of that input);
+                                  0  automatic: 1 for the half-precision library; for the bfloat16 library by
+                                     depth, because the rounding errors of the layers add up on the residual
+                                     stream: 1 up to 4 layers, 3 from 5 layers, 4 from 9 layers (one bfloat16
+                                     plane comes to 8e-3 of the 1e-2 relative-L2 budget at 8 layers). */
   int32_t vocab_size;          /* 0, or the vocabulary size (multiple of 8, >= 64) of the output head this
                                   stage may run with stage_head (sizes the workspace for it) */
   int32_t weight_bits;         /* 0 or 16: the five projection matrices of a layer are bf16.  4: they are

@@ -113,6 +113,9 @@ __device__ __forceinline__ h16x8 bf16x8_to_half(e16x8 v) {
 __device__ __forceinline__ f32x16 mfma_32x32x16_half(h16x8 a, h16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
 }
+__device__ __forceinline__ f32x4 mfma_16x16x32_half(h16x8 a, h16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
 
 // 16-byte global load / store of 8 e16
 __device__ __forceinline__ e16x8 load8(const e16* p) { return *reinterpret_cast<const e16x8*>(p); }

@@ -198,17 +198,23 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(GemmAr
     constexpr int S = decltype(stage_c)::value;
     const char* la = Lds::template get<S>() + wm * TM * 128;
     const char* lb = Lds::template get<S>() + (AROWS + wn * TN) * 128;
+    auto read_a = [&] {
 #pragma unroll
-    for (int pl = 0; pl < NPLANE; ++pl)
+      for (int pl = 0; pl < NPLANE; ++pl)
 #pragma unroll
-      for (int i = 0; i < MT; ++i)
-        af[s][pl][i] = *reinterpret_cast<const e16x8*>(la + (pl * BM + i * 32) * 128 + frag_off[kk]);
+        for (int i = 0; i < MT; ++i)
+          af[s][pl][i] = *reinterpret_cast<const e16x8*>(la + (pl * BM + i * 32) * 128 + frag_off[kk]);
+    };
+    // half activations: the weight fragments are read first, so that they land - and can be turned into half, once
+    // per read - as early as possible (placing the conversions behind chosen MFMAs with scheduling hints was
+    // measured slower: 765 against 712 us on the Qwen2-shaped gate/up product)
+    if constexpr (!A_HALF) read_a();
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
       const e16x8 w = *reinterpret_cast<const e16x8*>(lb + j * 32 * 128 + frag_off[kk]);
-      // half activations: the weight fragment becomes half here, once per read
       bfr[s][j] = A_HALF ? __builtin_bit_cast(e16x8, bf16x8_to_half(w)) : w;
     }
+    if constexpr (A_HALF) read_a();
   };
   auto mfmas = [&](int s) {
 #pragma unroll
@@ -445,6 +451,11 @@ constexpr int kSkinnyKS = 1024;     // K elements per slice
 constexpr int kSkinnyRows = 16;     // weight rows per stage
 constexpr int kSkinnyStages = 4;
 
+//
+// A_HALF (bfloat16 library, half activations): the activations are IEEE half bits; every weight fragment is turned
+// into half in registers after its LDS read (exact) and the f16 instruction multiplies.  The conversion is vector
+// work of the multiplying waves only and stays far below the time the stage's bytes take to arrive.
+template <bool A_HALF>
 __global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs p, int nv, int splits, int groups, int swiglu) {
   constexpr int KS = kSkinnyKS, ROWS = kSkinnyRows, NST = kSkinnyStages;
   constexpr int STAGE_BYTES = ROWS * KS * 2;
@@ -556,7 +567,10 @@ __global__ __launch_bounds__(512) void gemm_skinny_kernel(GemmArgs p, int nv, in
     for (int s = 0; s < STEPS; ++s) {
       const int off = (s >> 4) * 1024 + (s & 15) * 64 + ((s & 1) ? frag_odd : frag_even);
       const e16x8 wf = *reinterpret_cast<const e16x8*>(stage + off);
-      acc[s & 3] = mfma_16x16x32(wf, act[s], acc[s & 3]);
+      if constexpr (A_HALF)
+        acc[s & 3] = mfma_16x16x32_half(bf16x8_to_half(wf), __builtin_bit_cast(h16x8, act[s]), acc[s & 3]);
+      else
+        acc[s & 3] = mfma_16x16x32(wf, act[s], acc[s & 3]);
     }
     // eight fragment reads run ahead of the MFMA that consumes the oldest of them
     __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
@@ -736,8 +750,16 @@ hipError_t launch_gemm_main(const GemmArgs& a, GemmEpilogue epi, const GemmPlan&
     const int cus = 256;
     const int nwg = units < cus ? (int)units : (cus > plan.splits ? cus : plan.splits);
     dim3 grid(nwg);
-    if (a.a_half) return hipErrorInvalidValue;     // half activations are planned onto the 64-row tiles
-    hipLaunchKernelGGL(gemm_skinny_kernel, grid, dim3(512), 0, stream, a, plan.nv, plan.splits, groups,
+    if (a.a_half) {
+#ifdef MOLINK_F16
+      return hipErrorInvalidValue;                 // the element type is half already
+#else
+      hipLaunchKernelGGL(gemm_skinny_kernel<true>, grid, dim3(512), 0, stream, a, plan.nv, plan.splits, groups,
+                         epi == kEpiSwiGLU ? 1 : 0);
+      return hipGetLastError();
+#endif
+    }
+    hipLaunchKernelGGL(gemm_skinny_kernel<false>, grid, dim3(512), 0, stream, a, plan.nv, plan.splits, groups,
                        epi == kEpiSwiGLU ? 1 : 0);
     return hipGetLastError();
   }

@@ -100,10 +100,10 @@ int check_config(const stage_config* c) {
   if (c->num_q_heads / c->num_kv_heads > 16)
     return fail(STAGE_ERR_CONFIG, "at most 16 query heads per KV head are supported");
   if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return fail(STAGE_ERR_CONFIG, "rms_eps must be > 0 and rope_theta > 1");
-  if (c->activation_planes < 0 || c->activation_planes > 3)
-    return fail(STAGE_ERR_CONFIG, "activation_planes must be 0 (automatic), 1, 2 or 3 (half activations)");
-  if (c->activation_planes == 3 && kElemIsF16)
-    return fail(STAGE_ERR_CONFIG, "activation_planes 3 (half activations) is a mode of the bfloat16 library; this one stores half already");
+  if (c->activation_planes < 0 || c->activation_planes > 4)
+    return fail(STAGE_ERR_CONFIG, "activation_planes must be 0 (automatic), 1, 2, 3 or 4 (half activations)");
+  if (c->activation_planes >= 3 && kElemIsF16)
+    return fail(STAGE_ERR_CONFIG, "activation_planes 3 and 4 (half activations) are modes of the bfloat16 library; this one stores half already");
   if (c->vocab_size != 0 && (c->vocab_size < 64 || c->vocab_size % 8))
     return fail(STAGE_ERR_CONFIG, "vocab_size must be 0 or a multiple of 8 that is at least 64");
   if (c->weight_bits != 0 && c->weight_bits != 16 && c->weight_bits != 4)
@@ -136,10 +136,10 @@ Dims dims_of(const stage_config& c) {
 // Number of compute units the work decomposition is sized for.  The library targets MI355X only.
 constexpr int kNumCus = 256;
 
-// One bfloat16 rounding per GEMM input costs about 1.7e-3 relative error per layer on the residual
-// stream; the errors of the layers add in quadrature (8.0e-3 measured at eight layers), and beyond
-// eight layers bfloat16 activations no longer keep a margin to the 1e-2 relative-L2 budget on the
-// stage output.  Two ways to carry more bits (stage_config.activation_planes):
+// One bfloat16 rounding per GEMM input costs about 2.8e-3 relative error per layer on the residual
+// stream; the errors of the layers add in quadrature (8.0e-3 measured at eight layers, 9.5e-3 on the rows of
+// a long prefill chunk at seven), which leaves no margin to the 1e-2 relative-L2 budget on the stage output
+// from about five layers on.  Two ways to carry more bits (stage_config.activation_planes):
 //  - two planes (2): every GEMM input - both norm outputs, the attention output, silu(gate)*up - and the
 //    rotated queries as two e16 planes, value = hi + lo, both multiplied into the same accumulators:
 //    sixteen bits at twice the matrix work of the projections.
@@ -147,23 +147,30 @@ constexpr int kNumCus = 256;
 //    bits) in the same buffers and the GEMMs convert the bfloat16 weight fragments to half in registers,
 //    which is exact; the matrix work stays what it is.  The rotated queries keep a second bfloat16 plane
 //    for the attention kernels, whose cache operands are bfloat16.
-// Left to the library (0), a bfloat16 stage deeper than eight layers takes half activations, and for
-// micro-batches with prefill chunks it also gives the q/k/v projection's input - the first norm's output -
-// a second half plane: the rows of a chunk that attend to few keys amplify input rounding about ninefold,
+// Mode 4 is mode 3 that, for micro-batches with prefill chunks, also gives the q/k/v projection's input - the
+// first norm's output - a second half plane: the rows of a chunk that attend to few keys amplify input rounding about ninefold,
 // mostly through keys and values that land on the other side of a rounding boundary of the bfloat16 cache
 // (measured on 20 layers, a chunk with a short cached prefix: relative error of its rows 1.2e-2 with one
-// half plane everywhere, its largest error above the max-abs bar; decode rows 3.0e-3).  The half-precision
-// library keeps three more mantissa bits in e16 itself and chooses none of this.
-bool deep_auto_of(const stage_config& c) { return !kElemIsF16 && c.activation_planes == 0 && c.num_layers > 8; }
+// half plane everywhere, its largest error above the max-abs bar; decode rows 3.0e-3).  Left to the library (0),
+// a bfloat16 stage takes one bfloat16 plane up to four layers, half activations (3) from five, and mode 4 from
+// nine.  The half-precision library keeps three more mantissa bits in e16 itself and chooses none of this.
+constexpr int kHalfFromLayers = 5;       // automatic mode: half activations from this depth on
+constexpr int kQkvPlaneFromLayers = 9;   // automatic mode: also the second half plane of the q/k/v input
+// the mode a configuration runs in: its own, or by depth when left to the library
+int mode_of(const stage_config& c) {
+  if (c.activation_planes != 0) return c.activation_planes;
+  if (kElemIsF16) return 1;
+  return c.num_layers >= kQkvPlaneFromLayers ? 4 : (c.num_layers >= kHalfFromLayers ? 3 : 1);
+}
 // workspace: are the second planes of the GEMM inputs / of the rotated queries laid out?
-bool lo_planes_of(const stage_config& c) { return c.activation_planes == 2; }
-bool norm1_lo_plane_of(const stage_config& c) { return lo_planes_of(c) || deep_auto_of(c); }
-bool q_lo_plane_of(const stage_config& c) { return lo_planes_of(c) || deep_auto_of(c) || c.activation_planes == 3; }
+bool lo_planes_of(const stage_config& c) { return mode_of(c) == 2; }
+bool norm1_lo_plane_of(const stage_config& c) { return mode_of(c) == 2 || mode_of(c) == 4; }
+bool q_lo_plane_of(const stage_config& c) { return mode_of(c) >= 2; }
 // per micro-batch
-bool half_act_of(const stage_config& c) { return !kElemIsF16 && (c.activation_planes == 3 || deep_auto_of(c)); }
-bool two_plane_of(const stage_config& c) { return c.activation_planes == 2; }
+bool half_act_of(const stage_config& c) { return !kElemIsF16 && mode_of(c) >= 3; }
+bool two_plane_of(const stage_config& c) { return mode_of(c) == 2; }
 // half activations: does the q/k/v projection's input get a second (half) plane?
-bool qkv_lo_of(const stage_config& c, bool has_prefill) { return deep_auto_of(c) && has_prefill; }
+bool qkv_lo_of(const stage_config& c, bool has_prefill) { return mode_of(c) == 4 && has_prefill; }
 
 int decode_target_items(const Dims& d) { return (kNumCus * kDecodeWavesPerCu + d.nkv - 1) / d.nkv; }
 
@@ -190,7 +197,7 @@ WorkspaceLayout layout_of(const stage_config& c) {
   size_t pf = 0, v;
   for (int sp = 0; sp < 2; ++sp) {
     if (sp == 1 && !(lo_planes_of(c) || half_act_of(c))) continue;
-    if (sp == 0 && c.activation_planes == 2) continue;
+    if (sp == 0 && lo_planes_of(c)) continue;
     if ((v = gemm_partial_floats(c.max_tokens, d.qkv_out, d.H, kEpiStoreF32, kNumCus, sp)) > pf) pf = v;
     if ((v = gemm_partial_floats(c.max_tokens, d.H, d.nq * d.d, kEpiResidualF32, kNumCus, sp)) > pf) pf = v;
     if ((v = gemm_partial_floats(c.max_tokens, d.F, d.H, kEpiSwiGLU, kNumCus, sp)) > pf) pf = v;
@@ -382,12 +389,11 @@ int bind_weights(stage_handle* st, hipStream_t stream, GemmArgs& g, const void* 
   return STAGE_OK;
 }
 
-// The plan of a projection.  At most 64 rows: 4-bit weights in their stored form need the streaming kernel; half
-// activations run on the 64-row tiles (the bf16 streaming kernel takes e16 activations); otherwise the shape decides.
-GemmPlan plan_projection(const stage_config& c, int m, int n, int k, GemmEpilogue epi, bool two_planes, bool a_half) {
+// The plan of a projection.  At most 64 rows: 4-bit weights in their stored form need the streaming kernel;
+// otherwise the shape decides between it and the 64-row tiles.
+GemmPlan plan_projection(const stage_config& c, int m, int n, int k, GemmEpilogue epi, bool two_planes) {
   const bool stored_w4 = c.weight_bits == 4 && skinny_w4_supports(m, k, c.weight_group_size, two_planes);
-  const GemmFewRows few = stored_w4 ? kFewRowsStreaming : (a_half ? kFewRowsTiles : kFewRowsByShape);
-  return plan_gemm(m, n, k, epi, kNumCus, two_planes, few);
+  return plan_gemm(m, n, k, epi, kNumCus, two_planes, stored_w4 ? kFewRowsStreaming : kFewRowsByShape);
 }
 
 // The plans of a layer's four projections for one micro-batch; they depend on the shapes only, so they are made -
@@ -406,14 +412,14 @@ int check_plan(const stage_handle* st, int m, const GemmPlan& plan) {
   return STAGE_OK;
 }
 
-int plan_layer(const stage_handle* st, int T, bool qkv_two_planes, bool two_planes, bool a_half, LayerPlans* out) {
+int plan_layer(const stage_handle* st, int T, bool qkv_two_planes, bool two_planes, LayerPlans* out) {
   const stage_config& c = st->cfg;
   const Dims& d = st->dim;
-  out->qkv = plan_projection(c, T, d.qkv_out, d.H, kEpiStoreF32, qkv_two_planes, a_half);
-  out->o = plan_projection(c, T, d.H, d.nq * d.d, kEpiResidualF32, two_planes, a_half);
-  out->gateup = plan_projection(c, T, d.F, d.H, kEpiSwiGLU, two_planes, a_half);
-  out->down = plan_projection(c, T, d.H, d.F, kEpiResidualF32, two_planes, a_half);
-  out->down_out = plan_projection(c, T, d.H, d.F, kEpiResidualOut, two_planes, a_half);
+  out->qkv = plan_projection(c, T, d.qkv_out, d.H, kEpiStoreF32, qkv_two_planes);
+  out->o = plan_projection(c, T, d.H, d.nq * d.d, kEpiResidualF32, two_planes);
+  out->gateup = plan_projection(c, T, d.F, d.H, kEpiSwiGLU, two_planes);
+  out->down = plan_projection(c, T, d.H, d.F, kEpiResidualF32, two_planes);
+  out->down_out = plan_projection(c, T, d.H, d.F, kEpiResidualOut, two_planes);
   for (const GemmPlan* p : {&out->qkv, &out->o, &out->gateup, &out->down, &out->down_out})
     if (int rc = check_plan(st, T, *p)) return rc;
   return STAGE_OK;
@@ -529,7 +535,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
   const bool half_act = half_act_of(c);                // GEMM inputs as IEEE half bits (bfloat16 library)
   const bool qkv_lo = half_act && qkv_lo_of(c, n_tiles > 0);
   LayerPlans plans;
-  if (int rc = plan_layer(st, T, two_plane || qkv_lo, two_plane, half_act, &plans)) return rc;
+  if (int rc = plan_layer(st, T, two_plane || qkv_lo, two_plane, &plans)) return rc;
 
   HIP_TRY(hipSetDevice(st->device));
   hipStream_t stream = (hipStream_t)hip_stream;

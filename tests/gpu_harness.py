@@ -51,13 +51,14 @@ def check_output(gpu_out: torch.Tensor, ref: torch.Tensor, what: str = "output")
 
 
 def check_output_stratified(gpu_out: torch.Tensor, ref: torch.Tensor, strata, what: str = "output",
-                            gate_max_abs: bool = True) -> Dict[str, float]:
+                            gate_max_abs: bool = True, gate_strata: bool = False) -> Dict[str, float]:
     """The whole-output metric estimated from a stratified sample of rows.
 
     strata: list of (row_slice_into_the_sample, rows_in_the_population).  Every sampled row of a
     stratum stands for population/sample rows, so the sums of squared error and of squared reference
     are scaled per stratum before the ratio is taken (rows of a stratum are exact; only which
-    sequences were drawn is a sample).  Also reports every stratum on its own.
+    sequences were drawn is a sample).  Also reports every stratum on its own, and with gate_strata holds
+    every stratum to the tolerance by itself, so that many good rows cannot outvote a few bad ones.
     """
     got = gpu_out.detach().cpu().double()
     ref = ref.double()
@@ -75,6 +76,8 @@ def check_output_stratified(gpu_out: torch.Tensor, ref: torch.Tensor, strata, wh
     est = (num / den) ** 0.5
     rms = float(ref.pow(2).mean().sqrt())
     assert est <= REL_L2_TOL, f"{what}: estimated whole-output rel-L2 {est:.3e} > {REL_L2_TOL} (strata {per})"
+    if gate_strata:
+        assert max(per) <= REL_L2_TOL, f"{what}: a stratum's rel-L2 exceeds {REL_L2_TOL}: {per}"
     if gate_max_abs:
         assert max_abs <= MAX_ABS_TOL * max(1.0, rms), f"{what}: max-abs {max_abs:.3e} (rms {rms:.3f})"
     return {"rel_l2": est, "per_stratum": per, "max_abs": max_abs, "rms": rms}

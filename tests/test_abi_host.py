@@ -93,6 +93,26 @@ def test_half_activations_are_a_mode_of_the_bfloat16_library_only(lib):
     assert S.load_library(torch.float16).stage_workspace_bytes(ctypes.byref(cfg), ctypes.byref(out)) == -2
 
 
+def test_automatic_activation_mode_goes_by_depth(lib):
+    """Left to the library, the bfloat16 stage carries one bfloat16 plane up to four layers, half activations from
+    five and the extra half plane of the q/k/v input from nine; seen from the host as the workspace each mode needs."""
+    def ws(layers, planes, dtype=torch.bfloat16):
+        return S.stage_workspace_bytes(tiny_cfg(num_layers=layers, activation_planes=planes), dtype)
+    for layers, mode in ((1, 1), (4, 1), (5, 3), (8, 3), (9, 4), (20, 4)):
+        assert ws(layers, 0) == ws(layers, mode), (layers, mode)
+    assert ws(8, 1) < ws(8, 3) < ws(8, 4) <= ws(8, 2)
+    # the half-precision library never takes a mode of its own accord
+    assert ws(20, 0, torch.float16) == ws(20, 1, torch.float16)
+
+
+def test_matrices_of_four_gib_and_more_are_accepted(lib):
+    """Tile addressing takes a 64-bit base per workgroup, so an output head of 262144 x 8192 (4 GiB) and
+    projections of that size are within the configuration limits."""
+    cfg = tiny_cfg(hidden=8192, num_q_heads=64, num_kv_heads=8, head_dim=128, ffn=8192 * 36, vocab_size=262144,
+                   max_tokens=64, max_seqs=64)
+    assert S.stage_workspace_bytes(cfg) > 64 * 262144 * 4
+
+
 def test_config_struct_matches_header_size(lib):
     # uint32 + 6 int32 + 2 float + 2 int32 (+ 4 pad) + int64 + 7 int32 (+ 4 pad)
     assert ctypes.sizeof(S.StageConfig) == 88
@@ -102,7 +122,7 @@ def test_config_struct_matches_header_size(lib):
 
 @pytest.mark.parametrize("bad", [dict(kv_block_size=32), dict(head_dim=96), dict(hidden=252), dict(num_q_heads=5),
                                  dict(num_q_heads=34, num_kv_heads=2), dict(rms_eps=0.0), dict(num_layers=0),
-                                 dict(activation_planes=4), dict(vocab_size=1001), dict(vocab_size=32),
+                                 dict(activation_planes=5), dict(vocab_size=1001), dict(vocab_size=32),
                                  dict(weight_bits=3), dict(weight_group_size=128), dict(weight_bits=4, weight_group_size=48),
                                  dict(weight_bits=4, weight_group_size=128, ffn=768 + 64),
                                  dict(weight_bits=4, weight_group_size=128)])   # ffn 688 is no multiple of 128

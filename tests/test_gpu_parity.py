@@ -130,6 +130,54 @@ def test_half_activations_in_the_bfloat16_library(case):
         assert stats3["rel_l2"] <= 1.05 * stats1["rel_l2"]
 
 
+def test_half_activations_with_a_second_plane_of_the_qkv_input():
+    """activation_planes = 4 (what stages of nine layers and more take by themselves): half activations, and for
+    micro-batches with prefill chunks a second half plane of the first norm's output; a decode-only micro-batch
+    of the same stage runs without it."""
+    shape = _shape("half-act-mid", 2, 1024, 8, 2, 128, 2816)
+    mixed = synth.make_microbatch([130, 61, 1, 1, 1, 1, 1, 1, 1, 1, 1], [0, 40] + [20 + 9 * i for i in range(9)], seed=3,
+                                  max_blocks_per_seq=16)
+    s4 = full_parity(shape, mixed, 11, "fan_in", qkv_bias=True, activation_planes=4)
+    s1 = full_parity(shape, mixed, 11, "fan_in", qkv_bias=True, activation_planes=1, taps=False, check_kv=False)
+    assert s4["rel_l2"] < 0.85 * s1["rel_l2"]
+    few = synth.make_microbatch([20, 1, 1], [5, 30, 64], seed=4, max_blocks_per_seq=16)      # at most 64 rows, with a chunk
+    full_parity(shape, few, 12, "fan_in", activation_planes=4)
+    decode = synth.make_microbatch([1] * 64, [40 + 97 * i % 700 for i in range(64)], seed=5, max_blocks_per_seq=48)
+    full_parity(shape, decode, 13, "fan_in", activation_planes=4)
+
+
+def test_half_activations_saturate_instead_of_overflowing():
+    """A projection input beyond the half range is carried as +-65504: the output stays finite.  The up projection
+    is scaled so that the largest silu(gate) * up of the micro-batch is about 1.5 times the largest half."""
+    shape = _shape("half-act-sat", 1, 256, 4, 2, 64, 688)
+    mb = synth.make_microbatch([40, 1, 1], [0, 20, 3], seed=6)
+    layers = draw_layers(shape, 6, "fan_in", device="cuda:0")
+    _, _, _, otaps0 = H.run_oracle(shape, mb, 6, layers=[{k: v.cpu() for k, v in layers[0].items()}], want_taps=True)
+    factor = 1.5 * 65504.0 / float(otaps0[0]["m"].abs().max())
+    layers[0]["wup"] = (layers[0]["wup"].float() * factor).to(torch.bfloat16)
+    from paper_2507_05043_amd.stage import Stage, make_config
+    outs = {}
+    for planes in (1, 3):
+        cfg = make_config(num_layers=1, hidden=shape.hidden, num_q_heads=shape.num_q_heads, num_kv_heads=shape.num_kv_heads,
+                          head_dim=shape.head_dim, ffn=shape.ffn, rms_eps=shape.rms_eps, rope_theta=shape.rope_theta,
+                          num_kv_blocks=mb.num_kv_blocks, max_tokens=mb.num_tokens, max_seqs=mb.num_seqs,
+                          max_blocks_per_seq=mb.max_blocks_per_seq, activation_planes=planes)
+        st = Stage(cfg, layers)
+        H.fill_pool(st, shape, mb, 6)
+        out, _, taps = H.run_gpu(st, shape, mb, 6, taps_layer=0)
+        assert torch.isfinite(out.float()).all() and torch.isfinite(taps["m"].float()).all()
+        outs[planes] = (out.float().cpu(), taps["m"].float().cpu())
+        st.close()
+    ref, _, _, otaps = H.run_oracle(shape, mb, 6, layers=[{k: v.cpu() for k, v in layers[0].items()}], want_taps=True)
+    m_ref = otaps[0]["m"]
+    assert float(m_ref.abs().max()) > 1.2 * 65504.0                     # the unclamped definition leaves the half range
+    assert float(outs[3][1].abs().max()) <= 65536.0                     # the half plane saturated (65504, seen through a bf16 tap)
+    H.check_output(outs[1][0], ref, "bfloat16 plane beyond the half range")     # bfloat16 has the range: still the definition
+    inside = m_ref.abs().max(dim=1).values < 60000.0                    # rows that never left the range agree with it
+    assert int(inside.sum()) >= 1
+    assert rel_l2(outs[3][0][inside], ref[inside]) <= H.REL_L2_TOL
+
+
 @pytest.mark.parametrize("n_decode,elem", [(1, torch.bfloat16), (40, torch.float16), (64, torch.bfloat16)],
                          ids=["1-bf16", "40-f16", "64-bf16"])
 def test_wide_projections_at_few_rows(n_decode, elem):
@@ -159,7 +207,7 @@ def test_seeded_random_small_stages(case):
     ctx = [rng.choice([0, rng.randint(1, 400)]) if q > 1 else rng.randint(0, 900) for q in q_lens]
     mb = synth.make_microbatch(q_lens, ctx, seed=case)
     elem = rng.choice([torch.bfloat16, torch.float16])
-    planes = rng.choice([1, 2, 3]) if elem == torch.bfloat16 else rng.choice([1, 2])
+    planes = rng.choice([1, 2, 3, 4]) if elem == torch.bfloat16 else rng.choice([1, 2])
     full_parity(shape, mb, 2000 + case, rng.choice([None, "fan_in"]), qkv_bias=rng.random() < 0.4,
                 qk_norm=rng.random() < 0.4, activation_planes=planes, elem=elem)
 
@@ -395,24 +443,27 @@ def test_invalid_batches_are_rejected_and_leave_the_pool_untouched():
     st.close()
 
 
-def test_llama2_7b_stage_sampled_rows_at_full_size():
-    """The benchmark workload at its real shape: 8 of 64 sequences checked row by row against the
-    oracle at full depth (rows of different sequences are independent, so the sample is exact)."""
-    shape, mb = synth.workload("llama2-7b", seed=0)
-    print(f"[case] {shape.name} T={mb.num_tokens} blocks={mb.num_kv_blocks}", flush=True)
-    st = H.make_stage(shape, mb, 0)
-    out, slots = H.run_gpu(st, shape, mb, 0)
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_llama2_7b_stage_every_row_at_full_size(seed):
+    """The Llama-2-7B-shaped decode workload at its real shape, three seeds: all 64 sequences row by row against the
+    oracle at full depth."""
+    shape, mb = synth.workload("llama2-7b", seed=seed)
+    print(f"[case] {shape.name} seed={seed} T={mb.num_tokens} blocks={mb.num_kv_blocks}", flush=True)
+    st = H.make_stage(shape, mb, seed)
+    out, slots = H.run_gpu(st, shape, mb, seed)
     assert slots == oracle.slot_mapping(mb.q_lens, mb.ctx_lens, mb.block_tables, 16)
     assert torch.isfinite(out.float()).all()
-    seqs = list(range(0, 64, 8))
-    sub, rows, pool = H.sub_problem(shape, mb, seqs, 0, dtype=torch.float32, draw_device="cuda:0")
-    layers = draw_layers(shape, 0, device="cuda:0")
+    seqs = list(range(64))
+    sub, rows, pool = H.sub_problem(shape, mb, seqs, seed, dtype=torch.float32, draw_device="cuda:0")
+    layers = draw_layers(shape, seed, device="cuda:0")
     layers = [{k: v.cpu() for k, v in w.items()} for w in layers]
-    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=0)[rows]
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=seed)[rows]
     ref, _ = oracle.stage_forward(oracle_shape(shape), layers, hidden, sub.positions, sub.q_lens, sub.ctx_lens,
                                   sub.block_tables, pool, dtype=torch.float32)
-    stats = H.check_output(out[rows.cuda()], ref, "llama2-7b sampled rows")
+    stats = H.check_output(out[rows.cuda()], ref, "llama2-7b all rows")
     print(f"  rel-L2 {stats['rel_l2']:.3e} max-abs {stats['max_abs']:.3e} rms {stats['rms']:.3f}", flush=True)
+    # the margin the automatic mode (half activations from five layers) is there for
+    assert stats["rel_l2"] <= 5e-3 and stats["max_abs"] <= 0.7 * H.MAX_ABS_TOL * max(1.0, stats["rms"])
     st.close()
 
 
@@ -433,65 +484,84 @@ def _layer0_reference(shape, layers0, hidden, mb):
     return a, q, k, v
 
 
-def test_qwen2_7b_stage_at_full_size():
-    """Mixed micro-batch at its real shape (2048-token prefill chunk + 128 decode tokens, 7 layers).
-    Whole-stage output: the first 320 rows of the chunk (causal, so exact on their own) and 8 decode
-    sequences, row by row.  Layer 0 taps: q/k/v of every row, attention of late prefill rows.
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_qwen2_7b_stage_at_full_size(seed):
+    """Mixed micro-batch at its real shape (2048-token prefill chunk + 128 decode tokens, 7 layers), three seeds.
+    Whole-stage output at full depth: every row of the chunk and 16 decode sequences, row by row.  At seed 0 also
+    the layer 0 taps: q/k/v of every row, attention of early and late prefill rows.
     The q/k/v projections carry a bias, as in the Qwen2 family."""
-    shape, mb = synth.workload("qwen2-7b", seed=0)
-    print(f"[case] {shape.name} T={mb.num_tokens} blocks={mb.num_kv_blocks}", flush=True)
-    st = H.make_stage(shape, mb, 0, qkv_bias=True)
-    out, slots, taps = H.run_gpu(st, shape, mb, 0, taps_layer=0)
+    shape, mb = synth.workload("qwen2-7b", seed=seed)
+    print(f"[case] {shape.name} seed={seed} T={mb.num_tokens} blocks={mb.num_kv_blocks}", flush=True)
+    st = H.make_stage(shape, mb, seed, qkv_bias=True)
+    if seed == 0:
+        out, slots, taps = H.run_gpu(st, shape, mb, seed, taps_layer=0)
+    else:
+        out, slots = H.run_gpu(st, shape, mb, seed)
     assert slots == oracle.slot_mapping(mb.q_lens, mb.ctx_lens, mb.block_tables, 16)
     assert torch.isfinite(out.float()).all()
-    layers = [{k: v.cpu() for k, v in synth.draw_layer_weights(shape, l, seed=0, device="cuda:0").items()}
+    layers = [{k: v.cpu() for k, v in synth.draw_layer_weights(shape, l, seed=seed, device="cuda:0").items()}
               for l in range(shape.num_layers)]
     for l, w in enumerate(layers):
-        w["bqkv"] = synth.draw_qkv_bias(shape, l, seed=0)
-    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=0)
+        w["bqkv"] = synth.draw_qkv_bias(shape, l, seed=seed)
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=seed)
     print("  inputs ready", flush=True)
 
-    # -- layer 0 taps on all rows
-    a, q, k, v = _layer0_reference(shape, layers[0], hidden, mb)
-    t = mb.num_tokens
-    ref_qkv = torch.cat([q.reshape(t, -1), k.reshape(t, -1), v.reshape(t, -1)], dim=1)
-    e_a = rel_l2(taps["a"].cpu(), a)
-    e_qkv = rel_l2(taps["qkv"].cpu(), ref_qkv)
-    print(f"  layer-0 norm rel-L2 {e_a:.2e}, qkv rel-L2 {e_qkv:.2e}", flush=True)
-    assert e_a <= H.REL_L2_TOL and e_qkv <= H.REL_L2_TOL
-    late = torch.tensor([0, 1, 31, 32, 777, 1500, 2016, 2047])
-    ref_attn = torch.stack([oracle.attention_rows(q[r:r + 1], k[: r + 1], v[: r + 1], int(r))[0] for r in late.tolist()])
-    e_attn = rel_l2(taps["attn"].cpu()[late], ref_attn.reshape(len(late), -1))
-    print(f"  layer-0 attention of rows {late.tolist()} rel-L2 {e_attn:.2e}", flush=True)
-    assert e_attn <= H.REL_L2_TOL
+    if seed == 0:
+        # -- layer 0 taps on all rows
+        a, q, k, v = _layer0_reference(shape, layers[0], hidden, mb)
+        t = mb.num_tokens
+        ref_qkv = torch.cat([q.reshape(t, -1), k.reshape(t, -1), v.reshape(t, -1)], dim=1)
+        e_a = rel_l2(taps["a"].cpu(), a)
+        e_qkv = rel_l2(taps["qkv"].cpu(), ref_qkv)
+        print(f"  layer-0 norm rel-L2 {e_a:.2e}, qkv rel-L2 {e_qkv:.2e}", flush=True)
+        assert e_a <= H.REL_L2_TOL and e_qkv <= H.REL_L2_TOL
+        late = torch.tensor([0, 1, 31, 32, 777, 1500, 2016, 2047])
+        ref_attn = torch.stack([oracle.attention_rows(q[r:r + 1], k[: r + 1], v[: r + 1], int(r))[0] for r in late.tolist()])
+        e_attn = rel_l2(taps["attn"].cpu()[late], ref_attn.reshape(len(late), -1))
+        print(f"  layer-0 attention of rows {late.tolist()} rel-L2 {e_attn:.2e}", flush=True)
+        assert e_attn <= H.REL_L2_TOL
 
-    # -- whole stage on a sample: prefix of the chunk + 8 decode sequences
-    prefix = 320
-    dec = list(range(1, 129, 16))
-    sub_dec, rows_dec, pool_dec = H.sub_problem(shape, mb, dec, 0, dtype=torch.float32, draw_device="cuda:0")
+    # -- whole stage at full depth: the whole chunk + 16 decode sequences
+    chunk = mb.q_lens[0]
+    dec = list(range(1, 129, 8))
+    sub_dec, rows_dec, pool_dec = H.sub_problem(shape, mb, dec, seed, dtype=torch.float32, draw_device="cuda:0")
     osh = oracle_shape(shape)
     ref_dec, _ = oracle.stage_forward(osh, layers, hidden[rows_dec], sub_dec.positions, sub_dec.q_lens, sub_dec.ctx_lens,
                                       sub_dec.block_tables, pool_dec, dtype=torch.float32)
     s1 = H.check_output(out[rows_dec.cuda()], ref_dec, "qwen2 decode rows")
-    mbp = synth.make_microbatch([prefix], [0], seed=1, paging="identity")
+    mbp = synth.make_microbatch([chunk], [0], seed=1, paging="identity")
     poolp = oracle.new_pool(osh, mbp.num_kv_blocks, dtype=torch.float32)
-    ref_pre, _ = oracle.stage_forward(osh, layers, hidden[:prefix], mbp.positions, [prefix], [0], mbp.block_tables,
+    ref_pre, _ = oracle.stage_forward(osh, layers, hidden[:chunk], mbp.positions, [chunk], [0], mbp.block_tables,
                                       poolp, dtype=torch.float32)
-    s2 = H.check_output(out[:prefix], ref_pre, "qwen2 prefill prefix")
-    print(f"  decode rows rel-L2 {s1['rel_l2']:.3e}; prefill prefix rel-L2 {s2['rel_l2']:.3e} max-abs {s2['max_abs']:.3e} "
-          f"rms {s2['rms']:.2f}", flush=True)
+    s2 = H.check_output(out[:chunk], ref_pre, "qwen2 prefill chunk")
+    worst = max(rel_l2(out[lo:lo + 256].cpu(), ref_pre[lo:lo + 256]) for lo in range(0, chunk, 256))
+    print(f"  decode rows rel-L2 {s1['rel_l2']:.3e} max-abs {s1['max_abs']:.3e}; prefill chunk rel-L2 {s2['rel_l2']:.3e} "
+          f"(worst run of 256 rows {worst:.3e}) max-abs {s2['max_abs']:.3e} rms {s2['rms']:.2f}", flush=True)
+    # the margin the automatic mode (half activations from five layers) is there for
+    for stt in (s1, s2):
+        assert stt["rel_l2"] <= 6e-3 and stt["max_abs"] <= 0.7 * H.MAX_ABS_TOL * max(1.0, stt["rms"])
+    assert worst <= 6e-3
     st.close()
 
 
 @pytest.fixture(scope="module")
 def llama3_layers():
-    """bf16 weights of the 20-layer Llama-3-70B-shaped stage, drawn once on the GPU (34 GB)."""
+    """bf16 weights of the 20-layer Llama-3-70B-shaped stage, drawn once on the GPU (34 GB), and the same values
+    widened to fp32 on the host for the oracle (the oracle widens whatever it is given; handing it fp32 saves it
+    twenty 3 GB conversions per run)."""
     shape = synth.LLAMA3_70B_STAGE
-    layers = []
+
+    class Weights(list):
+        host = None
+
+    layers = Weights()
     for l in range(shape.num_layers):
         layers.append(synth.draw_layer_weights(shape, l, seed=0, device="cuda:0"))
-        print(f"  weights of layer {l} drawn", flush=True)
+    print("  weights of 20 layers drawn", flush=True)
+    layers.host = [{k: v.cpu().float() for k, v in w.items()} for w in layers]
+    print("  host copies ready", flush=True)
     yield layers
+    layers.host = None
     layers.clear()
     torch.cuda.empty_cache()
 
@@ -504,8 +574,14 @@ def _stage_70b(shape, mb, layers_dev, activation_planes=0):
                       max_seqs=mb.num_seqs, max_blocks_per_seq=mb.max_blocks_per_seq,
                       activation_planes=activation_planes)
     st = Stage(cfg, layers_dev[: shape.num_layers], device="cuda:0")
-    H.fill_pool(st, shape, mb, 0, progress=True)
+    H.fill_pool(st, shape, mb, 0, progress=False)
+    print("  KV pool filled", flush=True)
     return st
+
+
+def _spread(first, last, n):
+    """n sequence indices spread evenly over first .. last (both included)."""
+    return sorted({first + round(i * (last - first) / (n - 1)) for i in range(n)})
 
 
 def _check_sampled(shape, mb, st, layers_dev, seqs, what, stratified=False):
@@ -514,17 +590,18 @@ def _check_sampled(shape, mb, st, layers_dev, seqs, what, stratified=False):
     assert torch.isfinite(out.float()).all()
     print("  GPU forward done", flush=True)
     sub, rows, pool = H.sub_problem(shape, mb, seqs, 0, dtype=torch.float32, draw_device="cuda:0")
-    layers = [{k: v.cpu() for k, v in layers_dev[l].items()} for l in range(shape.num_layers)]
+    layers = layers_dev.host[: shape.num_layers]
     hidden = synth.draw_hidden(shape, mb.num_tokens, seed=0)[rows]
-    print("  oracle inputs ready", flush=True)
+    print(f"  oracle inputs ready ({len(seqs)} sequences, {sub.num_tokens} rows)", flush=True)
     ref, _ = oracle.stage_forward(oracle_shape(shape), layers, hidden, sub.positions, sub.q_lens, sub.ctx_lens,
                                   sub.block_tables, pool, dtype=torch.float32)
     if stratified:
         # The prefill chunk is taken whole (weight 1); the sampled decode rows stand for all decode rows.
         # Two references: the oracle as everywhere else (appended K/V kept unrounded in its pool), gated on
         # the whole-output rel-L2; and the oracle with appended K/V rounded once to the cache's bf16, which
-        # is what any reader of a bf16 cache sees, gated on rel-L2 and max-abs.  In a 20-layer stage the
-        # rows of a prefill chunk with a short cached prefix are dominated by that one rounding.
+        # is what any reader of a bf16 cache sees, gated on rel-L2 - of the whole output and of every stratum
+        # on its own - and on max-abs.  In a 20-layer stage the rows of a prefill chunk with a short cached
+        # prefix are dominated by that one rounding.
         n_pre = sub.q_lens[0]
         n_dec_pop = sum(1 for q in mb.q_lens if q == 1)
         strata = [(slice(0, n_pre), n_pre), (slice(n_pre, None), n_dec_pop)]
@@ -532,7 +609,7 @@ def _check_sampled(shape, mb, st, layers_dev, seqs, what, stratified=False):
         _, _, pool2 = H.sub_problem(shape, mb, seqs, 0, dtype=torch.float32, draw_device="cuda:0")
         ref2, _ = oracle.stage_forward(oracle_shape(shape), layers, hidden, sub.positions, sub.q_lens, sub.ctx_lens,
                                        sub.block_tables, pool2, dtype=torch.float32, kv_store_dtype=torch.bfloat16)
-        s2 = H.check_output_stratified(out[rows.cuda()], ref2, strata, what + " (bf16 cache writes)")
+        s2 = H.check_output_stratified(out[rows.cuda()], ref2, strata, what + " (bf16 cache writes)", gate_strata=True)
         for tag, st_ in (("unrounded appends", s1), ("bf16 cache writes", s2)):
             print(f"  {what} vs oracle with {tag}: whole-output rel-L2 {st_['rel_l2']:.3e} (prefill rows "
                   f"{st_['per_stratum'][0]:.3e}, decode rows {st_['per_stratum'][1]:.3e}) max-abs {st_['max_abs']:.3e} "
@@ -542,39 +619,41 @@ def _check_sampled(shape, mb, st, layers_dev, seqs, what, stratified=False):
     print(f"  {what}: rel-L2 {stats['rel_l2']:.3e} max-abs {stats['max_abs']:.3e} rms {stats['rms']:.3f}", flush=True)
 
 
-@pytest.mark.timeout(1100)
+@pytest.mark.timeout(600)
 def test_llama3_70b_stage_sampled_rows_at_full_size(llama3_layers):
-    """256 decode tokens, contexts up to 8192, 20 layers, 8 query heads per KV head: 4 sequences row by row."""
+    """256 decode tokens, contexts up to 8192, 20 layers, 8 query heads per KV head: 16 sequences row by row."""
     shape, mb = synth.workload("llama3-70b", seed=0)
     print(f"[case] {shape.name} T={mb.num_tokens} blocks={mb.num_kv_blocks}", flush=True)
     st = _stage_70b(shape, mb, llama3_layers)
-    _check_sampled(shape, mb, st, llama3_layers, [0, 85, 170, 255], "llama3-70b sampled rows")
+    _check_sampled(shape, mb, st, llama3_layers, _spread(0, 255, 16), "llama3-70b sampled rows")
     st.close()
 
 
-@pytest.mark.timeout(1100)
-def test_sweep_budget_256_at_full_depth(llama3_layers):
-    """Token budget 256 at 1 prefill : 4 decode on the 20-layer stage: the whole prefill chunk (which has a
-    cached prefix) and 3 decode sequences, row by row."""
-    shape, mb = synth.workload("sweep", seed=0, budget=256)
-    print(f"[case] sweep-256 {shape.name} T={mb.num_tokens} q0={mb.q_lens[0]} ctx0={mb.ctx_lens[0]} blocks={mb.num_kv_blocks}",
-          flush=True)
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("budget", [64, 128, 256, 512])
+def test_sweep_budgets_at_full_depth(llama3_layers, budget):
+    """Token budgets 64 to 512 at 1 prefill : 4 decode on the 20-layer stage: the whole prefill chunk (which may
+    have a cached prefix) and 16 decode sequences, row by row."""
+    shape, mb = synth.workload("sweep", seed=0, budget=budget)
+    print(f"[case] sweep-{budget} {shape.name} T={mb.num_tokens} q0={mb.q_lens[0]} ctx0={mb.ctx_lens[0]} "
+          f"blocks={mb.num_kv_blocks}", flush=True)
     st = _stage_70b(shape, mb, llama3_layers)
-    _check_sampled(shape, mb, st, llama3_layers, [0, 1, 100, 205], "sweep-256", stratified=True)
+    _check_sampled(shape, mb, st, llama3_layers, [0] + _spread(1, mb.num_seqs - 1, 16), f"sweep-{budget}", stratified=True)
     st.close()
 
 
-@pytest.mark.timeout(1100)
-@pytest.mark.parametrize("planes", [2, 3])
-def test_sweep_budget_2048_depth_reduced(llama3_layers, planes):
-    """Token budget 2048 needs more KV than one GPU holds at 20 layers; parity runs on the first 4 layers, in
-    the two modes that carry more than a bfloat16 plane: two planes, and half activations (what the 20-layer
-    stage takes; its second plane on the q/k/v input is covered at full depth by the budget-256 case)."""
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("budget,planes", [(1024, 4), (2048, 4), (2048, 2)])
+def test_sweep_budgets_1024_and_2048_depth_reduced(llama3_layers, budget, planes):
+    """Token budgets 1024 and 2048 need more KV than one GPU holds at 20 layers; parity runs on the first 4 layers,
+    in the mode the 20-layer stage takes by itself (half activations with the second plane of the q/k/v input;
+    its full depth is covered by the budgets up to 512), and at 2048 also with two planes."""
     import dataclasses
-    shape, mb = synth.workload("sweep", seed=0, budget=2048)
+    shape, mb = synth.workload("sweep", seed=0, budget=budget)
     shape = dataclasses.replace(shape, num_layers=4, name=shape.name + "-4layers")
-    print(f"[case] sweep-2048 {shape.name} T={mb.num_tokens} q0={mb.q_lens[0]} ctx0={mb.ctx_lens[0]} blocks={mb.num_kv_blocks}",
-          flush=True)
+    print(f"[case] sweep-{budget} {shape.name} T={mb.num_tokens} q0={mb.q_lens[0]} ctx0={mb.ctx_lens[0]} "
+          f"blocks={mb.num_kv_blocks}", flush=True)
     st = _stage_70b(shape, mb, llama3_layers, activation_planes=planes)
-    _check_sampled(shape, mb, st, llama3_layers, [0, 1, 800, 1638], f"sweep-2048 (4 layers, mode {planes})", stratified=True)
+    _check_sampled(shape, mb, st, llama3_layers, [0] + _spread(1, mb.num_seqs - 1, 16),
+                   f"sweep-{budget} (4 layers, mode {planes})", stratified=True)
     st.close()
