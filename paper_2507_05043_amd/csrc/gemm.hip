@@ -53,6 +53,56 @@ __device__ __forceinline__ void sched_step() {
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 
+// Epilogue of a wave's MT x NT block of 32x32 accumulator tiles whose first row / column are m_base / n_base.
+// Accumulator register r of lane l is C[row 8*(r/4) + 4*(l/32) + r%4][col l%32] of its tile.
+template <int EPI, bool SPLIT, int MT, int NT>
+__device__ __forceinline__ void tile_epilogue(const GemmArgs& p, f32x16 (&acc)[MT][NT], int m_base, int n_base, int nv,
+                                              int split, int lane) {
+  const int col_in_tile = lane & 31;
+  const int row_base = (lane >> 5) * 4;
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int m = m_base + i * 32 + 8 * (r / 4) + row_base + (r % 4);
+      if (m >= p.m) continue;
+      if constexpr (SPLIT) {
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+          const int v = n_base + j * 32 + col_in_tile;
+          if (v < nv) p.partial[((size_t)split * p.m + m) * nv + v] = acc[i][j][r];
+        }
+      } else if constexpr (EPI == kEpiSwiGLU) {
+#pragma unroll
+        for (int j = 0; j < NT; j += 2) {
+          const int v = n_base + j * 32 + col_in_tile;   // gate column; its up column is 32 further
+          const int f = (v >> 6) * 32 + (v & 31);
+          if (f < p.n) {
+            const float val = silu_f(acc[i][j][r]) * acc[i][j + 1][r];
+            const e16 hi = f32_to_act(val, p.out_half);
+            p.out_e16[(size_t)m * p.ldo + f] = hi;
+            if (p.out_lo) p.out_lo[(size_t)m * p.ldo + f] = f32_to_e16(val - e16_to_f32(hi));
+          }
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+          const int n = n_base + j * 32 + col_in_tile;
+          if (n >= p.n) continue;
+          const float c = acc[i][j][r];
+          if constexpr (EPI == kEpiStoreF32) {
+            p.out_f32[(size_t)m * p.ldo + n] = c;
+          } else if constexpr (EPI == kEpiResidualF32) {
+            p.resid[(size_t)m * p.n + n] += c;
+          } else {
+            p.out_e16[(size_t)m * p.ldo + n] = f32_to_e16(p.resid[(size_t)m * p.n + n] + c);
+          }
+        }
+      }
+    }
+  }
+}
+
 // Workgroup of 4 waves (2 x 2); wave tile (BM/2) x (BN/2) made of 32x32 MFMA tiles; K tile of 64.
 //
 // Tiles go from global memory straight into LDS (global_load_lds_dwordx4: each lane's 16 bytes land at
@@ -288,50 +338,201 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(GemmAr
     wait_vmcnt<0>();   // nothing may still be writing LDS when the workgroup ends
   }
 
-  // Epilogue.  Accumulator register r of lane l is C[row 8*(r/4) + 4*(l/32) + r%4][col l%32] of its tile.
-  const int col_in_tile = lane & 31;
-  const int row_base = (lane >> 5) * 4;
+  tile_epilogue<EPI, SPLIT, MT, NT>(p, acc, m0 + wm * TM, n0 + wn * TN, nv, split, lane);
+}
+
+// The 256 x 256 tile on K tiles of 32.
+//
+// What holds the matrix pipe of the tiles above back is LDS traffic: a ds_read_b128 occupies LDS for 12 clocks
+// instead of 8 while tile fills arrive (counters), about 85 bytes per clock, and at full MFMA rate a 128 x 256 tile
+// asks for 96 bytes per clock of fragment reads plus 48 of fills.  A 2 x 2 arrangement of 128 x 128 wave tiles
+// reads 64 + 32.  Its stages are too large for three of them at a K tile of 64 (the two-stage pipeline of
+// gemm_tile_kernel<256, 256> must refill a stage in one burst), so this kernel halves the K tile instead: rows of
+// 64 bytes, stages of 32 KB, four of them, three tiles in flight, the next tile's loads spread over the first
+// MFMA step.  One load instruction fills 16 rows; chunk c (16 bytes) of row r sits at position c ^ ((r >> 1) & 3),
+// which makes the 128-bit fragment reads of eight consecutive rows conflict free.
+constexpr int kBK32 = 32;
+
+template <int EPI, bool SPLIT, bool A_HALF>
+__global__ __launch_bounds__(256) void gemm_tile32_kernel(GemmArgs p, int nv, int tiles_m, int tiles_n, int splits,
+                                                          int k_tiles_per_split) {
+  constexpr int BM = 256, BN = 256, NWAVES = 4, TM = 128, TN = 128, MT = 4, NT = 4, NSTAGE = 4;
+  constexpr int GROUPS = (BM + BN) / 16;       // 16-row groups per stage (A rows first, then B rows)
+  constexpr int NI = GROUPS / NWAVES;          // load instructions per wave per tile
+  constexpr int STAGE_BYTES = (BM + BN) * 64;
+  constexpr int KSTEPS = kBK32 / 16;
+  static_assert(NSTAGE * STAGE_BYTES <= 160 * 1024 && KSTEPS == 2, "stages must fit in LDS");
+  using Lds = LdsStages<STAGE_BYTES>;
+
+  const int total = tiles_m * tiles_n * splits;
+  const int lid = xcd_logical_id(blockIdx.x, total);
+  if (lid < 0) return;
+  int tile_m, tile_n, split;
+  if (splits == 1 && tiles_m > kBandRows) {
+    const int band_size = kBandRows * tiles_n;
+    const int band = lid / band_size, rem = lid % band_size;
+    const int rows_in_band = min(kBandRows, tiles_m - band * kBandRows);
+    tile_m = band * kBandRows + rem % rows_in_band;
+    tile_n = rem / rows_in_band;
+    split = 0;
+  } else {
+    tile_m = lid % tiles_m;
+    split = (lid / tiles_m) % splits;
+    tile_n = lid / (tiles_m * splits);
+  }
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+
+  const int k_tiles = (p.k + kBK32 - 1) / kBK32;
+  const int kt_begin = split * k_tiles_per_split;
+  const int kt_end = min(kt_begin + k_tiles_per_split, k_tiles);
+  const int nkt = kt_end - kt_begin;
+
+  // Load instruction j of this wave fills row group g = 4 j + wave: rows 16 g .. 16 g + 15 of the stage.  This
+  // lane's slot is (row 16 g + lane / 4, position lane % 4) and receives the row's chunk (lane % 4) ^ ((row >> 1) & 3).
+  const int sw_chunk = (lane & 3) ^ ((lane >> 3) & 3);
+  const int b_row0 = EPI == kEpiSwiGLU ? (n0 >> 6) * 32 : n0;
+  uint32_t g_off[NI];
 #pragma unroll
-  for (int i = 0; i < MT; ++i) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int m = m0 + wm * TM + i * 32 + 8 * (r / 4) + row_base + (r % 4);
-      if (m >= p.m) continue;
-      if constexpr (SPLIT) {
-#pragma unroll
-        for (int j = 0; j < NT; ++j) {
-          const int v = n0 + wn * TN + j * 32 + col_in_tile;
-          if (v < nv) p.partial[((size_t)split * p.m + m) * nv + v] = acc[i][j][r];
-        }
-      } else if constexpr (EPI == kEpiSwiGLU) {
-#pragma unroll
-        for (int j = 0; j < NT; j += 2) {
-          const int v = n0 + wn * TN + j * 32 + col_in_tile;   // gate column; its up column is 32 further
-          const int f = (v >> 6) * 32 + (v & 31);
-          if (f < p.n) {
-            const float val = silu_f(acc[i][j][r]) * acc[i][j + 1][r];
-            const e16 hi = f32_to_act(val, p.out_half);
-            p.out_e16[(size_t)m * p.ldo + f] = hi;
-            if (p.out_lo) p.out_lo[(size_t)m * p.ldo + f] = f32_to_e16(val - e16_to_f32(hi));
-          }
-        }
+  for (int j = 0; j < NI; ++j) {
+    const int r = 16 * (NWAVES * j + wave) + (lane >> 2);
+    if (r < BM) {
+      int gm = m0 + r;
+      gm = gm < p.m ? gm : p.m - 1;
+      g_off[j] = ((uint32_t)(gm - m0) * (uint32_t)p.lda + sw_chunk * 8) * 2u;
+    } else {
+      int row;
+      if constexpr (EPI == kEpiSwiGLU) {
+        const int v = n0 + (r - BM);
+        row = (v >> 6) * 32 + (v & 31);
       } else {
-#pragma unroll
-        for (int j = 0; j < NT; ++j) {
-          const int n = n0 + wn * TN + j * 32 + col_in_tile;
-          if (n >= p.n) continue;
-          const float c = acc[i][j][r];
-          if constexpr (EPI == kEpiStoreF32) {
-            p.out_f32[(size_t)m * p.ldo + n] = c;
-          } else if constexpr (EPI == kEpiResidualF32) {
-            p.resid[(size_t)m * p.n + n] += c;
-          } else {
-            p.out_e16[(size_t)m * p.ldo + n] = f32_to_e16(p.resid[(size_t)m * p.n + n] + c);
-          }
-        }
+        row = n0 + (r - BM);
       }
+      row = row < p.n ? row : p.n - 1;
+      g_off[j] = ((uint32_t)(row - b_row0) * (uint32_t)p.k + sw_chunk * 8) * 2u;
     }
   }
+  const size_t a_tile0 = (size_t)m0 * p.lda, b_tile0 = (size_t)b_row0 * p.k;
+
+  int zero_below[NSTAGE];
+  auto fetch = [&](auto stage_c, int idx) {
+    constexpr int S = decltype(stage_c)::value;
+    int kt = kt_begin + idx;
+    kt = kt < kt_end - 1 ? kt : kt_end - 1;
+    int k0 = kt * kBK32;
+    const int k_last = p.k - kBK32;
+    zero_below[S] = k0 > k_last ? k0 - k_last : 0;
+    k0 = k0 > k_last ? k_last : k0;
+    const char* abase = reinterpret_cast<const char*>(p.a + a_tile0 + k0);
+    const char* w0base = reinterpret_cast<const char*>(p.w0 + b_tile0 + k0);
+    const char* w1base = EPI == kEpiSwiGLU ? reinterpret_cast<const char*>(p.w1 + b_tile0 + k0) : w0base;
+    char* stage = Lds::template get<S>();
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+      const int g = NWAVES * j + wave;                          // uniform
+      // gate/up: rows 32..63 of every 64 virtual columns are up rows, i.e. groups 2 and 3 of every four
+      const char* base = g < BM / 16 ? abase : ((EPI == kEpiSwiGLU && ((g - BM / 16) & 2)) ? w1base : w0base);
+      __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(base + g_off[j]),
+                                       reinterpret_cast<uint32_t*>(stage + g * 1024), 16, 0, 0);
+    }
+  };
+  auto patch_tail = [&](auto stage_c) {
+    constexpr int S = decltype(stage_c)::value;
+    if (zero_below[S] > 0 && sw_chunk * 8 < zero_below[S]) {
+      char* stage = Lds::template get<S>();
+      const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int j = 0; j < NI; ++j) *reinterpret_cast<u32x4*>(stage + (NWAVES * j + wave) * 1024 + lane * 16) = zero;
+    }
+  };
+
+  f32x16 acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // fragment reads: lane (row l % 32, k half l / 32) of step kk wants chunk 2 kk + l / 32 of its row
+  const int frag_row = lane & 31;
+  int frag_off[KSTEPS];
+#pragma unroll
+  for (int kk = 0; kk < KSTEPS; ++kk) frag_off[kk] = frag_row * 64 + (((2 * kk + (lane >> 5)) ^ ((frag_row >> 1) & 3)) * 16);
+
+  e16x8 af[2][MT], bfr[2][NT];
+  auto read_frags = [&](auto stage_c, int s, int kk) {
+    constexpr int S = decltype(stage_c)::value;
+    const char* la = Lds::template get<S>() + wm * TM * 64;
+    const char* lb = Lds::template get<S>() + (BM + wn * TN) * 64;
+    auto read_a = [&] {
+#pragma unroll
+      for (int i = 0; i < MT; ++i) af[s][i] = *reinterpret_cast<const e16x8*>(la + i * 32 * 64 + frag_off[kk]);
+    };
+    if constexpr (!A_HALF) read_a();
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      const e16x8 w = *reinterpret_cast<const e16x8*>(lb + j * 32 * 64 + frag_off[kk]);
+      bfr[s][j] = A_HALF ? __builtin_bit_cast(e16x8, bf16x8_to_half(w)) : w;
+    }
+    if constexpr (A_HALF) read_a();
+  };
+  auto mfmas = [&](int s) {
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+        acc[i][j] = A_HALF ? mfma_32x32x16_half(__builtin_bit_cast(h16x8, af[s][i]), __builtin_bit_cast(h16x8, bfr[s][j]), acc[i][j])
+                           : mfma_32x32x16(af[s][i], bfr[s][j], acc[i][j]);
+  };
+
+  constexpr int NMFMA = MT * NT, NREAD = MT + NT;
+  // Tile idx is in stage S and the fragments of its first MFMA step are in register set 0.  The stage read in the
+  // previous step takes tile idx + 3, its loads spread over the first MFMA step; before the second (last) step all
+  // loads but those of tiles idx + 2 and idx + 3 must have landed, and the barrier that publishes tile idx + 1 also
+  // frees stage S.
+  auto step = [&](auto stage_c, int idx) {
+    constexpr int S = decltype(stage_c)::value;
+    using Next = std::integral_constant<int, (S + 1) % NSTAGE>;
+    fetch(std::integral_constant<int, (S + NSTAGE - 1) % NSTAGE>{}, idx + NSTAGE - 1);
+    read_frags(stage_c, 1, 1);
+    mfmas(0);
+    sched_step<0, NMFMA, NREAD, NI>();
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vmcnt<2 * NI>();
+    patch_tail(Next{});
+    pipeline_barrier();
+    read_frags(Next{}, 0, 0);
+    mfmas(1);
+    sched_step<0, NMFMA, NREAD, 0>();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  if (nkt > 0) {
+    fetch(std::integral_constant<int, 0>{}, 0);
+    fetch(std::integral_constant<int, 1>{}, 1);
+    fetch(std::integral_constant<int, 2>{}, 2);
+    wait_vmcnt<2 * NI>();
+    patch_tail(std::integral_constant<int, 0>{});
+    pipeline_barrier();
+    read_frags(std::integral_constant<int, 0>{}, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    int i = 0;
+    for (; i + NSTAGE <= nkt; i += NSTAGE) {
+      step(std::integral_constant<int, 0>{}, i);
+      step(std::integral_constant<int, 1>{}, i + 1);
+      step(std::integral_constant<int, 2>{}, i + 2);
+      step(std::integral_constant<int, 3>{}, i + 3);
+    }
+    if (i < nkt) step(std::integral_constant<int, 0>{}, i);
+    if (i + 1 < nkt) step(std::integral_constant<int, 1>{}, i + 1);
+    if (i + 2 < nkt) step(std::integral_constant<int, 2>{}, i + 2);
+    wait_vmcnt<0>();   // nothing may still be writing LDS when the workgroup ends
+  }
+  tile_epilogue<EPI, SPLIT, MT, NT>(p, acc, m0 + wm * TM, n0 + wn * TN, nv, split, lane);
 }
 
 // Adds the split-K partial sums (split 0 first) and applies the epilogue.  Four consecutive outputs per
@@ -609,6 +810,22 @@ hipError_t launch_tile(const GemmArgs& a, const GemmPlan& plan, hipStream_t stre
   return hipGetLastError();
 }
 
+template <int EPI, bool A_HALF>
+hipError_t launch_tile32(const GemmArgs& a, const GemmPlan& plan, hipStream_t stream) {
+  const int tiles_m = (a.m + 255) / 256;
+  const int tiles_n = (plan.nv + 255) / 256;
+  const int total = tiles_m * tiles_n * plan.splits;
+  dim3 grid(xcd_grid(total)), block(256);
+  // K tiles of 32: a split takes twice the plan's count of 64-wide K tiles
+  if (plan.splits > 1)
+    hipLaunchKernelGGL((gemm_tile32_kernel<EPI, true, A_HALF>), grid, block, 0, stream, a, plan.nv, tiles_m, tiles_n, plan.splits,
+                       2 * plan.k_tiles_per_split);
+  else
+    hipLaunchKernelGGL((gemm_tile32_kernel<EPI, false, A_HALF>), grid, block, 0, stream, a, plan.nv, tiles_m, tiles_n, 1,
+                       2 * plan.k_tiles_per_split);
+  return hipGetLastError();
+}
+
 template <int EPI>
 hipError_t launch_epi(const GemmArgs& a, const GemmPlan& plan, hipStream_t stream) {
   if (a.a_lo) {
@@ -636,7 +853,7 @@ hipError_t launch_epi(const GemmArgs& a, const GemmPlan& plan, hipStream_t strea
       // twice as many workgroups over the same splits)
       // The 128x256 tile is cut 1 x 4 among the waves here (each wave all 128 rows of a 64-column strip): every
       // weight fragment is then converted by one wave instead of two, half the conversion work per MFMA.
-      case kTile256x256: return launch_tile<128, 256, 1, 4, 3, EPI, false, true>(a, plan, stream);
+      case kTile256x256: return launch_tile32<EPI, true>(a, plan, stream);
       case kTile256x128: return launch_tile<256, 128, 2, 2, 3, EPI, false, true>(a, plan, stream);
       case kTile128x128: return launch_tile<128, 128, 2, 2, 2, EPI, false, true>(a, plan, stream);
       case kTile128x256: return launch_tile<128, 256, 1, 4, 3, EPI, false, true>(a, plan, stream);
@@ -646,7 +863,7 @@ hipError_t launch_epi(const GemmArgs& a, const GemmPlan& plan, hipStream_t strea
   }
   switch (plan.tile) {
     case kTile64x128: return launch_tile<64, 128, 2, 2, 2, EPI, false>(a, plan, stream);
-    case kTile256x256: return launch_tile<256, 256, 2, 2, 2, EPI, false>(a, plan, stream);
+    case kTile256x256: return launch_tile32<EPI, false>(a, plan, stream);
     case kTile256x128: return launch_tile<256, 128, 2, 2, 3, EPI, false>(a, plan, stream);
     case kTile128x128: return launch_tile<128, 128, 2, 2, 2, EPI, false>(a, plan, stream);
     case kTile128x256: return launch_tile<128, 256, 2, 2, 3, EPI, false>(a, plan, stream);
@@ -665,7 +882,7 @@ GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool spli
   struct Cand { int tile, bm, bn, wg_per_cu; float eff; };
   // measured relative efficiency of the tile shapes and how many workgroups of each fit on a CU (LDS)
   static const Cand cands[] = {{kTile128x256, 128, 256, 1, 1.0f}, {kTile256x128, 256, 128, 1, 0.99f},
-                               {kTile256x256, 256, 256, 1, 0.97f}, {kTile128x128, 128, 128, 2, 0.86f}};
+                               {kTile256x256, 256, 256, 1, 1.08f}, {kTile128x128, 128, 128, 2, 0.86f}};
   if (m <= 64 && !split_a && streaming) {
     plan.tile = kTileSkinny;
     plan.splits = (k + kSkinnyKS - 1) / kSkinnyKS;

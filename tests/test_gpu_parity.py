@@ -257,6 +257,16 @@ def test_large_m_tiles_and_k_tails():
     full_parity(shape, mb, 23, "fan_in", activation_planes=3, elem=torch.bfloat16, qkv_bias=True, taps=False)
 
 
+@pytest.mark.parametrize("planes", [1, 3])
+def test_the_256_square_tile_with_ragged_rows_columns_and_inner_width(planes):
+    """700 rows against a gate/up pair of 5640 features with a hidden size of 1032: the planner takes the 256 x 256
+    tile on K tiles of 32 for it (264 tiles of 128 x 256 would need a second round), and nothing divides evenly:
+    188 rows in the last tile row, 8 columns in the last tile column, 8 elements in the last K tile."""
+    shape = _shape("tile32-ragged", 1, 1032, 8, 2, 128, 5640)
+    mb = synth.make_microbatch([700], [0], seed=41, max_blocks_per_seq=44)
+    full_parity(shape, mb, 41, "fan_in", activation_planes=planes)
+
+
 def test_chunked_prefill_equals_unsplit_on_gpu():
     shape = _shape("chunks", 2, 256, 4, 2, 64, 688)
     n = 75
