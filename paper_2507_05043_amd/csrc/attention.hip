@@ -288,12 +288,19 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const Decod
 // a column is a (token, head in group) pair, column = token * g + head_in_group, so grouped heads
 // share every K/V read; wave w owns columns 32w .. 32w+31.  The four waves need the same keys, so a
 // step's K and V tiles (32 keys = two blocks) are fetched once per workgroup, straight into LDS
-// (global_load_lds), four stages deep: three steps are in flight while one is multiplied, which is
-// what hides the memory latency (a wave that loads its own operands into registers can only run one
-// step ahead).  32x32x16 MFMA.  Row m of the key tile is (block m/16, slot
+// (global_load_lds), four stages deep.  32x32x16 MFMA.  Row m of the key tile is (block m/16, slot
 // 8*((m/4)%2) + 4*((m/8)%2) + m%4): accumulator registers 0..7 of lane group G = lane/32 are then
 // slots 8G..8G+7 of the first block, registers 8..15 the same slots of the second block, i.e. the
 // S^T accumulators are the P^T operand of the PV product as they stand.
+//
+// Software pipeline inside a wave.  A step's work is a chain - scores (MFMA), their maximum, the
+// exponentials and their rounding (vector unit), the PV product (MFMA) - and a wave that walks the chain
+// in order leaves the matrix pipe idle during the vector work and the vector unit idle during the
+// products.  Here the scores of step u+1 are multiplied while the exponentials of step u are taken
+// (one basic block: the compiler interleaves the two), and the maximum of step u+1 is found while the PV
+// product of step u runs (a second block).  What is rare - moving the reference of the exponentials -
+// sits in a branch between iterations; what is occasional - the causal mask, slots past the sequence's
+// end - in a second copy of the second block, chosen per step (wave-uniform).
 //
 // LDS stage: the K tile as it lies in the pool, [block][d/32][16 positions][64 bytes] (MFMA row m of the
 // tile is position m % 16 of block m / 16; every load instruction copies one 1 KB run), with the four
@@ -302,8 +309,283 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a, const Decod
 // bytes], so that the lanes of a fragment read (32 consecutive d, one half) are contiguous.  Both
 // arrangements are made by choosing which 16 bytes each lane of a load instruction fetches.
 // ------------------------------------------------------------------------------------------------
-template <int D, bool QLO>
-__global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const PrefillTile* __restrict__ tiles,
+
+// the maximum of lane l and lane l ^ 32, on every lane, without a trip through LDS
+__device__ __forceinline__ float max_across_halves(float v) {
+  const uint32_t u = __float_as_uint(v);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+template <int D>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void attn_prefill_kernel(AttnArgs a, const PrefillTile* __restrict__ tiles,
+                                                           int num_tiles) {
+  constexpr int KS = D / 16;                 // MFMA k-steps of the QK product
+  constexpr int DT = D / 32;                 // 32-row tiles of O^T
+  constexpr int NST = 4;                     // LDS stages
+  constexpr int K_BYTES = 32 * D * 2;        // K tile
+  constexpr int STAGE_BYTES = 2 * K_BYTES;   // + V^T tiles of the same size
+  constexpr int NI = STAGE_BYTES / 1024 / 4; // load instructions per wave per stage
+  constexpr int NP = D / 32;                 // 32-element pieces per K row
+  using Lds = LdsStages<STAGE_BYTES>;
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  // Work order.  The tile list is sorted by keys seen, longest first, and every tile exists once per KV head.  Two
+  // workgroups fit on a CU; when the launch is between one and two workgroups per CU, all of them are resident at
+  // once and a CU's time is the sum of its two.  The first 256 workgroups (one per CU) take the longest tiles in
+  // order, the rest take the remaining ones shortest first, so that the longest tile shares its CU with the
+  // shortest, the second longest with the second shortest, and so on.  Larger launches keep longest-first.
+  const int total = num_tiles * a.nkv;
+  constexpr int kFirstPass = 256;
+  int pos = blockIdx.x;
+  if (total > kFirstPass && total <= 2 * kFirstPass && pos >= kFirstPass) pos = total - 1 - (pos - kFirstPass);
+  const int tile_id = pos / a.nkv;
+  const int r = pos % a.nkv;
+  const int g = a.nq / a.nkv;
+  const int row0 = __builtin_amdgcn_readfirstlane(tiles[tile_id].row0);
+  const int q_len = __builtin_amdgcn_readfirstlane(tiles[tile_id].q_len);
+  const int ctx = __builtin_amdgcn_readfirstlane(tiles[tile_id].ctx);
+  const int bt_off = __builtin_amdgcn_readfirstlane(tiles[tile_id].bt_off);
+  const int tile_col0 = __builtin_amdgcn_readfirstlane(tiles[tile_id].col0);
+  // The block table is read through the constant address space (nothing writes it during the kernel): the
+  // reads become scalar loads, which do not queue behind the tile loads in flight.
+  typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+  const const_i32_ptr bt = (const_i32_ptr)(a.bt_flat + bt_off);
+  const int total_keys = ctx + q_len;
+  const int last_block = (total_keys - 1) / kKvBlock;
+  const int ncols = q_len * g;
+
+  const int col = lane & 31, grp = lane >> 5;
+  const int col0 = tile_col0 + 32 * wave;                      // this wave's first column
+  const bool wave_active = col0 < ncols;
+  const int my_col = min(col0 + col, ncols - 1);               // padding columns repeat the last real one
+  const int tok = my_col / g, hg = my_col % g;
+  const int limit = ctx + tok;                                  // last key this column may see
+  // steps with a key visible to this wave (0 for a wave of padding columns only)
+  const int wave_steps = wave_active ? (ctx + min(col0 + 31, ncols - 1) / g) / 32 + 1 : 0;
+  const int wave_min_limit = ctx + min(col0, ncols - 1) / g;               // smallest limit among this wave's columns
+  const int nsteps = (ctx + min(tile_col0 + 127, ncols - 1) / g) / 32 + 1; // ... to the workgroup
+  const int ldq = (a.nq + 2 * a.nkv) * D;
+
+  e16x8 qf[KS];
+  {
+    const e16* qp = a.qkv + (size_t)(row0 + tok) * ldq + (r * g + hg) * D + grp * 8;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) qf[kk] = load8(qp + kk * 16);
+  }
+
+  // ---- what this lane fetches for load instruction i of its wave (instruction id j = 4 i + wave;
+  // the first K_BYTES / 1024 instructions fill the K tile, the rest the V^T tiles)
+  const size_t blk_stride = (size_t)a.nkv * kKvBlock * D;     // elements per block (all heads)
+  const size_t head_off = (size_t)r * kKvBlock * D;
+  // An instruction never straddles two blocks (4 or 8 K rows, 64 of the 2 D positions of a V block), so
+  // the block is chosen per instruction (scalar) and only the offset inside the block is per lane.
+  uint32_t ld_off[NI];     // byte offset of this lane's 16 bytes inside the (block, head) region
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int j = 4 * i + wave;
+    if (j < K_BYTES / 1024) {
+      // instruction j copies piece j % NP of block j / NP: 16 positions x 64 bytes, one run in the pool
+      const int piece = j % NP, pos16 = lane >> 2, c = lane & 3;
+      ld_off[i] = (uint32_t)((piece * kKvBlock + pos16) * 32 + ((c ^ ((pos16 >> 1) & 3)) * 8)) * 2u;
+    } else {
+      const int pos16 = (j - K_BYTES / 1024) * 64 + lane;   // 16-byte position in the V part: [block][half][d]
+      const int d = pos16 % D, half = (pos16 / D) & 1;
+      ld_off[i] = (uint32_t)(d * kKvBlock + half * 8) * 2u;
+    }
+  }
+  // Every step issues the same loads (block indices past the sequence are clamped to its last block),
+  // so the wait counts below hold without control flow around the loads.
+  auto fetch = [&](auto stage_c, int step) {
+    constexpr int S = decltype(stage_c)::value;
+    int lb0 = 2 * step, lb1 = 2 * step + 1;
+    lb0 = lb0 < last_block ? lb0 : last_block;
+    lb1 = lb1 < last_block ? lb1 : last_block;
+    const int b0 = bt[lb0], b1 = bt[lb1];
+    char* stage = Lds::template get<S>();
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int j = 4 * i + wave;                                    // uniform
+      const bool is_k = j < K_BYTES / 1024;
+      const int second = is_k ? j / NP : ((j - K_BYTES / 1024) * 64) / (2 * D);
+      const int pb = second ? b1 : b0;
+      const char* base = reinterpret_cast<const char*>((is_k ? a.k_pool : a.v_pool) + (size_t)pb * blk_stride + head_off);
+      __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(base + ld_off[i]),
+                                       reinterpret_cast<uint32_t*>(stage + j * 1024), 16, 0, 0);
+    }
+  };
+
+  f32x16 acc[DT];
+#pragma unroll
+  for (int t = 0; t < DT; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+  // m_run: reference of the exponentials (see maximum()); l_run: this lane's share of the row sum
+  float m_run = -INFINITY, l_run = 0.f;
+
+  // fragment addresses: K row m = lane % 32 is position m % 16 of block m / 16; MFMA step kk wants chunk
+  // 2 (kk % 2) + grp of piece kk / 2;  V^T row d = 32 t + lane % 32 of half grp of block b
+  const int k_pos = col & 15;
+  const int k_row_off = ((col >> 4) * NP * kKvBlock + k_pos) * 64;
+  const int k_swz = (k_pos >> 1) & 3;
+  const int v_frag_off = K_BYTES + (grp * D + col) * 16;
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+  // scores of the step whose tiles are in stage S: register e of this lane is key 32*step + 16*(e/8) + 8*grp + e%8
+  auto scores = [&](auto stage_c, f32x16& s) {
+    constexpr int S = decltype(stage_c)::value;
+    const char* stage = Lds::template get<S>();
+    s = zero16;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      const e16x8 kf = *reinterpret_cast<const e16x8*>(stage + k_row_off + (kk >> 1) * (kKvBlock * 64) +
+                                                         (((2 * (kk & 1) + grp) ^ k_swz) * 16));
+      s = mfma_32x32x16(kf, qf[kk], s);
+    }
+  };
+  // Hides the keys a column may not see (MASK) and finds the columns' new maxima; returns whether the reference of
+  // the exponentials has to move.  The reference need not be the exact running maximum: softmax does not depend on
+  // it, it only has to keep exp2(score - m_run) in range.  It is moved (and the accumulators rescaled, 16 DT
+  // multiplications per lane) only when some column's maximum has grown by more than 2^8 since; until then
+  // probabilities up to 256 are accumulated as they are.
+  auto maximum = [&](auto mask_c, f32x16& s, int step, float& m_new) {
+    constexpr bool MASK = decltype(mask_c)::value;
+    float raw_max = -INFINITY;                               // maximum of the unscaled scores (the scale is positive)
+    if constexpr (MASK) {
+      const int key_base = 32 * step + 8 * grp;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int key = key_base + 16 * (e / 8) + (e % 8);
+        s[e] = (key <= limit) ? s[e] : -INFINITY;
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 16; ++e) raw_max = fmaxf(raw_max, s[e]);
+    raw_max = max_across_halves(raw_max);
+    m_new = fmaxf(m_run, raw_max * a.scale_log2e);           // finite from step 0 on: key 0 is visible to all
+    return __builtin_amdgcn_ballot_w64(m_new > m_run + 8.0f) != 0;
+  };
+  auto move_reference = [&](float m_new) {
+    const float alpha = fast_exp2(m_run - m_new);
+    l_run *= alpha;
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[t][e] *= alpha;
+    m_run = m_new;
+  };
+  // probabilities of a step from its (masked) scores, rounded into the two P^T operands
+  auto probabilities = [&](const f32x16& s, e16x8& p0, e16x8& p1) {
+    float sv[16], psum = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      sv[e] = fast_exp2(__builtin_fmaf(s[e], a.scale_log2e, -m_run));    // (-inf) * scale - m = -inf -> 0
+      psum += sv[e];
+    }
+    l_run += psum;
+    p0 = pack8(sv);
+    p1 = pack8(sv + 8);
+  };
+  auto pv = [&](auto stage_c, auto tail_c, const e16x8& p0, const e16x8& p1, int step) {
+    constexpr int S = decltype(stage_c)::value;
+    constexpr bool TAIL = decltype(tail_c)::value;
+    const char* stage = Lds::template get<S>();
+    const int nv0 = total_keys - (32 * step + 8 * grp), nv1 = nv0 - 16;    // slots past the sequence end hold anything
+#pragma unroll
+    for (int t = 0; t < DT; ++t) {
+      e16x8 v0 = *reinterpret_cast<const e16x8*>(stage + v_frag_off + t * 512);
+      e16x8 v1 = *reinterpret_cast<const e16x8*>(stage + v_frag_off + 2 * D * 16 + t * 512);
+      if constexpr (TAIL) {
+        v0 = zero_tail(v0, nv0 < 0 ? 0 : (nv0 > 8 ? 8 : nv0));
+        v1 = zero_tail(v1, nv1 < 0 ? 0 : (nv1 > 8 ? 8 : nv1));
+      }
+      acc[t] = mfma_32x32x16(v0, p0, acc[t]);
+      acc[t] = mfma_32x32x16(v1, p1, acc[t]);
+    }
+  };
+
+  f32x16 sc[2];          // scores of the step being turned into probabilities and of the one after it
+  float m_next = -INFINITY;
+  bool move_next = false;
+  // does step `step` need the causal mask or hold slots past the sequence's end (wave-uniform)?
+  auto special = [&](int step) { return 32 * step + 31 > wave_min_limit; };
+
+  // Iteration u: the tiles of steps u and u + 1 are in their stages, the masked scores of step u are in sc[u & 1]
+  // and their maximum has been taken.  After the wait only the loads of step u + 2 can still be in flight, so this
+  // wave's part of stage (u + 1) % 4 has landed; after the barrier everybody's has, and everybody is done with
+  // stage (u - 1) % 4, which is refilled with step u + 3.
+  auto iteration = [&](auto stage_c, auto par_c, int u) {
+    constexpr int S = decltype(stage_c)::value;
+    constexpr int P = decltype(par_c)::value;
+    using Next = std::integral_constant<int, (S + 1) % NST>;
+    wait_vmcnt<NI>();
+    pipeline_barrier();
+    fetch(std::integral_constant<int, (S + NST - 1) % NST>{}, u + NST - 1);
+    if (u >= wave_steps) return;                              // nothing visible to this wave's columns any more
+    if (move_next) move_reference(m_next);
+    e16x8 p0, p1;
+    // scores of step u + 1 under the exponentials of step u
+    scores(Next{}, sc[P ^ 1]);
+    probabilities(sc[P], p0, p1);
+    __builtin_amdgcn_sched_barrier(0);
+    // the PV product of step u over the maximum of step u + 1
+    if (special(u + 1) || special(u)) {
+      pv(stage_c, std::true_type{}, p0, p1, u);
+      move_next = maximum(std::true_type{}, sc[P ^ 1], u + 1, m_next);
+    } else {
+      pv(stage_c, std::false_type{}, p0, p1, u);
+      move_next = maximum(std::false_type{}, sc[P ^ 1], u + 1, m_next);
+    }
+  };
+
+  fetch(std::integral_constant<int, 0>{}, 0);
+  fetch(std::integral_constant<int, 1>{}, 1);
+  fetch(std::integral_constant<int, 2>{}, 2);
+  // step 0: its scores and their maximum before the pipeline starts
+  wait_vmcnt<2 * NI>();
+  pipeline_barrier();
+  if (wave_steps > 0) {
+    scores(std::integral_constant<int, 0>{}, sc[0]);
+    move_next = maximum(std::true_type{}, sc[0], 0, m_next);
+  }
+  for (int u = 0; u < nsteps; u += NST) {
+    iteration(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, u);
+    iteration(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{}, u + 1);
+    iteration(std::integral_constant<int, 2>{}, std::integral_constant<int, 0>{}, u + 2);
+    iteration(std::integral_constant<int, 3>{}, std::integral_constant<int, 1>{}, u + 3);
+  }
+  wait_vmcnt<0>();   // nothing may still be writing LDS when the workgroup ends
+
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (col0 + col < ncols) {
+    const float inv = 1.0f / l_tot;
+    const size_t at = (size_t)(row0 + tok) * a.nq * D + (r * g + hg) * D + 4 * grp;
+#pragma unroll
+    for (int t = 0; t < DT; ++t) {
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        e16x4 ob, ol;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float val = acc[t][q4 * 4 + e] * inv;
+          ob[e] = f32_to_act(val, a.out_half);
+          ol[e] = f32_to_e16(val - e16_to_f32(ob[e]));
+        }
+        *reinterpret_cast<e16x4*>(a.out + at + t * 32 + q4 * 8) = ob;
+        if (a.out_lo) *reinterpret_cast<e16x4*>(a.out_lo + at + t * 32 + q4 * 8) = ol;
+      }
+    }
+  }
+}
+
+// The same tiles for queries carried as two planes (q = hi + lo, every score takes both products): the steps of a
+// tile are walked one after the other, each step's scores, softmax and PV product in order.  With twice the score
+// MFMAs and the second plane's fragments in registers, the software-pipelined kernel above runs out of registers at
+// two waves per SIMD and was measured slower on these launches (116 against 80 us on the 2048-token chunk of the
+// Qwen2-shaped stage); overlap here comes from the second workgroup on the CU.
+template <int D>
+__global__ __launch_bounds__(256) void attn_prefill_two_plane_kernel(AttnArgs a, const PrefillTile* __restrict__ tiles,
                                                            int num_tiles) {
   constexpr int KS = D / 16;                 // MFMA k-steps of the QK product
   constexpr int DT = D / 32;                 // 32-row tiles of O^T
@@ -352,16 +634,14 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
   const int nsteps = (ctx + min(tile_col0 + 127, ncols - 1) / g) / 32 + 1; // ... to the workgroup
   const int ldq = (a.nq + 2 * a.nkv) * D;
 
-  e16x8 qf[KS], qf_lo[QLO ? KS : 1];
+  e16x8 qf[KS], qf_lo[KS];
   {
     const e16* qp = a.qkv + (size_t)(row0 + tok) * ldq + (r * g + hg) * D + grp * 8;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) qf[kk] = load8(qp + kk * 16);
-    if constexpr (QLO) {
-      const e16* ql = a.q_lo + ((size_t)(row0 + tok) * a.nq + r * g + hg) * D + grp * 8;
+    const e16* ql = a.q_lo + ((size_t)(row0 + tok) * a.nq + r * g + hg) * D + grp * 8;
 #pragma unroll
-      for (int kk = 0; kk < KS; ++kk) qf_lo[kk] = load8(ql + kk * 16);
-    }
+    for (int kk = 0; kk < KS; ++kk) qf_lo[kk] = load8(ql + kk * 16);
   }
 
   // ---- what this lane fetches for load instruction i of its wave (instruction id j = 4 i + wave;
@@ -430,7 +710,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
       const e16x8 kf = *reinterpret_cast<const e16x8*>(stage + k_row_off + (kk >> 1) * (kKvBlock * 64) +
                                                          (((2 * (kk & 1) + grp) ^ k_swz) * 16));
       s = mfma_32x32x16(kf, qf[kk], s);
-      if constexpr (QLO) s = mfma_32x32x16(kf, qf_lo[kk], s);
+      s = mfma_32x32x16(kf, qf_lo[kk], s);     // second query plane into the same scores
     }
     // register e of this lane is key 32*step + 16*(e/8) + 8*grp + e%8
     const int key_base = 32 * step + 8 * grp;
@@ -450,7 +730,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
         raw_max = fmaxf(raw_max, sv[e]);
       }
     }
-    raw_max = fmaxf(raw_max, __shfl_xor(raw_max, 32, 64));
+    raw_max = max_across_halves(raw_max);
     const float m_new = fmaxf(m_run, raw_max * a.scale_log2e);   // finite from step 0 on: key 0 is visible to all
     // The reference m_run of the exponentials need not be the exact running maximum: softmax does not
     // depend on it, it only has to keep exp2(score - m_run) in range.  It is moved (and the accumulators
@@ -537,11 +817,11 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a, const Pre
 hipError_t launch_attn_prefill(const AttnArgs& a, const PrefillTile* tiles, int num_tiles, hipStream_t stream) {
   dim3 grid(num_tiles * a.nkv), block(256);
   if (a.head_dim == 128) {
-    if (a.q_lo) hipLaunchKernelGGL((attn_prefill_kernel<128, true>), grid, block, 0, stream, a, tiles, num_tiles);
-    else hipLaunchKernelGGL((attn_prefill_kernel<128, false>), grid, block, 0, stream, a, tiles, num_tiles);
+    if (a.q_lo) hipLaunchKernelGGL((attn_prefill_two_plane_kernel<128>), grid, block, 0, stream, a, tiles, num_tiles);
+    else hipLaunchKernelGGL((attn_prefill_kernel<128>), grid, block, 0, stream, a, tiles, num_tiles);
   } else {
-    if (a.q_lo) hipLaunchKernelGGL((attn_prefill_kernel<64, true>), grid, block, 0, stream, a, tiles, num_tiles);
-    else hipLaunchKernelGGL((attn_prefill_kernel<64, false>), grid, block, 0, stream, a, tiles, num_tiles);
+    if (a.q_lo) hipLaunchKernelGGL((attn_prefill_two_plane_kernel<64>), grid, block, 0, stream, a, tiles, num_tiles);
+    else hipLaunchKernelGGL((attn_prefill_kernel<64>), grid, block, 0, stream, a, tiles, num_tiles);
   }
   return hipGetLastError();
 }
