@@ -24,8 +24,10 @@ if ROOT not in sys.path:
 # same counter reads for a plain 1 GiB copy (profiles/hbm_traffic_*.md).  A figure is only reported while the
 # kernel source it was taken on is unchanged.
 MEASURED_TRAFFIC = {
-    ("attn_decode", "llama2-7b", 0): {"bytes": 1.2971e9 + 4.6096e6, "source": "csrc/attention.hip",
-                                      "sha256_16": "f25008a04b495be7"},
+    ("attn_decode", "llama3-70b", 0): {"bytes": 4.92989e9 + 3.74436e7, "source": "csrc/attention.hip",
+                                       "sha256_16": "d82dda83caa0755c"},
+    ("attn_decode", "llama2-7b", 0): {"bytes": 1.29924e9 + 4.60947e6, "source": "csrc/attention.hip",
+                                      "sha256_16": "d82dda83caa0755c"},
 }
 
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
@@ -206,7 +208,7 @@ def run_workload(args, workload, budget, steps, warmup, extras):
 
     # the oracle baseline is timed on the benchmark configuration
     if extras and not args.no_cpu_baseline and not w4 and args.dtype == "bf16":
-        sample = {"tiny": mb.num_seqs, "llama2-7b": 64, "qwen2-7b": 8, "llama3-70b": 4, "sweep": 4}[workload]
+        sample = {"tiny": mb.num_seqs, "llama2-7b": 64, "qwen2-7b": 8, "llama3-70b": 16, "sweep": 8}[workload]
         result["cpu_baseline"] = cpu_baseline(shape, mb, args.seed, sample)
     st.close()
     del st, hidden, out
