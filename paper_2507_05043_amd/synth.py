@@ -136,6 +136,7 @@ class StageShape:
     rope_theta: float = 1e4
     kv_block_size: int = 16
     vocab: int = 0          # vocabulary size of the model the stage is cut from (embedding / output head)
+    rotary_dim: int = 0     # 0: whole heads rotate; else only the first rotary_dim elements of every head
 
     @property
     def qkv_out(self) -> int:

@@ -17,7 +17,10 @@ def matvec(w, x):
     return [sum(w[o][i] * x[i] for i in range(len(x))) for o in range(len(w))]
 
 
-def rope_head(u, p, theta):
+def rope_head(u, p, theta, rotary_dim=0):
+    """rotary_dim > 0: only u[:rotary_dim] rotates (as a head of that size), the rest is copied."""
+    if rotary_dim and rotary_dim < len(u):
+        return rope_head(u[:rotary_dim], p, theta) + list(u[rotary_dim:])
     d = len(u)
     half = d // 2
     y = [0.0] * d
@@ -46,8 +49,9 @@ def layer_one_sequence(shape, w, rows, pos, cache_k, cache_v):
         if w.get("qnorm") is not None:            # per-head norm of queries and keys, before the rotation
             qh = [rmsnorm_row(u, w["qnorm"], shape.rms_eps) for u in qh]
             kh = [rmsnorm_row(u, w["knorm"], shape.rms_eps) for u in kh]
-        q = [rope_head(u, pos[n], shape.rope_theta) for u in qh]
-        k = [rope_head(u, pos[n], shape.rope_theta) for u in kh]
+        rd = getattr(shape, "rotary_dim", 0)
+        q = [rope_head(u, pos[n], shape.rope_theta, rd) for u in qh]
+        k = [rope_head(u, pos[n], shape.rope_theta, rd) for u in kh]
         v = [qkv[(nq + nkv + r) * d:(nq + nkv + r + 1) * d] for r in range(nkv)]
         cache_k.append(k)
         cache_v.append(v)

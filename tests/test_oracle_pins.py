@@ -345,6 +345,67 @@ def test_rows_independent_of_batch_composition_and_order():
     assert torch.allclose(out_1, out[cu[s]:cu[s + 1]], rtol=1e-12, atol=1e-13)
 
 
+# ---------------------------------------------------------------- partial rotary
+
+@pytest.mark.parametrize("nq,nkv,rd", [(4, 2, 4), (3, 3, 2), (4, 1, 6)])
+def test_partial_rotary_matches_scalar_loops(nq, nkv, rd):
+    shape = small_shape(num_q_heads=nq, num_kv_heads=nkv, hidden=12, ffn=20, head_dim=8, kv_block_size=4, rotary_dim=rd)
+    q_lens, ctx_lens = [5, 1, 3], [0, 6, 2]
+    mb = synth.make_microbatch(q_lens, ctx_lens, seed=3, block=4)
+    layers = draw_layers(shape, 3, "fan_in")
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=3)
+    pool = oracle_pool(shape, mb, 3)
+    pool0 = pool.clone()
+    out, _, _ = run_oracle(shape, mb, layers=layers, hidden=hidden, pool=pool)
+    got, row0 = [], 0
+    x_rows = hidden.double().tolist()
+    for s, (q, c) in enumerate(zip(q_lens, ctx_lens)):
+        rows = x_rows[row0:row0 + q]
+        for l in range(shape.num_layers):
+            w = {k: v.double().tolist() for k, v in layers[l].items()}
+            ck, cv = [], []
+            for j in range(c):
+                blk = int(mb.block_tables[s][j // 4])
+                ck.append(pool0[l, 0, blk, j % 4].tolist())
+                cv.append(pool0[l, 1, blk, j % 4].tolist())
+            rows = brute_force.layer_one_sequence(shape, w, rows, list(range(c, c + q)), ck, cv)
+        got.extend(rows)
+        row0 += q
+    got = torch.tensor(got, dtype=F64)
+    assert torch.allclose(out, got, rtol=1e-10, atol=1e-11), float((out - got).abs().max())
+
+
+def test_partial_rotary_rotates_a_head_of_its_own_size_and_passes_the_rest():
+    import dataclasses
+    shape = small_shape(num_layers=1, head_dim=16)
+    mb = synth.make_microbatch([6, 1], [0, 9], seed=6, block=shape.kv_block_size)
+    layers = draw_layers(shape, 6, "fan_in")
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=6)
+    full, whole, part = [], [], []
+    run_oracle(shape, mb, seed=6, layers=layers, hidden=hidden, taps=full)
+    run_oracle(dataclasses.replace(shape, rotary_dim=16), mb, seed=6, layers=layers, hidden=hidden, taps=whole)
+    run_oracle(dataclasses.replace(shape, rotary_dim=8), mb, seed=6, layers=layers, hidden=hidden, taps=part)
+    # rotary_dim = head_dim is the default, bit for bit
+    assert torch.equal(whole[0]["x"], full[0]["x"]) and torch.equal(whole[0]["q"], full[0]["q"])
+    nq, nkv, d = shape.num_q_heads, shape.num_kv_heads, shape.head_dim
+    pre = part[0]["a"] @ layers[0]["wqkv"].double().T
+    pos = torch.as_tensor(mb.positions)
+    t = pre.shape[0]
+    for name, lo, n in (("q", 0, nq), ("k", nq * d, nkv)):
+        u = pre[:, lo: lo + n * d].reshape(t, n, d)
+        got = part[0][name]
+        assert torch.equal(got[..., 8:], u[..., 8:])                                    # the rest passes through
+        assert torch.equal(got[..., :8], oracle.rope_rotate(u[..., :8].contiguous(), pos, shape.rope_theta))
+        # the angle of pair (i, i + 4) is pos * theta**(-2i/8): element 1 of a unit vector at position 3
+        ang = 3 * shape.rope_theta ** (-2.0 * 1 / 8)
+        e = torch.zeros(1, 1, d, dtype=F64); e[0, 0, 1] = 1.0
+        z = oracle.rope_rotate(e, torch.tensor([3]), shape.rope_theta, 8)[0, 0]
+        assert math.isclose(float(z[1]), math.cos(ang), rel_tol=1e-14) and math.isclose(float(z[5]), math.sin(ang), rel_tol=1e-14)
+        assert float(z.abs().sum()) == pytest.approx(abs(math.cos(ang)) + abs(math.sin(ang)), rel=1e-14)
+    assert torch.equal(part[0]["v"], full[0]["v"])
+    assert not torch.allclose(part[0]["x"], full[0]["x"], rtol=1e-3)
+
+
 # ---------------------------------------------------------------- the cache as a store of a narrower type
 
 def test_cache_store_type_as_wide_as_the_arithmetic_changes_nothing():
