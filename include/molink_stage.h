@@ -99,6 +99,11 @@ typedef struct {
   int32_t weight_group_size;   /* weight_bits == 4 only: 32, 64 or 128 consecutive input features share one
                                   scale and one zero point; hidden, num_q_heads*head_dim and ffn must be
                                   multiples of it.  Otherwise 0. */
+  int32_t rotary_dim;          /* 0 (or head_dim): whole heads rotate.  Otherwise a multiple of 16 below head_dim: only
+                                  the first rotary_dim elements of every query and key head rotate, as a head of that
+                                  size would (pairs (i, i + rotary_dim/2), angle position * theta^(-2i/rotary_dim)); the
+                                  rest pass through unrotated.  The GLM / ChatGLM families of the paper's model table
+                                  (section 3.1.3) rotate half of each head.  Not together with qnorm / knorm. */
 } stage_config;
 
 /* Device pointers to one layer's weights, row-major [out_features][in_features], bf16 unless

@@ -80,14 +80,18 @@ __global__ __launch_bounds__(256) void rope_table_kernel(const int32_t* __restri
 // One workgroup per token row.  Work units of 8 elements:
 //   rotated heads (q then k): unit = (head, chunk of 8 pairs): reads the fp32 halves, rotates, rounds to
 //   e16 once, writes the e16 row and, for k heads, also the K pool row of the token's slot;
+//   with a partial rotary embedding, the elements of q and k heads past rotary_dim: unit = (head, chunk of 8),
+//   rounded and written like the rotated ones, unrotated;
 //   v heads: unit = (head, chunk of 8 dims): rounded once and scattered into the transposed V block.
 __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs p) {
   const int t = blockIdx.x;
   const int u = blockIdx.y * 256 + threadIdx.x;                  // one unit of 8 (rotated: 8 pairs) per thread
-  const int d = p.head_dim, half = d / 2, cpr = half / 8;       // chunks per rotated head
+  const int d = p.head_dim, half = p.rotary_dim / 2, cpr = half / 8;       // chunks per rotated head
+  const int ppr = (d - p.rotary_dim) / 8;                                    // unrotated chunks per q / k head
   const int rot_units = (p.nq + p.nkv) * cpr;
+  const int pass_units = (p.nq + p.nkv) * ppr;
   const int v_units = p.nkv * (d / 8);
-  if (u >= rot_units + v_units) return;
+  if (u >= rot_units + pass_units + v_units) return;
   const int row_elems = (p.nq + 2 * p.nkv) * d;
   const float* src = p.qkv_f32 + (size_t)t * row_elems;
   e16* row = p.qkv + (size_t)t * row_elems;
@@ -155,8 +159,26 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs p) {
       store8(dst + k_offset_in_block(s, c * 8), olo);
       store8(dst + k_offset_in_block(s, half + c * 8), ohi);
     }
-  } else {
+  } else if (u < rot_units + pass_units) {
     const int w = u - rot_units;
+    const int head = w / ppr, at = p.rotary_dim + (w % ppr) * 8;     // element of the head this unit starts at
+    float v[8];
+    load8f(src + head * d + at, v);
+    e16x8 hi, lo;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      hi[e] = f32_to_e16(v[e]);
+      lo[e] = f32_to_e16(v[e] - e16_to_f32(hi[e]));
+    }
+    store8(row + head * d + at, hi);
+    if (head < p.nq) {
+      if (p.q_lo) store8(p.q_lo + ((size_t)t * p.nq + head) * d + at, lo);
+    } else {
+      e16* dst = p.k_pool + ((size_t)blk * p.nkv + (head - p.nq)) * kKvBlock * d;
+      store8(dst + k_offset_in_block(s, at), hi);
+    }
+  } else {
+    const int w = u - rot_units - pass_units;
     const int r = w / (d / 8), c = w % (d / 8);
     float v[8];
     load8f(src + (p.nq + p.nkv + r) * d + c * 8, v);
@@ -272,9 +294,9 @@ hipError_t launch_rmsnorm(const e16* in_e16, float* x, const e16* gain, e16* out
   return hipGetLastError();
 }
 
-hipError_t launch_rope_table(const int32_t* positions, float2* cos_sin, int rows, int head_dim, float theta,
+hipError_t launch_rope_table(const int32_t* positions, float2* cos_sin, int rows, int rotary_dim, float theta,
                              hipStream_t stream) {
-  const int half = head_dim / 2;
+  const int half = rotary_dim / 2;
   const int total = rows * half;
   hipLaunchKernelGGL(rope_table_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, positions, cos_sin, rows, half,
                      log2((double)theta));
@@ -282,7 +304,8 @@ hipError_t launch_rope_table(const int32_t* positions, float2* cos_sin, int rows
 }
 
 hipError_t launch_rope_append(const RopeAppendArgs& args, hipStream_t stream) {
-  const int units = (args.nq + args.nkv) * (args.head_dim / 16) + args.nkv * (args.head_dim / 8);
+  const int units = (args.nq + args.nkv) * (args.rotary_dim / 16 + (args.head_dim - args.rotary_dim) / 8) +
+                    args.nkv * (args.head_dim / 8);
   hipLaunchKernelGGL(rope_append_kernel, dim3(args.rows, (units + 255) / 256), dim3(256), 0, stream, args);
   return hipGetLastError();
 }

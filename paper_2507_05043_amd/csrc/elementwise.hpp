@@ -15,8 +15,9 @@ namespace molink {
 hipError_t launch_rmsnorm(const e16* in_e16, float* x, const e16* gain, e16* out, e16* out_lo, int rows,
                           int hidden, float eps, bool from_e16, bool out_half, hipStream_t stream);
 
-// cos_sin[t][i] = (cos, sin)(positions[t] * theta^(-2i/d)), i < d/2, evaluated in fp64.
-hipError_t launch_rope_table(const int32_t* positions, float2* cos_sin, int rows, int head_dim, float theta,
+// cos_sin[t][i] = (cos, sin)(positions[t] * theta^(-2i/r)), i < r/2, evaluated in fp64; r = rotary_dim, the
+// number of leading elements of a head that rotate (head_dim unless the rotary embedding is partial).
+hipError_t launch_rope_table(const int32_t* positions, float2* cos_sin, int rows, int rotary_dim, float theta,
                              hipStream_t stream);
 
 struct RopeAppendArgs {
@@ -30,11 +31,12 @@ struct RopeAppendArgs {
   float head_eps;
   e16* qkv;             // [T][(nq + 2 nkv) d] e16: rotated q heads, rotated k heads, v heads
   e16* q_lo;            // optional [T][nq d]: e16(q - e16(q)), second plane of the rotated queries
-  const float2* cos_sin;   // [T][d/2]
+  const float2* cos_sin;   // [T][rotary_dim/2]
   const int64_t* slots;    // [T] pool slot of every row
   e16* k_pool;          // this layer's K region [blocks][nkv][16][d]
   e16* v_pool;          // this layer's V region [blocks][nkv][d][16]
   int rows, nq, nkv, head_dim;
+  int rotary_dim;          // leading elements of every q and k head that rotate (a multiple of 16, <= head_dim)
 };
 hipError_t launch_rope_append(const RopeAppendArgs& args, hipStream_t stream);
 

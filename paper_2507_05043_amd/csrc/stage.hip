@@ -74,6 +74,7 @@ constexpr int kMinDecodeRange = 128;    // shortest key range worth a separate w
 
 struct Dims {
   int L, H, nq, nkv, d, F, qkv_out, g;
+  int rd;   // leading elements of a head that rotate
 };
 
 struct WorkspaceLayout {
@@ -116,6 +117,8 @@ int check_config(const stage_config* c) {
   } else if (c->weight_group_size != 0) {
     return fail(STAGE_ERR_CONFIG, "weight_group_size must be 0 unless weight_bits is 4");
   }
+  if (c->rotary_dim != 0 && (c->rotary_dim < 16 || c->rotary_dim > c->head_dim || c->rotary_dim % 16))
+    return fail(STAGE_ERR_CONFIG, "rotary_dim must be 0 or a multiple of 16 in [16, head_dim], got %d", c->rotary_dim);
   if (c->num_kv_blocks < 1 || c->max_tokens < 1 || c->max_seqs < 1 || c->max_blocks_per_seq < 1)
     return fail(STAGE_ERR_CONFIG, "capacities must be positive");
   const size_t layer_bytes = (size_t)c->num_kv_blocks * c->num_kv_heads * 16 * c->head_dim * 2 * 2;
@@ -130,6 +133,7 @@ Dims dims_of(const stage_config& c) {
   d.L = c.num_layers; d.H = c.hidden; d.nq = c.num_q_heads; d.nkv = c.num_kv_heads; d.d = c.head_dim; d.F = c.ffn;
   d.qkv_out = (c.num_q_heads + 2 * c.num_kv_heads) * c.head_dim;
   d.g = c.num_q_heads / c.num_kv_heads;
+  d.rd = c.rotary_dim == 0 ? c.head_dim : c.rotary_dim;
   return d;
 }
 
@@ -636,7 +640,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
 
   {
     Timer t(st, stream, STAGE_K_ROPE_TABLE);
-    HIP_TRY(launch_rope_table(d_pos, cos_sin, T, d.d, c.rope_theta, stream));
+    HIP_TRY(launch_rope_table(d_pos, cos_sin, T, d.rd, c.rope_theta, stream));
   }
   const size_t kv_region = (size_t)c.num_kv_blocks * d.nkv * 16 * d.d;   // elements of one K (or V) region
   {
@@ -667,7 +671,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       Timer t(st, stream, STAGE_K_ROPE_APPEND);
       RopeAppendArgs r{plan.partials ? splitk : qkv_f32, plan.partials ? plan.splits : 1, (size_t)T * d.qkv_out,
                        (const e16*)w.bqkv, (const e16*)w.qnorm, (const e16*)w.knorm, c.rms_eps,
-                       qkv, q_lo, cos_sin, d_slots, k_pool, v_pool, T, d.nq, d.nkv, d.d};
+                       qkv, q_lo, cos_sin, d_slots, k_pool, v_pool, T, d.nq, d.nkv, d.d, d.rd};
       HIP_TRY(launch_rope_append(r, stream));
     }
     if (tap && taps->tap_qkv)
@@ -798,6 +802,8 @@ int stage_init(const stage_config* cfg, const stage_layer_weights* layers, void*
     if ((uintptr_t)w.bqkv % 16) return fail(STAGE_ERR_CONFIG, "layer %d: bqkv is not 16-byte aligned", l);
     if ((w.qnorm == nullptr) != (w.knorm == nullptr))
       return fail(STAGE_ERR_NULL, "layer %d: qnorm and knorm must both be set or both be NULL", l);
+    if (w.qnorm && cfg->rotary_dim != 0 && cfg->rotary_dim != cfg->head_dim)
+      return fail(STAGE_ERR_CONFIG, "layer %d: qnorm / knorm are not supported together with a partial rotary embedding", l);
     if ((uintptr_t)w.qnorm % 16 || (uintptr_t)w.knorm % 16)
       return fail(STAGE_ERR_CONFIG, "layer %d: qnorm or knorm is not 16-byte aligned", l);
     if (cfg->weight_bits == 4) {

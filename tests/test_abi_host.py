@@ -123,6 +123,7 @@ def test_config_struct_matches_header_size(lib):
 @pytest.mark.parametrize("bad", [dict(kv_block_size=32), dict(head_dim=96), dict(hidden=252), dict(num_q_heads=5),
                                  dict(num_q_heads=34, num_kv_heads=2), dict(rms_eps=0.0), dict(num_layers=0),
                                  dict(activation_planes=5), dict(vocab_size=1001), dict(vocab_size=32),
+                                 dict(rotary_dim=8), dict(rotary_dim=40), dict(rotary_dim=80),
                                  dict(weight_bits=3), dict(weight_group_size=128), dict(weight_bits=4, weight_group_size=48),
                                  dict(weight_bits=4, weight_group_size=128, ffn=768 + 64),
                                  dict(weight_bits=4, weight_group_size=128)])   # ffn 688 is no multiple of 128

@@ -212,6 +212,36 @@ def test_seeded_random_small_stages(case):
                 qk_norm=rng.random() < 0.4, activation_planes=planes, elem=elem)
 
 
+@pytest.mark.parametrize("d,rd,planes,elem", [(128, 64, 1, torch.bfloat16), (128, 64, 3, torch.bfloat16), (64, 32, 1, torch.float16),
+                                              (128, 96, 2, torch.bfloat16), (64, 64, 1, torch.bfloat16)])
+def test_partial_rotary_embedding(d, rd, planes, elem):
+    """Only the first rotary_dim elements of every query and key head rotate (the GLM / ChatGLM families rotate half
+    of each head); prefill chunks with and without a cached prefix, decode, a bias, every activation mode."""
+    import dataclasses
+    shape = dataclasses.replace(_shape(f"partial-rotary-d{d}-r{rd}", 2, 512, 8, 2, d, 1408), rotary_dim=rd)
+    mb = synth.make_microbatch([70, 33, 1, 1, 1, 1, 1], [0, 21, 9, 40, 77, 100, 130], seed=9, max_blocks_per_seq=12)
+    stats = full_parity(shape, mb, 9, "fan_in", qkv_bias=True, activation_planes=planes, elem=elem)
+    if rd < d:
+        # the same stage with whole heads rotating gives another output: the setting was used
+        whole = H.make_stage(dataclasses.replace(shape, rotary_dim=0), mb, 9, "fan_in", qkv_bias=True, activation_planes=planes,
+                             dtype=elem)
+        a, _ = H.run_gpu(whole, shape, mb, 9)
+        whole.close()
+        part = H.make_stage(shape, mb, 9, "fan_in", qkv_bias=True, activation_planes=planes, dtype=elem)
+        b, _ = H.run_gpu(part, shape, mb, 9)
+        part.close()
+        assert rel_l2(b.cpu(), a.cpu()) > 10 * max(stats["rel_l2"], 1e-3)
+
+
+def test_partial_rotary_with_head_norms_is_rejected():
+    import dataclasses
+    shape, mb = synth.workload("tiny", seed=0)
+    shape = dataclasses.replace(shape, rotary_dim=32)
+    with pytest.raises(StageError) as ei:
+        H.make_stage(shape, mb, 0, qk_norm=True)
+    assert ei.value.code == -2
+
+
 def test_one_head_norm_gain_without_the_other_is_rejected():
     shape, mb = synth.workload("tiny", seed=0)
     from paper_2507_05043_amd.stage import Stage, make_config
