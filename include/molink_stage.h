@@ -335,8 +335,10 @@ enum {
 int stage_profile_enable(stage_handle *st, uint32_t kernel_mask);
 int stage_profile_read(stage_handle *st, int32_t kernel, double *out_total_ms, int64_t *out_launches);
 
-/* Name of the device kernel (as a profiler lists it) that implements a kernel class for this stage's shapes
- * at the given token count; for matching profiler output.  Returns NULL for an unknown class. */
+/* Name of the device kernel family (as a profiler lists it, without template arguments) that implements a kernel
+ * class, for matching profiler output; the projections name their tiled kernel (gemm_tile_kernel) although a
+ * launch may run on gemm_tile32_kernel (256 x 256 tiles) or gemm_skinny_kernel (at most 64 rows), and prefill
+ * attention with two query planes runs on attn_prefill_two_plane_kernel.  Returns NULL for an unknown class. */
 const char *stage_kernel_name(int32_t kernel);
 
 /* Release the handle (host memory, events, pinned staging).  Synchronises the device first. */

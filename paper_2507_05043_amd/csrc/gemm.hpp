@@ -60,7 +60,8 @@ struct GemmPlan {
 // streaming kernel cuts K into slices of 1024 and writes one plane of partial sums per slice, and with 8 to 28
 // slices its reductions cost more than the tiles' few K splits (70B-shaped stage, 52 sequences: 8.5 ms of
 // projections and reductions per micro-batch against 7.2); at 7B shapes the streaming kernel is ahead (2.86 ms per
-// micro-batch against 3.00).
+// micro-batch against 3.00).  The stage plans by shape, or on the streaming kernel where 4-bit weights are read in
+// their stored form; kFewRowsTiles exists for sizing the scratch of either choice.
 enum GemmFewRows : int { kFewRowsByShape = 0, kFewRowsStreaming = 1, kFewRowsTiles = 2 };
 
 GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool split_a = false,
