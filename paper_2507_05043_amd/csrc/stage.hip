@@ -69,8 +69,12 @@ int static_scratch_of(int device, char** out) {
 
 constexpr int kStagingSlots = 4;
 constexpr int kMaxTimed = 8192;
-constexpr int kDecodeWavesPerCu = 32;   // decode work items aimed at per CU and KV head group (sets the key-range length)
-constexpr int kMinDecodeRange = 128;    // shortest key range worth a separate work item
+// Decode work items: at most this many per CU (sets the key-range length of large launches), and no key range shorter
+// than kMinDecodeRange unless the sequence is.  Measured on 70B-shaped decode launches of 0.84 / 4.9 GB and a
+// 7B-shaped one of 1.3 GB: 16 / 24 / 32 / 48 / 64 items per CU give 146 / 153 / 158 / 161 / 163 us, 766 / 761 / 768 /
+// 779 / 792 us and 217 / 214 / 216 / 217 / 218 us - about 400 keys per wave and more is what all three want.
+constexpr int kDecodeWavesPerCu = 24;
+constexpr int kMinDecodeRange = 384;
 
 struct Dims {
   int L, H, nq, nkv, d, F, qkv_out, g;
