@@ -126,8 +126,19 @@ typedef struct {
    *   scales       bf16 [N][K/group]   (s* below)
    *   zero points  bf16 [N][K/group]   (z* below; in code units, usually an integer in 0..15)
    * and stands for   W[n][k] = (code[n][k] - zero[n][k/group]) * scale[n][k/group].
-   * The product is formed in fp32 (it is exact for integer zero points); kernels that materialise W
-   * round it to bf16 once.  Norm gains, the bias and the output head stay bf16.
+   * Norm gains, the bias and the output head stay bf16.  How a projection reads its weights depends on the
+   * micro-batch (the result is the same product, to the stated tolerance, either way):
+   *   - at most 64 rows, one activation plane, groups of 128, K a multiple of 256: the stored form is streamed,
+   *     scale and zero point applied to fp32 sums - W itself is never rounded;
+   *   - more rows, the matrix instructions' operands IEEE half (half activations in the bfloat16 library -
+   *     activation_planes 3, 4 or the automatic choice of a deep stage - or the half-precision library), one
+   *     plane, groups of 128, K a multiple of 256: the stored form is read by the tiled kernel, each weight formed
+   *     as half(code * scale - zero * scale) on its way into the matrix instruction (scales below 2^-14 lose
+   *     precision there, products beyond 65504 overflow: per-group scales of weights of ordinary magnitude are
+   *     far from either);
+   *   - otherwise the matrix is expanded in the workspace first, the fp32 product (exact for integer zero points)
+   *     rounded to bf16 once, and the ordinary kernels read the copy: complete, but it costs a write and a read
+   *     of 2 bytes per weight per call.
    */
   const void *sqkv, *so, *sgate, *sup, *sdown;
   const void *zqkv, *zo, *zgate, *zup, *zdown;

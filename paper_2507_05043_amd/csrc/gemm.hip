@@ -17,6 +17,10 @@
 // gemm_skinny_kernel below, built around streaming the weights; the widest projections (K of 8192 and more)
 // run on 64-row tiles instead (see GemmFewRows).
 //
+// 4-bit group-quantised weights: micro-batches of more than 64 rows with half operands run on gemm_tile_w4_kernel,
+// which carries the codes into LDS as they are stored and expands them in registers; decode-sized ones on the
+// streaming kernel of w4.hip.
+//
 // Half activations (bfloat16 library, deep stages): with A_HALF the A operand holds IEEE half bits, every weight
 // fragment read from LDS is converted from bfloat16 to half in registers (exact) and the f16 MFMA is used; the
 // tiles, their pipeline and their epilogues are otherwise the same code.
@@ -141,9 +145,11 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(GemmAr
     tile_n = rem / rows_in_band;
     split = 0;
   } else {
+    // split-major: the workgroups of one K range are neighbours, i.e. share an XCD, so the slice of the activation
+    // matrix they all read enters that XCD's L2 once instead of every XCD streaming the whole matrix
     tile_m = lid % tiles_m;
-    split = (lid / tiles_m) % splits;
-    tile_n = lid / (tiles_m * splits);
+    tile_n = (lid / tiles_m) % tiles_n;
+    split = lid / (tiles_m * tiles_n);
   }
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
@@ -376,9 +382,11 @@ __global__ __launch_bounds__(256) void gemm_tile32_kernel(GemmArgs p, int nv, in
     tile_n = rem / rows_in_band;
     split = 0;
   } else {
+    // split-major: the workgroups of one K range are neighbours, i.e. share an XCD, so the slice of the activation
+    // matrix they all read enters that XCD's L2 once instead of every XCD streaming the whole matrix
     tile_m = lid % tiles_m;
-    split = (lid / tiles_m) % splits;
-    tile_n = lid / (tiles_m * splits);
+    tile_n = (lid / tiles_m) % tiles_n;
+    split = lid / (tiles_m * tiles_n);
   }
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
@@ -532,6 +540,265 @@ __global__ __launch_bounds__(256) void gemm_tile32_kernel(GemmArgs p, int nv, in
     if (i + 2 < nkt) step(std::integral_constant<int, 2>{}, i + 2);
     wait_vmcnt<0>();   // nothing may still be writing LDS when the workgroup ends
   }
+  tile_epilogue<EPI, SPLIT, MT, NT>(p, acc, m0 + wm * TM, n0 + wn * TN, nv, split, lane);
+}
+
+// 4-bit group-quantised weights (groups of 128) on 256 x 256 tiles, for more than 64 rows.
+//
+// The weights stay in their stored form all the way into LDS and are expanded in registers, per MFMA operand:
+// a quarter of the bytes from memory and in LDS, no expanded copy.  The matrix instruction is the f16 one, so the
+// activations must be IEEE half (a bfloat16 stage that keeps its projection inputs as half, or the
+// half-precision library); a weight enters it as half((code - zero) * scale), formed as one fused multiply-add
+// code * scale + (-zero * scale) on exact operands - the same eleven significant bits a bfloat16 weight converted
+// to half would carry, three more than the expanded bfloat16 copy.  Scales are assumed to lie in half's normal
+// range (2^-14 .. 65504), which per-group scales of weights of ordinary magnitude do.
+//
+// A K tile is 64 wide: 128 bytes per activation row (swizzled as in gemm_tile_kernel), 32 bytes of codes per
+// weight row, and per weight row the two words that hold the scale and the zero point of the tile's group (a word
+// holds two consecutive groups, i.e. serves four tiles; it travels with every tile so that each stage is
+// self-contained and every pipeline step issues the same number of loads).  43 KB per stage, three stages.
+// Within a tile, MFMA step s takes k = 32 h + 8 s .. + 7 from lane half h (not 16 s + 8 h): the four words a lane
+// needs for the four steps of a tile are then one 16-byte LDS read of its row's codes.
+//
+// Expansion of one word (eight codes, k ascending from bit 0), per pair (k, k + 1): a byte permute puts the
+// byte that holds both codes into either half, and-or isolates one code per half as the half number
+// 1024 + code (bits or-ed into 0x6400), a packed subtraction removes the 1024 (exact), the packed fused
+// multiply-add applies scale and zero point: 17 vector operations per 8 weights.  Mask and offset are held in
+// registers: as literals they would split the and-or into two instructions.
+
+__device__ __forceinline__ h16x8 expand_w4_word(uint32_t x, h16x2 scale2, h16x2 bias2, uint32_t mask, uint32_t base) {
+  const uint32_t u = x >> 4;
+  const h16x2 offset = {(h16)1024.f, (h16)1024.f};
+  u32x4 o;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    // bytes (x.byte i, 0, u.byte i, 0): the low nibbles are codes 2 i and 2 i + 1
+    const uint32_t t = __builtin_amdgcn_perm(u, x, 0x0c000c00u | (uint32_t)i | ((uint32_t)(4 + i) << 16));
+    const h16x2 code = __builtin_bit_cast(h16x2, (t & mask) | base) - offset;
+    o[i] = __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(code, scale2, bias2));
+  }
+  return __builtin_bit_cast(h16x8, o);
+}
+
+template <int BM, int EPI, bool SPLIT>
+__global__ __launch_bounds__(256, BM == 128 ? 2 : 1) void gemm_tile_w4_kernel(GemmArgs p, int nv, int tiles_m, int tiles_n,
+                                                                             int splits, int k_tiles_per_split) {
+  static_assert(BM == 128 || BM == 256, "tile rows");
+  constexpr int BN = 256, NWAVES = 4, TM = BM / 2, TN = 128, MT = TM / 32, NT = 4, NSTAGE = 3;
+  constexpr int A_BYTES = BM * 128, CODE_BYTES = BN * 32, QP_BYTES = BN * 4;
+  constexpr int STAGE_BYTES = A_BYTES + CODE_BYTES + 2 * QP_BYTES;
+  constexpr int NA = BM / 8 / NWAVES;          // activation loads per wave per tile (8 rows x 128 bytes each)
+  constexpr int NB = BN / 32 / NWAVES;         // code loads per wave per tile (32 rows x 32 bytes each)
+  constexpr int NI = NA + NB + 2;              // + this wave's 64 rows of scale words and of zero-point words
+  static_assert(NSTAGE * STAGE_BYTES * (BM == 128 ? 2 : 1) <= 160 * 1024, "stages must fit in LDS");
+  using Lds = LdsStages<STAGE_BYTES>;
+
+  const int total = tiles_m * tiles_n * splits;
+  const int lid = xcd_logical_id(blockIdx.x, total);
+  if (lid < 0) return;
+  int tile_m, tile_n, split;
+  if (splits == 1 && tiles_m > kBandRows) {
+    const int band_size = kBandRows * tiles_n;
+    const int band = lid / band_size, rem = lid % band_size;
+    const int rows_in_band = min(kBandRows, tiles_m - band * kBandRows);
+    tile_m = band * kBandRows + rem % rows_in_band;
+    tile_n = rem / rows_in_band;
+    split = 0;
+  } else {
+    // split-major: the workgroups of one K range are neighbours, i.e. share an XCD, so the slice of the activation
+    // matrix they all read enters that XCD's L2 once instead of every XCD streaming the whole matrix
+    tile_m = lid % tiles_m;
+    tile_n = (lid / tiles_m) % tiles_n;
+    split = lid / (tiles_m * tiles_n);
+  }
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+
+  const int k_tiles = p.k / kBK;               // K is a multiple of 256 (launcher)
+  const int kt_begin = split * k_tiles_per_split;
+  const int kt_end = min(kt_begin + k_tiles_per_split, k_tiles);
+  const int nkt = kt_end - kt_begin;
+
+  // virtual column v of the tile's column space -> weight row (gate/up: 32 gate rows, then the 32 up rows of the
+  // same features); rows past the matrix repeat its last row (never stored)
+  auto row_of = [&](int v) {
+    const int r = EPI == kEpiSwiGLU ? (v >> 6) * 32 + (v & 31) : v;
+    return r < p.n ? r : p.n - 1;
+  };
+  const int b_row0 = EPI == kEpiSwiGLU ? (n0 >> 6) * 32 : n0;
+
+  // activations: as in gemm_tile_kernel - load j of this wave fills rows 8 g .. 8 g + 7, g = 4 j + wave; slot
+  // lane % 8 of row lane / 8 receives the row's chunk (lane % 8) ^ (lane / 8)
+  uint32_t a_off[NA];
+#pragma unroll
+  for (int j = 0; j < NA; ++j) {
+    int gm = m0 + 8 * (NWAVES * j + wave) + (lane >> 3);
+    gm = gm < p.m ? gm : p.m - 1;
+    a_off[j] = ((uint32_t)(gm - m0) * (uint32_t)p.lda + (uint32_t)(((lane & 7) ^ (lane >> 3)) * 8)) * 2u;
+  }
+  // codes: load j fills rows 32 g .. 32 g + 31, g = 4 j + wave; lane l carries bytes 16 (l % 2) .. + 15 of row l / 2.
+  // g and wave have the same parity, so with gate/up a wave reads one of the two matrices only.
+  const int row_bytes = p.k / 2;
+  uint32_t c_off[NB];
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    const int v = n0 + 32 * (NWAVES * j + wave) + (lane >> 1);
+    c_off[j] = (uint32_t)(row_of(v) - b_row0) * (uint32_t)row_bytes + (uint32_t)((lane & 1) * 16);
+  }
+  const bool up_wave = EPI == kEpiSwiGLU && (wave & 1);
+  const char* const codes_tile = reinterpret_cast<const char*>(up_wave ? p.q1.codes : p.q0.codes) + (size_t)b_row0 * row_bytes;
+  // scale and zero-point words: lane l serves row 64 wave + l of the tile (gate/up: lanes 32-63 are up rows)
+  const char* scale_lane;
+  const char* zero_lane;
+  {
+    const int v = n0 + 64 * wave + lane;
+    const bool up = EPI == kEpiSwiGLU && (v & 32);
+    const size_t at = (size_t)row_of(v) * (p.k / 128) * 2;
+    scale_lane = reinterpret_cast<const char*>(up ? p.q1.scales : p.q0.scales) + at;
+    zero_lane = reinterpret_cast<const char*>(up ? p.q1.zeros : p.q0.zeros) + at;
+  }
+  const size_t a_tile0 = (size_t)m0 * p.lda;
+
+  auto fetch = [&](auto stage_c, int idx) {
+    constexpr int S = decltype(stage_c)::value;
+    int kt = kt_begin + idx;
+    kt = kt < kt_end - 1 ? kt : kt_end - 1;
+    const char* abase = reinterpret_cast<const char*>(p.a + a_tile0 + kt * kBK);
+    const char* cbase = codes_tile + kt * 32;
+    char* stage = Lds::template get<S>();
+#pragma unroll
+    for (int j = 0; j < NA; ++j)
+      __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(abase + a_off[j]),
+                                       reinterpret_cast<uint32_t*>(stage + (NWAVES * j + wave) * 1024), 16, 0, 0);
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+      __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(cbase + c_off[j]),
+                                       reinterpret_cast<uint32_t*>(stage + A_BYTES + (NWAVES * j + wave) * 1024), 16, 0, 0);
+    const int word = (kt >> 2) * 4;            // the word of groups 2 (kt / 4) and 2 (kt / 4) + 1
+    __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(scale_lane + word),
+                                     reinterpret_cast<uint32_t*>(stage + A_BYTES + CODE_BYTES + wave * 256), 4, 0, 0);
+    __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(zero_lane + word),
+                                     reinterpret_cast<uint32_t*>(stage + A_BYTES + CODE_BYTES + QP_BYTES + wave * 256), 4, 0, 0);
+  };
+
+  f32x16 acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // fragment reads: lane (row l % 32, half h = l / 32) of step s wants chunk 4 h + s of its activation row, stored
+  // at slot (4 h + s) ^ (l % 8), and word s of the 16 bytes of codes at 16 h of its weight row
+  const int frag_row = lane & 31, half = lane >> 5;
+  int frag_off[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) frag_off[s] = frag_row * 128 + (((4 * half + s) ^ (lane & 7)) * 16);
+  const int code_off = A_BYTES + (wn * TN + frag_row) * 32 + half * 16;
+  const int qp_off = A_BYTES + CODE_BYTES + (wn * TN + frag_row) * 4;
+
+  uint32_t mask, base;
+  asm("s_mov_b32 %0, 0x000F000F" : "=s"(mask));
+  asm("v_mov_b32 %0, 0x64006400" : "=v"(base));
+
+  e16x8 af[2][MT];
+  h16x8 bfr[2][NT];
+  u32x4 codes[NT];           // the current tile's codes of this lane's NT weight rows: word s feeds MFMA step s
+  h16x2 scale2[NT], bias2[NT];
+  auto read_a = [&](auto stage_c, int set, int s) {
+    constexpr int S = decltype(stage_c)::value;
+    const char* la = Lds::template get<S>() + wm * TM * 128;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) af[set][i] = *reinterpret_cast<const e16x8*>(la + i * 32 * 128 + frag_off[s]);
+  };
+  // the codes, scales and zero points of the tile in stage S, whose K tile index is kt
+  auto read_b = [&](auto stage_c, int kt) {
+    constexpr int S = decltype(stage_c)::value;
+    const char* st = Lds::template get<S>();
+    const bool odd_group = (kt >> 1) & 1;
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      codes[j] = *reinterpret_cast<const u32x4*>(st + code_off + j * 32 * 32);
+      const uint32_t sw = *reinterpret_cast<const uint32_t*>(st + qp_off + j * 32 * 4);
+      const uint32_t zw = *reinterpret_cast<const uint32_t*>(st + qp_off + QP_BYTES + j * 32 * 4);
+      const float sc = odd_group ? e16_hi(sw) : e16_lo(sw);
+      const float zp = odd_group ? e16_hi(zw) : e16_lo(zw);
+      const h16 sh = (h16)sc, bh = (h16)(-zp * sc);
+      scale2[j] = h16x2{sh, sh};
+      bias2[j] = h16x2{bh, bh};
+    }
+  };
+  auto expand = [&](int set, int s) {
+#pragma unroll
+    for (int j = 0; j < NT; ++j) bfr[set][j] = expand_w4_word(codes[j][s], scale2[j], bias2[j], mask, base);
+  };
+  auto mfmas = [&](int set) {
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+        acc[i][j] = mfma_32x32x16_half(__builtin_bit_cast(h16x8, af[set][i]), bfr[set][j], acc[i][j]);
+  };
+
+  // The pipeline of gemm_tile_kernel at three stages: tile idx is in stage S with the operands of its first MFMA
+  // step in register set 0; tile idx + 2 is requested into the stage read in the previous step, its loads spread
+  // over the first three MFMA steps; wait and barrier come before the last step, whose MFMAs cover the first reads
+  // and the first expansion of tile idx + 1.
+  constexpr int NMFMA = MT * NT;
+  constexpr int L0 = NI / 3, L1 = (2 * NI) / 3 - NI / 3, L2 = NI - (2 * NI) / 3;
+  auto step = [&](auto stage_c, int idx) {
+    constexpr int S = decltype(stage_c)::value;
+    using Next = std::integral_constant<int, (S + 1) % NSTAGE>;
+    fetch(std::integral_constant<int, (S + NSTAGE - 1) % NSTAGE>{}, idx + NSTAGE - 1);
+    read_a(stage_c, 1, 1);
+    expand(1, 1);
+    mfmas(0);
+    sched_step<0, NMFMA, MT, L0>();
+    read_a(stage_c, 0, 2);
+    expand(0, 2);
+    mfmas(1);
+    sched_step<0, NMFMA, MT, L1>();
+    read_a(stage_c, 1, 3);
+    expand(1, 3);
+    mfmas(0);
+    sched_step<0, NMFMA, MT, L2>();
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vmcnt<(NSTAGE - 2) * NI>();
+    pipeline_barrier();
+    read_a(Next{}, 0, 0);
+    int kt_next = kt_begin + idx + 1;
+    kt_next = kt_next < kt_end - 1 ? kt_next : kt_end - 1;
+    read_b(Next{}, kt_next);
+    expand(0, 0);
+    mfmas(1);
+    sched_step<0, NMFMA, MT + 3 * NT, 0>();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  if (nkt > 0) {
+    fetch(std::integral_constant<int, 0>{}, 0);
+    fetch(std::integral_constant<int, 1>{}, 1);
+    wait_vmcnt<NI>();
+    pipeline_barrier();
+    read_a(std::integral_constant<int, 0>{}, 0, 0);
+    read_b(std::integral_constant<int, 0>{}, kt_begin);
+    expand(0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    int i = 0;
+    for (; i + NSTAGE <= nkt; i += NSTAGE) {
+      step(std::integral_constant<int, 0>{}, i);
+      step(std::integral_constant<int, 1>{}, i + 1);
+      step(std::integral_constant<int, 2>{}, i + 2);
+    }
+    if (i < nkt) step(std::integral_constant<int, 0>{}, i);
+    if (i + 1 < nkt) step(std::integral_constant<int, 1>{}, i + 1);
+    wait_vmcnt<0>();   // nothing may still be writing LDS when the workgroup ends
+  }
+
   tile_epilogue<EPI, SPLIT, MT, NT>(p, acc, m0 + wm * TM, n0 + wn * TN, nv, split, lane);
 }
 
@@ -826,6 +1093,25 @@ hipError_t launch_tile32(const GemmArgs& a, const GemmPlan& plan, hipStream_t st
   return hipGetLastError();
 }
 
+template <int BM, int EPI>
+hipError_t launch_tile_w4(const GemmArgs& a, const GemmPlan& plan, hipStream_t stream) {
+  const int tiles_m = (a.m + BM - 1) / BM;
+  const int tiles_n = (plan.nv + 255) / 256;
+  const int total = tiles_m * tiles_n * plan.splits;
+  dim3 grid(xcd_grid(total)), block(256);
+  if (plan.splits > 1)
+    hipLaunchKernelGGL((gemm_tile_w4_kernel<BM, EPI, true>), grid, block, 0, stream, a, plan.nv, tiles_m, tiles_n, plan.splits,
+                       plan.k_tiles_per_split);
+  else
+    hipLaunchKernelGGL((gemm_tile_w4_kernel<BM, EPI, false>), grid, block, 0, stream, a, plan.nv, tiles_m, tiles_n, 1,
+                       plan.k_tiles_per_split);
+  return hipGetLastError();
+}
+template <int EPI>
+hipError_t launch_tile_w4(const GemmArgs& a, const GemmPlan& plan, hipStream_t stream) {
+  return plan.tile == kTileW4x128 ? launch_tile_w4<128, EPI>(a, plan, stream) : launch_tile_w4<256, EPI>(a, plan, stream);
+}
+
 template <int EPI>
 hipError_t launch_epi(const GemmArgs& a, const GemmPlan& plan, hipStream_t stream) {
   if (a.a_lo) {
@@ -935,6 +1221,57 @@ GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool spli
   return plan;
 }
 
+// Which of the two 4-bit tile heights a product of m rows runs on.  Up to 128 rows the 128-row tiles (two workgroups
+// per CU) are ahead - 70B-shaped stage, 128 tokens: 16.6 against 17.8 ms per micro-batch; at 256 and 512 rows the
+// 256-row tiles are (26.9 against 28.6 and 45.7 against 49.2 ms): every workgroup expands the codes of its own
+// columns, so two tile rows expand everything twice.
+static bool w4_tile_rows_128(int m) { return m <= 128; }
+
+bool tile_w4_supports(int m, int k, int group, bool two_planes, bool operands_half) {
+  return m > 64 && operands_half && !two_planes && group == 128 && k >= 256 && k % 256 == 0;
+}
+
+GemmPlan plan_gemm_w4_tile(int m, int n, int k, GemmEpilogue epi, int num_cus) {
+  GemmPlan plan;
+  plan.nv = epi == kEpiSwiGLU ? ((n + 31) / 32) * 64 : n;
+  const int k_tiles = k / kBK;
+  const int tiles_n = (plan.nv + 255) / 256;
+  // 128-row tiles run two workgroups per CU, 256-row tiles one
+  const bool rows128 = w4_tile_rows_128(m);
+  plan.tile = rows128 ? kTileW4x128 : kTileW4;
+  const int tiles = (rows128 ? (m + 127) / 128 : (m + 255) / 256) * tiles_n;
+  const int slots = rows128 ? 2 * num_cus : num_cus;
+  int splits = 1;
+  if (tiles * 2 <= slots) {
+    // as in plan_gemm: as many splits as fit one round of workgroups, at least 4 K tiles each, at most 16
+    splits = slots / tiles;
+    const int max_by_k = k_tiles / 4 > 0 ? k_tiles / 4 : 1;
+    if (splits > max_by_k) splits = max_by_k;
+    if (splits > 16) splits = 16;
+  }
+  plan.k_tiles_per_split = (k_tiles + splits - 1) / splits;
+  plan.splits = (k_tiles + plan.k_tiles_per_split - 1) / plan.k_tiles_per_split;
+  plan.partials = plan.splits > 1;
+  return plan;
+}
+
+size_t gemm_partial_floats_w4_tile(int max_m, int n, int k, GemmEpilogue epi, int num_cus) {
+  // The split count depends on the number of tile rows only, so the largest m of every such count is the worst:
+  // the multiples of 128 below max_m, and max_m itself.
+  size_t worst = 0;
+  for (int top = 128;; top += 128) {
+    const int m = top < max_m ? top : max_m;
+    if (m <= 64) break;
+    const GemmPlan p = plan_gemm_w4_tile(m, n, k, epi, num_cus);
+    if (p.partials) {
+      const size_t need = (size_t)p.splits * m * p.nv;
+      if (need > worst) worst = need;
+    }
+    if (top >= max_m) break;
+  }
+  return worst;
+}
+
 size_t gemm_partial_floats(int max_m, int n, int k, GemmEpilogue epi, int num_cus, bool split_a) {
   // The scratch of a shape is splits * m * nv; the split count falls as m grows, so every m at which the
   // plan can change (multiples of 64) is tried.
@@ -980,7 +1317,18 @@ hipError_t launch_gemm_main(const GemmArgs& a, GemmEpilogue epi, const GemmPlan&
                        epi == kEpiSwiGLU ? 1 : 0);
     return hipGetLastError();
   }
-  if (a.q0.codes) return hipErrorInvalidValue;   // the tiled kernels take e16 weights only
+  if (plan.tile == kTileW4 || plan.tile == kTileW4x128) {
+    if (!a.q0.codes || (epi == kEpiSwiGLU && !a.q1.codes) || a.a_lo || !(a.a_half || kElemIsF16) || a.k % 256)
+      return hipErrorInvalidValue;
+    switch (epi) {
+      case kEpiStoreF32: return launch_tile_w4<kEpiStoreF32>(a, plan, stream);
+      case kEpiResidualF32: return launch_tile_w4<kEpiResidualF32>(a, plan, stream);
+      case kEpiResidualOut: return launch_tile_w4<kEpiResidualOut>(a, plan, stream);
+      case kEpiSwiGLU: return launch_tile_w4<kEpiSwiGLU>(a, plan, stream);
+    }
+    return hipErrorInvalidValue;
+  }
+  if (a.q0.codes) return hipErrorInvalidValue;   // the other tiled kernels take e16 weights only
   switch (epi) {
     case kEpiStoreF32: return launch_epi<kEpiStoreF32>(a, plan, stream);
     case kEpiResidualF32: return launch_epi<kEpiResidualF32>(a, plan, stream);

@@ -31,7 +31,7 @@ struct GemmArgs {
   const e16* w0;     // [N][K]; for SwiGLU the gate matrix [F][K]
   const e16* w1;     // SwiGLU only: the up matrix [F][K]
   W4Matrix q0, q1;      // q0.codes != nullptr: the weights are 4-bit (groups of 128) and w0 / w1 are unused;
-                        // only plans of the weight-streaming kind (at most 64 rows) take them
+                        // only plans of the weight-streaming kind (at most 64 rows) and of the kTileW4 kind take them
   e16* out_e16;     // see GemmEpilogue
   float* out_f32;       // kEpiStoreF32 output [M][ldo]
   float* resid;         // fp32 residual stream [M][N]
@@ -45,7 +45,9 @@ struct GemmArgs {
 
 // kTileSkinny: at most 64 rows; K cut into slices of 1024, weights streamed in groups of 16 rows, always
 // through partial sums (the reduction applies the epilogue).
-enum GemmTile : int { kTile256x256 = 0, kTile256x128 = 1, kTile128x128 = 2, kTile64x128 = 3, kTileSkinny = 4, kTile128x256 = 5 };
+// kTileW4, kTileW4x128: 256 x 256 and 128 x 256 tiles on 4-bit weights in their stored form (more than 64 rows,
+// half operands).
+enum GemmTile : int { kTile256x256 = 0, kTile256x128 = 1, kTile128x128 = 2, kTile64x128 = 3, kTileSkinny = 4, kTile128x256 = 5, kTileW4 = 6, kTileW4x128 = 7 };
 
 struct GemmPlan {
   int tile;             // GemmTile: workgroup tile shape
@@ -69,6 +71,14 @@ GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool spli
 // Floats of split-K scratch that any GEMM with m <= max_m rows of this (n, k, epilogue) may need, however its
 // products of at most 64 rows are planned.
 size_t gemm_partial_floats(int max_m, int n, int k, GemmEpilogue epi, int num_cus, bool split_a = false);
+
+// 4-bit weights, more than 64 rows: whether the tiled kernel reads this shape as it is stored (otherwise the
+// caller expands the matrix and runs a e16 GEMM).  One activation plane held as IEEE half (`operands_half`: half
+// activations in the bfloat16 library, or the half-precision library), groups of 128, K a multiple of 256.
+bool tile_w4_supports(int m, int k, int group, bool two_planes, bool operands_half);
+// The plan of such a product (tile kTileW4), and the split-K scratch any m <= max_m may need under these plans.
+GemmPlan plan_gemm_w4_tile(int m, int n, int k, GemmEpilogue epi, int num_cus);
+size_t gemm_partial_floats_w4_tile(int max_m, int n, int k, GemmEpilogue epi, int num_cus);
 
 hipError_t launch_gemm_main(const GemmArgs& args, GemmEpilogue epi, const GemmPlan& plan, hipStream_t stream);
 // Only when plan.partials: sums the partial results in split order and applies the epilogue.

@@ -212,6 +212,12 @@ WorkspaceLayout layout_of(const stage_config& c) {
     if ((v = gemm_partial_floats(c.max_tokens, d.H, d.F, kEpiResidualF32, kNumCus, sp)) > pf) pf = v;
   }
   if (c.vocab_size > 0 && (v = gemm_partial_floats(c.max_seqs, c.vocab_size, d.H, kEpiStoreF32, kNumCus, false)) > pf) pf = v;
+  if (c.weight_bits == 4) {   // the tiles that read 4-bit weights as stored plan on their own
+    if ((v = gemm_partial_floats_w4_tile(c.max_tokens, d.qkv_out, d.H, kEpiStoreF32, kNumCus)) > pf) pf = v;
+    if ((v = gemm_partial_floats_w4_tile(c.max_tokens, d.H, d.nq * d.d, kEpiResidualF32, kNumCus)) > pf) pf = v;
+    if ((v = gemm_partial_floats_w4_tile(c.max_tokens, d.F, d.H, kEpiSwiGLU, kNumCus)) > pf) pf = v;
+    if ((v = gemm_partial_floats_w4_tile(c.max_tokens, d.H, d.F, kEpiResidualF32, kNumCus)) > pf) pf = v;
+  }
   w.splitk = take(pf * 4 + 16);
   w.splitk_floats = pf;
   // 4-bit weights: room for the largest projection (gate and up together) expanded to e16
@@ -366,10 +372,14 @@ hipError_t copy_activation_tap(void* dst, const e16* src, size_t n, bool src_hal
   return hipGetLastError();
 }
 
-// Points a projection's GEMM at its weights.  e16 weights are used where they lie.  4-bit weights go to
-// the weight-streaming kernel as they are stored when the micro-batch is decode-sized; otherwise they are
-// expanded to e16 in the workspace first (one projection at a time; `w1` is the second matrix of the
-// gate/up pair or NULL) and the GEMM reads the expanded copy.
+// Whether the operands of a stage's matrix instructions are IEEE half: the half-precision library, or half
+// activations in the bfloat16 one.
+bool operands_half_of(const stage_config& c) { return kElemIsF16 != 0 || half_act_of(c); }
+
+// Points a projection's GEMM at its weights.  e16 weights are used where they lie.  4-bit weights are read as
+// they are stored by the weight-streaming kernel (decode-sized micro-batches) and by the 4-bit tiles (more rows,
+// half operands); otherwise they are expanded to e16 in the workspace first (one projection at a time; `w1` is
+// the second matrix of the gate/up pair or NULL) and the GEMM reads the expanded copy.
 int bind_weights(stage_handle* st, hipStream_t stream, GemmArgs& g, const void* w0, const void* s0, const void* z0,
                  const void* w1, const void* s1, const void* z1) {
   if (st->cfg.weight_bits != 4) {
@@ -378,8 +388,9 @@ int bind_weights(stage_handle* st, hipStream_t stream, GemmArgs& g, const void* 
     return STAGE_OK;
   }
   const W4Matrix m0{(const uint32_t*)w0, (const e16*)s0, (const e16*)z0};
-  if (skinny_w4_supports(g.m, g.k, st->cfg.weight_group_size, g.a_lo != nullptr)) {
-    // decode-sized micro-batch: the weight-streaming kernel reads the stored form itself
+  if (skinny_w4_supports(g.m, g.k, st->cfg.weight_group_size, g.a_lo != nullptr) ||
+      tile_w4_supports(g.m, g.k, st->cfg.weight_group_size, g.a_lo != nullptr, g.a_half || kElemIsF16 != 0)) {
+    // the kernel the projection was planned on reads the stored form itself
     g.q0 = m0;
     if (w1) g.q1 = W4Matrix{(const uint32_t*)w1, (const e16*)s1, (const e16*)z1};
     return STAGE_OK;
@@ -397,9 +408,12 @@ int bind_weights(stage_handle* st, hipStream_t stream, GemmArgs& g, const void* 
   return STAGE_OK;
 }
 
-// The plan of a projection.  At most 64 rows: 4-bit weights in their stored form need the streaming kernel;
-// otherwise the shape decides between it and the 64-row tiles.
+// The plan of a projection.  4-bit weights with more than 64 rows and half operands: the tiles that read the stored
+// form.  At most 64 rows: 4-bit weights in their stored form need the streaming kernel; otherwise the shape decides
+// between it and the 64-row tiles.
 GemmPlan plan_projection(const stage_config& c, int m, int n, int k, GemmEpilogue epi, bool two_planes) {
+  if (c.weight_bits == 4 && tile_w4_supports(m, k, c.weight_group_size, two_planes, operands_half_of(c)))
+    return plan_gemm_w4_tile(m, n, k, epi, kNumCus);
   const bool stored_w4 = c.weight_bits == 4 && skinny_w4_supports(m, k, c.weight_group_size, two_planes);
   return plan_gemm(m, n, k, epi, kNumCus, two_planes, stored_w4 ? kFewRowsStreaming : kFewRowsByShape);
 }

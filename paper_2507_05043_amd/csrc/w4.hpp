@@ -13,9 +13,9 @@ namespace molink {
 // Writes the matrix as e16 [n][k] (the product formed in fp32, rounded once).  k % group == 0, group % 8 == 0.
 hipError_t launch_dequant_w4(const W4Matrix& w, int n, int k, int group, e16* out, hipStream_t stream);
 
-// Whether the weight-streaming kernel below takes this shape as it is stored (otherwise the caller expands
-// the matrix with launch_dequant_w4 and runs a e16 GEMM): at most 64 rows, one activation plane, groups
-// of 128, an even number of groups per row.
+// Whether the weight-streaming kernel below takes this shape as it is stored: at most 64 rows, one activation
+// plane, groups of 128, an even number of groups per row.  (Above 64 rows see tile_w4_supports in gemm.hpp; what
+// neither takes the caller expands with launch_dequant_w4 and hands to a e16 GEMM.)
 bool skinny_w4_supports(int m, int k, int group, bool two_planes);
 
 // Decode-sized GEMM on 4-bit weights, args.q0 (and args.q1 for the gate/up pair) in place of w0 / w1.

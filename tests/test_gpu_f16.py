@@ -117,6 +117,19 @@ def test_four_bit_weights_streamed_in_decode(n_decode):
     f16_parity(MID, mb, 4, group=128)
 
 
+def test_four_bit_tiles_read_the_stored_form_above_64_rows():
+    """A mixed micro-batch of 194 rows: every projection runs on the 4-bit tiles (the element type is half already),
+    nothing is expanded in the workspace."""
+    mb = synth.make_microbatch([130, 61, 1, 1, 1], [0, 40, 20, 29, 38], seed=3, max_blocks_per_seq=16)
+    st = H.make_stage(MID, mb, 6, weight_group_size=128, dtype=F16)
+    st.profile_enable(["dequant", "gemm_down"])
+    H.run_gpu(st, MID, mb, 6)
+    assert st.profile_read("dequant")[1] == 0
+    assert st.profile_read("gemm_down")[1] == MID.num_layers
+    st.close()
+    f16_parity(MID, mb, 6, group=128)
+
+
 def test_llama2_7b_stage_in_half_precision_sampled_rows_at_full_size():
     """The paper's 7B serving precision at the benchmark workload's real shape: 8 of 64 sequences checked row
     by row against the oracle at full depth (rows of different sequences are independent)."""
