@@ -104,6 +104,15 @@ typedef struct {
                                   size would (pairs (i, i + rotary_dim/2), angle position * theta^(-2i/rotary_dim)); the
                                   rest pass through unrotated.  The GLM / ChatGLM families of the paper's model table
                                   (section 3.1.3) rotate half of each head.  Not together with qnorm / knorm. */
+  int32_t weight_copies;       /* 0: the stage keeps a second copy of its 16-bit projection weights, made by stage_init
+                                  in the order and format its matrix instructions take them (IEEE half in a stage
+                                  with half activations), which the tiled GEMMs of micro-batches of more than 128
+                                  rows read straight into registers: about a quarter faster than reading the
+                                  caller's row-major matrices through LDS, for one more copy of the weights in the
+                                  workspace (stage_workspace_bytes counts it).  Made only when max_tokens > 128, the
+                                  weights are 16-bit and activation_planes is not 2; a matrix whose input width is
+                                  not a multiple of 256 has none.  1: no copies.  Results agree to the rounding of
+                                  the fp32 summation order. */
 } stage_config;
 
 /* Device pointers to one layer's weights, row-major [out_features][in_features], bf16 unless
@@ -187,14 +196,18 @@ int stage_check_batch(const stage_config *cfg, int32_t num_tokens, const int32_t
                       const int32_t *block_tables, int64_t *slot_mapping_out);
 
 /* Bytes of device workspace stage_init needs for this config (activations, split-K and
- * split-KV partial results, per-call metadata). */
+ * split-KV partial results, per-call metadata, and - see stage_config.weight_copies - the second copy of
+ * the projection weights). */
 int stage_workspace_bytes(const stage_config *cfg, size_t *out_bytes);
 
 /*
  * Create a stage.  layers: host array [num_layers] of device-pointer structs (copied).
  * kv_pool / workspace: device memory, 256-byte aligned, of at least kv_pool_bytes >=
  * (L-1)*stride + stage_kv_layer_bytes and stage_workspace_bytes.  device: HIP device ordinal
- * that owns all buffers.  No kernel is launched and no device memory is touched.
+ * that owns all buffers.  Unless the stage keeps copies of its weights (stage_config.weight_copies) no kernel
+ * is launched and no device memory is touched; with copies, the weights must be complete on the device when
+ * stage_init is called (it reads them on the default stream and returns when the copies are written) and must
+ * not change afterwards.
  * Errors: STAGE_ERR_NULL, STAGE_ERR_CONFIG, STAGE_ERR_SIZE, STAGE_ERR_HIP.
  */
 int stage_init(const stage_config *cfg, const stage_layer_weights *layers, void *kv_pool,
@@ -236,8 +249,9 @@ int stage_forward(stage_handle *st, void *hip_stream, int32_t num_tokens, const 
  * hipMalloc.  Same arguments, same result (bit for bit) and same errors as stage_forward, but every
  * intermediate of the call - activations between kernels, split-K and split-KV partial results, the per-call
  * metadata - lives in a scratch array of STAGE_STATIC_SCRATCH_BYTES that is part of the library's device
- * image (each GPU the library runs on holds one copy until the process ends); the workspace given to
- * stage_init is not touched.  The array is carved for exactly this micro-batch (num_tokens rows, num_seqs
+ * image (each GPU the library runs on holds one copy until the process ends); of the workspace given to
+ * stage_init nothing is written, and nothing is read but the weights' second copies that stage_init may
+ * have put there (stage_config.weight_copies).  The array is carved for exactly this micro-batch (num_tokens rows, num_seqs
  * sequences); a micro-batch that needs more is rejected with STAGE_ERR_SIZE before anything is enqueued.
  * The call allocates nothing, on the device or through the HIP runtime (no hipMalloc, hipFree, event or
  * stream creation; per-kernel timing is off for the call), and nothing in the array has to start at zero:

@@ -30,6 +30,8 @@ struct GemmArgs {
   e16* out_lo;       // SwiGLU epilogue only, optional: receives e16(result - e16(result)) [M][ldo]
   const e16* w0;     // [N][K]; for SwiGLU the gate matrix [F][K]
   const e16* w1;     // SwiGLU only: the up matrix [F][K]
+  const e16* wa0;    // optional: the same matrices once more in operand order (launch_arrange_weights), in the format
+  const e16* wa1;    // of the MFMA operands (IEEE half when a_half); read by plans of the kTileArranged kind
   W4Matrix q0, q1;      // q0.codes != nullptr: the weights are 4-bit (groups of 128) and w0 / w1 are unused;
                         // only plans of the weight-streaming kind (at most 64 rows) and of the kTileW4 kind take them
   e16* out_e16;     // see GemmEpilogue
@@ -46,8 +48,9 @@ struct GemmArgs {
 // kTileSkinny: at most 64 rows; K cut into slices of 1024, weights streamed in groups of 16 rows, always
 // through partial sums (the reduction applies the epilogue).
 // kTileW4, kTileW4x128: 256 x 256 and 128 x 256 tiles on 4-bit weights in their stored form (more than 64 rows,
-// half operands).
-enum GemmTile : int { kTile256x256 = 0, kTile256x128 = 1, kTile128x128 = 2, kTile64x128 = 3, kTileSkinny = 4, kTile128x256 = 5, kTileW4 = 6, kTileW4x128 = 7 };
+// half operands).  kTileArranged: 256 x 256 tiles that read the weights' copy in operand order (GemmArgs::wa0 / wa1)
+// straight into registers.
+enum GemmTile : int { kTile256x256 = 0, kTile256x128 = 1, kTile128x128 = 2, kTile64x128 = 3, kTileSkinny = 4, kTile128x256 = 5, kTileW4 = 6, kTileW4x128 = 7, kTileArranged = 8 };
 
 struct GemmPlan {
   int tile;             // GemmTile: workgroup tile shape
@@ -66,11 +69,19 @@ struct GemmPlan {
 // their stored form; kFewRowsTiles exists for sizing the scratch of either choice.
 enum GemmFewRows : int { kFewRowsByShape = 0, kFewRowsStreaming = 1, kFewRowsTiles = 2 };
 
+// arranged: the weights exist in operand order too, so plans of the kTileArranged kind may be chosen.
 GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool split_a = false,
-                   GemmFewRows few_rows = kFewRowsByShape);
+                   GemmFewRows few_rows = kFewRowsByShape, bool arranged = false);
 // Floats of split-K scratch that any GEMM with m <= max_m rows of this (n, k, epilogue) may need, however its
 // products of at most 64 rows are planned.
-size_t gemm_partial_floats(int max_m, int n, int k, GemmEpilogue epi, int num_cus, bool split_a = false);
+size_t gemm_partial_floats(int max_m, int n, int k, GemmEpilogue epi, int num_cus, bool split_a = false, bool arranged = false);
+
+// Weights in operand order (see gemm_tile_arranged_kernel): K must be a multiple of 256; the copy holds
+// arranged_weights_elems(n, k) elements (rows padded to a multiple of 32 with zeros).  to_half (bfloat16 library only):
+// the copy is IEEE half, converted as the GEMMs' registers would (exact within half's range).
+bool arranged_weights_supported(int k);
+size_t arranged_weights_elems(int n, int k);
+hipError_t launch_arrange_weights(const e16* w, int n, int k, bool to_half, e16* out, hipStream_t stream);
 
 // 4-bit weights, more than 64 rows: whether the tiled kernel reads this shape as it is stored (otherwise the
 // caller expands the matrix and runs a e16 GEMM).  One activation plane held as IEEE half (`operands_half`: half

@@ -111,6 +111,8 @@ int check_config(const stage_config* c) {
     return fail(STAGE_ERR_CONFIG, "activation_planes 3 and 4 (half activations) are modes of the bfloat16 library; this one stores half already");
   if (c->vocab_size != 0 && (c->vocab_size < 64 || c->vocab_size % 8))
     return fail(STAGE_ERR_CONFIG, "vocab_size must be 0 or a multiple of 8 that is at least 64");
+  if (c->weight_copies != 0 && c->weight_copies != 1)
+    return fail(STAGE_ERR_CONFIG, "weight_copies must be 0 (keep copies in operand order) or 1 (none), got %d", c->weight_copies);
   if (c->weight_bits != 0 && c->weight_bits != 16 && c->weight_bits != 4)
     return fail(STAGE_ERR_CONFIG, "weight_bits must be 0, 16 or 4, got %d", c->weight_bits);
   if (c->weight_bits == 4) {
@@ -182,6 +184,36 @@ bool qkv_lo_of(const stage_config& c, bool has_prefill) { return mode_of(c) == 4
 
 int decode_target_items(const Dims& d) { return (kNumCus * kDecodeWavesPerCu + d.nkv - 1) / d.nkv; }
 
+// Second copies of the projection weights in operand order (gemm_tile_arranged_kernel), behind the workspace proper.
+// Possible whenever the weights are 16-bit and the stage runs one activation plane; made when the stage can see a
+// micro-batch of more than 128 rows (smaller ones never use them).  A matrix whose K is not a multiple of 256 has none.
+constexpr size_t kNoCopy = ~(size_t)0;
+struct CopyLayout {
+  size_t qkv, o, gate, up, down;   // byte offsets inside one layer's copies, or kNoCopy
+  size_t per_layer;                // bytes per layer (0: nothing is copied)
+};
+bool copies_possible(const stage_config& c) { return c.weight_copies == 0 && c.weight_bits != 4 && !two_plane_of(c); }
+
+CopyLayout copy_layout_of(const stage_config& c) {
+  const Dims d = dims_of(c);
+  CopyLayout cl{kNoCopy, kNoCopy, kNoCopy, kNoCopy, kNoCopy, 0};
+  if (!copies_possible(c) || c.max_tokens <= 128) return cl;
+  size_t off = 0;
+  auto take = [&](int n, int k) {
+    if (!arranged_weights_supported(k)) return kNoCopy;
+    const size_t o = off;
+    off += align_up(arranged_weights_elems(n, k) * 2);
+    return o;
+  };
+  cl.qkv = take(d.qkv_out, d.H);
+  cl.o = take(d.H, d.nq * d.d);
+  cl.gate = take(d.F, d.H);
+  cl.up = take(d.F, d.H);
+  cl.down = take(d.H, d.F);
+  cl.per_layer = off;
+  return cl;
+}
+
 WorkspaceLayout layout_of(const stage_config& c) {
   const Dims d = dims_of(c);
   WorkspaceLayout w;
@@ -206,10 +238,13 @@ WorkspaceLayout layout_of(const stage_config& c) {
   for (int sp = 0; sp < 2; ++sp) {
     if (sp == 1 && !(lo_planes_of(c) || half_act_of(c))) continue;
     if (sp == 0 && lo_planes_of(c)) continue;
-    if ((v = gemm_partial_floats(c.max_tokens, d.qkv_out, d.H, kEpiStoreF32, kNumCus, sp)) > pf) pf = v;
-    if ((v = gemm_partial_floats(c.max_tokens, d.H, d.nq * d.d, kEpiResidualF32, kNumCus, sp)) > pf) pf = v;
-    if ((v = gemm_partial_floats(c.max_tokens, d.F, d.H, kEpiSwiGLU, kNumCus, sp)) > pf) pf = v;
-    if ((v = gemm_partial_floats(c.max_tokens, d.H, d.F, kEpiResidualF32, kNumCus, sp)) > pf) pf = v;
+    for (int arr = 0; arr < 2; ++arr) {      // with and without the copies in operand order (whether a call has them
+      if (arr && (sp || !copies_possible(c))) continue;   // depends on the handle, not on the capacity this is sized for)
+      if ((v = gemm_partial_floats(c.max_tokens, d.qkv_out, d.H, kEpiStoreF32, kNumCus, sp, arr)) > pf) pf = v;
+      if ((v = gemm_partial_floats(c.max_tokens, d.H, d.nq * d.d, kEpiResidualF32, kNumCus, sp, arr)) > pf) pf = v;
+      if ((v = gemm_partial_floats(c.max_tokens, d.F, d.H, kEpiSwiGLU, kNumCus, sp, arr)) > pf) pf = v;
+      if ((v = gemm_partial_floats(c.max_tokens, d.H, d.F, kEpiResidualF32, kNumCus, sp, arr)) > pf) pf = v;
+    }
   }
   if (c.vocab_size > 0 && (v = gemm_partial_floats(c.max_seqs, c.vocab_size, d.H, kEpiStoreF32, kNumCus, false)) > pf) pf = v;
   if (c.weight_bits == 4) {   // the tiles that read 4-bit weights as stored plan on their own
@@ -315,6 +350,9 @@ struct stage_handle {
   // workspace and layout of the call being enqueued (the handle's own, or the static scratch carved for the call)
   char* call_ws;
   const WorkspaceLayout* call_layout;
+  // the weights' copies in operand order: layer l's start at wcopy + l * copies.per_layer (wcopy NULL: none were made)
+  char* wcopy;
+  CopyLayout copies;
   int device;
   // pinned staging ring for the per-call metadata
   char* staging[kStagingSlots];
@@ -376,15 +414,22 @@ hipError_t copy_activation_tap(void* dst, const e16* src, size_t n, bool src_hal
 // activations in the bfloat16 one.
 bool operands_half_of(const stage_config& c) { return kElemIsF16 != 0 || half_act_of(c); }
 
-// Points a projection's GEMM at its weights.  e16 weights are used where they lie.  4-bit weights are read as
+// Points a projection's GEMM at its weights.  e16 weights are used where they lie (and, where the stage keeps a copy
+// in operand order, there too).  4-bit weights are read as
 // they are stored by the weight-streaming kernel (decode-sized micro-batches) and by the 4-bit tiles (more rows,
 // half operands); otherwise they are expanded to e16 in the workspace first (one projection at a time; `w1` is
 // the second matrix of the gate/up pair or NULL) and the GEMM reads the expanded copy.
 int bind_weights(stage_handle* st, hipStream_t stream, GemmArgs& g, const void* w0, const void* s0, const void* z0,
-                 const void* w1, const void* s1, const void* z1) {
+                 const void* w1, const void* s1, const void* z1, int layer, size_t copy0, size_t copy1) {
   if (st->cfg.weight_bits != 4) {
     g.w0 = (const e16*)w0;
     g.w1 = (const e16*)w1;
+    // the copies in operand order, where the stage keeps them (plans of the kind that reads them exist only then)
+    if (st->wcopy && copy0 != kNoCopy) {
+      const char* base = st->wcopy + (size_t)layer * st->copies.per_layer;
+      g.wa0 = (const e16*)(base + copy0);
+      if (w1) g.wa1 = (const e16*)(base + copy1);
+    }
     return STAGE_OK;
   }
   const W4Matrix m0{(const uint32_t*)w0, (const e16*)s0, (const e16*)z0};
@@ -411,11 +456,11 @@ int bind_weights(stage_handle* st, hipStream_t stream, GemmArgs& g, const void* 
 // The plan of a projection.  4-bit weights with more than 64 rows and half operands: the tiles that read the stored
 // form.  At most 64 rows: 4-bit weights in their stored form need the streaming kernel; otherwise the shape decides
 // between it and the 64-row tiles.
-GemmPlan plan_projection(const stage_config& c, int m, int n, int k, GemmEpilogue epi, bool two_planes) {
+GemmPlan plan_projection(const stage_config& c, int m, int n, int k, GemmEpilogue epi, bool two_planes, bool arranged) {
   if (c.weight_bits == 4 && tile_w4_supports(m, k, c.weight_group_size, two_planes, operands_half_of(c)))
     return plan_gemm_w4_tile(m, n, k, epi, kNumCus);
   const bool stored_w4 = c.weight_bits == 4 && skinny_w4_supports(m, k, c.weight_group_size, two_planes);
-  return plan_gemm(m, n, k, epi, kNumCus, two_planes, stored_w4 ? kFewRowsStreaming : kFewRowsByShape);
+  return plan_gemm(m, n, k, epi, kNumCus, two_planes, stored_w4 ? kFewRowsStreaming : kFewRowsByShape, arranged);
 }
 
 // The plans of a layer's four projections for one micro-batch; they depend on the shapes only, so they are made -
@@ -437,11 +482,13 @@ int check_plan(const stage_handle* st, int m, const GemmPlan& plan) {
 int plan_layer(const stage_handle* st, int T, bool qkv_two_planes, bool two_planes, LayerPlans* out) {
   const stage_config& c = st->cfg;
   const Dims& d = st->dim;
-  out->qkv = plan_projection(c, T, d.qkv_out, d.H, kEpiStoreF32, qkv_two_planes);
-  out->o = plan_projection(c, T, d.H, d.nq * d.d, kEpiResidualF32, two_planes);
-  out->gateup = plan_projection(c, T, d.F, d.H, kEpiSwiGLU, two_planes);
-  out->down = plan_projection(c, T, d.H, d.F, kEpiResidualF32, two_planes);
-  out->down_out = plan_projection(c, T, d.H, d.F, kEpiResidualOut, two_planes);
+  const CopyLayout& cl = st->copies;
+  const bool have = st->wcopy != nullptr;     // copies in operand order: a projection may be planned on the kernel that reads them
+  out->qkv = plan_projection(c, T, d.qkv_out, d.H, kEpiStoreF32, qkv_two_planes, have && cl.qkv != kNoCopy);
+  out->o = plan_projection(c, T, d.H, d.nq * d.d, kEpiResidualF32, two_planes, have && cl.o != kNoCopy);
+  out->gateup = plan_projection(c, T, d.F, d.H, kEpiSwiGLU, two_planes, have && cl.gate != kNoCopy);
+  out->down = plan_projection(c, T, d.H, d.F, kEpiResidualF32, two_planes, have && cl.down != kNoCopy);
+  out->down_out = plan_projection(c, T, d.H, d.F, kEpiResidualOut, two_planes, have && cl.down != kNoCopy);
   for (const GemmPlan* p : {&out->qkv, &out->o, &out->gateup, &out->down, &out->down_out})
     if (int rc = check_plan(st, T, *p)) return rc;
   return STAGE_OK;
@@ -679,7 +726,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       GemmArgs g{};
       g.a = a; g.a_lo = norm1_lo; g.a_half = half_act; g.out_f32 = qkv_f32; g.partial = splitk;
       g.m = T; g.n = d.qkv_out; g.k = d.H; g.lda = d.H; g.ldo = d.qkv_out;
-      if (int rc = bind_weights(st, stream, g, w.wqkv, w.sqkv, w.zqkv, nullptr, nullptr, nullptr)) return rc;
+      if (int rc = bind_weights(st, stream, g, w.wqkv, w.sqkv, w.zqkv, nullptr, nullptr, nullptr, l, st->copies.qkv, kNoCopy)) return rc;
       // the rotation kernel adds the split-K partial sums itself: no separate reduction pass
       const GemmPlan& plan = plans.qkv;
       {
@@ -713,7 +760,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       GemmArgs g{};
       g.a = attn; g.a_lo = attn_lo; g.a_half = half_act; g.resid = x; g.partial = splitk;
       g.m = T; g.n = d.H; g.k = d.nq * d.d; g.lda = d.nq * d.d; g.ldo = d.H;
-      if (int rc = bind_weights(st, stream, g, w.wo, w.so, w.zo, nullptr, nullptr, nullptr)) return rc;
+      if (int rc = bind_weights(st, stream, g, w.wo, w.so, w.zo, nullptr, nullptr, nullptr, l, st->copies.o, kNoCopy)) return rc;
       int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_O, g, kEpiResidualF32, plans.o, (const e16*)w.norm2, a, a_lo,
                                  half_act);
       if (rc) return rc;
@@ -725,7 +772,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       g.a = a; g.a_lo = a_lo; g.a_half = half_act; g.out_e16 = mlp; g.out_lo = mlp_lo; g.out_half = half_act;
       g.partial = splitk;
       g.m = T; g.n = d.F; g.k = d.H; g.lda = d.H; g.ldo = d.F;
-      if (int rc = bind_weights(st, stream, g, w.wgate, w.sgate, w.zgate, w.wup, w.sup, w.zup)) return rc;
+      if (int rc = bind_weights(st, stream, g, w.wgate, w.sgate, w.zgate, w.wup, w.sup, w.zup, l, st->copies.gate, st->copies.up)) return rc;
       int rc = run_gemm(st, stream, STAGE_K_GEMM_GATEUP, g, kEpiSwiGLU, plans.gateup);
       if (rc) return rc;
     }
@@ -738,7 +785,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       g.a = mlp; g.a_lo = mlp_lo; g.a_half = half_act; g.resid = x; g.out_e16 = (e16*)hidden_out;
       g.partial = splitk;
       g.m = T; g.n = d.H; g.k = d.F; g.lda = d.F; g.ldo = d.H;
-      if (int rc = bind_weights(st, stream, g, w.wdown, w.sdown, w.zdown, nullptr, nullptr, nullptr)) return rc;
+      if (int rc = bind_weights(st, stream, g, w.wdown, w.sdown, w.zdown, nullptr, nullptr, nullptr, l, st->copies.down, kNoCopy)) return rc;
       const e16* next_gain = last ? nullptr : (const e16*)st->layers[l + 1].norm1;
       int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_DOWN, g, fused_out ? kEpiResidualOut : kEpiResidualF32,
                                  fused_out ? plans.down_out : plans.down, next_gain, a, norm1_lo, half_act);
@@ -787,7 +834,7 @@ int stage_workspace_bytes(const stage_config* cfg, size_t* out_bytes) {
   if (!out_bytes) return fail(STAGE_ERR_NULL, "out_bytes is NULL");
   int rc = check_config(cfg);
   if (rc) return rc;
-  *out_bytes = layout_of(*cfg).total;
+  *out_bytes = layout_of(*cfg).total + (size_t)cfg->num_layers * copy_layout_of(*cfg).per_layer;
   return STAGE_OK;
 }
 
@@ -838,7 +885,9 @@ int stage_init(const stage_config* cfg, const stage_layer_weights* layers, void*
   const size_t need_pool = (size_t)(cfg->num_layers - 1) * (size_t)cfg->kv_layer_stride_bytes + layer_bytes;
   if (kv_pool_bytes < need_pool) return fail(STAGE_ERR_SIZE, "kv_pool_bytes %zu < %zu", kv_pool_bytes, need_pool);
   const WorkspaceLayout ws = layout_of(*cfg);
-  if (workspace_bytes < ws.total) return fail(STAGE_ERR_SIZE, "workspace_bytes %zu < %zu", workspace_bytes, ws.total);
+  const CopyLayout copies = copy_layout_of(*cfg);
+  const size_t need_ws = ws.total + (size_t)cfg->num_layers * copies.per_layer;
+  if (workspace_bytes < need_ws) return fail(STAGE_ERR_SIZE, "workspace_bytes %zu < %zu", workspace_bytes, need_ws);
   int ndev = 0;
   HIP_TRY(hipGetDeviceCount(&ndev));
   if (device < 0 || device >= ndev) return fail(STAGE_ERR_CONFIG, "device %d outside [0, %d)", device, ndev);
@@ -855,6 +904,8 @@ int stage_init(const stage_config* cfg, const stage_layer_weights* layers, void*
   st->static_scratch = nullptr;
   st->call_ws = (char*)workspace;
   st->call_layout = &st->ws;
+  st->copies = copies;
+  st->wcopy = copies.per_layer ? (char*)workspace + ws.total : nullptr;
   st->device = device;
   st->next_slot = 0;
   st->profile_mask = 0;
@@ -870,6 +921,27 @@ int stage_init(const stage_config* cfg, const stage_layer_weights* layers, void*
   if (int rc2 = static_scratch_of(device, &st->static_scratch)) {
     stage_destroy(st);
     return rc2;
+  }
+  if (st->wcopy) {
+    // the weights once more, in operand order and in the operand format of this stage's matrix instructions
+    const Dims& d = st->dim;
+    const bool to_half = half_act_of(*cfg);
+    hipError_t e = hipSuccess;
+    for (int l = 0; l < d.L && e == hipSuccess; ++l) {
+      const stage_layer_weights& w = st->layers[l];
+      char* base = st->wcopy + (size_t)l * copies.per_layer;
+      struct { const void* src; size_t at; int n, k; } jobs[5] = {{w.wqkv, copies.qkv, d.qkv_out, d.H}, {w.wo, copies.o, d.H, d.nq * d.d},
+                                                                 {w.wgate, copies.gate, d.F, d.H}, {w.wup, copies.up, d.F, d.H},
+                                                                 {w.wdown, copies.down, d.H, d.F}};
+      for (const auto& j : jobs)
+        if (j.at != kNoCopy && e == hipSuccess)
+          e = launch_arrange_weights((const e16*)j.src, j.n, j.k, to_half, (e16*)(base + j.at), nullptr);
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+    if (e != hipSuccess) {
+      stage_destroy(st);
+      return fail(STAGE_ERR_HIP, "copying the weights into operand order: %s", hipGetErrorString(e));
+    }
   }
   *out = st;
   return STAGE_OK;

@@ -13,11 +13,12 @@ def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_
                max_tokens: Optional[int] = None, alias_layers: bool = False, fill_kv: bool = True,
                device: str = "cuda:0", activation_planes: int = 0, vocab_size: int = 0,
                qkv_bias: bool = False, weight_group_size: int = 0, dtype: torch.dtype = torch.bfloat16,
-               qk_norm: bool = False) -> Stage:
+               qk_norm: bool = False, weight_copies: int = 0) -> Stage:
     """Draw the stage's weights on the device, size the pool and workspace for `mb`, fill the cache.
     weight_group_size > 0: 4-bit group-quantised projection weights with that group size.
     dtype: the 16-bit element type (bfloat16, or float16 for the half-precision library).
-    qk_norm: per-head RMSNorm gains for queries and keys (the Qwen3 family's block)."""
+    qk_norm: per-head RMSNorm gains for queries and keys (the Qwen3 family's block).
+    weight_copies: 1 = the stage keeps no second copy of its weights in operand order."""
     if weight_group_size:
         layers = [synth.draw_w4_layer(shape, l, seed=seed, group=weight_group_size, device=device,
                                       weight_std=0.02 if weight_std is None else float(weight_std), dtype=dtype)
@@ -38,7 +39,7 @@ def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_
                       max_blocks_per_seq=mb.max_blocks_per_seq,
                       kv_layer_stride_bytes=0 if alias_layers else None, activation_planes=activation_planes,
                       vocab_size=vocab_size, weight_bits=4 if weight_group_size else 0,
-                      weight_group_size=weight_group_size, rotary_dim=shape.rotary_dim)
+                      weight_group_size=weight_group_size, rotary_dim=shape.rotary_dim, weight_copies=weight_copies)
     st = Stage(cfg, layers, device=device, dtype=dtype)
     if fill_kv:
         fill_pool(st, shape, mb, seed)

@@ -114,8 +114,8 @@ def test_matrices_of_four_gib_and_more_are_accepted(lib):
 
 
 def test_config_struct_matches_header_size(lib):
-    # uint32 + 6 int32 + 2 float + 2 int32 (+ 4 pad) + int64 + 7 int32 (+ 4 pad)
-    assert ctypes.sizeof(S.StageConfig) == 88
+    # uint32 + 6 int32 + 2 float + 2 int32 (+ 4 pad) + int64 + 9 int32 (+ 4 pad)
+    assert ctypes.sizeof(S.StageConfig) == 96
     assert ctypes.sizeof(S.StageLayerWeights) == 20 * ctypes.sizeof(ctypes.c_void_p)
     assert S.stage_workspace_bytes(tiny_cfg()) > 0
 
@@ -234,3 +234,21 @@ def test_kernel_names(lib):
     assert S.stage_kernel_name(S.KERNEL_CLASSES["attn_decode"]) == "attn_decode_kernel"
     assert S.stage_kernel_name(S.KERNEL_CLASSES["dequant"]) == "dequant_w4_kernel"
     assert S.stage_kernel_name(99) is None
+
+
+def test_weight_copies_are_counted_in_the_workspace(lib):
+    """The second copy of the weights (operand order) sits behind the workspace proper: one more copy of every
+    projection matrix whose input width is a multiple of 256, rows padded to 32, when the stage can see more than 128
+    rows, the weights are 16-bit and the stage runs one activation plane."""
+    def ws(**kw):
+        return S.stage_workspace_bytes(tiny_cfg(**kw))
+    big = dict(hidden=512, num_q_heads=4, num_kv_heads=2, head_dim=128, ffn=1000, max_tokens=300, max_seqs=8)
+    # q/k/v [1024][512], o [512][512], gate and up [1000 -> 1024][512]; down has K = 1000: no copy
+    per_layer = (1024 * 512 + 512 * 512 + 2 * 1024 * 512) * 2
+    assert ws(**big) - ws(weight_copies=1, **big) == 2 * per_layer
+    assert ws(**dict(big, max_tokens=128)) == ws(weight_copies=1, **dict(big, max_tokens=128))
+    assert ws(activation_planes=2, **big) == ws(activation_planes=2, weight_copies=1, **big)
+    w4 = dict(big, ffn=1024, weight_bits=4, weight_group_size=128)
+    assert ws(**w4) == ws(weight_copies=1, **w4)
+    with pytest.raises(S.StageError):
+        ws(weight_copies=2, **big)

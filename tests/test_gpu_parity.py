@@ -45,6 +45,33 @@ def full_parity(shape, mb, seed, weight_std, taps=True, check_kv=True, qkv_bias=
     return stats
 
 
+@pytest.mark.parametrize("planes,elem", [(1, torch.bfloat16), (3, torch.bfloat16), (1, torch.float16)],
+                         ids=["bf16-operands", "half-activations", "f16-library"])
+@pytest.mark.parametrize("rows", [150, 365, 700])
+def test_weights_in_operand_order(planes, elem, rows):
+    """Micro-batches of more than 128 rows run their projections on the kernel that reads the stage's second copy of
+    the weights (operand order, straight into registers): whole-stage parity with taps - in the bfloat16 library with
+    bfloat16 and with half operands, and in the half-precision library -, at one ragged tile row, two and three; the
+    same stage without the copies gives the same output up to the order of the fp32 sums (the two paths cut K
+    differently), and needs the copies' bytes less workspace (and some split-K scratch less)."""
+    from paper_2507_05043_amd.stage import stage_workspace_bytes
+    shape = _shape("mid-k-multiples-of-256", 2, 1024, 8, 2, 128, 2816)
+    pre = rows - 4 - 61
+    mb = synth.make_microbatch([pre, 61, 1, 1, 1, 1], [0, 40, 20, 29, 38, 7], seed=3, max_blocks_per_seq=48)
+    assert mb.num_tokens == rows
+    outs = []
+    for copies in (0, 1):
+        st = H.make_stage(shape, mb, 3, "fan_in", activation_planes=planes, dtype=elem, weight_copies=copies)
+        outs.append((H.run_gpu(st, shape, mb, 3)[0].float(), stage_workspace_bytes(st.cfg, elem)))
+        st.close()
+    copy_bytes = 2 * 2 * (shape.qkv_out * 1024 + 1024 * 1024 + 2 * 2816 * 1024 + 1024 * 2816)
+    assert copy_bytes <= outs[0][1] - outs[1][1] <= copy_bytes + (32 << 20)
+    diff = rel_l2(outs[0][0].double(), outs[1][0].double())
+    print(f"  with against without copies: rel-L2 {diff:.3e}", flush=True)
+    assert diff <= 2e-3
+    full_parity(shape, mb, 3, "fan_in", activation_planes=planes, elem=elem)
+
+
 def test_generator_same_bits_on_gpu_and_cpu():
     a = synth.draw_normal_bf16(0, 7, 100000, std=0.02, mean=1.0)
     b = synth.draw_normal_bf16(0, 7, 100000, std=0.02, mean=1.0, device="cuda:0").cpu()

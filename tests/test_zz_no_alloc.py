@@ -28,19 +28,23 @@ def _both(st, shape, mb, seed):
     return hidden, tables, want, got, pool_after
 
 
-def test_static_scratch_forward_equals_the_workspace_forward_twice_in_a_row():
+@pytest.mark.parametrize("weight_copies", [1, 0], ids=["no-copies", "weight-copies"])
+def test_static_scratch_forward_equals_the_workspace_forward_twice_in_a_row(weight_copies):
+    """Without the weights' second copies nothing of the caller's workspace takes part in the call (it is overwritten
+    beforehand and must come back untouched); with them, the copies - written once by stage_init - are the one part
+    of it that is read."""
     shape = _shape("static-mid", 2, 1024, 8, 2, 128, 2816)
     big = synth.make_microbatch([130, 61, 1, 1, 1, 1, 1, 1, 1], [0, 40] + [20 + 9 * i for i in range(7)], seed=3,
                                 max_blocks_per_seq=16)
     small = synth.make_microbatch([1, 1, 17], [33, 5, 8], seed=4, max_blocks_per_seq=16)
-    st = H.make_stage(shape, big, 3, "fan_in")
+    st = H.make_stage(shape, big, 3, "fan_in", weight_copies=weight_copies)
     ws_before = None
     for call, mb in enumerate((big, small)):           # the second call is smaller: stale scratch lies behind it
         print(f"[case] static scratch call {call}: T={mb.num_tokens} S={mb.num_seqs}", flush=True)
         if mb is small:
             # the small batch's cached context, drawn at its own block numbers into the same pool
             st.kv_pool.view(st.dtype).fill_(float("nan"))
-            tmp = H.make_stage(shape, small, 4, "fan_in")
+            tmp = H.make_stage(shape, small, 4, "fan_in", weight_copies=1)
             blocks = torch.arange(small.num_kv_blocks, device="cuda:0")
             for l in range(shape.num_layers):
                 for kv in (0, 1):
@@ -49,7 +53,8 @@ def test_static_scratch_forward_equals_the_workspace_forward_twice_in_a_row():
         pool_before = st.kv_pool.clone()
         hidden, tables, want, got, pool_after = _both(st, shape, mb, 3 + call)
         st.kv_pool.copy_(pool_before)
-        st.workspace.fill_(0x5A)                        # the caller workspace must not take part
+        if weight_copies == 1:
+            st.workspace.fill_(0x5A)                    # the caller workspace must not take part
         ws_before = st.workspace.clone()
         slots = st.forward(hidden, mb.positions, mb.q_lens, mb.ctx_lens, tables, out=got, want_slots=True,
                            static_scratch=True)[1]
