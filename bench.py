@@ -156,7 +156,14 @@ def run_workload(args, workload, budget, steps, warmup, extras):
     if args.dtype != "bf16" or shape.num_layers < 5:
         inputs = args.dtype
     else:
-        inputs = "IEEE half, bf16 weights converted in the GEMMs"
+        inputs = "IEEE half (bf16 weights converted in the GEMMs, or once into the stage's copies)"
+    without = type(st.cfg).from_buffer_copy(st.cfg)
+    without.weight_copies = 1
+    copy_bytes = _stage.stage_workspace_bytes(st.cfg, st.dtype) - _stage.stage_workspace_bytes(without, st.dtype)
+    copies = (f"second copy of the projection weights in MFMA operand order, written by stage_init "
+              f"({copy_bytes / 1e9:.2f} GB incl. its split-K scratch)" if copy_bytes > 0 else "none")
+    if roofline["bound"] == "mfma" and copy_bytes > 0 and mb.num_tokens > 128:
+        roofline["kernel"] = "gemm_tile_arranged_kernel"   # the projection kernel of a stage that keeps the copies
     tag = f"sweep budget {budget}: " if workload == "sweep" else ""
     result = {
         "value": round(tokens_per_s, 1), "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 4),
@@ -164,7 +171,8 @@ def run_workload(args, workload, budget, steps, warmup, extras):
                                f"nkv={shape.num_kv_heads} d={shape.head_dim} F={shape.ffn}; micro-batch T={mb.num_tokens} "
                                f"S={mb.num_seqs} ({mb.num_seqs - n_dec} prefill chunks, {n_dec} decode tokens), KV block 16",
                    "seed": args.seed, "kv_layers_aliased": bool(alias), "projection_inputs": inputs,
-                   "weights": f"4-bit codes, {args.dtype} scale and zero point per 128 input features" if w4 else args.dtype},
+                   "weights": f"4-bit codes, {args.dtype} scale and zero point per 128 input features" if w4 else args.dtype,
+                   "weight_copies": copies},
         "stage_latency_ms": round(ms_per_step, 4),
         "ideal_ms": {"hbm": round(work["bytes_per_call"] / (HBM_PEAK_GBS * 1e9) * 1e3, 4),
                      "mfma": round(work["flops_per_call"] / (MFMA_BF16_PEAK_TFLOPS * 1e12) * 1e3, 4)},

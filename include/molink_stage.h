@@ -106,10 +106,10 @@ typedef struct {
                                   (section 3.1.3) rotate half of each head.  Not together with qnorm / knorm. */
   int32_t weight_copies;       /* 0: the stage keeps a second copy of its 16-bit projection weights, made by stage_init
                                   in the order and format its matrix instructions take them (IEEE half in a stage
-                                  with half activations), which the tiled GEMMs of micro-batches of more than 128
+                                  with half activations), which the tiled GEMMs of micro-batches of more than 64
                                   rows read straight into registers: about a quarter faster than reading the
                                   caller's row-major matrices through LDS, for one more copy of the weights in the
-                                  workspace (stage_workspace_bytes counts it).  Made only when max_tokens > 128, the
+                                  workspace (stage_workspace_bytes counts it).  Made only when max_tokens > 64, the
                                   weights are 16-bit and activation_planes is not 2; a matrix whose input width is
                                   not a multiple of 256 has none.  1: no copies.  Results agree to the rounding of
                                   the fp32 summation order. */
@@ -362,7 +362,8 @@ int stage_profile_read(stage_handle *st, int32_t kernel, double *out_total_ms, i
 
 /* Name of the device kernel family (as a profiler lists it, without template arguments) that implements a kernel
  * class, for matching profiler output; the projections name their tiled kernel (gemm_tile_kernel) although a
- * launch may run on gemm_tile32_kernel (256 x 256 tiles) or gemm_skinny_kernel (at most 64 rows), and prefill
+ * launch may run on gemm_tile_arranged_kernel (the weights' copies in operand order), gemm_tile32_kernel (256 x
+ * 256 tiles), gemm_tile_w4_kernel (4-bit weights) or gemm_skinny_kernel (at most 64 rows), and prefill
  * attention with two query planes runs on attn_prefill_two_plane_kernel.  Returns NULL for an unknown class. */
 const char *stage_kernel_name(int32_t kernel);
 

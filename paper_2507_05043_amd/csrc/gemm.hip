@@ -843,12 +843,14 @@ template <int N> __device__ __forceinline__ void wait_vm_lgkm0() {
 // written as assembly because the compiler counts a mixture of register loads and LDS-directed loads as unordered
 // and answers it with full waits, and scheduling barriers keep every wait between the instructions it separates.
 // HALF_OPS: the operands are IEEE half (f16 MFMA), else e16.
-template <int EPI, bool SPLIT, bool HALF_OPS>
+// BM: 256, or 128 for products of at most 128 rows (half the MFMA work per weight operand: bound by the weight stream).
+template <int BM, int EPI, bool SPLIT, bool HALF_OPS>
 __global__ __launch_bounds__(256) void gemm_tile_arranged_kernel(GemmArgs p, int nv, int tiles_m, int tiles_n, int splits,
                                                                  int k_tiles_per_split) {
-  constexpr int BM = 256, BN = 256, NWAVES = 4, TM = 128, TN = 128, MT = 4, NT = 4, NSTAGE = 4, RING = 8;
+  static_assert(BM == 128 || BM == 256, "tile rows");
+  constexpr int BN = 256, NWAVES = 4, TM = BM / 2, TN = 128, MT = TM / 32, NT = 4, NSTAGE = 4, RING = 8;
   constexpr int STAGE_BYTES = BM * 128;
-  constexpr int NA = BM / 8 / NWAVES;            // activation loads per wave per tile
+  constexpr int NA = BM / 8 / NWAVES;            // activation loads per wave per tile, issued in three parts
   using Lds = LdsStages<STAGE_BYTES>;
 
   const int total = tiles_m * tiles_n * splits;
@@ -901,7 +903,8 @@ __global__ __launch_bounds__(256) void gemm_tile_arranged_kernel(GemmArgs p, int
   }
   const uint32_t lane_off = lane * 16;
 
-  // part `part` (0..2) of the loads of activation tile idx into stage S: 3 + 3 + 2 instructions
+  // part `part` (0..2) of the loads of activation tile idx into stage S: load j belongs to part 3 j / NA
+  // (3 + 3 + 2 instructions at 256 rows, 2 + 1 + 1 at 128)
   auto fetch_a = [&](auto stage_c, int idx, int part) {
     constexpr int S = decltype(stage_c)::value;
     int kt = kt_begin + idx;
@@ -910,7 +913,7 @@ __global__ __launch_bounds__(256) void gemm_tile_arranged_kernel(GemmArgs p, int
     char* stage = Lds::template get<S>();
 #pragma unroll
     for (int j = 0; j < NA; ++j)
-      if (j / 3 == part)
+      if (3 * j / NA == part)
         __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(abase + a_off[j]),
                                          reinterpret_cast<uint32_t*>(stage + (NWAVES * j + wave) * 1024), 16, 0, 0);
   };
@@ -936,11 +939,13 @@ __global__ __launch_bounds__(256) void gemm_tile_arranged_kernel(GemmArgs p, int
                                   (uint32_t)(uintptr_t)(lds_ptr)(Lds::template get<2>()), (uint32_t)(uintptr_t)(lds_ptr)(Lds::template get<3>())};
   auto read_a = [&](int stage, int set, int kk) {
     const uint32_t at = lds_a[stage] + wm * TM * 128 + frag_off[kk];
-    static_assert(MT == 4, "four fragment reads are written out");
+    static_assert(MT == 2 || MT == 4, "the fragment reads are written out");
     asm volatile("ds_read_b128 %0, %1" : "=v"(af[set][0]) : "v"(at));
     asm volatile("ds_read_b128 %0, %1 offset:4096" : "=v"(af[set][1]) : "v"(at));
-    asm volatile("ds_read_b128 %0, %1 offset:8192" : "=v"(af[set][2]) : "v"(at));
-    asm volatile("ds_read_b128 %0, %1 offset:12288" : "=v"(af[set][3]) : "v"(at));
+    if constexpr (MT == 4) {
+      asm volatile("ds_read_b128 %0, %1 offset:8192" : "=v"(af[set][2]) : "v"(at));
+      asm volatile("ds_read_b128 %0, %1 offset:12288" : "=v"(af[set][3]) : "v"(at));
+    }
   };
   // The operands of local MFMA step `step` (counted from the split's first) into ring slot `slot`; steps past the
   // split's last repeat it (loaded, never multiplied).  Written as assembly so that the wait for them is the
@@ -967,12 +972,16 @@ __global__ __launch_bounds__(256) void gemm_tile_arranged_kernel(GemmArgs p, int
     }
   };
 
-  // Loads issued per MFMA step: a part of the next activation tile (3, 3, 2, 0 instructions) and the step's NT weight
-  // operands, i.e. 7, 7, 6, 4; 24 per tile.  The weight operands of a step were requested eight steps earlier, at
-  // the end of that step: when the step begins, everything but the loads of the seven steps in between has to have
-  // landed (loads complete in order) - 48 minus the issuing step's own count.  That wait also covers the activation
-  // tile, whose last part was requested earlier still.
-  constexpr int kWait0 = 48 - 7, kWait1 = 48 - 7, kWait2 = 48 - 6, kWait3 = 48 - 4;
+  // Loads issued per MFMA step: a part of the next activation tile (3, 3, 2, 0 instructions at 256 rows) and the
+  // step's NT weight operands, i.e. 7, 7, 6, 4; 24 per tile.  The weight operands of a step were requested eight steps
+  // earlier, at the end of that step: when the step begins, everything but the loads of the seven steps in between
+  // has to have landed (loads complete in order) - 48 minus the issuing step's own count.  That wait also covers the
+  // activation tile, whose last part was requested earlier still.
+  constexpr int kPart0 = (NA + 2) / 3, kPart1 = (2 * NA + 2) / 3 - kPart0, kPart2 = NA - kPart0 - kPart1;
+  static_assert(kPart0 == (NA == 8 ? 3 : 2) && kPart1 == (NA == 8 ? 3 : 1) && kPart2 == (NA == 8 ? 2 : 1), "parts as fetch_a cuts them");
+  constexpr int kTwoTiles = 2 * (NA + 4 * NT);
+  constexpr int kWait0 = kTwoTiles - (kPart0 + NT), kWait1 = kTwoTiles - (kPart1 + NT), kWait2 = kTwoTiles - (kPart2 + NT),
+                kWait3 = kTwoTiles - NT;
   // Tile idx (activations in stage S, weight operands in ring slots 4 P .. 4 P + 3); the activation tile idx + 3 goes
   // into the stage read in the previous tile; a step's weight operands are requested eight steps ahead, into the
   // slot the step's MFMAs have just read.
@@ -1353,33 +1362,36 @@ hipError_t launch_tile_w4(const GemmArgs& a, const GemmPlan& plan, hipStream_t s
   return plan.tile == kTileW4x128 ? launch_tile_w4<128, EPI>(a, plan, stream) : launch_tile_w4<256, EPI>(a, plan, stream);
 }
 
-template <int EPI>
+template <int BM, int EPI>
 hipError_t launch_tile_arranged(const GemmArgs& a, const GemmPlan& plan, hipStream_t stream) {
-  const int tiles_m = (a.m + 255) / 256;
+  const int tiles_m = (a.m + BM - 1) / BM;
   const int tiles_n = (plan.nv + 255) / 256;
   const int total = tiles_m * tiles_n * plan.splits;
   dim3 grid(xcd_grid(total)), block(256);
-  constexpr bool kHalfOps = true;
   if (a.a_half) {
 #ifdef MOLINK_F16
     return hipErrorInvalidValue;   // the element type is half already
 #else
     if (plan.splits > 1)
-      hipLaunchKernelGGL((gemm_tile_arranged_kernel<EPI, true, kHalfOps>), grid, block, 0, stream, a, plan.nv, tiles_m, tiles_n,
+      hipLaunchKernelGGL((gemm_tile_arranged_kernel<BM, EPI, true, true>), grid, block, 0, stream, a, plan.nv, tiles_m, tiles_n,
                          plan.splits, plan.k_tiles_per_split);
     else
-      hipLaunchKernelGGL((gemm_tile_arranged_kernel<EPI, false, kHalfOps>), grid, block, 0, stream, a, plan.nv, tiles_m, tiles_n, 1,
+      hipLaunchKernelGGL((gemm_tile_arranged_kernel<BM, EPI, false, true>), grid, block, 0, stream, a, plan.nv, tiles_m, tiles_n, 1,
                          plan.k_tiles_per_split);
     return hipGetLastError();
 #endif
   }
   if (plan.splits > 1)
-    hipLaunchKernelGGL((gemm_tile_arranged_kernel<EPI, true, false>), grid, block, 0, stream, a, plan.nv, tiles_m, tiles_n, plan.splits,
+    hipLaunchKernelGGL((gemm_tile_arranged_kernel<BM, EPI, true, false>), grid, block, 0, stream, a, plan.nv, tiles_m, tiles_n, plan.splits,
                        plan.k_tiles_per_split);
   else
-    hipLaunchKernelGGL((gemm_tile_arranged_kernel<EPI, false, false>), grid, block, 0, stream, a, plan.nv, tiles_m, tiles_n, 1,
+    hipLaunchKernelGGL((gemm_tile_arranged_kernel<BM, EPI, false, false>), grid, block, 0, stream, a, plan.nv, tiles_m, tiles_n, 1,
                        plan.k_tiles_per_split);
   return hipGetLastError();
+}
+template <int EPI>
+hipError_t launch_tile_arranged(const GemmArgs& a, const GemmPlan& plan, hipStream_t stream) {
+  return plan.tile == kTileArranged128 ? launch_tile_arranged<128, EPI>(a, plan, stream) : launch_tile_arranged<256, EPI>(a, plan, stream);
 }
 
 template <int EPI>
@@ -1432,13 +1444,15 @@ hipError_t launch_epi(const GemmArgs& a, const GemmPlan& plan, hipStream_t strea
 GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool split_a, GemmFewRows few_rows, bool arranged) {
   GemmPlan plan;
   plan.nv = epi == kEpiSwiGLU ? ((n + 31) / 32) * 64 : n;
-  if (arranged && arranged_weights_supported(k) && !split_a && m > 128) {
-    // The kernel that reads the weights in operand order: 256 x 256 tiles, one workgroup per CU, a split a multiple
-    // of four K tiles.  Measured against the tiles below on eighteen shapes of the 7B, 70B and Qwen2 stages at 192 to
-    // 2176 rows it is 4 to 32 % ahead everywhere except where few tiles meet many short splits (256 rows, 32 - 40
-    // tiles, 6 - 8 splits of 16 - 24 K tiles: 7 - 17 % behind; 192 rows, 8 splits of 56: 7 % behind), hence the rule.
+  if (arranged && arranged_weights_supported(k) && !split_a && m > 64) {
+    // The kernel that reads the weights in operand order: 256-row tiles (128-row ones up to 128 rows), 256 columns,
+    // one workgroup per CU, a split a multiple of four K tiles.  Measured against the tiles below on the shapes of
+    // the 7B, 70B and Qwen2 stages at 128 to 2176 rows it is 4 to 32 % ahead everywhere except where few tiles meet
+    // many short splits (256 rows, 32 - 40 tiles, 6 - 8 splits of 16 - 24 K tiles: 7 - 17 % behind; 192 rows, 8
+    // splits of 56: 7 % behind; 128 rows, 6 - 8 splits: level), hence the rule.
+    const int bm = m <= 128 ? 128 : 256;
     const int k_tiles = k / kBK;
-    const int tiles = ((m + 255) / 256) * ((plan.nv + 255) / 256);
+    const int tiles = ((m + bm - 1) / bm) * ((plan.nv + 255) / 256);
     int splits = 1;
     if (tiles * 2 <= num_cus) {
       splits = num_cus / tiles;
@@ -1449,7 +1463,7 @@ GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool spli
     const int per = ((k_tiles + splits - 1) / splits + 3) / 4 * 4;
     splits = (k_tiles + per - 1) / per;
     if (splits <= 4 || (per >= 48 && m > 192)) {
-      plan.tile = kTileArranged;
+      plan.tile = bm == 128 ? kTileArranged128 : kTileArranged;
       plan.k_tiles_per_split = per;
       plan.splits = splits;
       plan.partials = splits > 1;
@@ -1626,7 +1640,7 @@ hipError_t launch_gemm_main(const GemmArgs& a, GemmEpilogue epi, const GemmPlan&
                        epi == kEpiSwiGLU ? 1 : 0);
     return hipGetLastError();
   }
-  if (plan.tile == kTileArranged) {
+  if (plan.tile == kTileArranged || plan.tile == kTileArranged128) {
     if (!a.wa0 || (epi == kEpiSwiGLU && !a.wa1) || a.a_lo || a.m <= 64 || a.k % 256 || plan.k_tiles_per_split % 4)
       return hipErrorInvalidValue;
     switch (epi) {

@@ -48,9 +48,9 @@ struct GemmArgs {
 // kTileSkinny: at most 64 rows; K cut into slices of 1024, weights streamed in groups of 16 rows, always
 // through partial sums (the reduction applies the epilogue).
 // kTileW4, kTileW4x128: 256 x 256 and 128 x 256 tiles on 4-bit weights in their stored form (more than 64 rows,
-// half operands).  kTileArranged: 256 x 256 tiles that read the weights' copy in operand order (GemmArgs::wa0 / wa1)
+// half operands).  kTileArranged, kTileArranged128: 256 x 256 and 128 x 256 tiles that read the weights' copy in operand order (GemmArgs::wa0 / wa1)
 // straight into registers.
-enum GemmTile : int { kTile256x256 = 0, kTile256x128 = 1, kTile128x128 = 2, kTile64x128 = 3, kTileSkinny = 4, kTile128x256 = 5, kTileW4 = 6, kTileW4x128 = 7, kTileArranged = 8 };
+enum GemmTile : int { kTile256x256 = 0, kTile256x128 = 1, kTile128x128 = 2, kTile64x128 = 3, kTileSkinny = 4, kTile128x256 = 5, kTileW4 = 6, kTileW4x128 = 7, kTileArranged = 8, kTileArranged128 = 9 };
 
 struct GemmPlan {
   int tile;             // GemmTile: workgroup tile shape

@@ -186,7 +186,7 @@ int decode_target_items(const Dims& d) { return (kNumCus * kDecodeWavesPerCu + d
 
 // Second copies of the projection weights in operand order (gemm_tile_arranged_kernel), behind the workspace proper.
 // Possible whenever the weights are 16-bit and the stage runs one activation plane; made when the stage can see a
-// micro-batch of more than 128 rows (smaller ones never use them).  A matrix whose K is not a multiple of 256 has none.
+// micro-batch of more than 64 rows (smaller ones never use them).  A matrix whose K is not a multiple of 256 has none.
 constexpr size_t kNoCopy = ~(size_t)0;
 struct CopyLayout {
   size_t qkv, o, gate, up, down;   // byte offsets inside one layer's copies, or kNoCopy
@@ -197,7 +197,7 @@ bool copies_possible(const stage_config& c) { return c.weight_copies == 0 && c.w
 CopyLayout copy_layout_of(const stage_config& c) {
   const Dims d = dims_of(c);
   CopyLayout cl{kNoCopy, kNoCopy, kNoCopy, kNoCopy, kNoCopy, 0};
-  if (!copies_possible(c) || c.max_tokens <= 128) return cl;
+  if (!copies_possible(c) || c.max_tokens <= 64) return cl;
   size_t off = 0;
   auto take = [&](int n, int k) {
     if (!arranged_weights_supported(k)) return kNoCopy;

@@ -97,7 +97,7 @@ def test_automatic_activation_mode_goes_by_depth(lib):
     """Left to the library, the bfloat16 stage carries one bfloat16 plane up to four layers, half activations from
     five and the extra half plane of the q/k/v input from nine; seen from the host as the workspace each mode needs."""
     def ws(layers, planes, dtype=torch.bfloat16):
-        return S.stage_workspace_bytes(tiny_cfg(num_layers=layers, activation_planes=planes), dtype)
+        return S.stage_workspace_bytes(tiny_cfg(num_layers=layers, activation_planes=planes, weight_copies=1), dtype)
     for layers, mode in ((1, 1), (4, 1), (5, 3), (8, 3), (9, 4), (20, 4)):
         assert ws(layers, 0) == ws(layers, mode), (layers, mode)
     assert ws(8, 1) < ws(8, 3) < ws(8, 4) <= ws(8, 2)
@@ -223,7 +223,7 @@ def test_output_head_adds_its_scratch_to_the_workspace(lib):
 
 
 def test_four_bit_weights_add_room_for_one_expanded_projection(lib):
-    base = S.stage_workspace_bytes(tiny_cfg(ffn=768))
+    base = S.stage_workspace_bytes(tiny_cfg(ffn=768, weight_copies=1))
     w4 = S.stage_workspace_bytes(tiny_cfg(ffn=768, weight_bits=4, weight_group_size=128))
     assert w4 - base >= 2 * 768 * 256 * 2          # gate and up [F][H] as bf16
 
@@ -238,7 +238,7 @@ def test_kernel_names(lib):
 
 def test_weight_copies_are_counted_in_the_workspace(lib):
     """The second copy of the weights (operand order) sits behind the workspace proper: one more copy of every
-    projection matrix whose input width is a multiple of 256, rows padded to 32, when the stage can see more than 128
+    projection matrix whose input width is a multiple of 256, rows padded to 32, when the stage can see more than 64
     rows, the weights are 16-bit and the stage runs one activation plane."""
     def ws(**kw):
         return S.stage_workspace_bytes(tiny_cfg(**kw))
@@ -246,7 +246,7 @@ def test_weight_copies_are_counted_in_the_workspace(lib):
     # q/k/v [1024][512], o [512][512], gate and up [1000 -> 1024][512]; down has K = 1000: no copy
     per_layer = (1024 * 512 + 512 * 512 + 2 * 1024 * 512) * 2
     assert ws(**big) - ws(weight_copies=1, **big) == 2 * per_layer
-    assert ws(**dict(big, max_tokens=128)) == ws(weight_copies=1, **dict(big, max_tokens=128))
+    assert ws(**dict(big, max_tokens=64)) == ws(weight_copies=1, **dict(big, max_tokens=64))
     assert ws(activation_planes=2, **big) == ws(activation_planes=2, weight_copies=1, **big)
     w4 = dict(big, ffn=1024, weight_bits=4, weight_group_size=128)
     assert ws(**w4) == ws(weight_copies=1, **w4)

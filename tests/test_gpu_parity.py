@@ -47,11 +47,11 @@ def full_parity(shape, mb, seed, weight_std, taps=True, check_kv=True, qkv_bias=
 
 @pytest.mark.parametrize("planes,elem", [(1, torch.bfloat16), (3, torch.bfloat16), (1, torch.float16)],
                          ids=["bf16-operands", "half-activations", "f16-library"])
-@pytest.mark.parametrize("rows", [150, 365, 700])
+@pytest.mark.parametrize("rows", [100, 150, 365, 700])
 def test_weights_in_operand_order(planes, elem, rows):
-    """Micro-batches of more than 128 rows run their projections on the kernel that reads the stage's second copy of
+    """Micro-batches of more than 64 rows run their projections on the kernel that reads the stage's second copy of
     the weights (operand order, straight into registers): whole-stage parity with taps - in the bfloat16 library with
-    bfloat16 and with half operands, and in the half-precision library -, at one ragged tile row, two and three; the
+    bfloat16 and with half operands, and in the half-precision library -, at 100 rows (the 128-row tile), one ragged 256-row tile row, two and three; the
     same stage without the copies gives the same output up to the order of the fp32 sums (the two paths cut K
     differently), and needs the copies' bytes less workspace (and some split-K scratch less)."""
     from paper_2507_05043_amd.stage import stage_workspace_bytes
