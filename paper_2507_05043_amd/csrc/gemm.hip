@@ -1450,24 +1450,29 @@ GemmPlan plan_gemm(int m, int n, int k, GemmEpilogue epi, int num_cus, bool spli
     // the 7B, 70B and Qwen2 stages at 128 to 2176 rows it is 4 to 32 % ahead everywhere except where few tiles meet
     // many short splits (256 rows, 32 - 40 tiles, 6 - 8 splits of 16 - 24 K tiles: 7 - 17 % behind; 192 rows, 8
     // splits of 56: 7 % behind; 128 rows, 6 - 8 splits: level), hence the rule.
-    const int bm = m <= 128 ? 128 : 256;
+    // (Two rows of 128-row tiles where the 256-row tile is turned down at 256 rows - half the splits - measured
+    // level or ahead alone, 53 -> 48 us on 8192 x 8192, but level or behind inside the 70B-shaped stage, 58 -> 65 us
+    // on its q/k/v projection: not taken.)
     const int k_tiles = k / kBK;
-    const int tiles = ((m + bm - 1) / bm) * ((plan.nv + 255) / 256);
-    int splits = 1;
-    if (tiles * 2 <= num_cus) {
-      splits = num_cus / tiles;
-      const int max_by_k = k_tiles / 4 > 0 ? k_tiles / 4 : 1;
-      if (splits > max_by_k) splits = max_by_k;
-      if (splits > 16) splits = 16;
-    }
-    const int per = ((k_tiles + splits - 1) / splits + 3) / 4 * 4;
-    splits = (k_tiles + per - 1) / per;
-    if (splits <= 4 || (per >= 48 && m > 192)) {
-      plan.tile = bm == 128 ? kTileArranged128 : kTileArranged;
-      plan.k_tiles_per_split = per;
-      plan.splits = splits;
-      plan.partials = splits > 1;
-      return plan;
+    {
+      const int bm = m <= 128 ? 128 : 256;
+      const int tiles = ((m + bm - 1) / bm) * ((plan.nv + 255) / 256);
+      int splits = 1;
+      if (tiles * 2 <= num_cus) {
+        splits = num_cus / tiles;
+        const int max_by_k = k_tiles / 4 > 0 ? k_tiles / 4 : 1;
+        if (splits > max_by_k) splits = max_by_k;
+        if (splits > 16) splits = 16;
+      }
+      const int per = ((k_tiles + splits - 1) / splits + 3) / 4 * 4;
+      splits = (k_tiles + per - 1) / per;
+      if (splits <= 4 || (bm == 256 && per >= 48 && m > 192)) {
+        plan.tile = bm == 128 ? kTileArranged128 : kTileArranged;
+        plan.k_tiles_per_split = per;
+        plan.splits = splits;
+        plan.partials = splits > 1;
+        return plan;
+      }
     }
   }
   const bool wide = k >= 8192 && (long)plan.nv * k >= (64L << 20);
@@ -1643,13 +1648,43 @@ hipError_t launch_gemm_main(const GemmArgs& a, GemmEpilogue epi, const GemmPlan&
   if (plan.tile == kTileArranged || plan.tile == kTileArranged128) {
     if (!a.wa0 || (epi == kEpiSwiGLU && !a.wa1) || a.a_lo || a.m <= 64 || a.k % 256 || plan.k_tiles_per_split % 4)
       return hipErrorInvalidValue;
-    switch (epi) {
-      case kEpiStoreF32: return launch_tile_arranged<kEpiStoreF32>(a, plan, stream);
-      case kEpiResidualF32: return launch_tile_arranged<kEpiResidualF32>(a, plan, stream);
-      case kEpiResidualOut: return launch_tile_arranged<kEpiResidualOut>(a, plan, stream);
-      case kEpiSwiGLU: return launch_tile_arranged<kEpiSwiGLU>(a, plan, stream);
+    auto launch = [&](const GemmArgs& g, const GemmPlan& pl) {
+      switch (epi) {
+        case kEpiStoreF32: return launch_tile_arranged<kEpiStoreF32>(g, pl, stream);
+        case kEpiResidualF32: return launch_tile_arranged<kEpiResidualF32>(g, pl, stream);
+        case kEpiResidualOut: return launch_tile_arranged<kEpiResidualOut>(g, pl, stream);
+        case kEpiSwiGLU: return launch_tile_arranged<kEpiSwiGLU>(g, pl, stream);
+      }
+      return hipErrorInvalidValue;
+    };
+    // A last tile row of at most 128 rows, where it costs a whole round of workgroups of its own (2176 rows x 148
+    // tile columns: 1332 tiles are six rounds on 256 CUs, 1184 are five), goes to a second launch on 128-row tiles,
+    // which take about 0.55 of a 256-row tile's time.  Without K splits only: the two launches then share nothing.
+    const int rest = a.m % 256;
+    if (plan.tile == kTileArranged && plan.splits == 1 && a.m > 256 && rest > 0 && rest <= 128) {
+      const long tiles_n = (plan.nv + 255) / 256, cus = 256;
+      const long full_rows = a.m / 256;
+      const float one = (float)(((full_rows + 1) * tiles_n + cus - 1) / cus);
+      const float two = (float)((full_rows * tiles_n + cus - 1) / cus) + 0.55f * (float)((tiles_n + cus - 1) / cus);
+      if (two < one - 0.1f) {
+        GemmArgs head = a;
+        head.m = a.m - rest;
+        hipError_t e = launch(head, plan);
+        if (e != hipSuccess) return e;
+        GemmArgs tail = a;
+        const size_t at = (size_t)head.m;
+        tail.m = rest;
+        tail.a = a.a + at * a.lda;
+        if (a.out_e16) tail.out_e16 = a.out_e16 + at * a.ldo;
+        if (a.out_lo) tail.out_lo = a.out_lo + at * a.ldo;
+        if (a.out_f32) tail.out_f32 = a.out_f32 + at * a.ldo;
+        if (a.resid) tail.resid = a.resid + at * a.n;
+        GemmPlan tail_plan = plan;
+        tail_plan.tile = kTileArranged128;
+        return launch(tail, tail_plan);
+      }
     }
-    return hipErrorInvalidValue;
+    return launch(a, plan);
   }
   if (plan.tile == kTileW4 || plan.tile == kTileW4x128) {
     if (!a.q0.codes || (epi == kEpiSwiGLU && !a.q1.codes) || a.a_lo || !(a.a_half || kElemIsF16) || a.k % 256)
