@@ -19,7 +19,9 @@ and an optional RMSNorm over each query head and each key head (gains "qnorm",
 "knorm" of head_dim elements, the stage's eps) between the bias and the
 rotation, which is how the Qwen3 family of the same table (section 3.1.3)
 defines its block; optionally only the first rotary_dim elements of every head
-rotate (the GLM / ChatGLM families of that table); no final norm.
+rotate, and optionally the rotation pairs neighbouring elements (2i, 2i + 1)
+instead of (i, i + d/2) - the two together are the rotary embedding of the GLM /
+ChatGLM families of that table; no final norm.
 
 Numerics: every tensor is widened to `dtype` (float64 by default) on entry and
 nothing is rounded afterwards.  Library primitives used as steps: matmul,
@@ -39,7 +41,10 @@ for bit, a bfloat16 store rounds exactly the appended slots once, scalar loops
 that read back what they stored, chunked == unsplit under it; partial rotary:
 rotary_dim = head_dim is the default bit for bit, the elements past rotary_dim
 are the unrotated projection, the rotated part is the rotation of a head of that
-size, scalar loops with it.  The paper prints no numeric values
+size, scalar loops with it; neighbour pairing: equal to the half-split rotation
+of the head with its even elements first and its odd elements last, put back in
+place (a permutation identity), a literal angle, scalar loops with it.  The
+paper prints no numeric values
 for this path, so parity against printed values is unpinned; parity is against
 the definition.
 """
@@ -64,6 +69,7 @@ class OracleShape:
     rope_theta: float = 1e4
     kv_block_size: int = 16
     rotary_dim: int = 0          # 0: the whole head rotates; else only its first rotary_dim elements do
+    rope_interleaved: bool = False   # False: pairs (i, i + d/2); True: pairs (2i, 2i + 1)
 
 
 def new_pool(shape: OracleShape, num_kv_blocks: int, dtype=torch.float64, fill=float("nan")) -> torch.Tensor:
@@ -78,17 +84,19 @@ def rmsnorm(x: torch.Tensor, gain: torch.Tensor, eps: float) -> torch.Tensor:
     return x * gain / torch.sqrt(ms + eps)
 
 
-def rope_rotate(u: torch.Tensor, pos: torch.Tensor, theta: float, rotary_dim: int = 0) -> torch.Tensor:
-    """Rotary embedding, half-split pairing.  u: [T, heads, d]; pos: [T] integers.
+def rope_rotate(u: torch.Tensor, pos: torch.Tensor, theta: float, rotary_dim: int = 0,
+                interleaved: bool = False) -> torch.Tensor:
+    """Rotary embedding.  u: [T, heads, d]; pos: [T] integers.
 
-    Pair (i, i + d/2) of every head is rotated by the angle pos * theta**(-2i/d).
+    Half-split pairing (the default): pair (i, i + d/2) of every head is rotated by the angle
+    pos * theta**(-2i/d).  Neighbour pairing (interleaved): pair (2i, 2i + 1) is rotated by the same angle.
     Angles, cos and sin are evaluated in float64.
-    Partial rotary (the GLM / ChatGLM families of the paper's model table, section 3.1.3): with
-    0 < rotary_dim < d only the first rotary_dim elements of a head rotate, as a head of that size would
-    (pairs (i, i + rotary_dim/2), angles pos * theta**(-2i/rotary_dim)); the rest pass through.
+    Partial rotary (the GLM / ChatGLM families of the paper's model table, section 3.1.3, which also pair
+    neighbours): with 0 < rotary_dim < d only the first rotary_dim elements of a head rotate, as a head of that
+    size would (angles pos * theta**(-2i/rotary_dim)); the rest pass through.
     """
     if rotary_dim and rotary_dim < u.shape[-1]:
-        return torch.cat([rope_rotate(u[..., :rotary_dim], pos, theta), u[..., rotary_dim:]], dim=-1)
+        return torch.cat([rope_rotate(u[..., :rotary_dim], pos, theta, 0, interleaved), u[..., rotary_dim:]], dim=-1)
     t, _, d = u.shape
     half = d // 2
     i = torch.arange(half, dtype=torch.float64)
@@ -96,6 +104,12 @@ def rope_rotate(u: torch.Tensor, pos: torch.Tensor, theta: float, rotary_dim: in
     ang = pos.to(torch.float64).view(t, 1) * inv_freq.view(1, half)      # [T, d/2]
     cos = torch.cos(ang).to(u.dtype).view(t, 1, half)
     sin = torch.sin(ang).to(u.dtype).view(t, 1, half)
+    if interleaved:
+        first, second = u[..., 0::2], u[..., 1::2]
+        out = torch.empty_like(u)
+        out[..., 0::2] = first * cos - second * sin
+        out[..., 1::2] = second * cos + first * sin
+        return out
     lo, hi = u[..., :half], u[..., half:]
     return torch.cat([lo * cos - hi * sin, hi * cos + lo * sin], dim=-1)
 
@@ -162,8 +176,8 @@ def decoder_layer(shape: OracleShape, w: Dict[str, torch.Tensor], x: torch.Tenso
     if w.get("qnorm") is not None:                                    # optional per-head norm (Qwen3 family)
         q = rmsnorm(q, w["qnorm"].to(dt), shape.rms_eps)              # over the d elements of each head
         k = rmsnorm(k, w["knorm"].to(dt), shape.rms_eps)
-    q = rope_rotate(q, pos, shape.rope_theta, shape.rotary_dim)
-    k = rope_rotate(k, pos, shape.rope_theta, shape.rotary_dim)
+    q = rope_rotate(q, pos, shape.rope_theta, shape.rotary_dim, shape.rope_interleaved)
+    k = rope_rotate(k, pos, shape.rope_theta, shape.rotary_dim, shape.rope_interleaved)
     # append the new tokens' keys (rotated) and values at their slots
     slot_t = torch.as_tensor(slots, dtype=torch.int64)
     k_st = k if kv_store_dtype is None else k.to(kv_store_dtype).to(dt)

@@ -137,6 +137,7 @@ class StageShape:
     kv_block_size: int = 16
     vocab: int = 0          # vocabulary size of the model the stage is cut from (embedding / output head)
     rotary_dim: int = 0     # 0: whole heads rotate; else only the first rotary_dim elements of every head
+    rope_interleaved: bool = False   # rotation pairs: (i, i + d/2), or neighbours (2i, 2i + 1)
 
     @property
     def qkv_out(self) -> int:

@@ -17,18 +17,20 @@ def matvec(w, x):
     return [sum(w[o][i] * x[i] for i in range(len(x))) for o in range(len(w))]
 
 
-def rope_head(u, p, theta, rotary_dim=0):
-    """rotary_dim > 0: only u[:rotary_dim] rotates (as a head of that size), the rest is copied."""
+def rope_head(u, p, theta, rotary_dim=0, interleaved=False):
+    """rotary_dim > 0: only u[:rotary_dim] rotates (as a head of that size), the rest is copied.
+    interleaved: element 2i is rotated with element 2i + 1 instead of element i with element i + d/2."""
     if rotary_dim and rotary_dim < len(u):
-        return rope_head(u[:rotary_dim], p, theta) + list(u[rotary_dim:])
+        return rope_head(u[:rotary_dim], p, theta, 0, interleaved) + list(u[rotary_dim:])
     d = len(u)
     half = d // 2
     y = [0.0] * d
     for i in range(half):
         ang = p * theta ** (-2.0 * i / d)
         c, s = math.cos(ang), math.sin(ang)
-        y[i] = u[i] * c - u[i + half] * s
-        y[i + half] = u[i + half] * c + u[i] * s
+        a, b = (2 * i, 2 * i + 1) if interleaved else (i, i + half)
+        y[a] = u[a] * c - u[b] * s
+        y[b] = u[b] * c + u[a] * s
     return y
 
 
@@ -49,9 +51,9 @@ def layer_one_sequence(shape, w, rows, pos, cache_k, cache_v):
         if w.get("qnorm") is not None:            # per-head norm of queries and keys, before the rotation
             qh = [rmsnorm_row(u, w["qnorm"], shape.rms_eps) for u in qh]
             kh = [rmsnorm_row(u, w["knorm"], shape.rms_eps) for u in kh]
-        rd = getattr(shape, "rotary_dim", 0)
-        q = [rope_head(u, pos[n], shape.rope_theta, rd) for u in qh]
-        k = [rope_head(u, pos[n], shape.rope_theta, rd) for u in kh]
+        rd, il = getattr(shape, "rotary_dim", 0), getattr(shape, "rope_interleaved", False)
+        q = [rope_head(u, pos[n], shape.rope_theta, rd, il) for u in qh]
+        k = [rope_head(u, pos[n], shape.rope_theta, rd, il) for u in kh]
         v = [qkv[(nq + nkv + r) * d:(nq + nkv + r + 1) * d] for r in range(nkv)]
         cache_k.append(k)
         cache_v.append(v)

@@ -12,7 +12,7 @@ from paper_2507_05043_amd import synth
 def oracle_shape(shape: synth.StageShape) -> oracle.OracleShape:
     return oracle.OracleShape(shape.num_layers, shape.hidden, shape.num_q_heads, shape.num_kv_heads,
                               shape.head_dim, shape.ffn, shape.rms_eps, shape.rope_theta,
-                              shape.kv_block_size, shape.rotary_dim)
+                              shape.kv_block_size, shape.rotary_dim, shape.rope_interleaved)
 
 
 def draw_layers(shape: synth.StageShape, seed: int, weight_std=None, device="cpu",

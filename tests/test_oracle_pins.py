@@ -406,6 +406,71 @@ def test_partial_rotary_rotates_a_head_of_its_own_size_and_passes_the_rest():
     assert not torch.allclose(part[0]["x"], full[0]["x"], rtol=1e-3)
 
 
+# ---------------------------------------------------------------- rotation of neighbouring elements
+
+@pytest.mark.parametrize("nq,nkv,rd", [(4, 2, 0), (4, 2, 4), (3, 3, 6)])
+def test_neighbour_pairing_matches_scalar_loops(nq, nkv, rd):
+    """Whole heads and partial rotary (the GLM / ChatGLM block), two layers, prefill with and without prefix, decode."""
+    shape = small_shape(num_q_heads=nq, num_kv_heads=nkv, hidden=12, ffn=20, head_dim=8, kv_block_size=4, rotary_dim=rd,
+                        rope_interleaved=True)
+    q_lens, ctx_lens = [5, 1, 3], [0, 6, 2]
+    mb = synth.make_microbatch(q_lens, ctx_lens, seed=3, block=4)
+    layers = draw_layers(shape, 3, "fan_in")
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=3)
+    pool = oracle_pool(shape, mb, 3)
+    pool0 = pool.clone()
+    out, _, _ = run_oracle(shape, mb, layers=layers, hidden=hidden, pool=pool)
+    got, row0 = [], 0
+    x_rows = hidden.double().tolist()
+    for s, (q, c) in enumerate(zip(q_lens, ctx_lens)):
+        rows = x_rows[row0:row0 + q]
+        for l in range(shape.num_layers):
+            w = {k: v.double().tolist() for k, v in layers[l].items()}
+            ck, cv = [], []
+            for j in range(c):
+                blk = int(mb.block_tables[s][j // 4])
+                ck.append(pool0[l, 0, blk, j % 4].tolist())
+                cv.append(pool0[l, 1, blk, j % 4].tolist())
+            rows = brute_force.layer_one_sequence(shape, w, rows, list(range(c, c + q)), ck, cv)
+        got.extend(rows)
+        row0 += q
+    got = torch.tensor(got, dtype=F64)
+    assert torch.allclose(out, got, rtol=1e-10, atol=1e-11), float((out - got).abs().max())
+    import dataclasses
+    other, _, _ = run_oracle(dataclasses.replace(shape, rope_interleaved=False), mb, layers=layers, hidden=hidden,
+                             pool=oracle_pool(shape, mb, 3))
+    assert not torch.allclose(out, other, rtol=1e-3)             # the pairing matters
+
+
+def test_neighbour_pairing_is_the_half_split_rotation_of_the_regrouped_head():
+    """Moving a head's even elements to the front and its odd elements to the back turns neighbour pairs into
+    half-split pairs with the same index, hence the same angles: rotating the regrouped head the half-split way
+    and moving the elements back is the neighbour rotation (bit for bit: the same products and sums).  Also with
+    a partial rotary size, and one literal angle."""
+    gen = torch.Generator().manual_seed(5)
+    u = torch.randn(7, 3, 16, generator=gen, dtype=F64)
+    pos = torch.tensor([0, 1, 2, 9, 100, 1000, 4095])
+    for rd in (0, 8):
+        n = rd or 16
+        got = oracle.rope_rotate(u, pos, 1e4, rd, True)
+        head = u[..., :n]
+        regrouped = torch.cat([head[..., 0::2], head[..., 1::2]], dim=-1)
+        rot = oracle.rope_rotate(regrouped, pos, 1e4)
+        back = torch.empty_like(head)
+        back[..., 0::2] = rot[..., : n // 2]
+        back[..., 1::2] = rot[..., n // 2:]
+        assert torch.equal(got[..., :n], back)
+        assert torch.equal(got[..., n:], u[..., n:])
+        norm = lambda x: x.pow(2).sum(-1)
+        assert torch.allclose(norm(got), norm(u), rtol=1e-13)    # a rotation keeps the length
+    # pair (2, 3) of an 8-element rotary part turns by pos * theta**(-2*1/8): unit vector along element 2 at position 3
+    ang = 3 * 1e4 ** (-2.0 * 1 / 8)
+    e = torch.zeros(1, 1, 16, dtype=F64); e[0, 0, 2] = 1.0
+    z = oracle.rope_rotate(e, torch.tensor([3]), 1e4, 8, True)[0, 0]
+    assert math.isclose(float(z[2]), math.cos(ang), rel_tol=1e-14) and math.isclose(float(z[3]), math.sin(ang), rel_tol=1e-14)
+    assert float(z.abs().sum()) == pytest.approx(abs(math.cos(ang)) + abs(math.sin(ang)), rel=1e-14)
+
+
 # ---------------------------------------------------------------- the cache as a store of a narrower type
 
 def test_cache_store_type_as_wide_as_the_arithmetic_changes_nothing():
