@@ -103,7 +103,12 @@ typedef struct {
                                   the first rotary_dim elements of every query and key head rotate, as a head of that
                                   size would (pairs (i, i + rotary_dim/2), angle position * theta^(-2i/rotary_dim)); the
                                   rest pass through unrotated.  The GLM / ChatGLM families of the paper's model table
-                                  (section 3.1.3) rotate half of each head.  Not together with qnorm / knorm. */
+                                  (section 3.1.3) rotate half of each head (see also rope_interleaved).  Not together
+                                  with qnorm / knorm. */
+  int32_t rope_interleaved;    /* 0: the rotation pairs element i with element i + d/2 (d: head_dim, or rotary_dim).
+                                  1: it pairs neighbours, element 2i with element 2i + 1, at the same angle
+                                  position * theta^(-2i/d).  The GLM / ChatGLM families pair neighbours (and rotate
+                                  half of each head: rotary_dim). */
   int32_t weight_copies;       /* 0: the stage keeps a second copy of its 16-bit projection weights, made by stage_init
                                   in the order and format its matrix instructions take them (IEEE half in a stage
                                   with half activations), which the tiled GEMMs of micro-batches of more than 64

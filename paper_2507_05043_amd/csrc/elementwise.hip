@@ -78,7 +78,8 @@ __global__ __launch_bounds__(256) void rope_table_kernel(const int32_t* __restri
 }
 
 // One workgroup per token row.  Work units of 8 elements:
-//   rotated heads (q then k): unit = (head, chunk of 8 pairs): reads the fp32 halves, rotates, rounds to
+//   rotated heads (q then k): unit = (head, chunk of 8 pairs; a pair is (i, i + rotary_dim/2) or, with neighbour
+//   pairing, (2i, 2i + 1)): reads the 16 fp32 values, rotates, rounds to
 //   e16 once, writes the e16 row and, for k heads, also the K pool row of the token's slot;
 //   with a partial rotary embedding, the elements of q and k heads past rotary_dim: unit = (head, chunk of 8),
 //   rounded and written like the rotated ones, unrotated;
@@ -115,9 +116,23 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs p) {
   if (u < rot_units) {
     const int head = u / cpr, c = u % cpr;
     const float2* cs = p.cos_sin + (size_t)t * half + c * 8;
+    // the unit's 8 pairs (first[e], second[e]), pair index 8 c + e: elements (8 c + e, half + 8 c + e), or with
+    // neighbour pairing elements (16 c + 2 e, 16 c + 2 e + 1) - two consecutive chunks either way, at at0 and at1
+    const int at0 = p.interleaved ? 16 * c : 8 * c, at1 = p.interleaved ? 16 * c + 8 : half + 8 * c;
+    auto pairs_of = [&](const float* x0, const float* x1, float* first, float* second) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        first[e] = p.interleaved ? (e < 4 ? x0[2 * e] : x1[2 * e - 8]) : x0[e];
+        second[e] = p.interleaved ? (e < 4 ? x0[2 * e + 1] : x1[2 * e - 7]) : x1[e];
+      }
+    };
     float lo[8], hi[8];
-    load8f(src + head * d + c * 8, lo);
-    load8f(src + head * d + half + c * 8, hi);
+    {
+      float x0[8], x1[8];
+      load8f(src + head * d + at0, x0);
+      load8f(src + head * d + at1, x1);
+      pairs_of(x0, x1, lo, hi);
+    }
     if (p.q_gain) {
       // per-head RMSNorm: the head's d values sit in cpr consecutive lanes (cpr = 4 or 8, heads start at
       // multiples of cpr), all of them in this branch
@@ -127,37 +142,49 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeAppendArgs p) {
       for (int off = 1; off < cpr; off <<= 1) ss += __shfl_xor(ss, off, 64);
       const float inv = 1.0f / sqrtf(ss / (float)d + p.head_eps);
       const e16* gain = head < p.nq ? p.q_gain : p.k_gain;
-      const e16x8 gl = load8(gain + c * 8), gh = load8(gain + half + c * 8);
+      const e16x8 g0 = load8(gain + at0), g1 = load8(gain + at1);
+      float x0[8], x1[8], gl[8], gh[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { x0[e] = e16_to_f32(g0[e]); x1[e] = e16_to_f32(g1[e]); }
+      pairs_of(x0, x1, gl, gh);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        lo[e] = lo[e] * inv * e16_to_f32(gl[e]);
-        hi[e] = hi[e] * inv * e16_to_f32(gh[e]);
+        lo[e] = lo[e] * inv * gl[e];
+        hi[e] = hi[e] * inv * gh[e];
       }
     }
-    e16x8 olo, ohi, llo, lhi;
+    // rotate, round once, and put every value back where its input came from
+    float y0[8], y1[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const float2 f = cs[e];
-      const float y0 = lo[e] * f.x - hi[e] * f.y, y1 = hi[e] * f.x + lo[e] * f.y;
-      olo[e] = f32_to_e16(y0);
-      ohi[e] = f32_to_e16(y1);
-      llo[e] = f32_to_e16(y0 - e16_to_f32(olo[e]));
-      lhi[e] = f32_to_e16(y1 - e16_to_f32(ohi[e]));
+      y0[e] = lo[e] * f.x - hi[e] * f.y;
+      y1[e] = hi[e] * f.x + lo[e] * f.y;
     }
-    e16* base = row + head * d + c * 8;
-    store8(base, olo);
-    store8(base + half, ohi);
+    e16x8 o0, o1, l0, l1;     // the chunks at at0 and at1: values, and what rounding dropped
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float v0 = p.interleaved ? ((e & 1) ? y1[e >> 1] : y0[e >> 1]) : y0[e];
+      const float v1 = p.interleaved ? ((e & 1) ? y1[4 + (e >> 1)] : y0[4 + (e >> 1)]) : y1[e];
+      o0[e] = f32_to_e16(v0);
+      o1[e] = f32_to_e16(v1);
+      l0[e] = f32_to_e16(v0 - e16_to_f32(o0[e]));
+      l1[e] = f32_to_e16(v1 - e16_to_f32(o1[e]));
+    }
+    e16* base = row + head * d;
+    store8(base + at0, o0);
+    store8(base + at1, o1);
     if (head < p.nq) {
       if (p.q_lo) {
-        e16* lb = p.q_lo + ((size_t)t * p.nq + head) * d + c * 8;
-        store8(lb, llo);
-        store8(lb + half, lhi);
+        e16* lb = p.q_lo + ((size_t)t * p.nq + head) * d;
+        store8(lb + at0, l0);
+        store8(lb + at1, l1);
       }
     } else {
       const int r = head - p.nq;
       e16* dst = p.k_pool + ((size_t)blk * p.nkv + r) * kKvBlock * d;
-      store8(dst + k_offset_in_block(s, c * 8), olo);
-      store8(dst + k_offset_in_block(s, half + c * 8), ohi);
+      store8(dst + k_offset_in_block(s, at0), o0);
+      store8(dst + k_offset_in_block(s, at1), o1);
     }
   } else if (u < rot_units + pass_units) {
     const int w = u - rot_units;

@@ -37,6 +37,7 @@ struct RopeAppendArgs {
   e16* v_pool;          // this layer's V region [blocks][nkv][d][16]
   int rows, nq, nkv, head_dim;
   int rotary_dim;          // leading elements of every q and k head that rotate (a multiple of 16, <= head_dim)
+  int interleaved;         // 0: element i rotates with element i + rotary_dim/2; 1: element 2i with element 2i + 1
 };
 hipError_t launch_rope_append(const RopeAppendArgs& args, hipStream_t stream);
 

@@ -111,6 +111,8 @@ int check_config(const stage_config* c) {
     return fail(STAGE_ERR_CONFIG, "activation_planes 3 and 4 (half activations) are modes of the bfloat16 library; this one stores half already");
   if (c->vocab_size != 0 && (c->vocab_size < 64 || c->vocab_size % 8))
     return fail(STAGE_ERR_CONFIG, "vocab_size must be 0 or a multiple of 8 that is at least 64");
+  if (c->rope_interleaved != 0 && c->rope_interleaved != 1)
+    return fail(STAGE_ERR_CONFIG, "rope_interleaved must be 0 or 1, got %d", c->rope_interleaved);
   if (c->weight_copies != 0 && c->weight_copies != 1)
     return fail(STAGE_ERR_CONFIG, "weight_copies must be 0 (keep copies in operand order) or 1 (none), got %d", c->weight_copies);
   if (c->weight_bits != 0 && c->weight_bits != 16 && c->weight_bits != 4)
@@ -736,7 +738,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       Timer t(st, stream, STAGE_K_ROPE_APPEND);
       RopeAppendArgs r{plan.partials ? splitk : qkv_f32, plan.partials ? plan.splits : 1, (size_t)T * d.qkv_out,
                        (const e16*)w.bqkv, (const e16*)w.qnorm, (const e16*)w.knorm, c.rms_eps,
-                       qkv, q_lo, cos_sin, d_slots, k_pool, v_pool, T, d.nq, d.nkv, d.d, d.rd};
+                       qkv, q_lo, cos_sin, d_slots, k_pool, v_pool, T, d.nq, d.nkv, d.d, d.rd, c.rope_interleaved};
       HIP_TRY(launch_rope_append(r, stream));
     }
     if (tap && taps->tap_qkv)

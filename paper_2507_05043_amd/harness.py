@@ -39,7 +39,8 @@ def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_
                       max_blocks_per_seq=mb.max_blocks_per_seq,
                       kv_layer_stride_bytes=0 if alias_layers else None, activation_planes=activation_planes,
                       vocab_size=vocab_size, weight_bits=4 if weight_group_size else 0,
-                      weight_group_size=weight_group_size, rotary_dim=shape.rotary_dim, weight_copies=weight_copies)
+                      weight_group_size=weight_group_size, rotary_dim=shape.rotary_dim, weight_copies=weight_copies,
+                      rope_interleaved=int(shape.rope_interleaved))
     st = Stage(cfg, layers, device=device, dtype=dtype)
     if fill_kv:
         fill_pool(st, shape, mb, seed)

@@ -42,7 +42,7 @@ class StageConfig(ctypes.Structure):
         ("max_tokens", ctypes.c_int32), ("max_seqs", ctypes.c_int32), ("max_blocks_per_seq", ctypes.c_int32),
         ("activation_planes", ctypes.c_int32), ("vocab_size", ctypes.c_int32),
         ("weight_bits", ctypes.c_int32), ("weight_group_size", ctypes.c_int32), ("rotary_dim", ctypes.c_int32),
-        ("weight_copies", ctypes.c_int32),
+        ("rope_interleaved", ctypes.c_int32), ("weight_copies", ctypes.c_int32),
     ]
 
 
@@ -120,10 +120,11 @@ def _check(rc: int, lib: Optional[ctypes.CDLL] = None) -> None:
 def make_config(*, num_layers, hidden, num_q_heads, num_kv_heads, head_dim, ffn, rms_eps, rope_theta,
                 num_kv_blocks, max_tokens, max_seqs, max_blocks_per_seq, kv_block_size=16,
                 kv_layer_stride_bytes=None, activation_planes=0, vocab_size=0, weight_bits=0,
-                weight_group_size=0, rotary_dim=0, weight_copies=0) -> StageConfig:
+                weight_group_size=0, rotary_dim=0, weight_copies=0, rope_interleaved=0) -> StageConfig:
     cfg = StageConfig(ctypes.sizeof(StageConfig), num_layers, hidden, num_q_heads, num_kv_heads, head_dim, ffn,
                       rms_eps, rope_theta, kv_block_size, num_kv_blocks, 0, max_tokens, max_seqs, max_blocks_per_seq,
-                      activation_planes, vocab_size, weight_bits, weight_group_size, rotary_dim, weight_copies)
+                      activation_planes, vocab_size, weight_bits, weight_group_size, rotary_dim, int(rope_interleaved),
+                      weight_copies)
     if kv_layer_stride_bytes is None:
         kv_layer_stride_bytes = stage_kv_layer_bytes(cfg)
     cfg.kv_layer_stride_bytes = kv_layer_stride_bytes

@@ -252,3 +252,9 @@ def test_weight_copies_are_counted_in_the_workspace(lib):
     assert ws(**w4) == ws(weight_copies=1, **w4)
     with pytest.raises(S.StageError):
         ws(weight_copies=2, **big)
+
+
+def test_rope_pairing_flag_is_validated(lib):
+    assert S.stage_workspace_bytes(tiny_cfg(rope_interleaved=1)) == S.stage_workspace_bytes(tiny_cfg())
+    with pytest.raises(S.StageError):
+        S.stage_workspace_bytes(tiny_cfg(rope_interleaved=2))

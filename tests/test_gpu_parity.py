@@ -260,6 +260,28 @@ def test_partial_rotary_embedding(d, rd, planes, elem):
         assert rel_l2(b.cpu(), a.cpu()) > 10 * max(stats["rel_l2"], 1e-3)
 
 
+@pytest.mark.parametrize("d,rd,planes,elem,qk_norm", [(128, 64, 1, torch.bfloat16, False), (128, 64, 3, torch.bfloat16, False),
+                                                      (64, 32, 1, torch.float16, False), (128, 0, 2, torch.bfloat16, True),
+                                                      (64, 0, 1, torch.bfloat16, True), (128, 0, 4, torch.bfloat16, False)])
+def test_rotation_of_neighbouring_elements(d, rd, planes, elem, qk_norm):
+    """The rotation pairs elements (2i, 2i + 1) instead of (i, i + d/2): with half of each head rotating this is the
+    GLM / ChatGLM families' rotary embedding; also on whole heads, with the per-head query / key norms (whose gains
+    follow the elements), with a bias, in every activation mode and both libraries; prefill chunks with and without
+    a cached prefix, decode.  The taps compare the rotated q and k with the oracle; the cache check compares the keys."""
+    import dataclasses
+    shape = dataclasses.replace(_shape(f"neighbour-pairs-d{d}-r{rd}", 2, 512, 8, 2, d, 1408), rotary_dim=rd, rope_interleaved=True)
+    mb = synth.make_microbatch([70, 33, 1, 1, 1, 1, 1], [0, 21, 9, 40, 77, 100, 130], seed=9, max_blocks_per_seq=12)
+    stats = full_parity(shape, mb, 9, "fan_in", qkv_bias=not qk_norm, qk_norm=qk_norm, activation_planes=planes, elem=elem)
+    # the same stage with half-split pairs gives another output: the setting was used
+    outs = []
+    for interleaved in (False, True):
+        st = H.make_stage(dataclasses.replace(shape, rope_interleaved=interleaved), mb, 9, "fan_in", qkv_bias=not qk_norm,
+                          qk_norm=qk_norm, activation_planes=planes, dtype=elem)
+        outs.append(H.run_gpu(st, shape, mb, 9)[0].cpu())
+        st.close()
+    assert rel_l2(outs[1], outs[0]) > 10 * max(stats["rel_l2"], 1e-3)
+
+
 def test_partial_rotary_with_head_norms_is_rejected():
     import dataclasses
     shape, mb = synth.workload("tiny", seed=0)
