@@ -72,6 +72,24 @@ def test_weights_in_operand_order(planes, elem, rows):
     full_parity(shape, mb, 3, "fan_in", activation_planes=planes, elem=elem)
 
 
+@pytest.mark.parametrize("hidden,nq,nkv,d,ffn,rows,planes", [
+    (512, 4, 2, 128, 1000, 130, 3),     # gate/up 1000 rows: the last 32-row strip of the copy is zero-padded; down (K = 1000) has no copy
+    (512, 4, 2, 128, 1000, 257, 1),     # a second tile row of one row
+    (768, 6, 2, 128, 1792, 300, 3),     # K = 768: twelve K tiles, three turns of the four-stage loop; two tile rows
+    (768, 12, 4, 64, 1792, 513, 4),     # head_dim 64, three tile rows, the q/k/v input with its second plane (no copy used there)
+    (256, 4, 2, 64, 2560, 90, 1),       # the shortest K the copies take, on the 128-row tile
+])
+def test_operand_order_copies_on_ragged_shapes(hidden, nq, nkv, d, ffn, rows, planes):
+    """Row counts, column counts and inner widths around the edges of the kernel that reads the weights' copies:
+    columns that are not a multiple of 32 or 256, a last tile row of one row, K of 256 (one round of the ring) and
+    768, a projection without a copy beside projections with one, the mode whose q/k/v projection has two planes."""
+    shape = _shape(f"ragged-copies-{hidden}-{ffn}-{rows}", 2, hidden, nq, nkv, d, ffn)
+    pre = rows - 3 - 40
+    mb = synth.make_microbatch([pre, 40, 1, 1, 1], [0, 25, 20, 29, 38], seed=11, max_blocks_per_seq=40)
+    assert mb.num_tokens == rows
+    full_parity(shape, mb, 11, "fan_in", activation_planes=planes, qkv_bias=True)
+
+
 def test_generator_same_bits_on_gpu_and_cpu():
     a = synth.draw_normal_bf16(0, 7, 100000, std=0.02, mean=1.0)
     b = synth.draw_normal_bf16(0, 7, 100000, std=0.02, mean=1.0, device="cuda:0").cpu()
