@@ -21,7 +21,11 @@ rotation, which is how the Qwen3 family of the same table (section 3.1.3)
 defines its block; optionally only the first rotary_dim elements of every head
 rotate, and optionally the rotation pairs neighbouring elements (2i, 2i + 1)
 instead of (i, i + d/2) - the two together are the rotary embedding of the GLM /
-ChatGLM families of that table; no final norm.
+ChatGLM families of that table; or, when a layer carries "alibi" slopes (one per
+query head), no rotation at all and attention scores lowered in proportion to the
+distance between query and key (attention with linear biases: the larger
+Baichuan model of that table; distances are counted in logical indices of the
+sequence); no final norm.
 
 Numerics: every tensor is widened to `dtype` (float64 by default) on entry and
 nothing is rounded afterwards.  Library primitives used as steps: matmul,
@@ -43,8 +47,11 @@ rotary_dim = head_dim is the default bit for bit, the elements past rotary_dim
 are the unrotated projection, the rotated part is the rotation of a head of that
 size, scalar loops with it; neighbour pairing: equal to the half-split rotation
 of the head with its even elements first and its odd elements last, put back in
-place (a permutation identity), a literal angle, scalar loops with it.  The
-paper prints no numeric values
+place (a permutation identity), a literal angle, scalar loops with it; linear
+biases: zero slopes equal the rotation at position zero bit for bit, zero
+queries give geometric weights (closed form), a row-constant shift of the biases
+changes nothing, scalar loops with them, chunked == unsplit and decode == last
+prefill row under them.  The paper prints no numeric values
 for this path, so parity against printed values is unpinned; parity is against
 the definition.
 """
@@ -128,12 +135,15 @@ def slot_mapping(q_lens: Sequence[int], ctx_lens: Sequence[int], block_tables, b
     return slots
 
 
-def attention_rows(q: torch.Tensor, keys: torch.Tensor, values: torch.Tensor, ctx: int) -> torch.Tensor:
+def attention_rows(q: torch.Tensor, keys: torch.Tensor, values: torch.Tensor, ctx: int,
+                   slopes: Optional[torch.Tensor] = None) -> torch.Tensor:
     """Causal attention of one sequence's new rows over its whole logical cache.
 
     q: [n, nq, d] (rotated) rows at logical indices ctx .. ctx+n-1;
     keys, values: [ctx + n, nkv, d] in logical order.  Row i sees keys 0 .. ctx+i.
     Query head h reads kv head h // (nq // nkv).  Scores are scaled by 1/sqrt(d).
+    slopes [nq] (attention with linear biases): the score of the query at logical index i for the key at logical
+    index j is lowered by slopes[h] * (i - j).
     """
     n, nq, d = q.shape
     nkv = keys.shape[1]
@@ -146,6 +156,8 @@ def attention_rows(q: torch.Tensor, keys: torch.Tensor, values: torch.Tensor, ct
     for h in range(nq):
         r = h // g
         e = (q[:, h, :] @ keys[:, r, :].T) / math.sqrt(d)             # [n, total]
+        if slopes is not None:
+            e = e - slopes[h].to(e.dtype) * (limit - j).to(e.dtype)     # distance of key j from the row's own index
         e = e.masked_fill(hidden_mask, float("-inf"))
         e = e - e.max(dim=-1, keepdim=True).values
         w = torch.exp(e)
@@ -176,8 +188,10 @@ def decoder_layer(shape: OracleShape, w: Dict[str, torch.Tensor], x: torch.Tenso
     if w.get("qnorm") is not None:                                    # optional per-head norm (Qwen3 family)
         q = rmsnorm(q, w["qnorm"].to(dt), shape.rms_eps)              # over the d elements of each head
         k = rmsnorm(k, w["knorm"].to(dt), shape.rms_eps)
-    q = rope_rotate(q, pos, shape.rope_theta, shape.rotary_dim, shape.rope_interleaved)
-    k = rope_rotate(k, pos, shape.rope_theta, shape.rotary_dim, shape.rope_interleaved)
+    slopes = w.get("alibi")                                           # [nq]: linear biases instead of a rotation
+    if slopes is None:
+        q = rope_rotate(q, pos, shape.rope_theta, shape.rotary_dim, shape.rope_interleaved)
+        k = rope_rotate(k, pos, shape.rope_theta, shape.rotary_dim, shape.rope_interleaved)
     # append the new tokens' keys (rotated) and values at their slots
     slot_t = torch.as_tensor(slots, dtype=torch.int64)
     k_st = k if kv_store_dtype is None else k.to(kv_store_dtype).to(dt)
@@ -192,7 +206,7 @@ def decoder_layer(shape: OracleShape, w: Dict[str, torch.Tensor], x: torch.Tenso
         table = torch.as_tensor(block_tables[s][:nb], dtype=torch.int64)
         keys = pool_layer[0, table].reshape(nb * blk, nkv, d)[:total]   # logical order via the table
         vals = pool_layer[1, table].reshape(nb * blk, nkv, d)[:total]
-        o[row0: row0 + n] = attention_rows(q[row0: row0 + n], keys, vals, c)
+        o[row0: row0 + n] = attention_rows(q[row0: row0 + n], keys, vals, c, slopes)
         row0 += n
     h = x + o.reshape(t, nq * d) @ w["wo"].to(dt).T
     b = rmsnorm(h, w["norm2"].to(dt), shape.rms_eps)

@@ -345,6 +345,23 @@ def draw_w4_layer(shape: StageShape, layer: int, *, seed: int, group: int, devic
     return out
 
 
+def alibi_slopes(num_heads: int) -> torch.Tensor:
+    """The head slopes of attention with linear biases as its authors define them: for a power of two n the geometric
+    sequence 2^(-8/n), 2^(-16/n), ..., 2^(-8); otherwise the slopes of the largest power of two p below n, followed by
+    every second slope (the first, third, ...) of 2p until n slopes are there.  float32 [num_heads] (model constants,
+    inputs of both sides)."""
+    def power_of_two(n):
+        start = 2.0 ** (-8.0 / n)
+        return [start ** (i + 1) for i in range(n)]
+    p = 1
+    while p * 2 <= num_heads:
+        p *= 2
+    slopes = power_of_two(p)
+    if p < num_heads:
+        slopes += power_of_two(2 * p)[0::2][: num_heads - p]
+    return torch.tensor(slopes, dtype=torch.float32)
+
+
 def draw_qkv_bias(shape: StageShape, layer: int, *, seed: int, device="cpu", std: float = 0.5,
                   dtype: torch.dtype = torch.bfloat16) -> torch.Tensor:
     """bf16 bias [qkv_out] of a layer's q/k/v projection ~ N(0, std) (for the stages that have one)."""

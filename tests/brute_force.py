@@ -52,8 +52,11 @@ def layer_one_sequence(shape, w, rows, pos, cache_k, cache_v):
             qh = [rmsnorm_row(u, w["qnorm"], shape.rms_eps) for u in qh]
             kh = [rmsnorm_row(u, w["knorm"], shape.rms_eps) for u in kh]
         rd, il = getattr(shape, "rotary_dim", 0), getattr(shape, "rope_interleaved", False)
-        q = [rope_head(u, pos[n], shape.rope_theta, rd, il) for u in qh]
-        k = [rope_head(u, pos[n], shape.rope_theta, rd, il) for u in kh]
+        if w.get("alibi") is None:
+            q = [rope_head(u, pos[n], shape.rope_theta, rd, il) for u in qh]
+            k = [rope_head(u, pos[n], shape.rope_theta, rd, il) for u in kh]
+        else:                                     # linear biases: nothing rotates
+            q, k = qh, kh
         v = [qkv[(nq + nkv + r) * d:(nq + nkv + r + 1) * d] for r in range(nkv)]
         cache_k.append(k)
         cache_v.append(v)
@@ -65,6 +68,8 @@ def layer_one_sequence(shape, w, rows, pos, cache_k, cache_v):
             r = h // g
             last = ctx + n                       # causal: keys 0..ctx+n inclusive
             e = [sum(qs[n][h][c] * cache_k[j][r][c] for c in range(d)) / math.sqrt(d) for j in range(last + 1)]
+            if w.get("alibi") is not None:       # each key is penalised by its distance from the query
+                e = [e[j] - w["alibi"][h] * (last - j) for j in range(last + 1)]
             mx = max(e)
             wts = [math.exp(v_ - mx) for v_ in e]
             z = sum(wts)

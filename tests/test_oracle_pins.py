@@ -471,6 +471,118 @@ def test_neighbour_pairing_is_the_half_split_rotation_of_the_regrouped_head():
     assert float(z.abs().sum()) == pytest.approx(abs(math.cos(ang)) + abs(math.sin(ang)), rel=1e-14)
 
 
+# ---------------------------------------------------------------- attention with linear biases
+
+def _with_alibi(layers, slopes):
+    return [dict(w, alibi=slopes) for w in layers]
+
+
+def test_linear_bias_slopes_are_the_published_sequences():
+    assert synth.alibi_slopes(8).tolist() == [2.0 ** -(i + 1) for i in range(8)]
+    s12 = synth.alibi_slopes(12)
+    assert s12[:8].tolist() == [2.0 ** -(i + 1) for i in range(8)]
+    assert torch.allclose(s12[8:].double(), torch.tensor([2.0 ** -0.5, 2.0 ** -1.5, 2.0 ** -2.5, 2.0 ** -3.5], dtype=F64), rtol=1e-7)
+    assert synth.alibi_slopes(40).shape == (40,) and float(synth.alibi_slopes(40)[32]) == pytest.approx(2.0 ** -0.125, rel=1e-7)
+
+
+@pytest.mark.parametrize("nq,nkv", [(4, 2), (3, 3), (4, 1)])
+def test_linear_biases_match_scalar_loops(nq, nkv):
+    shape = small_shape(num_q_heads=nq, num_kv_heads=nkv, hidden=12, ffn=20, head_dim=8, kv_block_size=4)
+    q_lens, ctx_lens = [5, 1, 3], [0, 6, 2]
+    mb = synth.make_microbatch(q_lens, ctx_lens, seed=3, block=4)
+    slopes = synth.alibi_slopes(nq)
+    layers = _with_alibi(draw_layers(shape, 3, "fan_in"), slopes)
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=3)
+    pool = oracle_pool(shape, mb, 3)
+    pool0 = pool.clone()
+    out, _, _ = run_oracle(shape, mb, layers=layers, hidden=hidden, pool=pool)
+    got, row0 = [], 0
+    x_rows = hidden.double().tolist()
+    for s, (q, c) in enumerate(zip(q_lens, ctx_lens)):
+        rows = x_rows[row0:row0 + q]
+        for l in range(shape.num_layers):
+            w = {k: v.double().tolist() for k, v in layers[l].items()}
+            ck, cv = [], []
+            for j in range(c):
+                blk = int(mb.block_tables[s][j // 4])
+                ck.append(pool0[l, 0, blk, j % 4].tolist())
+                cv.append(pool0[l, 1, blk, j % 4].tolist())
+            rows = brute_force.layer_one_sequence(shape, w, rows, list(range(c, c + q)), ck, cv)
+        got.extend(rows)
+        row0 += q
+    got = torch.tensor(got, dtype=F64)
+    assert torch.allclose(out, got, rtol=1e-10, atol=1e-11), float((out - got).abs().max())
+    plain, _, _ = run_oracle(shape, mb, layers=draw_layers(shape, 3, "fan_in"), hidden=hidden, pool=oracle_pool(shape, mb, 3))
+    assert not torch.allclose(out, plain, rtol=1e-3)
+
+
+def test_zero_slopes_are_the_rotation_at_position_zero():
+    """With all slopes zero the scores carry no bias, and a rotary embedding at position 0 rotates by angle 0: the two
+    stages compute the same thing, bit for bit."""
+    shape = small_shape()
+    mb = synth.make_microbatch([9, 1, 1, 20], [3, 33, 0, 11], seed=31)
+    layers = draw_layers(shape, 31, "fan_in")
+    zeros = dataclasses_replace_positions(mb, 0)
+    a, _, pa = run_oracle(shape, zeros, seed=31, layers=layers)
+    b, _, pb = run_oracle(shape, mb, seed=31, layers=_with_alibi(layers, torch.zeros(shape.num_q_heads)))
+    assert torch.equal(a, b)
+    assert torch.equal(pa.nan_to_num(nan=-7.0), pb.nan_to_num(nan=-7.0))
+
+
+def dataclasses_replace_positions(mb, value):
+    import dataclasses
+    return dataclasses.replace(mb, positions=torch.full_like(torch.as_tensor(mb.positions), value))
+
+
+def test_zero_queries_give_geometric_weights():
+    """Queries of zero leave only the biases: the weight of key j for the query at index i is r^(i-j) / sum_k r^(i-k)
+    with r = exp(-slope) - a closed form, evaluated here with Python floats."""
+    gen = torch.Generator().manual_seed(8)
+    ctx, n, nq, nkv, d = 5, 3, 4, 2, 4
+    keys = torch.randn(ctx + n, nkv, d, generator=gen, dtype=F64)
+    vals = torch.randn(ctx + n, nkv, d, generator=gen, dtype=F64)
+    slopes = torch.tensor([0.5, 0.25, 0.0625, 1.5], dtype=F64)
+    out = oracle.attention_rows(torch.zeros(n, nq, d, dtype=F64), keys, vals, ctx, slopes)
+    for row in range(n):
+        i = ctx + row
+        for h in range(nq):
+            r = math.exp(-float(slopes[h]))
+            wts = [r ** (i - j) for j in range(i + 1)]
+            z = sum(wts)
+            for c in range(d):
+                want = sum(wts[j] / z * float(vals[j, h // 2, c]) for j in range(i + 1))
+                assert math.isclose(float(out[row, h, c]), want, rel_tol=1e-12, abs_tol=1e-14)
+    # steeper slopes look at nearer keys: with a huge slope only the query's own key is left
+    own = oracle.attention_rows(torch.zeros(n, nq, d, dtype=F64), keys, vals, ctx, torch.full((nq,), 800.0, dtype=F64))
+    for row in range(n):
+        assert torch.equal(own[row, 0], vals[ctx + row, 0])
+
+
+def test_linear_biases_keep_the_chunking_and_decode_identities():
+    """A chunk split in two, and a last prefill row against a decode row, under linear biases: distances are counted
+    from the row's own logical index, whatever the chunking."""
+    shape = small_shape()
+    slopes = synth.alibi_slopes(shape.num_q_heads)
+    layers = _with_alibi(draw_layers(shape, 12, "fan_in"), slopes)
+    whole = synth.make_microbatch([11], [5], seed=12)
+    hidden = synth.draw_hidden(shape, 11, seed=12)
+    pool = oracle_pool(shape, whole, 12)
+    want, _, pool_w = run_oracle(shape, whole, layers=layers, hidden=hidden, pool=pool.clone())
+    first = synth.MicroBatch([7], [5], whole.block_tables, whole.positions[:7], whole.num_kv_blocks)
+    second = synth.MicroBatch([4], [12], whole.block_tables, whole.positions[7:], whole.num_kv_blocks)
+    pool2 = pool.clone()
+    a, _, pool2 = run_oracle(shape, first, layers=layers, hidden=hidden[:7], pool=pool2)
+    b, _, pool2 = run_oracle(shape, second, layers=layers, hidden=hidden[7:], pool=pool2)
+    assert torch.allclose(torch.cat([a, b]), want, rtol=1e-11, atol=1e-12)
+    # the last row alone, as a decode token over the cache the first ten rows left
+    ten = synth.MicroBatch([10], [5], whole.block_tables, whole.positions[:10], whole.num_kv_blocks)
+    pool3 = pool.clone()
+    _, _, pool3 = run_oracle(shape, ten, layers=layers, hidden=hidden[:10], pool=pool3)
+    one = synth.MicroBatch([1], [15], whole.block_tables, whole.positions[10:], whole.num_kv_blocks)
+    last, _, _ = run_oracle(shape, one, layers=layers, hidden=hidden[10:], pool=pool3)
+    assert torch.allclose(last[0], want[10], rtol=1e-11, atol=1e-12)
+
+
 # ---------------------------------------------------------------- the cache as a store of a narrower type
 
 def test_cache_store_type_as_wide_as_the_arithmetic_changes_nothing():
