@@ -164,6 +164,14 @@ typedef struct {
    * values are not normalised.
    */
   const void *qnorm, *knorm;
+  /*
+   * NULL in every layer, or set in every layer: fp32 [num_q_heads] head slopes of attention with linear biases.
+   * The stage then rotates nothing (positions are ignored; rotary_dim and rope_interleaved must be 0, qnorm / knorm
+   * NULL), and the score of the query at logical index i of its sequence for the key at logical index j <= i is
+   * lowered by slope[head] * (i - j) before the softmax.  The larger Baichuan model of the paper's model table
+   * (section 3.1.3) is the Llama-style block with these biases in place of the rotary embedding.
+   */
+  const void *alibi;
 } stage_layer_weights;
 
 typedef struct stage_handle stage_handle;

@@ -54,7 +54,9 @@ struct DecodeStepLoads {
   e16x8 v[D / 16];                // V^T tiles, one per 16 output dims
 };
 
-template <int D, bool QLO>
+// ALIBI: attention with linear biases - the score of key j is lowered by slope[head] * (last_key - j), the distance
+// of the key from the token's own logical index.
+template <int D, bool QLO, bool ALIBI = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void attn_decode_kernel(AttnArgs a, const DecodeItem* __restrict__ items,
                                                           int num_items, float* __restrict__ part_o,
                                                           float2* __restrict__ part_ml) {
@@ -81,6 +83,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
 
   const int col = lane & 15, grp = lane >> 4;
   const int ldq = (a.nq + 2 * a.nkv) * D;
+  // linear biases: this column's slope in the exponent's unit (log2), and the token's own index
+  float slope_l2 = 0.f;
+  int last_key = 0;
+  if constexpr (ALIBI) {
+    slope_l2 = a.alibi[r * g + (col < g ? col : 0)] * 1.4426950408889634f;
+    last_key = __builtin_amdgcn_readfirstlane(items[item_id].last_key);
+  }
 
   // Q^T operand: column = query head of the group, lane group holds d = 32*kk + 8*grp .. +7
   e16x8 qf[KS], qf_lo[QLO ? KS : 1];
@@ -153,8 +162,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     float s[8];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      s[e] = (e < nvalid) ? sa[e] * a.scale_log2e : -INFINITY;
-      s[4 + e] = (4 + e < nvalid) ? sb[e] * a.scale_log2e : -INFINITY;
+      float va = sa[e] * a.scale_log2e, vb = sb[e] * a.scale_log2e;
+      if constexpr (ALIBI) {
+        va -= slope_l2 * (float)(last_key - (key0 + e));
+        vb -= slope_l2 * (float)(last_key - (key0 + 4 + e));
+      }
+      s[e] = (e < nvalid) ? va : -INFINITY;
+      s[4 + e] = (4 + e < nvalid) ? vb : -INFINITY;
     }
     float m_tile = s[0];
 #pragma unroll
@@ -584,7 +598,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
 // MFMAs and the second plane's fragments in registers, the software-pipelined kernel above runs out of registers at
 // two waves per SIMD and was measured slower on these launches (116 against 80 us on the 2048-token chunk of the
 // Qwen2-shaped stage); overlap here comes from the second workgroup on the CU.
-template <int D>
+// QLO = false: one query plane; ALIBI: attention with linear biases (the score of key j for the query at logical
+// index i is lowered by slope[head] * (i - j)) - every prefill launch with linear biases runs here.
+template <int D, bool QLO = true, bool ALIBI = false>
 __global__ __launch_bounds__(256) void attn_prefill_two_plane_kernel(AttnArgs a, const PrefillTile* __restrict__ tiles,
                                                            int num_tiles) {
   constexpr int KS = D / 16;                 // MFMA k-steps of the QK product
@@ -634,15 +650,21 @@ __global__ __launch_bounds__(256) void attn_prefill_two_plane_kernel(AttnArgs a,
   const int nsteps = (ctx + min(tile_col0 + 127, ncols - 1) / g) / 32 + 1; // ... to the workgroup
   const int ldq = (a.nq + 2 * a.nkv) * D;
 
-  e16x8 qf[KS], qf_lo[KS];
+  e16x8 qf[KS], qf_lo[QLO ? KS : 1];
   {
     const e16* qp = a.qkv + (size_t)(row0 + tok) * ldq + (r * g + hg) * D + grp * 8;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) qf[kk] = load8(qp + kk * 16);
-    const e16* ql = a.q_lo + ((size_t)(row0 + tok) * a.nq + r * g + hg) * D + grp * 8;
+    if constexpr (QLO) {
+      const e16* ql = a.q_lo + ((size_t)(row0 + tok) * a.nq + r * g + hg) * D + grp * 8;
 #pragma unroll
-    for (int kk = 0; kk < KS; ++kk) qf_lo[kk] = load8(ql + kk * 16);
+      for (int kk = 0; kk < KS; ++kk) qf_lo[kk] = load8(ql + kk * 16);
+    }
   }
+  // linear biases, in the unit of the unscaled scores: score * scale_log2e is the exponent, so a bias of
+  // slope * log2(e) per key of distance there is slope * log2(e) / scale_log2e here
+  float slope_raw = 0.f;
+  if constexpr (ALIBI) slope_raw = a.alibi[r * g + hg] * 1.4426950408889634f / a.scale_log2e;
 
   // ---- what this lane fetches for load instruction i of its wave (instruction id j = 4 i + wave;
   // the first K_BYTES / 1024 instructions fill the K tile, the rest the V^T tiles)
@@ -710,10 +732,14 @@ __global__ __launch_bounds__(256) void attn_prefill_two_plane_kernel(AttnArgs a,
       const e16x8 kf = *reinterpret_cast<const e16x8*>(stage + k_row_off + (kk >> 1) * (kKvBlock * 64) +
                                                          (((2 * (kk & 1) + grp) ^ k_swz) * 16));
       s = mfma_32x32x16(kf, qf[kk], s);
-      s = mfma_32x32x16(kf, qf_lo[kk], s);     // second query plane into the same scores
+      if constexpr (QLO) s = mfma_32x32x16(kf, qf_lo[kk], s);     // second query plane into the same scores
     }
     // register e of this lane is key 32*step + 16*(e/8) + 8*grp + e%8
     const int key_base = 32 * step + 8 * grp;
+    if constexpr (ALIBI) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[e] -= slope_raw * (float)(limit - (key_base + 16 * (e / 8) + (e % 8)));
+    }
     float sv[16];
     float raw_max = -INFINITY;                               // maximum of the unscaled scores (the scale is positive)
     if (32 * step + 31 <= wave_min_limit) {                  // wave-uniform: every key of the step is visible to every column
@@ -816,26 +842,39 @@ __global__ __launch_bounds__(256) void attn_prefill_two_plane_kernel(AttnArgs a,
 
 hipError_t launch_attn_prefill(const AttnArgs& a, const PrefillTile* tiles, int num_tiles, hipStream_t stream) {
   dim3 grid(num_tiles * a.nkv), block(256);
-  if (a.head_dim == 128) {
-    if (a.q_lo) hipLaunchKernelGGL((attn_prefill_two_plane_kernel<128>), grid, block, 0, stream, a, tiles, num_tiles);
-    else hipLaunchKernelGGL((attn_prefill_kernel<128>), grid, block, 0, stream, a, tiles, num_tiles);
+#define MOLINK_PREFILL(KERNEL) hipLaunchKernelGGL((KERNEL), grid, block, 0, stream, a, tiles, num_tiles)
+  if (a.alibi) {   // linear biases: the stepwise kernel, with one query plane or two
+    if (a.head_dim == 128) {
+      if (a.q_lo) MOLINK_PREFILL((attn_prefill_two_plane_kernel<128, true, true>));
+      else MOLINK_PREFILL((attn_prefill_two_plane_kernel<128, false, true>));
+    } else {
+      if (a.q_lo) MOLINK_PREFILL((attn_prefill_two_plane_kernel<64, true, true>));
+      else MOLINK_PREFILL((attn_prefill_two_plane_kernel<64, false, true>));
+    }
+  } else if (a.head_dim == 128) {
+    if (a.q_lo) MOLINK_PREFILL((attn_prefill_two_plane_kernel<128>));
+    else MOLINK_PREFILL((attn_prefill_kernel<128>));
   } else {
-    if (a.q_lo) hipLaunchKernelGGL((attn_prefill_two_plane_kernel<64>), grid, block, 0, stream, a, tiles, num_tiles);
-    else hipLaunchKernelGGL((attn_prefill_kernel<64>), grid, block, 0, stream, a, tiles, num_tiles);
+    if (a.q_lo) MOLINK_PREFILL((attn_prefill_two_plane_kernel<64>));
+    else MOLINK_PREFILL((attn_prefill_kernel<64>));
   }
+#undef MOLINK_PREFILL
   return hipGetLastError();
 }
 
 hipError_t launch_attn_decode(const AttnArgs& a, const DecodeItem* items, int num_items, float* part_o,
                               float2* part_ml, hipStream_t stream) {
   dim3 grid(num_items, (a.nkv + 3) / 4), block(256);
+#define MOLINK_DECODE(D, QLO, ALIBI) \
+  hipLaunchKernelGGL((attn_decode_kernel<D, QLO, ALIBI>), grid, block, 0, stream, a, items, num_items, part_o, part_ml)
   if (a.head_dim == 128) {
-    if (a.q_lo) hipLaunchKernelGGL((attn_decode_kernel<128, true>), grid, block, 0, stream, a, items, num_items, part_o, part_ml);
-    else hipLaunchKernelGGL((attn_decode_kernel<128, false>), grid, block, 0, stream, a, items, num_items, part_o, part_ml);
+    if (a.alibi) { if (a.q_lo) MOLINK_DECODE(128, true, true); else MOLINK_DECODE(128, false, true); }
+    else { if (a.q_lo) MOLINK_DECODE(128, true, false); else MOLINK_DECODE(128, false, false); }
   } else {
-    if (a.q_lo) hipLaunchKernelGGL((attn_decode_kernel<64, true>), grid, block, 0, stream, a, items, num_items, part_o, part_ml);
-    else hipLaunchKernelGGL((attn_decode_kernel<64, false>), grid, block, 0, stream, a, items, num_items, part_o, part_ml);
+    if (a.alibi) { if (a.q_lo) MOLINK_DECODE(64, true, true); else MOLINK_DECODE(64, false, true); }
+    else { if (a.q_lo) MOLINK_DECODE(64, true, false); else MOLINK_DECODE(64, false, false); }
   }
+#undef MOLINK_DECODE
   return hipGetLastError();
 }
 

@@ -14,7 +14,8 @@ struct DecodeItem {
   int32_t key_begin;  // first key of the range (multiple of 32)
   int32_t key_end;    // one past the last key (<= ctx + 1)
   int32_t part;       // index of this range's partial result (ranges of a token are consecutive)
-  int32_t pad[3];
+  int32_t last_key;   // the token's own logical index = its last key (linear biases count distances from it)
+  int32_t pad[2];
 };
 
 // One decode token: where its partial results live.
@@ -46,6 +47,7 @@ struct AttnArgs {
   int nq, nkv, head_dim;
   float scale_log2e;        // log2(e) / sqrt(d)
   bool out_half;            // bfloat16 library only: `out` receives IEEE half bits (for a projection that takes half activations)
+  const float* alibi;       // optional [nq] head slopes: scores are lowered by slope * (query index - key index)
 };
 
 hipError_t launch_attn_prefill(const AttnArgs& a, const PrefillTile* tiles, int num_tiles, hipStream_t stream);

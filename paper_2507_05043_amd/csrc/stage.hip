@@ -651,7 +651,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
         for (int k = 0; k < n; ++k) {
           const int kb = k * len;
           const int ke = kb + len < keys ? kb + len : keys;
-          h_items[it] = DecodeItem{row, bt_off, kb, ke, it, {0, 0, 0}};
+          h_items[it] = DecodeItem{row, bt_off, kb, ke, it, keys - 1, {0, 0}};
           ++it;
         }
       } else {
@@ -705,7 +705,9 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
   const DecodeToken* d_dtok = (const DecodeToken*)(meta + o_dtok);
   const PrefillTile* d_tiles = (const PrefillTile*)(meta + o_tiles);
 
-  {
+  const bool alibi = st->layers[0].alibi != nullptr;   // linear biases in the attention scores: nothing rotates
+  const int rotating = alibi ? 0 : d.rd;
+  if (rotating) {
     Timer t(st, stream, STAGE_K_ROPE_TABLE);
     HIP_TRY(launch_rope_table(d_pos, cos_sin, T, d.rd, c.rope_theta, stream));
   }
@@ -738,13 +740,13 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       Timer t(st, stream, STAGE_K_ROPE_APPEND);
       RopeAppendArgs r{plan.partials ? splitk : qkv_f32, plan.partials ? plan.splits : 1, (size_t)T * d.qkv_out,
                        (const e16*)w.bqkv, (const e16*)w.qnorm, (const e16*)w.knorm, c.rms_eps,
-                       qkv, q_lo, cos_sin, d_slots, k_pool, v_pool, T, d.nq, d.nkv, d.d, d.rd, c.rope_interleaved};
+                       qkv, q_lo, cos_sin, d_slots, k_pool, v_pool, T, d.nq, d.nkv, d.d, rotating, c.rope_interleaved};
       HIP_TRY(launch_rope_append(r, stream));
     }
     if (tap && taps->tap_qkv)
       HIP_TRY(hipMemcpyAsync(taps->tap_qkv, qkv, (size_t)T * d.qkv_out * 2, hipMemcpyDeviceToDevice, stream));
     AttnArgs aa{qkv, q_lo, k_pool, v_pool, d_bt, attn, attn_lo, d.nq, d.nkv, d.d, 1.4426950408889634f / sqrtf((float)d.d),
-                half_act};
+                half_act, (const float*)w.alibi};
     if (n_tiles) {
       Timer t(st, stream, STAGE_K_ATTN_PREFILL);
       HIP_TRY(launch_attn_prefill(aa, d_tiles, n_tiles, stream));
@@ -867,6 +869,12 @@ int stage_init(const stage_config* cfg, const stage_layer_weights* layers, void*
     for (const void* p : ptrs)
       if ((uintptr_t)p % 16) return fail(STAGE_ERR_CONFIG, "layer %d has a weight pointer that is not 16-byte aligned", l);
     if ((uintptr_t)w.bqkv % 16) return fail(STAGE_ERR_CONFIG, "layer %d: bqkv is not 16-byte aligned", l);
+    if ((w.alibi == nullptr) != (layers[0].alibi == nullptr))
+      return fail(STAGE_ERR_NULL, "layer %d: alibi slopes must be set in every layer or in none", l);
+    if (w.alibi && (w.qnorm || cfg->rotary_dim != 0 || cfg->rope_interleaved != 0))
+      return fail(STAGE_ERR_CONFIG, "layer %d: linear biases replace the rotation: rotary_dim and rope_interleaved must be 0, "
+                  "qnorm / knorm NULL", l);
+    if ((uintptr_t)w.alibi % 4) return fail(STAGE_ERR_CONFIG, "layer %d: alibi is not 4-byte aligned", l);
     if ((w.qnorm == nullptr) != (w.knorm == nullptr))
       return fail(STAGE_ERR_NULL, "layer %d: qnorm and knorm must both be set or both be NULL", l);
     if (w.qnorm && cfg->rotary_dim != 0 && cfg->rotary_dim != cfg->head_dim)

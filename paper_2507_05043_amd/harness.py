@@ -13,12 +13,13 @@ def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_
                max_tokens: Optional[int] = None, alias_layers: bool = False, fill_kv: bool = True,
                device: str = "cuda:0", activation_planes: int = 0, vocab_size: int = 0,
                qkv_bias: bool = False, weight_group_size: int = 0, dtype: torch.dtype = torch.bfloat16,
-               qk_norm: bool = False, weight_copies: int = 0) -> Stage:
+               qk_norm: bool = False, weight_copies: int = 0, alibi: bool = False) -> Stage:
     """Draw the stage's weights on the device, size the pool and workspace for `mb`, fill the cache.
     weight_group_size > 0: 4-bit group-quantised projection weights with that group size.
     dtype: the 16-bit element type (bfloat16, or float16 for the half-precision library).
     qk_norm: per-head RMSNorm gains for queries and keys (the Qwen3 family's block).
-    weight_copies: 1 = the stage keeps no second copy of its weights in operand order."""
+    weight_copies: 1 = the stage keeps no second copy of its weights in operand order.
+    alibi: attention with linear biases (the published head slopes) instead of the rotary embedding."""
     if weight_group_size:
         layers = [synth.draw_w4_layer(shape, l, seed=seed, group=weight_group_size, device=device,
                                       weight_std=0.02 if weight_std is None else float(weight_std), dtype=dtype)
@@ -32,6 +33,9 @@ def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_
     if qk_norm:
         for l, w in enumerate(layers):
             w.update(synth.draw_qk_norm(shape, l, seed=seed, device=device, dtype=dtype))
+    if alibi:
+        for w in layers:
+            w["alibi"] = synth.alibi_slopes(shape.num_q_heads).to(device)
     cfg = make_config(num_layers=shape.num_layers, hidden=shape.hidden, num_q_heads=shape.num_q_heads,
                       num_kv_heads=shape.num_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn,
                       rms_eps=shape.rms_eps, rope_theta=shape.rope_theta, num_kv_blocks=mb.num_kv_blocks,

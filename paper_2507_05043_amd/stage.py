@@ -53,7 +53,7 @@ W4_ZEROS = ("zqkv", "zo", "zgate", "zup", "zdown")
 
 class StageLayerWeights(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in ("norm1", "wqkv", "wo", "norm2", "wgate", "wup", "wdown", "bqkv")
-                + W4_SCALES + W4_ZEROS + ("qnorm", "knorm")]
+                + W4_SCALES + W4_ZEROS + ("qnorm", "knorm", "alibi")]
 
 
 class StageTaps(ctypes.Structure):
@@ -192,12 +192,14 @@ class Stage:
         for l, w in enumerate(self.layers):
             four_bit = cfg.weight_bits == 4
             for name, _ in StageLayerWeights._fields_:
-                if name in ("bqkv", "qnorm", "knorm") and w.get(name) is None:     # the optional tensors
+                if name in ("bqkv", "qnorm", "knorm", "alibi") and w.get(name) is None:     # the optional tensors
                     continue
                 if not four_bit and (name in W4_SCALES or name in W4_ZEROS):
                     continue
                 t = w[name]
                 want = torch.int32 if four_bit and name in W4_MATRICES else dtype   # code words / elements
+                if name == "alibi":
+                    want = torch.float32                                             # head slopes
                 if t.dtype != want or not t.is_contiguous() or t.device != self.device:
                     raise ValueError(f"layer {l} {name}: need a contiguous {want} tensor on {self.device}")
                 setattr(arr[l], name, t.data_ptr())

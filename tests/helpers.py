@@ -17,7 +17,7 @@ def oracle_shape(shape: synth.StageShape) -> oracle.OracleShape:
 
 def draw_layers(shape: synth.StageShape, seed: int, weight_std=None, device="cpu",
                 qkv_bias: bool = False, elem: torch.dtype = torch.bfloat16,
-                qk_norm: bool = False) -> List[Dict[str, torch.Tensor]]:
+                qk_norm: bool = False, alibi: bool = False) -> List[Dict[str, torch.Tensor]]:
     layers = [synth.draw_layer_weights(shape, l, seed=seed, device=device, weight_std=weight_std, dtype=elem)
               for l in range(shape.num_layers)]
     if qkv_bias:
@@ -26,6 +26,9 @@ def draw_layers(shape: synth.StageShape, seed: int, weight_std=None, device="cpu
     if qk_norm:
         for l, w in enumerate(layers):
             w.update(synth.draw_qk_norm(shape, l, seed=seed, device=device, dtype=elem))
+    if alibi:
+        for w in layers:
+            w["alibi"] = synth.alibi_slopes(shape.num_q_heads).to(device)
     return layers
 
 

@@ -116,7 +116,7 @@ def test_matrices_of_four_gib_and_more_are_accepted(lib):
 def test_config_struct_matches_header_size(lib):
     # uint32 + 6 int32 + 2 float + 2 int32 (+ 4 pad) + int64 + 9 int32 (+ 4 pad)
     assert ctypes.sizeof(S.StageConfig) == 96
-    assert ctypes.sizeof(S.StageLayerWeights) == 20 * ctypes.sizeof(ctypes.c_void_p)
+    assert ctypes.sizeof(S.StageLayerWeights) == 21 * ctypes.sizeof(ctypes.c_void_p)
     assert S.stage_workspace_bytes(tiny_cfg()) > 0
 
 

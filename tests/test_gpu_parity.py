@@ -15,15 +15,15 @@ def _shape(name, L, H_, nq, nkv, d, F, theta=1e4):
 
 
 def full_parity(shape, mb, seed, weight_std, taps=True, check_kv=True, qkv_bias=False, activation_planes=0,
-                qk_norm=False, elem=torch.bfloat16):
+                qk_norm=False, elem=torch.bfloat16, alibi=False):
     print(f"[case] {shape.name} T={mb.num_tokens} S={mb.num_seqs} q={mb.q_lens[:6]} ctx={mb.ctx_lens[:6]} "
           f"std={weight_std} seed={seed} bias={qkv_bias} planes={activation_planes} qk_norm={qk_norm} {elem}", flush=True)
     st = H.make_stage(shape, mb, seed, weight_std, qkv_bias=qkv_bias, activation_planes=activation_planes,
-                      qk_norm=qk_norm, dtype=elem)
+                      qk_norm=qk_norm, dtype=elem, alibi=alibi)
     before = H.snapshot_pool(st, shape, mb) if check_kv else None
     ref, ref_slots, ref_pool, otaps = H.run_oracle(
         shape, mb, seed, weight_std, want_taps=True, elem=elem,
-        layers=draw_layers(shape, seed, weight_std, qkv_bias=qkv_bias, qk_norm=qk_norm, elem=elem))
+        layers=draw_layers(shape, seed, weight_std, qkv_bias=qkv_bias, qk_norm=qk_norm, elem=elem, alibi=alibi))
     out, slots = H.run_gpu(st, shape, mb, seed)
     assert slots == ref_slots                                   # bit-exact slot indexing
     stats = H.check_output(out, ref)
@@ -298,6 +298,36 @@ def test_rotation_of_neighbouring_elements(d, rd, planes, elem, qk_norm):
         outs.append(H.run_gpu(st, shape, mb, 9)[0].cpu())
         st.close()
     assert rel_l2(outs[1], outs[0]) > 10 * max(stats["rel_l2"], 1e-3)
+
+
+@pytest.mark.parametrize("d,nq,nkv,planes,elem", [(128, 8, 2, 1, torch.bfloat16), (128, 8, 2, 3, torch.bfloat16), (128, 8, 8, 2, torch.bfloat16),
+                                                  (64, 12, 4, 1, torch.float16), (128, 5, 5, 4, torch.bfloat16)])
+def test_attention_with_linear_biases(d, nq, nkv, planes, elem):
+    """The Llama-style block with linear biases in the attention scores instead of a rotary embedding (the larger
+    Baichuan model): prefill chunks with and without a cached prefix (the longer one spans several key steps and,
+    with two planes, the second query plane), decode tokens whose keys are cut into several ranges, head counts that
+    are and are not powers of two, grouped and ungrouped heads, every activation mode, both libraries."""
+    shape = _shape(f"linear-biases-d{d}-{nq}-{nkv}", 2, 512, nq, nkv, d, 1408)
+    mb = synth.make_microbatch([70, 33, 1, 1, 1, 1, 1], [0, 21, 9, 40, 77, 500, 1300], seed=9, max_blocks_per_seq=90)
+    stats = full_parity(shape, mb, 9, "fan_in", activation_planes=planes, elem=elem, alibi=True)
+    # the same stage with the rotary embedding gives another output: the biases were used
+    rot = H.make_stage(shape, mb, 9, "fan_in", activation_planes=planes, dtype=elem)
+    a, _ = H.run_gpu(rot, shape, mb, 9)
+    rot.close()
+    lin = H.make_stage(shape, mb, 9, "fan_in", activation_planes=planes, dtype=elem, alibi=True)
+    b, _ = H.run_gpu(lin, shape, mb, 9)
+    lin.close()
+    assert rel_l2(b.cpu(), a.cpu()) > 10 * max(stats["rel_l2"], 1e-3)
+
+
+def test_linear_biases_exclude_the_rotation_settings():
+    import dataclasses
+    shape, mb = synth.workload("tiny", seed=0)
+    for bad in (dict(qk_norm=True), dict()):
+        sh = shape if bad else dataclasses.replace(shape, rotary_dim=32)
+        with pytest.raises(StageError) as ei:
+            H.make_stage(sh, mb, 0, alibi=True, **bad)
+        assert ei.value.code == -2
 
 
 def test_partial_rotary_with_head_norms_is_rejected():
