@@ -844,17 +844,19 @@ template <int N> __device__ __forceinline__ void wait_vm_lgkm0() {
 // and answers it with full waits, and scheduling barriers keep every wait between the instructions it separates.
 // HALF_OPS: the operands are IEEE half (f16 MFMA), else e16.
 // BM: 256, or 128 for products of at most 128 rows (half the MFMA work per weight operand: bound by the weight stream).
-template <int BM, int EPI, bool SPLIT, bool HALF_OPS>
-__global__ __launch_bounds__(256) void gemm_tile_arranged_kernel(GemmArgs p, int nv, int tiles_m, int tiles_n, int splits,
-                                                                 int k_tiles_per_split) {
+// The tile of workgroup `block_id` of a launch of xcd_grid(tiles_m * tiles_n * splits) workgroups; STAGE_BYTES: size of
+// an LDS stage (at least BM * 128; a kernel that runs tiles of both heights gives both the larger).
+template <int BM, int STAGE_BYTES, int EPI, bool SPLIT, bool HALF_OPS>
+__device__ __forceinline__ void arranged_tile(const GemmArgs& p, int nv, int tiles_m, int tiles_n, int splits, int k_tiles_per_split,
+                                              int block_id) {
   static_assert(BM == 128 || BM == 256, "tile rows");
+  static_assert(STAGE_BYTES >= BM * 128, "a stage holds the tile's activation rows");
   constexpr int BN = 256, NWAVES = 4, TM = BM / 2, TN = 128, MT = TM / 32, NT = 4, NSTAGE = 4, RING = 8;
-  constexpr int STAGE_BYTES = BM * 128;
   constexpr int NA = BM / 8 / NWAVES;            // activation loads per wave per tile, issued in three parts
   using Lds = LdsStages<STAGE_BYTES>;
 
   const int total = tiles_m * tiles_n * splits;
-  const int lid = xcd_logical_id(blockIdx.x, total);
+  const int lid = xcd_logical_id(block_id, total);
   if (lid < 0) return;
   int tile_m, tile_n, split;
   if (splits == 1 && tiles_m > kBandRows) {
@@ -1050,6 +1052,25 @@ __global__ __launch_bounds__(256) void gemm_tile_arranged_kernel(GemmArgs p, int
   }
 
   tile_epilogue<EPI, SPLIT, MT, NT>(p, acc, m0 + wm * TM, n0 + wn * TN, nv, split, lane);
+}
+
+template <int BM, int EPI, bool SPLIT, bool HALF_OPS>
+__global__ __launch_bounds__(256) void gemm_tile_arranged_kernel(GemmArgs p, int nv, int tiles_m, int tiles_n, int splits,
+                                                                 int k_tiles_per_split) {
+  arranged_tile<BM, BM * 128, EPI, SPLIT, HALF_OPS>(p, nv, tiles_m, tiles_n, splits, k_tiles_per_split, blockIdx.x);
+}
+
+// A product whose last tile row holds at most 128 rows, without K splits, where that row would cost a whole round of
+// workgroups of its own: the first head_blocks workgroups take the 256-row tiles of `head` (all full tile rows), the
+// rest take `tail` (the remaining rows, with every pointer moved to its first row) on 128-row tiles, which run
+// beside the last, partly filled round of the big tiles instead of after it.
+template <int EPI, bool HALF_OPS>
+__global__ __launch_bounds__(256) void gemm_tile_arranged_ragged_kernel(GemmArgs head, GemmArgs tail, int nv, int tiles_m_head,
+                                                                        int tiles_n, int k_tiles, int head_blocks) {
+  if ((int)blockIdx.x < head_blocks)
+    arranged_tile<256, 256 * 128, EPI, false, HALF_OPS>(head, nv, tiles_m_head, tiles_n, 1, k_tiles, blockIdx.x);
+  else
+    arranged_tile<128, 256 * 128, EPI, false, HALF_OPS>(tail, nv, 1, tiles_n, 1, k_tiles, blockIdx.x - head_blocks);
 }
 
 // Adds the split-K partial sums (split 0 first) and applies the epilogue.  Four consecutive outputs per
@@ -1658,19 +1679,17 @@ hipError_t launch_gemm_main(const GemmArgs& a, GemmEpilogue epi, const GemmPlan&
       return hipErrorInvalidValue;
     };
     // A last tile row of at most 128 rows, where it costs a whole round of workgroups of its own (2176 rows x 148
-    // tile columns: 1332 tiles are six rounds on 256 CUs, 1184 are five), goes to a second launch on 128-row tiles,
-    // which take about 0.55 of a 256-row tile's time.  Without K splits only: the two launches then share nothing.
+    // tile columns: 1332 tiles are six rounds on 256 CUs, 1184 are five), runs on 128-row tiles - about 0.55 of a
+    // 256-row tile's time - in the same launch, behind the big tiles.  Without K splits only.
     const int rest = a.m % 256;
     if (plan.tile == kTileArranged && plan.splits == 1 && a.m > 256 && rest > 0 && rest <= 128) {
       const long tiles_n = (plan.nv + 255) / 256, cus = 256;
       const long full_rows = a.m / 256;
       const float one = (float)(((full_rows + 1) * tiles_n + cus - 1) / cus);
-      const float two = (float)((full_rows * tiles_n + cus - 1) / cus) + 0.55f * (float)((tiles_n + cus - 1) / cus);
-      if (two < one - 0.1f) {
+      const float mixed = ceilf(((float)(full_rows * tiles_n) + 0.55f * (float)tiles_n) / (float)cus);   // rounds of 256-row tiles
+      if (mixed < one - 0.1f) {
         GemmArgs head = a;
         head.m = a.m - rest;
-        hipError_t e = launch(head, plan);
-        if (e != hipSuccess) return e;
         GemmArgs tail = a;
         const size_t at = (size_t)head.m;
         tail.m = rest;
@@ -1679,9 +1698,33 @@ hipError_t launch_gemm_main(const GemmArgs& a, GemmEpilogue epi, const GemmPlan&
         if (a.out_lo) tail.out_lo = a.out_lo + at * a.ldo;
         if (a.out_f32) tail.out_f32 = a.out_f32 + at * a.ldo;
         if (a.resid) tail.resid = a.resid + at * a.n;
-        GemmPlan tail_plan = plan;
-        tail_plan.tile = kTileArranged128;
-        return launch(tail, tail_plan);
+        const int head_blocks = xcd_grid((int)(full_rows * tiles_n)), tail_blocks = xcd_grid((int)tiles_n);
+        dim3 grid(head_blocks + tail_blocks), block(256);
+        const int k_tiles = plan.k_tiles_per_split;
+#define MOLINK_RAGGED(EPI, HALF)                                                                                          \
+  hipLaunchKernelGGL((gemm_tile_arranged_ragged_kernel<EPI, HALF>), grid, block, 0, stream, head, tail, plan.nv, (int)full_rows, \
+                     (int)tiles_n, k_tiles, head_blocks)
+        if (a.a_half) {
+#ifdef MOLINK_F16
+          return hipErrorInvalidValue;   // the element type is half already
+#else
+          switch (epi) {
+            case kEpiStoreF32: MOLINK_RAGGED(kEpiStoreF32, true); break;
+            case kEpiResidualF32: MOLINK_RAGGED(kEpiResidualF32, true); break;
+            case kEpiResidualOut: MOLINK_RAGGED(kEpiResidualOut, true); break;
+            case kEpiSwiGLU: MOLINK_RAGGED(kEpiSwiGLU, true); break;
+          }
+#endif
+        } else {
+          switch (epi) {
+            case kEpiStoreF32: MOLINK_RAGGED(kEpiStoreF32, false); break;
+            case kEpiResidualF32: MOLINK_RAGGED(kEpiResidualF32, false); break;
+            case kEpiResidualOut: MOLINK_RAGGED(kEpiResidualOut, false); break;
+            case kEpiSwiGLU: MOLINK_RAGGED(kEpiSwiGLU, false); break;
+          }
+        }
+#undef MOLINK_RAGGED
+        return hipGetLastError();
       }
     }
     return launch(a, plan);
