@@ -25,7 +25,14 @@ ChatGLM families of that table; or, when a layer carries "alibi" slopes (one per
 query head), no rotation at all and attention scores lowered in proportion to the
 distance between query and key (attention with linear biases: the larger
 Baichuan model of that table; distances are counted in logical indices of the
-sequence); no final norm.
+sequence); no final norm.  Three more switches of the shape cover the remaining dense blocks of that table
+(the Falcon, GPT-2 and Cohere families): norm_kind "layer" makes both norms LayerNorms (mean removed, variance
+instead of mean square, an optional bias "norm1_bias" / "norm2_bias" besides the gain); mlp_kind "gelu_tanh" or
+"gelu_erf" replaces the gated MLP by down(gelu(up(b))), with optional biases "bup", "bdown" (and "bo" on the output
+projection of the attention); parallel_block feeds the attention branch and the MLP branch from the same block
+input x and adds both to it, y = x + attn(norm1(x)) + mlp(norm2(x)), where a layer without "norm2" feeds the
+MLP from norm1(x) as well.  A block without any rotation or bias of the scores (GPT-2: positions enter outside
+the layers) is the linear-bias block with zero slopes.
 
 Numerics: every tensor is widened to `dtype` (float64 by default) on entry and
 nothing is rounded afterwards.  Library primitives used as steps: matmul,
@@ -51,7 +58,11 @@ place (a permutation identity), a literal angle, scalar loops with it; linear
 biases: zero slopes equal the rotation at position zero bit for bit, zero
 queries give geometric weights (closed form), a row-constant shift of the biases
 changes nothing, scalar loops with them, chunked == unsplit and decode == last
-prefill row under them.  The paper prints no numeric values
+prefill row under them; LayerNorm against the library routine, zero mean and unit variance of its output, its
+shift invariance, and a constant row (closed form: the bias); both GELU forms against the library routine and
+literal values; the parallel block from the sequential one (zero output projection: both agree; zero down
+projection: y = x + attention branch), shared norm == the same norm given twice, scalar loops with every
+switch.  The paper prints no numeric values
 for this path, so parity against printed values is unpinned; parity is against
 the definition.
 """
@@ -77,6 +88,9 @@ class OracleShape:
     kv_block_size: int = 16
     rotary_dim: int = 0          # 0: the whole head rotates; else only its first rotary_dim elements do
     rope_interleaved: bool = False   # False: pairs (i, i + d/2); True: pairs (2i, 2i + 1)
+    norm_kind: str = "rms"       # "rms" | "layer": both norms of the block (rms_eps is the epsilon of either)
+    mlp_kind: str = "swiglu"     # "swiglu": down(silu(gate(b)) * up(b)); "gelu_tanh" | "gelu_erf": down(gelu(up(b)))
+    parallel_block: bool = False  # True: y = x + attn(norm1(x)) + mlp(norm2(x)); False: the branches in sequence
 
 
 def new_pool(shape: OracleShape, num_kv_blocks: int, dtype=torch.float64, fill=float("nan")) -> torch.Tensor:
@@ -89,6 +103,32 @@ def rmsnorm(x: torch.Tensor, gain: torch.Tensor, eps: float) -> torch.Tensor:
     """x * gain / sqrt(mean(x^2) + eps), per row."""
     ms = (x * x).mean(dim=-1, keepdim=True)
     return x * gain / torch.sqrt(ms + eps)
+
+
+def layernorm(x: torch.Tensor, gain: torch.Tensor, bias: Optional[torch.Tensor], eps: float) -> torch.Tensor:
+    """(x - mean) / sqrt(var + eps) * gain (+ bias), per row; var is the mean of the squared deviations."""
+    mean = x.mean(dim=-1, keepdim=True)
+    dev = x - mean
+    var = (dev * dev).mean(dim=-1, keepdim=True)
+    y = dev / torch.sqrt(var + eps) * gain
+    return y if bias is None else y + bias
+
+
+def block_norm(shape: "OracleShape", x: torch.Tensor, gain: torch.Tensor, bias: Optional[torch.Tensor]) -> torch.Tensor:
+    """The norm in front of a branch of the block, by shape.norm_kind."""
+    if shape.norm_kind == "layer":
+        return layernorm(x, gain, bias, shape.rms_eps)
+    assert shape.norm_kind == "rms" and bias is None
+    return rmsnorm(x, gain, shape.rms_eps)
+
+
+def gelu(z: torch.Tensor, form: str) -> torch.Tensor:
+    """z * Phi(z) with the normal distribution function Phi ("gelu_erf"), or its tanh form
+    0.5 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3))) ("gelu_tanh")."""
+    if form == "gelu_erf":
+        return 0.5 * z * (1.0 + torch.erf(z / math.sqrt(2.0)))
+    assert form == "gelu_tanh"
+    return 0.5 * z * (1.0 + torch.tanh(math.sqrt(2.0 / math.pi) * (z + 0.044715 * z * z * z)))
 
 
 def rope_rotate(u: torch.Tensor, pos: torch.Tensor, theta: float, rotary_dim: int = 0,
@@ -178,7 +218,11 @@ def decoder_layer(shape: OracleShape, w: Dict[str, torch.Tensor], x: torch.Tenso
     nq, nkv, d, blk = shape.num_q_heads, shape.num_kv_heads, shape.head_dim, shape.kv_block_size
     t = x.shape[0]
     wqkv = w["wqkv"].to(dt)
-    a = rmsnorm(x, w["norm1"].to(dt), shape.rms_eps)
+
+    def opt(name):
+        return None if w.get(name) is None else w[name].to(dt)
+
+    a = block_norm(shape, x, w["norm1"].to(dt), opt("norm1_bias"))
     qkv = a @ wqkv.T                                                  # weights are [out, in]
     if w.get("bqkv") is not None:                                     # optional projection bias (Qwen2 family)
         qkv = qkv + w["bqkv"].to(dt)
@@ -208,10 +252,27 @@ def decoder_layer(shape: OracleShape, w: Dict[str, torch.Tensor], x: torch.Tenso
         vals = pool_layer[1, table].reshape(nb * blk, nkv, d)[:total]
         o[row0: row0 + n] = attention_rows(q[row0: row0 + n], keys, vals, c, slopes)
         row0 += n
-    h = x + o.reshape(t, nq * d) @ w["wo"].to(dt).T
-    b = rmsnorm(h, w["norm2"].to(dt), shape.rms_eps)
-    m = silu(b @ w["wgate"].to(dt).T) * (b @ w["wup"].to(dt).T)
-    y = h + m @ w["wdown"].to(dt).T
+    branch = o.reshape(t, nq * d) @ w["wo"].to(dt).T
+    if opt("bo") is not None:
+        branch = branch + opt("bo")
+    h = x + branch                                                    # sequential: the MLP branch starts from here
+    src = x if shape.parallel_block else h
+    if w.get("norm2") is None:                                        # one norm for both branches
+        assert shape.parallel_block
+        b = a
+    else:
+        b = block_norm(shape, src, w["norm2"].to(dt), opt("norm2_bias"))
+    if shape.mlp_kind == "swiglu":
+        m = silu(b @ w["wgate"].to(dt).T) * (b @ w["wup"].to(dt).T)
+    else:
+        up = b @ w["wup"].to(dt).T
+        if opt("bup") is not None:
+            up = up + opt("bup")
+        m = gelu(up, shape.mlp_kind)
+    down = m @ w["wdown"].to(dt).T
+    if opt("bdown") is not None:
+        down = down + opt("bdown")
+    y = h + down                                                      # parallel: x + both branches
     if taps is not None:
         taps.update(a=a, q=q, k=k, v=v, attn=o.reshape(t, nq * d), h=h, b=b, m=m, x=y)
     return y

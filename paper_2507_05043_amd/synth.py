@@ -138,6 +138,9 @@ class StageShape:
     vocab: int = 0          # vocabulary size of the model the stage is cut from (embedding / output head)
     rotary_dim: int = 0     # 0: whole heads rotate; else only the first rotary_dim elements of every head
     rope_interleaved: bool = False   # rotation pairs: (i, i + d/2), or neighbours (2i, 2i + 1)
+    norm_kind: str = "rms"          # "rms" | "layer": the block's two norms
+    mlp_kind: str = "swiglu"        # "swiglu" | "gelu_tanh" | "gelu_erf" (the latter two: down(gelu(up(b))), no gate)
+    parallel_block: bool = False    # attention branch and MLP branch both start from the block's input
 
     @property
     def qkv_out(self) -> int:
@@ -366,6 +369,20 @@ def draw_qkv_bias(shape: StageShape, layer: int, *, seed: int, device="cpu", std
                   dtype: torch.dtype = torch.bfloat16) -> torch.Tensor:
     """bf16 bias [qkv_out] of a layer's q/k/v projection ~ N(0, std) (for the stages that have one)."""
     return draw_normal_bf16(seed, STREAM_LAYER_BASE + 10 * layer + 7, shape.qkv_out, std=std, device=device, dtype=dtype)
+
+
+STREAM_BLOCK_BIAS_BASE = 200000   # + 10*layer + {0 norm1_bias, 1 norm2_bias, 2 bo, 3 bup, 4 bdown}
+
+
+def draw_block_biases(shape: StageShape, layer: int, *, seed: int, device="cpu", std: float = 0.25,
+                      dtype: torch.dtype = torch.bfloat16) -> Dict[str, torch.Tensor]:
+    """Biases ~ N(0, std) of the blocks that have them: of the two LayerNorms [hidden], of the attention's output
+    projection [hidden], and of the two matrices of an ungated MLP ([ffn] and [hidden])."""
+    sizes = (("norm1_bias", shape.hidden), ("norm2_bias", shape.hidden), ("bo", shape.hidden), ("bup", shape.ffn),
+             ("bdown", shape.hidden))
+    return {name: draw_normal_bf16(seed, STREAM_BLOCK_BIAS_BASE + 10 * layer + k, n, std=std, device=device,
+                                   dtype=dtype)
+            for k, (name, n) in enumerate(sizes)}
 
 
 def draw_qk_norm(shape: StageShape, layer: int, *, seed: int, device="cpu", std: float = 0.25,

@@ -12,6 +12,28 @@ def rmsnorm_row(x, g, eps):
     return [x[j] * g[j] / math.sqrt(ms + eps) for j in range(len(x))]
 
 
+def layernorm_row(x, g, b, eps):
+    """Variance through the plain two-moment formula E[x^2] - E[x]^2 (the tensor code sums squared deviations)."""
+    n = len(x)
+    mean = sum(x) / n
+    var = sum(v * v for v in x) / n - mean * mean
+    return [(x[j] - mean) / math.sqrt(var + eps) * g[j] + (b[j] if b is not None else 0.0) for j in range(n)]
+
+
+def norm_row(shape, x, g, b):
+    if getattr(shape, "norm_kind", "rms") == "layer":
+        return layernorm_row(x, g, b, shape.rms_eps)
+    return rmsnorm_row(x, g, shape.rms_eps)
+
+
+def gelu_scalar(z, form):
+    """Phi(z) through the complementary error function, and the tanh form written with exponentials."""
+    if form == "gelu_erf":
+        return z * 0.5 * math.erfc(-z / math.sqrt(2.0))
+    t = math.sqrt(2.0 / math.pi) * (z + 0.044715 * z ** 3)
+    return z / (1.0 + math.exp(-2.0 * t))            # 0.5 (1 + tanh t) = 1 / (1 + exp(-2 t))
+
+
 def matvec(w, x):
     """w[out][in] times x[in]."""
     return [sum(w[o][i] * x[i] for i in range(len(x))) for o in range(len(w))]
@@ -42,7 +64,7 @@ def layer_one_sequence(shape, w, rows, pos, cache_k, cache_v):
     ctx = len(cache_k)
     qs = []
     for n, x in enumerate(rows):
-        a = rmsnorm_row(x, w["norm1"], shape.rms_eps)
+        a = norm_row(shape, x, w["norm1"], w.get("norm1_bias"))
         qkv = matvec(w["wqkv"], a)
         if w.get("bqkv") is not None:
             qkv = [u + b for u, b in zip(qkv, w["bqkv"])]
@@ -75,13 +97,27 @@ def layer_one_sequence(shape, w, rows, pos, cache_k, cache_v):
             z = sum(wts)
             o.extend(sum(wts[j] / z * cache_v[j][r][c] for j in range(last + 1)) for c in range(d))
         proj = matvec(w["wo"], o)
-        hrow = [x[j] + proj[j] for j in range(hdim)]
-        b = rmsnorm_row(hrow, w["norm2"], shape.rms_eps)
-        gate = matvec(w["wgate"], b)
+        if w.get("bo") is not None:
+            proj = [proj[j] + w["bo"][j] for j in range(hdim)]
+        parallel = getattr(shape, "parallel_block", False)
+        mlp_in = x if parallel else [x[j] + proj[j] for j in range(hdim)]
+        if w.get("norm2") is None:               # the block's one norm feeds both branches
+            b = norm_row(shape, x, w["norm1"], w.get("norm1_bias"))
+        else:
+            b = norm_row(shape, mlp_in, w["norm2"], w.get("norm2_bias"))
         up = matvec(w["wup"], b)
-        m = [gate[f] / (1.0 + math.exp(-gate[f])) * up[f] for f in range(len(gate))]
+        kind = getattr(shape, "mlp_kind", "swiglu")
+        if kind == "swiglu":
+            gate = matvec(w["wgate"], b)
+            m = [gate[f] / (1.0 + math.exp(-gate[f])) * up[f] for f in range(len(gate))]
+        else:
+            if w.get("bup") is not None:
+                up = [up[f] + w["bup"][f] for f in range(len(up))]
+            m = [gelu_scalar(u, kind) for u in up]
         dn = matvec(w["wdown"], m)
-        outs.append([hrow[j] + dn[j] for j in range(hdim)])
+        if w.get("bdown") is not None:
+            dn = [dn[j] + w["bdown"][j] for j in range(hdim)]
+        outs.append([x[j] + proj[j] + dn[j] for j in range(hdim)])
     return outs
 
 

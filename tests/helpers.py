@@ -12,14 +12,31 @@ from paper_2507_05043_amd import synth
 def oracle_shape(shape: synth.StageShape) -> oracle.OracleShape:
     return oracle.OracleShape(shape.num_layers, shape.hidden, shape.num_q_heads, shape.num_kv_heads,
                               shape.head_dim, shape.ffn, shape.rms_eps, shape.rope_theta,
-                              shape.kv_block_size, shape.rotary_dim, shape.rope_interleaved)
+                              shape.kv_block_size, shape.rotary_dim, shape.rope_interleaved,
+                              shape.norm_kind, shape.mlp_kind, shape.parallel_block)
 
 
 def draw_layers(shape: synth.StageShape, seed: int, weight_std=None, device="cpu",
                 qkv_bias: bool = False, elem: torch.dtype = torch.bfloat16,
-                qk_norm: bool = False, alibi: bool = False) -> List[Dict[str, torch.Tensor]]:
+                qk_norm: bool = False, alibi: bool = False, block_biases: bool = False,
+                shared_norm: bool = False) -> List[Dict[str, torch.Tensor]]:
+    """block_biases: the norms' biases (LayerNorm shapes only), bo, bdown, and for an ungated MLP bup.
+    shared_norm (parallel blocks): no second norm - both branches read the first.  An ungated MLP has no wgate."""
     layers = [synth.draw_layer_weights(shape, l, seed=seed, device=device, weight_std=weight_std, dtype=elem)
               for l in range(shape.num_layers)]
+    for l, w in enumerate(layers):
+        if shape.mlp_kind != "swiglu":
+            del w["wgate"]
+        if block_biases:
+            b = synth.draw_block_biases(shape, l, seed=seed, device=device, dtype=elem)
+            if shape.norm_kind != "layer":
+                del b["norm1_bias"], b["norm2_bias"]
+            if shape.mlp_kind == "swiglu":
+                del b["bup"]
+            w.update(b)
+        if shared_norm:
+            del w["norm2"]
+            w.pop("norm2_bias", None)
     if qkv_bias:
         for l, w in enumerate(layers):
             w["bqkv"] = synth.draw_qkv_bias(shape, l, seed=seed, device=device, dtype=elem)

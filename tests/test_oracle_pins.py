@@ -585,6 +585,167 @@ def test_linear_biases_keep_the_chunking_and_decode_identities():
 
 # ---------------------------------------------------------------- the cache as a store of a narrower type
 
+# ---------------------------------------------------------------- LayerNorm, ungated GELU MLP, parallel branches
+
+def _scalar_loops(shape, mb, layers, hidden, pool0, q_lens, ctx_lens, blk=4):
+    got, row0 = [], 0
+    x_rows = hidden.double().tolist()
+    for s, (q, c) in enumerate(zip(q_lens, ctx_lens)):
+        rows = x_rows[row0:row0 + q]
+        for l in range(shape.num_layers):
+            w = {k: v.double().tolist() for k, v in layers[l].items()}
+            ck, cv = [], []
+            for j in range(c):
+                b = int(mb.block_tables[s][j // blk])
+                ck.append(pool0[l, 0, b, j % blk].tolist())
+                cv.append(pool0[l, 1, b, j % blk].tolist())
+            rows = brute_force.layer_one_sequence(shape, w, rows, list(range(c, c + q)), ck, cv)
+        got.extend(rows)
+        row0 += q
+    return torch.tensor(got, dtype=F64)
+
+
+BLOCK_KINDS = [
+    dict(norm_kind="layer"),                                                                 # LayerNorm, rest default
+    dict(mlp_kind="gelu_tanh"),
+    dict(mlp_kind="gelu_erf", biases=True),
+    dict(parallel_block=True),
+    dict(parallel_block=True, shared=True),
+    dict(norm_kind="layer", mlp_kind="gelu_tanh", biases=True, alibi_zero=True),             # the GPT-2 block
+    dict(norm_kind="layer", mlp_kind="gelu_erf", parallel_block=True, biases=True, alibi=True),   # Falcon, two norms
+    dict(norm_kind="layer", mlp_kind="gelu_erf", parallel_block=True, shared=True),          # Falcon, one norm
+    dict(norm_kind="layer", parallel_block=True, shared=True, rope_interleaved=True),        # Cohere
+]
+
+
+def _block_layers(shape, seed, kind):
+    layers = draw_layers(shape, seed, "fan_in", block_biases=kind.get("biases", False), shared_norm=kind.get("shared", False))
+    if kind.get("alibi") or kind.get("alibi_zero"):
+        slopes = synth.alibi_slopes(shape.num_q_heads)
+        layers = _with_alibi(layers, slopes * 0 if kind.get("alibi_zero") else slopes)
+    return layers
+
+
+def _block_shape(kind, **kw):
+    keys = ("norm_kind", "mlp_kind", "parallel_block", "rope_interleaved")
+    return small_shape(**{k: kind[k] for k in keys if k in kind}, **kw)
+
+
+@pytest.mark.parametrize("kind", BLOCK_KINDS, ids=lambda k: "-".join(f"{a}={b}" for a, b in k.items()))
+def test_block_kinds_match_scalar_loops(kind):
+    shape = _block_shape(kind, num_q_heads=4, num_kv_heads=2, hidden=12, ffn=20, head_dim=8, kv_block_size=4)
+    q_lens, ctx_lens = [5, 1, 3], [0, 6, 2]
+    mb = synth.make_microbatch(q_lens, ctx_lens, seed=3, block=4)
+    layers = _block_layers(shape, 3, kind)
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=3) + 0.5           # rows with a mean: LayerNorm removes it
+    pool = oracle_pool(shape, mb, 3)
+    pool0 = pool.clone()
+    out, _, _ = run_oracle(shape, mb, layers=layers, hidden=hidden, pool=pool)
+    got = _scalar_loops(shape, mb, layers, hidden, pool0, q_lens, ctx_lens)
+    assert torch.allclose(out, got, rtol=1e-9, atol=1e-10), float((out - got).abs().max())
+    base = small_shape(num_q_heads=4, num_kv_heads=2, hidden=12, ffn=20, head_dim=8, kv_block_size=4)
+    plain, _, _ = run_oracle(base, mb, layers=draw_layers(base, 3, "fan_in"), hidden=hidden, pool=oracle_pool(base, mb, 3))
+    assert not torch.allclose(out, plain, rtol=1e-3)
+
+
+def test_layernorm_against_the_library_and_closed_forms():
+    g = torch.Generator().manual_seed(5)
+    x = torch.randn(7, 24, dtype=F64, generator=g) * 3 + 2
+    gain = torch.randn(24, dtype=F64, generator=g)
+    bias = torch.randn(24, dtype=F64, generator=g)
+    want = torch.nn.functional.layer_norm(x, (24,), gain, bias, 1e-5)
+    assert torch.allclose(oracle.layernorm(x, gain, bias, 1e-5), want, rtol=1e-12, atol=1e-13)
+    want = torch.nn.functional.layer_norm(x, (24,), gain, None, 1e-5)
+    assert torch.allclose(oracle.layernorm(x, gain, None, 1e-5), want, rtol=1e-12, atol=1e-13)
+    y = oracle.layernorm(x, torch.ones(24, dtype=F64), None, 0.0)            # zero mean, unit variance
+    assert y.mean(dim=-1).abs().max() < 1e-14
+    assert ((y * y).mean(dim=-1) - 1).abs().max() < 1e-13
+    shifted = oracle.layernorm(x + 10.0, gain, bias, 1e-5)                    # a shift of the row changes nothing
+    assert torch.allclose(shifted, oracle.layernorm(x, gain, bias, 1e-5), rtol=1e-11, atol=1e-12)
+    scaled = oracle.layernorm(x * 4.0, gain, bias, 0.0)                       # nor does its scale, without epsilon
+    assert torch.allclose(scaled, oracle.layernorm(x, gain, bias, 0.0), rtol=1e-12, atol=1e-12)
+    const = torch.full((2, 24), 3.25, dtype=F64)                              # no deviations: the bias alone
+    assert torch.equal(oracle.layernorm(const, gain, bias, 1e-5), bias.expand(2, 24))
+    # epsilon sits under the root, next to the variance: variance 1 (values +-1) divides by sqrt(1 + eps)
+    pm = torch.tensor([[1.0, -1.0] * 12], dtype=F64)
+    assert torch.allclose(oracle.layernorm(pm, torch.ones(24, dtype=F64), None, 3.0), pm / 2.0, rtol=1e-15)
+    # and it differs from the RMSNorm exactly by the removed mean
+    assert torch.allclose(oracle.layernorm(x, gain, None, 1e-5),
+                          oracle.rmsnorm(x - x.mean(dim=-1, keepdim=True), gain, 1e-5), rtol=1e-12, atol=1e-13)
+
+
+def test_gelu_forms_against_the_library_and_literal_values():
+    z = torch.linspace(-6, 6, 241, dtype=F64)
+    assert torch.allclose(oracle.gelu(z, "gelu_erf"), torch.nn.functional.gelu(z), rtol=1e-12, atol=1e-14)
+    assert torch.allclose(oracle.gelu(z, "gelu_tanh"), torch.nn.functional.gelu(z, approximate="tanh"), rtol=1e-12, atol=1e-14)
+    one = torch.tensor([1.0, -1.0, 0.0, 0.5], dtype=F64)
+    # Phi(1) = 0.841344746068543, Phi(0.5) = 0.691462461274013 (normal distribution tables)
+    assert torch.allclose(oracle.gelu(one, "gelu_erf"),
+                          torch.tensor([0.841344746068543, -0.158655253931457, 0.0, 0.3457312306370065], dtype=F64), rtol=1e-13)
+    # tanh form at 1: 0.5 (1 + tanh(0.7978845608 * 1.044715)) = 0.5 (1 + tanh(0.8335619..)) = 0.841191990608
+    t1 = 0.5 * (1 + math.tanh(math.sqrt(2 / math.pi) * 1.044715))
+    assert abs(t1 - 0.841191990608) < 1e-11
+    assert torch.allclose(oracle.gelu(one[:1], "gelu_tanh"), torch.tensor([t1], dtype=F64), rtol=1e-14)
+    big = torch.tensor([30.0, -30.0], dtype=F64)
+    for form in ("gelu_erf", "gelu_tanh"):
+        assert torch.equal(oracle.gelu(big, form), torch.tensor([30.0, -0.0], dtype=F64)) or \
+            torch.equal(oracle.gelu(big, form).abs(), torch.tensor([30.0, 0.0], dtype=F64))
+        assert float((oracle.gelu(z, form) - oracle.gelu(z, "gelu_erf")).abs().max()) < 5e-4   # the two forms are close
+        # gelu(z) - gelu(-z) = z for both forms (Phi(z) + Phi(-z) = 1; tanh is odd)
+        assert torch.allclose(oracle.gelu(z, form) - oracle.gelu(-z, form), z, rtol=1e-13, atol=1e-14)
+
+
+def test_parallel_block_from_the_sequential_one():
+    """With a zero output projection the attention branch adds nothing, and the MLP branch reads the same rows in either
+    wiring: both blocks agree.  With a zero down projection only the attention branch remains in either.  Otherwise they
+    differ.  A parallel block without a second norm equals the block given its first norm twice."""
+    mb = synth.make_microbatch([6, 1, 3], [0, 9, 4], seed=8, block=16)
+    seq, par = small_shape(), small_shape(parallel_block=True)
+    hidden = synth.draw_hidden(seq, mb.num_tokens, seed=8)
+
+    def both(edit):
+        outs = []
+        for shape in (seq, par):
+            layers = draw_layers(shape, 8, "fan_in")
+            for w in layers:
+                edit(w)
+            outs.append(run_oracle(shape, mb, layers=layers, hidden=hidden, pool=oracle_pool(shape, mb, 8))[0])
+        return outs
+
+    a, b = both(lambda w: w["wo"].zero_())
+    assert torch.equal(a, b)
+    a, b = both(lambda w: w["wdown"].zero_())
+    assert torch.equal(a, b)
+    a, b = both(lambda w: None)
+    assert not torch.allclose(a, b, rtol=1e-3)
+    twice = draw_layers(par, 8, "fan_in")
+    for w in twice:
+        w["norm2"] = w["norm1"].clone()
+    shared = draw_layers(par, 8, "fan_in", shared_norm=True)
+    assert all("norm2" not in w for w in shared)
+    a = run_oracle(par, mb, layers=twice, hidden=hidden, pool=oracle_pool(par, mb, 8))[0]
+    b = run_oracle(par, mb, layers=shared, hidden=hidden, pool=oracle_pool(par, mb, 8))[0]
+    assert torch.equal(a, b)
+
+
+def test_zero_block_biases_change_nothing_and_real_ones_shift_by_themselves():
+    shape = small_shape(norm_kind="layer", mlp_kind="gelu_tanh", num_layers=1)
+    mb = synth.make_microbatch([4, 1], [0, 5], seed=9, block=16)
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=9)
+    none = draw_layers(shape, 9, "fan_in")
+    zero = draw_layers(shape, 9, "fan_in", block_biases=True)
+    for w in zero:
+        for k in ("norm1_bias", "norm2_bias", "bo", "bup", "bdown"):
+            w[k].zero_()
+    a = run_oracle(shape, mb, layers=none, hidden=hidden, pool=oracle_pool(shape, mb, 9))[0]
+    b = run_oracle(shape, mb, layers=zero, hidden=hidden, pool=oracle_pool(shape, mb, 9))[0]
+    assert torch.equal(a, b)
+    # the last bias of the block lands on the output as it is
+    zero[0]["bdown"] = synth.draw_block_biases(shape, 0, seed=9)["bdown"]
+    c = run_oracle(shape, mb, layers=zero, hidden=hidden, pool=oracle_pool(shape, mb, 9))[0]
+    assert torch.allclose(c - a, zero[0]["bdown"].double().expand_as(a), rtol=0, atol=1e-12)
+
+
 def test_cache_store_type_as_wide_as_the_arithmetic_changes_nothing():
     """kv_store_dtype = the oracle's own float64: a rounding that rounds nothing; output and pool bit for bit."""
     shape = small_shape()
