@@ -15,6 +15,10 @@
  *   append k,v to the paged pool     o = causal GQA attention of q over the sequence's cache
  *   h = x + o Wo^T                   b = RMSNorm(h; norm2)
  *   x' = h + (silu(b Wgate^T) * (b Wup^T)) Wdown^T
+ * Switches of stage_config and optional tensors of stage_layer_weights turn this block into the other dense
+ * blocks of the paper's model table (section 3.1.3): a bias on q/k/v, per-head norms of q and k, a partial or
+ * neighbour-pairing rotation, linear score biases instead of a rotation, LayerNorms, an ungated GELU MLP with
+ * biases, and branches that both start from x (norm_kind, mlp_kind, parallel_block).
  *
  * All device buffers (weights, KV pool, workspace, input, output) are allocated and owned by
  * the caller and must stay valid until stage_destroy; the library allocates no device memory.
@@ -118,6 +122,18 @@ typedef struct {
                                   weights are 16-bit and activation_planes is not 2; a matrix whose input width is
                                   not a multiple of 256 has none.  1: no copies.  Results agree to the rounding of
                                   the fp32 summation order. */
+  int32_t norm_kind;           /* 0: both norms of the block are RMSNorms (gain only).  1: LayerNorms,
+                                    (x - mean(x)) / sqrt(mean((x - mean(x))^2) + rms_eps) * gain + bias,
+                                  bias optional (stage_layer_weights.norm1_bias / norm2_bias).  The Falcon, GPT-2 and
+                                  Cohere families of the paper's model table (section 3.1.3). */
+  int32_t mlp_kind;            /* 0: the gated MLP down(silu(gate(b)) * up(b)).  1, 2: the ungated MLP
+                                  down(gelu(up(b) + bup)) + bdown, with gelu in its tanh form
+                                  0.5 z (1 + tanh(sqrt(2/pi) (z + 0.044715 z^3))) (1: GPT-2) or as z Phi(z) (2: Falcon);
+                                  wgate is then unused and must be NULL.  16-bit weights only. */
+  int32_t parallel_block;      /* 0: y = h + mlp(norm2(h)) with h = x + attention(norm1(x)).  1: both branches start
+                                  from the block's input, y = x + attention(norm1(x)) + mlp(norm2(x)) (Falcon, Cohere);
+                                  norm2 may then be NULL in every layer: the MLP reads norm1(x) too (one norm per block).
+                                  16-bit weights only. */
 } stage_config;
 
 /* Device pointers to one layer's weights, row-major [out_features][in_features], bf16 unless
@@ -126,8 +142,8 @@ typedef struct {
   const void *norm1;  /* [H]  gain of the input RMSNorm */
   const void *wqkv;   /* [(nq + 2 nkv) d][H]: q head rows, then k head rows, then v head rows */
   const void *wo;     /* [H][nq d] */
-  const void *norm2;  /* [H]  gain of the post-attention RMSNorm */
-  const void *wgate;  /* [F][H] */
+  const void *norm2;  /* [H]  gain of the norm in front of the MLP (NULL: see stage_config.parallel_block) */
+  const void *wgate;  /* [F][H]  (NULL with an ungated MLP: stage_config.mlp_kind) */
   const void *wup;    /* [F][H] */
   const void *wdown;  /* [H][F] */
   const void *bqkv;   /* [(nq + 2 nkv) d] bias of the q/k/v projection, added before the rotation
@@ -172,6 +188,16 @@ typedef struct {
    * (section 3.1.3) is the Llama-style block with these biases in place of the rotary embedding.
    */
   const void *alibi;
+  /*
+   * Optional biases, each NULL or set independently per layer, element type of the library:
+   *   norm1_bias, norm2_bias [H]  of the LayerNorms (norm_kind 1 only; must be NULL otherwise)
+   *   bo    [H]  added to the attention's output projection
+   *   bup   [F]  added to up(b) before the gelu (mlp_kind 1 or 2 only; must be NULL otherwise)
+   *   bdown [H]  added to the MLP's down projection
+   * A block with neither a rotation nor score biases (GPT-2: its positions enter with the embedding, outside the
+   * layers) is the linear-bias block with all slopes zero.
+   */
+  const void *norm1_bias, *norm2_bias, *bo, *bup, *bdown;
 } stage_layer_weights;
 
 typedef struct stage_handle stage_handle;
@@ -320,7 +346,8 @@ int stage_forward_taps(stage_handle *st, void *hip_stream, int32_t num_tokens, c
  *   logits_out   device f32 [S][vocab], or NULL when only the tokens are wanted
  *   next_tokens  device int32 [S]
  * Asynchronous on hip_stream like stage_forward, shares the handle's workspace with it (same ordering
- * rule).  Errors: STAGE_ERR_NULL, STAGE_ERR_CONFIG (vocab mismatch), STAGE_ERR_BATCH, STAGE_ERR_HIP.
+ * rule).  Errors: STAGE_ERR_NULL, STAGE_ERR_CONFIG (vocab mismatch; a stage whose blocks use LayerNorms,
+ * norm_kind 1: the head's norm is an RMSNorm only), STAGE_ERR_BATCH, STAGE_ERR_HIP.
  */
 int stage_embed(stage_handle *st, void *hip_stream, const void *table, int32_t vocab, int32_t num_tokens,
                 const int32_t *token_ids, void *hidden_out);

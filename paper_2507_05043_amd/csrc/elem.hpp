@@ -14,4 +14,12 @@ typedef __bf16 e16;
 constexpr int kElemIsF16 = 0;
 #endif
 
+// The norm in front of a branch of the block: RMSNorm (layer = 0; gain only) or LayerNorm (layer = 1; bias optional).
+struct NormSpec {
+  const e16* gain;   // nullptr: no norm asked for
+  const e16* bias;   // LayerNorm only, may be nullptr
+  float eps;
+  int layer;
+};
+
 }  // namespace molink

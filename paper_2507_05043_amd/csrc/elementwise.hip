@@ -9,59 +9,137 @@ namespace molink {
 
 namespace {
 
+// One row per workgroup.  RMSNorm: one pass for the mean square, one to scale.  LayerNorm (ns.layer): a pass for the
+// mean first, then the mean of the squared deviations, then (x - mean) * rs * gain + bias; the row stays in the
+// caches between the passes.
 template <bool FROM_BF16>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const e16* __restrict__ in_e16, float* __restrict__ x,
-                                                      const e16* __restrict__ gain, e16* __restrict__ out,
-                                                      e16* __restrict__ out_lo, int hidden, float eps, bool out_half) {
+                                                      NormSpec ns, e16* __restrict__ out,
+                                                      e16* __restrict__ out_lo, int hidden, bool out_half) {
   __shared__ float partial[4];
+  __shared__ float partial_sum[4];
   const int row = blockIdx.x, tid = threadIdx.x;
   const int chunks = hidden / 8;
   const e16* src_b = in_e16 + (size_t)row * hidden;
   float* xr = x + (size_t)row * hidden;
-  float ss = 0.f;
-  for (int c = tid; c < chunks; c += 256) {
-    float v[8];
+  auto load_row8 = [&](int c, float* v) {
     if constexpr (FROM_BF16) {
       const e16x8 b = load8(src_b + c * 8);
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[e] = e16_to_f32(b[e]);
-      *reinterpret_cast<float4*>(xr + c * 8) = make_float4(v[0], v[1], v[2], v[3]);
-      *reinterpret_cast<float4*>(xr + c * 8 + 4) = make_float4(v[4], v[5], v[6], v[7]);
     } else {
       const float4 p = *reinterpret_cast<const float4*>(xr + c * 8);
       const float4 q = *reinterpret_cast<const float4*>(xr + c * 8 + 4);
       v[0] = p.x; v[1] = p.y; v[2] = p.z; v[3] = p.w; v[4] = q.x; v[5] = q.y; v[6] = q.z; v[7] = q.w;
     }
+  };
+  float mean = 0.f;
+  if (ns.layer) {
+    float sum = 0.f;
+    for (int c = tid; c < chunks; c += 256) {
+      float v[8];
+      load_row8(c, v);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) ss += v[e] * v[e];
+      for (int e = 0; e < 8; ++e) sum += v[e];
+    }
+    sum = wave_sum(sum);
+    if ((tid & 63) == 0) partial_sum[tid >> 6] = sum;
+    __syncthreads();
+    mean = (partial_sum[0] + partial_sum[1] + partial_sum[2] + partial_sum[3]) / (float)hidden;
+  }
+  float ss = 0.f;
+  for (int c = tid; c < chunks; c += 256) {
+    float v[8];
+    load_row8(c, v);
+    if constexpr (FROM_BF16) {
+      *reinterpret_cast<float4*>(xr + c * 8) = make_float4(v[0], v[1], v[2], v[3]);
+      *reinterpret_cast<float4*>(xr + c * 8 + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ss += (v[e] - mean) * (v[e] - mean);
   }
   ss = wave_sum(ss);
   if ((tid & 63) == 0) partial[tid >> 6] = ss;
   __syncthreads();
   const float total = partial[0] + partial[1] + partial[2] + partial[3];
-  const float rs = 1.0f / sqrtf(total / (float)hidden + eps);
+  const float rs = 1.0f / sqrtf(total / (float)hidden + ns.eps);
   for (int c = tid; c < chunks; c += 256) {
     float v[8];
-    if constexpr (FROM_BF16) {
-      const e16x8 b = load8(src_b + c * 8);
+    load_row8(c, v);
+    const e16x8 g = load8(ns.gain + c * 8);
+    float add[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (ns.bias) {
+      const e16x8 b = load8(ns.bias + c * 8);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = e16_to_f32(b[e]);
-    } else {
-      const float4 p = *reinterpret_cast<const float4*>(xr + c * 8);
-      const float4 q = *reinterpret_cast<const float4*>(xr + c * 8 + 4);
-      v[0] = p.x; v[1] = p.y; v[2] = p.z; v[3] = p.w; v[4] = q.x; v[5] = q.y; v[6] = q.z; v[7] = q.w;
+      for (int e = 0; e < 8; ++e) add[e] = e16_to_f32(b[e]);
     }
-    const e16x8 g = load8(gain + c * 8);
     e16x8 o, lo;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const float val = v[e] * rs * e16_to_f32(g[e]);
+      float val = (v[e] - mean) * rs * e16_to_f32(g[e]);
+      if (ns.bias) val += add[e];
       o[e] = f32_to_act(val, out_half);
       lo[e] = f32_to_act(val - act_to_f32(o[e], out_half), out_half);     // what the rounding dropped, for two-plane GEMMs
     }
     store8(out + (size_t)row * hidden + c * 8, o);
     if (out_lo) store8(out_lo + (size_t)row * hidden + c * 8, lo);
   }
+}
+
+__device__ __forceinline__ float gelu_tanh_f(float z) {
+  // 0.5 z (1 + tanh(t)) = z / (1 + exp(-2 t)),  t = sqrt(2/pi) (z + 0.044715 z^3)
+  const float t = 0.7978845608028654f * (z + 0.044715f * z * z * z);
+  return z / (1.0f + __expf(-2.0f * t));
+}
+__device__ __forceinline__ float gelu_erf_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.7071067811865476f)); }
+
+// x[t][:] += bias, ahead of a projection whose product is added to x and carries a bias.
+__global__ __launch_bounds__(256) void add_row_bias_kernel(float* __restrict__ x, const e16* __restrict__ bias, int hidden,
+                                                           size_t count8) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= count8) return;
+  const int col = (int)(idx % (size_t)(hidden / 8)) * 8;
+  const e16x8 b = load8(bias + col);
+  f32x4 p = *reinterpret_cast<const f32x4*>(x + idx * 8), q = *reinterpret_cast<const f32x4*>(x + idx * 8 + 4);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    p[e] += e16_to_f32(b[e]);
+    q[e] += e16_to_f32(b[e + 4]);
+  }
+  *reinterpret_cast<f32x4*>(x + idx * 8) = p;
+  *reinterpret_cast<f32x4*>(x + idx * 8 + 4) = q;
+}
+
+// The ungated MLP's first half after its matrix product: out[t][f] = gelu(sum of the product's split-K planes + bias),
+// rounded once.  One thread per 8 consecutive features.
+__global__ __launch_bounds__(256) void bias_gelu_kernel(const float* __restrict__ src, int planes, size_t plane_stride,
+                                                        const e16* __restrict__ bias, int erf_form,
+                                                        e16* __restrict__ out, e16* __restrict__ out_lo, int ffn,
+                                                        size_t count8, bool out_half) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= count8) return;
+  const int col = (int)(idx % (size_t)(ffn / 8)) * 8;
+  const float* q = src + idx * 8;
+  f32x4 a = *reinterpret_cast<const f32x4*>(q), b = *reinterpret_cast<const f32x4*>(q + 4);
+  for (int k = 1; k < planes; ++k) {
+    a += *reinterpret_cast<const f32x4*>(q + k * plane_stride);
+    b += *reinterpret_cast<const f32x4*>(q + k * plane_stride + 4);
+  }
+  float v[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  if (bias) {
+    const e16x8 bb = load8(bias + col);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] += e16_to_f32(bb[e]);
+  }
+  e16x8 o, lo;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float val = erf_form ? gelu_erf_f(v[e]) : gelu_tanh_f(v[e]);
+    o[e] = f32_to_act(val, out_half);
+    lo[e] = f32_to_act(val - act_to_f32(o[e], out_half), out_half);
+  }
+  store8(out + idx * 8, o);
+  if (out_lo) store8(out_lo + idx * 8, lo);
 }
 
 __global__ __launch_bounds__(256) void rope_table_kernel(const int32_t* __restrict__ positions,
@@ -310,14 +388,29 @@ hipError_t launch_argmax_rows(const float* src, int planes, size_t plane_stride,
   return hipGetLastError();
 }
 
-hipError_t launch_rmsnorm(const e16* in_e16, float* x, const e16* gain, e16* out, e16* out_lo, int rows,
-                          int hidden, float eps, bool from_e16, bool out_half, hipStream_t stream) {
+hipError_t launch_rmsnorm(const e16* in_e16, float* x, const NormSpec& norm, e16* out, e16* out_lo, int rows,
+                          int hidden, bool from_e16, bool out_half, hipStream_t stream) {
   if (from_e16)
-    hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(rows), dim3(256), 0, stream, in_e16, x, gain, out, out_lo, hidden, eps,
+    hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(rows), dim3(256), 0, stream, in_e16, x, norm, out, out_lo, hidden,
                        out_half);
   else
-    hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(rows), dim3(256), 0, stream, in_e16, x, gain, out, out_lo, hidden,
-                       eps, out_half);
+    hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(rows), dim3(256), 0, stream, in_e16, x, norm, out, out_lo, hidden,
+                       out_half);
+  return hipGetLastError();
+}
+
+hipError_t launch_add_row_bias(float* x, const e16* bias, int rows, int hidden, hipStream_t stream) {
+  const size_t count8 = (size_t)rows * (size_t)(hidden / 8);
+  hipLaunchKernelGGL(add_row_bias_kernel, dim3((unsigned)((count8 + 255) / 256)), dim3(256), 0, stream, x, bias, hidden,
+                     count8);
+  return hipGetLastError();
+}
+
+hipError_t launch_bias_gelu(const float* src, int planes, size_t plane_stride, const e16* bias, bool erf_form, e16* out,
+                            e16* out_lo, int rows, int ffn, bool out_half, hipStream_t stream) {
+  const size_t count8 = (size_t)rows * (size_t)(ffn / 8);
+  hipLaunchKernelGGL(bias_gelu_kernel, dim3((unsigned)((count8 + 255) / 256)), dim3(256), 0, stream, src, planes,
+                     plane_stride, bias, erf_form ? 1 : 0, out, out_lo, ffn, count8, out_half);
   return hipGetLastError();
 }
 

@@ -7,13 +7,24 @@
 
 namespace molink {
 
-// a[t][:] = x[t][:] * gain / sqrt(mean(x[t][:]^2) + eps), rounded to e16.
+// a[t][:] = x[t][:] * gain / sqrt(mean(x[t][:]^2) + eps), rounded to e16; or, with norm.layer, the LayerNorm
+// (x - mean) / sqrt(mean((x - mean)^2) + eps) * gain + bias.
 // from_e16: the row source is in_e16 (the stage input) and the fp32 residual stream x is also
 // initialised from it; otherwise the source is x.
 // out_lo (optional): receives e16(value - e16(value)), the second activation plane of the two-plane GEMMs.
 // out_half (bfloat16 library only): the output is written as IEEE half bits, for GEMMs that take half activations.
-hipError_t launch_rmsnorm(const e16* in_e16, float* x, const e16* gain, e16* out, e16* out_lo, int rows,
-                          int hidden, float eps, bool from_e16, bool out_half, hipStream_t stream);
+hipError_t launch_rmsnorm(const e16* in_e16, float* x, const NormSpec& norm, e16* out, e16* out_lo, int rows,
+                          int hidden, bool from_e16, bool out_half, hipStream_t stream);
+
+// x[t][:] += bias[:] on the fp32 residual stream x [rows][hidden]: the bias of a projection whose product is added to
+// x, put there ahead of the product (the sum is the same up to fp32 rounding order).
+hipError_t launch_add_row_bias(float* x, const e16* bias, int rows, int hidden, hipStream_t stream);
+
+// The ungated MLP between its two matrix products: out[t][f] = gelu(sum over `planes` planes of src[t][f] + bias[f]),
+// planes `plane_stride` floats apart (split-K partial sums, or one plane), gelu in its tanh form or (erf_form) as
+// z Phi(z); rounded once to e16 (or IEEE half with out_half), with the optional second plane out_lo.
+hipError_t launch_bias_gelu(const float* src, int planes, size_t plane_stride, const e16* bias, bool erf_form, e16* out,
+                            e16* out_lo, int rows, int ffn, bool out_half, hipStream_t stream);
 
 // cos_sin[t][i] = (cos, sin)(positions[t] * theta^(-2i/r)), i < r/2, evaluated in fp64; r = rotary_dim, the
 // number of leading elements of a head that rotate (head_dim unless the rotary embedding is partial).

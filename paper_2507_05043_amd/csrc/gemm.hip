@@ -1117,20 +1117,22 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(GemmArgs p, int
   }
 }
 
-// Sum of the split-K partial results + residual add + (RMSNorm | e16 rounding), one workgroup per row.
+// Sum of the split-K partial results + residual add + (norm | e16 rounding), one workgroup
+// per row.  The norm is an RMSNorm, or (ns.layer) a LayerNorm, which takes one more pass over the row for its mean.
 template <bool NORM>
 __global__ __launch_bounds__(1024) void reduce_residual_norm_kernel(const float* __restrict__ partial, int splits,
                                                                    int m_rows, int n, float* __restrict__ x,
-                                                                   const e16* __restrict__ gain, float eps,
+                                                                   NormSpec ns,
                                                                    e16* __restrict__ out, e16* __restrict__ out_lo,
                                                                    int ldo, bool out_half) {
   __shared__ float wsum[16];
+  __shared__ float wmean[16];
   const int row = blockIdx.x, tid = threadIdx.x;
   const int stride = blockDim.x * 4, nwaves = blockDim.x >> 6;
   const size_t plane = (size_t)m_rows * n;
   float* xr = x + (size_t)row * n;
   const float* pr = partial + (size_t)row * n;
-  float ss = 0.f;
+  float ss = 0.f, sum = 0.f;
   for (int c = tid * 4; c < n; c += stride) {
     f32x4 v = *reinterpret_cast<const f32x4*>(xr + c);
     f32x4 s = {0.f, 0.f, 0.f, 0.f};
@@ -1139,6 +1141,7 @@ __global__ __launch_bounds__(1024) void reduce_residual_norm_kernel(const float*
     if constexpr (NORM) {
       *reinterpret_cast<f32x4*>(xr + c) = v;
       ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+      sum += v[0] + v[1] + v[2] + v[3];
     } else {
       e16x4 o;
 #pragma unroll
@@ -1147,19 +1150,41 @@ __global__ __launch_bounds__(1024) void reduce_residual_norm_kernel(const float*
     }
   }
   if constexpr (NORM) {
+    float mean = 0.f;
+    if (ns.layer) {
+      sum = wave_sum(sum);
+      if ((tid & 63) == 0) wmean[tid >> 6] = sum;
+      __syncthreads();
+      float tot = 0.f;
+      for (int w = 0; w < nwaves; ++w) tot += wmean[w];
+      mean = tot / (float)n;
+      ss = 0.f;
+      for (int c = tid * 4; c < n; c += stride) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(xr + c);     // written by this same thread above
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ss += (v[e] - mean) * (v[e] - mean);
+      }
+    }
     ss = wave_sum(ss);
     if ((tid & 63) == 0) wsum[tid >> 6] = ss;
     __syncthreads();
     float tot = 0.f;
     for (int w = 0; w < nwaves; ++w) tot += wsum[w];
-    const float rs = 1.0f / sqrtf(tot / (float)n + eps);
+    const float rs = 1.0f / sqrtf(tot / (float)n + ns.eps);
     for (int c = tid * 4; c < n; c += stride) {
       const f32x4 v = *reinterpret_cast<const f32x4*>(xr + c);     // written by this same thread above
-      const e16x4 g = *reinterpret_cast<const e16x4*>(gain + c);
+      const e16x4 g = *reinterpret_cast<const e16x4*>(ns.gain + c);
+      f32x4 add = {0.f, 0.f, 0.f, 0.f};
+      if (ns.bias) {
+        const e16x4 b = *reinterpret_cast<const e16x4*>(ns.bias + c);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) add[e] = e16_to_f32(b[e]);
+      }
       e16x4 o, lo;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const float val = v[e] * rs * e16_to_f32(g[e]);
+        float val = (v[e] - mean) * rs * e16_to_f32(g[e]);
+        if (ns.bias) val += add[e];
         o[e] = f32_to_act(val, out_half);
         lo[e] = f32_to_act(val - act_to_f32(o[e], out_half), out_half);
       }
@@ -1771,15 +1796,15 @@ hipError_t launch_gemm_reduce(const GemmArgs& a, GemmEpilogue epi, const GemmPla
 }
 
 hipError_t launch_gemm_reduce_residual_norm(const GemmArgs& a, GemmEpilogue epi, const GemmPlan& plan,
-                                            const e16* gain, float eps, e16* norm_out, e16* norm_out_lo,
+                                            const NormSpec& norm, e16* norm_out, e16* norm_out_lo,
                                             bool norm_out_half, hipStream_t stream) {
   const int threads = a.n >= 4096 ? 1024 : (a.n >= 2048 ? 512 : 256);
   if (epi == kEpiResidualOut) {
     hipLaunchKernelGGL(reduce_residual_norm_kernel<false>, dim3(a.m), dim3(threads), 0, stream, a.partial, plan.splits, a.m,
-                       a.n, a.resid, (const e16*)nullptr, eps, a.out_e16, (e16*)nullptr, a.ldo, false);
+                       a.n, a.resid, NormSpec{nullptr, nullptr, norm.eps, 0}, a.out_e16, (e16*)nullptr, a.ldo, false);
   } else {
     hipLaunchKernelGGL(reduce_residual_norm_kernel<true>, dim3(a.m), dim3(threads), 0, stream, a.partial, plan.splits, a.m,
-                       a.n, a.resid, gain, eps, norm_out, norm_out_lo, a.n, norm_out_half);
+                       a.n, a.resid, norm, norm_out, norm_out_lo, a.n, norm_out_half);
   }
   return hipGetLastError();
 }

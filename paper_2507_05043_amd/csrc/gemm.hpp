@@ -97,10 +97,10 @@ hipError_t launch_gemm_reduce(const GemmArgs& args, GemmEpilogue epi, const Gemm
 
 // Only when plan.partials and the epilogue is a residual one: one kernel that sums the partial
 // results in split order, adds them to the fp32 residual stream x[m][n] (in place), and then either
-// writes RMSNorm(x; gain, eps) as e16 to norm_out (gain != nullptr) or rounds x to e16 into
+// writes the norm of x (RMSNorm or LayerNorm: NormSpec) as e16 to norm_out (norm.gain != nullptr) or rounds x to e16 into
 // args.out_e16 (kEpiResidualOut).  Replaces launch_gemm_reduce plus the following RMSNorm.
 hipError_t launch_gemm_reduce_residual_norm(const GemmArgs& args, GemmEpilogue epi, const GemmPlan& plan,
-                                            const e16* gain, float eps, e16* norm_out, e16* norm_out_lo,
+                                            const NormSpec& norm, e16* norm_out, e16* norm_out_lo,
                                             bool norm_out_half, hipStream_t stream);
 
 }  // namespace molink

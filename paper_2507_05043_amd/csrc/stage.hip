@@ -83,6 +83,8 @@ struct Dims {
 
 struct WorkspaceLayout {
   size_t x, a, a_lo, qkv_f32, qkv, q_lo, attn, attn_lo, mlp, mlp_lo, cos_sin, splitk, part_o, part_ml, meta, total;
+  size_t b2, b2_lo;                        // parallel block: the second norm of the block's input (and its second plane)
+  size_t up_f32;                           // ungated MLP: the first product before bias and gelu, fp32
   size_t splitk_floats;                    // capacity of the split-K scratch
   size_t head_a, head_logits, ends_meta;   // output head: normalised last rows, fp32 logits, token ids / row indices
   size_t wexp;                             // 4-bit weights: one projection's matrices expanded to e16
@@ -115,6 +117,14 @@ int check_config(const stage_config* c) {
     return fail(STAGE_ERR_CONFIG, "rope_interleaved must be 0 or 1, got %d", c->rope_interleaved);
   if (c->weight_copies != 0 && c->weight_copies != 1)
     return fail(STAGE_ERR_CONFIG, "weight_copies must be 0 (keep copies in operand order) or 1 (none), got %d", c->weight_copies);
+  if (c->norm_kind != 0 && c->norm_kind != 1)
+    return fail(STAGE_ERR_CONFIG, "norm_kind must be 0 (RMSNorm) or 1 (LayerNorm), got %d", c->norm_kind);
+  if (c->mlp_kind < 0 || c->mlp_kind > 2)
+    return fail(STAGE_ERR_CONFIG, "mlp_kind must be 0 (gated, SiLU), 1 (ungated, tanh GELU) or 2 (ungated, erf GELU), got %d", c->mlp_kind);
+  if (c->parallel_block != 0 && c->parallel_block != 1)
+    return fail(STAGE_ERR_CONFIG, "parallel_block must be 0 or 1, got %d", c->parallel_block);
+  if (c->weight_bits == 4 && (c->mlp_kind != 0 || c->parallel_block != 0))
+    return fail(STAGE_ERR_CONFIG, "4-bit weights are supported for the gated, sequential block only (mlp_kind 0, parallel_block 0)");
   if (c->weight_bits != 0 && c->weight_bits != 16 && c->weight_bits != 4)
     return fail(STAGE_ERR_CONFIG, "weight_bits must be 0, 16 or 4, got %d", c->weight_bits);
   if (c->weight_bits == 4) {
@@ -209,7 +219,7 @@ CopyLayout copy_layout_of(const stage_config& c) {
   };
   cl.qkv = take(d.qkv_out, d.H);
   cl.o = take(d.H, d.nq * d.d);
-  cl.gate = take(d.F, d.H);
+  cl.gate = c.mlp_kind == 0 ? take(d.F, d.H) : kNoCopy;
   cl.up = take(d.F, d.H);
   cl.down = take(d.H, d.F);
   cl.per_layer = off;
@@ -233,6 +243,9 @@ WorkspaceLayout layout_of(const stage_config& c) {
   w.mlp = take(T * d.F * 2);
   w.mlp_lo = take(lo_planes_of(c) ? T * d.F * 2 : 0);
   w.cos_sin = take(T * (d.d / 2) * 8);
+  w.b2 = take(c.parallel_block ? T * d.H * 2 : 0);
+  w.b2_lo = take(c.parallel_block && lo_planes_of(c) ? T * d.H * 2 : 0);
+  w.up_f32 = take(c.mlp_kind != 0 ? T * d.F * 4 : 0);
   // split-K scratch for every way the projections may be planned: as for one activation plane, and - with two
   // planes, or with half activations, whose decode-sized projections take the two-plane plans' 64-row tiles -
   // as for two
@@ -244,7 +257,7 @@ WorkspaceLayout layout_of(const stage_config& c) {
       if (arr && (sp || !copies_possible(c))) continue;   // depends on the handle, not on the capacity this is sized for)
       if ((v = gemm_partial_floats(c.max_tokens, d.qkv_out, d.H, kEpiStoreF32, kNumCus, sp, arr)) > pf) pf = v;
       if ((v = gemm_partial_floats(c.max_tokens, d.H, d.nq * d.d, kEpiResidualF32, kNumCus, sp, arr)) > pf) pf = v;
-      if ((v = gemm_partial_floats(c.max_tokens, d.F, d.H, kEpiSwiGLU, kNumCus, sp, arr)) > pf) pf = v;
+      if ((v = gemm_partial_floats(c.max_tokens, d.F, d.H, c.mlp_kind == 0 ? kEpiSwiGLU : kEpiStoreF32, kNumCus, sp, arr)) > pf) pf = v;
       if ((v = gemm_partial_floats(c.max_tokens, d.H, d.F, kEpiResidualF32, kNumCus, sp, arr)) > pf) pf = v;
     }
   }
@@ -488,7 +501,8 @@ int plan_layer(const stage_handle* st, int T, bool qkv_two_planes, bool two_plan
   const bool have = st->wcopy != nullptr;     // copies in operand order: a projection may be planned on the kernel that reads them
   out->qkv = plan_projection(c, T, d.qkv_out, d.H, kEpiStoreF32, qkv_two_planes, have && cl.qkv != kNoCopy);
   out->o = plan_projection(c, T, d.H, d.nq * d.d, kEpiResidualF32, two_planes, have && cl.o != kNoCopy);
-  out->gateup = plan_projection(c, T, d.F, d.H, kEpiSwiGLU, two_planes, have && cl.gate != kNoCopy);
+  out->gateup = c.mlp_kind == 0 ? plan_projection(c, T, d.F, d.H, kEpiSwiGLU, two_planes, have && cl.gate != kNoCopy)
+                                : plan_projection(c, T, d.F, d.H, kEpiStoreF32, two_planes, have && cl.up != kNoCopy);
   out->down = plan_projection(c, T, d.H, d.F, kEpiResidualF32, two_planes, have && cl.down != kNoCopy);
   out->down_out = plan_projection(c, T, d.H, d.F, kEpiResidualOut, two_planes, have && cl.down != kNoCopy);
   for (const GemmPlan* p : {&out->qkv, &out->o, &out->gateup, &out->down, &out->down_out})
@@ -510,10 +524,11 @@ int run_gemm(stage_handle* st, hipStream_t stream, int kernel_class, const GemmA
 }
 
 // A projection whose result is added to the fp32 residual stream x, followed by what consumes x next:
-// an RMSNorm into `norm_out` (gain != nullptr), or nothing.  When the GEMM splits K across workgroups
+// a norm into `norm_out` (norm.gain != nullptr), or nothing.  When the GEMM splits K across workgroups
 // the sum of the partial results, the residual add and the norm run as one kernel.
 int run_residual_gemm(stage_handle* st, hipStream_t stream, int kernel_class, const GemmArgs& args, GemmEpilogue epi,
-                      const GemmPlan& plan, const e16* gain, e16* norm_out, e16* norm_out_lo, bool norm_out_half) {
+                      const GemmPlan& plan, const NormSpec& norm, e16* norm_out, e16* norm_out_lo, bool norm_out_half) {
+  const e16* gain = norm.gain;
   {
     Timer t(st, stream, kernel_class);
     HIP_TRY(launch_gemm_main(args, epi, plan, stream));
@@ -521,8 +536,7 @@ int run_residual_gemm(stage_handle* st, hipStream_t stream, int kernel_class, co
   const bool fused = plan.partials && (gain != nullptr || epi == kEpiResidualOut);
   if (fused) {
     Timer t(st, stream, STAGE_K_SPLITK_REDUCE);
-    HIP_TRY(launch_gemm_reduce_residual_norm(args, epi, plan, gain, st->cfg.rms_eps, norm_out, norm_out_lo, norm_out_half,
-                                             stream));
+    HIP_TRY(launch_gemm_reduce_residual_norm(args, epi, plan, norm, norm_out, norm_out_lo, norm_out_half, stream));
     return STAGE_OK;
   }
   if (plan.partials) {
@@ -531,8 +545,7 @@ int run_residual_gemm(stage_handle* st, hipStream_t stream, int kernel_class, co
   }
   if (gain) {
     Timer t(st, stream, STAGE_K_RMSNORM);
-    HIP_TRY(launch_rmsnorm(nullptr, args.resid, gain, norm_out, norm_out_lo, args.m, args.n, st->cfg.rms_eps, false,
-                           norm_out_half, stream));
+    HIP_TRY(launch_rmsnorm(nullptr, args.resid, norm, norm_out, norm_out_lo, args.m, args.n, false, norm_out_half, stream));
   }
   return STAGE_OK;
 }
@@ -705,6 +718,17 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
   const DecodeToken* d_dtok = (const DecodeToken*)(meta + o_dtok);
   const PrefillTile* d_tiles = (const PrefillTile*)(meta + o_tiles);
 
+  // the norm in front of layer l's attention branch (second = false) or MLP branch
+  auto norm_of = [&](int l, bool second) {
+    const stage_layer_weights& lw = st->layers[l];
+    return NormSpec{(const e16*)(second ? lw.norm2 : lw.norm1), (const e16*)(second ? lw.norm2_bias : lw.norm1_bias),
+                    c.rms_eps, c.norm_kind};
+  };
+  const NormSpec no_norm{nullptr, nullptr, c.rms_eps, 0};
+  const bool parallel = c.parallel_block != 0;
+  e16* b2 = parallel ? (e16*)(ws + wl.b2) : nullptr;
+  e16* b2_lo = parallel && two_plane ? (e16*)(ws + wl.b2_lo) : nullptr;
+  float* up_f32 = (float*)(ws + wl.up_f32);
   const bool alibi = st->layers[0].alibi != nullptr;   // linear biases in the attention scores: nothing rotates
   const int rotating = alibi ? 0 : d.rd;
   if (rotating) {
@@ -715,8 +739,7 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
   {
     // the first layer's input norm also initialises the fp32 residual stream from the e16 input
     Timer t(st, stream, STAGE_K_RMSNORM);
-    HIP_TRY(launch_rmsnorm((const e16*)hidden_in, x, (const e16*)st->layers[0].norm1, a, norm1_lo, T, d.H, c.rms_eps,
-                           true, half_act, stream));
+    HIP_TRY(launch_rmsnorm((const e16*)hidden_in, x, norm_of(0, false), a, norm1_lo, T, d.H, true, half_act, stream));
   }
   for (int l = 0; l < d.L; ++l) {
     const stage_layer_weights& w = st->layers[l];
@@ -726,6 +749,15 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
     e16* v_pool = k_pool + kv_region;
     // `a` holds RMSNorm(x; norm1 of this layer) here
     if (tap && taps->tap_norm1) HIP_TRY(copy_activation_tap(taps->tap_norm1, a, (size_t)T * d.H, half_act, stream));
+    // parallel block: the MLP branch starts from the block's input too - its norm is taken now, before the
+    // attention branch is added to x (a block with one norm reads `a` in both branches)
+    const bool own_norm2 = parallel && w.norm2 != nullptr;
+    if (own_norm2) {
+      Timer t(st, stream, STAGE_K_RMSNORM);
+      HIP_TRY(launch_rmsnorm(nullptr, x, norm_of(l, true), b2, b2_lo, T, d.H, false, half_act, stream));
+    }
+    const e16* mlp_in = parallel ? (own_norm2 ? b2 : a) : a;
+    const e16* mlp_in_lo = own_norm2 ? b2_lo : a_lo;
     {
       GemmArgs g{};
       g.a = a; g.a_lo = norm1_lo; g.a_half = half_act; g.out_f32 = qkv_f32; g.partial = splitk;
@@ -765,20 +797,38 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       g.a = attn; g.a_lo = attn_lo; g.a_half = half_act; g.resid = x; g.partial = splitk;
       g.m = T; g.n = d.H; g.k = d.nq * d.d; g.lda = d.nq * d.d; g.ldo = d.H;
       if (int rc = bind_weights(st, stream, g, w.wo, w.so, w.zo, nullptr, nullptr, nullptr, l, st->copies.o, kNoCopy)) return rc;
-      int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_O, g, kEpiResidualF32, plans.o, (const e16*)w.norm2, a, a_lo,
-                                 half_act);
+      if (w.bo) {        // the projection's bias joins the residual stream ahead of its product
+        Timer t(st, stream, STAGE_K_SPLITK_REDUCE);
+        HIP_TRY(launch_add_row_bias(x, (const e16*)w.bo, T, d.H, stream));
+      }
+      int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_O, g, kEpiResidualF32, plans.o,
+                                 parallel ? no_norm : norm_of(l, true), a, a_lo, half_act);
       if (rc) return rc;
     }
     if (tap && taps->tap_h)
       HIP_TRY(hipMemcpyAsync(taps->tap_h, x, (size_t)T * d.H * 4, hipMemcpyDeviceToDevice, stream));
     {
       GemmArgs g{};
-      g.a = a; g.a_lo = a_lo; g.a_half = half_act; g.out_e16 = mlp; g.out_lo = mlp_lo; g.out_half = half_act;
+      g.a = mlp_in; g.a_lo = mlp_in_lo; g.a_half = half_act; g.out_e16 = mlp; g.out_lo = mlp_lo; g.out_half = half_act;
       g.partial = splitk;
       g.m = T; g.n = d.F; g.k = d.H; g.lda = d.H; g.ldo = d.F;
-      if (int rc = bind_weights(st, stream, g, w.wgate, w.sgate, w.zgate, w.wup, w.sup, w.zup, l, st->copies.gate, st->copies.up)) return rc;
-      int rc = run_gemm(st, stream, STAGE_K_GEMM_GATEUP, g, kEpiSwiGLU, plans.gateup);
-      if (rc) return rc;
+      if (c.mlp_kind == 0) {
+        if (int rc = bind_weights(st, stream, g, w.wgate, w.sgate, w.zgate, w.wup, w.sup, w.zup, l, st->copies.gate, st->copies.up)) return rc;
+        int rc = run_gemm(st, stream, STAGE_K_GEMM_GATEUP, g, kEpiSwiGLU, plans.gateup);
+        if (rc) return rc;
+      } else {
+        // ungated: the product in fp32 (one plane, or the split-K partial sums), then bias + gelu + rounding in one pass
+        g.out_f32 = up_f32;
+        if (int rc = bind_weights(st, stream, g, w.wup, w.sup, w.zup, nullptr, nullptr, nullptr, l, st->copies.up, kNoCopy)) return rc;
+        const GemmPlan& plan = plans.gateup;
+        {
+          Timer t(st, stream, STAGE_K_GEMM_GATEUP);
+          HIP_TRY(launch_gemm_main(g, kEpiStoreF32, plan, stream));
+        }
+        Timer t(st, stream, STAGE_K_SPLITK_REDUCE);
+        HIP_TRY(launch_bias_gelu(plan.partials ? splitk : up_f32, plan.partials ? plan.splits : 1, (size_t)T * d.F,
+                                 (const e16*)w.bup, c.mlp_kind == 2, mlp, mlp_lo, T, d.F, half_act, stream));
+      }
     }
     if (tap && taps->tap_mlp) HIP_TRY(copy_activation_tap(taps->tap_mlp, mlp, (size_t)T * d.F, half_act, stream));
     {
@@ -790,9 +840,13 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       g.partial = splitk;
       g.m = T; g.n = d.H; g.k = d.F; g.lda = d.F; g.ldo = d.H;
       if (int rc = bind_weights(st, stream, g, w.wdown, w.sdown, w.zdown, nullptr, nullptr, nullptr, l, st->copies.down, kNoCopy)) return rc;
-      const e16* next_gain = last ? nullptr : (const e16*)st->layers[l + 1].norm1;
+      if (w.bdown) {
+        Timer t(st, stream, STAGE_K_SPLITK_REDUCE);
+        HIP_TRY(launch_add_row_bias(x, (const e16*)w.bdown, T, d.H, stream));
+      }
       int rc = run_residual_gemm(st, stream, STAGE_K_GEMM_DOWN, g, fused_out ? kEpiResidualOut : kEpiResidualF32,
-                                 fused_out ? plans.down_out : plans.down, next_gain, a, norm1_lo, half_act);
+                                 fused_out ? plans.down_out : plans.down, last ? no_norm : norm_of(l + 1, false), a,
+                                 norm1_lo, half_act);
       if (rc) return rc;
       if (tap && taps->tap_x)
         HIP_TRY(hipMemcpyAsync(taps->tap_x, x, (size_t)T * d.H * 4, hipMemcpyDeviceToDevice, stream));
@@ -863,11 +917,21 @@ int stage_init(const stage_config* cfg, const stage_layer_weights* layers, void*
   if (!layers || !kv_pool || !workspace) return fail(STAGE_ERR_NULL, "layers, kv_pool or workspace is NULL");
   for (int l = 0; l < cfg->num_layers; ++l) {
     const stage_layer_weights& w = layers[l];
-    if (!w.norm1 || !w.wqkv || !w.wo || !w.norm2 || !w.wgate || !w.wup || !w.wdown)
+    if (!w.norm1 || !w.wqkv || !w.wo || !w.wup || !w.wdown)
       return fail(STAGE_ERR_NULL, "layer %d has a NULL weight pointer", l);
-    const void* ptrs[7] = {w.norm1, w.wqkv, w.wo, w.norm2, w.wgate, w.wup, w.wdown};
+    if ((w.wgate == nullptr) != (cfg->mlp_kind != 0))
+      return fail(cfg->mlp_kind ? STAGE_ERR_CONFIG : STAGE_ERR_NULL,
+                  "layer %d: wgate must be set for the gated MLP (mlp_kind 0) and NULL for the ungated one", l);
+    if (!w.norm2 && !cfg->parallel_block) return fail(STAGE_ERR_NULL, "layer %d: norm2 is NULL (allowed with parallel_block only)", l);
+    if ((w.norm2 == nullptr) != (layers[0].norm2 == nullptr))
+      return fail(STAGE_ERR_NULL, "layer %d: norm2 must be set in every layer or in none", l);
+    if ((w.norm1_bias || w.norm2_bias) && cfg->norm_kind != 1)
+      return fail(STAGE_ERR_CONFIG, "layer %d: norm1_bias / norm2_bias belong to LayerNorms (norm_kind 1)", l);
+    if (w.norm2_bias && !w.norm2) return fail(STAGE_ERR_CONFIG, "layer %d: norm2_bias without norm2", l);
+    if (w.bup && cfg->mlp_kind == 0) return fail(STAGE_ERR_CONFIG, "layer %d: bup belongs to the ungated MLP (mlp_kind 1 or 2)", l);
+    const void* ptrs[12] = {w.norm1, w.wqkv, w.wo, w.norm2, w.wgate, w.wup, w.wdown, w.norm1_bias, w.norm2_bias, w.bo, w.bup, w.bdown};
     for (const void* p : ptrs)
-      if ((uintptr_t)p % 16) return fail(STAGE_ERR_CONFIG, "layer %d has a weight pointer that is not 16-byte aligned", l);
+      if ((uintptr_t)p % 16) return fail(STAGE_ERR_CONFIG, "layer %d has a weight or bias pointer that is not 16-byte aligned", l);
     if ((uintptr_t)w.bqkv % 16) return fail(STAGE_ERR_CONFIG, "layer %d: bqkv is not 16-byte aligned", l);
     if ((w.alibi == nullptr) != (layers[0].alibi == nullptr))
       return fail(STAGE_ERR_NULL, "layer %d: alibi slopes must be set in every layer or in none", l);
@@ -944,7 +1008,7 @@ int stage_init(const stage_config* cfg, const stage_layer_weights* layers, void*
                                                                  {w.wgate, copies.gate, d.F, d.H}, {w.wup, copies.up, d.F, d.H},
                                                                  {w.wdown, copies.down, d.H, d.F}};
       for (const auto& j : jobs)
-        if (j.at != kNoCopy && e == hipSuccess)
+        if (j.at != kNoCopy && j.src && e == hipSuccess)
           e = launch_arrange_weights((const e16*)j.src, j.n, j.k, to_half, (e16*)(base + j.at), nullptr);
     }
     if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
@@ -1073,6 +1137,8 @@ int stage_head(stage_handle* st, void* hip_stream, int32_t num_tokens, const voi
                const int32_t* q_lens, const void* final_norm, const void* lm_head, int32_t vocab, void* logits_out,
                int32_t* next_tokens) {
   if (!st) return fail(STAGE_ERR_NULL, "stage handle is NULL");
+  if (st && st->cfg.norm_kind != 0)
+    return fail(STAGE_ERR_CONFIG, "stage_head normalises with an RMSNorm; this stage's blocks use LayerNorms (norm_kind 1)");
   if (!hidden || !q_lens || !final_norm || !lm_head || !next_tokens)
     return fail(STAGE_ERR_NULL, "a required argument of stage_head is NULL");
   const stage_config& c = st->cfg;

@@ -13,13 +13,18 @@ def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_
                max_tokens: Optional[int] = None, alias_layers: bool = False, fill_kv: bool = True,
                device: str = "cuda:0", activation_planes: int = 0, vocab_size: int = 0,
                qkv_bias: bool = False, weight_group_size: int = 0, dtype: torch.dtype = torch.bfloat16,
-               qk_norm: bool = False, weight_copies: int = 0, alibi: bool = False) -> Stage:
+               qk_norm: bool = False, weight_copies: int = 0, alibi=False, block_biases: bool = False,
+               shared_norm: bool = False) -> Stage:
     """Draw the stage's weights on the device, size the pool and workspace for `mb`, fill the cache.
     weight_group_size > 0: 4-bit group-quantised projection weights with that group size.
     dtype: the 16-bit element type (bfloat16, or float16 for the half-precision library).
     qk_norm: per-head RMSNorm gains for queries and keys (the Qwen3 family's block).
     weight_copies: 1 = the stage keeps no second copy of its weights in operand order.
-    alibi: attention with linear biases (the published head slopes) instead of the rotary embedding."""
+    alibi: attention with linear biases (the published head slopes; "zero": all slopes zero, a block without
+    positions) instead of the rotary embedding.
+    block_biases: the biases the shape's block kind can carry (of its LayerNorms, of the output and down projections,
+    of an ungated MLP's first matrix).  shared_norm: a parallel block whose two branches read one norm.
+    The block's kind itself (norm_kind, mlp_kind, parallel_block) comes with the shape."""
     if weight_group_size:
         layers = [synth.draw_w4_layer(shape, l, seed=seed, group=weight_group_size, device=device,
                                       weight_std=0.02 if weight_std is None else float(weight_std), dtype=dtype)
@@ -35,7 +40,21 @@ def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_
             w.update(synth.draw_qk_norm(shape, l, seed=seed, device=device, dtype=dtype))
     if alibi:
         for w in layers:
-            w["alibi"] = synth.alibi_slopes(shape.num_q_heads).to(device)
+            slopes = synth.alibi_slopes(shape.num_q_heads).to(device)
+            w["alibi"] = slopes * 0 if alibi == "zero" else slopes
+    for l, w in enumerate(layers):
+        if shape.mlp_kind != "swiglu":
+            del w["wgate"]
+        if block_biases:
+            b = synth.draw_block_biases(shape, l, seed=seed, device=device, dtype=dtype)
+            if shape.norm_kind != "layer":
+                del b["norm1_bias"], b["norm2_bias"]
+            if shape.mlp_kind == "swiglu":
+                del b["bup"]
+            w.update(b)
+        if shared_norm:
+            del w["norm2"]
+            w.pop("norm2_bias", None)
     cfg = make_config(num_layers=shape.num_layers, hidden=shape.hidden, num_q_heads=shape.num_q_heads,
                       num_kv_heads=shape.num_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn,
                       rms_eps=shape.rms_eps, rope_theta=shape.rope_theta, num_kv_blocks=mb.num_kv_blocks,
@@ -44,7 +63,8 @@ def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_
                       kv_layer_stride_bytes=0 if alias_layers else None, activation_planes=activation_planes,
                       vocab_size=vocab_size, weight_bits=4 if weight_group_size else 0,
                       weight_group_size=weight_group_size, rotary_dim=shape.rotary_dim, weight_copies=weight_copies,
-                      rope_interleaved=int(shape.rope_interleaved))
+                      rope_interleaved=int(shape.rope_interleaved), norm_kind=shape.norm_kind, mlp_kind=shape.mlp_kind,
+                      parallel_block=int(shape.parallel_block))
     st = Stage(cfg, layers, device=device, dtype=dtype)
     if fill_kv:
         fill_pool(st, shape, mb, seed)

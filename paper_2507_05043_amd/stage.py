@@ -43,6 +43,7 @@ class StageConfig(ctypes.Structure):
         ("activation_planes", ctypes.c_int32), ("vocab_size", ctypes.c_int32),
         ("weight_bits", ctypes.c_int32), ("weight_group_size", ctypes.c_int32), ("rotary_dim", ctypes.c_int32),
         ("rope_interleaved", ctypes.c_int32), ("weight_copies", ctypes.c_int32),
+        ("norm_kind", ctypes.c_int32), ("mlp_kind", ctypes.c_int32), ("parallel_block", ctypes.c_int32),
     ]
 
 
@@ -51,9 +52,16 @@ W4_SCALES = ("sqkv", "so", "sgate", "sup", "sdown")
 W4_ZEROS = ("zqkv", "zo", "zgate", "zup", "zdown")
 
 
+BLOCK_BIASES = ("norm1_bias", "norm2_bias", "bo", "bup", "bdown")
+# tensors a layer may leave out (wgate: the ungated MLP; norm2: a parallel block with one norm)
+OPTIONAL_TENSORS = ("bqkv", "qnorm", "knorm", "alibi", "wgate", "norm2") + BLOCK_BIASES
+NORM_KINDS = {"rms": 0, "layer": 1}
+MLP_KINDS = {"swiglu": 0, "gelu_tanh": 1, "gelu_erf": 2}
+
+
 class StageLayerWeights(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in ("norm1", "wqkv", "wo", "norm2", "wgate", "wup", "wdown", "bqkv")
-                + W4_SCALES + W4_ZEROS + ("qnorm", "knorm", "alibi")]
+                + W4_SCALES + W4_ZEROS + ("qnorm", "knorm", "alibi") + BLOCK_BIASES]
 
 
 class StageTaps(ctypes.Structure):
@@ -120,11 +128,13 @@ def _check(rc: int, lib: Optional[ctypes.CDLL] = None) -> None:
 def make_config(*, num_layers, hidden, num_q_heads, num_kv_heads, head_dim, ffn, rms_eps, rope_theta,
                 num_kv_blocks, max_tokens, max_seqs, max_blocks_per_seq, kv_block_size=16,
                 kv_layer_stride_bytes=None, activation_planes=0, vocab_size=0, weight_bits=0,
-                weight_group_size=0, rotary_dim=0, weight_copies=0, rope_interleaved=0) -> StageConfig:
+                weight_group_size=0, rotary_dim=0, weight_copies=0, rope_interleaved=0, norm_kind=0, mlp_kind=0,
+                parallel_block=0) -> StageConfig:
     cfg = StageConfig(ctypes.sizeof(StageConfig), num_layers, hidden, num_q_heads, num_kv_heads, head_dim, ffn,
                       rms_eps, rope_theta, kv_block_size, num_kv_blocks, 0, max_tokens, max_seqs, max_blocks_per_seq,
                       activation_planes, vocab_size, weight_bits, weight_group_size, rotary_dim, int(rope_interleaved),
-                      weight_copies)
+                      weight_copies, NORM_KINDS.get(norm_kind, norm_kind), MLP_KINDS.get(mlp_kind, mlp_kind),
+                      int(parallel_block))
     if kv_layer_stride_bytes is None:
         kv_layer_stride_bytes = stage_kv_layer_bytes(cfg)
     cfg.kv_layer_stride_bytes = kv_layer_stride_bytes
@@ -192,7 +202,7 @@ class Stage:
         for l, w in enumerate(self.layers):
             four_bit = cfg.weight_bits == 4
             for name, _ in StageLayerWeights._fields_:
-                if name in ("bqkv", "qnorm", "knorm", "alibi") and w.get(name) is None:     # the optional tensors
+                if name in OPTIONAL_TENSORS and w.get(name) is None:
                     continue
                 if not four_bit and (name in W4_SCALES or name in W4_ZEROS):
                     continue

@@ -376,11 +376,12 @@ STREAM_BLOCK_BIAS_BASE = 200000   # + 10*layer + {0 norm1_bias, 1 norm2_bias, 2 
 
 def draw_block_biases(shape: StageShape, layer: int, *, seed: int, device="cpu", std: float = 0.25,
                       dtype: torch.dtype = torch.bfloat16) -> Dict[str, torch.Tensor]:
-    """Biases ~ N(0, std) of the blocks that have them: of the two LayerNorms [hidden], of the attention's output
-    projection [hidden], and of the two matrices of an ungated MLP ([ffn] and [hidden])."""
+    """Biases ~ N(std, std) of the blocks that have them: of the two LayerNorms [hidden], of the attention's output
+    projection [hidden], and of the two matrices of an ungated MLP ([ffn] and [hidden]).  Their mean is not zero, so
+    that the rows of the residual stream they are added to get a mean of their own (which a LayerNorm removes)."""
     sizes = (("norm1_bias", shape.hidden), ("norm2_bias", shape.hidden), ("bo", shape.hidden), ("bup", shape.ffn),
              ("bdown", shape.hidden))
-    return {name: draw_normal_bf16(seed, STREAM_BLOCK_BIAS_BASE + 10 * layer + k, n, std=std, device=device,
+    return {name: draw_normal_bf16(seed, STREAM_BLOCK_BIAS_BASE + 10 * layer + k, n, std=std, mean=std, device=device,
                                    dtype=dtype)
             for k, (name, n) in enumerate(sizes)}
 

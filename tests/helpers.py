@@ -18,7 +18,7 @@ def oracle_shape(shape: synth.StageShape) -> oracle.OracleShape:
 
 def draw_layers(shape: synth.StageShape, seed: int, weight_std=None, device="cpu",
                 qkv_bias: bool = False, elem: torch.dtype = torch.bfloat16,
-                qk_norm: bool = False, alibi: bool = False, block_biases: bool = False,
+                qk_norm: bool = False, alibi=False, block_biases: bool = False,
                 shared_norm: bool = False) -> List[Dict[str, torch.Tensor]]:
     """block_biases: the norms' biases (LayerNorm shapes only), bo, bdown, and for an ungated MLP bup.
     shared_norm (parallel blocks): no second norm - both branches read the first.  An ungated MLP has no wgate."""
@@ -45,7 +45,8 @@ def draw_layers(shape: synth.StageShape, seed: int, weight_std=None, device="cpu
             w.update(synth.draw_qk_norm(shape, l, seed=seed, device=device, dtype=elem))
     if alibi:
         for w in layers:
-            w["alibi"] = synth.alibi_slopes(shape.num_q_heads).to(device)
+            slopes = synth.alibi_slopes(shape.num_q_heads).to(device)
+            w["alibi"] = slopes * 0 if alibi == "zero" else slopes
     return layers
 
 

@@ -114,9 +114,9 @@ def test_matrices_of_four_gib_and_more_are_accepted(lib):
 
 
 def test_config_struct_matches_header_size(lib):
-    # uint32 + 6 int32 + 2 float + 2 int32 (+ 4 pad) + int64 + 9 int32 (+ 4 pad)
-    assert ctypes.sizeof(S.StageConfig) == 96
-    assert ctypes.sizeof(S.StageLayerWeights) == 21 * ctypes.sizeof(ctypes.c_void_p)
+    # uint32 + 6 int32 + 2 float + 2 int32 (+ 4 pad) + int64 + 13 int32 (+ 4 pad)
+    assert ctypes.sizeof(S.StageConfig) == 112
+    assert ctypes.sizeof(S.StageLayerWeights) == 26 * ctypes.sizeof(ctypes.c_void_p)
     assert S.stage_workspace_bytes(tiny_cfg()) > 0
 
 
@@ -126,7 +126,10 @@ def test_config_struct_matches_header_size(lib):
                                  dict(rotary_dim=8), dict(rotary_dim=40), dict(rotary_dim=80),
                                  dict(weight_bits=3), dict(weight_group_size=128), dict(weight_bits=4, weight_group_size=48),
                                  dict(weight_bits=4, weight_group_size=128, ffn=768 + 64),
-                                 dict(weight_bits=4, weight_group_size=128)])   # ffn 688 is no multiple of 128
+                                 dict(weight_bits=4, weight_group_size=128),    # ffn 688 is no multiple of 128
+                                 dict(norm_kind=2), dict(mlp_kind=3), dict(mlp_kind=-1), dict(parallel_block=2),
+                                 dict(weight_bits=4, weight_group_size=128, ffn=768, mlp_kind=1),
+                                 dict(weight_bits=4, weight_group_size=128, ffn=768, parallel_block=1)])
 def test_unsupported_configs_are_rejected(lib, bad):
     with pytest.raises(StageError) as ei:
         cfg = tiny_cfg(**bad)
@@ -258,3 +261,19 @@ def test_rope_pairing_flag_is_validated(lib):
     assert S.stage_workspace_bytes(tiny_cfg(rope_interleaved=1)) == S.stage_workspace_bytes(tiny_cfg())
     with pytest.raises(S.StageError):
         S.stage_workspace_bytes(tiny_cfg(rope_interleaved=2))
+
+
+def test_block_kinds_size_the_workspace(lib):
+    """A parallel block keeps the second norm of the block's input (one more [T][H] plane), an ungated MLP its first
+    product in fp32 before bias and gelu ([T][F] floats) - and has one matrix less to copy into operand order."""
+    base = S.stage_workspace_bytes(tiny_cfg(weight_copies=1))
+    assert S.stage_workspace_bytes(tiny_cfg(weight_copies=1, norm_kind="layer")) == base
+    par = S.stage_workspace_bytes(tiny_cfg(weight_copies=1, parallel_block=1))
+    assert 128 * 256 * 2 <= par - base < 128 * 256 * 2 + 512
+    ung = S.stage_workspace_bytes(tiny_cfg(weight_copies=1, mlp_kind="gelu_tanh"))
+    assert ung - base >= 128 * 688 * 4 - 2 * 1024 * 1024        # the split-K scratch may shrink: no gate/up pair
+    wide = dict(ffn=768, max_tokens=128)
+    with_gate = S.stage_workspace_bytes(tiny_cfg(**wide)) - S.stage_workspace_bytes(tiny_cfg(weight_copies=1, **wide))
+    without = (S.stage_workspace_bytes(tiny_cfg(mlp_kind="gelu_erf", **wide))
+               - S.stage_workspace_bytes(tiny_cfg(mlp_kind="gelu_erf", weight_copies=1, **wide)))
+    assert 0 < without < with_gate

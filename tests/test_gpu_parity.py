@@ -15,15 +15,16 @@ def _shape(name, L, H_, nq, nkv, d, F, theta=1e4):
 
 
 def full_parity(shape, mb, seed, weight_std, taps=True, check_kv=True, qkv_bias=False, activation_planes=0,
-                qk_norm=False, elem=torch.bfloat16, alibi=False):
+                qk_norm=False, elem=torch.bfloat16, alibi=False, block_biases=False, shared_norm=False):
     print(f"[case] {shape.name} T={mb.num_tokens} S={mb.num_seqs} q={mb.q_lens[:6]} ctx={mb.ctx_lens[:6]} "
           f"std={weight_std} seed={seed} bias={qkv_bias} planes={activation_planes} qk_norm={qk_norm} {elem}", flush=True)
     st = H.make_stage(shape, mb, seed, weight_std, qkv_bias=qkv_bias, activation_planes=activation_planes,
-                      qk_norm=qk_norm, dtype=elem, alibi=alibi)
+                      qk_norm=qk_norm, dtype=elem, alibi=alibi, block_biases=block_biases, shared_norm=shared_norm)
     before = H.snapshot_pool(st, shape, mb) if check_kv else None
     ref, ref_slots, ref_pool, otaps = H.run_oracle(
         shape, mb, seed, weight_std, want_taps=True, elem=elem,
-        layers=draw_layers(shape, seed, weight_std, qkv_bias=qkv_bias, qk_norm=qk_norm, elem=elem, alibi=alibi))
+        layers=draw_layers(shape, seed, weight_std, qkv_bias=qkv_bias, qk_norm=qk_norm, elem=elem, alibi=alibi,
+                           block_biases=block_biases, shared_norm=shared_norm))
     out, slots = H.run_gpu(st, shape, mb, seed)
     assert slots == ref_slots                                   # bit-exact slot indexing
     stats = H.check_output(out, ref)
@@ -318,6 +319,103 @@ def test_attention_with_linear_biases(d, nq, nkv, planes, elem):
     b, _ = H.run_gpu(lin, shape, mb, 9)
     lin.close()
     assert rel_l2(b.cpu(), a.cpu()) > 10 * max(stats["rel_l2"], 1e-3)
+
+
+BLOCK_KIND_CASES = {
+    # GPT-2: LayerNorms with biases, ungated tanh-GELU MLP, biases on every projection, no rotation and no score
+    # biases (zero slopes); a mixed micro-batch of more than 64 rows
+    "gpt2": dict(shape=dict(norm_kind="layer", mlp_kind="gelu_tanh"), alibi="zero", block_biases=True, qkv_bias=True,
+                 q=[70, 33, 1, 1, 1, 1, 1], c=[0, 21, 9, 40, 77, 500, 1300]),
+    # Falcon with two norms: parallel branches, erf GELU, linear biases; decode only (the weight-streaming kernel)
+    "falcon-two-norms-decode": dict(shape=dict(norm_kind="layer", mlp_kind="gelu_erf", parallel_block=True), alibi=True,
+                                    block_biases=True, q=[1] * 24, c=[3 + 41 * i for i in range(24)]),
+    # Falcon with one norm and a rotary embedding, a long chunk, half activations
+    "falcon-one-norm-prefill": dict(shape=dict(norm_kind="layer", mlp_kind="gelu_erf", parallel_block=True),
+                                    shared_norm=True, block_biases=True, planes=3, q=[365], c=[0]),
+    # Cohere: LayerNorm without bias, one norm, parallel, gated MLP, neighbour pairing; two activation planes
+    "cohere-two-planes": dict(shape=dict(norm_kind="layer", parallel_block=True, rope_interleaved=True), shared_norm=True,
+                              planes=2, q=[61, 1, 1, 37], c=[0, 15, 700, 12]),
+    # each switch on its own
+    "parallel-only-two-planes": dict(shape=dict(parallel_block=True), planes=2, q=[40, 1, 1], c=[0, 33, 200]),
+    "parallel-only-mid": dict(shape=dict(parallel_block=True), planes=3, q=[150, 1, 1], c=[16, 33, 200]),
+    "ungated-only-f16": dict(shape=dict(mlp_kind="gelu_tanh"), elem=torch.float16, block_biases=True, q=[70, 1], c=[5, 90]),
+    "layernorm-only-decode": dict(shape=dict(norm_kind="layer"), block_biases=True, q=[1] * 9, c=[20 * i for i in range(9)]),
+    "ungated-erf-no-bias-700": dict(shape=dict(mlp_kind="gelu_erf"), planes=3, q=[700], c=[0]),
+}
+
+
+@pytest.mark.parametrize("name", list(BLOCK_KIND_CASES))
+def test_block_kinds(name):
+    """The dense blocks of the paper's model table that are not the Llama block (section 3.1.3: the GPT-2, Falcon and
+    Cohere families): LayerNorm instead of RMSNorm, the ungated GELU MLP, biases on the projections, and attention and
+    MLP branches that both start from the block's input - together as those families combine them, and one at a
+    time; whole-stage parity with taps on micro-batches on either side of 64 rows, in every activation mode."""
+    import dataclasses
+    case = BLOCK_KIND_CASES[name]
+    shape = dataclasses.replace(_shape(f"block-{name}", 2, 1024, 8, 2, 128, 2816), **case["shape"])
+    mb = synth.make_microbatch(case["q"], case["c"], seed=13, max_blocks_per_seq=90)
+    kw = dict(activation_planes=case.get("planes", 0), elem=case.get("elem", torch.bfloat16),
+              alibi=case.get("alibi", False), qkv_bias=case.get("qkv_bias", False),
+              block_biases=case.get("block_biases", False), shared_norm=case.get("shared_norm", False))
+    stats = full_parity(shape, mb, 13, "fan_in", **kw)
+    # the Llama block on the same weights gives another output: the switches were used
+    plain_shape = _shape("block-plain", 2, 1024, 8, 2, 128, 2816)
+    plain = H.make_stage(plain_shape, mb, 13, "fan_in", activation_planes=kw["activation_planes"], dtype=kw["elem"])
+    a, _ = H.run_gpu(plain, plain_shape, mb, 13)
+    plain.close()
+    other = H.make_stage(shape, mb, 13, "fan_in", activation_planes=kw["activation_planes"], dtype=kw["elem"],
+                         alibi=kw["alibi"], qkv_bias=kw["qkv_bias"], block_biases=kw["block_biases"],
+                         shared_norm=kw["shared_norm"])
+    b, _ = H.run_gpu(other, shape, mb, 13)
+    other.close()
+    assert rel_l2(b.cpu(), a.cpu()) > 10 * max(stats["rel_l2"], 1e-3)
+
+
+def test_block_kinds_in_a_deep_stage():
+    """Nine layers: the automatic activation mode of that depth (half activations, and a second plane for the q/k/v
+    projection's input when the micro-batch has prefill chunks) with a parallel LayerNorm block."""
+    import dataclasses
+    shape = dataclasses.replace(_shape("block-deep", 9, 512, 4, 2, 128, 1024), norm_kind="layer", mlp_kind="gelu_tanh",
+                                parallel_block=True)
+    mb = synth.make_microbatch([90, 1, 1], [7, 60, 300], seed=14, max_blocks_per_seq=40)
+    full_parity(shape, mb, 14, "fan_in", taps=False, block_biases=True, shared_norm=True)
+
+
+def test_block_kind_weights_are_validated():
+    import dataclasses
+    base, mb = synth.workload("tiny", seed=0)
+    from paper_2507_05043_amd.stage import Stage, make_config
+
+    def cfg_of(shape):
+        return make_config(num_layers=shape.num_layers, hidden=shape.hidden, num_q_heads=shape.num_q_heads,
+                           num_kv_heads=shape.num_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn, rms_eps=shape.rms_eps,
+                           rope_theta=shape.rope_theta, num_kv_blocks=mb.num_kv_blocks, max_tokens=mb.num_tokens,
+                           max_seqs=mb.num_seqs, max_blocks_per_seq=mb.max_blocks_per_seq, norm_kind=shape.norm_kind,
+                           mlp_kind=shape.mlp_kind, parallel_block=int(shape.parallel_block))
+
+    ungated = dataclasses.replace(base, mlp_kind="gelu_tanh")
+    layers = draw_layers(base, 0, device="cuda:0")                       # a gate matrix with an ungated MLP
+    with pytest.raises(StageError) as ei:
+        Stage(cfg_of(ungated), layers)
+    assert ei.value.code == -2
+    layers = draw_layers(ungated, 0, device="cuda:0")                    # no gate matrix with the gated MLP
+    with pytest.raises(StageError) as ei:
+        Stage(cfg_of(base), layers)
+    assert ei.value.code == -1
+    layers = draw_layers(dataclasses.replace(base, parallel_block=True), 0, device="cuda:0", shared_norm=True)
+    with pytest.raises(StageError) as ei:                                # one norm, but the branches in sequence
+        Stage(cfg_of(base), layers)
+    assert ei.value.code == -1
+    layers = draw_layers(dataclasses.replace(base, norm_kind="layer"), 0, device="cuda:0", block_biases=True)
+    with pytest.raises(StageError) as ei:                                # norm biases with RMSNorms
+        Stage(cfg_of(base), layers)
+    assert ei.value.code == -2
+    layers = draw_layers(ungated, 0, device="cuda:0", block_biases=True)
+    for w in layers:
+        w["wgate"] = draw_layers(base, 0, device="cuda:0")[0]["wgate"]
+    with pytest.raises(StageError) as ei:                                # a bias of the ungated MLP with the gated one
+        Stage(cfg_of(base), layers)
+    assert ei.value.code == -2
 
 
 def test_linear_biases_exclude_the_rotation_settings():
