@@ -55,13 +55,16 @@ __device__ __forceinline__ void sched_step() {
   }
 }
 
-__device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
+// z * sigmoid(z); the reciprocal is the hardware's (one ulp), not the IEEE division sequence: the result is rounded
+// to 16 bits right after, and the division would be ten vector instructions per output in a tile's epilogue.
+__device__ __forceinline__ float silu_f(float z) { return z * __builtin_amdgcn_rcpf(1.0f + __expf(-z)); }
 
 // Epilogue of a wave's MT x NT block of 32x32 accumulator tiles whose first row / column are m_base / n_base.
 // Accumulator register r of lane l is C[row 8*(r/4) + 4*(l/32) + r%4][col l%32] of its tile.
-template <int EPI, bool SPLIT, int MT, int NT>
-__device__ __forceinline__ void tile_epilogue(const GemmArgs& p, f32x16 (&acc)[MT][NT], int m_base, int n_base, int nv,
-                                              int split, int lane) {
+// CHECKED = false: the whole block lies inside the output (no per-element bounds tests).
+template <int EPI, bool SPLIT, int MT, int NT, bool CHECKED>
+__device__ __forceinline__ void tile_epilogue_body(const GemmArgs& p, f32x16 (&acc)[MT][NT], int m_base, int n_base,
+                                                   int nv, int split, int lane) {
   const int col_in_tile = lane & 31;
   const int row_base = (lane >> 5) * 4;
 #pragma unroll
@@ -69,19 +72,19 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs& p, f32x16 (&acc)[M
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int m = m_base + i * 32 + 8 * (r / 4) + row_base + (r % 4);
-      if (m >= p.m) continue;
+      if (CHECKED && m >= p.m) continue;
       if constexpr (SPLIT) {
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
           const int v = n_base + j * 32 + col_in_tile;
-          if (v < nv) p.partial[((size_t)split * p.m + m) * nv + v] = acc[i][j][r];
+          if (!CHECKED || v < nv) p.partial[((size_t)split * p.m + m) * nv + v] = acc[i][j][r];
         }
       } else if constexpr (EPI == kEpiSwiGLU) {
 #pragma unroll
         for (int j = 0; j < NT; j += 2) {
           const int v = n_base + j * 32 + col_in_tile;   // gate column; its up column is 32 further
           const int f = (v >> 6) * 32 + (v & 31);
-          if (f < p.n) {
+          if (!CHECKED || f < p.n) {
             const float val = silu_f(acc[i][j][r]) * acc[i][j + 1][r];
             const e16 hi = f32_to_act(val, p.out_half);
             p.out_e16[(size_t)m * p.ldo + f] = hi;
@@ -92,7 +95,7 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs& p, f32x16 (&acc)[M
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
           const int n = n_base + j * 32 + col_in_tile;
-          if (n >= p.n) continue;
+          if (CHECKED && n >= p.n) continue;
           const float c = acc[i][j][r];
           if constexpr (EPI == kEpiStoreF32) {
             p.out_f32[(size_t)m * p.ldo + n] = c;
@@ -105,6 +108,25 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs& p, f32x16 (&acc)[M
       }
     }
   }
+}
+
+template <int EPI, bool SPLIT, int MT, int NT>
+__device__ __forceinline__ void tile_epilogue(const GemmArgs& p, f32x16 (&acc)[MT][NT], int m_base, int n_base, int nv,
+                                              int split, int lane) {
+  // a block is interior when its last row and its last column exist (wave-uniform): partial sums live in the nv
+  // columns the kernel iterates, outputs in p.n columns (for SwiGLU: features, two 32-wide column tiles each 32)
+  const bool rows_in = m_base + MT * 32 <= p.m;
+  bool cols_in = n_base + NT * 32 <= nv;
+  if constexpr (!SPLIT && EPI == kEpiSwiGLU) {
+    const int v_last = n_base + NT * 32 - 1;             // an up column; its feature index is the block's largest
+    cols_in = ((v_last >> 6) * 32 + (v_last & 31)) < p.n;
+  } else if constexpr (!SPLIT) {
+    cols_in = n_base + NT * 32 <= p.n;
+  }
+  if (rows_in && cols_in)
+    tile_epilogue_body<EPI, SPLIT, MT, NT, false>(p, acc, m_base, n_base, nv, split, lane);
+  else
+    tile_epilogue_body<EPI, SPLIT, MT, NT, true>(p, acc, m_base, n_base, nv, split, lane);
 }
 
 // Workgroup of 4 waves (2 x 2); wave tile (BM/2) x (BN/2) made of 32x32 MFMA tiles; K tile of 64.
