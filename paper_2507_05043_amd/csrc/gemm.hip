@@ -62,7 +62,10 @@ __device__ __forceinline__ float silu_f(float z) { return z * __builtin_amdgcn_r
 // Epilogue of a wave's MT x NT block of 32x32 accumulator tiles whose first row / column are m_base / n_base.
 // Accumulator register r of lane l is C[row 8*(r/4) + 4*(l/32) + r%4][col l%32] of its tile.
 // CHECKED = false: the whole block lies inside the output (no per-element bounds tests).
-template <int EPI, bool SPLIT, int MT, int NT, bool CHECKED>
+// OUT: how the SwiGLU epilogue stores - kOutByFlags: by p.out_half / p.out_lo, tested per element; kOutHalf: IEEE
+// half bits, one plane; kOutOnePlane: the element type, one plane (the two cases that matter, decided once per block).
+enum { kOutByFlags = 0, kOutHalf = 1, kOutOnePlane = 2 };
+template <int EPI, bool SPLIT, int MT, int NT, bool CHECKED, int OUT = kOutByFlags>
 __device__ __forceinline__ void tile_epilogue_body(const GemmArgs& p, f32x16 (&acc)[MT][NT], int m_base, int n_base,
                                                    int nv, int split, int lane) {
   const int col_in_tile = lane & 31;
@@ -86,9 +89,13 @@ __device__ __forceinline__ void tile_epilogue_body(const GemmArgs& p, f32x16 (&a
           const int f = (v >> 6) * 32 + (v & 31);
           if (!CHECKED || f < p.n) {
             const float val = silu_f(acc[i][j][r]) * acc[i][j + 1][r];
-            const e16 hi = f32_to_act(val, p.out_half);
-            p.out_e16[(size_t)m * p.ldo + f] = hi;
-            if (p.out_lo) p.out_lo[(size_t)m * p.ldo + f] = f32_to_e16(val - e16_to_f32(hi));
+            if constexpr (OUT == kOutByFlags) {
+              const e16 hi = f32_to_act(val, p.out_half);
+              p.out_e16[(size_t)m * p.ldo + f] = hi;
+              if (p.out_lo) p.out_lo[(size_t)m * p.ldo + f] = f32_to_e16(val - e16_to_f32(hi));
+            } else {
+              p.out_e16[(size_t)m * p.ldo + f] = f32_to_act(val, OUT == kOutHalf);
+            }
           }
         }
       } else {
@@ -123,9 +130,15 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs& p, f32x16 (&acc)[M
   } else if constexpr (!SPLIT) {
     cols_in = n_base + NT * 32 <= p.n;
   }
-  if (rows_in && cols_in)
-    tile_epilogue_body<EPI, SPLIT, MT, NT, false>(p, acc, m_base, n_base, nv, split, lane);
-  else
+  if (rows_in && cols_in) {
+    if constexpr (!SPLIT && EPI == kEpiSwiGLU) {
+      if (p.out_lo) tile_epilogue_body<EPI, SPLIT, MT, NT, false>(p, acc, m_base, n_base, nv, split, lane);
+      else if (p.out_half) tile_epilogue_body<EPI, SPLIT, MT, NT, false, kOutHalf>(p, acc, m_base, n_base, nv, split, lane);
+      else tile_epilogue_body<EPI, SPLIT, MT, NT, false, kOutOnePlane>(p, acc, m_base, n_base, nv, split, lane);
+    } else {
+      tile_epilogue_body<EPI, SPLIT, MT, NT, false>(p, acc, m_base, n_base, nv, split, lane);
+    }
+  } else
     tile_epilogue_body<EPI, SPLIT, MT, NT, true>(p, acc, m_base, n_base, nv, split, lane);
 }
 
