@@ -109,7 +109,7 @@ def run_workload(args, workload, budget, steps, warmup, extras):
     want_ends = extras and args.ends
     st = make_stage(shape, mb, args.seed, alias_layers=alias, vocab_size=shape.vocab if want_ends else 0,
                     qkv_bias=workload == "qwen2-7b",     # the Qwen2 family has a q/k/v bias
-                    weight_group_size=128 if w4 else 0, dtype=elem)
+                    weight_group_size=128 if w4 else 0, dtype=elem, pool_first=not args.weights_first)
     hidden = synth.draw_hidden(shape, mb.num_tokens, seed=args.seed, device="cuda:0", dtype=elem)
     out = torch.empty_like(hidden)
     n_dec = sum(1 for q in mb.q_lens if q == 1)
@@ -172,7 +172,8 @@ def run_workload(args, workload, budget, steps, warmup, extras):
                                f"S={mb.num_seqs} ({mb.num_seqs - n_dec} prefill chunks, {n_dec} decode tokens), KV block 16",
                    "seed": args.seed, "kv_layers_aliased": bool(alias), "projection_inputs": inputs,
                    "weights": f"4-bit codes, {args.dtype} scale and zero point per 128 input features" if w4 else args.dtype,
-                   "weight_copies": copies},
+                   "weight_copies": copies,
+                   "allocation_order": "weights, then KV pool" if args.weights_first else "KV pool, then weights"},
         "stage_latency_ms": round(ms_per_step, 4),
         "ideal_ms": {"hbm": round(work["bytes_per_call"] / (HBM_PEAK_GBS * 1e9) * 1e3, 4),
                      "mfma": round(work["flops_per_call"] / (MFMA_BF16_PEAK_TFLOPS * 1e12) * 1e3, 4)},
@@ -238,6 +239,9 @@ def main():
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "f16"],
                     help="f16: the IEEE-half library (a variant, not the benchmark configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--weights-first", action="store_true",
+                    help="allocate the weights before the KV pool (default: the pool first, as an engine that reserves "
+                         "its cache when it starts; the decode kernel's stream is 2-5 %% faster over a pool mapped first)")
     ap.add_argument("--no-per-config", action="store_true", help="headline workload only")
     ap.add_argument("--ends", action="store_true",
                     help="also time the pipeline's two ends (embedding; final norm + output head + greedy choice)")

@@ -14,7 +14,7 @@ def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_
                device: str = "cuda:0", activation_planes: int = 0, vocab_size: int = 0,
                qkv_bias: bool = False, weight_group_size: int = 0, dtype: torch.dtype = torch.bfloat16,
                qk_norm: bool = False, weight_copies: int = 0, alibi=False, block_biases: bool = False,
-               shared_norm: bool = False) -> Stage:
+               shared_norm: bool = False, pool_first: bool = False) -> Stage:
     """Draw the stage's weights on the device, size the pool and workspace for `mb`, fill the cache.
     weight_group_size > 0: 4-bit group-quantised projection weights with that group size.
     dtype: the 16-bit element type (bfloat16, or float16 for the half-precision library).
@@ -24,7 +24,23 @@ def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_
     positions) instead of the rotary embedding.
     block_biases: the biases the shape's block kind can carry (of its LayerNorms, of the output and down projections,
     of an ungated MLP's first matrix).  shared_norm: a parallel block whose two branches read one norm.
-    The block's kind itself (norm_kind, mlp_kind, parallel_block) comes with the shape."""
+    The block's kind itself (norm_kind, mlp_kind, parallel_block) comes with the shape.
+    pool_first: allocate the KV pool before the weights are drawn (an engine reserves its cache when it starts)."""
+    cfg = make_config(num_layers=shape.num_layers, hidden=shape.hidden, num_q_heads=shape.num_q_heads,
+                      num_kv_heads=shape.num_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn,
+                      rms_eps=shape.rms_eps, rope_theta=shape.rope_theta, num_kv_blocks=mb.num_kv_blocks,
+                      max_tokens=max_tokens or mb.num_tokens, max_seqs=mb.num_seqs,
+                      max_blocks_per_seq=mb.max_blocks_per_seq,
+                      kv_layer_stride_bytes=0 if alias_layers else None, activation_planes=activation_planes,
+                      vocab_size=vocab_size, weight_bits=4 if weight_group_size else 0,
+                      weight_group_size=weight_group_size, rotary_dim=shape.rotary_dim, weight_copies=weight_copies,
+                      rope_interleaved=int(shape.rope_interleaved), norm_kind=shape.norm_kind, mlp_kind=shape.mlp_kind,
+                      parallel_block=int(shape.parallel_block))
+    kv_pool = None
+    if pool_first:
+        from .stage import stage_kv_layer_bytes
+        pool_bytes = (cfg.num_layers - 1) * cfg.kv_layer_stride_bytes + stage_kv_layer_bytes(cfg)
+        kv_pool = torch.empty(pool_bytes, dtype=torch.uint8, device=device)
     if weight_group_size:
         layers = [synth.draw_w4_layer(shape, l, seed=seed, group=weight_group_size, device=device,
                                       weight_std=0.02 if weight_std is None else float(weight_std), dtype=dtype)
@@ -55,17 +71,7 @@ def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_
         if shared_norm:
             del w["norm2"]
             w.pop("norm2_bias", None)
-    cfg = make_config(num_layers=shape.num_layers, hidden=shape.hidden, num_q_heads=shape.num_q_heads,
-                      num_kv_heads=shape.num_kv_heads, head_dim=shape.head_dim, ffn=shape.ffn,
-                      rms_eps=shape.rms_eps, rope_theta=shape.rope_theta, num_kv_blocks=mb.num_kv_blocks,
-                      max_tokens=max_tokens or mb.num_tokens, max_seqs=mb.num_seqs,
-                      max_blocks_per_seq=mb.max_blocks_per_seq,
-                      kv_layer_stride_bytes=0 if alias_layers else None, activation_planes=activation_planes,
-                      vocab_size=vocab_size, weight_bits=4 if weight_group_size else 0,
-                      weight_group_size=weight_group_size, rotary_dim=shape.rotary_dim, weight_copies=weight_copies,
-                      rope_interleaved=int(shape.rope_interleaved), norm_kind=shape.norm_kind, mlp_kind=shape.mlp_kind,
-                      parallel_block=int(shape.parallel_block))
-    st = Stage(cfg, layers, device=device, dtype=dtype)
+    st = Stage(cfg, layers, device=device, dtype=dtype, kv_pool=kv_pool)
     if fill_kv:
         fill_pool(st, shape, mb, seed)
     return st
