@@ -24,7 +24,9 @@ gather against direct indexing of hand-written tables; an identity-like head
 whose logits are the normalised activations themselves; invariance of the
 logits under positive scaling of the hidden rows (up to eps); permutation of
 vocabulary rows permutes logits; rows other than each sequence's last have no
-influence; ties resolve to the smallest index.  The paper prints no numeric
+influence; ties resolve to the smallest index; the LayerNorm head against the
+library's layer_norm followed by a matmul, scalar loops, and invariance to a
+shift of the hidden rows.  The paper prints no numeric
 values for this path: parity against printed values is unpinned; parity is
 against the definition.
 """
@@ -62,14 +64,26 @@ def last_rows(q_lens: Sequence[int]) -> list:
 
 
 def head_logits(hidden: torch.Tensor, q_lens: Sequence[int], gain: torch.Tensor, w_vocab: torch.Tensor,
-                eps: float, dtype=torch.float64) -> torch.Tensor:
-    """logits[s] = RMSNorm(hidden[last row of s]; gain, eps) @ w_vocab^T.  Returns [S, vocab]."""
+                eps: float, dtype=torch.float64, norm_kind: str = "rms", bias: torch.Tensor = None) -> torch.Tensor:
+    """logits[s] = norm(hidden[last row of s]) @ w_vocab^T.  Returns [S, vocab].
+
+    norm_kind "rms": x * gain / sqrt(mean(x^2) + eps).  "layer" (the families whose blocks use LayerNorms end with
+    one too): (x - mean) / sqrt(mean((x - mean)^2) + eps) * gain (+ bias)."""
     idx = last_rows(q_lens)
     if sum(int(q) for q in q_lens) != hidden.shape[0]:
         raise ValueError("q_lens do not add up to the number of rows")
     x = hidden.to(dtype)[idx]                                        # [S, hidden]
-    ms = (x * x).mean(dim=-1, keepdim=True)
-    xn = x * gain.to(dtype) / torch.sqrt(ms + eps)
+    if norm_kind == "layer":
+        dev = x - x.mean(dim=-1, keepdim=True)
+        var = (dev * dev).mean(dim=-1, keepdim=True)
+        xn = dev / torch.sqrt(var + eps) * gain.to(dtype)
+        if bias is not None:
+            xn = xn + bias.to(dtype)
+    else:
+        if norm_kind != "rms" or bias is not None:
+            raise ValueError("an RMSNorm head has no bias")
+        ms = (x * x).mean(dim=-1, keepdim=True)
+        xn = x * gain.to(dtype) / torch.sqrt(ms + eps)
     return xn @ w_vocab.to(dtype).T
 
 

@@ -133,3 +133,47 @@ def test_an_embedded_token_is_chosen_again_by_a_tied_head():
     hidden = oracle.embed_tokens(table, ids)
     logits = oracle.head_logits(hidden, [1, 1, 1], torch.ones(6), table, 1e-6)
     assert oracle.greedy_tokens(logits).tolist() == ids
+
+
+# ---------------------------------------------------------------- the LayerNorm head
+
+def _brute_layernorm_logits(hidden, q_lens, gain, bias, w, eps):
+    """Scalar loops; the variance by the two-moment formula (the tensor code sums squared deviations)."""
+    out = []
+    start = 0
+    for q in q_lens:
+        row = [float(v) for v in hidden[start + q - 1]]
+        start += q
+        h = len(row)
+        mean = sum(row) / h
+        var = sum(v * v for v in row) / h - mean * mean
+        r = 1.0 / math.sqrt(var + eps)
+        xn = [(row[k] - mean) * r * float(gain[k]) + (float(bias[k]) if bias is not None else 0.0) for k in range(h)]
+        out.append([sum(xn[k] * float(w[v][k]) for k in range(h)) for v in range(len(w))])
+    return torch.tensor(out, dtype=torch.float64)
+
+
+@pytest.mark.parametrize("with_bias", [False, True])
+def test_layernorm_head_equals_scalar_loops_and_the_library(with_bias):
+    q_lens = [2, 1, 4]
+    hidden = _rand((7, 12), 3) + 0.75                    # rows with a mean of their own
+    gain = 1.0 + _rand((12,), 13, 0.1)
+    bias = _rand((12,), 23, 0.3) if with_bias else None
+    w = _rand((9, 12), 33)
+    got = oracle.head_logits(hidden, q_lens, gain, w, 1e-5, norm_kind="layer", bias=bias)
+    want = _brute_layernorm_logits(hidden.tolist(), q_lens, gain.tolist(), None if bias is None else bias.tolist(),
+                                   w.tolist(), 1e-5)
+    assert torch.allclose(got, want, rtol=1e-10, atol=1e-11)
+    rows = hidden.double()[oracle.last_rows(q_lens)]
+    lib = torch.nn.functional.layer_norm(rows, (12,), gain.double(), None if bias is None else bias.double(), 1e-5)
+    assert torch.allclose(got, lib @ w.double().T, rtol=1e-12, atol=1e-12)
+    # a shift of the hidden rows changes nothing; an RMSNorm head would change
+    shifted = oracle.head_logits(hidden + 3.0, q_lens, gain, w, 1e-5, norm_kind="layer", bias=bias)
+    assert torch.allclose(shifted, got, rtol=1e-9, atol=1e-10)
+    rms = oracle.head_logits(hidden, q_lens, gain, w, 1e-5)
+    assert not torch.allclose(rms, got, rtol=1e-2)
+
+
+def test_an_rmsnorm_head_takes_no_bias():
+    with pytest.raises(ValueError):
+        oracle.head_logits(_rand((2, 8), 1), [2], torch.ones(8), _rand((4, 8), 2), 1e-5, bias=torch.zeros(8))
