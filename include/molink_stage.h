@@ -346,14 +346,24 @@ int stage_forward_taps(stage_handle *st, void *hip_stream, int32_t num_tokens, c
  *   logits_out   device f32 [S][vocab], or NULL when only the tokens are wanted
  *   next_tokens  device int32 [S]
  * Asynchronous on hip_stream like stage_forward, shares the handle's workspace with it (same ordering
- * rule).  Errors: STAGE_ERR_NULL, STAGE_ERR_CONFIG (vocab mismatch; a stage whose blocks use LayerNorms,
- * norm_kind 1: the head's norm is an RMSNorm only), STAGE_ERR_BATCH, STAGE_ERR_HIP.
+ * rule).  Errors: STAGE_ERR_NULL, STAGE_ERR_CONFIG (vocab mismatch; the wrong head for the stage's norm_kind),
+ * STAGE_ERR_BATCH, STAGE_ERR_HIP.
+ *
+ * stage_head_layernorm: the same for a stage whose blocks use LayerNorms (norm_kind 1; the GPT-2, Falcon and Cohere
+ * families end with a LayerNorm too):
+ *   logits[s] = LayerNorm(hidden[r(s)]; final_norm, final_norm_bias, rms_eps) * lm_head^T
+ *   final_norm_bias  device bf16 [H], or NULL for a LayerNorm without bias
+ * stage_head serves stages with norm_kind 0 only, stage_head_layernorm stages with norm_kind 1 only.
  */
 int stage_embed(stage_handle *st, void *hip_stream, const void *table, int32_t vocab, int32_t num_tokens,
                 const int32_t *token_ids, void *hidden_out);
 int stage_head(stage_handle *st, void *hip_stream, int32_t num_tokens, const void *hidden, int32_t num_seqs,
                const int32_t *q_lens, const void *final_norm, const void *lm_head, int32_t vocab,
                void *logits_out, int32_t *next_tokens);
+int stage_head_layernorm(stage_handle *st, void *hip_stream, int32_t num_tokens, const void *hidden,
+                         int32_t num_seqs, const int32_t *q_lens, const void *final_norm,
+                         const void *final_norm_bias, const void *lm_head, int32_t vocab, void *logits_out,
+                         int32_t *next_tokens);
 
 /*
  * Start-up profiling (paper section 4.1: every engine times its own stage over a grid of batch sizes and

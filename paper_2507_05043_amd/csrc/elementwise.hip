@@ -306,27 +306,47 @@ __global__ __launch_bounds__(256) void embed_gather_kernel(const e16* __restrict
 }
 
 __global__ __launch_bounds__(256) void gather_rmsnorm_kernel(const e16* __restrict__ in, const int32_t* __restrict__ rows,
-                                                             const e16* __restrict__ gain, e16* __restrict__ out,
-                                                             int hidden, float eps) {
+                                                             NormSpec ns, e16* __restrict__ out, int hidden) {
   __shared__ float wsum[4];
+  __shared__ float wmean[4];
   const int s = blockIdx.x, tid = threadIdx.x;
   const e16* src = in + (size_t)rows[s] * hidden;
+  float mean = 0.f;
+  if (ns.layer) {                       // LayerNorm: the mean first, then the squared deviations from it
+    float sum = 0.f;
+    for (int c = tid * 8; c < hidden; c += 256 * 8) {
+      const e16x8 v = load8(src + c);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sum += e16_to_f32(v[e]);
+    }
+    sum = wave_sum(sum);
+    if ((tid & 63) == 0) wmean[tid >> 6] = sum;
+    __syncthreads();
+    mean = ((wmean[0] + wmean[1]) + (wmean[2] + wmean[3])) / (float)hidden;
+  }
   float ss = 0.f;
   for (int c = tid * 8; c < hidden; c += 256 * 8) {
     const e16x8 v = load8(src + c);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { const float f = e16_to_f32(v[e]); ss += f * f; }
+    for (int e = 0; e < 8; ++e) { const float f = e16_to_f32(v[e]) - mean; ss += f * f; }
   }
   ss = wave_sum(ss);
   if ((tid & 63) == 0) wsum[tid >> 6] = ss;
   __syncthreads();
   const float tot = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
-  const float rs = 1.0f / sqrtf(tot / (float)hidden + eps);
+  const float rs = 1.0f / sqrtf(tot / (float)hidden + ns.eps);
   for (int c = tid * 8; c < hidden; c += 256 * 8) {
-    const e16x8 v = load8(src + c), g = load8(gain + c);
+    const e16x8 v = load8(src + c), g = load8(ns.gain + c);
     e16x8 o;
+    if (ns.bias) {
+      const e16x8 b = load8(ns.bias + c);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = f32_to_e16(e16_to_f32(v[e]) * rs * e16_to_f32(g[e]));
+      for (int e = 0; e < 8; ++e)
+        o[e] = f32_to_e16((e16_to_f32(v[e]) - mean) * rs * e16_to_f32(g[e]) + e16_to_f32(b[e]));
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = f32_to_e16((e16_to_f32(v[e]) - mean) * rs * e16_to_f32(g[e]));
+    }
     store8(out + (size_t)s * hidden + c, o);
   }
 }
@@ -375,9 +395,9 @@ hipError_t launch_embed_gather(const e16* table, const int32_t* ids, e16* out, i
   return hipGetLastError();
 }
 
-hipError_t launch_gather_rmsnorm(const e16* in, const int32_t* rows, const e16* gain, e16* out, int n_rows,
-                                 int hidden, float eps, hipStream_t stream) {
-  hipLaunchKernelGGL(gather_rmsnorm_kernel, dim3(n_rows), dim3(256), 0, stream, in, rows, gain, out, hidden, eps);
+hipError_t launch_gather_rmsnorm(const e16* in, const int32_t* rows, const NormSpec& norm, e16* out, int n_rows,
+                                 int hidden, hipStream_t stream) {
+  hipLaunchKernelGGL(gather_rmsnorm_kernel, dim3(n_rows), dim3(256), 0, stream, in, rows, norm, out, hidden);
   return hipGetLastError();
 }
 

@@ -56,9 +56,9 @@ hipError_t launch_rope_append(const RopeAppendArgs& args, hipStream_t stream);
 hipError_t launch_embed_gather(const e16* table, const int32_t* ids, e16* out, int rows, int hidden,
                                hipStream_t stream);
 
-// out[s][:] = e16(RMSNorm(in[rows[s]][:]; gain, eps)), norm in fp32
-hipError_t launch_gather_rmsnorm(const e16* in, const int32_t* rows, const e16* gain, e16* out, int n_rows,
-                                 int hidden, float eps, hipStream_t stream);
+// out[s][:] = e16(norm(in[rows[s]][:])), the norm (RMSNorm, or LayerNorm with optional bias) in fp32
+hipError_t launch_gather_rmsnorm(const e16* in, const int32_t* rows, const NormSpec& norm, e16* out, int n_rows,
+                                 int hidden, hipStream_t stream);
 
 // Per row: logits = sum over `planes` of src[plane][row][:] (in plane order), optionally stored, and the
 // index of their maximum (the smallest index among equals) written to tokens[row].

@@ -1133,14 +1133,11 @@ int stage_embed(stage_handle* st, void* hip_stream, const void* table, int32_t v
   return STAGE_OK;
 }
 
-int stage_head(stage_handle* st, void* hip_stream, int32_t num_tokens, const void* hidden, int32_t num_seqs,
-               const int32_t* q_lens, const void* final_norm, const void* lm_head, int32_t vocab, void* logits_out,
-               int32_t* next_tokens) {
-  if (!st) return fail(STAGE_ERR_NULL, "stage handle is NULL");
-  if (st && st->cfg.norm_kind != 0)
-    return fail(STAGE_ERR_CONFIG, "stage_head normalises with an RMSNorm; this stage's blocks use LayerNorms (norm_kind 1)");
+static int head_impl(stage_handle* st, void* hip_stream, int32_t num_tokens, const void* hidden, int32_t num_seqs,
+              const int32_t* q_lens, const void* final_norm, const void* final_norm_bias, const void* lm_head,
+              int32_t vocab, void* logits_out, int32_t* next_tokens) {
   if (!hidden || !q_lens || !final_norm || !lm_head || !next_tokens)
-    return fail(STAGE_ERR_NULL, "a required argument of stage_head is NULL");
+    return fail(STAGE_ERR_NULL, "a required argument of the output head is NULL");
   const stage_config& c = st->cfg;
   const Dims& d = st->dim;
   if (c.vocab_size == 0 || vocab != c.vocab_size)
@@ -1169,8 +1166,9 @@ int stage_head(stage_handle* st, void* hip_stream, int32_t num_tokens, const voi
   e16* head_a = (e16*)(ws + st->ws.head_a);
   {
     Timer t(st, stream, STAGE_K_HEAD_NORM);
-    HIP_TRY(launch_gather_rmsnorm((const e16*)hidden, d_rows, (const e16*)final_norm, head_a, num_seqs, d.H,
-                                  c.rms_eps, stream));
+    HIP_TRY(launch_gather_rmsnorm((const e16*)hidden, d_rows,
+                                  NormSpec{(const e16*)final_norm, (const e16*)final_norm_bias, c.rms_eps, c.norm_kind},
+                                  head_a, num_seqs, d.H, stream));
   }
   GemmArgs g{};
   g.a = head_a; g.w0 = (const e16*)lm_head; g.partial = (float*)(ws + st->ws.splitk);
@@ -1190,6 +1188,30 @@ int stage_head(stage_handle* st, void* hip_stream, int32_t num_tokens, const voi
     HIP_TRY(launch_argmax_rows(direct, 1, 0, num_seqs, vocab, nullptr, next_tokens, stream));
   return STAGE_OK;
 }
+
+int stage_head(stage_handle* st, void* hip_stream, int32_t num_tokens, const void* hidden, int32_t num_seqs,
+               const int32_t* q_lens, const void* final_norm, const void* lm_head, int32_t vocab, void* logits_out,
+               int32_t* next_tokens) {
+  if (!st) return fail(STAGE_ERR_NULL, "stage handle is NULL");
+  if (st->cfg.norm_kind != 0)
+    return fail(STAGE_ERR_CONFIG, "stage_head normalises with an RMSNorm; this stage's blocks use LayerNorms (norm_kind 1): "
+                                  "call stage_head_layernorm");
+  return head_impl(st, hip_stream, num_tokens, hidden, num_seqs, q_lens, final_norm, nullptr, lm_head, vocab, logits_out,
+                   next_tokens);
+}
+
+int stage_head_layernorm(stage_handle* st, void* hip_stream, int32_t num_tokens, const void* hidden, int32_t num_seqs,
+                         const int32_t* q_lens, const void* final_norm, const void* final_norm_bias, const void* lm_head,
+                         int32_t vocab, void* logits_out, int32_t* next_tokens) {
+  if (!st) return fail(STAGE_ERR_NULL, "stage handle is NULL");
+  if (st->cfg.norm_kind != 1)
+    return fail(STAGE_ERR_CONFIG, "stage_head_layernorm belongs to stages whose blocks use LayerNorms (norm_kind 1): "
+                                  "call stage_head");
+  if ((uintptr_t)final_norm_bias % 16) return fail(STAGE_ERR_CONFIG, "final_norm_bias is not 16-byte aligned");
+  return head_impl(st, hip_stream, num_tokens, hidden, num_seqs, q_lens, final_norm, final_norm_bias, lm_head, vocab,
+                   logits_out, next_tokens);
+}
+
 
 int stage_profile_enable(stage_handle* st, uint32_t kernel_mask) {
   if (!st) return fail(STAGE_ERR_NULL, "stage handle is NULL");

@@ -100,6 +100,9 @@ def load_library(dtype: torch.dtype = torch.bfloat16) -> ctypes.CDLL:
                                 ctypes.c_void_p]
     lib.stage_head.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, i32p,
                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+    lib.stage_head_layernorm.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32,
+                                         i32p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
+                                         ctypes.c_void_p, ctypes.c_void_p]
     lib.stage_profile.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int32] * 5 + [
         ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double)]
     lib.stage_profile_enable.argtypes = [ctypes.c_void_p, ctypes.c_uint32]
@@ -111,7 +114,7 @@ def load_library(dtype: torch.dtype = torch.bfloat16) -> ctypes.CDLL:
     lib.stage_last_error.restype = ctypes.c_char_p
     for name in ("stage_kv_layer_bytes", "stage_kv_element_offset", "stage_check_batch", "stage_workspace_bytes",
                  "stage_init", "stage_forward", "stage_forward_static", "stage_forward_taps", "stage_profile", "stage_profile_enable",
-                 "stage_profile_read", "stage_embed", "stage_head"):
+                 "stage_profile_read", "stage_embed", "stage_head", "stage_head_layernorm"):
         getattr(lib, name).restype = ctypes.c_int
     lib.stage_elem_type.restype = ctypes.c_int32
     if lib.stage_elem_type() != ELEM_TYPES[dtype]:
@@ -342,8 +345,9 @@ class Stage:
         return out
 
     def head(self, hidden: torch.Tensor, q_lens, final_norm: torch.Tensor, lm_head: torch.Tensor, *,
-             want_logits: bool = True):
-        """(next_tokens int32 [S], logits f32 [S, vocab] or None) for the last row of every sequence."""
+             want_logits: bool = True, final_norm_bias: Optional[torch.Tensor] = None):
+        """(next_tokens int32 [S], logits f32 [S, vocab] or None) for the last row of every sequence.
+        A stage whose blocks use LayerNorms ends with one (stage_head_layernorm; final_norm_bias optional)."""
         c = self.cfg
         if hidden.dtype != self.dtype or not hidden.is_contiguous() or hidden.shape[1] != c.hidden:
             raise ValueError("hidden must be a contiguous 16-bit [T, hidden] tensor")
@@ -358,9 +362,18 @@ class Stage:
         logits = torch.empty(s, vocab, dtype=torch.float32, device=self.device) if want_logits else None
         tokens = torch.empty(s, dtype=torch.int32, device=self.device)
         stream = torch.cuda.current_stream(self.device).cuda_stream
-        self._check(self._lib.stage_head(self._handle, ctypes.c_void_p(stream), hidden.shape[0], hidden.data_ptr(), s, q_p,
-                                         final_norm.data_ptr(), lm_head.data_ptr(), vocab,
-                                         logits.data_ptr() if want_logits else None, tokens.data_ptr()))
+        if c.norm_kind == 0 and final_norm_bias is None:
+            self._check(self._lib.stage_head(self._handle, ctypes.c_void_p(stream), hidden.shape[0], hidden.data_ptr(), s,
+                                             q_p, final_norm.data_ptr(), lm_head.data_ptr(), vocab,
+                                             logits.data_ptr() if want_logits else None, tokens.data_ptr()))
+        else:
+            if final_norm_bias is not None and (final_norm_bias.dtype != self.dtype or not final_norm_bias.is_contiguous()
+                                                or final_norm_bias.numel() != c.hidden):
+                raise ValueError("final_norm_bias must be a contiguous 16-bit [hidden] tensor")
+            self._check(self._lib.stage_head_layernorm(
+                self._handle, ctypes.c_void_p(stream), hidden.shape[0], hidden.data_ptr(), s, q_p, final_norm.data_ptr(),
+                final_norm_bias.data_ptr() if final_norm_bias is not None else None, lm_head.data_ptr(), vocab,
+                logits.data_ptr() if want_logits else None, tokens.data_ptr()))
         return tokens, logits
 
     # ---- per-kernel timing

@@ -50,21 +50,26 @@ def _check_tokens(tokens, gpu_logits, ref_logits, what):
     return int(clear.sum())
 
 
-def _head_case(shape, num_seqs, seed, sample=None, head_std=0.02):
+def _head_case(shape, num_seqs, seed, sample=None, head_std=0.02, norm_bias=False):
+    """shape.norm_kind "layer": the LayerNorm head (stage_head_layernorm), with a bias if norm_bias; the hidden rows
+    then get a mean of their own."""
+    layer = shape.norm_kind == "layer"
     q_lens = _q_lens(num_seqs, seed)
     t = sum(q_lens)
     print(f"[case] head {shape.name} S={num_seqs} T={t} vocab={shape.vocab} seed={seed}", flush=True)
     st = _head_stage(shape, num_seqs, t, seed)
     ends = synth.draw_ends_weights(shape, seed=seed, device="cuda:0", head_std=head_std)
-    hidden = (synth.draw_hidden(shape, t, seed=seed, device="cuda:0").float() * 3.0).to(torch.bfloat16)
-    tokens, logits = st.head(hidden, q_lens, ends["final_norm"], ends["lm_head"])
-    tokens2, none = st.head(hidden, q_lens, ends["final_norm"], ends["lm_head"], want_logits=False)
+    hidden = (synth.draw_hidden(shape, t, seed=seed, device="cuda:0").float() * 3.0 + (2.0 if layer else 0.0)).to(torch.bfloat16)
+    bias = synth.draw_block_biases(shape, 0, seed=seed, device="cuda:0")["norm1_bias"] if norm_bias else None
+    tokens, logits = st.head(hidden, q_lens, ends["final_norm"], ends["lm_head"], final_norm_bias=bias)
+    tokens2, none = st.head(hidden, q_lens, ends["final_norm"], ends["lm_head"], want_logits=False, final_norm_bias=bias)
     torch.cuda.synchronize()
     assert none is None and torch.equal(tokens, tokens2), "tokens differ when no logits are requested"
     # oracle on the same bf16 inputs; at the largest shape on a sample of sequences (rows are independent)
     seqs = list(range(num_seqs)) if sample is None else sample
     hid_cpu, gain, w = hidden.cpu(), ends["final_norm"].cpu(), ends["lm_head"].cpu()
-    ref = oracle.head_logits(hid_cpu, q_lens, gain, w, shape.rms_eps)[seqs]
+    ref = oracle.head_logits(hid_cpu, q_lens, gain, w, shape.rms_eps, norm_kind=shape.norm_kind,
+                             bias=None if bias is None else bias.cpu())[seqs]
     got = logits[seqs]
     r = rel_l2(got.cpu().double(), ref)
     rms = float(ref.pow(2).mean().sqrt())
@@ -90,6 +95,33 @@ def test_head_vocab_and_width_tails():
     shape = synth.StageShape("tails", 1, 328, 2, 2, 64, 128, vocab=1064)
     _head_case(shape, 7, seed=3, head_std=0.05)
     _head_case(shape, 70, seed=4, head_std=0.05)
+
+
+@pytest.mark.parametrize("num_seqs,norm_bias", [(5, True), (64, False), (130, True)])
+def test_layernorm_head(num_seqs, norm_bias):
+    """The head of the families whose blocks use LayerNorms: a LayerNorm, with and without a bias, on rows with a
+    mean; both GEMM paths of the vocabulary projection."""
+    shape = dataclasses.replace(synth.TINY, norm_kind="layer")
+    _head_case(shape, num_seqs, seed=40 + num_seqs, head_std=0.06, norm_bias=norm_bias)
+
+
+def test_each_head_serves_its_own_norm_kind():
+    st = _head_stage(synth.TINY, 4, 4, 0)
+    ends = synth.draw_ends_weights(synth.TINY, seed=0, device="cuda:0")
+    hidden = synth.draw_hidden(synth.TINY, 4, seed=0, device="cuda:0")
+    with pytest.raises(StageError) as ei:                     # a bias asks for the LayerNorm head
+        st.head(hidden, [1] * 4, ends["final_norm"], ends["lm_head"], final_norm_bias=ends["final_norm"])
+    assert ei.value.code == -2
+    st.close()
+    layer = dataclasses.replace(synth.TINY, norm_kind="layer")
+    st = _head_stage(layer, 4, 4, 0)
+    import ctypes
+    tokens = torch.empty(4, dtype=torch.int32, device="cuda:0")
+    q = (ctypes.c_int32 * 4)(1, 1, 1, 1)
+    rc = st._lib.stage_head(st._handle, None, 4, hidden.data_ptr(), 4, q, ends["final_norm"].data_ptr(),
+                            ends["lm_head"].data_ptr(), layer.vocab, None, tokens.data_ptr())
+    assert rc == -2
+    st.close()
 
 
 def test_head_llama2_7b_full_size():
