@@ -65,8 +65,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
   const int lane = threadIdx.x & 63;
   // the four waves of a workgroup take four neighbouring KV heads of the same key range: their
   // blocks are adjacent in the pool, so the workgroup reads 16 KB runs
-  const int item_id = blockIdx.x;
-  const int r = __builtin_amdgcn_readfirstlane(blockIdx.y * 4 + (threadIdx.x >> 6));   // KV head
+  // workgroup order: the head groups of one key range follow each other eight apart, i.e. on the same XCD (workgroups
+  // go to the eight XCDs in turn) and close in time, so that they find each other's lines and translations
+  const int hgroups = (a.nkv + 3) / 4;
+  const int item_id = (int)(blockIdx.x / (8 * hgroups)) * 8 + (int)(blockIdx.x % 8);
+  const int hg = (int)(blockIdx.x % (8 * hgroups)) / 8;
+  if (item_id >= num_items) return;
+  const int r = __builtin_amdgcn_readfirstlane(hg * 4 + (threadIdx.x >> 6));   // KV head
   if (r >= a.nkv) return;
   const int g = a.nq / a.nkv;
   const int row = __builtin_amdgcn_readfirstlane(items[item_id].row);
@@ -864,7 +869,7 @@ hipError_t launch_attn_prefill(const AttnArgs& a, const PrefillTile* tiles, int 
 
 hipError_t launch_attn_decode(const AttnArgs& a, const DecodeItem* items, int num_items, float* part_o,
                               float2* part_ml, hipStream_t stream) {
-  dim3 grid(num_items, (a.nkv + 3) / 4), block(256);
+  dim3 grid(((num_items + 7) / 8) * 8 * ((a.nkv + 3) / 4)), block(256);
 #define MOLINK_DECODE(D, QLO, ALIBI) \
   hipLaunchKernelGGL((attn_decode_kernel<D, QLO, ALIBI>), grid, block, 0, stream, a, items, num_items, part_o, part_ml)
   if (a.head_dim == 128) {
