@@ -24,10 +24,10 @@ if ROOT not in sys.path:
 # same counter reads for a plain 1 GiB copy (profiles/hbm_traffic_*.md).  A figure is only reported while the
 # kernel source it was taken on is unchanged.
 MEASURED_TRAFFIC = {
-    ("attn_decode", "llama3-70b", 0): {"bytes": 4.92260e9 + 2.95559e7, "source": "csrc/attention.hip",
-                                       "sha256_16": "cd57a3728ed26b43"},
-    ("attn_decode", "llama2-7b", 0): {"bytes": 1.29827e9 + 3.71090e6, "source": "csrc/attention.hip",
-                                      "sha256_16": "cd57a3728ed26b43"},
+    ("attn_decode", "llama3-70b", 0): {"bytes": 4.92217e9 + 2.95565e7, "source": "csrc/attention.hip",
+                                       "sha256_16": "7730ca679be14cef"},
+    ("attn_decode", "llama2-7b", 0): {"bytes": 1.29793e9 + 3.71099e6, "source": "csrc/attention.hip",
+                                      "sha256_16": "7730ca679be14cef"},
 }
 
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
