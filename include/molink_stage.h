@@ -84,7 +84,8 @@ typedef struct {
                                   3  (bfloat16 library only) one plane of IEEE half - eleven significant bits
                                      instead of eight - with the bfloat16 weights converted to half, exactly, on
                                      their way into the matrix instruction; the rotated queries keep a second
-                                     bfloat16 plane for the attention kernels.  Values beyond the half range
+                                     bfloat16 plane for the attention kernels (the decode kernel multiplies both; the
+                                     prefill kernel both in mode 4, the first alone in mode 3).  Values beyond the half range
                                      saturate: a projection input larger than 65504 in magnitude is carried as
                                      +-65504 (finite, no longer the unclamped result; activations of that size
                                      do not occur behind an RMSNorm with gains of order one);
