@@ -24,9 +24,9 @@ if ROOT not in sys.path:
 # same counter reads for a plain 1 GiB copy (profiles/hbm_traffic_*.md).  A figure is only reported while the
 # kernel source it was taken on is unchanged.
 MEASURED_TRAFFIC = {
-    ("attn_decode", "llama3-70b", 0): {"bytes": 4.92217e9 + 2.95565e7, "source": "csrc/attention.hip",
+    ("attn_decode", "llama3-70b", 0): {"bytes": 4.92217e9 + 2.95563e7, "source": "csrc/attention.hip",
                                        "sha256_16": "7730ca679be14cef"},
-    ("attn_decode", "llama2-7b", 0): {"bytes": 1.29793e9 + 3.71099e6, "source": "csrc/attention.hip",
+    ("attn_decode", "llama2-7b", 0): {"bytes": 1.29793e9 + 3.71089e6, "source": "csrc/attention.hip",
                                       "sha256_16": "7730ca679be14cef"},
 }
 
@@ -34,6 +34,9 @@ HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 HEADLINE = "llama3-70b"
 # (workload, sweep budget) of the per-configuration entries; the headline's own entry is the headline run itself
+# the stage's other builds: the half-precision library and 4-bit weights on the small decode workload, 4-bit weights
+# on the headline workload (the paper serves its 70B model with 4-bit weights, section 5 "Models")
+VARIANTS = [("llama2-7b", {"dtype": "f16"}), ("llama2-7b", {"weights": "w4"}), ("llama3-70b", {"weights": "w4"})]
 PER_CONFIG = [("llama2-7b", None), ("qwen2-7b", None), ("llama3-70b", None), ("sweep", 64), ("sweep", 256), ("sweep", 2048)]
 
 
@@ -290,6 +293,19 @@ def main():
             r["unit"] = "tokens/s"
             entries.append(r)
         result["per_config"] = entries
+        if args.weights == "bf16" and args.dtype == "bf16":
+            import copy
+            variants = []
+            for workload, override in VARIANTS:
+                a2 = copy.copy(args)
+                for k, v in override.items():
+                    setattr(a2, k, v)
+                r = run_workload(a2, workload, None, args.steps, args.warmup, extras=False)
+                r.pop("stage_latency_ms")
+                r["unit"] = "tokens/s"
+                r["variant"] = override
+                variants.append(r)
+            result["variants"] = variants
     print(json.dumps(result))
 
 
