@@ -89,3 +89,24 @@ def test_static_scratch_rejects_what_does_not_fit_and_leaves_the_pool_untouched(
     torch.cuda.synchronize()
     assert torch.isfinite(out.float()).all()
     st.close()
+
+
+def test_static_scratch_forward_of_a_parallel_layernorm_block():
+    """The blocks that keep more intermediates (the second norm of a parallel block, the ungated MLP's first product)
+    carve them from the library's array too: same bits as with the caller's workspace."""
+    import dataclasses
+    shape = dataclasses.replace(_shape("static-block-kinds", 2, 1024, 8, 2, 128, 2816), norm_kind="layer",
+                                mlp_kind="gelu_erf", parallel_block=True)
+    mb = synth.make_microbatch([90, 1, 1, 1], [5, 40, 300, 17], seed=6, max_blocks_per_seq=24)
+    st = H.make_stage(shape, mb, 6, "fan_in", block_biases=True, alibi=True)
+    pool_before = st.kv_pool.clone()
+    hidden, tables, want, got, pool_after = _both(st, shape, mb, 6)
+    st.kv_pool.copy_(pool_before)
+    st.forward(hidden, mb.positions, mb.q_lens, mb.ctx_lens, tables, out=got, static_scratch=True)
+    torch.cuda.synchronize()
+    assert torch.equal(got.view(torch.int16), want.view(torch.int16))
+    assert torch.equal(st.kv_pool, pool_after)
+    from tests.helpers import draw_layers
+    ref, _, _, _ = H.run_oracle(shape, mb, 6, "fan_in", layers=draw_layers(shape, 6, "fan_in", block_biases=True, alibi=True))
+    H.check_output(got, ref, "static scratch, parallel LayerNorm block")
+    st.close()
