@@ -381,6 +381,20 @@ def test_block_kinds_in_a_deep_stage():
     full_parity(shape, mb, 14, "fan_in", taps=False, block_biases=True, shared_norm=True)
 
 
+def test_parallel_layernorm_block_at_real_widths():
+    """A parallel LayerNorm block with an ungated erf-GELU MLP, biases and a rotary embedding at the widths of a 7B-class
+    model (hidden 4096, 32 query heads on 8 KV heads, inner width 16384), two layers, 150 rows: every projection on the
+    operand-order kernel (the ungated MLP's first product through its fp32 store and the bias + gelu pass), decode
+    tokens with several key ranges."""
+    import dataclasses
+    shape = dataclasses.replace(_shape("block-real-widths", 2, 4096, 32, 8, 128, 16384), norm_kind="layer",
+                                mlp_kind="gelu_erf", parallel_block=True)
+    q = [90, 31] + [1] * 29
+    c = [0, 77] + [40 + 67 * i for i in range(29)]
+    mb = synth.make_microbatch(q, c, seed=15, max_blocks_per_seq=130)
+    full_parity(shape, mb, 15, "fan_in", taps=False, block_biases=True)
+
+
 def test_block_kind_weights_are_validated():
     import dataclasses
     base, mb = synth.workload("tiny", seed=0)
