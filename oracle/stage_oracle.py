@@ -62,7 +62,10 @@ prefill row under them; LayerNorm against the library routine, zero mean and uni
 shift invariance, and a constant row (closed form: the bias); both GELU forms against the library routine and
 literal values; the parallel block from the sequential one (zero output projection: both agree; zero down
 projection: y = x + attention branch), shared norm == the same norm given twice, scalar loops with every
-switch.  The paper prints no numeric values
+switch; frequency scaling of the rotation: factor 1 changes nothing bit for bit, the linear
+kind equals the unscaled rotation at position / factor, the wavelength kind keeps fast pairs, divides slow pairs'
+frequencies by the factor, is continuous at both borders and monotone between them, literal pair counts for the
+published Llama-3.1 parameters, scalar loops with it.  The paper prints no numeric values
 for this path, so parity against printed values is unpinned; parity is against
 the definition.
 """
@@ -91,6 +94,9 @@ class OracleShape:
     norm_kind: str = "rms"       # "rms" | "layer": both norms of the block (rms_eps is the epsilon of either)
     mlp_kind: str = "swiglu"     # "swiglu": down(silu(gate(b)) * up(b)); "gelu_tanh" | "gelu_erf": down(gelu(up(b)))
     parallel_block: bool = False  # True: y = x + attn(norm1(x)) + mlp(norm2(x)); False: the branches in sequence
+    # frequency scaling of the rotary embedding for contexts beyond the trained length: None, ("linear", factor) or
+    # ("llama3", factor, low_freq_factor, high_freq_factor, original_max_position)
+    rope_scaling: Optional[tuple] = None
 
 
 def new_pool(shape: OracleShape, num_kv_blocks: int, dtype=torch.float64, fill=float("nan")) -> torch.Tensor:
@@ -131,23 +137,54 @@ def gelu(z: torch.Tensor, form: str) -> torch.Tensor:
     return 0.5 * z * (1.0 + torch.tanh(math.sqrt(2.0 / math.pi) * (z + 0.044715 * z * z * z)))
 
 
+def scaled_inv_freq(inv_freq: torch.Tensor, scaling: Optional[tuple]) -> torch.Tensor:
+    """The rotation frequencies of a model served beyond its trained context (the Llama family the paper evaluates
+    publishes its long-context members this way).
+
+    ("linear", f): every frequency divided by f - positions are compressed by f.
+    ("llama3", f, low, high, L): by wavelength w = 2 pi / frequency against the trained length L: pairs that turn
+    often, w < L / high, keep their frequency; pairs that turn rarely, w > L / low, get frequency / f; between the two
+    the frequency is the mix (1 - s) * frequency / f + s * frequency with s = (L / w - low) / (high - low), which is
+    0 and 1 at the two borders."""
+    if scaling is None:
+        return inv_freq
+    if scaling[0] == "linear":
+        return inv_freq / float(scaling[1])
+    assert scaling[0] == "llama3"
+    _, f, low, high, length = scaling
+    out = inv_freq.clone()
+    for i in range(inv_freq.numel()):
+        freq = float(inv_freq[i])
+        wavelength = 2.0 * math.pi / freq
+        if wavelength < length / high:
+            continue
+        if wavelength > length / low:
+            out[i] = freq / f
+        else:
+            smooth = (length / wavelength - low) / (high - low)
+            out[i] = (1.0 - smooth) * freq / f + smooth * freq
+    return out
+
+
 def rope_rotate(u: torch.Tensor, pos: torch.Tensor, theta: float, rotary_dim: int = 0,
-                interleaved: bool = False) -> torch.Tensor:
+                interleaved: bool = False, scaling: Optional[tuple] = None) -> torch.Tensor:
     """Rotary embedding.  u: [T, heads, d]; pos: [T] integers.
 
     Half-split pairing (the default): pair (i, i + d/2) of every head is rotated by the angle
     pos * theta**(-2i/d).  Neighbour pairing (interleaved): pair (2i, 2i + 1) is rotated by the same angle.
     Angles, cos and sin are evaluated in float64.
+    scaling: see scaled_inv_freq (the frequencies theta**(-2i/d) are replaced by their scaled values).
     Partial rotary (the GLM / ChatGLM families of the paper's model table, section 3.1.3, which also pair
     neighbours): with 0 < rotary_dim < d only the first rotary_dim elements of a head rotate, as a head of that
     size would (angles pos * theta**(-2i/rotary_dim)); the rest pass through.
     """
     if rotary_dim and rotary_dim < u.shape[-1]:
-        return torch.cat([rope_rotate(u[..., :rotary_dim], pos, theta, 0, interleaved), u[..., rotary_dim:]], dim=-1)
+        return torch.cat([rope_rotate(u[..., :rotary_dim], pos, theta, 0, interleaved, scaling), u[..., rotary_dim:]],
+                         dim=-1)
     t, _, d = u.shape
     half = d // 2
     i = torch.arange(half, dtype=torch.float64)
-    inv_freq = theta ** (-2.0 * i / d)
+    inv_freq = scaled_inv_freq(theta ** (-2.0 * i / d), scaling)
     ang = pos.to(torch.float64).view(t, 1) * inv_freq.view(1, half)      # [T, d/2]
     cos = torch.cos(ang).to(u.dtype).view(t, 1, half)
     sin = torch.sin(ang).to(u.dtype).view(t, 1, half)
@@ -234,8 +271,8 @@ def decoder_layer(shape: OracleShape, w: Dict[str, torch.Tensor], x: torch.Tenso
         k = rmsnorm(k, w["knorm"].to(dt), shape.rms_eps)
     slopes = w.get("alibi")                                           # [nq]: linear biases instead of a rotation
     if slopes is None:
-        q = rope_rotate(q, pos, shape.rope_theta, shape.rotary_dim, shape.rope_interleaved)
-        k = rope_rotate(k, pos, shape.rope_theta, shape.rotary_dim, shape.rope_interleaved)
+        q = rope_rotate(q, pos, shape.rope_theta, shape.rotary_dim, shape.rope_interleaved, shape.rope_scaling)
+        k = rope_rotate(k, pos, shape.rope_theta, shape.rotary_dim, shape.rope_interleaved, shape.rope_scaling)
     # append the new tokens' keys (rotated) and values at their slots
     slot_t = torch.as_tensor(slots, dtype=torch.int64)
     k_st = k if kv_store_dtype is None else k.to(kv_store_dtype).to(dt)

@@ -141,6 +141,8 @@ class StageShape:
     norm_kind: str = "rms"          # "rms" | "layer": the block's two norms
     mlp_kind: str = "swiglu"        # "swiglu" | "gelu_tanh" | "gelu_erf" (the latter two: down(gelu(up(b))), no gate)
     parallel_block: bool = False    # attention branch and MLP branch both start from the block's input
+    # None, ("linear", factor) or ("llama3", factor, low_freq_factor, high_freq_factor, original_max_position)
+    rope_scaling: Optional[tuple] = None
 
     @property
     def qkv_out(self) -> int:

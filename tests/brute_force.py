@@ -39,16 +39,33 @@ def matvec(w, x):
     return [sum(w[o][i] * x[i] for i in range(len(x))) for o in range(len(w))]
 
 
-def rope_head(u, p, theta, rotary_dim=0, interleaved=False):
+def scaled_frequency(freq, scaling):
+    """In terms of turns over the trained length L (turns = L * freq / 2 pi): more than `high` turns - unchanged; fewer
+    than `low` - divided by the factor; in between - the weight of the unchanged frequency rises linearly with the turns."""
+    if scaling is None:
+        return freq
+    if scaling[0] == "linear":
+        return freq / scaling[1]
+    _, f, low, high, length = scaling
+    turns = length * freq / (2.0 * math.pi)
+    if turns > high:
+        return freq
+    if turns < low:
+        return freq / f
+    keep = (turns - low) / (high - low)
+    return keep * freq + (1.0 - keep) * freq / f
+
+
+def rope_head(u, p, theta, rotary_dim=0, interleaved=False, scaling=None):
     """rotary_dim > 0: only u[:rotary_dim] rotates (as a head of that size), the rest is copied.
     interleaved: element 2i is rotated with element 2i + 1 instead of element i with element i + d/2."""
     if rotary_dim and rotary_dim < len(u):
-        return rope_head(u[:rotary_dim], p, theta, 0, interleaved) + list(u[rotary_dim:])
+        return rope_head(u[:rotary_dim], p, theta, 0, interleaved, scaling) + list(u[rotary_dim:])
     d = len(u)
     half = d // 2
     y = [0.0] * d
     for i in range(half):
-        ang = p * theta ** (-2.0 * i / d)
+        ang = p * scaled_frequency(theta ** (-2.0 * i / d), scaling)
         c, s = math.cos(ang), math.sin(ang)
         a, b = (2 * i, 2 * i + 1) if interleaved else (i, i + half)
         y[a] = u[a] * c - u[b] * s
@@ -74,9 +91,10 @@ def layer_one_sequence(shape, w, rows, pos, cache_k, cache_v):
             qh = [rmsnorm_row(u, w["qnorm"], shape.rms_eps) for u in qh]
             kh = [rmsnorm_row(u, w["knorm"], shape.rms_eps) for u in kh]
         rd, il = getattr(shape, "rotary_dim", 0), getattr(shape, "rope_interleaved", False)
+        sc = getattr(shape, "rope_scaling", None)
         if w.get("alibi") is None:
-            q = [rope_head(u, pos[n], shape.rope_theta, rd, il) for u in qh]
-            k = [rope_head(u, pos[n], shape.rope_theta, rd, il) for u in kh]
+            q = [rope_head(u, pos[n], shape.rope_theta, rd, il, sc) for u in qh]
+            k = [rope_head(u, pos[n], shape.rope_theta, rd, il, sc) for u in kh]
         else:                                     # linear biases: nothing rotates
             q, k = qh, kh
         v = [qkv[(nq + nkv + r) * d:(nq + nkv + r + 1) * d] for r in range(nkv)]

@@ -13,7 +13,7 @@ def oracle_shape(shape: synth.StageShape) -> oracle.OracleShape:
     return oracle.OracleShape(shape.num_layers, shape.hidden, shape.num_q_heads, shape.num_kv_heads,
                               shape.head_dim, shape.ffn, shape.rms_eps, shape.rope_theta,
                               shape.kv_block_size, shape.rotary_dim, shape.rope_interleaved,
-                              shape.norm_kind, shape.mlp_kind, shape.parallel_block)
+                              shape.norm_kind, shape.mlp_kind, shape.parallel_block, shape.rope_scaling)
 
 
 def draw_layers(shape: synth.StageShape, seed: int, weight_std=None, device="cpu",

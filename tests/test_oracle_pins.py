@@ -4,6 +4,7 @@ The paper prints no numbers for a stage's forward pass (it leaves the computatio
 engine runtime, section 3.2.2), so the oracle is pinned to the mathematics of the decoder
 block instead of to printed values.
 """
+import dataclasses
 import math
 
 import pytest
@@ -744,6 +745,89 @@ def test_zero_block_biases_change_nothing_and_real_ones_shift_by_themselves():
     zero[0]["bdown"] = synth.draw_block_biases(shape, 0, seed=9)["bdown"]
     c = run_oracle(shape, mb, layers=zero, hidden=hidden, pool=oracle_pool(shape, mb, 9))[0]
     assert torch.allclose(c - a, zero[0]["bdown"].double().expand_as(a), rtol=0, atol=1e-12)
+
+
+# ---------------------------------------------------------------- frequency scaling of the rotation
+
+LLAMA31 = ("llama3", 8.0, 1.0, 4.0, 8192)          # the parameters the Llama-3.1 models are published with
+
+
+def test_rope_scaling_with_factor_one_changes_nothing_and_linear_scaling_compresses_positions():
+    g = torch.Generator().manual_seed(3)
+    u = torch.randn(6, 3, 16, dtype=F64, generator=g)
+    pos = torch.tensor([0, 4, 8, 12, 400, 8000])
+    plain = oracle.rope_rotate(u, pos, 1e4)
+    assert torch.equal(oracle.rope_rotate(u, pos, 1e4, scaling=("linear", 1.0)), plain)
+    assert torch.equal(oracle.rope_rotate(u, pos, 1e4, scaling=("llama3", 1.0, 1.0, 4.0, 8192)), plain)
+    # positions that are multiples of the factor: the scaled rotation is the plain one at position / factor
+    got = oracle.rope_rotate(u, pos, 1e4, scaling=("linear", 4.0))
+    want = oracle.rope_rotate(u, pos // 4, 1e4)
+    assert torch.allclose(got, want, rtol=1e-12, atol=1e-12)
+    assert not torch.allclose(got, plain, rtol=1e-3)
+
+
+def test_wavelength_scaling_keeps_fast_pairs_and_slows_the_slow_ones():
+    d, theta = 128, 5e5
+    i = torch.arange(d // 2, dtype=F64)
+    inv = theta ** (-2.0 * i / d)
+    got = oracle.scaled_inv_freq(inv, LLAMA31)
+    ratio = got / inv
+    wavelength = 2 * math.pi / inv
+    fast, slow = wavelength < 8192 / 4.0, wavelength > 8192 / 1.0
+    assert torch.equal(ratio[fast], torch.ones(int(fast.sum()), dtype=F64))
+    assert torch.allclose(ratio[slow], torch.full((int(slow.sum()),), 1 / 8.0, dtype=F64), rtol=1e-15)
+    mid = ~(fast | slow)
+    # theta = 500000, 64 pairs: wavelengths 2 pi theta^(i/64); 2048 and 8192 are passed after pairs 28 and 35
+    assert int(fast.sum()) == 29 and int(mid.sum()) == 6 and int(slow.sum()) == 29
+    assert (ratio[mid] > 1 / 8.0).all() and (ratio[mid] < 1.0).all()
+    assert (ratio[1:] <= ratio[:-1] + 1e-15).all()                       # never rising with the pair index
+    # continuous at the borders: a frequency exactly at a border gets the neighbouring rule's value
+    for turns, want in ((4.0, 1.0), (1.0, 1 / 8.0)):
+        f = torch.tensor([turns * 2 * math.pi / 8192], dtype=F64)
+        for eps in (-1e-9, 1e-9):
+            r = float(oracle.scaled_inv_freq(f * (1 + eps), LLAMA31) / (f * (1 + eps)))
+            assert abs(r - want) < 1e-6
+    # halfway between the borders in turns (2.5 of them over the trained length): the mean of both frequencies
+    f = torch.tensor([2.5 * 2 * math.pi / 8192], dtype=F64)
+    assert abs(float(oracle.scaled_inv_freq(f, LLAMA31) / f) - 0.5 * (1 + 1 / 8.0)) < 1e-12
+
+
+@pytest.mark.parametrize("scaling", [("linear", 4.0), ("llama3", 8.0, 1.0, 4.0, 64)])
+def test_rope_scaling_matches_scalar_loops(scaling):
+    """Whole block with scaled rotation frequencies; the trained length of the wavelength kind is chosen so that the
+    eight pairs of this small head fall into all three ranges."""
+    shape = small_shape(num_q_heads=4, num_kv_heads=2, hidden=12, ffn=20, head_dim=16, kv_block_size=4, rope_theta=100.0,
+                        rope_scaling=scaling)
+    if scaling[0] == "llama3":
+        inv = 100.0 ** (-2.0 * torch.arange(8, dtype=F64) / 16)
+        r = oracle.scaled_inv_freq(inv, scaling) / inv
+        assert (r == 1).any() and (r == 1 / 8.0).any() and ((r > 1 / 8.0) & (r < 1)).any()
+    q_lens, ctx_lens = [5, 1, 3], [0, 6, 2]
+    mb = synth.make_microbatch(q_lens, ctx_lens, seed=3, block=4, position_shift=40)
+    layers = draw_layers(shape, 3, "fan_in")
+    hidden = synth.draw_hidden(shape, mb.num_tokens, seed=3)
+    pool = oracle_pool(shape, mb, 3)
+    pool0 = pool.clone()
+    out, _, _ = run_oracle(shape, mb, layers=layers, hidden=hidden, pool=pool)
+    got, row0 = [], 0
+    x_rows = hidden.double().tolist()
+    for s, (q, c) in enumerate(zip(q_lens, ctx_lens)):
+        rows = x_rows[row0:row0 + q]
+        for l in range(shape.num_layers):
+            w = {k: v.double().tolist() for k, v in layers[l].items()}
+            ck, cv = [], []
+            for j in range(c):
+                b = int(mb.block_tables[s][j // 4])
+                ck.append(pool0[l, 0, b, j % 4].tolist())
+                cv.append(pool0[l, 1, b, j % 4].tolist())
+            rows = brute_force.layer_one_sequence(shape, w, rows, list(range(c + 40, c + q + 40)), ck, cv)
+        got.extend(rows)
+        row0 += q
+    got = torch.tensor(got, dtype=F64)
+    assert torch.allclose(out, got, rtol=1e-9, atol=1e-10), float((out - got).abs().max())
+    base = dataclasses.replace(shape, rope_scaling=None)
+    plain, _, _ = run_oracle(base, mb, layers=layers, hidden=hidden, pool=pool0.clone())
+    assert not torch.allclose(out, plain, rtol=1e-3)
 
 
 def test_cache_store_type_as_wide_as_the_arithmetic_changes_nothing():
