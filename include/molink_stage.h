@@ -135,6 +135,17 @@ typedef struct {
                                   from the block's input, y = x + attention(norm1(x)) + mlp(norm2(x)) (Falcon, Cohere);
                                   norm2 may then be NULL in every layer: the MLP reads norm1(x) too (one norm per block).
                                   16-bit weights only. */
+  int32_t rope_scaling;        /* Frequency scaling of the rotary embedding for contexts beyond the trained length (the
+                                  Llama family publishes its long-context models this way).  0: none.  1: linear - every
+                                  frequency theta^(-2i/d) is divided by rope_scaling_factor.  2: by wavelength
+                                  w = 2 pi / frequency against rope_original_max_position L: w < L / rope_high_freq_factor
+                                  keeps its frequency, w > L / rope_low_freq_factor gets frequency / rope_scaling_factor,
+                                  in between the mix (1 - s) frequency / factor + s frequency with
+                                  s = (L / w - low) / (high - low).  The four fields below are 0 unless this is set. */
+  float rope_scaling_factor;       /* >= 1 */
+  float rope_low_freq_factor;      /* kind 2: > 0 and below rope_high_freq_factor */
+  float rope_high_freq_factor;     /* kind 2 */
+  int32_t rope_original_max_position;  /* kind 2: the trained context length L, > 0 */
 } stage_config;
 
 /* Device pointers to one layer's weights, row-major [out_features][in_features], bf16 unless
@@ -183,8 +194,8 @@ typedef struct {
   const void *qnorm, *knorm;
   /*
    * NULL in every layer, or set in every layer: fp32 [num_q_heads] head slopes of attention with linear biases.
-   * The stage then rotates nothing (positions are ignored; rotary_dim and rope_interleaved must be 0, qnorm / knorm
-   * NULL), and the score of the query at logical index i of its sequence for the key at logical index j <= i is
+   * The stage then rotates nothing (positions are ignored; rotary_dim, rope_interleaved and rope_scaling must be 0,
+   * qnorm / knorm NULL), and the score of the query at logical index i of its sequence for the key at logical index j <= i is
    * lowered by slope[head] * (i - j) before the softmax.  The larger Baichuan model of the paper's model table
    * (section 3.1.3) is the Llama-style block with these biases in place of the rotary embedding.
    */

@@ -144,11 +144,25 @@ __global__ __launch_bounds__(256) void bias_gelu_kernel(const float* __restrict_
 
 __global__ __launch_bounds__(256) void rope_table_kernel(const int32_t* __restrict__ positions,
                                                          float2* __restrict__ cos_sin, int rows, int half,
-                                                         double log2_theta) {
+                                                         double log2_theta, RopeScaling sc) {
   const int idx = blockIdx.x * 256 + threadIdx.x;
   if (idx >= rows * half) return;
   const int t = idx / half, i = idx % half;
-  const double inv_freq = exp2(-(double)i / (double)half * log2_theta);   // theta^(-2i/d), d = 2*half
+  double inv_freq = exp2(-(double)i / (double)half * log2_theta);   // theta^(-2i/d), d = 2*half
+  if (sc.kind == 1) {
+    inv_freq /= (double)sc.factor;
+  } else if (sc.kind == 2) {
+    // by wavelength against the trained length: fast pairs keep their frequency, slow ones are divided by the
+    // factor, those in between get the mix that is continuous at both borders
+    const double wavelength = 6.283185307179586 / inv_freq, length = (double)sc.original_max_position;
+    if (wavelength > length / (double)sc.low_freq_factor) {
+      inv_freq /= (double)sc.factor;
+    } else if (!(wavelength < length / (double)sc.high_freq_factor)) {
+      const double smooth = (length / wavelength - (double)sc.low_freq_factor) /
+                            ((double)sc.high_freq_factor - (double)sc.low_freq_factor);
+      inv_freq = (1.0 - smooth) * inv_freq / (double)sc.factor + smooth * inv_freq;
+    }
+  }
   const double ang = (double)positions[t] * inv_freq;
   double s, c;
   sincos(ang, &s, &c);
@@ -435,11 +449,11 @@ hipError_t launch_bias_gelu(const float* src, int planes, size_t plane_stride, c
 }
 
 hipError_t launch_rope_table(const int32_t* positions, float2* cos_sin, int rows, int rotary_dim, float theta,
-                             hipStream_t stream) {
+                             const RopeScaling& scaling, hipStream_t stream) {
   const int half = rotary_dim / 2;
   const int total = rows * half;
   hipLaunchKernelGGL(rope_table_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, positions, cos_sin, rows, half,
-                     log2((double)theta));
+                     log2((double)theta), scaling);
   return hipGetLastError();
 }
 

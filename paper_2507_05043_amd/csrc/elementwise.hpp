@@ -28,8 +28,15 @@ hipError_t launch_bias_gelu(const float* src, int planes, size_t plane_stride, c
 
 // cos_sin[t][i] = (cos, sin)(positions[t] * theta^(-2i/r)), i < r/2, evaluated in fp64; r = rotary_dim, the
 // number of leading elements of a head that rotate (head_dim unless the rotary embedding is partial).
+// scaling: the frequencies theta^(-2i/r) are replaced by their scaled values (stage_config.rope_scaling: 0 none,
+// 1 every frequency / factor, 2 by wavelength against the trained length).
+struct RopeScaling {
+  int kind;
+  float factor, low_freq_factor, high_freq_factor;
+  int original_max_position;
+};
 hipError_t launch_rope_table(const int32_t* positions, float2* cos_sin, int rows, int rotary_dim, float theta,
-                             hipStream_t stream);
+                             const RopeScaling& scaling, hipStream_t stream);
 
 struct RopeAppendArgs {
   const float* qkv_f32;    // [planes][T][(nq + 2 nkv) d] projection output, fp32 (rounded to e16 only after the

@@ -123,6 +123,18 @@ int check_config(const stage_config* c) {
     return fail(STAGE_ERR_CONFIG, "mlp_kind must be 0 (gated, SiLU), 1 (ungated, tanh GELU) or 2 (ungated, erf GELU), got %d", c->mlp_kind);
   if (c->parallel_block != 0 && c->parallel_block != 1)
     return fail(STAGE_ERR_CONFIG, "parallel_block must be 0 or 1, got %d", c->parallel_block);
+  if (c->rope_scaling < 0 || c->rope_scaling > 2)
+    return fail(STAGE_ERR_CONFIG, "rope_scaling must be 0 (none), 1 (linear) or 2 (by wavelength), got %d", c->rope_scaling);
+  if (c->rope_scaling == 0 && (c->rope_scaling_factor != 0.f || c->rope_low_freq_factor != 0.f ||
+                               c->rope_high_freq_factor != 0.f || c->rope_original_max_position != 0))
+    return fail(STAGE_ERR_CONFIG, "the rope scaling parameters must be 0 unless rope_scaling is set");
+  if (c->rope_scaling != 0 && !(c->rope_scaling_factor >= 1.f))
+    return fail(STAGE_ERR_CONFIG, "rope_scaling_factor must be at least 1");
+  if (c->rope_scaling == 1 && (c->rope_low_freq_factor != 0.f || c->rope_high_freq_factor != 0.f || c->rope_original_max_position != 0))
+    return fail(STAGE_ERR_CONFIG, "linear rope scaling takes rope_scaling_factor only");
+  if (c->rope_scaling == 2 && (!(c->rope_low_freq_factor > 0.f) || !(c->rope_high_freq_factor > c->rope_low_freq_factor) ||
+                               c->rope_original_max_position < 1))
+    return fail(STAGE_ERR_CONFIG, "rope scaling by wavelength needs 0 < rope_low_freq_factor < rope_high_freq_factor and a positive rope_original_max_position");
   if (c->weight_bits == 4 && (c->mlp_kind != 0 || c->parallel_block != 0))
     return fail(STAGE_ERR_CONFIG, "4-bit weights are supported for the gated, sequential block only (mlp_kind 0, parallel_block 0)");
   if (c->weight_bits != 0 && c->weight_bits != 16 && c->weight_bits != 4)
@@ -733,7 +745,9 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
   const int rotating = alibi ? 0 : d.rd;
   if (rotating) {
     Timer t(st, stream, STAGE_K_ROPE_TABLE);
-    HIP_TRY(launch_rope_table(d_pos, cos_sin, T, d.rd, c.rope_theta, stream));
+    HIP_TRY(launch_rope_table(d_pos, cos_sin, T, d.rd, c.rope_theta,
+                              RopeScaling{c.rope_scaling, c.rope_scaling_factor, c.rope_low_freq_factor,
+                                          c.rope_high_freq_factor, c.rope_original_max_position}, stream));
   }
   const size_t kv_region = (size_t)c.num_kv_blocks * d.nkv * 16 * d.d;   // elements of one K (or V) region
   {
@@ -941,7 +955,7 @@ int stage_init(const stage_config* cfg, const stage_layer_weights* layers, void*
     if ((uintptr_t)w.bqkv % 16) return fail(STAGE_ERR_CONFIG, "layer %d: bqkv is not 16-byte aligned", l);
     if ((w.alibi == nullptr) != (layers[0].alibi == nullptr))
       return fail(STAGE_ERR_NULL, "layer %d: alibi slopes must be set in every layer or in none", l);
-    if (w.alibi && (w.qnorm || cfg->rotary_dim != 0 || cfg->rope_interleaved != 0))
+    if (w.alibi && (w.qnorm || cfg->rotary_dim != 0 || cfg->rope_interleaved != 0 || cfg->rope_scaling != 0))
       return fail(STAGE_ERR_CONFIG, "layer %d: linear biases replace the rotation: rotary_dim and rope_interleaved must be 0, "
                   "qnorm / knorm NULL", l);
     if ((uintptr_t)w.alibi % 4) return fail(STAGE_ERR_CONFIG, "layer %d: alibi is not 4-byte aligned", l);

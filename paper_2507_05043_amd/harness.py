@@ -35,7 +35,7 @@ def make_stage(shape: synth.StageShape, mb: synth.MicroBatch, seed: int, weight_
                       vocab_size=vocab_size, weight_bits=4 if weight_group_size else 0,
                       weight_group_size=weight_group_size, rotary_dim=shape.rotary_dim, weight_copies=weight_copies,
                       rope_interleaved=int(shape.rope_interleaved), norm_kind=shape.norm_kind, mlp_kind=shape.mlp_kind,
-                      parallel_block=int(shape.parallel_block))
+                      parallel_block=int(shape.parallel_block), rope_scaling=shape.rope_scaling)
     kv_pool = None
     if pool_first:
         from .stage import stage_kv_layer_bytes

@@ -44,6 +44,9 @@ class StageConfig(ctypes.Structure):
         ("weight_bits", ctypes.c_int32), ("weight_group_size", ctypes.c_int32), ("rotary_dim", ctypes.c_int32),
         ("rope_interleaved", ctypes.c_int32), ("weight_copies", ctypes.c_int32),
         ("norm_kind", ctypes.c_int32), ("mlp_kind", ctypes.c_int32), ("parallel_block", ctypes.c_int32),
+        ("rope_scaling", ctypes.c_int32), ("rope_scaling_factor", ctypes.c_float),
+        ("rope_low_freq_factor", ctypes.c_float), ("rope_high_freq_factor", ctypes.c_float),
+        ("rope_original_max_position", ctypes.c_int32),
     ]
 
 
@@ -132,12 +135,22 @@ def make_config(*, num_layers, hidden, num_q_heads, num_kv_heads, head_dim, ffn,
                 num_kv_blocks, max_tokens, max_seqs, max_blocks_per_seq, kv_block_size=16,
                 kv_layer_stride_bytes=None, activation_planes=0, vocab_size=0, weight_bits=0,
                 weight_group_size=0, rotary_dim=0, weight_copies=0, rope_interleaved=0, norm_kind=0, mlp_kind=0,
-                parallel_block=0) -> StageConfig:
+                parallel_block=0, rope_scaling=None) -> StageConfig:
+    """rope_scaling: None, ("linear", factor) or ("llama3", factor, low_freq_factor, high_freq_factor,
+    original_max_position)."""
+    if rope_scaling is None:
+        scaling = (0, 0.0, 0.0, 0.0, 0)
+    elif rope_scaling[0] == "linear":
+        scaling = (1, float(rope_scaling[1]), 0.0, 0.0, 0)
+    elif rope_scaling[0] == "llama3":
+        scaling = (2, float(rope_scaling[1]), float(rope_scaling[2]), float(rope_scaling[3]), int(rope_scaling[4]))
+    else:
+        scaling = tuple(rope_scaling)          # raw field values (tests of the validation)
     cfg = StageConfig(ctypes.sizeof(StageConfig), num_layers, hidden, num_q_heads, num_kv_heads, head_dim, ffn,
                       rms_eps, rope_theta, kv_block_size, num_kv_blocks, 0, max_tokens, max_seqs, max_blocks_per_seq,
                       activation_planes, vocab_size, weight_bits, weight_group_size, rotary_dim, int(rope_interleaved),
                       weight_copies, NORM_KINDS.get(norm_kind, norm_kind), MLP_KINDS.get(mlp_kind, mlp_kind),
-                      int(parallel_block))
+                      int(parallel_block), *scaling)
     if kv_layer_stride_bytes is None:
         kv_layer_stride_bytes = stage_kv_layer_bytes(cfg)
     cfg.kv_layer_stride_bytes = kv_layer_stride_bytes

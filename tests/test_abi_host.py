@@ -114,8 +114,8 @@ def test_matrices_of_four_gib_and_more_are_accepted(lib):
 
 
 def test_config_struct_matches_header_size(lib):
-    # uint32 + 6 int32 + 2 float + 2 int32 (+ 4 pad) + int64 + 13 int32 (+ 4 pad)
-    assert ctypes.sizeof(S.StageConfig) == 112
+    # uint32 + 6 int32 + 2 float + 2 int32 (+ 4 pad) + int64 + 14 int32 + 3 float + int32
+    assert ctypes.sizeof(S.StageConfig) == 128
     assert ctypes.sizeof(S.StageLayerWeights) == 26 * ctypes.sizeof(ctypes.c_void_p)
     assert S.stage_workspace_bytes(tiny_cfg()) > 0
 
@@ -127,6 +127,9 @@ def test_config_struct_matches_header_size(lib):
                                  dict(weight_bits=3), dict(weight_group_size=128), dict(weight_bits=4, weight_group_size=48),
                                  dict(weight_bits=4, weight_group_size=128, ffn=768 + 64),
                                  dict(weight_bits=4, weight_group_size=128),    # ffn 688 is no multiple of 128
+                                 dict(rope_scaling=(3, 2.0, 0.0, 0.0, 0)), dict(rope_scaling=(0, 2.0, 0.0, 0.0, 0)),
+                                 dict(rope_scaling=("linear", 0.5)), dict(rope_scaling=(1, 2.0, 1.0, 4.0, 8192)),
+                                 dict(rope_scaling=("llama3", 8.0, 4.0, 1.0, 8192)), dict(rope_scaling=("llama3", 8.0, 1.0, 4.0, 0)),
                                  dict(norm_kind=2), dict(mlp_kind=3), dict(mlp_kind=-1), dict(parallel_block=2),
                                  dict(weight_bits=4, weight_group_size=128, ffn=768, mlp_kind=1),
                                  dict(weight_bits=4, weight_group_size=128, ffn=768, parallel_block=1)])
@@ -277,3 +280,9 @@ def test_block_kinds_size_the_workspace(lib):
     without = (S.stage_workspace_bytes(tiny_cfg(mlp_kind="gelu_erf", **wide))
                - S.stage_workspace_bytes(tiny_cfg(mlp_kind="gelu_erf", weight_copies=1, **wide)))
     assert 0 < without < with_gate
+
+
+def test_rope_scaling_settings_are_accepted(lib):
+    base = S.stage_workspace_bytes(tiny_cfg())
+    assert S.stage_workspace_bytes(tiny_cfg(rope_scaling=("linear", 4.0))) == base
+    assert S.stage_workspace_bytes(tiny_cfg(rope_scaling=("llama3", 8.0, 1.0, 4.0, 8192))) == base

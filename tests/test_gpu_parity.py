@@ -432,6 +432,42 @@ def test_block_kind_weights_are_validated():
     assert ei.value.code == -2
 
 
+@pytest.mark.parametrize("scaling,extra", [
+    (("linear", 4.0), {}),
+    (("llama3", 8.0, 1.0, 4.0, 256), {}),                                      # 64 pairs: kept, mixed and divided ones
+    (("llama3", 8.0, 1.0, 4.0, 64), dict(rotary_dim=64, rope_interleaved=True)),   # with the GLM families' rotation
+    (("llama3", 8.0, 1.0, 4.0, 8192), dict(rope_theta=5e5)),                   # the published Llama-3.1 parameters
+], ids=["linear", "wavelength", "wavelength-partial-neighbour", "llama31"])
+def test_rope_frequency_scaling(scaling, extra):
+    """Rotation frequencies scaled for contexts beyond the trained length (stage_config.rope_scaling): the linear
+    kind and the wavelength rule, on chunks and decode tokens at positions from 0 to 1300 and, shifted, near 20000;
+    whole-stage parity (with taps at the small positions), and at the large ones a different output than without the
+    scaling."""
+    import dataclasses
+    shape = dataclasses.replace(_shape("rope-scaling", 2, 512, 8, 2, 128, 1408), rope_scaling=scaling, **extra)
+    for shift in (0, 19000):
+        mb = synth.make_microbatch([70, 33, 1, 1, 1, 1, 1], [0, 21, 9, 40, 77, 500, 1300], seed=9, max_blocks_per_seq=90,
+                                   position_shift=shift)
+        stats = full_parity(shape, mb, 9, "fan_in", taps=shift == 0)
+        if shift == 0:
+            continue        # at small positions the slowly turning pairs, the ones the wavelength rule changes, hardly turn
+        plain_shape = dataclasses.replace(shape, rope_scaling=None)
+        outs = []
+        for sh in (plain_shape, shape):
+            st = H.make_stage(sh, mb, 9, "fan_in")
+            outs.append(H.run_gpu(st, sh, mb, 9)[0].cpu())
+            st.close()
+        assert rel_l2(outs[1], outs[0]) > 10 * max(stats["rel_l2"], 1e-3)
+
+
+def test_linear_biases_exclude_rope_scaling():
+    import dataclasses
+    shape, mb = synth.workload("tiny", seed=0)
+    with pytest.raises(StageError) as ei:
+        H.make_stage(dataclasses.replace(shape, rope_scaling=("linear", 2.0)), mb, 0, alibi=True)
+    assert ei.value.code == -2
+
+
 def test_linear_biases_exclude_the_rotation_settings():
     import dataclasses
     shape, mb = synth.workload("tiny", seed=0)
