@@ -341,6 +341,8 @@ BLOCK_KIND_CASES = {
     "ungated-only-f16": dict(shape=dict(mlp_kind="gelu_tanh"), elem=torch.float16, block_biases=True, q=[70, 1], c=[5, 90]),
     "layernorm-only-decode": dict(shape=dict(norm_kind="layer"), block_biases=True, q=[1] * 9, c=[20 * i for i in range(9)]),
     "ungated-erf-no-bias-700": dict(shape=dict(mlp_kind="gelu_erf"), planes=3, q=[700], c=[0]),
+    "ungated-layernorm-two-planes": dict(shape=dict(mlp_kind="gelu_tanh", norm_kind="layer"), planes=2, block_biases=True,
+                                         q=[40, 1, 1], c=[0, 33, 200]),
 }
 
 
