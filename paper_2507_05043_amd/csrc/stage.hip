@@ -632,6 +632,29 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
   const bool qkv_lo = half_act && qkv_lo_of(c, n_tiles > 0);
   LayerPlans plans;
   if (int rc = plan_layer(st, T, two_plane || qkv_lo, two_plane, &plans)) return rc;
+  // The q/k/v input's second plane is there for the rows of prefill chunks.  When chunk rows and decode rows lie in a
+  // few contiguous runs (a scheduler that puts its chunks first or last gives two), every run gets its own product:
+  // chunk rows with both planes, decode rows with one - on the kernel that reads the weights' copy in operand order
+  // where the stage keeps one.  Otherwise one product with both planes covers all rows.
+  struct QkvRun { int row0, rows; bool two_planes; GemmPlan plan; };
+  std::vector<QkvRun> qkv_runs;
+  if (qkv_lo && !two_plane) {
+    int row = 0, decode_rows = 0;
+    for (int s = 0; s < S; ++s) {
+      const bool chunk = q_lens[s] > 1;
+      if (!qkv_runs.empty() && qkv_runs.back().two_planes == chunk) qkv_runs.back().rows += q_lens[s];
+      else qkv_runs.push_back(QkvRun{row, q_lens[s], chunk, GemmPlan{}});
+      row += q_lens[s];
+      if (!chunk) ++decode_rows;
+    }
+    constexpr int kMaxQkvRuns = 4, kMinDecodeRows = 16;
+    if (qkv_runs.size() < 2 || qkv_runs.size() > kMaxQkvRuns || decode_rows < kMinDecodeRows) qkv_runs.clear();
+    const bool copy = st->wcopy != nullptr && st->copies.qkv != kNoCopy;
+    for (QkvRun& r : qkv_runs) {
+      r.plan = plan_projection(c, r.rows, d.qkv_out, d.H, kEpiStoreF32, r.two_planes, copy && !r.two_planes);
+      if (int rc = check_plan(st, r.rows, r.plan)) return rc;
+    }
+  }
 
   HIP_TRY(hipSetDevice(st->device));
   hipStream_t stream = (hipStream_t)hip_stream;
@@ -772,22 +795,32 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
     }
     const e16* mlp_in = parallel ? (own_norm2 ? b2 : a) : a;
     const e16* mlp_in_lo = own_norm2 ? b2_lo : a_lo;
-    {
+    // q/k/v projection, rotation and cache append of rows row0 .. row0 + rows - 1
+    auto qkv_rows = [&](int row0, int rows, bool second_plane, const GemmPlan& plan) -> int {
       GemmArgs g{};
-      g.a = a; g.a_lo = norm1_lo; g.a_half = half_act; g.out_f32 = qkv_f32; g.partial = splitk;
-      g.m = T; g.n = d.qkv_out; g.k = d.H; g.lda = d.H; g.ldo = d.qkv_out;
+      g.a = a + (size_t)row0 * d.H; g.a_lo = second_plane ? norm1_lo + (size_t)row0 * d.H : nullptr; g.a_half = half_act;
+      g.out_f32 = qkv_f32 + (size_t)row0 * d.qkv_out; g.partial = splitk;
+      g.m = rows; g.n = d.qkv_out; g.k = d.H; g.lda = d.H; g.ldo = d.qkv_out;
       if (int rc = bind_weights(st, stream, g, w.wqkv, w.sqkv, w.zqkv, nullptr, nullptr, nullptr, l, st->copies.qkv, kNoCopy)) return rc;
       // the rotation kernel adds the split-K partial sums itself: no separate reduction pass
-      const GemmPlan& plan = plans.qkv;
       {
         Timer t(st, stream, STAGE_K_GEMM_QKV);
         HIP_TRY(launch_gemm_main(g, kEpiStoreF32, plan, stream));
       }
       Timer t(st, stream, STAGE_K_ROPE_APPEND);
-      RopeAppendArgs r{plan.partials ? splitk : qkv_f32, plan.partials ? plan.splits : 1, (size_t)T * d.qkv_out,
+      RopeAppendArgs r{plan.partials ? splitk : g.out_f32, plan.partials ? plan.splits : 1, (size_t)rows * d.qkv_out,
                        (const e16*)w.bqkv, (const e16*)w.qnorm, (const e16*)w.knorm, c.rms_eps,
-                       qkv, q_lo, cos_sin, d_slots, k_pool, v_pool, T, d.nq, d.nkv, d.d, rotating, c.rope_interleaved};
+                       qkv + (size_t)row0 * d.qkv_out, q_lo ? q_lo + (size_t)row0 * d.nq * d.d : nullptr,
+                       cos_sin + (size_t)row0 * (rotating / 2), d_slots + row0, k_pool, v_pool, rows, d.nq, d.nkv, d.d,
+                       rotating, c.rope_interleaved};
       HIP_TRY(launch_rope_append(r, stream));
+      return STAGE_OK;
+    };
+    if (qkv_runs.empty()) {
+      if (int rc = qkv_rows(0, T, norm1_lo != nullptr, plans.qkv)) return rc;
+    } else {
+      for (const QkvRun& r : qkv_runs)
+        if (int rc = qkv_rows(r.row0, r.rows, r.two_planes, r.plan)) return rc;
     }
     if (tap && taps->tap_qkv)
       HIP_TRY(hipMemcpyAsync(taps->tap_qkv, qkv, (size_t)T * d.qkv_out * 2, hipMemcpyDeviceToDevice, stream));
