@@ -397,6 +397,22 @@ def test_parallel_layernorm_block_at_real_widths():
     full_parity(shape, mb, 15, "fan_in", taps=False, block_biases=True)
 
 
+@pytest.mark.parametrize("q", [
+    [1] * 10 + [40] + [1] * 10 + [33],            # decode, chunk, decode, chunk: four runs, each with its own product
+    [37] + [1] * 150,                             # a chunk first, then enough decode rows for the 256-row tile's kernel
+    [1] * 70 + [50],                              # the chunk last
+    [1] * 6 + [20] + [1] * 6 + [18] + [1] * 6 + [17],   # six runs: one product with both planes for all rows
+], ids=["four-runs", "chunk-first", "chunk-last", "six-runs"])
+def test_deep_stage_gives_the_second_qkv_plane_to_chunk_rows_only(q):
+    """Nine layers (the automatic mode: half activations plus a second plane for the q/k/v input of micro-batches with
+    prefill chunks): chunk rows and decode rows in contiguous runs get separate q/k/v products, rotations and cache
+    appends; parity of the whole stage and of the appended keys and values, whatever the order of the runs."""
+    shape = _shape("deep-runs", 9, 512, 4, 2, 128, 1024)
+    ctx = [(13 * i) % 200 + (0 if n > 1 else 5) for i, n in enumerate(q)]
+    mb = synth.make_microbatch(q, ctx, seed=16, max_blocks_per_seq=20)
+    full_parity(shape, mb, 16, "fan_in", taps=False)
+
+
 def test_block_kind_weights_are_validated():
     import dataclasses
     base, mb = synth.workload("tiny", seed=0)
