@@ -647,7 +647,8 @@ int forward_impl(stage_handle* st, void* hip_stream, int32_t T, const void* hidd
       row += q_lens[s];
       if (!chunk) ++decode_rows;
     }
-    constexpr int kMaxQkvRuns = 4, kMinDecodeRows = 16;
+    // below about 128 decode rows the products are bound by the weight stream, and two products read it twice
+    constexpr int kMaxQkvRuns = 4, kMinDecodeRows = 128;
     if (qkv_runs.size() < 2 || qkv_runs.size() > kMaxQkvRuns || decode_rows < kMinDecodeRows) qkv_runs.clear();
     const bool copy = st->wcopy != nullptr && st->copies.qkv != kNoCopy;
     for (QkvRun& r : qkv_runs) {

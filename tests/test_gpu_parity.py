@@ -398,11 +398,12 @@ def test_parallel_layernorm_block_at_real_widths():
 
 
 @pytest.mark.parametrize("q", [
-    [1] * 10 + [40] + [1] * 10 + [33],            # decode, chunk, decode, chunk: four runs, each with its own product
+    [1] * 70 + [40] + [1] * 70 + [33],            # decode, chunk, decode, chunk: four runs, each with its own product
     [37] + [1] * 150,                             # a chunk first, then enough decode rows for the 256-row tile's kernel
-    [1] * 70 + [50],                              # the chunk last
+    [1] * 130 + [50],                             # the chunk last
+    [1] * 40 + [50],                              # few decode rows: one product (two would read the weights twice)
     [1] * 6 + [20] + [1] * 6 + [18] + [1] * 6 + [17],   # six runs: one product with both planes for all rows
-], ids=["four-runs", "chunk-first", "chunk-last", "six-runs"])
+], ids=["four-runs", "chunk-first", "chunk-last", "few-decode-rows", "six-runs"])
 def test_deep_stage_gives_the_second_qkv_plane_to_chunk_rows_only(q):
     """Nine layers (the automatic mode: half activations plus a second plane for the q/k/v input of micro-batches with
     prefill chunks): chunk rows and decode rows in contiguous runs get separate q/k/v products, rotations and cache
