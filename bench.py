@@ -37,7 +37,8 @@ HEADLINE = "llama3-70b"
 # the stage's other builds: the half-precision library and 4-bit weights on the small decode workload, 4-bit weights
 # on the headline workload (the paper serves its 70B model with 4-bit weights, section 5 "Models")
 VARIANTS = [("llama2-7b", {"dtype": "f16"}), ("llama2-7b", {"weights": "w4"}), ("llama3-70b", {"weights": "w4"})]
-PER_CONFIG = [("llama2-7b", None), ("qwen2-7b", None), ("llama3-70b", None), ("sweep", 64), ("sweep", 256), ("sweep", 2048)]
+PER_CONFIG = [("llama2-7b", None), ("qwen2-7b", None), ("llama3-70b", None), ("sweep", 64), ("sweep", 128), ("sweep", 256),
+              ("sweep", 512), ("sweep", 1024), ("sweep", 2048)]
 
 
 def algorithmic_work(shape, mb, weight_bytes_per_param=2.0):
@@ -102,6 +103,10 @@ def run_workload(args, workload, budget, steps, warmup, extras):
     from paper_2507_05043_amd import stage as _stage
     from paper_2507_05043_amd.harness import make_stage
 
+    # progress goes to stderr (stdout carries the one JSON line): a run of several minutes must not look hung
+    t_begin = time.time()
+    print(f"[bench] {workload}{'' if budget is None else ' budget ' + str(budget)} weights={args.weights} "
+          f"dtype={args.dtype}: setting up", file=sys.stderr, flush=True)
     shape, mb = synth.workload(workload, seed=args.seed, budget=budget or 256)
     w4 = args.weights == "w4"
     elem = torch.float16 if args.dtype == "f16" else torch.bfloat16
@@ -123,6 +128,7 @@ def run_workload(args, workload, budget, steps, warmup, extras):
     def step():
         st.forward(hidden, mb.positions, mb.q_lens, mb.ctx_lens, mb.block_tables, out=out)
 
+    print(f"[bench]   stage ready after {time.time() - t_begin:.0f} s, timing {steps} steps", file=sys.stderr, flush=True)
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
@@ -228,6 +234,7 @@ def run_workload(args, workload, budget, steps, warmup, extras):
     st.close()
     del st, hidden, out
     torch.cuda.empty_cache()
+    print(f"[bench]   {ms_per_step:.3f} ms per micro-batch ({time.time() - t_begin:.0f} s in all)", file=sys.stderr, flush=True)
     return result
 
 
